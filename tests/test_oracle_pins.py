@@ -1,0 +1,338 @@
+"""Pins for the CPU oracle: each one ties an oracle function to something other than
+itself -- brute force on tiny inputs, a library routine on a special case, a closed
+form, an invariant, or a value printed in the paper (tests/golden/)."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2209_06979_amd import workloads as wl
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _tiny(M, K, N, V, density, seed, lo=-128, hi=127):
+    rng = np.random.default_rng(seed)
+    P = M // V
+    flags = (rng.random((P, K)) < density).astype(np.uint8)
+    A = rng.integers(lo, hi + 1, size=(M, K)).astype(np.int32)
+    A *= np.repeat(flags, V, axis=0).astype(np.int32)
+    B = rng.integers(-128, 128, size=(K, N)).astype(np.int32)
+    return A, flags, B
+
+
+# ------------------------------------------------------------------ SpMM ----
+@pytest.mark.parametrize("V", [1, 2, 4, 8])
+def test_spmm_bruteforce_triple_loop(V):
+    """Zeros materialised, plain python loops over i, j, k (no mask needed then)."""
+    M, K, N = 2 * V, 7, 5
+    A, flags, B = _tiny(M, K, N, V, 0.5, 11 + V)
+    want = [[sum(int(A[i][k]) * int(B[k][j]) for k in range(K)) for j in range(N)] for i in range(M)]
+    got = oracle.spmm_dense(A, flags, B, V)
+    assert got.dtype == np.int32 and got.tolist() == want
+
+
+def test_spmm_flags_gate_the_sum():
+    """Entries outside the stored vectors must not contribute even if nonzero."""
+    V, M, K, N = 4, 8, 9, 3
+    rng = np.random.default_rng(5)
+    A = rng.integers(-128, 128, size=(M, K)).astype(np.int32)      # fully dense values
+    flags = (rng.random((M // V, K)) < 0.4).astype(np.uint8)
+    B = rng.integers(-128, 128, size=(K, N)).astype(np.int32)
+    masked = A * np.repeat(flags, V, axis=0)
+    want = masked.astype(np.int64) @ B.astype(np.int64)
+    assert np.array_equal(oracle.spmm_dense(A, flags, B, V), want)
+    assert not np.array_equal(want, A.astype(np.int64) @ B.astype(np.int64))
+
+
+def test_spmm_sparsity_zero_is_library_matmul():
+    V, M, K, N = 8, 64, 96, 48
+    A, flags, B = _tiny(M, K, N, V, 1.1, 3)
+    assert flags.all()
+    assert np.array_equal(oracle.spmm_dense(A, flags, B, V), A.astype(np.int64) @ B.astype(np.int64))
+    t = torch.from_numpy(A).to(torch.int64) @ torch.from_numpy(B).to(torch.int64)
+    assert np.array_equal(oracle.spmm_dense(A, flags, B, V), t.numpy())
+
+
+def test_spmm_not_transposed_or_swapped():
+    """Asymmetric shapes and a one-hot probe: C[i][j] picks A[i][k0] * B[k0][j]."""
+    V, M, K, N = 2, 4, 3, 5
+    A = np.zeros((M, K), np.int32); A[3, 1] = 7
+    flags = np.zeros((M // V, K), np.uint8); flags[1, 1] = 1
+    B = np.arange(K * N, dtype=np.int32).reshape(K, N) - 6
+    C = oracle.spmm_dense(A, flags, B, V)
+    want = np.zeros((M, N), np.int64); want[3] = 7 * B[1]
+    assert np.array_equal(C, want)
+
+
+def test_spmm_closed_forms():
+    V, M, K, N = 8, 32, 40, 16
+    A, flags, _ = _tiny(M, K, N, V, 0.3, 9)
+    ones = np.ones((K, N), np.int32)
+    C = oracle.spmm_dense(A, flags, ones, V)
+    assert np.array_equal(C, np.repeat(A.sum(axis=1, keepdims=True), N, axis=1))
+    # one stored vector per panel holding the unit vector e_v: row p*V+v gathers B[col]
+    B = np.random.default_rng(1).integers(-128, 128, size=(K, N)).astype(np.int32)
+    A1 = np.zeros((M, K), np.int32); f1 = np.zeros((M // V, K), np.uint8)
+    for p in range(M // V):
+        col, v = (5 * p + 3) % K, p % V
+        f1[p, col] = 1; A1[p * V + v, col] = 1
+    C1 = oracle.spmm_dense(A1, f1, B, V)
+    for p in range(M // V):
+        for v in range(V):
+            want = B[(5 * p + 3) % K] if v == p % V else np.zeros(N, np.int32)
+            assert np.array_equal(C1[p * V + v], want)
+
+
+def test_spmm_linearity():
+    V, M, K, N = 4, 16, 24, 8
+    A, flags, B = _tiny(M, K, N, V, 0.5, 21, lo=-60, hi=60)
+    A2, _, B2 = _tiny(M, K, N, V, 0.5, 22, lo=-60, hi=60)
+    A2 *= np.repeat(flags, V, axis=0).astype(np.int32)
+    f = oracle.spmm_dense
+    assert np.array_equal(f(A, flags, B + B2, V), f(A, flags, B, V) + f(A, flags, B2, V))
+    assert np.array_equal(f(A + A2, flags, B, V), f(A, flags, B, V) + f(A2, flags, B, V))
+    assert np.array_equal(f(3 * A, flags, B, V), 3 * f(A, flags, B, V))
+
+
+def test_spmm_overflow_is_reported():
+    V, K = 2, 4
+    A = np.full((2, K), 2**30, np.int32); flags = np.ones((1, K), np.uint8)
+    B = np.full((K, 1), 2, np.int32)
+    with pytest.raises(OverflowError):
+        oracle.spmm_dense(A, flags, B, V)
+    B[:] = 0; B[0, 0] = 1
+    assert oracle.spmm_dense(A, flags, B, V)[0, 0] == 2**30
+
+
+def test_bcrs_to_dense_and_vector_order_invariance():
+    """Vectors may be listed in any order inside a panel; the product does not change."""
+    V, M, K, N = 4, 12, 10, 6
+    rp, ci = wl.ragged_pattern(M, K, V, [3, 0, 5], 17)
+    vals = wl.uniform_int8((len(ci), V), 18)
+    A, flags = oracle.bcrs_to_dense(M, K, V, rp, ci, vals)
+    # independent construction with python loops
+    A_ref = np.zeros((M, K), np.int64)
+    for p in range(M // V):
+        for i in range(rp[p], rp[p + 1]):
+            for v in range(V):
+                A_ref[p * V + v, ci[i]] = vals[i, v]
+    assert np.array_equal(A, A_ref)
+    assert flags.sum() == len(ci) and flags[1].sum() == 0
+    B = wl.uniform_int8((K, N), 19)
+    C = oracle.spmm(M, K, V, rp, ci, vals, B, "L8R8")
+    assert np.array_equal(C, A_ref @ B.astype(np.int64))
+    assert not C[V:2 * V].any()                      # empty panel -> zero rows
+    rng = np.random.default_rng(3)
+    ci2, vals2 = ci.copy(), vals.copy()
+    for p in range(M // V):
+        perm = rng.permutation(rp[p + 1] - rp[p]) + rp[p]
+        ci2[rp[p]:rp[p + 1]] = ci[perm]; vals2[rp[p]:rp[p + 1]] = vals[perm]
+    assert np.array_equal(oracle.spmm(M, K, V, rp, ci2, vals2, B, "L8R8"), C)
+
+
+# ----------------------------------------------------------------- SDDMM ----
+def test_sddmm_bruteforce_and_order():
+    V, M, Nc, Kd = 2, 6, 5, 3
+    rng = np.random.default_rng(2)
+    Q = rng.integers(-128, 128, size=(M, Kd)).astype(np.int32)
+    Kmat = rng.integers(-128, 128, size=(Nc, Kd)).astype(np.int32)
+    flags = np.array([[1, 0, 1, 0, 0], [0, 0, 0, 0, 0], [0, 1, 1, 0, 1]], np.uint8)
+    want = []
+    for p in range(M // V):
+        for c in range(Nc):
+            if flags[p][c]:
+                for v in range(V):
+                    want.append(sum(int(Q[p * V + v][k]) * int(Kmat[c][k]) for k in range(Kd)))
+    assert oracle.sddmm_dense(Q, Kmat, flags, V).tolist() == want
+
+
+@pytest.mark.parametrize("V", [2, 4, 8])
+def test_sddmm_is_dense_product_at_mask_positions(V):
+    M, Nc, Kd = 8 * V, 40, 32
+    c = wl.sddmm_case(M, Nc, Kd, V, 0.7, "L8R8", 100 + V)
+    dense = c["Q"].astype(np.int64) @ c["Kmat"].astype(np.int64).T          # library routine
+    S = oracle.sddmm(M, Nc, V, c["row_ptr"], c["col_idx"], c["Q"], c["Kmat"], "L8R8")
+    S = S.reshape(-1, V)
+    for p in range(M // V):
+        for i in range(c["row_ptr"][p], c["row_ptr"][p + 1]):
+            assert np.array_equal(S[i], dense[p * V:(p + 1) * V, c["col_idx"][i]])
+
+
+def test_sddmm_full_mask_is_library_matmul():
+    V, M, Nc, Kd = 4, 16, 12, 20
+    rng = np.random.default_rng(8)
+    Q = rng.integers(-128, 128, size=(M, Kd)).astype(np.int32)
+    Kmat = rng.integers(-128, 128, size=(Nc, Kd)).astype(np.int32)
+    S = oracle.sddmm_dense(Q, Kmat, np.ones((M // V, Nc), np.uint8), V)
+    dense = (torch.from_numpy(Q).long() @ torch.from_numpy(Kmat).long().T).numpy()
+    # S[p][c][v] -> dense[p*V+v][c]
+    got = S.reshape(M // V, Nc, V).transpose(0, 2, 1).reshape(M, Nc)
+    assert np.array_equal(got, dense)
+
+
+# ------------------------------------------------- nibbles and planes ----
+def _golden_rows():
+    rows = []
+    with open(os.path.join(GOLDEN, "split_examples.txt")) as f:
+        for line in f:
+            if line.strip() and not line.startswith("#"):
+                kind, val, bits, low_bits, lo, hi = line.split()
+                rows.append((kind, int(val), bits, int(low_bits), int(lo), int(hi)))
+    return rows
+
+
+def test_split_matches_the_papers_worked_examples():
+    rows = _golden_rows()
+    assert len(rows) == 2
+    for kind, val, bits, low_bits, lo, hi in rows:
+        # the printed bit pattern is the 8-bit encoding of the printed value
+        assert int(bits, 2) == val % 256
+        fn = oracle.split_unsigned if kind == "unsigned" else oracle.split_signed
+        got_lo, got_hi = fn(val, low_bits)
+        assert (int(got_lo), int(got_hi)) == (lo, hi)
+        assert lo + (hi << low_bits) == val
+
+
+def test_unpack_int4_convention():
+    # 0xED: bits 3:0 = 1101 -> -3 (element 0), bits 7:4 = 1110 -> -2 (element 1);
+    # the high nibble read signed is the -2 of the paper's signed example.
+    assert oracle.unpack_int4(np.array([0xED], np.uint8)).tolist() == [-3, -2]
+    assert oracle.unpack_int4(np.array([0x70, 0x08], np.uint8)).tolist() == [0, 7, -8, 0]
+    allb = np.arange(256, dtype=np.uint8)
+    u = oracle.unpack_int4(allb).reshape(256, 2)
+    assert u.min() == -8 and u.max() == 7
+    assert np.array_equal((u[:, 0] & 15) | ((u[:, 1] & 15) << 4), np.arange(256))
+
+
+@pytest.mark.parametrize("split", ["textbook", "balanced"])
+def test_plane_split_identity_16bit(split):
+    """(hi << 8) * B + lo * B == A16 * B with int64 sums, for both ways of splitting."""
+    V, M, K, N = 8, 16, 64, 8
+    rng = np.random.default_rng(77)
+    flags = (rng.random((M // V, K)) < 0.5).astype(np.uint8)
+    A16 = rng.integers(-32768, 32640, size=(M, K)).astype(np.int32) * np.repeat(flags, V, axis=0)
+    A16[0, :4] = [-32768, 32639, -129, 127]
+    A16[0, :4] *= flags[0, :4]
+    B = rng.integers(-128, 128, size=(K, N)).astype(np.int32)
+    lo, hi = (oracle.split_signed if split == "textbook" else oracle.split_balanced)(A16, 8)
+    assert np.array_equal(lo + (hi << 8), A16)
+    if split == "textbook":
+        assert lo.min() >= 0 and lo.max() <= 255 and hi.min() >= -128 and hi.max() <= 127
+    else:
+        assert lo.min() >= -128 and lo.max() <= 127 and hi.min() >= -128 and hi.max() <= 127
+    full = A16.astype(np.int64) @ B.astype(np.int64)
+    assert np.array_equal(oracle.spmm_dense(A16, flags, B, V), full)
+    c_hi = oracle.spmm_dense(hi.astype(np.int32), flags, B, V).astype(np.int64)
+    c_lo = oracle.spmm_dense(lo.astype(np.int32), flags, B, V).astype(np.int64)
+    assert np.array_equal((c_hi << 8) + c_lo, full)
+
+
+def test_low_precision_cases_equal_widened_int8_cases():
+    V, M, K, N = 8, 32, 48, 32
+    c = wl.spmm_case(M, K, N, V, 0.5, "L4R4", 31)
+    nvec = len(c["col_idx"])
+    # widen by hand with an independent formula: sign-extend each nibble via int8 shifts
+    def widen(packed):
+        p = packed.astype(np.uint8)
+        lo = (np.left_shift(p, 4).astype(np.uint8).view(np.int8) >> 4).astype(np.int8)
+        hi = (p.view(np.int8) >> 4).astype(np.int8)
+        return np.stack([lo, hi], axis=-1).reshape(p.shape[:-1] + (-1,))
+    A8, B8 = widen(c["values"]), widen(c["B"])
+    assert A8.shape == (nvec, V) and B8.shape == (K, N)
+    want = oracle.spmm(M, K, V, c["row_ptr"], c["col_idx"], A8, B8, "L8R8")
+    assert np.array_equal(oracle.spmm(M, K, V, c["row_ptr"], c["col_idx"], c["values"], c["B"], "L4R4"), want)
+    assert np.array_equal(oracle.spmm(M, K, V, c["row_ptr"], c["col_idx"], A8, c["B"], "L8R4"), want)
+    s = wl.sddmm_case(M, K, 64, V, 0.5, "L4R4", 32)
+    want = oracle.sddmm(M, K, V, s["row_ptr"], s["col_idx"], widen(s["Q"]), widen(s["Kmat"]), "L8R8")
+    assert np.array_equal(oracle.sddmm(M, K, V, s["row_ptr"], s["col_idx"], s["Q"], s["Kmat"], "L4R4"), want)
+
+
+def test_l16r8_from_interchange_data():
+    V, M, K, N = 8, 16, 32, 16
+    c = wl.spmm_case(M, K, N, V, 0.5, "L16R8", 41)
+    A, flags = oracle.bcrs_to_dense(M, K, V, c["row_ptr"], c["col_idx"], c["values"])
+    want = A.astype(np.int64) @ c["B"].astype(np.int64)
+    assert np.array_equal(oracle.spmm(M, K, V, c["row_ptr"], c["col_idx"], c["values"], c["B"], "L16R8"), want)
+
+
+# ------------------------------------------------------------ attention ----
+def test_softmax_rows_sum_to_one_and_uniform_case():
+    V = 8
+    rp = np.array([0, 3, 3, 10], np.int32)
+    rng = np.random.default_rng(4)
+    S = rng.integers(-2000, 2000, size=10 * V).astype(np.int32)
+    p = oracle.sparse_softmax(S, rp, V, 0.01).reshape(10, V)
+    assert np.allclose(p[0:3].sum(axis=0), 1.0, atol=1e-14)
+    assert np.allclose(p[3:10].sum(axis=0), 1.0, atol=1e-14)
+    S[:] = 123
+    p = oracle.sparse_softmax(S, rp, V, 0.5).reshape(10, V)
+    assert np.allclose(p[0:3], 1 / 3) and np.allclose(p[3:], 1 / 7)
+
+
+def test_requantize_rounding():
+    p = np.array([0.0, 0.5 / 127, 1.5 / 127, 2.5 / 127, 1.0, 0.49999 / 127])
+    # exact ties cannot be represented exactly in binary; check neighbours and ends
+    q = oracle.requantize_probabilities(np.array([0.0, 1.0, 0.3 / 127, 0.7 / 127, 63.4 / 127]), 1 / 127)
+    assert q.tolist() == [0, 127, 0, 1, 63]
+    assert oracle.requantize_probabilities(np.array([2.0]), 1 / 127).tolist() == [127]
+    assert oracle.requantize_probabilities(np.array([2.5, 3.5]), 1.0).tolist() == [2, 4]  # ties to even
+    del p
+
+
+def test_quantizer_agrees_with_input_preparation():
+    x = wl.normal_fp32((2, 64, 16), 5)
+    q1, s1 = oracle.quantize_per_tensor(x)
+    q2, s2 = wl.quantize_inputs_int8(x)
+    assert s1 == s2 and np.array_equal(q1, q2)
+    assert np.abs(q1).max() == 127
+    assert np.max(np.abs(q1 * np.float64(s1) - x)) <= 0.5 * s1 + 1e-7
+
+
+def test_attention_against_dense_torch_reference():
+    """Second, independent route: dense fp64 attention in torch with -inf at masked
+    positions and the same fake-quantisation steps."""
+    heads, L, dk, V = 2, 64, 16, 8
+    c = wl.attention_case(heads, L, dk, V, 0.75, 900)
+    q8, s_q = wl.quantize_inputs_int8(c["q"]); k8, s_k = wl.quantize_inputs_int8(c["k"])
+    v8, s_v = wl.quantize_inputs_int8(c["v"])
+    s_p = np.float32(1.0 / 127.0)
+    O, scores, probs, codes = oracle.attention(q8, k8, v8, c["row_ptr"], c["col_idx"], V, s_q, s_k, s_v, s_p)
+    flags = oracle.stored_flags(L, L, V, c["row_ptr"], c["col_idx"])
+    keep = torch.from_numpy(np.repeat(flags, V, axis=0).astype(bool))
+    assert bool(keep.diagonal().all())
+    for h in range(heads):
+        Sd = torch.from_numpy(q8[h]).double() @ torch.from_numpy(k8[h]).double().T
+        x = Sd * (float(s_q) * float(s_k) / np.sqrt(dk))
+        x = x.masked_fill(~keep, float("-inf"))
+        Pd = torch.softmax(x, dim=1)
+        Pq = torch.clamp(torch.round(Pd / float(s_p)), 0, 127)
+        Od = (Pq @ torch.from_numpy(v8[h]).double()) * (float(s_p) * float(s_v))
+        assert np.allclose(O[h], Od.numpy(), rtol=0, atol=1e-12)
+        # stored probabilities are the dense ones at the mask positions
+        pr = probs[h].reshape(-1, V)
+        for p in range(L // V):
+            for i in range(c["row_ptr"][p], c["row_ptr"][p + 1]):
+                assert np.allclose(pr[i], Pd[p * V:(p + 1) * V, c["col_idx"][i]].numpy(), atol=1e-15)
+    # quantised attention stays close to the unquantised fp64 attention on the same mask
+    for h in range(heads):
+        x = (torch.from_numpy(c["q"][h]).double() @ torch.from_numpy(c["k"][h]).double().T) / np.sqrt(dk)
+        ref = torch.softmax(x.masked_fill(~keep, float("-inf")), dim=1) @ torch.from_numpy(c["v"][h]).double()
+        assert np.max(np.abs(O[h] - ref.numpy())) < 0.15
+
+
+# ------------------------------------------------------------ generators ----
+def test_generators_are_seeded_and_exact():
+    rp, ci = wl.vector_sparse_pattern(64, 512, 8, 0.8, wl.seed_for(1))
+    rp2, ci2 = wl.vector_sparse_pattern(64, 512, 8, 0.8, wl.seed_for(1))
+    assert np.array_equal(ci, ci2) and np.array_equal(rp, rp2)
+    assert wl.vectors_per_panel(512, 0.8) == 102 and len(ci) == 8 * 102
+    assert wl.vectors_per_panel(4096, 0.9) == 410 and wl.vectors_per_panel(4096, 0.98) == 82
+    for p in range(8):
+        seg = ci[rp[p]:rp[p + 1]]
+        assert np.all(np.diff(seg) > 0) and seg.min() >= 0 and seg.max() < 512
+    rp, ci = wl.vector_sparse_pattern(64, 64, 8, 0.5, 3, keep_diagonal=True)
+    for p in range(8):
+        assert set(range(8 * p, 8 * p + 8)) <= set(ci[rp[p]:rp[p + 1]].tolist())
