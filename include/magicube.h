@@ -1,0 +1,191 @@
+/*
+ * magicube.h -- C ABI of the MI355X (gfx950) library for quantized sparse matrix
+ * operations with 1-D block ("column vector") sparsity.
+ *
+ * Operations (all integer results are exact int32):
+ *   SpMM   C[M x N] = A_sparse[M x K] * B[K x N]           (paper, Section 4.2)
+ *   SDDMM  S = (Q[M x Kd] * Kmat[Nc x Kd]^T) at a mask     (paper, Section 4.3)
+ *   mixed precision Lx-Ry: x-bit sparse/left operand, y-bit dense/right operand
+ *          (paper, Section 4.4 and its table of supported precisions)
+ *   quantized sparse self-attention: SDDMM -> softmax -> int8 -> SpMM
+ *          (paper, Section 5.3)
+ *
+ * Sparse operand, interchange form ("BCRS with 1-D blocks", Section 4.1):
+ *   V          block length, 2, 4 or 8; rows p*V .. p*V+V-1 form row panel p, P = M / V
+ *   row_ptr    P + 1 int32; panel p owns vectors row_ptr[p] .. row_ptr[p+1]-1
+ *   col_idx    one int32 column per stored vector, strictly ascending inside a panel
+ *   values     the V elements of each vector consecutively (vector-major):
+ *              8-bit: int8; 16-bit: little-endian int16; 4-bit: two's-complement
+ *              nibbles, element 2j in bits 3:0 and element 2j+1 in bits 7:4 of byte j
+ * The library converts it into its own device format (a strided row-major layout in
+ * the spirit of SR-BCRS, Section 4.1): vectors of a panel are grouped in chunks of 64
+ * (the reduction depth of one gfx950 i8 MFMA), the last chunk zero-padded, values
+ * row-major inside sub-strides of 16 vectors, two pointers per panel (chunk-aligned
+ * start and real end).
+ *
+ * Conventions
+ *   - "dev" pointers are device (HBM) addresses owned by the caller, "host" pointers
+ *     are ordinary host memory.  The library owns only mc_mat handles.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Compute
+ *     calls are asynchronous on it and never synchronise or allocate.
+ *   - Every int-returning function returns MC_OK (0) or a negative mc_status; nothing
+ *     throws or aborts.  Argument checks are done on the host before any launch.
+ *   - Dense operands are row-major.  int4 dense operands hold two elements per byte
+ *     along a row (same nibble order as above); leading dimensions are in ELEMENTS.
+ */
+#ifndef MAGICUBE_H
+#define MAGICUBE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    MC_OK = 0,
+    MC_EINVAL = -1,       /* bad size, V, pattern (unsorted / out of range), null pointer   */
+    MC_EUNSUPPORTED = -2, /* precision / operation pair outside the supported table         */
+    MC_EALIGN = -3,       /* device pointer or leading dimension not 16-byte aligned        */
+    MC_EHIP = -4,         /* a HIP runtime call failed                                       */
+    MC_ENOMEM = -5,       /* host or device allocation failed / workspace too small         */
+    MC_ERANGE = -6        /* a value cannot be represented (16-bit value above 32639, ...)  */
+} mc_status;
+
+/* Lx-Ry: bits of the left (sparse for SpMM) and right operands. */
+typedef enum { MC_L8R8 = 0, MC_L8R4 = 1, MC_L4R4 = 2, MC_L16R8 = 3 } mc_prec;
+
+/* Vectors per chunk of the device format (= reduction depth of v_mfma_i32_16x16x64_i8). */
+#define MC_CHUNK 64
+
+typedef struct mc_mat mc_mat; /* opaque: device-resident sparse matrix or mask */
+
+const char *mc_strerror(int status);
+/* "major.minor gfx950": build identification. */
+const char *mc_version(void);
+/* After a call returned MC_EHIP on this thread: which HIP call failed and its message
+ * (empty string if none yet).  The pointer stays valid for the thread's lifetime. */
+const char *mc_last_error_detail(void);
+
+/* ------------------------------------------------------------------------------------
+ * Host-side format builder (Section 4.1).  Pure host code: usable without a GPU.
+ * ---------------------------------------------------------------------------------- */
+typedef struct {
+    int32_t P;           /* row panels = M / V                                       */
+    int64_t nvec;        /* stored vectors = row_ptr[P]                              */
+    int64_t nslots;      /* vector slots after padding each panel to a multiple of 64 */
+    int64_t vals_bytes;  /* bytes of the packed value array (0 for lhs_bits == 0)    */
+} mc_layout;
+
+/* Checks M, K, V, lhs_bits (0 = pattern only, 4, 8, 16) and row_ptr (host, P+1,
+ * non-decreasing from 0) and fills *out.  MC_EINVAL on any violation. */
+int mc_layout_query(int M, int K, int V, int lhs_bits, const int32_t *row_ptr, mc_layout *out);
+
+/* Converts interchange data (host) into the device format (host buffers the caller
+ * sized with mc_layout_query):
+ *   panel_ptr  2*P int32: [2p] first slot of panel p (multiple of 64), [2p+1] = [2p] +
+ *              number of real vectors (the "two row pointers" of Section 4.1)
+ *   slot_idx   nslots int32: column of each slot; padded slots repeat the panel's last
+ *              real column (their values are zero, so they add nothing)
+ *   slot_vals  vals_bytes bytes (ignored when lhs_bits == 0 or values == NULL):
+ *              chunk-major; inside a chunk 4 sub-strides of 16 slots; inside a
+ *              sub-stride row-major: 8-bit  [row v][16 slots]
+ *                                    16-bit [plane hi,lo][row v][16 slots] with the
+ *                                           balanced split a = 256*hi + lo, both int8
+ *                                    4-bit  [row v][8 bytes], byte b = slot b (low
+ *                                           nibble) and slot b + 8 (high nibble)
+ * Validates col_idx (ascending per panel, 0 <= c < K): MC_EINVAL; 16-bit values above
+ * 32639 cannot be split into two signed bytes: MC_ERANGE. */
+int mc_pack_host(int M, int K, int V, int lhs_bits, const int32_t *row_ptr, const int32_t *col_idx,
+                 const void *values, int32_t *panel_ptr, int32_t *slot_idx, void *slot_vals);
+
+/* Inverse of mc_pack_host (for round-trip checks): rebuilds row_ptr, col_idx and the
+ * vector-major values from device-format host buffers.  Output buffers are sized for
+ * P+1, nvec and nvec*V elements of the given width. */
+int mc_unpack_host(int M, int K, int V, int lhs_bits, const int32_t *panel_ptr, const int32_t *slot_idx,
+                   const void *slot_vals, int32_t *row_ptr, int32_t *col_idx, void *values);
+
+/* ------------------------------------------------------------------------------------
+ * Device-resident sparse operand.
+ * ---------------------------------------------------------------------------------- */
+/* Builds the device format from HOST interchange arrays and uploads it on `stream`
+ * (the call returns after the upload has completed).  values == NULL or lhs_bits == 0
+ * gives a pattern-only mask (for SDDMM / attention).  *out is owned by the caller
+ * until mc_mat_destroy.  Errors as mc_pack_host, plus MC_EHIP / MC_ENOMEM. */
+int mc_mat_create(int M, int K, int V, int lhs_bits, const int32_t *row_ptr, const int32_t *col_idx,
+                  const void *values, void *stream, mc_mat **out);
+/* Replaces the values from a DEVICE array in interchange order (nvec*V elements of the
+ * matrix's width; e.g. the output of a softmax).  Asynchronous on `stream`. */
+int mc_mat_set_values_device(mc_mat *A, const void *values_dev, void *stream);
+void mc_mat_destroy(mc_mat *A);
+/* Shape queries; return MC_EINVAL on a null handle. */
+int mc_mat_info(const mc_mat *A, int *M, int *K, int *V, int *lhs_bits, int64_t *nvec, int64_t *nslots);
+
+/* ------------------------------------------------------------------------------------
+ * SpMM (Section 4.2): C = A * B, exact int32.
+ *   A      sparse M x K, width must match prec (L8: 8, L4: 4, L16: 16 bits)
+ *   B_dev  dense K x N row-major, int8 (R8) or packed int4 (R4); ldb in elements
+ *   C_dev  dense M x N row-major int32; ldc in elements
+ * Requirements: B_dev, C_dev 16-byte aligned; N a multiple of 16 (R8) or 32 (R4);
+ * ldb*bits/8 a multiple of 16 and >= the row bytes; ldc a multiple of 4 and >= N.
+ * R4 paths keep 16x (L8-R4) or 256x (L4-R4) scaled sums in int32, so they require
+ * K <= 131072.  L16-R8 is computed as two signed int8 planes in one MFMA and
+ * recombined as (C_hi << 8) + C_lo (Section 4.4).
+ * Results that do not fit int32 wrap (two's complement).
+ * ---------------------------------------------------------------------------------- */
+int mc_spmm(const mc_mat *A, const void *B_dev, int N, int ldb, mc_prec prec, int32_t *C_dev, int ldc,
+            void *stream);
+
+/* ------------------------------------------------------------------------------------
+ * SDDMM (Section 4.3): for every stored vector i of the mask (panel p, column c):
+ *   S[i*V + v] = sum_k Q[p*V + v][k] * Kmat[c][k],  v = 0..V-1
+ *   Q_dev     M x Kd row-major, Kmat_dev  Nc x Kd row-major (the paper's column-major
+ *             right operand), int8 (MC_L8R8) or packed int4 (MC_L4R4); ldq/ldk in elements
+ *   mask      pattern of an M x Nc matrix (values ignored)
+ *   S_dev     nvec*V int32 in interchange (vector-major) order
+ * Requirements: 16-byte aligned pointers; Kd*bits/8 a multiple of 16; ld*bits/8 a
+ * multiple of 16.  Other precisions: MC_EUNSUPPORTED.
+ * ---------------------------------------------------------------------------------- */
+int mc_sddmm(const void *Q_dev, int ldq, const void *Kmat_dev, int ldk, int Kd, const mc_mat *mask,
+             mc_prec prec, int32_t *S_dev, void *stream);
+
+/* ------------------------------------------------------------------------------------
+ * Sparse softmax with fused (de)quantisation (Section 5.3): for each row (p, v) over its
+ * stored entries i:  x_i = S[i*V+v] * score_scale;  p_i = exp(x_i - max) / sum;
+ * code_i = clamp(rint(p_i * inv_s_p), 0, 127) as int8, in interchange order.  fp32 math.
+ *   batch     number of independent score sets sharing the mask (heads)
+ *   S_dev     batch * nvec*V int32;  codes_dev  batch * nvec*V int8
+ * ---------------------------------------------------------------------------------- */
+int mc_sparse_softmax(const mc_mat *mask, int batch, const int32_t *S_dev, float score_scale,
+                      float inv_s_p, int8_t *codes_dev, void *stream);
+
+/* ------------------------------------------------------------------------------------
+ * Quantized sparse self-attention layer (Section 5.3), one mask shared by all heads:
+ *   O[h] = ( P_q[h] * Vm[h] ) * (s_p * s_v),
+ *   P_q[h] = int8( softmax( SDDMM(Q[h], Km[h]; mask) * s_q*s_k/sqrt(dk) ) / s_p )
+ *   Q_dev, Km_dev, Vm_dev   heads x L x dk int8, contiguous
+ *   mask                    L x L pattern, V = 8
+ *   O_dev                   heads x L x dk fp32
+ *   workspace_dev           at least mc_attention_workspace_bytes(heads, mask) bytes,
+ *                           256-byte aligned, caller-owned; contents undefined after
+ * Requirements: dk a multiple of 16.  Entries excluded by the mask do not take part in
+ * the softmax.  Empty rows give zeros.
+ * ---------------------------------------------------------------------------------- */
+size_t mc_attention_workspace_bytes(int heads, const mc_mat *mask);
+int mc_sparse_attention(const int8_t *Q_dev, const int8_t *Km_dev, const int8_t *Vm_dev, int heads, int L,
+                        int dk, const mc_mat *mask, float s_q, float s_k, float s_v, float s_p,
+                        float *O_dev, void *workspace_dev, size_t workspace_bytes, void *stream);
+
+/* ------------------------------------------------------------------------------------
+ * Tuning knob (not needed for correctness): selects the SpMM tile variant.
+ *   bytes_per_row_tile  0 = automatic, else 64, 128 or 256 bytes of a B row per workgroup
+ *   waves               0 = automatic, else 1, 2 or 4 wavefronts sharing a panel's chunks
+ * Returns MC_EINVAL for other values.  Process-wide.
+ * ---------------------------------------------------------------------------------- */
+int mc_set_spmm_variant(int bytes_per_row_tile, int waves);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MAGICUBE_H */

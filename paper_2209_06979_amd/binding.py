@@ -1,0 +1,231 @@
+"""Thin Python binding over the C ABI of libmagicube.so (see include/magicube.h).
+
+Argument marshalling only: every step of the path runs in the library's HIP kernels.
+PyTorch supplies device memory (tensors) and the current stream, nothing else.  If the
+shared library is missing the import fails -- there is no fallback implementation.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from ctypes import POINTER, c_char_p, c_float, c_int, c_int32, c_int64, c_size_t, c_void_p
+
+import numpy as np
+import torch  # noqa: F401  -- must come first: the library then binds to the HIP runtime torch ships
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libmagicube.so")
+
+MC_OK, MC_EINVAL, MC_EUNSUPPORTED, MC_EALIGN, MC_EHIP, MC_ENOMEM, MC_ERANGE = 0, -1, -2, -3, -4, -5, -6
+PREC = {"L8R8": 0, "L8R4": 1, "L4R4": 2, "L16R8": 3}
+LHS_BITS = {"L8R8": 8, "L8R4": 8, "L4R4": 4, "L16R8": 16}
+RHS_BITS = {"L8R8": 8, "L8R4": 4, "L4R4": 4, "L16R8": 8}
+CHUNK = 64
+
+
+class Layout(ctypes.Structure):
+    _fields_ = [("P", c_int32), ("nvec", c_int64), ("nslots", c_int64), ("vals_bytes", c_int64)]
+
+
+class MagicubeError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        detail = lib.mc_last_error_detail().decode() if status == MC_EHIP else ""
+        super().__init__(f"{where}: {lib.mc_strerror(status).decode()} ({status}) {detail}".rstrip())
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it first (python -m paper_2209_06979_amd.build); "
+            "there is no CPU fallback")
+    L = ctypes.CDLL(LIB_PATH)
+    i32p = POINTER(c_int32)
+    L.mc_strerror.argtypes = [c_int]; L.mc_strerror.restype = c_char_p
+    L.mc_version.argtypes = []; L.mc_version.restype = c_char_p
+    L.mc_last_error_detail.argtypes = []; L.mc_last_error_detail.restype = c_char_p
+    L.mc_layout_query.argtypes = [c_int, c_int, c_int, c_int, i32p, POINTER(Layout)]
+    L.mc_pack_host.argtypes = [c_int, c_int, c_int, c_int, i32p, i32p, c_void_p, i32p, i32p, c_void_p]
+    L.mc_unpack_host.argtypes = [c_int, c_int, c_int, c_int, i32p, i32p, c_void_p, i32p, i32p, c_void_p]
+    L.mc_mat_create.argtypes = [c_int, c_int, c_int, c_int, i32p, i32p, c_void_p, c_void_p, POINTER(c_void_p)]
+    L.mc_mat_set_values_device.argtypes = [c_void_p, c_void_p, c_void_p]
+    L.mc_mat_destroy.argtypes = [c_void_p]; L.mc_mat_destroy.restype = None
+    L.mc_mat_info.argtypes = [c_void_p, POINTER(c_int), POINTER(c_int), POINTER(c_int), POINTER(c_int),
+                              POINTER(c_int64), POINTER(c_int64)]
+    L.mc_spmm.argtypes = [c_void_p, c_void_p, c_int, c_int, c_int, c_void_p, c_int, c_void_p]
+    L.mc_sddmm.argtypes = [c_void_p, c_int, c_void_p, c_int, c_int, c_void_p, c_int, c_void_p, c_void_p]
+    L.mc_sparse_softmax.argtypes = [c_void_p, c_int, c_void_p, c_float, c_float, c_void_p, c_void_p]
+    L.mc_attention_workspace_bytes.argtypes = [c_int, c_void_p]; L.mc_attention_workspace_bytes.restype = c_size_t
+    L.mc_sparse_attention.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_void_p,
+                                      c_float, c_float, c_float, c_float, c_void_p, c_void_p, c_size_t, c_void_p]
+    L.mc_set_spmm_variant.argtypes = [c_int, c_int]
+    for name in ("mc_layout_query", "mc_pack_host", "mc_unpack_host", "mc_mat_create", "mc_mat_set_values_device",
+                 "mc_mat_info", "mc_spmm", "mc_sddmm", "mc_sparse_softmax", "mc_sparse_attention",
+                 "mc_set_spmm_variant"):
+        getattr(L, name).restype = c_int
+    return L
+
+
+lib = _load()
+
+
+def _check(status: int, where: str) -> None:
+    if status != MC_OK:
+        raise MagicubeError(status, where)
+
+
+def _i32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _p32(a: np.ndarray):
+    return a.ctypes.data_as(POINTER(c_int32))
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+# ------------------------------------------------------------------ host format ----
+def layout_query(M, K, V, lhs_bits, row_ptr) -> Layout:
+    rp = _i32(row_ptr)
+    if rp.shape[0] < 1 or (M > 0 and V > 0 and M % V == 0 and rp.shape[0] != M // V + 1):
+        raise MagicubeError(MC_EINVAL, "layout_query(row_ptr length)")
+    lay = Layout()
+    _check(lib.mc_layout_query(M, K, V, lhs_bits, _p32(rp), ctypes.byref(lay)), "mc_layout_query")
+    return lay
+
+
+def pack_host(M, K, V, lhs_bits, row_ptr, col_idx, values):
+    """Interchange arrays -> (panel_ptr, slot_idx, slot_vals) host arrays in device format."""
+    rp, ci = _i32(row_ptr), _i32(col_idx)
+    lay = layout_query(M, K, V, lhs_bits, rp)
+    if ci.shape[0] != lay.nvec:
+        raise MagicubeError(MC_EINVAL, "pack_host(col_idx length)")
+    panel_ptr = np.zeros(2 * lay.P, np.int32)
+    slot_idx = np.zeros(max(lay.nslots, 1), np.int32)
+    slot_vals = np.zeros(max(lay.vals_bytes, 1), np.uint8)
+    vals = None if values is None else np.ascontiguousarray(values)
+    _check(lib.mc_pack_host(M, K, V, lhs_bits, _p32(rp), _p32(ci),
+                            None if vals is None else vals.ctypes.data, _p32(panel_ptr), _p32(slot_idx),
+                            slot_vals.ctypes.data), "mc_pack_host")
+    return panel_ptr, slot_idx[:lay.nslots], slot_vals[:lay.vals_bytes]
+
+
+def unpack_host(M, K, V, lhs_bits, panel_ptr, slot_idx, slot_vals):
+    pp, si = _i32(panel_ptr), _i32(slot_idx)
+    P = M // V
+    nvec = int(sum(int(pp[2 * p + 1]) - int(pp[2 * p]) for p in range(P)))
+    row_ptr = np.zeros(P + 1, np.int32)
+    col_idx = np.zeros(max(nvec, 1), np.int32)
+    values = np.zeros(max(nvec * V * max(lhs_bits, 8) // 8, 1), np.uint8)
+    sv = np.ascontiguousarray(slot_vals, dtype=np.uint8)
+    _check(lib.mc_unpack_host(M, K, V, lhs_bits, _p32(pp), _p32(si), sv.ctypes.data if lhs_bits else None,
+                              _p32(row_ptr), _p32(col_idx), values.ctypes.data), "mc_unpack_host")
+    return row_ptr, col_idx[:nvec], values[:nvec * V * lhs_bits // 8]
+
+
+# ---------------------------------------------------------------- device objects ----
+class SparseMatrix:
+    """Device-resident vector-sparse matrix or mask (owns an mc_mat handle)."""
+
+    def __init__(self, M, K, V, row_ptr, col_idx, values=None, lhs_bits=0):
+        rp, ci = _i32(row_ptr), _i32(col_idx)
+        if M > 0 and V > 0 and M % V == 0 and rp.shape[0] != M // V + 1:
+            raise MagicubeError(MC_EINVAL, "SparseMatrix(row_ptr length)")
+        if rp.shape[0] and ci.shape[0] != int(rp[-1]):
+            raise MagicubeError(MC_EINVAL, "SparseMatrix(col_idx length)")
+        vals = None if values is None else np.ascontiguousarray(values)
+        if vals is not None and vals.nbytes != ci.shape[0] * V * lhs_bits // 8:
+            raise MagicubeError(MC_EINVAL, "SparseMatrix(values size)")
+        h = c_void_p()
+        _check(lib.mc_mat_create(M, K, V, lhs_bits if vals is not None else 0, _p32(rp), _p32(ci),
+                                 None if vals is None else vals.ctypes.data, _stream(), ctypes.byref(h)),
+               "mc_mat_create")
+        self.handle = h
+        self.M, self.K, self.V, self.lhs_bits = M, K, V, (lhs_bits if vals is not None else 0)
+        nvec, nslots = c_int64(), c_int64()
+        _check(lib.mc_mat_info(h, None, None, None, None, ctypes.byref(nvec), ctypes.byref(nslots)), "mc_mat_info")
+        self.nvec, self.nslots = nvec.value, nslots.value
+
+    def set_values(self, values_dev) -> None:
+        """values_dev: device tensor, nvec*V elements in interchange (vector-major) order."""
+        assert values_dev.is_cuda and values_dev.is_contiguous()
+        assert values_dev.numel() * values_dev.element_size() == self.nvec * self.V * self.lhs_bits // 8
+        _check(lib.mc_mat_set_values_device(self.handle, values_dev.data_ptr(), _stream()), "mc_mat_set_values_device")
+
+    def close(self) -> None:
+        if getattr(self, "handle", None):
+            lib.mc_mat_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def set_spmm_variant(bytes_per_row_tile: int = 0, waves: int = 0) -> None:
+    _check(lib.mc_set_spmm_variant(bytes_per_row_tile, waves), "mc_set_spmm_variant")
+
+
+def spmm(A: SparseMatrix, B, prec: str, out=None):
+    """C = A * B (int32, M x N).  B: device tensor (K, N) int8, or (K, N/2) uint8 for R4."""
+    assert B.is_cuda and B.dim() == 2 and B.stride(1) == 1
+    rbits = RHS_BITS[prec]
+    N = B.shape[1] * 8 // rbits
+    ldb = B.stride(0) * 8 // rbits
+    if out is None:
+        out = torch.empty((A.M, N), dtype=torch.int32, device=B.device)
+    assert out.is_cuda and out.dtype == torch.int32 and out.shape == (A.M, N) and out.stride(1) == 1
+    _check(lib.mc_spmm(A.handle, B.data_ptr(), N, ldb, PREC[prec], out.data_ptr(), out.stride(0), _stream()), "mc_spmm")
+    return out
+
+
+def sddmm(Q, Kmat, mask: SparseMatrix, prec: str, out=None):
+    """S (nvec*V int32, interchange order) = (Q * Kmat^T) at the mask's stored vectors."""
+    assert Q.is_cuda and Kmat.is_cuda and Q.dim() == 2 and Kmat.dim() == 2
+    assert Q.stride(1) == 1 and Kmat.stride(1) == 1 and Q.shape[1] == Kmat.shape[1]
+    bits = LHS_BITS[prec]
+    Kd = Q.shape[1] * 8 // bits
+    if out is None:
+        out = torch.empty(mask.nvec * mask.V, dtype=torch.int32, device=Q.device)
+    assert out.is_cuda and out.dtype == torch.int32 and out.numel() == mask.nvec * mask.V and out.is_contiguous()
+    _check(lib.mc_sddmm(Q.data_ptr(), Q.stride(0) * 8 // bits, Kmat.data_ptr(), Kmat.stride(0) * 8 // bits, Kd,
+                        mask.handle, PREC[prec], out.data_ptr(), _stream()), "mc_sddmm")
+    return out
+
+
+def sparse_softmax(mask: SparseMatrix, S, score_scale: float, inv_s_p: float, out=None):
+    """int8 codes of the row softmax over the stored entries; S: (batch, nvec*V) int32."""
+    assert S.is_cuda and S.dtype == torch.int32 and S.is_contiguous()
+    S2 = S.reshape(-1, mask.nvec * mask.V)
+    if out is None:
+        out = torch.empty(S2.shape, dtype=torch.int8, device=S.device)
+    assert out.is_cuda and out.dtype == torch.int8 and out.is_contiguous() and out.numel() == S2.numel()
+    _check(lib.mc_sparse_softmax(mask.handle, S2.shape[0], S2.data_ptr(), score_scale, inv_s_p, out.data_ptr(),
+                                 _stream()), "mc_sparse_softmax")
+    return out.reshape(S.shape)
+
+
+def attention_workspace_bytes(heads: int, mask: SparseMatrix) -> int:
+    return int(lib.mc_attention_workspace_bytes(heads, mask.handle))
+
+
+def sparse_attention(Q8, K8, V8, mask: SparseMatrix, s_q, s_k, s_v, s_p, out=None, workspace=None):
+    """Quantized sparse self-attention; Q8/K8/V8: (heads, L, dk) int8 device tensors."""
+    for t in (Q8, K8, V8):
+        assert t.is_cuda and t.dtype == torch.int8 and t.is_contiguous() and t.shape == Q8.shape
+    heads, L, dk = Q8.shape
+    if out is None:
+        out = torch.empty((heads, L, dk), dtype=torch.float32, device=Q8.device)
+    need = attention_workspace_bytes(heads, mask)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=Q8.device)
+    assert workspace.is_cuda and workspace.is_contiguous()
+    _check(lib.mc_sparse_attention(Q8.data_ptr(), K8.data_ptr(), V8.data_ptr(), heads, L, dk, mask.handle,
+                                   float(s_q), float(s_k), float(s_v), float(s_p), out.data_ptr(),
+                                   workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream()),
+           "mc_sparse_attention")
+    return out

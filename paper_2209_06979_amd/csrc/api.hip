@@ -1,0 +1,315 @@
+// C-ABI entry points: argument checks on the host, then kernel launches on the caller's
+// stream.  See include/magicube.h for the contract of every function.
+#include "internal.h"
+
+#include <cmath>
+#include <cstdio>
+#include <cstdlib>
+#include <new>
+#include <vector>
+
+namespace {
+
+int g_variant_bnb = 0, g_variant_waves = 0;
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline int lhs_bits_of(mc_prec p) { return p == MC_L4R4 ? 4 : (p == MC_L16R8 ? 16 : 8); }
+inline int rhs_bits_of(mc_prec p) { return (p == MC_L8R4 || p == MC_L4R4) ? 4 : 8; }
+inline bool valid_prec(int p) { return p >= MC_L8R8 && p <= MC_L16R8; }
+
+thread_local char g_detail[256] = "";
+
+// Remembers which HIP call failed and why (read back with mc_last_error_detail).
+bool hip_ok(hipError_t e, const char *what)
+{
+    if (e == hipSuccess) return true;
+    snprintf(g_detail, sizeof g_detail, "%s: %s", what, hipGetErrorString(e));
+    (void)hipGetLastError();
+    return false;
+}
+
+#define MC_HIP(call)                               \
+    do {                                           \
+        if (!hip_ok((call), #call)) return MC_EHIP; \
+    } while (0)
+
+void free_device(mc_mat *A)
+{
+    if (A->d_panel_ptr) (void)hipFree(A->d_panel_ptr);
+    if (A->d_row_ptr) (void)hipFree(A->d_row_ptr);
+    if (A->d_slot_idx) (void)hipFree(A->d_slot_idx);
+    if (A->d_vals) (void)hipFree(A->d_vals);
+}
+
+// Tile variant for a problem: wide row tiles when rows are long enough for a whole
+// 128-byte line per lane group, more waves per panel when panels hold many chunks.
+void choose_variant(const mc_mat *A, int row_bytes, bool r4, int *bnb, int *waves)
+{
+    int b = g_variant_bnb, w = g_variant_waves;
+    if (b == 0) b = (row_bytes >= 128) ? 128 : 64;
+    if (b == 256 && r4) b = 128;
+    if (w == 0) {
+        const double avg = A->P ? (double)(A->nslots / MC_CHUNK) / A->P : 0.0;
+        w = avg >= 6.0 ? 4 : (avg >= 2.5 ? 2 : 1);
+    }
+    *bnb = b;
+    *waves = w;
+}
+
+} // namespace
+
+extern "C" const char *mc_strerror(int status)
+{
+    switch (status) {
+    case MC_OK: return "ok";
+    case MC_EINVAL: return "invalid argument";
+    case MC_EUNSUPPORTED: return "unsupported precision or operation";
+    case MC_EALIGN: return "pointer or leading dimension not 16-byte aligned";
+    case MC_EHIP: return "HIP runtime error";
+    case MC_ENOMEM: return "out of memory or workspace too small";
+    case MC_ERANGE: return "value out of representable range";
+    default: return "unknown status";
+    }
+}
+
+extern "C" const char *mc_version(void) { return "0.1 gfx950"; }
+
+extern "C" const char *mc_last_error_detail(void) { return g_detail; }
+
+extern "C" int mc_set_spmm_variant(int bytes_per_row_tile, int waves)
+{
+    if (bytes_per_row_tile != 0 && bytes_per_row_tile != 64 && bytes_per_row_tile != 128 && bytes_per_row_tile != 256)
+        return MC_EINVAL;
+    if (waves != 0 && waves != 1 && waves != 2 && waves != 4) return MC_EINVAL;
+    g_variant_bnb = bytes_per_row_tile;
+    g_variant_waves = waves;
+    return MC_OK;
+}
+
+extern "C" int mc_mat_create(int M, int K, int V, int lhs_bits, const int32_t *row_ptr, const int32_t *col_idx,
+                             const void *values, void *stream, mc_mat **out)
+{
+    if (!out) return MC_EINVAL;
+    *out = nullptr;
+    if (!values) lhs_bits = 0;
+    mc_layout lay;
+    int rc = mc_layout_query(M, K, V, lhs_bits, row_ptr, &lay);
+    if (rc != MC_OK) return rc;
+
+    std::vector<int32_t> panel_ptr, slot_idx;
+    std::vector<uint8_t> vals;
+    try {
+        panel_ptr.resize((size_t)2 * lay.P);
+        slot_idx.resize((size_t)lay.nslots);
+        vals.resize((size_t)lay.vals_bytes);
+    } catch (const std::bad_alloc &) {
+        return MC_ENOMEM;
+    }
+    rc = mc_pack_host(M, K, V, lhs_bits, row_ptr, col_idx, values, panel_ptr.data(), slot_idx.data(),
+                      vals.empty() ? nullptr : vals.data());
+    if (rc != MC_OK) return rc;
+
+    mc_mat *A = new (std::nothrow) mc_mat();
+    if (!A) return MC_ENOMEM;
+    A->M = M; A->K = K; A->V = V; A->lhs_bits = lhs_bits; A->P = lay.P;
+    A->nvec = lay.nvec; A->nslots = lay.nslots; A->vals_bytes = lay.vals_bytes;
+    A->max_panel_chunks = 0;
+    for (int p = 0; p < lay.P; ++p) {
+        const int c = (row_ptr[p + 1] - row_ptr[p] + MC_CHUNK - 1) / MC_CHUNK;
+        if (c > A->max_panel_chunks) A->max_panel_chunks = c;
+    }
+    A->d_panel_ptr = A->d_row_ptr = A->d_slot_idx = nullptr;
+    A->d_vals = nullptr;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+#define MC_TRY(call) (ok = ok && hip_ok((call), #call))
+    bool ok = true;
+    MC_TRY(hipGetDevice(&A->device));
+    // the index array gets one spare chunk so that 16-byte index reads never leave it
+    MC_TRY(hipMalloc(&A->d_panel_ptr, sizeof(int32_t) * 2 * (size_t)(lay.P + 1)));
+    MC_TRY(hipMalloc(&A->d_row_ptr, sizeof(int32_t) * (size_t)(lay.P + 1)));
+    MC_TRY(hipMalloc(&A->d_slot_idx, sizeof(int32_t) * (size_t)(lay.nslots + MC_CHUNK)));
+    if (lay.vals_bytes) MC_TRY(hipMalloc(&A->d_vals, (size_t)lay.vals_bytes));
+    MC_TRY(hipMemcpyAsync(A->d_panel_ptr, panel_ptr.data(), sizeof(int32_t) * 2 * (size_t)lay.P, hipMemcpyHostToDevice, s));
+    MC_TRY(hipMemcpyAsync(A->d_row_ptr, row_ptr, sizeof(int32_t) * (size_t)(lay.P + 1), hipMemcpyHostToDevice, s));
+    if (lay.nslots)
+        MC_TRY(hipMemcpyAsync(A->d_slot_idx, slot_idx.data(), sizeof(int32_t) * (size_t)lay.nslots, hipMemcpyHostToDevice, s));
+    if (lay.vals_bytes)
+        MC_TRY(hipMemcpyAsync(A->d_vals, vals.data(), (size_t)lay.vals_bytes, hipMemcpyHostToDevice, s));
+    MC_TRY(hipStreamSynchronize(s)); // host staging buffers die at return
+#undef MC_TRY
+    if (!ok) {
+        free_device(A);
+        delete A;
+        return MC_EHIP;
+    }
+    *out = A;
+    return MC_OK;
+}
+
+extern "C" void mc_mat_destroy(mc_mat *A)
+{
+    if (!A) return;
+    free_device(A);
+    delete A;
+}
+
+extern "C" int mc_mat_info(const mc_mat *A, int *M, int *K, int *V, int *lhs_bits, int64_t *nvec, int64_t *nslots)
+{
+    if (!A) return MC_EINVAL;
+    if (M) *M = A->M;
+    if (K) *K = A->K;
+    if (V) *V = A->V;
+    if (lhs_bits) *lhs_bits = A->lhs_bits;
+    if (nvec) *nvec = A->nvec;
+    if (nslots) *nslots = A->nslots;
+    return MC_OK;
+}
+
+extern "C" int mc_mat_set_values_device(mc_mat *A, const void *values_dev, void *stream)
+{
+    if (!A || !values_dev) return MC_EINVAL;
+    if (A->lhs_bits == 0 || !A->d_vals) return MC_EINVAL;
+    RepackArgs r;
+    r.panel_ptr = A->d_panel_ptr; r.row_ptr = A->d_row_ptr;
+    r.src = static_cast<const uint8_t *>(values_dev); r.src_batch_stride = 0;
+    r.dst = A->d_vals; r.dst_batch_stride = 0;
+    r.P = A->P; r.V = A->V; r.bits = A->lhs_bits; r.batch = 1;
+    MC_HIP(launch_repack(r, static_cast<hipStream_t>(stream)));
+    return MC_OK;
+}
+
+extern "C" int mc_spmm(const mc_mat *A, const void *B_dev, int N, int ldb, mc_prec prec, int32_t *C_dev, int ldc,
+                       void *stream)
+{
+    if (!A || !B_dev || !C_dev) return MC_EINVAL;
+    if (!valid_prec((int)prec)) return MC_EUNSUPPORTED;
+    if (!A->d_vals || A->lhs_bits != lhs_bits_of(prec)) return MC_EINVAL;
+    const int rb = rhs_bits_of(prec);
+    if (N <= 0 || N % (128 / rb) != 0) return MC_EINVAL; // whole 16-byte pieces of a row
+    if (ldb < N || ldc < N) return MC_EINVAL;
+    if (((int64_t)ldb * rb / 8) % 16 != 0 || ldc % 4 != 0) return MC_EALIGN;
+    if (!aligned16(B_dev) || !aligned16(C_dev)) return MC_EALIGN;
+    if (rb == 4 && A->K > 131072) return MC_EUNSUPPORTED;
+
+    SpmmArgs a;
+    a.panel_ptr = A->d_panel_ptr; a.slot_idx = A->d_slot_idx;
+    a.vals = A->d_vals; a.vals_batch_stride = 0;
+    a.B = static_cast<const uint8_t *>(B_dev); a.ldb_bytes = (int64_t)ldb * rb / 8; a.B_batch_stride = 0;
+    a.row_bytes = N * rb / 8;
+    a.C = C_dev; a.ldc = ldc; a.C_batch_stride = 0;
+    a.P = A->P; a.V = A->V; a.batch = 1; a.float_out = 0; a.out_scale = 1.f;
+    int bnb, waves;
+    choose_variant(A, a.row_bytes, rb == 4, &bnb, &waves);
+    MC_HIP(launch_spmm(prec, a, bnb, waves, static_cast<hipStream_t>(stream)));
+    return MC_OK;
+}
+
+extern "C" int mc_sddmm(const void *Q_dev, int ldq, const void *Kmat_dev, int ldk, int Kd, const mc_mat *mask,
+                        mc_prec prec, int32_t *S_dev, void *stream)
+{
+    if (!Q_dev || !Kmat_dev || !mask || !S_dev) return MC_EINVAL;
+    if (!valid_prec((int)prec)) return MC_EUNSUPPORTED;
+    if (prec != MC_L8R8 && prec != MC_L4R4) return MC_EUNSUPPORTED;
+    const int bits = lhs_bits_of(prec);
+    if (Kd <= 0 || Kd % (128 / bits) != 0 || ldq < Kd || ldk < Kd) return MC_EINVAL;
+    if (((int64_t)ldq * bits / 8) % 16 != 0 || ((int64_t)ldk * bits / 8) % 16 != 0) return MC_EALIGN;
+    if (!aligned16(Q_dev) || !aligned16(Kmat_dev) || !aligned16(S_dev)) return MC_EALIGN;
+
+    SddmmArgs a;
+    a.panel_ptr = mask->d_panel_ptr; a.row_ptr = mask->d_row_ptr; a.slot_idx = mask->d_slot_idx;
+    a.Q = static_cast<const uint8_t *>(Q_dev); a.ldq_bytes = (int64_t)ldq * bits / 8; a.Q_batch_stride = 0;
+    a.Kmat = static_cast<const uint8_t *>(Kmat_dev); a.ldk_bytes = (int64_t)ldk * bits / 8; a.K_batch_stride = 0;
+    a.row_bytes = Kd * bits / 8;
+    a.S = S_dev; a.S_batch_stride = 0;
+    a.P = mask->P; a.V = mask->V; a.batch = 1;
+    MC_HIP(launch_sddmm(bits == 4, a, static_cast<hipStream_t>(stream)));
+    return MC_OK;
+}
+
+extern "C" int mc_sparse_softmax(const mc_mat *mask, int batch, const int32_t *S_dev, float score_scale,
+                                 float inv_s_p, int8_t *codes_dev, void *stream)
+{
+    if (!mask || !S_dev || !codes_dev || batch <= 0) return MC_EINVAL;
+    if (!std::isfinite(score_scale) || !std::isfinite(inv_s_p)) return MC_EINVAL;
+    SoftmaxArgs a;
+    a.row_ptr = mask->d_row_ptr; a.S = S_dev; a.codes = codes_dev;
+    a.batch_stride = mask->nvec * mask->V;
+    a.score_scale = score_scale; a.inv_s_p = inv_s_p;
+    a.P = mask->P; a.V = mask->V; a.batch = batch;
+    MC_HIP(launch_softmax(a, static_cast<hipStream_t>(stream)));
+    return MC_OK;
+}
+
+namespace {
+inline size_t round256(size_t x) { return (x + 255) / 256 * 256; }
+struct AttnWs { size_t scores, codes, vals, total; };
+AttnWs attn_layout(int heads, const mc_mat *mask)
+{
+    AttnWs w;
+    const size_t nnz = (size_t)mask->nvec * mask->V;
+    w.scores = 0;
+    w.codes = w.scores + round256((size_t)heads * nnz * sizeof(int32_t));
+    w.vals = w.codes + round256((size_t)heads * nnz);
+    w.total = w.vals + round256((size_t)heads * (size_t)mask->nslots * mask->V);
+    return w;
+}
+} // namespace
+
+extern "C" size_t mc_attention_workspace_bytes(int heads, const mc_mat *mask)
+{
+    if (!mask || heads <= 0) return 0;
+    return attn_layout(heads, mask).total;
+}
+
+extern "C" int mc_sparse_attention(const int8_t *Q_dev, const int8_t *Km_dev, const int8_t *Vm_dev, int heads, int L,
+                                   int dk, const mc_mat *mask, float s_q, float s_k, float s_v, float s_p,
+                                   float *O_dev, void *workspace_dev, size_t workspace_bytes, void *stream)
+{
+    if (!Q_dev || !Km_dev || !Vm_dev || !mask || !O_dev || !workspace_dev) return MC_EINVAL;
+    if (heads <= 0 || L <= 0 || dk <= 0 || dk % 16 != 0) return MC_EINVAL;
+    if (mask->M != L || mask->K != L || mask->V != 8) return MC_EINVAL;
+    if (!(s_p > 0.f) || !std::isfinite(s_q * s_k * s_v / s_p)) return MC_EINVAL;
+    if (!aligned16(Q_dev) || !aligned16(Km_dev) || !aligned16(Vm_dev) || !aligned16(O_dev)) return MC_EALIGN;
+    if ((reinterpret_cast<uintptr_t>(workspace_dev) & 255u) != 0) return MC_EALIGN;
+    const AttnWs ws = attn_layout(heads, mask);
+    if (workspace_bytes < ws.total) return MC_ENOMEM;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    uint8_t *wsb = static_cast<uint8_t *>(workspace_dev);
+    int32_t *scores = reinterpret_cast<int32_t *>(wsb + ws.scores);
+    int8_t *codes = reinterpret_cast<int8_t *>(wsb + ws.codes);
+    uint8_t *pvals = wsb + ws.vals;
+    const int64_t nnz = mask->nvec * mask->V;
+    const int64_t head_elems = (int64_t)L * dk;
+
+    SddmmArgs d;
+    d.panel_ptr = mask->d_panel_ptr; d.row_ptr = mask->d_row_ptr; d.slot_idx = mask->d_slot_idx;
+    d.Q = reinterpret_cast<const uint8_t *>(Q_dev); d.ldq_bytes = dk; d.Q_batch_stride = head_elems;
+    d.Kmat = reinterpret_cast<const uint8_t *>(Km_dev); d.ldk_bytes = dk; d.K_batch_stride = head_elems;
+    d.row_bytes = dk; d.S = scores; d.S_batch_stride = nnz;
+    d.P = mask->P; d.V = 8; d.batch = heads;
+    MC_HIP(launch_sddmm(false, d, s));
+
+    SoftmaxArgs f;
+    f.row_ptr = mask->d_row_ptr; f.S = scores; f.codes = codes; f.batch_stride = nnz;
+    f.score_scale = s_q * s_k / std::sqrt((float)dk); f.inv_s_p = 1.f / s_p;
+    f.P = mask->P; f.V = 8; f.batch = heads;
+    MC_HIP(launch_softmax(f, s));
+
+    RepackArgs r;
+    r.panel_ptr = mask->d_panel_ptr; r.row_ptr = mask->d_row_ptr;
+    r.src = reinterpret_cast<const uint8_t *>(codes); r.src_batch_stride = nnz;
+    r.dst = pvals; r.dst_batch_stride = mask->nslots * 8;
+    r.P = mask->P; r.V = 8; r.bits = 8; r.batch = heads;
+    MC_HIP(launch_repack(r, s));
+
+    SpmmArgs m;
+    m.panel_ptr = mask->d_panel_ptr; m.slot_idx = mask->d_slot_idx;
+    m.vals = pvals; m.vals_batch_stride = mask->nslots * 8;
+    m.B = reinterpret_cast<const uint8_t *>(Vm_dev); m.ldb_bytes = dk; m.B_batch_stride = head_elems;
+    m.row_bytes = dk; m.C = O_dev; m.ldc = dk; m.C_batch_stride = head_elems;
+    m.P = mask->P; m.V = 8; m.batch = heads; m.float_out = 1; m.out_scale = s_p * s_v;
+    int bnb, waves;
+    choose_variant(mask, m.row_bytes, false, &bnb, &waves);
+    MC_HIP(launch_spmm(MC_L8R8, m, bnb, waves, s));
+    return MC_OK;
+}

@@ -1,0 +1,163 @@
+// Host-side format builder: interchange BCRS (V x 1 blocks) <-> device panel format.
+//
+// The device format follows the idea of SR-BCRS (paper, Section 4.1): inside a row
+// panel the stored vectors are grouped into strides whose length equals the reduction
+// depth of the matrix instruction, the last stride is zero-padded, values are stored
+// row-major inside a stride, and each panel carries two pointers (aligned start, real
+// end).  Here a stride ("chunk") is 64 vectors = one v_mfma_i32_16x16x64_i8, and it is
+// cut into 4 sub-strides of 16 vectors because one MFMA lane group consumes 16
+// consecutive reduction bytes of one row.
+#include "internal.h"
+
+#include <cstring>
+
+namespace {
+
+inline int64_t pad_to_chunk(int64_t n) { return (n + MC_CHUNK - 1) / MC_CHUNK * MC_CHUNK; }
+
+// bytes of one chunk of packed values
+inline int64_t chunk_value_bytes(int V, int bits) { return (int64_t)MC_CHUNK * V * bits / 8; }
+
+// signed int8 planes of a 16-bit value: a = 256 * hi + lo, lo in [-128, 127]
+inline bool split_balanced(int a, int8_t *hi, int8_t *lo)
+{
+    int h = (a + 128) >> 8; // arithmetic shift, floor
+    int l = a - h * 256;
+    if (h < -128 || h > 127) return false;
+    *hi = (int8_t)h;
+    *lo = (int8_t)l;
+    return true;
+}
+
+inline int nibble_at(const uint8_t *bytes, int64_t elem)
+{
+    uint8_t b = bytes[elem >> 1];
+    return (elem & 1) ? (b >> 4) : (b & 15);
+}
+
+} // namespace
+
+extern "C" int mc_layout_query(int M, int K, int V, int lhs_bits, const int32_t *row_ptr, mc_layout *out)
+{
+    if (!row_ptr || !out) return MC_EINVAL;
+    if (M <= 0 || K <= 0) return MC_EINVAL;
+    if (V != 2 && V != 4 && V != 8) return MC_EINVAL;
+    if (M % V != 0) return MC_EINVAL;
+    if (lhs_bits != 0 && lhs_bits != 4 && lhs_bits != 8 && lhs_bits != 16) return MC_EINVAL;
+    const int P = M / V;
+    if (row_ptr[0] != 0) return MC_EINVAL;
+    int64_t nslots = 0;
+    for (int p = 0; p < P; ++p) {
+        const int64_t n = (int64_t)row_ptr[p + 1] - row_ptr[p];
+        if (n < 0 || n > K) return MC_EINVAL;
+        nslots += pad_to_chunk(n);
+    }
+    if (nslots > (int64_t)INT32_MAX - MC_CHUNK) return MC_EINVAL;
+    out->P = P;
+    out->nvec = row_ptr[P];
+    out->nslots = nslots;
+    out->vals_bytes = lhs_bits ? (nslots / MC_CHUNK) * chunk_value_bytes(V, lhs_bits) : 0;
+    return MC_OK;
+}
+
+extern "C" int mc_pack_host(int M, int K, int V, int lhs_bits, const int32_t *row_ptr, const int32_t *col_idx,
+                            const void *values, int32_t *panel_ptr, int32_t *slot_idx, void *slot_vals)
+{
+    mc_layout lay;
+    int rc = mc_layout_query(M, K, V, lhs_bits, row_ptr, &lay);
+    if (rc != MC_OK) return rc;
+    if (!panel_ptr || (lay.nslots && !slot_idx) || (lay.nvec && !col_idx)) return MC_EINVAL;
+    const bool with_vals = lhs_bits != 0 && values != nullptr;
+    if (with_vals && lay.vals_bytes && !slot_vals) return MC_EINVAL;
+
+    // pattern
+    int64_t slot0 = 0;
+    for (int p = 0; p < lay.P; ++p) {
+        const int64_t lo = row_ptr[p], n = (int64_t)row_ptr[p + 1] - lo;
+        panel_ptr[2 * p] = (int32_t)slot0;
+        panel_ptr[2 * p + 1] = (int32_t)(slot0 + n);
+        int32_t prev = -1;
+        for (int64_t i = 0; i < n; ++i) {
+            const int32_t c = col_idx[lo + i];
+            if (c <= prev || c >= K) return MC_EINVAL;
+            slot_idx[slot0 + i] = c;
+            prev = c;
+        }
+        for (int64_t i = n; i < pad_to_chunk(n); ++i) slot_idx[slot0 + i] = prev; // n > 0 here
+        slot0 += pad_to_chunk(n);
+    }
+    if (!with_vals) return MC_OK;
+
+    std::memset(slot_vals, 0, (size_t)lay.vals_bytes);
+    uint8_t *dst = static_cast<uint8_t *>(slot_vals);
+    const int64_t cbytes = chunk_value_bytes(V, lhs_bits);
+    for (int p = 0; p < lay.P; ++p) {
+        const int64_t lo = row_ptr[p], n = (int64_t)row_ptr[p + 1] - lo;
+        const int64_t s0 = panel_ptr[2 * p];
+        for (int64_t i = 0; i < n; ++i) {
+            const int64_t s = s0 + i;
+            uint8_t *chunk = dst + (s / MC_CHUNK) * cbytes;
+            const int g = (int)(s % MC_CHUNK) / 16, b = (int)(s % 16);
+            for (int v = 0; v < V; ++v) {
+                const int64_t e = (lo + i) * V + v; // element in interchange order
+                if (lhs_bits == 8) {
+                    chunk[g * (16 * V) + v * 16 + b] = static_cast<const uint8_t *>(values)[e];
+                } else if (lhs_bits == 16) {
+                    int8_t hi, l8;
+                    if (!split_balanced(static_cast<const int16_t *>(values)[e], &hi, &l8)) return MC_ERANGE;
+                    chunk[g * (32 * V) + v * 16 + b] = (uint8_t)hi;
+                    chunk[g * (32 * V) + 16 * V + v * 16 + b] = (uint8_t)l8;
+                } else { // 4 bits
+                    const int nib = nibble_at(static_cast<const uint8_t *>(values), e);
+                    uint8_t *byte = &chunk[g * (8 * V) + v * 8 + (b & 7)];
+                    *byte |= (uint8_t)((b < 8) ? nib : (nib << 4));
+                }
+            }
+        }
+    }
+    return MC_OK;
+}
+
+extern "C" int mc_unpack_host(int M, int K, int V, int lhs_bits, const int32_t *panel_ptr,
+                              const int32_t *slot_idx, const void *slot_vals, int32_t *row_ptr,
+                              int32_t *col_idx, void *values)
+{
+    if (M <= 0 || K <= 0 || (V != 2 && V != 4 && V != 8) || M % V) return MC_EINVAL;
+    if (lhs_bits != 0 && lhs_bits != 4 && lhs_bits != 8 && lhs_bits != 16) return MC_EINVAL;
+    if (!panel_ptr || !row_ptr) return MC_EINVAL;
+    const int P = M / V;
+    const uint8_t *src = static_cast<const uint8_t *>(slot_vals);
+    const int64_t cbytes = lhs_bits ? chunk_value_bytes(V, lhs_bits) : 0;
+    const bool with_vals = lhs_bits != 0 && slot_vals != nullptr && values != nullptr;
+    int64_t out = 0;
+    row_ptr[0] = 0;
+    for (int p = 0; p < P; ++p) {
+        const int64_t s0 = panel_ptr[2 * p], n = (int64_t)panel_ptr[2 * p + 1] - s0;
+        if (n < 0 || s0 % MC_CHUNK) return MC_EINVAL;
+        for (int64_t i = 0; i < n; ++i, ++out) {
+            const int64_t s = s0 + i;
+            col_idx[out] = slot_idx[s];
+            if (!with_vals) continue;
+            const uint8_t *chunk = src + (s / MC_CHUNK) * cbytes;
+            const int g = (int)(s % MC_CHUNK) / 16, b = (int)(s % 16);
+            for (int v = 0; v < V; ++v) {
+                const int64_t e = out * V + v;
+                if (lhs_bits == 8) {
+                    static_cast<uint8_t *>(values)[e] = chunk[g * (16 * V) + v * 16 + b];
+                } else if (lhs_bits == 16) {
+                    const int hi = (int8_t)chunk[g * (32 * V) + v * 16 + b];
+                    const int l8 = (int8_t)chunk[g * (32 * V) + 16 * V + v * 16 + b];
+                    static_cast<int16_t *>(values)[e] = (int16_t)(hi * 256 + l8);
+                } else {
+                    const uint8_t byte = chunk[g * (8 * V) + v * 8 + (b & 7)];
+                    const int nib = (b < 8) ? (byte & 15) : (byte >> 4);
+                    uint8_t *o = &static_cast<uint8_t *>(values)[e >> 1];
+                    if (e & 1) *o = (uint8_t)((*o & 0x0F) | (nib << 4));
+                    else *o = (uint8_t)((*o & 0xF0) | nib);
+                }
+            }
+        }
+        row_ptr[p + 1] = (int32_t)out;
+    }
+    return MC_OK;
+}

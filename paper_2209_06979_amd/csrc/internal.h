@@ -1,0 +1,74 @@
+// Internal declarations shared by the translation units of the library (not installed).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/magicube.h"
+
+struct mc_mat {
+    int M, K, V, lhs_bits, P;
+    int64_t nvec, nslots, vals_bytes;
+    int max_panel_chunks;      // longest panel, in chunks of 64 vectors
+    int device;                // HIP device the buffers live on
+    int32_t *d_panel_ptr;      // 2*P: chunk-aligned first slot, real end slot
+    int32_t *d_row_ptr;        // P+1: interchange row pointers (vector offsets)
+    int32_t *d_slot_idx;       // nslots
+    uint8_t *d_vals;           // vals_bytes (null for a pattern-only mask)
+};
+
+// One SpMM launch (optionally a batch of problems sharing the sparsity pattern).
+struct SpmmArgs {
+    const int32_t *panel_ptr;
+    const int32_t *slot_idx;
+    const uint8_t *vals;
+    int64_t vals_batch_stride; // bytes
+    const uint8_t *B;
+    int64_t ldb_bytes;
+    int64_t B_batch_stride;    // bytes
+    int row_bytes;             // bytes of one B row that take part (N * bits / 8)
+    void *C;                   // int32 or float
+    int64_t ldc;               // elements
+    int64_t C_batch_stride;    // elements
+    int P, V, batch;
+    int float_out;             // 1: write float(acc) * out_scale
+    float out_scale;
+};
+
+struct SddmmArgs {
+    const int32_t *panel_ptr;
+    const int32_t *row_ptr;
+    const int32_t *slot_idx;
+    const uint8_t *Q;
+    int64_t ldq_bytes, Q_batch_stride;
+    const uint8_t *Kmat;
+    int64_t ldk_bytes, K_batch_stride;
+    int row_bytes;             // Kd * bits / 8
+    int32_t *S;
+    int64_t S_batch_stride;    // elements
+    int P, V, batch;
+};
+
+struct SoftmaxArgs {
+    const int32_t *row_ptr;
+    const int32_t *S;
+    int8_t *codes;
+    int64_t batch_stride;      // elements (nvec * V)
+    float score_scale, inv_s_p;
+    int P, V, batch;
+};
+
+struct RepackArgs {
+    const int32_t *panel_ptr;
+    const int32_t *row_ptr;
+    const uint8_t *src;        // interchange order values
+    int64_t src_batch_stride;  // bytes
+    uint8_t *dst;              // device-format values
+    int64_t dst_batch_stride;  // bytes
+    int P, V, bits, batch;
+};
+
+hipError_t launch_spmm(mc_prec prec, const SpmmArgs &a, int bnb, int waves, hipStream_t s);
+hipError_t launch_sddmm(bool int4, const SddmmArgs &a, hipStream_t s);
+hipError_t launch_softmax(const SoftmaxArgs &a, hipStream_t s);
+hipError_t launch_repack(const RepackArgs &a, hipStream_t s);

@@ -1,0 +1,227 @@
+// SDDMM, sparse softmax and value-repack kernels for gfx950.
+//
+// SDDMM (paper, Section 4.3): a workgroup owns one row panel of the mask.  The panel's
+// V rows of Q are the row operand of v_mfma_i32_16x16x64_i8 and stay in registers for
+// the whole panel (the paper keeps this block in shared memory for its warps); the rows
+// of Kmat named by 16 consecutive mask vectors are the column operand.  Both operands
+// are contiguous along the reduction dimension, so each lane loads its 16 reduction
+// bytes straight from memory and no transpose is needed (Section 4.3.1).  Lane group
+// g = lane/16 covers bytes 64*kc + 16*g .. +15 of a row on both sides.
+// The output is written in interchange (BCRS) order: V consecutive int32 per vector.
+#include "internal.h"
+
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v2i __attribute__((ext_vector_type(2)));
+
+constexpr int SDDMM_WAVES = 4;
+constexpr int NIBBLE_HI = (int)0xF0F0F0F0;
+
+// Packed int4 -> two int8 operands holding 16 x the signed nibbles (even / odd elements).
+__device__ __forceinline__ void widen4(v4i x, v4i &even, v4i &odd)
+{
+    const v4i m = {NIBBLE_HI, NIBBLE_HI, NIBBLE_HI, NIBBLE_HI};
+    even = (x << 4) & m;
+    odd = x & m;
+}
+
+// KC = number of 64-byte steps along a row kept in registers (0: any length, Q re-read).
+template <bool R4, int KC>
+__global__ __launch_bounds__(64 * SDDMM_WAVES) void sddmm_kernel(SddmmArgs a)
+{
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int j = lane & 15, g = lane >> 4;
+    const int panel = blockIdx.x, batch = blockIdx.y;
+    const int s0 = a.panel_ptr[2 * panel], n = a.panel_ptr[2 * panel + 1] - s0;
+    const int ntile = (n + 15) / 16;
+    const int64_t out0 = (int64_t)batch * a.S_batch_stride + (int64_t)a.row_ptr[panel] * a.V;
+    const uint8_t *Q = a.Q + (int64_t)batch * a.Q_batch_stride + (int64_t)(panel * a.V + j) * a.ldq_bytes + g * 16;
+    const uint8_t *Km = a.Kmat + (int64_t)batch * a.K_batch_stride + g * 16;
+    const int kc_n = (a.row_bytes + 63) / 64;
+    const bool qrow = j < a.V;
+
+    v4i qf[KC > 0 ? KC : 1];
+    if (KC > 0) {
+#pragma unroll
+        for (int kc = 0; kc < KC; ++kc) {
+            qf[kc] = (v4i){0, 0, 0, 0};
+            if (qrow && kc * 64 + g * 16 < a.row_bytes) qf[kc] = *reinterpret_cast<const v4i *>(Q + kc * 64);
+        }
+    }
+
+    for (int t = w; t < ntile; t += SDDMM_WAVES) {
+        const int slot = t * 16 + j;
+        const int row = a.slot_idx[s0 + slot]; // padded slots name a valid row
+        const uint8_t *kr = Km + (int64_t)row * a.ldk_bytes;
+        v4i acc = {0, 0, 0, 0};
+        if (KC > 0) {
+            v4i kf[KC > 0 ? KC : 1];
+#pragma unroll
+            for (int kc = 0; kc < KC; ++kc) {
+                kf[kc] = (v4i){0, 0, 0, 0};
+                if (kc * 64 + g * 16 < a.row_bytes) kf[kc] = *reinterpret_cast<const v4i *>(kr + kc * 64);
+            }
+#pragma unroll
+            for (int kc = 0; kc < KC; ++kc) {
+                if (R4) {
+                    v4i qe, qo, ke, ko;
+                    widen4(qf[kc], qe, qo);
+                    widen4(kf[kc], ke, ko);
+                    acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(qe, ke, acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(qo, ko, acc, 0, 0, 0);
+                } else {
+                    acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(qf[kc], kf[kc], acc, 0, 0, 0);
+                }
+            }
+        } else {
+            for (int kc = 0; kc < kc_n; ++kc) {
+                v4i q = {0, 0, 0, 0}, k = {0, 0, 0, 0};
+                if (kc * 64 + g * 16 < a.row_bytes) {
+                    k = *reinterpret_cast<const v4i *>(kr + kc * 64);
+                    if (qrow) q = *reinterpret_cast<const v4i *>(Q + kc * 64);
+                }
+                if (R4) {
+                    v4i qe, qo, ke, ko;
+                    widen4(q, qe, qo);
+                    widen4(k, ke, ko);
+                    acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(qe, ke, acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(qo, ko, acc, 0, 0, 0);
+                } else {
+                    acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(q, k, acc, 0, 0, 0);
+                }
+            }
+        }
+        if (R4) acc = acc >> 8; // both operands carried a factor 16
+        // accumulator register r of lane (j, g) is row 4g + r of vector `slot`
+        if (slot < n && 4 * g < a.V) {
+            int32_t *o = a.S + out0 + (int64_t)slot * a.V + 4 * g;
+            if (a.V >= 4) *reinterpret_cast<v4i *>(o) = acc;
+            else *reinterpret_cast<v2i *>(o) = (v2i){acc.x, acc.y};
+        }
+    }
+}
+
+// ---- sparse softmax + int8 re-quantisation (Section 5.3) ---------------------------
+// One workgroup per (panel, batch).  Thread t owns elements t, t+256, ... of the panel's
+// contiguous score block; 256 % V == 0, so a thread always stays in row v = t % V.
+__global__ __launch_bounds__(256) void softmax_kernel(SoftmaxArgs a)
+{
+    __shared__ float red[256];
+    const int tid = threadIdx.x, panel = blockIdx.x, batch = blockIdx.y;
+    const int V = a.V, v = tid % V;
+    const int64_t base = (int64_t)batch * a.batch_stride + (int64_t)a.row_ptr[panel] * V;
+    const int cnt = (a.row_ptr[panel + 1] - a.row_ptr[panel]) * V;
+    const int32_t *S = a.S + base;
+
+    float m = -INFINITY;
+    for (int e = tid; e < cnt; e += 256) m = fmaxf(m, (float)S[e] * a.score_scale);
+    red[tid] = m;
+    __syncthreads();
+    m = -INFINITY;
+    for (int t = v; t < 256; t += V) m = fmaxf(m, red[t]);
+    __syncthreads();
+
+    float sum = 0.f;
+    for (int e = tid; e < cnt; e += 256) sum += expf((float)S[e] * a.score_scale - m);
+    red[tid] = sum;
+    __syncthreads();
+    sum = 0.f;
+    for (int t = v; t < 256; t += V) sum += red[t];
+
+    int8_t *codes = a.codes + base;
+    for (int e = tid; e < cnt; e += 256) {
+        const float p = expf((float)S[e] * a.score_scale - m) / sum;
+        const float q = fminf(fmaxf(rintf(p * a.inv_s_p), 0.f), 127.f);
+        codes[e] = (int8_t)(int)q;
+    }
+}
+
+// ---- interchange-order values -> device panel format -------------------------------
+// One workgroup per (panel, batch); a thread handles one padded slot (8/16 bit) or the
+// slot pair (b, b+8) that shares bytes (4 bit).
+__global__ __launch_bounds__(256) void repack_kernel(RepackArgs a)
+{
+    const int panel = blockIdx.x, batch = blockIdx.y, V = a.V;
+    const int s0 = a.panel_ptr[2 * panel], n = a.panel_ptr[2 * panel + 1] - s0;
+    const int npad = (n + MC_CHUNK - 1) / MC_CHUNK * MC_CHUNK;
+    const uint8_t *src = a.src + (int64_t)batch * a.src_batch_stride;
+    uint8_t *dst = a.dst + (int64_t)batch * a.dst_batch_stride;
+    const int64_t vec0 = a.row_ptr[panel];
+    if (a.bits == 8 || a.bits == 16) {
+        const int cbytes = MC_CHUNK * V * a.bits / 8;
+        for (int i = threadIdx.x; i < npad; i += 256) {
+            const int s = s0 + i, g = (i % MC_CHUNK) / 16, b = i % 16;
+            uint8_t *chunk = dst + (int64_t)(s / MC_CHUNK) * cbytes;
+            for (int v = 0; v < V; ++v) {
+                if (a.bits == 8) {
+                    chunk[g * (16 * V) + v * 16 + b] = (i < n) ? src[(vec0 + i) * V + v] : (uint8_t)0;
+                } else {
+                    const int x = (i < n) ? reinterpret_cast<const int16_t *>(src)[(vec0 + i) * V + v] : 0;
+                    const int hi = (x + 128) >> 8, lo = x - hi * 256;
+                    chunk[g * (32 * V) + v * 16 + b] = (uint8_t)hi;
+                    chunk[g * (32 * V) + 16 * V + v * 16 + b] = (uint8_t)lo;
+                }
+            }
+        }
+    } else { // 4 bits
+        const int cbytes = MC_CHUNK * V / 2;
+        for (int i2 = threadIdx.x; i2 < npad / 2; i2 += 256) {
+            // pair index i2 -> (chunk, g, b < 8): slots i_lo = .. + b and i_hi = i_lo + 8
+            const int ch = i2 / 32, g = (i2 % 32) / 8, b = i2 % 8;
+            const int i_lo = ch * MC_CHUNK + g * 16 + b, i_hi = i_lo + 8;
+            uint8_t *chunk = dst + (int64_t)(s0 / MC_CHUNK + ch) * cbytes;
+            for (int v = 0; v < V; ++v) {
+                int nl = 0, nh = 0;
+                if (i_lo < n) {
+                    const int64_t e = (vec0 + i_lo) * V + v;
+                    nl = (src[e >> 1] >> ((e & 1) * 4)) & 15;
+                }
+                if (i_hi < n) {
+                    const int64_t e = (vec0 + i_hi) * V + v;
+                    nh = (src[e >> 1] >> ((e & 1) * 4)) & 15;
+                }
+                chunk[g * (8 * V) + v * 8 + b] = (uint8_t)(nl | (nh << 4));
+            }
+        }
+    }
+}
+
+} // namespace
+
+hipError_t launch_sddmm(bool int4, const SddmmArgs &a, hipStream_t s)
+{
+    if (a.P == 0 || a.batch == 0) return hipSuccess;
+    dim3 grid((unsigned)a.P, (unsigned)a.batch), block(64 * SDDMM_WAVES);
+    const int kc = (a.row_bytes + 63) / 64;
+#define MC_SDDMM(R4, KC) hipLaunchKernelGGL((sddmm_kernel<R4, KC>), grid, block, 0, s, a)
+    if (int4) {
+        if (kc == 1) MC_SDDMM(true, 1);
+        else if (kc == 2) MC_SDDMM(true, 2);
+        else if (kc <= 4) MC_SDDMM(true, 4);
+        else MC_SDDMM(true, 0);
+    } else {
+        if (kc == 1) MC_SDDMM(false, 1);
+        else if (kc == 2) MC_SDDMM(false, 2);
+        else if (kc <= 4) MC_SDDMM(false, 4);
+        else MC_SDDMM(false, 0);
+    }
+#undef MC_SDDMM
+    return hipGetLastError();
+}
+
+hipError_t launch_softmax(const SoftmaxArgs &a, hipStream_t s)
+{
+    if (a.P == 0 || a.batch == 0) return hipSuccess;
+    dim3 grid((unsigned)a.P, (unsigned)a.batch), block(256);
+    hipLaunchKernelGGL(softmax_kernel, grid, block, 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_repack(const RepackArgs &a, hipStream_t s)
+{
+    if (a.P == 0 || a.batch == 0) return hipSuccess;
+    dim3 grid((unsigned)a.P, (unsigned)a.batch), block(256);
+    hipLaunchKernelGGL(repack_kernel, grid, block, 0, s, a);
+    return hipGetLastError();
+}

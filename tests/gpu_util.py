@@ -1,0 +1,51 @@
+"""Helpers for the GPU parity tests: run one problem through the C ABI (via the thin
+binding) and through the CPU oracle on the same seeded inputs."""
+import numpy as np
+
+
+def torch_dev(a: np.ndarray):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def run_spmm_gpu(case, variant=(0, 0)):
+    import torch
+    from paper_2209_06979_amd import binding as mc
+    bits = mc.LHS_BITS[case["prec"]]
+    A = mc.SparseMatrix(case["M"], case["K"], case["V"], case["row_ptr"], case["col_idx"], case["values"], bits)
+    mc.set_spmm_variant(*variant)
+    try:
+        B = torch_dev(case["B"])
+        # poison the output so that unwritten elements are caught
+        out = torch.full((case["M"], case["N"]), -7777777, dtype=torch.int32, device="cuda")
+        C = mc.spmm(A, B, case["prec"], out=out)
+        torch.cuda.synchronize()
+        return C.cpu().numpy()
+    finally:
+        mc.set_spmm_variant(0, 0)
+        A.close()
+
+
+def run_spmm_oracle(case):
+    import oracle
+    return oracle.spmm(case["M"], case["K"], case["V"], case["row_ptr"], case["col_idx"], case["values"],
+                       case["B"], case["prec"])
+
+
+def run_sddmm_gpu(case):
+    import torch
+    from paper_2209_06979_amd import binding as mc
+    mask = mc.SparseMatrix(case["M"], case["Nc"], case["V"], case["row_ptr"], case["col_idx"])
+    try:
+        out = torch.full((mask.nvec * mask.V,), -7777777, dtype=torch.int32, device="cuda")
+        S = mc.sddmm(torch_dev(case["Q"]), torch_dev(case["Kmat"]), mask, case["prec"], out=out)
+        torch.cuda.synchronize()
+        return S.cpu().numpy()
+    finally:
+        mask.close()
+
+
+def run_sddmm_oracle(case):
+    import oracle
+    return oracle.sddmm(case["M"], case["Nc"], case["V"], case["row_ptr"], case["col_idx"], case["Q"],
+                        case["Kmat"], case["prec"])

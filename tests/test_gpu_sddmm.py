@@ -1,0 +1,140 @@
+"""GPU parity of SDDMM, sparse softmax and the attention layer against the CPU oracle."""
+import numpy as np
+import pytest
+
+from paper_2209_06979_amd import workloads as wl
+from gpu_util import run_sddmm_gpu, run_sddmm_oracle, torch_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def _check(case):
+    print(f"sddmm case M={case['M']} Nc={case['Nc']} Kd={case['Kd']} V={case['V']} {case['prec']}", flush=True)
+    got = run_sddmm_gpu(case)
+    want = run_sddmm_oracle(case)
+    assert got.shape == want.shape
+    bad = np.flatnonzero(got != want)
+    assert bad.size == 0, f"{len(bad)} mismatches, first at {bad[0]}: got {got[bad[0]]} want {want[bad[0]]}"
+
+
+@pytest.mark.parametrize("prec", ["L8R8", "L4R4"])
+@pytest.mark.parametrize("V", [2, 4, 8])
+@pytest.mark.parametrize("Kd", [64, 128, 256])
+def test_small(prec, V, Kd):
+    _check(wl.sddmm_case(16 * V, 300, Kd, V, 0.7, prec, 1000 + V + Kd))
+
+
+@pytest.mark.parametrize("prec,Kd", [("L8R8", 16), ("L8R8", 48), ("L8R8", 320), ("L8R8", 1024), ("L4R4", 32),
+                                     ("L4R4", 96), ("L4R4", 1056)])
+def test_odd_reduction_lengths(prec, Kd):
+    _check(wl.sddmm_case(64, 200, Kd, 8, 0.5, prec, 1100 + Kd))
+
+
+@pytest.mark.parametrize("prec", ["L8R8", "L4R4"])
+def test_ragged_and_empty_panels(prec):
+    V, Nc, Kd = 8, 500, 128
+    counts = [0, 1, 15, 16, 17, 63, 64, 65, 0, 129, 500, 3]
+    M = V * len(counts)
+    rp, ci = wl.ragged_pattern(M, Nc, V, counts, 81)
+    if prec == "L4R4":
+        Q, Km = wl.uniform_packed_int4((M, Kd // 2), 82), wl.uniform_packed_int4((Nc, Kd // 2), 83)
+    else:
+        Q, Km = wl.uniform_int8((M, Kd), 82), wl.uniform_int8((Nc, Kd), 83)
+    _check(dict(M=M, Nc=Nc, Kd=Kd, V=V, prec=prec, row_ptr=rp, col_idx=ci, Q=Q, Kmat=Km))
+
+
+@pytest.mark.parametrize("prec,Kd,s", [("L8R8", 64, 0.9), ("L8R8", 256, 0.7), ("L4R4", 128, 0.95), ("L4R4", 64, 0.9)])
+def test_full_size_4096(prec, Kd, s):
+    """BASELINE config 3 at full size, whole output compared."""
+    _check(wl.sddmm_case(4096, 4096, Kd, 8, s, prec, wl.seed_for(3, Kd + int(100 * s))))
+
+
+def test_unsupported_precisions():
+    import torch
+    from paper_2209_06979_amd import binding as mc
+    c = wl.sddmm_case(16, 64, 64, 8, 0.5, "L8R8", 5)
+    mask = mc.SparseMatrix(c["M"], c["Nc"], c["V"], c["row_ptr"], c["col_idx"])
+    for prec in ("L8R4", "L16R8"):
+        with pytest.raises(mc.MagicubeError) as e:
+            mc.sddmm(torch_dev(c["Q"]), torch_dev(c["Kmat"]), mask, prec)
+        assert e.value.status == mc.MC_EUNSUPPORTED
+    mask.close()
+
+
+# ------------------------------------------------------------------ softmax ----
+def _tie_ambiguous(probs, s_p):
+    """Entries whose code may legitimately differ by one step between fp32 and fp64.
+
+    x = p / s_p lies within the fp32 error of a rounding boundary.  The fp32 path makes a
+    relative error of a few 1e-6 on p (two roundings of |x| <= ~30 in the exponent, expf,
+    the sum and the division), i.e. up to ~1e-5 * x absolute on x, plus 1e-4 of slack.
+    """
+    x = probs / np.float64(s_p)
+    return np.abs((x - np.floor(x)) - 0.5) < 1e-4 + 1e-5 * x
+
+
+def test_sparse_softmax_codes():
+    import torch
+    import oracle
+    from paper_2209_06979_amd import binding as mc
+    V, L = 8, 512
+    rp, ci = wl.ragged_pattern(L, L, V, np.r_[[1, 2, 0, 64, 300], np.full(L // V - 5, 51)], 91)
+    nnz = len(ci) * V
+    rng = np.random.default_rng(92)
+    S = rng.integers(-60000, 60000, size=(3, nnz)).astype(np.int32)
+    scale = np.float32(2.5e-4)
+    mask = mc.SparseMatrix(L, L, V, rp, ci)
+    codes = mc.sparse_softmax(mask, torch_dev(S), float(scale), 127.0)
+    torch.cuda.synchronize()
+    codes = codes.cpu().numpy()
+    for b in range(3):
+        p = oracle.sparse_softmax(S[b], rp, V, scale)
+        want = oracle.requantize_probabilities(p, 1 / 127)
+        amb = _tie_ambiguous(p, 1 / 127)
+        diff = codes[b].astype(np.int32) - want.astype(np.int32)
+        assert (diff[~amb] == 0).all(), f"{np.count_nonzero(diff[~amb])} code mismatches away from ties"
+        assert (np.abs(diff[amb]) <= 1).all()
+    mask.close()
+
+
+# ---------------------------------------------------------------- attention ----
+def _attention_check(heads, L, dk, sparsity, seed):
+    import torch
+    import oracle
+    from paper_2209_06979_amd import binding as mc
+    V = 8
+    c = wl.attention_case(heads, L, dk, V, sparsity, seed)
+    q8, s_q = wl.quantize_inputs_int8(c["q"]); k8, s_k = wl.quantize_inputs_int8(c["k"])
+    v8, s_v = wl.quantize_inputs_int8(c["v"])
+    s_p = np.float32(1.0 / 127.0)
+    print(f"attention heads={heads} L={L} dk={dk} s={sparsity}", flush=True)
+    mask = mc.SparseMatrix(L, L, V, c["row_ptr"], c["col_idx"])
+    O = mc.sparse_attention(torch_dev(q8), torch_dev(k8), torch_dev(v8), mask, s_q, s_k, s_v, s_p)
+    torch.cuda.synchronize()
+    O = O.cpu().numpy().astype(np.float64)
+    mask.close()
+    want, scores, probs, codes = oracle.attention(q8, k8, v8, c["row_ptr"], c["col_idx"], V, s_q, s_k, s_v, s_p)
+    # rows that contain a rounding tie of the re-quantisation may differ by one code step
+    # per tied entry: allow s_p * s_v * 127 for each of them, 1e-3 everywhere else
+    amb = _tie_ambiguous(probs, s_p).reshape(heads, -1, V)
+    rp = c["row_ptr"]
+    n_amb_rows = np.zeros((heads, L), np.int64)
+    for p in range(L // V):
+        n_amb_rows[:, p * V:(p + 1) * V] = amb[:, rp[p]:rp[p + 1], :].sum(axis=1)
+    tol = 1e-3 + n_amb_rows[:, :, None] * float(s_p) * float(s_v) * 127.0
+    err = np.abs(O - want)
+    assert (err <= tol).all(), f"max err {err.max()} (ambiguous entries: {int(amb.sum())})"
+    clean = n_amb_rows == 0
+    assert clean.mean() > 0.9
+    print(f"  max abs err {err.max():.3e}; clean rows max err {err[clean].max():.3e}; ambiguous {int(amb.sum())}",
+          flush=True)
+
+
+def test_attention_small():
+    _attention_check(2, 256, 64, 0.75, 1200)
+    _attention_check(3, 512, 32, 0.9, 1201)
+
+
+def test_attention_config5_full():
+    """BASELINE config 5: 8 heads, L=4096, dk=64, 90 % vector sparsity, diagonal kept."""
+    _attention_check(8, 4096, 64, 0.9, wl.seed_for(5))

@@ -1,0 +1,130 @@
+"""GPU parity of SpMM (all precisions) against the CPU oracle: bit-exact int32."""
+import numpy as np
+import pytest
+
+from paper_2209_06979_amd import workloads as wl
+from gpu_util import run_spmm_gpu, run_spmm_oracle
+
+pytestmark = pytest.mark.gpu
+
+PRECS = ["L8R8", "L8R4", "L4R4", "L16R8"]
+
+
+def _check(case, variant=(0, 0)):
+    print(f"spmm case M={case['M']} K={case['K']} N={case['N']} V={case['V']} {case['prec']} variant={variant}",
+          flush=True)
+    got = run_spmm_gpu(case, variant)
+    want = run_spmm_oracle(case)
+    assert got.dtype == np.int32 and got.shape == want.shape
+    bad = np.argwhere(got != want)
+    assert bad.size == 0, f"{len(bad)} mismatches, first at {bad[0]}: got {got[tuple(bad[0])]} want {want[tuple(bad[0])]}"
+
+
+def test_config1_l8r8_512():
+    """BASELINE config 1: 512x512, V=8, 80 % of vectors zero, N=128."""
+    _check(wl.spmm_case(512, 512, 128, 8, 0.8, "L8R8", wl.seed_for(1)))
+
+
+@pytest.mark.parametrize("prec", PRECS)
+@pytest.mark.parametrize("V", [2, 4, 8])
+def test_small_all_precisions_and_vector_lengths(prec, V):
+    # 3 chunks of 64 per panel (one ragged), several row tiles
+    _check(wl.spmm_case(16 * V, 640, 256, V, 0.75, prec, 500 + V))
+
+
+@pytest.mark.parametrize("bnb", [64, 128, 256])
+@pytest.mark.parametrize("waves", [1, 2, 4])
+@pytest.mark.parametrize("prec", PRECS)
+def test_every_tile_variant(bnb, waves, prec):
+    N = 320 if prec in ("L8R8", "L16R8") else 384   # ragged last row tile for 128- and 256-byte tiles
+    _check(wl.spmm_case(64, 1024, N, 8, 0.7, prec, 600 + bnb + waves), (bnb, waves))
+
+
+@pytest.mark.parametrize("prec", PRECS)
+def test_ragged_panels_and_empty_panels(prec):
+    V, K, N = 8, 700, 192
+    counts = [0, 1, 15, 16, 17, 63, 64, 65, 127, 128, 129, 0, 300, 700, 2, 0]
+    M = V * len(counts)
+    rp, ci = wl.ragged_pattern(M, K, V, counts, 71)
+    nvec = len(ci)
+    vals = {"L4R4": lambda: wl.uniform_packed_int4((nvec, V // 2), 72),
+            "L16R8": lambda: wl.uniform_int16((nvec, V), 72)}.get(prec, lambda: wl.uniform_int8((nvec, V), 72))()
+    B = wl.uniform_packed_int4((K, N // 2), 73) if prec in ("L8R4", "L4R4") else wl.uniform_int8((K, N), 73)
+    case = dict(M=M, K=K, N=N, V=V, prec=prec, row_ptr=rp, col_idx=ci, values=vals, B=B)
+    for variant in [(0, 0), (64, 4), (128, 2)]:
+        _check(case, variant)
+
+
+@pytest.mark.parametrize("N", [16, 32, 48, 80, 144])
+def test_narrow_and_odd_widths(N):
+    _check(wl.spmm_case(32, 256, N, 8, 0.5, "L8R8", 800 + N))
+    _check(wl.spmm_case(32, 256, 2 * N, 4, 0.5, "L8R4", 900 + N))
+
+
+def test_extreme_values_saturate_nothing():
+    """All operands at -128 / most negative int4: the largest magnitudes the MFMA sees."""
+    V, M, K, N = 8, 16, 512, 64
+    rp, ci = wl.vector_sparse_pattern(M, K, V, 0.0, 5)
+    vals = np.full((len(ci), V), -128, np.int8)
+    B = np.full((K, N), -128, np.int8)
+    _check(dict(M=M, K=K, N=N, V=V, prec="L8R8", row_ptr=rp, col_idx=ci, values=vals, B=B))
+    v4 = np.full((len(ci), V // 2), 0x88, np.uint8)
+    B4 = np.full((K, N // 2), 0x88, np.uint8)
+    _check(dict(M=M, K=K, N=N, V=V, prec="L4R4", row_ptr=rp, col_idx=ci, values=v4, B=B4))
+    v16 = np.full((len(ci), V), -32768, np.int16)
+    B1 = np.full((K, N), 127, np.int8)
+    _check(dict(M=M, K=K, N=N, V=V, prec="L16R8", row_ptr=rp, col_idx=ci, values=v16, B=B1))
+    v16[:] = 32639
+    _check(dict(M=M, K=K, N=N, V=V, prec="L16R8", row_ptr=rp, col_idx=ci, values=v16, B=B1))
+
+
+def test_strided_operands_and_repeatability():
+    import torch
+    from paper_2209_06979_amd import binding as mc
+    import oracle
+    c = wl.spmm_case(64, 512, 128, 8, 0.8, "L8R8", 44)
+    A = mc.SparseMatrix(c["M"], c["K"], c["V"], c["row_ptr"], c["col_idx"], c["values"], 8)
+    Bbig = torch.zeros((c["K"], 160), dtype=torch.int8, device="cuda")
+    Bbig[:, :128] = torch.from_numpy(c["B"]).cuda()
+    Cbig = torch.full((c["M"], 132), 5, dtype=torch.int32, device="cuda")
+    want = oracle.spmm(c["M"], c["K"], c["V"], c["row_ptr"], c["col_idx"], c["values"], c["B"], "L8R8")
+    for _ in range(3):
+        mc.spmm(A, Bbig[:, :128], "L8R8", out=Cbig[:, :128])
+        torch.cuda.synchronize()
+        got = Cbig.cpu().numpy()
+        assert np.array_equal(got[:, :128], want) and (got[:, 128:] == 5).all()
+    # argument checks that need a live handle
+    with pytest.raises(mc.MagicubeError) as e:
+        mc.spmm(A, Bbig[:, :128], "L16R8")
+    assert e.value.status == mc.MC_EINVAL
+    with pytest.raises(mc.MagicubeError) as e:
+        mc.spmm(A, Bbig[:, 1:129], "L8R8")
+    assert e.value.status == mc.MC_EALIGN
+    with pytest.raises(mc.MagicubeError) as e:
+        mc.spmm(A, Bbig[:, :120], "L8R8")
+    assert e.value.status == mc.MC_EINVAL
+    A.close()
+
+
+@pytest.mark.parametrize("prec,V,s,N", [("L8R8", 8, 0.9, 256), ("L8R8", 2, 0.5, 128), ("L8R4", 4, 0.98, 512),
+                                        ("L4R4", 8, 0.7, 512), ("L16R8", 8, 0.9, 256)])
+def test_full_size_4096(prec, V, s, N):
+    """BASELINE configs 2 and 4 at full size, whole output compared."""
+    seed = wl.seed_for(4 if prec == "L16R8" else 2, int(s * 100) + V)
+    _check(wl.spmm_case(4096, 4096, N, V, s, prec, seed))
+
+
+def test_set_values_device_round_trip():
+    import torch
+    from paper_2209_06979_amd import binding as mc
+    import oracle
+    for prec in PRECS:
+        c = wl.spmm_case(64, 512, 128, 8, 0.6, prec, 300)
+        bits = mc.LHS_BITS[prec]
+        zeros = np.zeros_like(c["values"])
+        A = mc.SparseMatrix(c["M"], c["K"], c["V"], c["row_ptr"], c["col_idx"], zeros, bits)
+        A.set_values(torch.from_numpy(np.ascontiguousarray(c["values"]).view(np.uint8)).cuda())
+        C = mc.spmm(A, torch.from_numpy(c["B"]).cuda(), prec)
+        torch.cuda.synchronize()
+        assert np.array_equal(C.cpu().numpy(), run_spmm_oracle(c)), prec
+        A.close()
