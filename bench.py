@@ -1,0 +1,240 @@
+#!/usr/bin/env python3
+"""Benchmark of the quantized vector-sparse hot path on one MI355X.
+
+A *step* is one pass of every kernel row of the path at the headline shape
+(4096 x 4096, V = 8, 90 % of the vectors zero): SpMM L8-R8 / L8-R4 / L4-R4 / L16-R8
+with N = 256, SDDMM L8-R8 / L4-R4 with K = 256, and the quantized sparse-attention
+layer (8 heads, L = 4096, d_k = 64: SDDMM -> softmax -> int8 -> SpMM).  Inputs are
+seeded synthetic data already resident in HBM; the sparse operands were converted to
+the device format beforehand (the paper builds its format offline as well).
+
+The reported value is effective TOPS = sum(2 * nnz * N) / time over the step.  The
+step is replayed as one HIP graph so that host launch latency is not what is measured
+(`--eager` launches the kernels one by one instead).
+
+Prints ONE JSON line (see the keys below) -- `roofline` describes the kernel that takes
+the largest share of the step, `cpu_baseline` is the CPU oracle timed on this host.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published
+I8_MFMA_PEAK_TOPS = 5000.0  # MI355X dense int8, published
+
+M = K = 4096
+V = 8
+SPARSITY = 0.9
+N_SPMM = 256
+KD_SDDMM = 256
+HEADS, L_ATT, DK = 8, 4096, 64
+
+
+def build_problem():
+    """Seeded inputs of one step, on the host."""
+    from paper_2209_06979_amd import workloads as wl
+    prob = {}
+    for i, prec in enumerate(["L8R8", "L8R4", "L4R4", "L16R8"]):
+        prob["spmm_" + prec] = wl.spmm_case(M, K, N_SPMM, V, SPARSITY, prec, wl.seed_for(2, 10 * i))
+    for i, prec in enumerate(["L8R8", "L4R4"]):
+        prob["sddmm_" + prec] = wl.sddmm_case(M, K, KD_SDDMM, V, SPARSITY, prec, wl.seed_for(3, 10 * i))
+    att = wl.attention_case(HEADS, L_ATT, DK, V, SPARSITY, wl.seed_for(5))
+    for n in ("q", "k", "v"):
+        att[n + "8"], att["s_" + n] = wl.quantize_inputs_int8(att[n])
+    att["s_p"] = np.float32(1.0 / 127.0)
+    prob["attention"] = att
+    return prob
+
+
+def spmm_alg_bytes(nvec, P, lbits, rbits, N):
+    return nvec * V * lbits // 8 + 4 * nvec + 8 * P + K * N * rbits // 8 + 4 * M * N
+
+
+def sddmm_alg_bytes(nvec, P, bits, Kd):
+    return 2 * M * Kd * bits // 8 + 4 * nvec + 8 * P + 4 * nvec * V
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--eager", action="store_true", help="launch kernel by kernel instead of replaying a HIP graph")
+    ap.add_argument("--reps", type=int, default=200, help="back-to-back launches for the per-kernel timings")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--only", default="", help="comma-separated kernel names: run only these in the step")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2209_06979_amd import binding as mc
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    prob = build_problem()
+    t0 = time.perf_counter()
+    kernels = []  # name, launch(), ops, algorithmic bytes, device kernel name
+
+    def up(a):
+        return torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+
+    keep = []
+    for prec in ["L8R8", "L8R4", "L4R4", "L16R8"]:
+        c = prob["spmm_" + prec]
+        A = mc.SparseMatrix(M, K, V, c["row_ptr"], c["col_idx"], c["values"], mc.LHS_BITS[prec])
+        B = up(c["B"])
+        C = torch.empty((M, N_SPMM), dtype=torch.int32, device=dev)
+        keep += [A, B, C]
+        nvec = A.nvec
+        kernels.append(dict(
+            name="spmm_" + prec, launch=(lambda A=A, B=B, C=C, prec=prec: mc.spmm(A, B, prec, out=C)),
+            ops=2 * nvec * V * N_SPMM,
+            bytes=spmm_alg_bytes(nvec, M // V, mc.LHS_BITS[prec], mc.RHS_BITS[prec], N_SPMM)))
+    for prec in ["L8R8", "L4R4"]:
+        c = prob["sddmm_" + prec]
+        mask = mc.SparseMatrix(M, K, V, c["row_ptr"], c["col_idx"])
+        Q, Km = up(c["Q"]), up(c["Kmat"])
+        S = torch.empty(mask.nvec * V, dtype=torch.int32, device=dev)
+        keep += [mask, Q, Km, S]
+        kernels.append(dict(
+            name="sddmm_" + prec, launch=(lambda Q=Q, Km=Km, mask=mask, S=S, prec=prec: mc.sddmm(Q, Km, mask, prec, out=S)),
+            ops=2 * mask.nvec * V * KD_SDDMM,
+            bytes=sddmm_alg_bytes(mask.nvec, M // V, mc.LHS_BITS[prec], KD_SDDMM)))
+    att = prob["attention"]
+    amask = mc.SparseMatrix(L_ATT, L_ATT, V, att["row_ptr"], att["col_idx"])
+    q8, k8, v8 = up(att["q8"]), up(att["k8"]), up(att["v8"])
+    O = torch.empty((HEADS, L_ATT, DK), dtype=torch.float32, device=dev)
+    ws = torch.empty(mc.attention_workspace_bytes(HEADS, amask), dtype=torch.uint8, device=dev)
+    keep += [amask, q8, k8, v8, O, ws]
+    nnz_att = amask.nvec * V
+    att_bytes = HEADS * (3 * L_ATT * DK + 4 * L_ATT * DK          # Q, K, V in, O out
+                         + 2 * 4 * nnz_att + 2 * nnz_att)        # scores out+in, codes out+in
+    att_bytes += 3 * (4 * amask.nvec + 8 * (L_ATT // V))          # pattern read by three kernels
+    kernels.append(dict(
+        name="attention", launch=(lambda: mc.sparse_attention(q8, k8, v8, amask, att["s_q"], att["s_k"], att["s_v"],
+                                                              att["s_p"], out=O, workspace=ws)),
+        ops=HEADS * 2 * (2 * nnz_att * DK), bytes=att_bytes))
+    torch.cuda.synchronize()
+    format_build_s = time.perf_counter() - t0
+
+    if args.only:
+        names = set(args.only.split(","))
+        kernels = [k for k in kernels if k["name"] in names]
+
+    def step():
+        for k in kernels:
+            k["launch"]()
+
+    stream = torch.cuda.Stream()
+    graph = None
+    with torch.cuda.stream(stream):
+        step()                       # first touch outside capture
+        stream.synchronize()
+        if not args.eager:
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=stream):
+                step()
+        run = graph.replay if graph is not None else step
+        for _ in range(args.warmup):
+            run()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            run()
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+
+        # per-kernel timings: back-to-back launches between two events on the launch stream
+        for k in kernels:
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=stream):
+                for _ in range(args.reps):
+                    k["launch"]()
+            g.replay()
+            stream.synchronize()
+            samples = []
+            for _ in range(5):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                g.replay()
+                e1.record(stream)
+                e1.synchronize()
+                samples.append(e0.elapsed_time(e1) * 1e3 / args.reps)   # microseconds per launch
+            k["us"] = float(np.median(samples))
+            del g
+    ms_per_step = elapsed / args.steps * 1e3
+    total_ops = sum(k["ops"] for k in kernels)
+    value = total_ops / (elapsed / args.steps) / 1e12
+
+    dom = max(kernels, key=lambda k: k["us"])
+    achieved = dom["bytes"] / (dom["us"] * 1e-6) / 1e9
+    roofline = dict(bound="hbm", kernel=dom["name"], achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s",
+                    frac=round(achieved / HBM_PEAK_GBS, 4), traffic=None,
+                    us_per_launch=round(dom["us"], 2), algorithmic_bytes=int(dom["bytes"]))
+    per_kernel = {k["name"]: dict(us=round(k["us"], 2), eff_tops=round(k["ops"] / k["us"] / 1e6, 1),
+                                  alg_gbs=round(k["bytes"] / k["us"] / 1e3, 1),
+                                  hbm_frac=round(k["bytes"] / k["us"] / 1e3 / HBM_PEAK_GBS, 4),
+                                  i8_mfma_frac=round(k["ops"] / k["us"] / 1e6 / I8_MFMA_PEAK_TOPS, 4))
+                  for k in kernels}
+
+    cpu = None
+    if not args.no_cpu:
+        cpu = cpu_baseline(prob)
+
+    out = {
+        "metric": "SpMM/SDDMM effective TOPS (2*nnz*N/s), 90% sparse, V=8, L8-R8; % roofline",
+        "value": round(value, 2), "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int8", "data": "synthetic",
+        "config": {"workload": "4096x4096 V=8 s=0.9: SpMM L8-R8/L8-R4/L4-R4/L16-R8 N=256 + SDDMM L8-R8/L4-R4 K=256 "
+                               "+ sparse attention 8 heads L=4096 dk=64",
+                   "launch": "eager" if args.eager else "hip_graph", "kernels_in_step": [k["name"] for k in kernels]},
+        "headline_spmm_l8r8": per_kernel.get("spmm_L8R8"),
+        "per_kernel": per_kernel,
+        "format_build_s": round(format_build_s, 3),
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+def cpu_baseline(prob):
+    """The CPU oracle on a bounded sample of the step: SpMM L8-R8, SDDMM L8-R8 (both whole)
+    and one head of the attention layer."""
+    import oracle
+    ops = 0
+    t0 = time.perf_counter()
+    c = prob["spmm_L8R8"]
+    oracle.spmm(M, K, V, c["row_ptr"], c["col_idx"], c["values"], c["B"], "L8R8")
+    ops += 2 * len(c["col_idx"]) * V * N_SPMM
+    c = prob["sddmm_L8R8"]
+    oracle.sddmm(M, K, V, c["row_ptr"], c["col_idx"], c["Q"], c["Kmat"], "L8R8")
+    ops += 2 * len(c["col_idx"]) * V * KD_SDDMM
+    a = prob["attention"]
+    oracle.attention(a["q8"][:1], a["k8"][:1], a["v8"][:1], a["row_ptr"], a["col_idx"], V, a["s_q"], a["s_k"],
+                     a["s_v"], a["s_p"])
+    ops += 2 * (2 * len(a["col_idx"]) * V * DK)
+    dt = time.perf_counter() - t0
+    return dict(value=round(ops / dt / 1e12, 5), unit="TOPS", cores=oracle.num_threads(), kind="oracle",
+                seconds=round(dt, 3),
+                sample="SpMM L8-R8 N=256 and SDDMM L8-R8 K=256 (whole) + 1 of 8 attention heads, "
+                       "including the oracle's dense/int32 operand preparation")
+
+
+if __name__ == "__main__":
+    main()
