@@ -170,7 +170,8 @@ int mc_sparse_softmax(const mc_mat *mask, int batch, const int32_t *S_dev, float
  *   workspace_dev           at least mc_attention_workspace_bytes(heads, mask) bytes,
  *                           256-byte aligned, caller-owned; contents undefined after
  * Requirements: dk a multiple of 16.  Entries excluded by the mask do not take part in
- * the softmax.  Empty rows give zeros.
+ * the softmax.  Empty rows give zeros.  The workspace is only touched by the four-kernel
+ * pipeline (see mc_set_attention_mode) but must always be supplied.
  * ---------------------------------------------------------------------------------- */
 size_t mc_attention_workspace_bytes(int heads, const mc_mat *mask);
 int mc_sparse_attention(const int8_t *Q_dev, const int8_t *Km_dev, const int8_t *Vm_dev, int heads, int L,
@@ -184,6 +185,11 @@ int mc_sparse_attention(const int8_t *Q_dev, const int8_t *Km_dev, const int8_t 
  * Returns MC_EINVAL for other values.  Process-wide.
  * ---------------------------------------------------------------------------------- */
 int mc_set_spmm_variant(int bytes_per_row_tile, int waves);
+/* Attention path: 0 = automatic (a single fused kernel when dk == 64 and no panel holds
+ * more than 512 vectors, else the four-kernel pipeline), 1 = always the four-kernel
+ * pipeline SDDMM -> softmax -> repack -> SpMM.  Both give the same result up to fp32
+ * summation order in the softmax.  Process-wide; MC_EINVAL for other values. */
+int mc_set_attention_mode(int mode);
 
 #ifdef __cplusplus
 }

@@ -59,9 +59,10 @@ def _load() -> ctypes.CDLL:
     L.mc_sparse_attention.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_void_p,
                                       c_float, c_float, c_float, c_float, c_void_p, c_void_p, c_size_t, c_void_p]
     L.mc_set_spmm_variant.argtypes = [c_int, c_int]
+    L.mc_set_attention_mode.argtypes = [c_int]
     for name in ("mc_layout_query", "mc_pack_host", "mc_unpack_host", "mc_mat_create", "mc_mat_set_values_device",
                  "mc_mat_info", "mc_spmm", "mc_sddmm", "mc_sparse_softmax", "mc_sparse_attention",
-                 "mc_set_spmm_variant"):
+                 "mc_set_spmm_variant", "mc_set_attention_mode"):
         getattr(L, name).restype = c_int
     return L
 
@@ -168,6 +169,10 @@ class SparseMatrix:
 
 def set_spmm_variant(bytes_per_row_tile: int = 0, waves: int = 0) -> None:
     _check(lib.mc_set_spmm_variant(bytes_per_row_tile, waves), "mc_set_spmm_variant")
+
+
+def set_attention_mode(mode: int = 0) -> None:
+    _check(lib.mc_set_attention_mode(mode), "mc_set_attention_mode")
 
 
 def spmm(A: SparseMatrix, B, prec: str, out=None):

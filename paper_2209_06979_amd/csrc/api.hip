@@ -11,6 +11,7 @@
 namespace {
 
 int g_variant_bnb = 0, g_variant_waves = 0;
+int g_attention_mode = 0; // 0 automatic, 1 always the unfused four-kernel pipeline
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline int lhs_bits_of(mc_prec p) { return p == MC_L4R4 ? 4 : (p == MC_L16R8 ? 16 : 8); }
@@ -41,16 +42,20 @@ void free_device(mc_mat *A)
     if (A->d_vals) (void)hipFree(A->d_vals);
 }
 
-// Tile variant for a problem: wide row tiles when rows are long enough for a whole
-// 128-byte line per lane group, more waves per panel when panels hold many chunks.
-void choose_variant(const mc_mat *A, int row_bytes, bool r4, int *bnb, int *waves)
+// Tile variant for a problem.  Measured on MI355X: 64-byte row tiles win until a row has
+// 512 bytes or more; the chunks of a panel are shared by as many waves as it takes to put
+// about 4096 waves on the chip, but never more than one wave per ~2 chunks.
+void choose_variant(const mc_mat *A, int row_bytes, bool r4, int batch, int *bnb, int *waves)
 {
     int b = g_variant_bnb, w = g_variant_waves;
-    if (b == 0) b = (row_bytes >= 128) ? 128 : 64;
+    if (b == 0) b = (row_bytes >= 512) ? 128 : 64;
     if (b == 256 && r4) b = 128;
     if (w == 0) {
         const double avg = A->P ? (double)(A->nslots / MC_CHUNK) / A->P : 0.0;
-        w = avg >= 6.0 ? 4 : (avg >= 2.5 ? 2 : 1);
+        const double groups = (double)A->P * ((row_bytes + b - 1) / b) * (batch > 0 ? batch : 1);
+        w = groups <= 1024 ? 4 : (groups <= 2048 ? 2 : 1);
+        if (avg < 3.0) w = 1;
+        else if (avg < 6.0 && w > 2) w = 2;
     }
     *bnb = b;
     *waves = w;
@@ -83,6 +88,13 @@ extern "C" int mc_set_spmm_variant(int bytes_per_row_tile, int waves)
     if (waves != 0 && waves != 1 && waves != 2 && waves != 4) return MC_EINVAL;
     g_variant_bnb = bytes_per_row_tile;
     g_variant_waves = waves;
+    return MC_OK;
+}
+
+extern "C" int mc_set_attention_mode(int mode)
+{
+    if (mode != 0 && mode != 1) return MC_EINVAL;
+    g_attention_mode = mode;
     return MC_OK;
 }
 
@@ -199,7 +211,7 @@ extern "C" int mc_spmm(const mc_mat *A, const void *B_dev, int N, int ldb, mc_pr
     a.C = C_dev; a.ldc = ldc; a.C_batch_stride = 0;
     a.P = A->P; a.V = A->V; a.batch = 1; a.float_out = 0; a.out_scale = 1.f;
     int bnb, waves;
-    choose_variant(A, a.row_bytes, rb == 4, &bnb, &waves);
+    choose_variant(A, a.row_bytes, rb == 4, 1, &bnb, &waves);
     MC_HIP(launch_spmm(prec, a, bnb, waves, static_cast<hipStream_t>(stream)));
     return MC_OK;
 }
@@ -281,6 +293,17 @@ extern "C" int mc_sparse_attention(const int8_t *Q_dev, const int8_t *Km_dev, co
     const int64_t nnz = mask->nvec * mask->V;
     const int64_t head_elems = (int64_t)L * dk;
 
+    if (g_attention_mode == 0 && dk == 64 && mask->max_panel_chunks * MC_CHUNK <= attention_fused_max_vectors()) {
+        AttnArgs f;
+        f.panel_ptr = mask->d_panel_ptr; f.slot_idx = mask->d_slot_idx;
+        f.Q = reinterpret_cast<const uint8_t *>(Q_dev); f.Km = reinterpret_cast<const uint8_t *>(Km_dev);
+        f.Vm = reinterpret_cast<const uint8_t *>(Vm_dev); f.O = O_dev; f.head_stride = head_elems;
+        f.score_scale = s_q * s_k / std::sqrt((float)dk); f.inv_s_p = 1.f / s_p; f.out_scale = s_p * s_v;
+        f.P = mask->P; f.heads = heads;
+        MC_HIP(launch_attention_fused(f, s));
+        return MC_OK;
+    }
+
     SddmmArgs d;
     d.panel_ptr = mask->d_panel_ptr; d.row_ptr = mask->d_row_ptr; d.slot_idx = mask->d_slot_idx;
     d.Q = reinterpret_cast<const uint8_t *>(Q_dev); d.ldq_bytes = dk; d.Q_batch_stride = head_elems;
@@ -309,7 +332,7 @@ extern "C" int mc_sparse_attention(const int8_t *Q_dev, const int8_t *Km_dev, co
     m.row_bytes = dk; m.C = O_dev; m.ldc = dk; m.C_batch_stride = head_elems;
     m.P = mask->P; m.V = 8; m.batch = heads; m.float_out = 1; m.out_scale = s_p * s_v;
     int bnb, waves;
-    choose_variant(mask, m.row_bytes, false, &bnb, &waves);
+    choose_variant(mask, m.row_bytes, false, heads, &bnb, &waves);
     MC_HIP(launch_spmm(MC_L8R8, m, bnb, waves, s));
     return MC_OK;
 }

@@ -114,8 +114,10 @@ __global__ __launch_bounds__(256) void softmax_kernel(SoftmaxArgs a)
     const int cnt = (a.row_ptr[panel + 1] - a.row_ptr[panel]) * V;
     const int32_t *S = a.S + base;
 
+    // softmax in base 2: exp(x - max) = 2^(x*log2(e) - max2), one v_exp_f32 per element
+    const float scale2 = a.score_scale * 1.4426950408889634f;
     float m = -INFINITY;
-    for (int e = tid; e < cnt; e += 256) m = fmaxf(m, (float)S[e] * a.score_scale);
+    for (int e = tid; e < cnt; e += 256) m = fmaxf(m, (float)S[e] * scale2);
     red[tid] = m;
     __syncthreads();
     m = -INFINITY;
@@ -123,7 +125,7 @@ __global__ __launch_bounds__(256) void softmax_kernel(SoftmaxArgs a)
     __syncthreads();
 
     float sum = 0.f;
-    for (int e = tid; e < cnt; e += 256) sum += expf((float)S[e] * a.score_scale - m);
+    for (int e = tid; e < cnt; e += 256) sum += __builtin_amdgcn_exp2f((float)S[e] * scale2 - m);
     red[tid] = sum;
     __syncthreads();
     sum = 0.f;
@@ -131,7 +133,7 @@ __global__ __launch_bounds__(256) void softmax_kernel(SoftmaxArgs a)
 
     int8_t *codes = a.codes + base;
     for (int e = tid; e < cnt; e += 256) {
-        const float p = expf((float)S[e] * a.score_scale - m) / sum;
+        const float p = __builtin_amdgcn_exp2f((float)S[e] * scale2 - m) / sum;
         const float q = fminf(fmaxf(rintf(p * a.inv_s_p), 0.f), 127.f);
         codes[e] = (int8_t)(int)q;
     }

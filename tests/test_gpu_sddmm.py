@@ -98,7 +98,7 @@ def test_sparse_softmax_codes():
 
 
 # ---------------------------------------------------------------- attention ----
-def _attention_check(heads, L, dk, sparsity, seed):
+def _attention_check(heads, L, dk, sparsity, seed, mode=0):
     import torch
     import oracle
     from paper_2209_06979_amd import binding as mc
@@ -107,10 +107,15 @@ def _attention_check(heads, L, dk, sparsity, seed):
     q8, s_q = wl.quantize_inputs_int8(c["q"]); k8, s_k = wl.quantize_inputs_int8(c["k"])
     v8, s_v = wl.quantize_inputs_int8(c["v"])
     s_p = np.float32(1.0 / 127.0)
-    print(f"attention heads={heads} L={L} dk={dk} s={sparsity}", flush=True)
+    print(f"attention heads={heads} L={L} dk={dk} s={sparsity} mode={mode}", flush=True)
     mask = mc.SparseMatrix(L, L, V, c["row_ptr"], c["col_idx"])
-    O = mc.sparse_attention(torch_dev(q8), torch_dev(k8), torch_dev(v8), mask, s_q, s_k, s_v, s_p)
-    torch.cuda.synchronize()
+    mc.set_attention_mode(mode)
+    try:
+        out = torch.full((heads, L, dk), float("nan"), dtype=torch.float32, device="cuda")
+        O = mc.sparse_attention(torch_dev(q8), torch_dev(k8), torch_dev(v8), mask, s_q, s_k, s_v, s_p, out=out)
+        torch.cuda.synchronize()
+    finally:
+        mc.set_attention_mode(0)
     O = O.cpu().numpy().astype(np.float64)
     mask.close()
     want, scores, probs, codes = oracle.attention(q8, k8, v8, c["row_ptr"], c["col_idx"], V, s_q, s_k, s_v, s_p)
@@ -130,11 +135,46 @@ def _attention_check(heads, L, dk, sparsity, seed):
           flush=True)
 
 
-def test_attention_small():
-    _attention_check(2, 256, 64, 0.75, 1200)
-    _attention_check(3, 512, 32, 0.9, 1201)
+@pytest.mark.parametrize("mode", [0, 1])
+def test_attention_small(mode):
+    _attention_check(2, 256, 64, 0.75, 1200, mode)      # one chunk per panel
+    _attention_check(3, 512, 32, 0.9, 1201, mode)       # dk != 64: always the four-kernel pipeline
+    _attention_check(2, 1024, 64, 0.6, 1202, mode)      # 410 vectors per panel: 7 chunks, ragged tail
+    _attention_check(1, 2048, 64, 0.75, 1203, mode)     # 512 vectors: the longest panel the fused kernel takes
+    _attention_check(1, 2048, 64, 0.7, 1204, mode)      # 614 vectors: falls back to the pipeline
 
 
-def test_attention_config5_full():
+@pytest.mark.parametrize("mode", [0, 1])
+def test_attention_config5_full(mode):
     """BASELINE config 5: 8 heads, L=4096, dk=64, 90 % vector sparsity, diagonal kept."""
-    _attention_check(8, 4096, 64, 0.9, wl.seed_for(5))
+    _attention_check(8, 4096, 64, 0.9, wl.seed_for(5), mode)
+
+
+def test_attention_ragged_rows():
+    """Panels of very different lengths, including empty ones (their output rows are zero)."""
+    import torch
+    import oracle
+    from paper_2209_06979_amd import binding as mc
+    V, L, dk, heads = 8, 512, 64, 2
+    counts = np.r_[[0, 1, 2, 15, 16, 17, 63, 64, 65, 127, 128, 129, 300, 511, 512, 0], np.full(L // V - 16, 40)]
+    rp, ci = wl.ragged_pattern(L, L, V, counts, 1300)
+    q8, s_q = wl.quantize_inputs_int8(wl.normal_fp32((heads, L, dk), 1301))
+    k8, s_k = wl.quantize_inputs_int8(wl.normal_fp32((heads, L, dk), 1302))
+    v8, s_v = wl.quantize_inputs_int8(wl.normal_fp32((heads, L, dk), 1303))
+    s_p = np.float32(1 / 127)
+    want, _, probs, _ = oracle.attention(q8, k8, v8, rp, ci, V, s_q, s_k, s_v, s_p)
+    amb = _tie_ambiguous(probs, s_p).reshape(heads, -1, V)
+    mask = mc.SparseMatrix(L, L, V, rp, ci)
+    for mode in (0, 1):
+        mc.set_attention_mode(mode)
+        out = torch.full((heads, L, dk), float("nan"), dtype=torch.float32, device="cuda")
+        O = mc.sparse_attention(torch_dev(q8), torch_dev(k8), torch_dev(v8), mask, s_q, s_k, s_v, s_p, out=out)
+        torch.cuda.synchronize()
+        mc.set_attention_mode(0)
+        O = O.cpu().numpy().astype(np.float64)
+        tol = np.full((heads, L), 1e-3)
+        for p in range(L // V):
+            tol[:, p * V:(p + 1) * V] += amb[:, rp[p]:rp[p + 1], :].sum(axis=1) * float(s_p) * float(s_v) * 127
+        assert (np.abs(O - want) <= tol[:, :, None]).all(), mode
+        assert not O[:, :8].any() and not O[:, 15 * 8:16 * 8].any()
+    mask.close()
