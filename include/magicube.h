@@ -181,10 +181,14 @@ int mc_sparse_attention(const int8_t *Q_dev, const int8_t *Km_dev, const int8_t 
 /* ------------------------------------------------------------------------------------
  * Tuning knob (not needed for correctness): selects the SpMM tile variant.
  *   bytes_per_row_tile  0 = automatic, else 64, 128 or 256 bytes of a B row per workgroup
- *   waves               0 = automatic, else 1, 2 or 4 wavefronts sharing a panel's chunks
+ *   waves               0 = automatic, else 1, 2, 4 or 8 wavefronts sharing a panel's chunks
  * Returns MC_EINVAL for other values.  Process-wide.
  * ---------------------------------------------------------------------------------- */
 int mc_set_spmm_variant(int bytes_per_row_tile, int waves);
+/* SDDMM variant: -1 = automatic, 0 = the kernel that loads operands straight from memory
+ * (any row length), 1, 2, 4 or 8 = waves per panel of the kernel that stages Kmat rows in
+ * LDS (used when a row has 64, 128 or 256 bytes, else ignored).  Process-wide. */
+int mc_set_sddmm_variant(int waves);
 /* Attention path: 0 = automatic (a single fused kernel when dk == 64 and no panel holds
  * more than 512 vectors, else the four-kernel pipeline), 1 = always the four-kernel
  * pipeline SDDMM -> softmax -> repack -> SpMM.  Both give the same result up to fp32

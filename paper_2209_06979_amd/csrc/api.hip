@@ -11,6 +11,7 @@
 namespace {
 
 int g_variant_bnb = 0, g_variant_waves = 0;
+int g_sddmm_waves = -1;   // -1 automatic, 0 direct-load kernel, 1/2/4/8 waves of the LDS-staged kernel
 int g_attention_mode = 0; // 0 automatic, 1 always the unfused four-kernel pipeline
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -42,20 +43,34 @@ void free_device(mc_mat *A)
     if (A->d_vals) (void)hipFree(A->d_vals);
 }
 
-// Tile variant for a problem.  Measured on MI355X: 64-byte row tiles win until a row has
-// 512 bytes or more; the chunks of a panel are shared by as many waves as it takes to put
-// about 4096 waves on the chip, but never more than one wave per ~2 chunks.
+// Tile variant for a problem (measured on MI355X).  Rows of 256 bytes or more are cut into
+// 128-byte tiles (256-byte tiles when panels are long), shorter rows into 64-byte tiles;
+// the chunks of a panel are shared by as many waves as it takes to put about 2048 waves
+// on the chip, but never more waves than a panel has chunks.
+// Waves per panel for SDDMM: enough to put about 2048 waves on the chip, at most one per chunk.
+int choose_sddmm_waves(const mc_mat *mask, int batch)
+{
+    if (g_sddmm_waves >= 0) return g_sddmm_waves;
+    const double avg = mask->P ? (double)(mask->nslots / MC_CHUNK) / mask->P : 0.0;
+    const double groups = (double)mask->P * (batch > 0 ? batch : 1);
+    int w = 1;
+    while (w < 8 && groups * w * 2 <= 2048.0 && w * 2 <= avg) w *= 2;
+    return w;
+}
+
 void choose_variant(const mc_mat *A, int row_bytes, bool r4, int batch, int *bnb, int *waves)
 {
     int b = g_variant_bnb, w = g_variant_waves;
-    if (b == 0) b = (row_bytes >= 512) ? 128 : 64;
+    const double avg = A->P ? (double)(A->nslots / MC_CHUNK) / A->P : 0.0;
+    if (b == 0) {
+        b = (row_bytes >= 256) ? 128 : 64;
+        if (!r4 && row_bytes >= 256 && avg >= 16.0) b = 256;
+    }
     if (b == 256 && r4) b = 128;
     if (w == 0) {
-        const double avg = A->P ? (double)(A->nslots / MC_CHUNK) / A->P : 0.0;
         const double groups = (double)A->P * ((row_bytes + b - 1) / b) * (batch > 0 ? batch : 1);
-        w = groups <= 1024 ? 4 : (groups <= 2048 ? 2 : 1);
-        if (avg < 3.0) w = 1;
-        else if (avg < 6.0 && w > 2) w = 2;
+        w = 1;
+        while (w < 8 && groups * w * 2 <= 2048.0 && w * 2 <= avg) w *= 2;
     }
     *bnb = b;
     *waves = w;
@@ -85,9 +100,16 @@ extern "C" int mc_set_spmm_variant(int bytes_per_row_tile, int waves)
 {
     if (bytes_per_row_tile != 0 && bytes_per_row_tile != 64 && bytes_per_row_tile != 128 && bytes_per_row_tile != 256)
         return MC_EINVAL;
-    if (waves != 0 && waves != 1 && waves != 2 && waves != 4) return MC_EINVAL;
+    if (waves != 0 && waves != 1 && waves != 2 && waves != 4 && waves != 8) return MC_EINVAL;
     g_variant_bnb = bytes_per_row_tile;
     g_variant_waves = waves;
+    return MC_OK;
+}
+
+extern "C" int mc_set_sddmm_variant(int waves)
+{
+    if (waves != -1 && waves != 0 && waves != 1 && waves != 2 && waves != 4 && waves != 8) return MC_EINVAL;
+    g_sddmm_waves = waves;
     return MC_OK;
 }
 
@@ -234,7 +256,7 @@ extern "C" int mc_sddmm(const void *Q_dev, int ldq, const void *Kmat_dev, int ld
     a.row_bytes = Kd * bits / 8;
     a.S = S_dev; a.S_batch_stride = 0;
     a.P = mask->P; a.V = mask->V; a.batch = 1;
-    MC_HIP(launch_sddmm(bits == 4, a, static_cast<hipStream_t>(stream)));
+    MC_HIP(launch_sddmm(bits == 4, a, choose_sddmm_waves(mask, 1), static_cast<hipStream_t>(stream)));
     return MC_OK;
 }
 
@@ -310,7 +332,7 @@ extern "C" int mc_sparse_attention(const int8_t *Q_dev, const int8_t *Km_dev, co
     d.Kmat = reinterpret_cast<const uint8_t *>(Km_dev); d.ldk_bytes = dk; d.K_batch_stride = head_elems;
     d.row_bytes = dk; d.S = scores; d.S_batch_stride = nnz;
     d.P = mask->P; d.V = 8; d.batch = heads;
-    MC_HIP(launch_sddmm(false, d, s));
+    MC_HIP(launch_sddmm(false, d, choose_sddmm_waves(mask, heads), s));
 
     SoftmaxArgs f;
     f.row_ptr = mask->d_row_ptr; f.S = scores; f.codes = codes; f.batch_stride = nnz;

@@ -4,9 +4,16 @@
 // V rows of Q are the row operand of v_mfma_i32_16x16x64_i8 and stay in registers for
 // the whole panel (the paper keeps this block in shared memory for its warps); the rows
 // of Kmat named by 16 consecutive mask vectors are the column operand.  Both operands
-// are contiguous along the reduction dimension, so each lane loads its 16 reduction
-// bytes straight from memory and no transpose is needed (Section 4.3.1).  Lane group
-// g = lane/16 covers bytes 64*kc + 16*g .. +15 of a row on both sides.
+// are contiguous along the reduction dimension, so no transpose is needed
+// (Section 4.3.1): lane group g = lane/16 covers bytes 64*kc + 16*g .. +15 of a row on
+// both sides.  The waves of a workgroup take the panel's chunks of 64 vectors round-robin
+// and never have to meet: every chunk produces its own outputs.
+// Two kernels:
+//   sddmm_lds_kernel   rows of 64, 128 or 256 bytes: the 64 Kmat rows of a chunk are copied
+//                      from global memory straight into LDS with coalesced 16-byte pieces
+//                      (global_load_lds), then read as 128-bit MFMA operands; the
+//                      16-byte segments are XOR-swizzled against bank conflicts.
+//   sddmm_direct_kernel any row length: each lane loads its 16 operand bytes from memory.
 // The output is written in interchange (BCRS) order: V consecutive int32 per vector.
 #include "internal.h"
 
@@ -14,6 +21,8 @@ namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v2i __attribute__((ext_vector_type(2)));
+typedef __attribute__((address_space(1))) const void gptr_t;
+typedef __attribute__((address_space(3))) void lptr_t;
 
 constexpr int SDDMM_WAVES = 4;
 constexpr int NIBBLE_HI = (int)0xF0F0F0F0;
@@ -26,9 +35,88 @@ __device__ __forceinline__ void widen4(v4i x, v4i &even, v4i &odd)
     odd = x & m;
 }
 
+__device__ __forceinline__ void store_scores(const SddmmArgs &a, int64_t out0, int slot, int n, int g, v4i acc)
+{
+    // accumulator register r of lane (j, g) is row 4g + r of vector `slot`
+    if (slot < n && 4 * g < a.V) {
+        int32_t *o = a.S + out0 + (int64_t)slot * a.V + 4 * g;
+        if (a.V >= 4) *reinterpret_cast<v4i *>(o) = acc;
+        else *reinterpret_cast<v2i *>(o) = (v2i){acc.x, acc.y};
+    }
+}
+
+// RB: bytes of a Kmat row (64, 128, 256).  WK: waves per workgroup.
+template <bool R4, int RB, int WK>
+__global__ __launch_bounds__(64 * WK) void sddmm_lds_kernel(SddmmArgs a)
+{
+    constexpr int LPR = RB / 16, NI = LPR, RPI = 64 / LPR, KC = RB / 64;
+    __shared__ __attribute__((aligned(16))) char lds[WK * 64 * RB];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int j = lane & 15, g = lane >> 4;
+    const int rg = lane / LPR, seg = lane % LPR;
+    const int panel = blockIdx.x, batch = blockIdx.y;
+    const int s0 = a.panel_ptr[2 * panel], n = a.panel_ptr[2 * panel + 1] - s0;
+    const int nch = (n + MC_CHUNK - 1) / MC_CHUNK;
+    const int32_t *idx = a.slot_idx + s0;
+    const int64_t out0 = (int64_t)batch * a.S_batch_stride + (int64_t)a.row_ptr[panel] * a.V;
+    const uint8_t *Km = a.Kmat + (int64_t)batch * a.K_batch_stride;
+    char *stage = lds + w * (64 * RB);
+
+    v4i qf[KC];
+#pragma unroll
+    for (int kc = 0; kc < KC; ++kc) {
+        qf[kc] = (v4i){0, 0, 0, 0};
+        if (j < a.V)
+            qf[kc] = *reinterpret_cast<const v4i *>(a.Q + (int64_t)batch * a.Q_batch_stride +
+                                                    (int64_t)(panel * a.V + j) * a.ldq_bytes + kc * 64 + g * 16);
+    }
+    // load instruction i: lane (rg, seg) copies segment seg ^ i of the row in slot rg*NI + i
+    // to LDS row i*RPI + rg (byte i*1024 + lane*16 of the stage)
+    const int nmy = (nch > w) ? (nch - w + WK - 1) / WK : 0;
+    v4i idxv[NI / 4];
+    auto load_idx = [&](int c) {
+#pragma unroll
+        for (int t = 0; t < NI / 4; ++t) idxv[t] = *reinterpret_cast<const v4i *>(idx + c * MC_CHUNK + rg * NI + 4 * t);
+    };
+    if (nmy > 0) load_idx(w);
+    for (int k = 0; k < nmy; ++k) {
+        const int c = w + k * WK;
+#pragma unroll
+        for (int i = 0; i < NI; ++i)
+            __builtin_amdgcn_global_load_lds((gptr_t *)(Km + (int64_t)idxv[i >> 2][i & 3] * a.ldk_bytes + ((seg ^ i) * 16)),
+                                             (lptr_t *)(stage + i * 1024), 16, 0, 0);
+        if (k + 1 < nmy) load_idx(c + WK);
+        if (k + 1 < nmy) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NI / 4) : "memory"); // rows landed, indices may still fly
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+        for (int tl = 0; tl < 4; ++tl) {
+            const int s = tl * 16 + j;              // slot within the chunk
+            const int i = s % NI, r = s / NI;       // its load instruction and row group
+            const char *rowp = stage + i * 1024 + r * RB;
+            v4i acc = {0, 0, 0, 0};
+#pragma unroll
+            for (int kc = 0; kc < KC; ++kc) {
+                const v4i kf = *reinterpret_cast<const v4i *>(rowp + (((kc * 4 + g) ^ i) * 16));
+                if (R4) {
+                    v4i qe, qo, ke, ko;
+                    widen4(qf[kc], qe, qo);
+                    widen4(kf, ke, ko);
+                    acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(qe, ke, acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(qo, ko, acc, 0, 0, 0);
+                } else {
+                    acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(qf[kc], kf, acc, 0, 0, 0);
+                }
+            }
+            if (R4) acc = acc >> 8; // both operands carried a factor 16
+            store_scores(a, out0, c * MC_CHUNK + s, n, g, acc);
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); // reads done before the rows are overwritten
+    }
+}
+
 // KC = number of 64-byte steps along a row kept in registers (0: any length, Q re-read).
 template <bool R4, int KC>
-__global__ __launch_bounds__(64 * SDDMM_WAVES) void sddmm_kernel(SddmmArgs a)
+__global__ __launch_bounds__(64 * SDDMM_WAVES) void sddmm_direct_kernel(SddmmArgs a)
 {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int j = lane & 15, g = lane >> 4;
@@ -93,12 +181,7 @@ __global__ __launch_bounds__(64 * SDDMM_WAVES) void sddmm_kernel(SddmmArgs a)
             }
         }
         if (R4) acc = acc >> 8; // both operands carried a factor 16
-        // accumulator register r of lane (j, g) is row 4g + r of vector `slot`
-        if (slot < n && 4 * g < a.V) {
-            int32_t *o = a.S + out0 + (int64_t)slot * a.V + 4 * g;
-            if (a.V >= 4) *reinterpret_cast<v4i *>(o) = acc;
-            else *reinterpret_cast<v2i *>(o) = (v2i){acc.x, acc.y};
-        }
+        store_scores(a, out0, slot, n, g, acc);
     }
 }
 
@@ -191,12 +274,36 @@ __global__ __launch_bounds__(256) void repack_kernel(RepackArgs a)
 
 } // namespace
 
-hipError_t launch_sddmm(bool int4, const SddmmArgs &a, hipStream_t s)
+template <bool R4, int RB> hipError_t launch_sddmm_lds(const SddmmArgs &a, int waves, hipStream_t s)
+{
+    dim3 grid((unsigned)a.P, (unsigned)a.batch);
+    constexpr int MAXW = (64 * RB * 8 <= 65536) ? 8 : 4;
+    if (waves > MAXW) waves = MAXW;
+    switch (waves) {
+    case 1: hipLaunchKernelGGL((sddmm_lds_kernel<R4, RB, 1>), grid, dim3(64), 0, s, a); break;
+    case 2: hipLaunchKernelGGL((sddmm_lds_kernel<R4, RB, 2>), grid, dim3(128), 0, s, a); break;
+    case 4: hipLaunchKernelGGL((sddmm_lds_kernel<R4, RB, 4>), grid, dim3(256), 0, s, a); break;
+    default: hipLaunchKernelGGL((sddmm_lds_kernel<R4, RB, MAXW>), grid, dim3(64 * MAXW), 0, s, a); break;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_sddmm(bool int4, const SddmmArgs &a, int waves, hipStream_t s)
 {
     if (a.P == 0 || a.batch == 0) return hipSuccess;
+    if (waves > 0 && (a.row_bytes == 64 || a.row_bytes == 128 || a.row_bytes == 256)) {
+        if (int4) {
+            if (a.row_bytes == 64) return launch_sddmm_lds<true, 64>(a, waves, s);
+            if (a.row_bytes == 128) return launch_sddmm_lds<true, 128>(a, waves, s);
+            return launch_sddmm_lds<true, 256>(a, waves, s);
+        }
+        if (a.row_bytes == 64) return launch_sddmm_lds<false, 64>(a, waves, s);
+        if (a.row_bytes == 128) return launch_sddmm_lds<false, 128>(a, waves, s);
+        return launch_sddmm_lds<false, 256>(a, waves, s);
+    }
     dim3 grid((unsigned)a.P, (unsigned)a.batch), block(64 * SDDMM_WAVES);
     const int kc = (a.row_bytes + 63) / 64;
-#define MC_SDDMM(R4, KC) hipLaunchKernelGGL((sddmm_kernel<R4, KC>), grid, block, 0, s, a)
+#define MC_SDDMM(R4, KC) hipLaunchKernelGGL((sddmm_direct_kernel<R4, KC>), grid, block, 0, s, a)
     if (int4) {
         if (kc == 1) MC_SDDMM(true, 1);
         else if (kc == 2) MC_SDDMM(true, 2);

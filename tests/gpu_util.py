@@ -32,16 +32,18 @@ def run_spmm_oracle(case):
                        case["B"], case["prec"])
 
 
-def run_sddmm_gpu(case):
+def run_sddmm_gpu(case, waves=-1):
     import torch
     from paper_2209_06979_amd import binding as mc
     mask = mc.SparseMatrix(case["M"], case["Nc"], case["V"], case["row_ptr"], case["col_idx"])
+    mc.set_sddmm_variant(waves)
     try:
         out = torch.full((mask.nvec * mask.V,), -7777777, dtype=torch.int32, device="cuda")
         S = mc.sddmm(torch_dev(case["Q"]), torch_dev(case["Kmat"]), mask, case["prec"], out=out)
         torch.cuda.synchronize()
         return S.cpu().numpy()
     finally:
+        mc.set_sddmm_variant(-1)
         mask.close()
 
 

@@ -8,20 +8,22 @@ from gpu_util import run_sddmm_gpu, run_sddmm_oracle, torch_dev
 pytestmark = pytest.mark.gpu
 
 
-def _check(case):
-    print(f"sddmm case M={case['M']} Nc={case['Nc']} Kd={case['Kd']} V={case['V']} {case['prec']}", flush=True)
-    got = run_sddmm_gpu(case)
+def _check(case, variants=(-1,)):
     want = run_sddmm_oracle(case)
-    assert got.shape == want.shape
-    bad = np.flatnonzero(got != want)
-    assert bad.size == 0, f"{len(bad)} mismatches, first at {bad[0]}: got {got[bad[0]]} want {want[bad[0]]}"
+    for waves in variants:
+        print(f"sddmm case M={case['M']} Nc={case['Nc']} Kd={case['Kd']} V={case['V']} {case['prec']} waves={waves}",
+              flush=True)
+        got = run_sddmm_gpu(case, waves)
+        assert got.shape == want.shape
+        bad = np.flatnonzero(got != want)
+        assert bad.size == 0, f"{len(bad)} mismatches, first at {bad[0]}: got {got[bad[0]]} want {want[bad[0]]}"
 
 
 @pytest.mark.parametrize("prec", ["L8R8", "L4R4"])
 @pytest.mark.parametrize("V", [2, 4, 8])
 @pytest.mark.parametrize("Kd", [64, 128, 256])
 def test_small(prec, V, Kd):
-    _check(wl.sddmm_case(16 * V, 300, Kd, V, 0.7, prec, 1000 + V + Kd))
+    _check(wl.sddmm_case(16 * V, 300, Kd, V, 0.7, prec, 1000 + V + Kd), variants=(-1, 0, 1, 2, 4, 8))
 
 
 @pytest.mark.parametrize("prec,Kd", [("L8R8", 16), ("L8R8", 48), ("L8R8", 320), ("L8R8", 1024), ("L4R4", 32),
@@ -40,7 +42,7 @@ def test_ragged_and_empty_panels(prec):
         Q, Km = wl.uniform_packed_int4((M, Kd // 2), 82), wl.uniform_packed_int4((Nc, Kd // 2), 83)
     else:
         Q, Km = wl.uniform_int8((M, Kd), 82), wl.uniform_int8((Nc, Kd), 83)
-    _check(dict(M=M, Nc=Nc, Kd=Kd, V=V, prec=prec, row_ptr=rp, col_idx=ci, Q=Q, Kmat=Km))
+    _check(dict(M=M, Nc=Nc, Kd=Kd, V=V, prec=prec, row_ptr=rp, col_idx=ci, Q=Q, Kmat=Km), variants=(-1, 0, 2, 8))
 
 
 @pytest.mark.parametrize("prec,Kd,s", [("L8R8", 64, 0.9), ("L8R8", 256, 0.7), ("L4R4", 128, 0.95), ("L4R4", 64, 0.9)])

@@ -33,7 +33,7 @@ def test_small_all_precisions_and_vector_lengths(prec, V):
 
 
 @pytest.mark.parametrize("bnb", [64, 128, 256])
-@pytest.mark.parametrize("waves", [1, 2, 4])
+@pytest.mark.parametrize("waves", [1, 2, 4, 8])
 @pytest.mark.parametrize("prec", PRECS)
 def test_every_tile_variant(bnb, waves, prec):
     N = 320 if prec in ("L8R8", "L16R8") else 384   # ragged last row tile for 128- and 256-byte tiles
