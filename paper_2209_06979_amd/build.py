@@ -14,6 +14,8 @@ FLAGS = [
     # packed fp32 VALU forms are kept out of generated code on this target
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-command-line-argument",
+    # the asynchronous-copy helper writes M0 from inline assembly and says so in its clobber list
+    "-Wno-inline-asm",
 ]
 
 

@@ -23,15 +23,11 @@
 // lane's 4 column indices are consecutive) and its 16-byte segments are XOR-swizzled with
 // s % 4 so that rows read together fall into different banks.
 #include "internal.h"
+#include "lds_async.h"
 
 namespace {
 
-typedef int v4i __attribute__((ext_vector_type(4)));
-typedef int v2i __attribute__((ext_vector_type(2)));
-typedef float v4f __attribute__((ext_vector_type(4)));
-typedef __attribute__((address_space(3))) v2i lds_v2i;
-typedef __attribute__((address_space(1))) const void gptr_t;
-typedef __attribute__((address_space(3))) void lptr_t;
+using namespace mcu;
 
 // max / sum over the 16 lanes of a DPP row via rotations by 1, 2, 4, 8 (VALU only)
 template <int CTRL> __device__ __forceinline__ float dpp_rot(float v)
@@ -61,13 +57,17 @@ __global__ __launch_bounds__(64, 4) void attention_fused_kernel(AttnArgs a)
 {
     constexpr int DK = 64;
     constexpr int NPR = MAXCH * 2; // pairs of score tiles
-    __shared__ __attribute__((aligned(16))) char stage[4096];       // one chunk of gathered rows
+    constexpr int GROUP = 5;       // memory instructions per chunk: 4 row copies + 1 index load
+    __shared__ __attribute__((aligned(16))) char stage[2 * 4096];    // two chunks of gathered rows
     __shared__ __attribute__((aligned(16))) char Pl[MAXCH * 64 * 8]; // codes, [slot][8 rows]
 
     const int lane = threadIdx.x;
     const int j = lane & 15, g = lane >> 4;
     const int rg = lane >> 2, seg = lane & 3;
-    const int panel = blockIdx.x, head = blockIdx.y;
+    // Workgroups are handed to the 8 XCDs round-robin by linear id.  With id = panel * heads +
+    // head, an XCD only ever sees the heads congruent to its number, so its L2 has to hold the
+    // Kmat and V rows of those heads (1/8 of the data for 8 heads) instead of all of them.
+    const int head = blockIdx.x % a.heads, panel = blockIdx.x / a.heads;
     const int s0 = a.panel_ptr[2 * panel], n = a.panel_ptr[2 * panel + 1] - s0;
     const int nch = (n + MC_CHUNK - 1) / MC_CHUNK;
     const int32_t *idx = a.slot_idx + s0;
@@ -81,39 +81,65 @@ __global__ __launch_bounds__(64, 4) void attention_fused_kernel(AttnArgs a)
         const v4i qv = *reinterpret_cast<const v4i *>(a.Q + hoff + (int64_t)(panel * 8 + (j & 7)) * DK + g * 16);
         if (j < 8) q_lo = qv; else q_hi = qv;
     }
-    // lane (rg, seg), load instruction i: segment seg ^ i of the row in slot rg*4 + i
+    // Lane (rg, seg), copy instruction i: segment seg ^ i of the row in slot rg*4 + i.
+    // One group of GROUP memory instructions per chunk: its 4 row copies, then the load of the
+    // column indices of the chunk two steps ahead (clamped) into the registers the copies have
+    // just consumed -- the index registers alternate with the chunk parity.
     int segoff[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) segoff[i] = (seg ^ i) * 16;
-    auto gather = [&](const uint8_t *base, int c) {
-        const v4i ix = *reinterpret_cast<const v4i *>(idx + c * MC_CHUNK + rg * 4);
+    const unsigned stage_u = lds_addr_uniform(stage);
+    v4i ixv[2];
+    auto issue = [&](const uint8_t *base, auto CC) {
+        constexpr int c = CC;
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-            __builtin_amdgcn_global_load_lds((gptr_t *)(base + (unsigned)ix[i] * DK + segoff[i]), (lptr_t *)(stage + i * 1024), 16, 0, 0);
+            copy16_to_lds(base + (unsigned)ixv[c & 1][i] * DK + segoff[i], stage_u + (c & 1) * 4096 + i * 1024);
+        const int cn = (c + 2 < nch) ? c + 2 : c;
+        ixv[c & 1] = gload128(idx + cn * MC_CHUNK + rg * 4);
+    };
+    auto start_pipeline = [&](const uint8_t *base) {
+        ixv[0] = gload128(idx + rg * 4);
+        ixv[1] = gload128(idx + ((nch > 1) ? MC_CHUNK : 0) + rg * 4);
+        vm_wait<0>();
+        tie(ixv[0]);
+        tie(ixv[1]);
+        if (nch > 0) issue(base, std::integral_constant<int, 0>{});
+        if (nch > 1) issue(base, std::integral_constant<int, 1>{});
+    };
+    // Chunk c (and the indices loaded with it) has landed when only the younger group, if
+    // any, is still outstanding.
+    auto wait_chunk = [&](auto CC) {
+        constexpr int c = CC;
+        if (c + 1 < nch) vm_wait<GROUP>(); else vm_wait<0>();
+        tie(ixv[c & 1]);
     };
 
     // ---- phase K: scores; lane (j, g) owns row 4*(g&1) + r of tile 2*pr + (g >> 1) -----
     constexpr float LOG2E = 1.4426950408889634f;
     const float scale2 = a.score_scale * LOG2E; // softmax in base 2: exp(x - m) = 2^(x2 - m2)
     // K operand of tile tl: slot tl*16 + j -> LDS row (j&3)*16 + tl*4 + (j>>2), segment g ^ (j&3)
-    const int krow = ((j & 3) * 16 + (j >> 2)) * 64 + ((g ^ (j & 3)) * 16);
+    const unsigned kaddr = lds_addr(stage) + ((j & 3) * 16 + (j >> 2)) * 64 + ((g ^ (j & 3)) * 16);
     float x[NPR][4];
     float mrow[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
-#pragma unroll
-    for (int c = 0; c < MAXCH; ++c) {
+    start_pipeline(Kh);
+    static_for<MAXCH>([&](auto C) {
+        constexpr int c = C, ST = (c & 1) * 4096;
+        v4i acc0 = {0, 0, 0, 0}, acc1 = {0, 0, 0, 0};
         if (c < nch) {
-            gather(Kh, c);
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            wait_chunk(C);
+            v4i kA0 = lds_read128<ST>(kaddr), kB0 = lds_read128<ST + 256>(kaddr);
+            v4i kA1 = lds_read128<ST + 512>(kaddr), kB1 = lds_read128<ST + 768>(kaddr);
+            lds_wait(kA0, kB0, kA1, kB1);
+            if (c + 2 < nch) issue(Kh, std::integral_constant<int, c + 2>{}); // the stage is free again
+            acc0 = __builtin_amdgcn_mfma_i32_16x16x64_i8(q_lo, kA0, acc0, 0, 0, 0);
+            acc0 = __builtin_amdgcn_mfma_i32_16x16x64_i8(q_hi, kB0, acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_i32_16x16x64_i8(q_lo, kA1, acc1, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_i32_16x16x64_i8(q_hi, kB1, acc1, 0, 0, 0);
         }
 #pragma unroll
         for (int pr = 0; pr < 2; ++pr) {
-            v4i acc = {0, 0, 0, 0};
-            if (c < nch) {
-                const v4i kA = *reinterpret_cast<const v4i *>(stage + krow + (2 * pr) * 256);
-                const v4i kB = *reinterpret_cast<const v4i *>(stage + krow + (2 * pr + 1) * 256);
-                acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(q_lo, kA, acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(q_hi, kB, acc, 0, 0, 0);
-            }
+            const v4i acc = pr ? acc1 : acc0;
             const bool valid = c * MC_CHUNK + (2 * pr + (g >> 1)) * 16 + j < n;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
@@ -121,8 +147,9 @@ __global__ __launch_bounds__(64, 4) void attention_fused_kernel(AttnArgs a)
                 mrow[r] = fmaxf(mrow[r], x[c * 2 + pr][r]);
             }
         }
-        if (c < nch) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); // rows consumed before the next gather
-    }
+    });
+    // all Kmat rows are consumed: start copying V rows while the softmax runs
+    start_pipeline(Vh);
 
     // ---- softmax over row 4*(g&1) + r ---------------------------------------------------------
     float srow[4] = {0.f, 0.f, 0.f, 0.f};
@@ -167,32 +194,41 @@ __global__ __launch_bounds__(64, 4) void attention_fused_kernel(AttnArgs a)
 #pragma unroll
     for (int ct = 0; ct < 4; ++ct) o[ct] = (v4i){0, 0, 0, 0};
     const int src = lane & 15, ii = src >> 1;
-    int vaddr[2], paddr[2];
+    unsigned vaddr[2][4], paddr[2];
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
         const int s = g * 16 + 8 * h + ii;   // slot within the chunk supplied by this lane
-        vaddr[h] = (s & 3) * 1024 + (s >> 2) * 64 + ((s & 3) * 16) + 8 * (src & 1);
-        paddr[h] = s * 8;
-    }
-    for (int c = 0; c < nch; ++c) {
-        gather(Vh, c);
-        // codes of this chunk, transposed to the MFMA row operand: row j < 8, slots g*16 .. +15
-        const v2i p0 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(Pl + c * 512 + paddr[0]));
-        const v2i p1 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(Pl + c * 512 + paddr[1]));
-        v4i aop = {p0.x, p0.y, p1.x, p1.y};
-        if (j >= 8) aop = (v4i){0, 0, 0, 0};
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        const int base = (s & 3) * 1024 + (s >> 2) * 64 + ((s & 3) * 16) + 8 * (src & 1);
 #pragma unroll
-        for (int ct = 0; ct < 4; ++ct) {
-            const v2i d0 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(stage + (vaddr[0] ^ (ct * 16))));
-            const v2i d1 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(stage + (vaddr[1] ^ (ct * 16))));
-            const v4i bop = {d0.x, d0.y, d1.x, d1.y};
-            o[ct] = __builtin_amdgcn_mfma_i32_16x16x64_i8(aop, bop, o[ct], 0, 0, 0);
-        }
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        for (int ct = 0; ct < 4; ++ct) vaddr[h][ct] = lds_addr(stage) + (base ^ (ct * 16));
+        paddr[h] = lds_addr(Pl) + s * 8;
     }
+    static_for<MAXCH>([&](auto C) {
+        constexpr int c = C;
+        if (c < nch) {
+            wait_chunk(C);
+            // codes of this chunk, transposed to the MFMA row operand: row j < 8, slots g*16 .. +15
+            v2i p0 = lds_read_tr8<c * 512>(paddr[0]), p1 = lds_read_tr8<c * 512>(paddr[1]);
+            v2i d[4][2];
+#pragma unroll
+            for (int ct = 0; ct < 4; ++ct) {
+                d[ct][0] = lds_read_tr8<(c & 1) * 4096>(vaddr[0][ct]);
+                d[ct][1] = lds_read_tr8<(c & 1) * 4096>(vaddr[1][ct]);
+            }
+            lds_wait(p0, p1, d[0][0], d[0][1], d[1][0], d[1][1], d[2][0], d[2][1], d[3][0], d[3][1]);
+            if (c + 2 < nch) issue(Vh, std::integral_constant<int, c + 2>{});
+            v4i aop = {p0.x, p0.y, p1.x, p1.y};
+            if (j >= 8) aop = (v4i){0, 0, 0, 0};
+#pragma unroll
+            for (int ct = 0; ct < 4; ++ct) {
+                const v4i bop = {d[ct][0].x, d[ct][0].y, d[ct][1].x, d[ct][1].y};
+                o[ct] = __builtin_amdgcn_mfma_i32_16x16x64_i8(aop, bop, o[ct], 0, 0, 0);
+            }
+        }
+    });
 
     // ---- output: 8 x 64 tile through LDS, scaled, 16-byte stores ------------------------------
+    vm_wait<0>();
     int *Ol = reinterpret_cast<int *>(stage);
     if (g < 2) {
 #pragma unroll
@@ -218,7 +254,7 @@ int attention_fused_max_vectors() { return 8 * 64; }
 hipError_t launch_attention_fused(const AttnArgs &a, hipStream_t s)
 {
     if (a.P == 0 || a.heads == 0) return hipSuccess;
-    dim3 grid((unsigned)a.P, (unsigned)a.heads), block(64);
+    dim3 grid((unsigned)a.P * (unsigned)a.heads), block(64);
     hipLaunchKernelGGL((attention_fused_kernel<8>), grid, block, 0, s, a);
     return hipGetLastError();
 }
