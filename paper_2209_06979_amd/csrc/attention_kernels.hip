@@ -234,14 +234,14 @@ __global__ __launch_bounds__(64, 4) void attention_fused_kernel(AttnArgs a)
 #pragma unroll
         for (int ct = 0; ct < 4; ++ct)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) Ol[(4 * g + r) * DK + ct * 16 + j] = o[ct][r];
+            for (int r = 0; r < 4; ++r) Ol[(4 * g + r) * (DK + 4) + ct * 16 + j] = o[ct][r];
     }
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     __builtin_amdgcn_wave_barrier();
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
         const int piece = h * 64 + lane, row = piece >> 4, col = (piece & 15) * 4;
-        const v4i sres = *reinterpret_cast<const v4i *>(&Ol[row * DK + col]);
+        const v4i sres = *reinterpret_cast<const v4i *>(&Ol[row * (DK + 4) + col]);
         const v4f f = {sres.x * a.out_scale, sres.y * a.out_scale, sres.z * a.out_scale, sres.w * a.out_scale};
         *reinterpret_cast<v4f *>(Oh + row * DK + col) = f;
     }

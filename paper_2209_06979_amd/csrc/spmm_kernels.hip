@@ -73,7 +73,8 @@ template <int BNB, int WK, int MODE> struct SpmmCfg {
     static constexpr int STAGE = 64 * BNB;               // LDS bytes of one staged chunk
     static constexpr int COLS = BNB * (R4 ? 2 : 1);      // output columns of the tile
     static constexpr int OROWS = (MODE == PREC_L16R8) ? 16 : 8;
-    static constexpr int OTILE = OROWS * COLS * 4;       // bytes of one wave's partial tile
+    static constexpr int TST = COLS + 4;                 // row stride (ints) of a partial tile: +4 keeps rows 4 apart in different banks
+    static constexpr int OTILE = OROWS * TST * 4;        // bytes of one wave's partial tile
     static constexpr int PERWAVE = (STAGE > OTILE) ? STAGE : OTILE;
     static constexpr int LDS = WK * PERWAVE;
 };
@@ -82,7 +83,7 @@ template <int BNB, int WK, int MODE>
 __global__ __launch_bounds__(64 * WK) void spmm_kernel(SpmmArgs a)
 {
     using Cfg = SpmmCfg<BNB, WK, MODE>;
-    constexpr int LPR = Cfg::LPR, NI = Cfg::NI, RPI = Cfg::RPI, NACC = Cfg::NACC, COLS = Cfg::COLS;
+    constexpr int LPR = Cfg::LPR, NI = Cfg::NI, RPI = Cfg::RPI, NACC = Cfg::NACC, COLS = Cfg::COLS, TST = Cfg::TST;
     constexpr bool R4 = Cfg::R4;
     __shared__ __attribute__((aligned(16))) char lds[Cfg::LDS];
 
@@ -173,9 +174,9 @@ __global__ __launch_bounds__(64 * WK) void spmm_kernel(SpmmArgs a)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 if (!R4) {
-                    tile_w[(4 * g + r) * COLS + ct * 16 + j] = acc[ct][r];
+                    tile_w[(4 * g + r) * TST + ct * 16 + j] = acc[ct][r];
                 } else {
-                    *reinterpret_cast<v2i *>(&tile_w[(4 * g + r) * COLS + ct * 32 + 2 * j]) = (v2i){acc[2 * ct][r], acc[2 * ct + 1][r]};
+                    *reinterpret_cast<v2i *>(&tile_w[(4 * g + r) * TST + ct * 32 + 2 * j]) = (v2i){acc[2 * ct][r], acc[2 * ct + 1][r]};
                 }
             }
     }
@@ -192,8 +193,8 @@ __global__ __launch_bounds__(64 * WK) void spmm_kernel(SpmmArgs a)
 #pragma unroll
         for (int ww = 0; ww < WK; ++ww) {
             const int *t = reinterpret_cast<const int *>(lds + ww * Cfg::PERWAVE);
-            s += *reinterpret_cast<const v4i *>(&t[row * COLS + col]);
-            if (MODE == PREC_L16R8) lo += *reinterpret_cast<const v4i *>(&t[(row + 8) * COLS + col]);
+            s += *reinterpret_cast<const v4i *>(&t[row * TST + col]);
+            if (MODE == PREC_L16R8) lo += *reinterpret_cast<const v4i *>(&t[(row + 8) * TST + col]);
         }
         if (MODE == PREC_L16R8) s = (s << 8) + lo;      // wrapping 32-bit arithmetic
         else if (MODE == PREC_L8R4) s = s >> 4;
@@ -218,13 +219,13 @@ template <int BNB, int WK, int MODE> hipError_t launch_one(const SpmmArgs &a, hi
 
 template <int BNB, int MODE> hipError_t launch_wk(const SpmmArgs &a, int waves, hipStream_t s)
 {
-    // one staged chunk of 64 x BNB bytes per wave must fit the 64 KB of static LDS
-    constexpr int MAXW = (64 * BNB * 8 <= 65536) ? 8 : 4;
+    // the per-wave LDS regions of a workgroup must fit 64 KB
+    constexpr int MAXW = (SpmmCfg<BNB, 8, MODE>::LDS <= 65536) ? 8 : ((SpmmCfg<BNB, 4, MODE>::LDS <= 65536) ? 4 : 2);
     if (waves > MAXW) waves = MAXW;
     switch (waves) {
     case 1: return launch_one<BNB, 1, MODE>(a, s);
     case 2: return launch_one<BNB, 2, MODE>(a, s);
-    case 4: return launch_one<BNB, 4, MODE>(a, s);
+    case 4: return launch_one<BNB, (MAXW < 4 ? MAXW : 4), MODE>(a, s);
     default: return launch_one<BNB, MAXW, MODE>(a, s);
     }
 }
