@@ -4,7 +4,7 @@
 A *step* is one pass of every kernel row of the path at the headline shape
 (4096 x 4096, V = 8, 90 % of the vectors zero): SpMM L8-R8 / L8-R4 / L4-R4 / L16-R8
 with N = 256, SDDMM L8-R8 / L4-R4 with K = 256, and the quantized sparse-attention
-layer (8 heads, L = 4096, d_k = 64: SDDMM -> softmax -> int8 -> SpMM).  Inputs are
+layer (8 heads, L = 4096, d_k = 64, token-major Q/K/V: SDDMM -> softmax -> int8 -> SpMM).  Inputs are
 seeded synthetic data already resident in HBM; the sparse operands were converted to
 the device format beforehand (the paper builds its format offline as well).
 
@@ -74,6 +74,8 @@ def main():
     ap.add_argument("--reps", type=int, default=200, help="back-to-back launches for the per-kernel timings")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--only", default="", help="comma-separated kernel names: run only these in the step")
+    ap.add_argument("--attention-layout", choices=["token", "head"], default="token",
+                    help="Q/K/V buffers token-major (L, heads, dk) as a projection writes them, or head-major (heads, L, dk)")
     ap.add_argument("--no-per-kernel", action="store_true", help="skip the per-kernel timing runs (counter collection)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 64 MiB device copy, the known-size kernel that scales FETCH_SIZE / WRITE_SIZE")
@@ -122,8 +124,16 @@ def main():
             bytes=sddmm_alg_bytes(mask.nvec, M // V, mc.LHS_BITS[prec], KD_SDDMM)))
     att = prob["attention"]
     amask = mc.SparseMatrix(L_ATT, L_ATT, V, att["row_ptr"], att["col_idx"])
-    q8, k8, v8 = up(att["q8"]), up(att["k8"]), up(att["v8"])
-    O = torch.empty((HEADS, L_ATT, DK), dtype=torch.float32, device=dev)
+    # token-major layout, as a QKV projection writes it: buffer (L, heads, dk), viewed (heads, L, dk)
+    def token_major(a):
+        if args.attention_layout == "head":
+            return up(a)
+        return up(np.ascontiguousarray(np.transpose(a, (1, 0, 2)))).permute(1, 0, 2)
+    q8, k8, v8 = token_major(att["q8"]), token_major(att["k8"]), token_major(att["v8"])
+    if args.attention_layout == "head":
+        O = torch.empty((HEADS, L_ATT, DK), dtype=torch.float32, device=dev)
+    else:
+        O = torch.empty((L_ATT, HEADS, DK), dtype=torch.float32, device=dev).permute(1, 0, 2)
     ws = torch.empty(mc.attention_workspace_bytes(HEADS, amask), dtype=torch.uint8, device=dev)
     keep += [amask, q8, k8, v8, O, ws]
     nnz_att = amask.nvec * V

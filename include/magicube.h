@@ -164,7 +164,7 @@ int mc_sparse_softmax(const mc_mat *mask, int batch, const int32_t *S_dev, float
  * Quantized sparse self-attention layer (Section 5.3), one mask shared by all heads:
  *   O[h] = ( P_q[h] * Vm[h] ) * (s_p * s_v),
  *   P_q[h] = int8( softmax( SDDMM(Q[h], Km[h]; mask) * s_q*s_k/sqrt(dk) ) / s_p )
- *   Q_dev, Km_dev, Vm_dev   heads x L x dk int8, contiguous
+ *   Q_dev, Km_dev, Vm_dev   heads x L x dk int8, contiguous (see the strided variant below)
  *   mask                    L x L pattern, V = 8
  *   O_dev                   heads x L x dk fp32
  *   workspace_dev           at least mc_attention_workspace_bytes(heads, mask) bytes,
@@ -174,6 +174,16 @@ int mc_sparse_softmax(const mc_mat *mask, int batch, const int32_t *S_dev, float
  * pipeline (see mc_set_attention_mode) but must always be supplied.
  * ---------------------------------------------------------------------------------- */
 size_t mc_attention_workspace_bytes(int heads, const mc_mat *mask);
+/* The same layer for any regular layout: element (head h, token l, d) of Q, Km, Vm (int8)
+ * and of O (fp32) sits at h*head_stride + l*token_stride + d (strides in elements, both
+ * multiples of 16).  mc_sparse_attention is the case head_stride = L*dk, token_stride = dk.
+ * The token-major layout a QKV projection produces (head_stride = dk, token_stride =
+ * heads*dk) is the fast one: with dk = 64 and an even number of heads, two neighbouring
+ * heads are gathered with one 128-byte request per token. */
+int mc_sparse_attention_strided(const int8_t *Q_dev, const int8_t *Km_dev, const int8_t *Vm_dev, int heads, int L,
+                                int dk, int64_t head_stride, int64_t token_stride, const mc_mat *mask, float s_q,
+                                float s_k, float s_v, float s_p, float *O_dev, void *workspace_dev,
+                                size_t workspace_bytes, void *stream);
 int mc_sparse_attention(const int8_t *Q_dev, const int8_t *Km_dev, const int8_t *Vm_dev, int heads, int L,
                         int dk, const mc_mat *mask, float s_q, float s_k, float s_v, float s_p,
                         float *O_dev, void *workspace_dev, size_t workspace_bytes, void *stream);

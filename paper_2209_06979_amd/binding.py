@@ -58,11 +58,14 @@ def _load() -> ctypes.CDLL:
     L.mc_attention_workspace_bytes.argtypes = [c_int, c_void_p]; L.mc_attention_workspace_bytes.restype = c_size_t
     L.mc_sparse_attention.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_void_p,
                                       c_float, c_float, c_float, c_float, c_void_p, c_void_p, c_size_t, c_void_p]
+    L.mc_sparse_attention_strided.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int64, c_int64,
+                                              c_void_p, c_float, c_float, c_float, c_float, c_void_p, c_void_p,
+                                              c_size_t, c_void_p]
     L.mc_set_spmm_variant.argtypes = [c_int, c_int]
     L.mc_set_attention_mode.argtypes = [c_int]
     L.mc_set_sddmm_variant.argtypes = [c_int]
     for name in ("mc_layout_query", "mc_pack_host", "mc_unpack_host", "mc_mat_create", "mc_mat_set_values_device",
-                 "mc_mat_info", "mc_spmm", "mc_sddmm", "mc_sparse_softmax", "mc_sparse_attention",
+                 "mc_mat_info", "mc_spmm", "mc_sddmm", "mc_sparse_softmax", "mc_sparse_attention", "mc_sparse_attention_strided",
                  "mc_set_spmm_variant", "mc_set_attention_mode", "mc_set_sddmm_variant"):
         getattr(L, name).restype = c_int
     return L
@@ -224,18 +227,30 @@ def attention_workspace_bytes(heads: int, mask: SparseMatrix) -> int:
 
 
 def sparse_attention(Q8, K8, V8, mask: SparseMatrix, s_q, s_k, s_v, s_p, out=None, workspace=None):
-    """Quantized sparse self-attention; Q8/K8/V8: (heads, L, dk) int8 device tensors."""
-    for t in (Q8, K8, V8):
-        assert t.is_cuda and t.dtype == torch.int8 and t.is_contiguous() and t.shape == Q8.shape
+    """Quantized sparse self-attention; Q8/K8/V8: (heads, L, dk) int8 device tensors.
+
+    Any layout with unit stride along dk is accepted as long as the three tensors (and
+    ``out``) share it; a (heads, L, dk) view of a token-major (L, heads, dk) buffer, i.e.
+    ``x.permute(1, 0, 2)``, selects the fast two-heads-per-request path.
+    """
     heads, L, dk = Q8.shape
+    hs, ts = Q8.stride(0), Q8.stride(1)
+    for t in (Q8, K8, V8):
+        assert t.is_cuda and t.dtype == torch.int8 and t.shape == Q8.shape and t.stride() == (hs, ts, 1)
     if out is None:
-        out = torch.empty((heads, L, dk), dtype=torch.float32, device=Q8.device)
+        # same layout as the inputs
+        if hs < ts:
+            out = torch.empty((L, heads, dk), dtype=torch.float32, device=Q8.device).permute(1, 0, 2)
+        else:
+            out = torch.empty((heads, L, dk), dtype=torch.float32, device=Q8.device)
+    assert out.is_cuda and out.dtype == torch.float32 and out.shape == Q8.shape and out.stride() == (hs, ts, 1)
     need = attention_workspace_bytes(heads, mask)
     if workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=Q8.device)
     assert workspace.is_cuda and workspace.is_contiguous()
-    _check(lib.mc_sparse_attention(Q8.data_ptr(), K8.data_ptr(), V8.data_ptr(), heads, L, dk, mask.handle,
-                                   float(s_q), float(s_k), float(s_v), float(s_p), out.data_ptr(),
-                                   workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream()),
-           "mc_sparse_attention")
+    _check(lib.mc_sparse_attention_strided(Q8.data_ptr(), K8.data_ptr(), V8.data_ptr(), heads, L, dk, hs, ts,
+                                           mask.handle, float(s_q), float(s_k), float(s_v), float(s_p),
+                                           out.data_ptr(), workspace.data_ptr(),
+                                           workspace.numel() * workspace.element_size(), _stream()),
+           "mc_sparse_attention_strided")
     return out

@@ -299,37 +299,53 @@ extern "C" int mc_sparse_attention(const int8_t *Q_dev, const int8_t *Km_dev, co
                                    int dk, const mc_mat *mask, float s_q, float s_k, float s_v, float s_p,
                                    float *O_dev, void *workspace_dev, size_t workspace_bytes, void *stream)
 {
+    return mc_sparse_attention_strided(Q_dev, Km_dev, Vm_dev, heads, L, dk, (int64_t)L * dk, dk, mask, s_q, s_k, s_v,
+                                       s_p, O_dev, workspace_dev, workspace_bytes, stream);
+}
+
+extern "C" int mc_sparse_attention_strided(const int8_t *Q_dev, const int8_t *Km_dev, const int8_t *Vm_dev, int heads,
+                                           int L, int dk, int64_t head_stride, int64_t token_stride,
+                                           const mc_mat *mask, float s_q, float s_k, float s_v, float s_p,
+                                           float *O_dev, void *workspace_dev, size_t workspace_bytes, void *stream)
+{
     if (!Q_dev || !Km_dev || !Vm_dev || !mask || !O_dev || !workspace_dev) return MC_EINVAL;
     if (heads <= 0 || L <= 0 || dk <= 0 || dk % 16 != 0) return MC_EINVAL;
     if (mask->M != L || mask->K != L || mask->V != 8) return MC_EINVAL;
     if (!(s_p > 0.f) || !std::isfinite(s_q * s_k * s_v / s_p)) return MC_EINVAL;
+    if (token_stride < dk || head_stride < dk) return MC_EINVAL;
+    if ((int64_t)(L - 1) * token_stride + (int64_t)(heads - 1) * head_stride + dk > (int64_t)INT32_MAX) return MC_EINVAL;
+    if (L > (1 << 24) || token_stride >= (1 << 24)) return MC_EINVAL; // kernels use 24-bit multiplies
+    if (token_stride % 16 != 0 || head_stride % 16 != 0) return MC_EALIGN;
     if (!aligned16(Q_dev) || !aligned16(Km_dev) || !aligned16(Vm_dev) || !aligned16(O_dev)) return MC_EALIGN;
     if ((reinterpret_cast<uintptr_t>(workspace_dev) & 255u) != 0) return MC_EALIGN;
     const AttnWs ws = attn_layout(heads, mask);
     if (workspace_bytes < ws.total) return MC_ENOMEM;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    uint8_t *wsb = static_cast<uint8_t *>(workspace_dev);
-    int32_t *scores = reinterpret_cast<int32_t *>(wsb + ws.scores);
-    int8_t *codes = reinterpret_cast<int8_t *>(wsb + ws.codes);
-    uint8_t *pvals = wsb + ws.vals;
     const int64_t nnz = mask->nvec * mask->V;
-    const int64_t head_elems = (int64_t)L * dk;
 
     if (g_attention_mode == 0 && dk == 64 && mask->max_panel_chunks * MC_CHUNK <= attention_fused_max_vectors()) {
         AttnArgs f;
         f.panel_ptr = mask->d_panel_ptr; f.slot_idx = mask->d_slot_idx;
         f.Q = reinterpret_cast<const uint8_t *>(Q_dev); f.Km = reinterpret_cast<const uint8_t *>(Km_dev);
-        f.Vm = reinterpret_cast<const uint8_t *>(Vm_dev); f.O = O_dev; f.head_stride = head_elems;
+        f.Vm = reinterpret_cast<const uint8_t *>(Vm_dev); f.O = O_dev;
+        f.head_stride = head_stride; f.token_stride = token_stride;
         f.score_scale = s_q * s_k / std::sqrt((float)dk); f.inv_s_p = 1.f / s_p; f.out_scale = s_p * s_v;
         f.P = mask->P; f.heads = heads;
-        MC_HIP(launch_attention_fused(f, s));
+        // neighbouring heads contiguous inside a token: two heads per workgroup, 128-byte gathers
+        const int hpg = (head_stride == 64 && heads % 2 == 0) ? 2 : 1;
+        MC_HIP(launch_attention_fused(f, hpg, s));
         return MC_OK;
     }
 
+    uint8_t *wsb = static_cast<uint8_t *>(workspace_dev);
+    int32_t *scores = reinterpret_cast<int32_t *>(wsb + ws.scores);
+    int8_t *codes = reinterpret_cast<int8_t *>(wsb + ws.codes);
+    uint8_t *pvals = wsb + ws.vals;
+
     SddmmArgs d;
     d.panel_ptr = mask->d_panel_ptr; d.row_ptr = mask->d_row_ptr; d.slot_idx = mask->d_slot_idx;
-    d.Q = reinterpret_cast<const uint8_t *>(Q_dev); d.ldq_bytes = dk; d.Q_batch_stride = head_elems;
-    d.Kmat = reinterpret_cast<const uint8_t *>(Km_dev); d.ldk_bytes = dk; d.K_batch_stride = head_elems;
+    d.Q = reinterpret_cast<const uint8_t *>(Q_dev); d.ldq_bytes = token_stride; d.Q_batch_stride = head_stride;
+    d.Kmat = reinterpret_cast<const uint8_t *>(Km_dev); d.ldk_bytes = token_stride; d.K_batch_stride = head_stride;
     d.row_bytes = dk; d.S = scores; d.S_batch_stride = nnz;
     d.P = mask->P; d.V = 8; d.batch = heads;
     MC_HIP(launch_sddmm(false, d, choose_sddmm_waves(mask, heads), s));
@@ -350,8 +366,8 @@ extern "C" int mc_sparse_attention(const int8_t *Q_dev, const int8_t *Km_dev, co
     SpmmArgs m;
     m.panel_ptr = mask->d_panel_ptr; m.slot_idx = mask->d_slot_idx;
     m.vals = pvals; m.vals_batch_stride = mask->nslots * 8;
-    m.B = reinterpret_cast<const uint8_t *>(Vm_dev); m.ldb_bytes = dk; m.B_batch_stride = head_elems;
-    m.row_bytes = dk; m.C = O_dev; m.ldc = dk; m.C_batch_stride = head_elems;
+    m.B = reinterpret_cast<const uint8_t *>(Vm_dev); m.ldb_bytes = token_stride; m.B_batch_stride = head_stride;
+    m.row_bytes = dk; m.C = O_dev; m.ldc = token_stride; m.C_batch_stride = head_stride;
     m.P = mask->P; m.V = 8; m.batch = heads; m.float_out = 1; m.out_scale = s_p * s_v;
     int bnb, waves;
     choose_variant(mask, m.row_bytes, false, heads, &bnb, &waves);

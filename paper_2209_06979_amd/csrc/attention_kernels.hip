@@ -1,27 +1,35 @@
 // Fused quantized sparse self-attention for gfx950 (paper, Section 5.3): for one head and
 // one row panel of the mask ONE WAVEFRONT runs SDDMM -> softmax -> int8 codes -> SpMM with
-// the scores, probabilities and codes never leaving registers / LDS.  A wave never waits
-// for another wave; latency is hidden by keeping ~16 such waves resident per CU, each
-// with one 4 KB chunk of gathered rows in flight.
+// the scores, probabilities and codes never leaving registers / LDS.  Latency is hidden by
+// keeping a dozen such waves resident per CU, each with chunks of gathered rows in flight.
 //
 //   phase K  per chunk of 64 mask vectors: the Kmat rows named by the column indices are
-//            copied from global memory straight into LDS (global_load_lds, 4 neighbouring
-//            lanes per 64-byte row, no registers in between); one v_mfma_i32_16x16x64_i8
-//            per 16 vectors gives the scores (head dim 64 = one MFMA; both operands are
-//            contiguous along the reduction, Section 4.3).  The 8 Q rows sit in MFMA rows
-//            0..7 for even tiles and in rows 8..15 for odd tiles, so two tiles share one
-//            accumulator and all 64 lanes carry real scores.
+//            copied from global memory straight into LDS (global_load_lds, no registers in
+//            between); one v_mfma_i32_16x16x64_i8 per 16 vectors gives the scores (head dim
+//            64 = one MFMA; both operands are contiguous along the reduction, Section 4.3).
+//            The 8 Q rows sit in MFMA rows 0..7 for even tiles and in rows 8..15 for odd
+//            tiles, so two tiles share one accumulator and all 64 lanes carry real scores.
 //   softmax  fp32, base 2, over the panel's stored entries: in-lane over the tiles, DPP
 //            rotations over the 16 lanes of a row, one cross-lane exchange for the two
 //            tile parities; codes = clamp(rint(p / s_p), 0, 127) go to LDS as
 //            [slot][8 rows] bytes (one 32-bit write per 4 codes).
-//   phase V  SpMM (Section 4.2) per chunk: V rows are copied into the same LDS stage;
+//   phase V  SpMM (Section 4.2) per chunk: V rows are copied into the same LDS stages;
 //            ds_read_b64_tr_b8 delivers both MFMA operands in place: the codes transposed
 //            to [row][16 slots] and the V rows transposed to [column][16 slots].
 //   output   the 8 x 64 tile goes through LDS once to be stored as fp32 with 16-byte stores.
-// LDS rows are 64 bytes; slot s of a chunk lives in row (s % 4) * 16 + s / 4 (so that a
-// lane's 4 column indices are consecutive) and its 16-byte segments are XOR-swizzled with
-// s % 4 so that rows read together fall into different banks.
+//
+// Two variants (HPW = heads per workgroup):
+//   HPW 1  any layout: the wave gathers the 64-byte rows of its own head; two chunks in
+//          flight, ordered by counted vmcnt waits.
+//   HPW 2  token-major layout (the heads of a token are contiguous, as a QKV projection
+//          writes them): two waves own two neighbouring heads and gather their 128 bytes of
+//          a token with ONE request.  The L2 serves a 128-byte line at the cost of a 64-byte
+//          half, so this halves the number of gather requests, which is what bounds the
+//          kernel.  Each wave copies half of a chunk's rows; one s_barrier per chunk.
+// LDS rows are 64*HPW bytes; slot s of a chunk lives in row (s % NIT) * (64/NIT) + s / NIT
+// (NIT = 4*HPW copy instructions per chunk, so that a lane's 4 column indices are
+// consecutive) and its 16-byte segments are XOR-swizzled with s % NIT so that rows read
+// together fall into different banks.
 #include "internal.h"
 #include "lds_async.h"
 
@@ -42,6 +50,14 @@ __device__ __forceinline__ float row16_max(float v)
     v = fmaxf(v, dpp_rot<0x128>(v));
     return v;
 }
+__device__ __forceinline__ int row16_imax(int v)
+{
+    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x121, 0xF, 0xF, false)); // row_ror:1
+    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x122, 0xF, 0xF, false));
+    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x124, 0xF, 0xF, false));
+    v = max(v, __builtin_amdgcn_update_dpp(0, v, 0x128, 0xF, 0xF, false));
+    return v;
+}
 __device__ __forceinline__ float row16_sum(float v)
 {
     v += dpp_rot<0x121>(v);
@@ -51,143 +67,192 @@ __device__ __forceinline__ float row16_sum(float v)
     return v;
 }
 
-// MAXCH: longest panel in chunks of 64 vectors.
-template <int MAXCH>
-__global__ __launch_bounds__(64, 4) void attention_fused_kernel(AttnArgs a)
+// MAXCH: longest panel in chunks of 64 vectors.  HPW: heads (= waves) per workgroup.
+template <int MAXCH, int HPW>
+__global__ __launch_bounds__(64 * HPW, (HPW == 1 ? 4 : 3)) void attention_fused_kernel(AttnArgs a)
 {
     constexpr int DK = 64;
-    constexpr int NPR = MAXCH * 2; // pairs of score tiles
-    constexpr int GROUP = 5;       // memory instructions per chunk: 4 row copies + 1 index load
-    __shared__ __attribute__((aligned(16))) char stage[2 * 4096];    // two chunks of gathered rows
-    __shared__ __attribute__((aligned(16))) char Pl[MAXCH * 64 * 8]; // codes, [slot][8 rows]
+    constexpr int NPR = MAXCH * 2;   // pairs of score tiles
+    constexpr int ROWB = DK * HPW;   // bytes of a gathered row
+    constexpr int LPR = ROWB / 16;   // lanes per row
+    constexpr int NIT = LPR;         // copy instructions per chunk (4 of them per wave)
+    constexpr int SWZ = LPR - 1;
+    constexpr int STG = 64 * ROWB;   // bytes of one stage
+    constexpr int GROUP = 5;         // memory instructions per chunk and wave: 4 row copies + 1 index load
+    __shared__ __attribute__((aligned(16))) char stage[2 * STG];           // two chunks of gathered rows
+    __shared__ __attribute__((aligned(16))) char Pl_all[HPW * MAXCH * 512]; // codes, [slot][8 rows], per wave
 
-    const int lane = threadIdx.x;
+    const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int j = lane & 15, g = lane >> 4;
-    const int rg = lane >> 2, seg = lane & 3;
-    // Workgroups are handed to the 8 XCDs round-robin by linear id.  With id = panel * heads +
-    // head, an XCD only ever sees the heads congruent to its number, so its L2 has to hold the
-    // Kmat and V rows of those heads (1/8 of the data for 8 heads) instead of all of them.
-    const int head = blockIdx.x % a.heads, panel = blockIdx.x / a.heads;
+    const int rg = lane / LPR, seg = lane % LPR;
+    // Workgroups are handed to the 8 XCDs round-robin by linear id.  With id = panel * groups +
+    // head group, an XCD only ever sees the head groups congruent to its number, so its L2 has
+    // to hold the Kmat and V rows of those heads only.
+    const int groups = a.heads / HPW;
+    const int hgrp = blockIdx.x % groups, panel = blockIdx.x / groups;
+    const int head = hgrp * HPW + w;
     const int s0 = a.panel_ptr[2 * panel], n = a.panel_ptr[2 * panel + 1] - s0;
     const int nch = (n + MC_CHUNK - 1) / MC_CHUNK;
     const int32_t *idx = a.slot_idx + s0;
+    const int64_t goff = (int64_t)hgrp * HPW * a.head_stride; // first head of the group
     const int64_t hoff = (int64_t)head * a.head_stride;
-    const uint8_t *Kh = a.Km + hoff, *Vh = a.Vm + hoff;
-    float *Oh = a.O + hoff + (int64_t)panel * 8 * DK;
+    const uint8_t *Kg = a.Km + goff, *Vg = a.Vm + goff;
+    float *Oh = a.O + hoff + (int64_t)panel * 8 * a.token_stride;
+    char *Pl = Pl_all + w * (MAXCH * 512);
 
     // Q rows twice: in MFMA rows 0..7 (q_lo) and in rows 8..15 (q_hi)
     v4i q_lo = {0, 0, 0, 0}, q_hi = {0, 0, 0, 0};
     {
-        const v4i qv = *reinterpret_cast<const v4i *>(a.Q + hoff + (int64_t)(panel * 8 + (j & 7)) * DK + g * 16);
+        const v4i qv = *reinterpret_cast<const v4i *>(a.Q + hoff + (int64_t)(panel * 8 + (j & 7)) * a.token_stride + g * 16);
         if (j < 8) q_lo = qv; else q_hi = qv;
     }
-    // Lane (rg, seg), copy instruction i: segment seg ^ i of the row in slot rg*4 + i.
-    // One group of GROUP memory instructions per chunk: its 4 row copies, then the load of the
-    // column indices of the chunk two steps ahead (clamped) into the registers the copies have
-    // just consumed -- the index registers alternate with the chunk parity.
-    int segoff[4];
+    // Copy instruction i of a chunk: lane (rg, seg) fetches segment seg ^ i of the row in slot
+    // rg*NIT + i; it lands in LDS row i*(64/NIT) + rg.  Wave w issues instructions 4w .. 4w+3,
+    // whose 4 column indices are consecutive slots: one 128-bit index load per chunk.
+    unsigned segoff[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) segoff[i] = (seg ^ i) * 16;
+    for (int i = 0; i < 4; ++i) segoff[i] = (seg ^ ((4 * w + i) & SWZ)) * 16;
     const unsigned stage_u = lds_addr_uniform(stage);
+    const int32_t *myidx = idx + rg * NIT + 4 * w;
+    const unsigned tstride = (unsigned)a.token_stride;
     v4i ixv[2];
+    // HPW 1: group(c) = copies of chunk c, then the indices of chunk c+2 into the registers
+    //        the copies have consumed; two groups in flight.
+    // HPW 2: group(c) = copies of chunk c, then the indices of chunk c+1 into the other
+    //        register set; one group in flight, issued right after the chunk barrier.
     auto issue = [&](const uint8_t *base, auto CC) {
         constexpr int c = CC;
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-            copy16_to_lds(base + (unsigned)ixv[c & 1][i] * DK + segoff[i], stage_u + (c & 1) * 4096 + i * 1024);
-        const int cn = (c + 2 < nch) ? c + 2 : c;
-        ixv[c & 1] = gload128(idx + cn * MC_CHUNK + rg * 4);
+            copy16_to_lds(base, __umul24(ixv[c & 1][i], tstride) + segoff[i], stage_u + (c & 1) * STG + (4 * w + i) * 1024);
+        if (HPW == 1) {
+            const int cn = (c + 2 < nch) ? c + 2 : c;
+            ixv[c & 1] = gload128(myidx + cn * MC_CHUNK);
+        } else {
+            const int cn = (c + 1 < nch) ? c + 1 : c;
+            ixv[(c + 1) & 1] = gload128(myidx + cn * MC_CHUNK);
+        }
     };
     auto start_pipeline = [&](const uint8_t *base) {
-        ixv[0] = gload128(idx + rg * 4);
-        ixv[1] = gload128(idx + ((nch > 1) ? MC_CHUNK : 0) + rg * 4);
+        if (HPW > 1) __builtin_amdgcn_s_barrier(); // both waves are done with the stages
+        ixv[0] = gload128(myidx);
+        if (HPW == 1) ixv[1] = gload128(myidx + ((nch > 1) ? MC_CHUNK : 0));
         vm_wait<0>();
         tie(ixv[0]);
-        tie(ixv[1]);
+        if (HPW == 1) tie(ixv[1]);
         if (nch > 0) issue(base, std::integral_constant<int, 0>{});
-        if (nch > 1) issue(base, std::integral_constant<int, 1>{});
+        if (HPW == 1 && nch > 1) issue(base, std::integral_constant<int, 1>{});
     };
-    // Chunk c (and the indices loaded with it) has landed when only the younger group, if
-    // any, is still outstanding.
-    auto wait_chunk = [&](auto CC) {
+    // Makes chunk c readable and keeps the pipeline full.
+    auto acquire = [&](const uint8_t *base, auto CC) {
         constexpr int c = CC;
-        if (c + 1 < nch) vm_wait<GROUP>(); else vm_wait<0>();
-        tie(ixv[c & 1]);
+        if (HPW == 1) {
+            // landed when only the younger group, if any, is still outstanding
+            if (c + 1 < nch) vm_wait<GROUP>(); else vm_wait<0>();
+            tie(ixv[c & 1]);
+        } else {
+            vm_wait<0>();                 // my half of chunk c and the next indices
+            tie(ixv[(c + 1) & 1]);
+            __builtin_amdgcn_s_barrier(); // the other half too; and everybody is done reading chunk c-1
+            if (c + 1 < nch) issue(base, std::integral_constant<int, c + 1>{});
+        }
+    };
+    auto release = [&](const uint8_t *base, auto CC) { // after the reads of chunk c have completed
+        constexpr int c = CC;
+        if (HPW == 1 && c + 2 < nch) issue(base, std::integral_constant<int, c + 2>{});
     };
 
     // ---- phase K: scores; lane (j, g) owns row 4*(g&1) + r of tile 2*pr + (g >> 1) -----
-    constexpr float LOG2E = 1.4426950408889634f;
-    const float scale2 = a.score_scale * LOG2E; // softmax in base 2: exp(x - m) = 2^(x2 - m2)
-    // K operand of tile tl: slot tl*16 + j -> LDS row (j&3)*16 + tl*4 + (j>>2), segment g ^ (j&3)
-    const unsigned kaddr = lds_addr(stage) + ((j & 3) * 16 + (j >> 2)) * 64 + ((g ^ (j & 3)) * 16);
-    float x[NPR][4];
-    float mrow[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
-    start_pipeline(Kh);
+    // The integer scores stay in registers; only the last chunk can hold padded slots, which
+    // are kept out of the row maximum here and out of the row sum below.
+    // K operand of tile tl: slot s = tl*16 + j sits in LDS row (s % NIT)*(64/NIT) + s/NIT,
+    // i.e. byte (j % NIT)*1024 + (j / NIT)*ROWB + tl*256; segment (4w + g) ^ (j % NIT)
+    const unsigned kaddr = lds_addr(stage) + (j % NIT) * 1024 + (j / NIT) * ROWB + (((4 * w + g) ^ (j % NIT)) * 16);
+    v4i sc[NPR];
+    int imax[4] = {INT32_MIN, INT32_MIN, INT32_MIN, INT32_MIN};
+    const int tail = n - (nch - 1) * MC_CHUNK; // real vectors in the last chunk
+    bool keep[2];                               // this lane's slots of the last chunk are real
+#pragma unroll
+    for (int pr = 0; pr < 2; ++pr) keep[pr] = (2 * pr + (g >> 1)) * 16 + j < tail;
+    start_pipeline(Kg);
     static_for<MAXCH>([&](auto C) {
-        constexpr int c = C, ST = (c & 1) * 4096;
-        v4i acc0 = {0, 0, 0, 0}, acc1 = {0, 0, 0, 0};
+        constexpr int c = C, ST = (c & 1) * STG;
+        sc[2 * c] = (v4i){0, 0, 0, 0};
+        sc[2 * c + 1] = (v4i){0, 0, 0, 0};
         if (c < nch) {
-            wait_chunk(C);
+            acquire(Kg, C);
             v4i kA0 = lds_read128<ST>(kaddr), kB0 = lds_read128<ST + 256>(kaddr);
             v4i kA1 = lds_read128<ST + 512>(kaddr), kB1 = lds_read128<ST + 768>(kaddr);
             lds_wait(kA0, kB0, kA1, kB1);
-            if (c + 2 < nch) issue(Kh, std::integral_constant<int, c + 2>{}); // the stage is free again
-            acc0 = __builtin_amdgcn_mfma_i32_16x16x64_i8(q_lo, kA0, acc0, 0, 0, 0);
-            acc0 = __builtin_amdgcn_mfma_i32_16x16x64_i8(q_hi, kB0, acc0, 0, 0, 0);
-            acc1 = __builtin_amdgcn_mfma_i32_16x16x64_i8(q_lo, kA1, acc1, 0, 0, 0);
-            acc1 = __builtin_amdgcn_mfma_i32_16x16x64_i8(q_hi, kB1, acc1, 0, 0, 0);
-        }
+            release(Kg, C);
+            sc[2 * c] = __builtin_amdgcn_mfma_i32_16x16x64_i8(q_lo, kA0, sc[2 * c], 0, 0, 0);
+            sc[2 * c] = __builtin_amdgcn_mfma_i32_16x16x64_i8(q_hi, kB0, sc[2 * c], 0, 0, 0);
+            sc[2 * c + 1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(q_lo, kA1, sc[2 * c + 1], 0, 0, 0);
+            sc[2 * c + 1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(q_hi, kB1, sc[2 * c + 1], 0, 0, 0);
+            if (c == nch - 1) {
 #pragma unroll
-        for (int pr = 0; pr < 2; ++pr) {
-            const v4i acc = pr ? acc1 : acc0;
-            const bool valid = c * MC_CHUNK + (2 * pr + (g >> 1)) * 16 + j < n;
+                for (int pr = 0; pr < 2; ++pr)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                x[c * 2 + pr][r] = valid ? (float)acc[r] * scale2 : -INFINITY;
-                mrow[r] = fmaxf(mrow[r], x[c * 2 + pr][r]);
+                    for (int r = 0; r < 4; ++r) imax[r] = max(imax[r], keep[pr] ? sc[2 * c + pr][r] : INT32_MIN);
+            } else {
+#pragma unroll
+                for (int pr = 0; pr < 2; ++pr)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) imax[r] = max(imax[r], sc[2 * c + pr][r]);
             }
         }
     });
     // all Kmat rows are consumed: start copying V rows while the softmax runs
-    start_pipeline(Vh);
+    start_pipeline(Vg);
 
-    // ---- softmax over row 4*(g&1) + r ---------------------------------------------------------
-    float srow[4] = {0.f, 0.f, 0.f, 0.f};
+    // ---- softmax over row 4*(g&1) + r, in base 2: exp(x - max) = 2^((s - smax) * scale2) -----
+    constexpr float LOG2E = 1.4426950408889634f;
+    const float scale2 = a.score_scale * LOG2E;
+    float m2[4], srow[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-        mrow[r] = row16_max(mrow[r]);
-        mrow[r] = fmaxf(mrow[r], __shfl_xor(mrow[r], 32, 64));
-        if (mrow[r] == -INFINITY) mrow[r] = 0.f; // empty panel: keep exp2 away from inf - inf
+        imax[r] = row16_imax(imax[r]);
+        imax[r] = max(imax[r], __shfl_xor(imax[r], 32, 64));
+        m2[r] = (float)imax[r] * scale2;
     }
+    float x[NPR][4];
+    static_for<MAXCH>([&](auto C) {
+        constexpr int c = C;
+        if (c < nch) {
 #pragma unroll
-    for (int t = 0; t < NPR; ++t)
+            for (int pr = 0; pr < 2; ++pr)
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            x[t][r] = __builtin_amdgcn_exp2f(x[t][r] - mrow[r]);
-            srow[r] += x[t][r];
+                for (int r = 0; r < 4; ++r) {
+                    float e = __builtin_amdgcn_exp2f(__builtin_fmaf((float)sc[2 * c + pr][r], scale2, -m2[r]));
+                    if (c == nch - 1) e = keep[pr] ? e : 0.f;
+                    x[2 * c + pr][r] = e;
+                    srow[r] += e;
+                }
         }
+    });
+    float rinv[4]; // p / s_p = e * (1 / (sum * s_p)): one division per row instead of one per entry
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
         srow[r] = row16_sum(srow[r]);
         srow[r] += __shfl_xor(srow[r], 32, 64);
+        rinv[r] = a.inv_s_p / srow[r];
     }
-    // codes of slot (tile*16 + j), rows 4*(g&1) .. +3: one 32-bit LDS write
-#pragma unroll
-    for (int c = 0; c < MAXCH; ++c) {
+    // codes of slot (tile*16 + j), rows 4*(g&1) .. +3: one 32-bit LDS write.  v_cvt_pk_u8_f32
+    // rounds to nearest even, saturates to [0, 255] and drops the byte into place; e * rinv
+    // cannot exceed 127 by more than rounding noise.
+    static_for<MAXCH>([&](auto C) {
+        constexpr int c = C;
         if (c < nch) {
 #pragma unroll
             for (int pr = 0; pr < 2; ++pr) {
                 unsigned packed = 0;
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const float code = fminf(fmaxf(rintf(x[c * 2 + pr][r] / srow[r] * a.inv_s_p), 0.f), 127.f);
-                    packed |= (unsigned)(int)code << (8 * r);
-                }
+                for (int r = 0; r < 4; ++r) packed = __builtin_amdgcn_cvt_pk_u8_f32(x[2 * c + pr][r] * rinv[r], r, packed);
                 const int slot = c * MC_CHUNK + (2 * pr + (g >> 1)) * 16 + j;
                 *reinterpret_cast<unsigned *>(Pl + slot * 8 + 4 * (g & 1)) = packed;
             }
         }
-    }
+    });
 
     // ---- phase V: O = codes * V ------------------------------------------------------------------
     v4i o[4];
@@ -198,7 +263,8 @@ __global__ __launch_bounds__(64, 4) void attention_fused_kernel(AttnArgs a)
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
         const int s = g * 16 + 8 * h + ii;   // slot within the chunk supplied by this lane
-        const int base = (s & 3) * 1024 + (s >> 2) * 64 + ((s & 3) * 16) + 8 * (src & 1);
+        const int i = s % NIT, r = s / NIT;
+        const int base = i * 1024 + r * ROWB + (((4 * w) ^ i) * 16) + 8 * (src & 1);
 #pragma unroll
         for (int ct = 0; ct < 4; ++ct) vaddr[h][ct] = lds_addr(stage) + (base ^ (ct * 16));
         paddr[h] = lds_addr(Pl) + s * 8;
@@ -206,17 +272,17 @@ __global__ __launch_bounds__(64, 4) void attention_fused_kernel(AttnArgs a)
     static_for<MAXCH>([&](auto C) {
         constexpr int c = C;
         if (c < nch) {
-            wait_chunk(C);
+            acquire(Vg, C);
             // codes of this chunk, transposed to the MFMA row operand: row j < 8, slots g*16 .. +15
             v2i p0 = lds_read_tr8<c * 512>(paddr[0]), p1 = lds_read_tr8<c * 512>(paddr[1]);
             v2i d[4][2];
 #pragma unroll
             for (int ct = 0; ct < 4; ++ct) {
-                d[ct][0] = lds_read_tr8<(c & 1) * 4096>(vaddr[0][ct]);
-                d[ct][1] = lds_read_tr8<(c & 1) * 4096>(vaddr[1][ct]);
+                d[ct][0] = lds_read_tr8<(c & 1) * STG>(vaddr[0][ct]);
+                d[ct][1] = lds_read_tr8<(c & 1) * STG>(vaddr[1][ct]);
             }
             lds_wait(p0, p1, d[0][0], d[0][1], d[1][0], d[1][1], d[2][0], d[2][1], d[3][0], d[3][1]);
-            if (c + 2 < nch) issue(Vh, std::integral_constant<int, c + 2>{});
+            release(Vg, C);
             v4i aop = {p0.x, p0.y, p1.x, p1.y};
             if (j >= 8) aop = (v4i){0, 0, 0, 0};
 #pragma unroll
@@ -227,9 +293,9 @@ __global__ __launch_bounds__(64, 4) void attention_fused_kernel(AttnArgs a)
         }
     });
 
-    // ---- output: 8 x 64 tile through LDS, scaled, 16-byte stores ------------------------------
+    // ---- output: 8 x 64 tile through this wave's code area, scaled, 16-byte stores -------------
     vm_wait<0>();
-    int *Ol = reinterpret_cast<int *>(stage);
+    int *Ol = reinterpret_cast<int *>(Pl);
     if (g < 2) {
 #pragma unroll
         for (int ct = 0; ct < 4; ++ct)
@@ -243,7 +309,7 @@ __global__ __launch_bounds__(64, 4) void attention_fused_kernel(AttnArgs a)
         const int piece = h * 64 + lane, row = piece >> 4, col = (piece & 15) * 4;
         const v4i sres = *reinterpret_cast<const v4i *>(&Ol[row * (DK + 4) + col]);
         const v4f f = {sres.x * a.out_scale, sres.y * a.out_scale, sres.z * a.out_scale, sres.w * a.out_scale};
-        *reinterpret_cast<v4f *>(Oh + row * DK + col) = f;
+        *reinterpret_cast<v4f *>(Oh + (int64_t)row * a.token_stride + col) = f;
     }
 }
 
@@ -251,10 +317,15 @@ __global__ __launch_bounds__(64, 4) void attention_fused_kernel(AttnArgs a)
 
 int attention_fused_max_vectors() { return 8 * 64; }
 
-hipError_t launch_attention_fused(const AttnArgs &a, hipStream_t s)
+hipError_t launch_attention_fused(const AttnArgs &a, int heads_per_group, hipStream_t s)
 {
     if (a.P == 0 || a.heads == 0) return hipSuccess;
-    dim3 grid((unsigned)a.P * (unsigned)a.heads), block(64);
-    hipLaunchKernelGGL((attention_fused_kernel<8>), grid, block, 0, s, a);
+    if (heads_per_group == 2) {
+        dim3 grid((unsigned)a.P * (unsigned)(a.heads / 2)), block(128);
+        hipLaunchKernelGGL((attention_fused_kernel<8, 2>), grid, block, 0, s, a);
+    } else {
+        dim3 grid((unsigned)a.P * (unsigned)a.heads), block(64);
+        hipLaunchKernelGGL((attention_fused_kernel<8, 1>), grid, block, 0, s, a);
+    }
     return hipGetLastError();
 }

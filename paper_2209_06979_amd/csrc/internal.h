@@ -68,13 +68,14 @@ struct RepackArgs {
     int P, V, bits, batch;
 };
 
-// Fused attention for head dimension 64: one workgroup per (panel, head).
+// Fused attention for head dimension 64.  Element (head h, token l, d) of Q, Km, Vm (int8)
+// and O (fp32) sits at h*head_stride + l*token_stride + d.
 struct AttnArgs {
     const int32_t *panel_ptr;
     const int32_t *slot_idx;
-    const uint8_t *Q, *Km, *Vm; // heads x L x 64 int8
-    float *O;                   // heads x L x 64 fp32
-    int64_t head_stride;        // elements between heads (L * 64)
+    const uint8_t *Q, *Km, *Vm;
+    float *O;
+    int64_t head_stride, token_stride; // elements
     float score_scale, inv_s_p, out_scale;
     int P, heads;
 };
@@ -85,5 +86,6 @@ hipError_t launch_spmm(mc_prec prec, const SpmmArgs &a, int bnb, int waves, hipS
 hipError_t launch_sddmm(bool int4, const SddmmArgs &a, int waves, hipStream_t s);
 hipError_t launch_softmax(const SoftmaxArgs &a, hipStream_t s);
 hipError_t launch_repack(const RepackArgs &a, hipStream_t s);
-hipError_t launch_attention_fused(const AttnArgs &a, hipStream_t s);
+// heads_per_group 2 needs head_stride == 64 (token-major layout) and an even head count
+hipError_t launch_attention_fused(const AttnArgs &a, int heads_per_group, hipStream_t s);
 int attention_fused_max_vectors(); // longest panel (in vectors) the fused kernel accepts

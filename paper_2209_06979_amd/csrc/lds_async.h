@@ -42,7 +42,17 @@ __device__ __forceinline__ unsigned lds_addr_uniform(const void *p) { return __b
 // wave-uniform value (see lds_addr_uniform).  Untracked: pair with vm_wait<N>().
 __device__ __forceinline__ void copy16_to_lds(const void *gsrc, unsigned lds_base)
 {
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gsrc), "s"(lds_base) : "memory", "m0");
+    const unsigned base = __builtin_amdgcn_readfirstlane(lds_base); // no-op for a value already known to be uniform
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gsrc), "s"(base) : "memory", "m0");
+}
+
+// The same with the address split into a wave-uniform base pointer (SGPR pair) and a 32-bit
+// per-lane byte offset: no 64-bit address arithmetic per lane.
+__device__ __forceinline__ void copy16_to_lds(const void *gbase_uniform, unsigned lane_offset, unsigned lds_base)
+{
+    const unsigned base = __builtin_amdgcn_readfirstlane(lds_base);
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(lane_offset), "s"(gbase_uniform), "s"(base)
+                 : "memory", "m0");
 }
 
 // Untracked 128-bit / 64-bit global loads: the result may be used only after a vm_wait that

@@ -215,9 +215,9 @@ __global__ __launch_bounds__(256) void softmax_kernel(SoftmaxArgs a)
     for (int t = v; t < 256; t += V) sum += red[t];
 
     int8_t *codes = a.codes + base;
+    const float rinv = a.inv_s_p / sum; // p / s_p = e * (1 / (sum * s_p)): one division per row
     for (int e = tid; e < cnt; e += 256) {
-        const float p = __builtin_amdgcn_exp2f((float)S[e] * scale2 - m) / sum;
-        const float q = fminf(fmaxf(rintf(p * a.inv_s_p), 0.f), 127.f);
+        const float q = fminf(fmaxf(rintf(__builtin_amdgcn_exp2f((float)S[e] * scale2 - m) * rinv), 0.f), 127.f);
         codes[e] = (int8_t)(int)q;
     }
 }

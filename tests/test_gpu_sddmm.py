@@ -100,7 +100,14 @@ def test_sparse_softmax_codes():
 
 
 # ---------------------------------------------------------------- attention ----
-def _attention_check(heads, L, dk, sparsity, seed, mode=0):
+def _layout(t, token_major):
+    """(heads, L, dk) device tensor; token_major: a view of a contiguous (L, heads, dk) buffer."""
+    import torch
+    x = torch.from_numpy(np.ascontiguousarray(t)).cuda()
+    return x.permute(1, 0, 2).contiguous().permute(1, 0, 2) if token_major else x
+
+
+def _attention_check(heads, L, dk, sparsity, seed, mode=0, token_major=False):
     import torch
     import oracle
     from paper_2209_06979_amd import binding as mc
@@ -109,12 +116,13 @@ def _attention_check(heads, L, dk, sparsity, seed, mode=0):
     q8, s_q = wl.quantize_inputs_int8(c["q"]); k8, s_k = wl.quantize_inputs_int8(c["k"])
     v8, s_v = wl.quantize_inputs_int8(c["v"])
     s_p = np.float32(1.0 / 127.0)
-    print(f"attention heads={heads} L={L} dk={dk} s={sparsity} mode={mode}", flush=True)
+    print(f"attention heads={heads} L={L} dk={dk} s={sparsity} mode={mode} token_major={token_major}", flush=True)
     mask = mc.SparseMatrix(L, L, V, c["row_ptr"], c["col_idx"])
     mc.set_attention_mode(mode)
     try:
-        out = torch.full((heads, L, dk), float("nan"), dtype=torch.float32, device="cuda")
-        O = mc.sparse_attention(torch_dev(q8), torch_dev(k8), torch_dev(v8), mask, s_q, s_k, s_v, s_p, out=out)
+        out = _layout(np.full((heads, L, dk), np.nan, np.float32), token_major)
+        O = mc.sparse_attention(_layout(q8, token_major), _layout(k8, token_major), _layout(v8, token_major), mask,
+                                s_q, s_k, s_v, s_p, out=out)
         torch.cuda.synchronize()
     finally:
         mc.set_attention_mode(0)
@@ -137,19 +145,22 @@ def _attention_check(heads, L, dk, sparsity, seed, mode=0):
           flush=True)
 
 
+@pytest.mark.parametrize("token_major", [False, True])
 @pytest.mark.parametrize("mode", [0, 1])
-def test_attention_small(mode):
-    _attention_check(2, 256, 64, 0.75, 1200, mode)      # one chunk per panel
-    _attention_check(3, 512, 32, 0.9, 1201, mode)       # dk != 64: always the four-kernel pipeline
-    _attention_check(2, 1024, 64, 0.6, 1202, mode)      # 410 vectors per panel: 7 chunks, ragged tail
-    _attention_check(1, 2048, 64, 0.75, 1203, mode)     # 512 vectors: the longest panel the fused kernel takes
-    _attention_check(1, 2048, 64, 0.7, 1204, mode)      # 614 vectors: falls back to the pipeline
+def test_attention_small(mode, token_major):
+    _attention_check(2, 256, 64, 0.75, 1200, mode, token_major)   # one chunk per panel
+    _attention_check(3, 512, 32, 0.9, 1201, mode, token_major)    # dk != 64: always the four-kernel pipeline
+    _attention_check(2, 1024, 64, 0.6, 1202, mode, token_major)   # 410 vectors per panel: 7 chunks, ragged tail
+    _attention_check(3, 1024, 64, 0.8, 1205, mode, token_major)   # odd head count: one head per workgroup
+    _attention_check(2, 2048, 64, 0.75, 1203, mode, token_major)  # 512 vectors: the longest panel the fused kernel takes
+    _attention_check(1, 2048, 64, 0.7, 1204, mode, token_major)   # 614 vectors: falls back to the pipeline
 
 
+@pytest.mark.parametrize("token_major", [False, True])
 @pytest.mark.parametrize("mode", [0, 1])
-def test_attention_config5_full(mode):
+def test_attention_config5_full(mode, token_major):
     """BASELINE config 5: 8 heads, L=4096, dk=64, 90 % vector sparsity, diagonal kept."""
-    _attention_check(8, 4096, 64, 0.9, wl.seed_for(5), mode)
+    _attention_check(8, 4096, 64, 0.9, wl.seed_for(5), mode, token_major)
 
 
 def test_attention_ragged_rows():
@@ -167,10 +178,11 @@ def test_attention_ragged_rows():
     want, _, probs, _ = oracle.attention(q8, k8, v8, rp, ci, V, s_q, s_k, s_v, s_p)
     amb = _tie_ambiguous(probs, s_p).reshape(heads, -1, V)
     mask = mc.SparseMatrix(L, L, V, rp, ci)
-    for mode in (0, 1):
+    for mode, token_major in ((0, False), (0, True), (1, False), (1, True)):
         mc.set_attention_mode(mode)
-        out = torch.full((heads, L, dk), float("nan"), dtype=torch.float32, device="cuda")
-        O = mc.sparse_attention(torch_dev(q8), torch_dev(k8), torch_dev(v8), mask, s_q, s_k, s_v, s_p, out=out)
+        out = _layout(np.full((heads, L, dk), np.nan, np.float32), token_major)
+        O = mc.sparse_attention(_layout(q8, token_major), _layout(k8, token_major), _layout(v8, token_major), mask,
+                                s_q, s_k, s_v, s_p, out=out)
         torch.cuda.synchronize()
         mc.set_attention_mode(0)
         O = O.cpu().numpy().astype(np.float64)
