@@ -237,23 +237,6 @@ __global__ __launch_bounds__(64 * HPW, (HPW == 1 ? 4 : 3)) void attention_fused_
         srow[r] += __shfl_xor(srow[r], 32, 64);
         rinv[r] = a.inv_s_p / srow[r];
     }
-    // codes of slot (tile*16 + j), rows 4*(g&1) .. +3: one 32-bit LDS write.  v_cvt_pk_u8_f32
-    // rounds to nearest even, saturates to [0, 255] and drops the byte into place; e * rinv
-    // cannot exceed 127 by more than rounding noise.
-    static_for<MAXCH>([&](auto C) {
-        constexpr int c = C;
-        if (c < nch) {
-#pragma unroll
-            for (int pr = 0; pr < 2; ++pr) {
-                unsigned packed = 0;
-#pragma unroll
-                for (int r = 0; r < 4; ++r) packed = __builtin_amdgcn_cvt_pk_u8_f32(x[2 * c + pr][r] * rinv[r], r, packed);
-                const int slot = c * MC_CHUNK + (2 * pr + (g >> 1)) * 16 + j;
-                *reinterpret_cast<unsigned *>(Pl + slot * 8 + 4 * (g & 1)) = packed;
-            }
-        }
-    });
-
     // ---- phase V: O = codes * V ------------------------------------------------------------------
     v4i o[4];
 #pragma unroll
@@ -272,8 +255,20 @@ __global__ __launch_bounds__(64 * HPW, (HPW == 1 ? 4 : 3)) void attention_fused_
     static_for<MAXCH>([&](auto C) {
         constexpr int c = C;
         if (c < nch) {
+            // Codes of this chunk's slots (tile*16 + j), rows 4*(g&1) .. +3: one 32-bit LDS write
+            // per tile.  v_cvt_pk_u8_f32 rounds to nearest even, saturates to [0, 255] and drops
+            // the byte into place; e * rinv cannot exceed 127 by more than rounding noise.
+            // Done here, chunk by chunk, so that this ALU work overlaps the V copies in flight.
+#pragma unroll
+            for (int pr = 0; pr < 2; ++pr) {
+                unsigned packed = 0;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) packed = __builtin_amdgcn_cvt_pk_u8_f32(x[2 * c + pr][r] * rinv[r], r, packed);
+                const int slot = c * MC_CHUNK + (2 * pr + (g >> 1)) * 16 + j;
+                *reinterpret_cast<unsigned *>(Pl + slot * 8 + 4 * (g & 1)) = packed;
+            }
             acquire(Vg, C);
-            // codes of this chunk, transposed to the MFMA row operand: row j < 8, slots g*16 .. +15
+            // the codes, transposed to the MFMA row operand: row j < 8, slots g*16 .. +15
             v2i p0 = lds_read_tr8<c * 512>(paddr[0]), p1 = lds_read_tr8<c * 512>(paddr[1]);
             v2i d[4][2];
 #pragma unroll
