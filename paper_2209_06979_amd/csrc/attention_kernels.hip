@@ -19,8 +19,8 @@
 //   output   the 8 x 64 tile goes through LDS once to be stored as fp32 with 16-byte stores.
 //
 // Two variants (HPW = heads per workgroup):
-//   HPW 1  any layout: the wave gathers the 64-byte rows of its own head; two chunks in
-//          flight, ordered by counted vmcnt waits.
+//   HPW 1  any layout: the wave gathers the 64-byte rows of its own head into its one LDS
+//          stage (8 KB of LDS per wave, so 16 waves fit a CU).
 //   HPW 2  token-major layout (the heads of a token are contiguous, as a QKV projection
 //          writes them): two waves own two neighbouring heads and gather their 128 bytes of
 //          a token with ONE request.  The L2 serves a 128-byte line at the cost of a 64-byte
@@ -78,8 +78,8 @@ __global__ __launch_bounds__(64 * HPW, (HPW == 1 ? 4 : 3)) void attention_fused_
     constexpr int NIT = LPR;         // copy instructions per chunk (4 of them per wave)
     constexpr int SWZ = LPR - 1;
     constexpr int STG = 64 * ROWB;   // bytes of one stage
-    constexpr int GROUP = 5;         // memory instructions per chunk and wave: 4 row copies + 1 index load
-    __shared__ __attribute__((aligned(16))) char stage[2 * STG];           // two chunks of gathered rows
+    constexpr int NST = HPW;         // stages: one for a lone wave, two when two waves share the chunks
+    __shared__ __attribute__((aligned(16))) char stage[NST * STG];         // chunks of gathered rows
     __shared__ __attribute__((aligned(16))) char Pl_all[HPW * MAXCH * 512]; // codes, [slot][8 rows], per wave
 
     const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -115,51 +115,38 @@ __global__ __launch_bounds__(64 * HPW, (HPW == 1 ? 4 : 3)) void attention_fused_
     const unsigned stage_u = lds_addr_uniform(stage);
     const int32_t *myidx = idx + rg * NIT + 4 * w;
     const unsigned tstride = (unsigned)a.token_stride;
-    v4i ixv[2];
-    // HPW 1: group(c) = copies of chunk c, then the indices of chunk c+2 into the registers
-    //        the copies have consumed; two groups in flight.
-    // HPW 2: group(c) = copies of chunk c, then the indices of chunk c+1 into the other
-    //        register set; one group in flight, issued right after the chunk barrier.
-    auto issue = [&](const uint8_t *base, auto CC) {
-        constexpr int c = CC;
+    // issue(c): this wave's copies of chunk c into stage c % NST, from the column indices held
+    // in ixn; then the indices of the following chunk are requested (an ordinary load that has
+    // long arrived by the time they are needed: a vm_wait<0>() lies in between).
+    v4i ixn = {0, 0, 0, 0};
+    auto issue = [&](const uint8_t *base, int c) {
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-            copy16_to_lds(base, __umul24(ixv[c & 1][i], tstride) + segoff[i], stage_u + (c & 1) * STG + (4 * w + i) * 1024);
-        if (HPW == 1) {
-            const int cn = (c + 2 < nch) ? c + 2 : c;
-            ixv[c & 1] = gload128(myidx + cn * MC_CHUNK);
-        } else {
-            const int cn = (c + 1 < nch) ? c + 1 : c;
-            ixv[(c + 1) & 1] = gload128(myidx + cn * MC_CHUNK);
-        }
+            copy16_to_lds(base, __umul24(ixn[i], tstride) + segoff[i], stage_u + (c % NST) * STG + (4 * w + i) * 1024);
+        ixn = *reinterpret_cast<const v4i *>(myidx + ((c + 1 < nch) ? c + 1 : c) * MC_CHUNK);
     };
     auto start_pipeline = [&](const uint8_t *base) {
         if (HPW > 1) __builtin_amdgcn_s_barrier(); // both waves are done with the stages
-        ixv[0] = gload128(myidx);
-        if (HPW == 1) ixv[1] = gload128(myidx + ((nch > 1) ? MC_CHUNK : 0));
-        vm_wait<0>();
-        tie(ixv[0]);
-        if (HPW == 1) tie(ixv[1]);
-        if (nch > 0) issue(base, std::integral_constant<int, 0>{});
-        if (HPW == 1 && nch > 1) issue(base, std::integral_constant<int, 1>{});
-    };
-    // Makes chunk c readable and keeps the pipeline full.
-    auto acquire = [&](const uint8_t *base, auto CC) {
-        constexpr int c = CC;
-        if (HPW == 1) {
-            // landed when only the younger group, if any, is still outstanding
-            if (c + 1 < nch) vm_wait<GROUP>(); else vm_wait<0>();
-            tie(ixv[c & 1]);
-        } else {
-            vm_wait<0>();                 // my half of chunk c and the next indices
-            tie(ixv[(c + 1) & 1]);
-            __builtin_amdgcn_s_barrier(); // the other half too; and everybody is done reading chunk c-1
-            if (c + 1 < nch) issue(base, std::integral_constant<int, c + 1>{});
+        if (nch > 0) {
+            ixn = *reinterpret_cast<const v4i *>(myidx);
+            issue(base, 0);
         }
     };
-    auto release = [&](const uint8_t *base, auto CC) { // after the reads of chunk c have completed
-        constexpr int c = CC;
-        if (HPW == 1 && c + 2 < nch) issue(base, std::integral_constant<int, c + 2>{});
+    // Makes chunk c readable.  HPW 1: the next chunk is issued by release() once this one has
+    // been read.  HPW 2: both halves have landed after the barrier, which also tells that
+    // everybody is done reading chunk c-1, so the next chunk can go into the other stage now.
+    auto acquire = [&](const uint8_t *base, int c) {
+        vm_wait<0>();
+        if (HPW > 1) {
+            __builtin_amdgcn_s_barrier();
+            if (c + 1 < nch) issue(base, c + 1);
+        }
+    };
+    auto release = [&](const uint8_t *base, int c) { // the reads of chunk c have been issued
+        if (HPW == 1 && c + 1 < nch) {
+            lgkm_wait(); // ... and have returned: the one stage may be overwritten
+            issue(base, c + 1);
+        }
     };
 
     // ---- phase K: scores; lane (j, g) owns row 4*(g&1) + r of tile 2*pr + (g >> 1) -----
@@ -167,7 +154,7 @@ __global__ __launch_bounds__(64 * HPW, (HPW == 1 ? 4 : 3)) void attention_fused_
     // are kept out of the row maximum here and out of the row sum below.
     // K operand of tile tl: slot s = tl*16 + j sits in LDS row (s % NIT)*(64/NIT) + s/NIT,
     // i.e. byte (j % NIT)*1024 + (j / NIT)*ROWB + tl*256; segment (4w + g) ^ (j % NIT)
-    const unsigned kaddr = lds_addr(stage) + (j % NIT) * 1024 + (j / NIT) * ROWB + (((4 * w + g) ^ (j % NIT)) * 16);
+    const char *kaddr = stage + (j % NIT) * 1024 + (j / NIT) * ROWB + (((4 * w + g) ^ (j % NIT)) * 16);
     v4i sc[NPR];
     int imax[4] = {INT32_MIN, INT32_MIN, INT32_MIN, INT32_MIN};
     const int tail = n - (nch - 1) * MC_CHUNK; // real vectors in the last chunk
@@ -176,15 +163,14 @@ __global__ __launch_bounds__(64 * HPW, (HPW == 1 ? 4 : 3)) void attention_fused_
     for (int pr = 0; pr < 2; ++pr) keep[pr] = (2 * pr + (g >> 1)) * 16 + j < tail;
     start_pipeline(Kg);
     static_for<MAXCH>([&](auto C) {
-        constexpr int c = C, ST = (c & 1) * STG;
+        constexpr int c = C, ST = (c % NST) * STG;
         sc[2 * c] = (v4i){0, 0, 0, 0};
         sc[2 * c + 1] = (v4i){0, 0, 0, 0};
         if (c < nch) {
-            acquire(Kg, C);
-            v4i kA0 = lds_read128<ST>(kaddr), kB0 = lds_read128<ST + 256>(kaddr);
-            v4i kA1 = lds_read128<ST + 512>(kaddr), kB1 = lds_read128<ST + 768>(kaddr);
-            lds_wait(kA0, kB0, kA1, kB1);
-            release(Kg, C);
+            acquire(Kg, c);
+            const v4i kA0 = *reinterpret_cast<const v4i *>(kaddr + ST), kB0 = *reinterpret_cast<const v4i *>(kaddr + ST + 256);
+            const v4i kA1 = *reinterpret_cast<const v4i *>(kaddr + ST + 512), kB1 = *reinterpret_cast<const v4i *>(kaddr + ST + 768);
+            release(Kg, c);
             sc[2 * c] = __builtin_amdgcn_mfma_i32_16x16x64_i8(q_lo, kA0, sc[2 * c], 0, 0, 0);
             sc[2 * c] = __builtin_amdgcn_mfma_i32_16x16x64_i8(q_hi, kB0, sc[2 * c], 0, 0, 0);
             sc[2 * c + 1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(q_lo, kA1, sc[2 * c + 1], 0, 0, 0);
@@ -242,15 +228,14 @@ __global__ __launch_bounds__(64 * HPW, (HPW == 1 ? 4 : 3)) void attention_fused_
 #pragma unroll
     for (int ct = 0; ct < 4; ++ct) o[ct] = (v4i){0, 0, 0, 0};
     const int src = lane & 15, ii = src >> 1;
-    unsigned vaddr[2][4], paddr[2];
+    int vbase[2];
+    const char *paddr[2];
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
         const int s = g * 16 + 8 * h + ii;   // slot within the chunk supplied by this lane
         const int i = s % NIT, r = s / NIT;
-        const int base = i * 1024 + r * ROWB + (((4 * w) ^ i) * 16) + 8 * (src & 1);
-#pragma unroll
-        for (int ct = 0; ct < 4; ++ct) vaddr[h][ct] = lds_addr(stage) + (base ^ (ct * 16));
-        paddr[h] = lds_addr(Pl) + s * 8;
+        vbase[h] = i * 1024 + r * ROWB + (((4 * w) ^ i) * 16) + 8 * (src & 1);
+        paddr[h] = Pl + s * 8;
     }
     static_for<MAXCH>([&](auto C) {
         constexpr int c = C;
@@ -267,17 +252,16 @@ __global__ __launch_bounds__(64 * HPW, (HPW == 1 ? 4 : 3)) void attention_fused_
                 const int slot = c * MC_CHUNK + (2 * pr + (g >> 1)) * 16 + j;
                 *reinterpret_cast<unsigned *>(Pl + slot * 8 + 4 * (g & 1)) = packed;
             }
-            acquire(Vg, C);
+            acquire(Vg, c);
             // the codes, transposed to the MFMA row operand: row j < 8, slots g*16 .. +15
-            v2i p0 = lds_read_tr8<c * 512>(paddr[0]), p1 = lds_read_tr8<c * 512>(paddr[1]);
+            const v2i p0 = lds_read_tr8(paddr[0] + c * 512), p1 = lds_read_tr8(paddr[1] + c * 512);
             v2i d[4][2];
 #pragma unroll
             for (int ct = 0; ct < 4; ++ct) {
-                d[ct][0] = lds_read_tr8<(c & 1) * STG>(vaddr[0][ct]);
-                d[ct][1] = lds_read_tr8<(c & 1) * STG>(vaddr[1][ct]);
+                d[ct][0] = lds_read_tr8(stage + (c % NST) * STG + (vbase[0] ^ (ct * 16)));
+                d[ct][1] = lds_read_tr8(stage + (c % NST) * STG + (vbase[1] ^ (ct * 16)));
             }
-            lds_wait(p0, p1, d[0][0], d[0][1], d[1][0], d[1][1], d[2][0], d[2][1], d[3][0], d[3][1]);
-            release(Vg, C);
+            release(Vg, c);
             v4i aop = {p0.x, p0.y, p1.x, p1.y};
             if (j >= 8) aop = (v4i){0, 0, 0, 0};
 #pragma unroll
@@ -297,7 +281,7 @@ __global__ __launch_bounds__(64 * HPW, (HPW == 1 ? 4 : 3)) void attention_fused_
 #pragma unroll
             for (int r = 0; r < 4; ++r) Ol[(4 * g + r) * (DK + 4) + ct * 16 + j] = o[ct][r];
     }
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    lgkm_wait();
     __builtin_amdgcn_wave_barrier();
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
