@@ -4,7 +4,7 @@
 A *step* is one pass of every kernel row of the path at the headline shape
 (4096 x 4096, V = 8, 90 % of the vectors zero): SpMM L8-R8 / L8-R4 / L4-R4 / L16-R8
 with N = 256, SDDMM L8-R8 / L4-R4 with K = 256, and the quantized sparse-attention
-layer (8 heads, L = 4096, d_k = 64, token-major Q/K/V: SDDMM -> softmax -> int8 -> SpMM).  Inputs are
+layer (8 heads, L = 4096, d_k = 64, Q/K/V as (heads, L, d_k): SDDMM -> softmax -> int8 -> SpMM).  Inputs are
 seeded synthetic data already resident in HBM; the sparse operands were converted to
 the device format beforehand (the paper builds its format offline as well).
 
@@ -83,7 +83,7 @@ def main():
     ap.add_argument("--reps", type=int, default=200, help="back-to-back launches for the per-kernel timings")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--only", default="", help="comma-separated kernel names: run only these in the step")
-    ap.add_argument("--attention-layout", choices=["token", "head"], default="token",
+    ap.add_argument("--attention-layout", choices=["token", "head"], default="head",
                     help="Q/K/V buffers token-major (L, heads, dk) as a projection writes them, or head-major (heads, L, dk)")
     ap.add_argument("--no-per-kernel", action="store_true", help="skip the per-kernel timing runs (counter collection)")
     ap.add_argument("--calib-copy", action="store_true",
@@ -133,7 +133,7 @@ def main():
             bytes=sddmm_alg_bytes(mask.nvec, M // V, mc.LHS_BITS[prec], KD_SDDMM)))
     att = prob["attention"]
     amask = mc.SparseMatrix(L_ATT, L_ATT, V, att["row_ptr"], att["col_idx"])
-    # token-major layout, as a QKV projection writes it: buffer (L, heads, dk), viewed (heads, L, dk)
+    # --attention-layout token: buffer (L, heads, dk) as a QKV projection writes it, viewed (heads, L, dk)
     def token_major(a):
         if args.attention_layout == "head":
             return up(a)
@@ -223,7 +223,7 @@ def main():
     achieved = dom["bytes"] / (dom["us"] * 1e-6) / 1e9
     roofline = dict(bound="hbm", kernel=dom["name"], achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s",
                     frac=round(achieved / HBM_PEAK_GBS, 4),
-                    traffic=(MEASURED_TRAFFIC_BYTES.get(dom["name"]) if args.attention_layout == "token" else None),
+                    traffic=(MEASURED_TRAFFIC_BYTES.get(dom["name"]) if args.attention_layout == "head" else None),
                     us_per_launch=round(dom["us"], 2), algorithmic_bytes=int(dom["bytes"]))
     per_kernel = {k["name"]: dict(us=round(k["us"], 2), eff_tops=round(k["ops"] / k["us"] / 1e6, 1),
                                   alg_gbs=round(k["bytes"] / k["us"] / 1e3, 1),

@@ -201,8 +201,9 @@ int mc_set_spmm_variant(int bytes_per_row_tile, int waves);
 int mc_set_sddmm_variant(int waves);
 /* Attention path: 0 = automatic (a single fused kernel when dk == 64 and no panel holds
  * more than 512 vectors, else the four-kernel pipeline), 1 = always the four-kernel
- * pipeline SDDMM -> softmax -> repack -> SpMM.  Both give the same result up to fp32
- * summation order in the softmax.  Process-wide; MC_EINVAL for other values. */
+ * pipeline SDDMM -> softmax -> repack -> SpMM, 2 = the fused kernel with one head per
+ * workgroup even for token-major tensors.  All give the same result up to fp32 summation
+ * order in the softmax.  Process-wide; MC_EINVAL for other values. */
 int mc_set_attention_mode(int mode);
 
 #ifdef __cplusplus

@@ -115,7 +115,7 @@ extern "C" int mc_set_sddmm_variant(int waves)
 
 extern "C" int mc_set_attention_mode(int mode)
 {
-    if (mode != 0 && mode != 1) return MC_EINVAL;
+    if (mode < 0 || mode > 2) return MC_EINVAL;
     g_attention_mode = mode;
     return MC_OK;
 }
@@ -323,7 +323,7 @@ extern "C" int mc_sparse_attention_strided(const int8_t *Q_dev, const int8_t *Km
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int64_t nnz = mask->nvec * mask->V;
 
-    if (g_attention_mode == 0 && dk == 64 && mask->max_panel_chunks * MC_CHUNK <= attention_fused_max_vectors()) {
+    if (g_attention_mode != 1 && dk == 64 && mask->max_panel_chunks * MC_CHUNK <= attention_fused_max_vectors()) {
         AttnArgs f;
         f.panel_ptr = mask->d_panel_ptr; f.slot_idx = mask->d_slot_idx;
         f.Q = reinterpret_cast<const uint8_t *>(Q_dev); f.Km = reinterpret_cast<const uint8_t *>(Km_dev);
@@ -332,7 +332,7 @@ extern "C" int mc_sparse_attention_strided(const int8_t *Q_dev, const int8_t *Km
         f.score_scale = s_q * s_k / std::sqrt((float)dk); f.inv_s_p = 1.f / s_p; f.out_scale = s_p * s_v;
         f.P = mask->P; f.heads = heads;
         // neighbouring heads contiguous inside a token: two heads per workgroup, 128-byte gathers
-        const int hpg = (head_stride == 64 && heads % 2 == 0) ? 2 : 1;
+        const int hpg = (g_attention_mode == 0 && head_stride == 64 && heads % 2 == 0) ? 2 : 1;
         MC_HIP(launch_attention_fused(f, hpg, s));
         return MC_OK;
     }

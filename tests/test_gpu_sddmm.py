@@ -192,3 +192,9 @@ def test_attention_ragged_rows():
         assert (np.abs(O - want) <= tol[:, :, None]).all(), mode
         assert not O[:, :8].any() and not O[:, 15 * 8:16 * 8].any()
     mask.close()
+
+
+@pytest.mark.parametrize("prec,Kd,s,V", [("L8R8", 128, 0.9, 8), ("L8R8", 64, 0.7, 4), ("L4R4", 256, 0.7, 8),
+                                          ("L8R8", 256, 0.95, 2), ("L4R4", 64, 0.95, 4)])
+def test_config3_more_points_full_size(prec, Kd, s, V):
+    _check(wl.sddmm_case(4096, 4096, Kd, V, s, prec, wl.seed_for(3, 500 + Kd + int(100 * s) + V)))

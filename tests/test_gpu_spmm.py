@@ -128,3 +128,23 @@ def test_set_values_device_round_trip():
         torch.cuda.synchronize()
         assert np.array_equal(C.cpu().numpy(), run_spmm_oracle(c)), prec
         A.close()
+
+
+SWEEP = [(prec, V, s, N)
+         for prec in PRECS for V, s, N in [(8, 0.5, 128), (8, 0.7, 512), (8, 0.95, 256), (4, 0.8, 256), (2, 0.9, 512),
+                                           (4, 0.5, 128), (2, 0.98, 128)]]
+
+
+@pytest.mark.parametrize("prec,V,s,N", SWEEP)
+def test_config2_sweep_points_full_size(prec, V, s, N):
+    """A spread of BASELINE config 2 grid points (4096 x 4096; V, sparsity, N, precision), whole output compared,
+    in the launch configuration the library picks by itself (the one bench.py times)."""
+    _check(wl.spmm_case(4096, 4096, N, V, s, prec, wl.seed_for(2, 1000 + int(s * 100) + 10 * V + N)))
+
+
+def test_ablation_shape_and_tall_matrix():
+    """The shape of the paper's ablation matrix (Section 5.1: M=256, K=2304, N=512) and a tall, very sparse one."""
+    for prec in PRECS:
+        _check(wl.spmm_case(256, 2304, 512, 8, 0.7, prec, 77))
+    _check(wl.spmm_case(32768, 8192, 64, 8, 0.99, "L8R8", 78))
+    _check(wl.spmm_case(16384, 1024, 1024, 4, 0.9, "L8R4", 79))
