@@ -154,15 +154,19 @@ def stored_flags(M: int, K: int, V: int, row_ptr, col_idx) -> np.ndarray:
 def vector_values_as_int(values, nvec: int, V: int, bits: int) -> np.ndarray:
     """(nvec, V) int32 from vector-major stored values of the given width.
 
-    bits=8: int8; bits=16: int16; bits=4: two elements per byte along the V axis.
+    bits=8: int8; bits=16: int16; bits=12: int16 container restricted to 12-bit values;
+    bits=4: two elements per byte along the V axis.
     """
     if bits == 8:
         return np.asarray(values).view(np.int8).reshape(nvec, V).astype(np.int32)
-    if bits == 16:
-        return np.asarray(values).view(np.int16).reshape(nvec, V).astype(np.int32)
+    if bits == 16 or bits == 12:
+        vv = np.asarray(values).view(np.int16).reshape(nvec, V).astype(np.int32)
+        if bits == 12 and vv.size and (vv.min() < -2048 or vv.max() > 2047):
+            raise ValueError("12-bit operand outside [-2048, 2047]")
+        return vv
     if bits == 4:
         return unpack_int4(np.asarray(values).view(np.uint8).reshape(nvec, V // 2))
-    raise ValueError("bits must be 4, 8 or 16")
+    raise ValueError("bits must be 4, 8, 12 or 16")
 
 
 def bcrs_to_dense(M: int, K: int, V: int, row_ptr, col_idx, vec_vals) -> tuple[np.ndarray, np.ndarray]:
@@ -180,17 +184,22 @@ def bcrs_to_dense(M: int, K: int, V: int, row_ptr, col_idx, vec_vals) -> tuple[n
     return A, stored_flags(M, K, V, row_ptr, col_idx)
 
 
-_LHS_BITS = {"L8R8": 8, "L8R4": 8, "L4R4": 4, "L16R8": 16}
-_RHS_BITS = {"L8R8": 8, "L8R4": 4, "L4R4": 4, "L16R8": 8}
+# Table of supported precisions (Section 4.4).  A 12-bit operand travels in an int16
+# container and must lie in [-2048, 2047].
+_LHS_BITS = {"L8R8": 8, "L8R4": 8, "L4R4": 4, "L16R8": 16, "L16R16": 16, "L16R4": 16, "L12R4": 12}
+_RHS_BITS = {"L8R8": 8, "L8R4": 4, "L4R4": 4, "L16R8": 8, "L16R16": 16, "L16R4": 4, "L12R4": 4}
 
 
 def dense_rhs_as_int(B, bits: int) -> np.ndarray:
-    """Row-major dense operand as int32; bits=4 means two elements per byte along a row."""
+    """Row-major dense operand as int32; bits=4 means two elements per byte along a row,
+    bits=16 little-endian int16 elements."""
     if bits == 8:
         return np.asarray(B).view(np.int8).astype(np.int32)
+    if bits == 16:
+        return np.asarray(B).view(np.int16).astype(np.int32)
     if bits == 4:
         return unpack_int4(np.asarray(B).view(np.uint8))
-    raise ValueError("bits must be 4 or 8")
+    raise ValueError("bits must be 4, 8 or 16")
 
 
 def spmm(M, K, V, row_ptr, col_idx, values, B, prec: str) -> np.ndarray:
@@ -208,8 +217,8 @@ def spmm(M, K, V, row_ptr, col_idx, values, B, prec: str) -> np.ndarray:
 def sddmm(M, Nc, V, row_ptr, col_idx, Q, Kmat, prec: str) -> np.ndarray:
     """SDDMM from interchange data; Q and Kmat are row-major (packed along Kd for int4)."""
     bits = _LHS_BITS[prec]
-    if bits not in (4, 8) or _RHS_BITS[prec] != bits:
-        raise ValueError("SDDMM is defined here for L8R8 and L4R4")
+    if bits not in (4, 8, 16) or _RHS_BITS[prec] != bits:
+        raise ValueError("SDDMM is defined here for L8R8, L4R4 and L16R16")
     flags = stored_flags(M, Nc, V, row_ptr, col_idx)
     return sddmm_dense(dense_rhs_as_int(Q, bits), dense_rhs_as_int(Kmat, bits), flags, V)
 

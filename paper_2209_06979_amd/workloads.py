@@ -90,19 +90,22 @@ def normal_fp32(shape, seed: int) -> np.ndarray:
 def spmm_case(M, K, N, V, sparsity, prec: str, seed: int):
     """One SpMM problem: pattern, vector-major LHS values and the dense RHS.
 
-    prec: "L8R8" | "L8R4" | "L4R4" | "L16R8".  int4 operands are packed two per byte
-    (LHS along the V axis of a vector, RHS along a row).
+    prec: "L8R8" | "L8R4" | "L4R4" | "L16R8" | "L16R16" | "L16R4" | "L12R4".  int4 operands
+    are packed two per byte (LHS along the V axis of a vector, RHS along a row); 16-bit and
+    12-bit operands are int16 arrays drawn from [-2048, 2047] so that exact sums fit int32.
     """
     row_ptr, col_idx = vector_sparse_pattern(M, K, V, sparsity, seed)
     nvec = len(col_idx)
     if prec == "L4R4":
         vals = uniform_packed_int4((nvec, V // 2), seed + 1)
-    elif prec == "L16R8":
+    elif prec in ("L16R8", "L16R16", "L16R4", "L12R4"):
         vals = uniform_int16((nvec, V), seed + 1)
     else:
         vals = uniform_int8((nvec, V), seed + 1)
-    if prec in ("L8R4", "L4R4"):
+    if prec in ("L8R4", "L4R4", "L16R4", "L12R4"):
         B = uniform_packed_int4((K, N // 2), seed + 2)
+    elif prec == "L16R16":
+        B = uniform_int16((K, N), seed + 2)
     else:
         B = uniform_int8((K, N), seed + 2)
     return dict(M=M, K=K, N=N, V=V, prec=prec, row_ptr=row_ptr, col_idx=col_idx, values=vals, B=B)
@@ -114,6 +117,9 @@ def sddmm_case(M, Nc, Kd, V, sparsity, prec: str, seed: int):
     if prec == "L4R4":
         Q = uniform_packed_int4((M, Kd // 2), seed + 1)
         Kmat = uniform_packed_int4((Nc, Kd // 2), seed + 2)
+    elif prec == "L16R16":
+        Q = uniform_int16((M, Kd), seed + 1)
+        Kmat = uniform_int16((Nc, Kd), seed + 2)
     else:
         Q = uniform_int8((M, Kd), seed + 1)
         Kmat = uniform_int8((Nc, Kd), seed + 2)

@@ -258,6 +258,67 @@ def test_l16r8_from_interchange_data():
     assert np.array_equal(oracle.spmm(M, K, V, c["row_ptr"], c["col_idx"], c["values"], c["B"], "L16R8"), want)
 
 
+@pytest.mark.parametrize("prec", ["L16R16", "L16R4", "L12R4"])
+def test_wide_spmm_precisions_from_interchange_data(prec):
+    """Python-integer loops over the stored vectors only, operands widened by hand."""
+    V, M, K, N = 4, 8, 12, 32
+    c = wl.spmm_case(M, K, N, V, 0.5, prec, 43)
+    vals = c["values"].astype(np.int64)                       # (nvec, V) int16 container
+    if prec == "L16R16":
+        Bw = [[int(x) for x in row] for row in c["B"]]
+    else:                                                     # nibbles: low first, two's complement
+        Bw = [[(((b >> sh) & 15) ^ 8) - 8 for b in row.tolist() for sh in (0, 4)] for row in c["B"]]
+    want = [[0] * N for _ in range(M)]
+    for p in range(M // V):
+        for i in range(c["row_ptr"][p], c["row_ptr"][p + 1]):
+            k = int(c["col_idx"][i])
+            for v in range(V):
+                for n in range(N):
+                    want[p * V + v][n] += int(vals[i, v]) * Bw[k][n]
+    got = oracle.spmm(M, K, V, c["row_ptr"], c["col_idx"], c["values"], c["B"], prec)
+    assert got.tolist() == want
+
+
+def test_l12_rejects_wider_values():
+    V, M, K, N = 4, 8, 12, 32
+    c = wl.spmm_case(M, K, N, V, 0.5, "L12R4", 44)
+    bad = c["values"].copy()
+    bad[0, 0] = 2048
+    with pytest.raises(ValueError):
+        oracle.spmm(M, K, V, c["row_ptr"], c["col_idx"], bad, c["B"], "L12R4")
+
+
+def test_l16r16_is_the_four_plane_sum():
+    """Section 4.4 with both operands split: A = Ah*256 + Al, B = Bh*256 + Bl (high parts signed,
+    low parts unsigned) gives C = (Ch_h << 16) + ((Ch_l + Cl_h) << 8) + Cl_l, planes multiplied by
+    the library matmul."""
+    V, M, K, N = 8, 16, 40, 16
+    c = wl.spmm_case(M, K, N, V, 0.5, "L16R16", 45)
+    vals = c["values"].copy()
+    vals.reshape(-1)[:4] = [-2048, 2047, -1, 255]
+    A, flags = oracle.bcrs_to_dense(M, K, V, c["row_ptr"], c["col_idx"], vals)
+    al, ah = oracle.split_signed(A, 8)
+    bl, bh = oracle.split_signed(c["B"], 8)
+    want = ((ah @ bh) << 16) + (((ah @ bl) + (al @ bh)) << 8) + (al @ bl)
+    assert np.array_equal(oracle.spmm(M, K, V, c["row_ptr"], c["col_idx"], vals, c["B"], "L16R16"), want)
+
+
+def test_sddmm_l16r16_against_library_matmul_and_loops():
+    V, M, Nc, Kd = 4, 8, 12, 16
+    c = wl.sddmm_case(M, Nc, Kd, V, 0.5, "L16R16", 46)
+    got = oracle.sddmm(M, Nc, V, c["row_ptr"], c["col_idx"], c["Q"], c["Kmat"], "L16R16")
+    full = torch.from_numpy(c["Q"].astype(np.int64)) @ torch.from_numpy(c["Kmat"].astype(np.int64)).T
+    want = []
+    for p in range(M // V):
+        for i in range(c["row_ptr"][p], c["row_ptr"][p + 1]):
+            for v in range(V):
+                want.append(int(full[p * V + v, int(c["col_idx"][i])]))
+    assert got.tolist() == want
+    q, k = c["Q"].tolist(), c["Kmat"].tolist()
+    i = int(c["row_ptr"][1])                                   # first vector of panel 1, row v = 2
+    assert got[i * V + 2] == sum(a * b for a, b in zip(q[V + 2], k[int(c["col_idx"][i])]))
+
+
 # ------------------------------------------------------------ attention ----
 def test_softmax_rows_sum_to_one_and_uniform_case():
     V = 8
