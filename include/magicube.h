@@ -15,7 +15,8 @@
  *   row_ptr    P + 1 int32; panel p owns vectors row_ptr[p] .. row_ptr[p+1]-1
  *   col_idx    one int32 column per stored vector, strictly ascending inside a panel
  *   values     the V elements of each vector consecutively (vector-major):
- *              8-bit: int8; 16-bit: little-endian int16; 4-bit: two's-complement
+ *              8-bit: int8; 16-bit: little-endian int16; 12-bit: int16 restricted to
+ *              [-2048, 2047]; 4-bit: two's-complement
  *              nibbles, element 2j in bits 3:0 and element 2j+1 in bits 7:4 of byte j
  * The library converts it into its own device format (a strided row-major layout in
  * the spirit of SR-BCRS, Section 4.1): vectors of a panel are grouped in chunks of 64
@@ -54,7 +55,10 @@ typedef enum {
 } mc_status;
 
 /* Lx-Ry: bits of the left (sparse for SpMM) and right operands. */
-typedef enum { MC_L8R8 = 0, MC_L8R4 = 1, MC_L4R4 = 2, MC_L16R8 = 3 } mc_prec;
+typedef enum {
+    MC_L8R8 = 0, MC_L8R4 = 1, MC_L4R4 = 2, MC_L16R8 = 3,
+    MC_L16R16 = 4, MC_L16R4 = 5, MC_L12R4 = 6
+} mc_prec;
 
 /* Vectors per chunk of the device format (= reduction depth of v_mfma_i32_16x16x64_i8). */
 #define MC_CHUNK 64
@@ -78,7 +82,7 @@ typedef struct {
     int64_t vals_bytes;  /* bytes of the packed value array (0 for lhs_bits == 0)    */
 } mc_layout;
 
-/* Checks M, K, V, lhs_bits (0 = pattern only, 4, 8, 16) and row_ptr (host, P+1,
+/* Checks M, K, V, lhs_bits (0 = pattern only, 4, 8, 12, 16) and row_ptr (host, P+1,
  * non-decreasing from 0) and fills *out.  MC_EINVAL on any violation. */
 int mc_layout_query(int M, int K, int V, int lhs_bits, const int32_t *row_ptr, mc_layout *out);
 
@@ -96,7 +100,8 @@ int mc_layout_query(int M, int K, int V, int lhs_bits, const int32_t *row_ptr, m
  *                                    4-bit  [row v][8 bytes], byte b = slot b (low
  *                                           nibble) and slot b + 8 (high nibble)
  * Validates col_idx (ascending per panel, 0 <= c < K): MC_EINVAL; 16-bit values above
- * 32639 cannot be split into two signed bytes: MC_ERANGE. */
+ * 32639 cannot be split into two signed bytes: MC_ERANGE; lhs_bits == 12 is stored like
+ * 16 and additionally requires every value in [-2048, 2047]: MC_ERANGE. */
 int mc_pack_host(int M, int K, int V, int lhs_bits, const int32_t *row_ptr, const int32_t *col_idx,
                  const void *values, int32_t *panel_ptr, int32_t *slot_idx, void *slot_vals);
 
@@ -124,14 +129,16 @@ int mc_mat_info(const mc_mat *A, int *M, int *K, int *V, int *lhs_bits, int64_t 
 
 /* ------------------------------------------------------------------------------------
  * SpMM (Section 4.2): C = A * B, exact int32.
- *   A      sparse M x K, width must match prec (L8: 8, L4: 4, L16: 16 bits)
- *   B_dev  dense K x N row-major, int8 (R8) or packed int4 (R4); ldb in elements
+ *   A      sparse M x K, width must match prec (L8: 8, L4: 4, L12: 12, L16: 16 bits)
+ *   B_dev  dense K x N row-major, int8 (R8), packed int4 (R4) or little-endian int16 (R16);
+ *          ldb in elements
  *   C_dev  dense M x N row-major int32; ldc in elements
- * Requirements: B_dev, C_dev 16-byte aligned; N a multiple of 16 (R8) or 32 (R4);
+ * Requirements: B_dev, C_dev 16-byte aligned; N a multiple of 16 (R8), 32 (R4) or 8 (R16);
  * ldb*bits/8 a multiple of 16 and >= the row bytes; ldc a multiple of 4 and >= N.
- * R4 paths keep 16x (L8-R4) or 256x (L4-R4) scaled sums in int32, so they require
- * K <= 131072.  L16-R8 is computed as two signed int8 planes in one MFMA and
- * recombined as (C_hi << 8) + C_lo (Section 4.4).
+ * R4 paths keep 16x (L8-R4, L16-R4, L12-R4) or 256x (L4-R4) scaled plane sums in int32, so
+ * they require K <= 131072.  A 16-bit (12-bit) A is computed as two signed int8 planes in one
+ * MFMA and recombined as (C_hi << 8) + C_lo; a 16-bit B is read as its high (signed) and low
+ * (unsigned) bytes, any int16 value, and recombined the same way (Section 4.4).
  * Results that do not fit int32 wrap (two's complement).
  * ---------------------------------------------------------------------------------- */
 int mc_spmm(const mc_mat *A, const void *B_dev, int N, int ldb, mc_prec prec, int32_t *C_dev, int ldc,
@@ -141,7 +148,9 @@ int mc_spmm(const mc_mat *A, const void *B_dev, int N, int ldb, mc_prec prec, in
  * SDDMM (Section 4.3): for every stored vector i of the mask (panel p, column c):
  *   S[i*V + v] = sum_k Q[p*V + v][k] * Kmat[c][k],  v = 0..V-1
  *   Q_dev     M x Kd row-major, Kmat_dev  Nc x Kd row-major (the paper's column-major
- *             right operand), int8 (MC_L8R8) or packed int4 (MC_L4R4); ldq/ldk in elements
+ *             right operand), int8 (MC_L8R8), packed int4 (MC_L4R4) or int16 (MC_L16R16,
+ *             every value <= 32639: both operands are split into signed byte planes);
+ *             ldq/ldk in elements
  *   mask      pattern of an M x Nc matrix (values ignored)
  *   S_dev     nvec*V int32 in interchange (vector-major) order
  * Requirements: 16-byte aligned pointers; Kd*bits/8 a multiple of 16; ld*bits/8 a

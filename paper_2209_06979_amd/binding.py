@@ -17,9 +17,14 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libmagicube.so")
 
 MC_OK, MC_EINVAL, MC_EUNSUPPORTED, MC_EALIGN, MC_EHIP, MC_ENOMEM, MC_ERANGE = 0, -1, -2, -3, -4, -5, -6
-PREC = {"L8R8": 0, "L8R4": 1, "L4R4": 2, "L16R8": 3}
-LHS_BITS = {"L8R8": 8, "L8R4": 8, "L4R4": 4, "L16R8": 16}
-RHS_BITS = {"L8R8": 8, "L8R4": 4, "L4R4": 4, "L16R8": 8}
+PREC = {"L8R8": 0, "L8R4": 1, "L4R4": 2, "L16R8": 3, "L16R16": 4, "L16R4": 5, "L12R4": 6}
+LHS_BITS = {"L8R8": 8, "L8R4": 8, "L4R4": 4, "L16R8": 16, "L16R16": 16, "L16R4": 16, "L12R4": 12}
+RHS_BITS = {"L8R8": 8, "L8R4": 4, "L4R4": 4, "L16R8": 8, "L16R16": 16, "L16R4": 4, "L12R4": 4}
+
+
+def _container_bits(bits: int) -> int:
+    """Bits an element occupies in memory (a 12-bit value travels as int16)."""
+    return 16 if bits == 12 else bits
 CHUNK = 64
 
 
@@ -123,11 +128,11 @@ def unpack_host(M, K, V, lhs_bits, panel_ptr, slot_idx, slot_vals):
     nvec = int(sum(int(pp[2 * p + 1]) - int(pp[2 * p]) for p in range(P)))
     row_ptr = np.zeros(P + 1, np.int32)
     col_idx = np.zeros(max(nvec, 1), np.int32)
-    values = np.zeros(max(nvec * V * max(lhs_bits, 8) // 8, 1), np.uint8)
+    values = np.zeros(max(nvec * V * max(_container_bits(lhs_bits), 8) // 8, 1), np.uint8)
     sv = np.ascontiguousarray(slot_vals, dtype=np.uint8)
     _check(lib.mc_unpack_host(M, K, V, lhs_bits, _p32(pp), _p32(si), sv.ctypes.data if lhs_bits else None,
                               _p32(row_ptr), _p32(col_idx), values.ctypes.data), "mc_unpack_host")
-    return row_ptr, col_idx[:nvec], values[:nvec * V * lhs_bits // 8]
+    return row_ptr, col_idx[:nvec], values[:nvec * V * _container_bits(lhs_bits) // 8]
 
 
 # ---------------------------------------------------------------- device objects ----
@@ -141,7 +146,7 @@ class SparseMatrix:
         if rp.shape[0] and ci.shape[0] != int(rp[-1]):
             raise MagicubeError(MC_EINVAL, "SparseMatrix(col_idx length)")
         vals = None if values is None else np.ascontiguousarray(values)
-        if vals is not None and vals.nbytes != ci.shape[0] * V * lhs_bits // 8:
+        if vals is not None and vals.nbytes != ci.shape[0] * V * _container_bits(lhs_bits) // 8:
             raise MagicubeError(MC_EINVAL, "SparseMatrix(values size)")
         h = c_void_p()
         _check(lib.mc_mat_create(M, K, V, lhs_bits if vals is not None else 0, _p32(rp), _p32(ci),
@@ -156,7 +161,7 @@ class SparseMatrix:
     def set_values(self, values_dev) -> None:
         """values_dev: device tensor, nvec*V elements in interchange (vector-major) order."""
         assert values_dev.is_cuda and values_dev.is_contiguous()
-        assert values_dev.numel() * values_dev.element_size() == self.nvec * self.V * self.lhs_bits // 8
+        assert values_dev.numel() * values_dev.element_size() == self.nvec * self.V * _container_bits(self.lhs_bits) // 8
         _check(lib.mc_mat_set_values_device(self.handle, values_dev.data_ptr(), _stream()), "mc_mat_set_values_device")
 
     def close(self) -> None:
@@ -184,11 +189,11 @@ def set_attention_mode(mode: int = 0) -> None:
 
 
 def spmm(A: SparseMatrix, B, prec: str, out=None):
-    """C = A * B (int32, M x N).  B: device tensor (K, N) int8, or (K, N/2) uint8 for R4."""
+    """C = A * B (int32, M x N).  B: device tensor (K, N) int8, (K, N/2) uint8 for R4, (K, N) int16 for R16."""
     assert B.is_cuda and B.dim() == 2 and B.stride(1) == 1
     rbits = RHS_BITS[prec]
-    N = B.shape[1] * 8 // rbits
-    ldb = B.stride(0) * 8 // rbits
+    N = B.shape[1] * B.element_size() * 8 // rbits
+    ldb = B.stride(0) * B.element_size() * 8 // rbits
     if out is None:
         out = torch.empty((A.M, N), dtype=torch.int32, device=B.device)
     assert out.is_cuda and out.dtype == torch.int32 and out.shape == (A.M, N) and out.stride(1) == 1
@@ -201,11 +206,13 @@ def sddmm(Q, Kmat, mask: SparseMatrix, prec: str, out=None):
     assert Q.is_cuda and Kmat.is_cuda and Q.dim() == 2 and Kmat.dim() == 2
     assert Q.stride(1) == 1 and Kmat.stride(1) == 1 and Q.shape[1] == Kmat.shape[1]
     bits = LHS_BITS[prec]
-    Kd = Q.shape[1] * 8 // bits
+    Kd = Q.shape[1] * Q.element_size() * 8 // bits
+    assert Q.element_size() == Kmat.element_size()
     if out is None:
         out = torch.empty(mask.nvec * mask.V, dtype=torch.int32, device=Q.device)
     assert out.is_cuda and out.dtype == torch.int32 and out.numel() == mask.nvec * mask.V and out.is_contiguous()
-    _check(lib.mc_sddmm(Q.data_ptr(), Q.stride(0) * 8 // bits, Kmat.data_ptr(), Kmat.stride(0) * 8 // bits, Kd,
+    _check(lib.mc_sddmm(Q.data_ptr(), Q.stride(0) * Q.element_size() * 8 // bits, Kmat.data_ptr(),
+                        Kmat.stride(0) * Kmat.element_size() * 8 // bits, Kd,
                         mask.handle, PREC[prec], out.data_ptr(), _stream()), "mc_sddmm")
     return out
 

@@ -15,9 +15,24 @@ int g_sddmm_waves = -1;   // -1 automatic, 0 direct-load kernel, 1/2/4/8 waves o
 int g_attention_mode = 0; // 0 automatic, 1 always the unfused four-kernel pipeline
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
-inline int lhs_bits_of(mc_prec p) { return p == MC_L4R4 ? 4 : (p == MC_L16R8 ? 16 : 8); }
-inline int rhs_bits_of(mc_prec p) { return (p == MC_L8R4 || p == MC_L4R4) ? 4 : 8; }
-inline bool valid_prec(int p) { return p >= MC_L8R8 && p <= MC_L16R8; }
+inline int lhs_bits_of(mc_prec p)
+{
+    switch (p) {
+    case MC_L4R4: return 4;
+    case MC_L16R8: case MC_L16R16: case MC_L16R4: return 16;
+    case MC_L12R4: return 12;
+    default: return 8;
+    }
+}
+inline int rhs_bits_of(mc_prec p)
+{
+    switch (p) {
+    case MC_L8R4: case MC_L4R4: case MC_L16R4: case MC_L12R4: return 4;
+    case MC_L16R16: return 16;
+    default: return 8;
+    }
+}
+inline bool valid_prec(int p) { return p >= MC_L8R8 && p <= MC_L12R4; }
 
 thread_local char g_detail[256] = "";
 
@@ -207,7 +222,7 @@ extern "C" int mc_mat_set_values_device(mc_mat *A, const void *values_dev, void 
     r.panel_ptr = A->d_panel_ptr; r.row_ptr = A->d_row_ptr;
     r.src = static_cast<const uint8_t *>(values_dev); r.src_batch_stride = 0;
     r.dst = A->d_vals; r.dst_batch_stride = 0;
-    r.P = A->P; r.V = A->V; r.bits = A->lhs_bits; r.batch = 1;
+    r.P = A->P; r.V = A->V; r.bits = (A->lhs_bits == 12) ? 16 : A->lhs_bits; r.batch = 1;
     MC_HIP(launch_repack(r, static_cast<hipStream_t>(stream)));
     return MC_OK;
 }
@@ -243,7 +258,7 @@ extern "C" int mc_sddmm(const void *Q_dev, int ldq, const void *Kmat_dev, int ld
 {
     if (!Q_dev || !Kmat_dev || !mask || !S_dev) return MC_EINVAL;
     if (!valid_prec((int)prec)) return MC_EUNSUPPORTED;
-    if (prec != MC_L8R8 && prec != MC_L4R4) return MC_EUNSUPPORTED;
+    if (prec != MC_L8R8 && prec != MC_L4R4 && prec != MC_L16R16) return MC_EUNSUPPORTED;
     const int bits = lhs_bits_of(prec);
     if (Kd <= 0 || Kd % (128 / bits) != 0 || ldq < Kd || ldk < Kd) return MC_EINVAL;
     if (((int64_t)ldq * bits / 8) % 16 != 0 || ((int64_t)ldk * bits / 8) % 16 != 0) return MC_EALIGN;
@@ -256,7 +271,7 @@ extern "C" int mc_sddmm(const void *Q_dev, int ldq, const void *Kmat_dev, int ld
     a.row_bytes = Kd * bits / 8;
     a.S = S_dev; a.S_batch_stride = 0;
     a.P = mask->P; a.V = mask->V; a.batch = 1;
-    MC_HIP(launch_sddmm(bits == 4, a, choose_sddmm_waves(mask, 1), static_cast<hipStream_t>(stream)));
+    MC_HIP(launch_sddmm(bits, a, choose_sddmm_waves(mask, 1), static_cast<hipStream_t>(stream)));
     return MC_OK;
 }
 
@@ -348,7 +363,7 @@ extern "C" int mc_sparse_attention_strided(const int8_t *Q_dev, const int8_t *Km
     d.Kmat = reinterpret_cast<const uint8_t *>(Km_dev); d.ldk_bytes = token_stride; d.K_batch_stride = head_stride;
     d.row_bytes = dk; d.S = scores; d.S_batch_stride = nnz;
     d.P = mask->P; d.V = 8; d.batch = heads;
-    MC_HIP(launch_sddmm(false, d, choose_sddmm_waves(mask, heads), s));
+    MC_HIP(launch_sddmm(8, d, choose_sddmm_waves(mask, heads), s));
 
     SoftmaxArgs f;
     f.row_ptr = mask->d_row_ptr; f.S = scores; f.codes = codes; f.batch_stride = nnz;

@@ -16,7 +16,10 @@ namespace {
 inline int64_t pad_to_chunk(int64_t n) { return (n + MC_CHUNK - 1) / MC_CHUNK * MC_CHUNK; }
 
 // bytes of one chunk of packed values
-inline int64_t chunk_value_bytes(int V, int bits) { return (int64_t)MC_CHUNK * V * bits / 8; }
+// (a 12-bit operand is an int16 array restricted to [-2048, 2047] and is stored like a 16-bit one)
+inline int storage_bits(int bits) { return bits == 12 ? 16 : bits; }
+inline int64_t chunk_value_bytes(int V, int bits) { return (int64_t)MC_CHUNK * V * storage_bits(bits) / 8; }
+inline bool valid_lhs_bits(int b) { return b == 0 || b == 4 || b == 8 || b == 12 || b == 16; }
 
 // signed int8 planes of a 16-bit value: a = 256 * hi + lo, lo in [-128, 127]
 inline bool split_balanced(int a, int8_t *hi, int8_t *lo)
@@ -43,7 +46,7 @@ extern "C" int mc_layout_query(int M, int K, int V, int lhs_bits, const int32_t 
     if (M <= 0 || K <= 0) return MC_EINVAL;
     if (V != 2 && V != 4 && V != 8) return MC_EINVAL;
     if (M % V != 0) return MC_EINVAL;
-    if (lhs_bits != 0 && lhs_bits != 4 && lhs_bits != 8 && lhs_bits != 16) return MC_EINVAL;
+    if (!valid_lhs_bits(lhs_bits)) return MC_EINVAL;
     const int P = M / V;
     if (row_ptr[0] != 0) return MC_EINVAL;
     int64_t nslots = 0;
@@ -102,9 +105,11 @@ extern "C" int mc_pack_host(int M, int K, int V, int lhs_bits, const int32_t *ro
                 const int64_t e = (lo + i) * V + v; // element in interchange order
                 if (lhs_bits == 8) {
                     chunk[g * (16 * V) + v * 16 + b] = static_cast<const uint8_t *>(values)[e];
-                } else if (lhs_bits == 16) {
+                } else if (lhs_bits == 16 || lhs_bits == 12) {
                     int8_t hi, l8;
-                    if (!split_balanced(static_cast<const int16_t *>(values)[e], &hi, &l8)) return MC_ERANGE;
+                    const int x = static_cast<const int16_t *>(values)[e];
+                    if (lhs_bits == 12 && (x < -2048 || x > 2047)) return MC_ERANGE;
+                    if (!split_balanced(x, &hi, &l8)) return MC_ERANGE;
                     chunk[g * (32 * V) + v * 16 + b] = (uint8_t)hi;
                     chunk[g * (32 * V) + 16 * V + v * 16 + b] = (uint8_t)l8;
                 } else { // 4 bits
@@ -123,7 +128,7 @@ extern "C" int mc_unpack_host(int M, int K, int V, int lhs_bits, const int32_t *
                               int32_t *col_idx, void *values)
 {
     if (M <= 0 || K <= 0 || (V != 2 && V != 4 && V != 8) || M % V) return MC_EINVAL;
-    if (lhs_bits != 0 && lhs_bits != 4 && lhs_bits != 8 && lhs_bits != 16) return MC_EINVAL;
+    if (!valid_lhs_bits(lhs_bits)) return MC_EINVAL;
     if (!panel_ptr || !row_ptr) return MC_EINVAL;
     const int P = M / V;
     const uint8_t *src = static_cast<const uint8_t *>(slot_vals);
@@ -144,7 +149,7 @@ extern "C" int mc_unpack_host(int M, int K, int V, int lhs_bits, const int32_t *
                 const int64_t e = out * V + v;
                 if (lhs_bits == 8) {
                     static_cast<uint8_t *>(values)[e] = chunk[g * (16 * V) + v * 16 + b];
-                } else if (lhs_bits == 16) {
+                } else if (lhs_bits == 16 || lhs_bits == 12) {
                     const int hi = (int8_t)chunk[g * (32 * V) + v * 16 + b];
                     const int l8 = (int8_t)chunk[g * (32 * V) + 16 * V + v * 16 + b];
                     static_cast<int16_t *>(values)[e] = (int16_t)(hi * 256 + l8);

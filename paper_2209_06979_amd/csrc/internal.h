@@ -83,7 +83,7 @@ struct AttnArgs {
 hipError_t launch_spmm(mc_prec prec, const SpmmArgs &a, int bnb, int waves, hipStream_t s);
 // waves: 0 = the direct-load kernel; 1, 2, 4, 8 = waves per panel of the LDS-staged kernel
 // (used when a row has 64, 128 or 256 bytes)
-hipError_t launch_sddmm(bool int4, const SddmmArgs &a, int waves, hipStream_t s);
+hipError_t launch_sddmm(int bits, const SddmmArgs &a, int waves, hipStream_t s);
 hipError_t launch_softmax(const SoftmaxArgs &a, hipStream_t s);
 hipError_t launch_repack(const RepackArgs &a, hipStream_t s);
 // heads_per_group 2 needs head_stride == 64 (token-major layout) and an even head count

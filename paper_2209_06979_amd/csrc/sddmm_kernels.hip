@@ -14,6 +14,8 @@
 //                      (global_load_lds), then read as 128-bit MFMA operands; the
 //                      16-byte segments are XOR-swizzled against bank conflicts.
 //   sddmm_direct_kernel any row length: each lane loads its 16 operand bytes from memory.
+// int4 operands are widened in registers; int16 operands (L16-R16, Section 4.4) are split in
+// registers into signed byte planes, the two Q planes stacked in the MFMA rows 0..7 / 8..15.
 // The output is written in interchange (BCRS) order: V consecutive int32 per vector.
 #include "internal.h"
 
@@ -35,6 +37,62 @@ __device__ __forceinline__ void widen4(v4i x, v4i &even, v4i &odd)
     odd = x & m;
 }
 
+// 16 little-endian int16 elements (x: the first 8, y: the last 8) -> their signed byte planes
+// e = 256 * hi + lo with lo the low byte read as int8 and hi = (e + 128) >> 8 (Section 4.4 with
+// both planes signed; needs e <= 32639).  Byte t of a plane register belongs to element t of
+// the 32-byte piece on both operand sides, so the planes of Q and Kmat pair up term by term.
+__device__ __forceinline__ void split16(v4i x, v4i y, v4i &hi, v4i &lo)
+{
+    typedef unsigned short v8us __attribute__((ext_vector_type(8)));
+    const v8us half = {128, 128, 128, 128, 128, 128, 128, 128};
+    const v4i xr = __builtin_bit_cast(v4i, (v8us)(__builtin_bit_cast(v8us, x) + half));
+    const v4i yr = __builtin_bit_cast(v4i, (v8us)(__builtin_bit_cast(v8us, y) + half));
+    // v_perm_b32 picks bytes from {first operand: bytes 4..7, second operand: bytes 0..3}
+    constexpr unsigned EVEN = 0x06040200u, ODD = 0x07050301u;
+    lo = (v4i){(int)__builtin_amdgcn_perm(x.y, x.x, EVEN), (int)__builtin_amdgcn_perm(x.w, x.z, EVEN),
+               (int)__builtin_amdgcn_perm(y.y, y.x, EVEN), (int)__builtin_amdgcn_perm(y.w, y.z, EVEN)};
+    hi = (v4i){(int)__builtin_amdgcn_perm(xr.y, xr.x, ODD), (int)__builtin_amdgcn_perm(xr.w, xr.z, ODD),
+               (int)__builtin_amdgcn_perm(yr.y, yr.x, ODD), (int)__builtin_amdgcn_perm(yr.w, yr.z, ODD)};
+}
+
+// One reduction step of a 16-vector tile.  PB = operand width in bits.
+//   8:  q, k are the operands.
+//   4:  q, k hold packed nibbles; both are widened (16 x value) and multiplied pairwise.
+//   16: q is ONE plane of the Q row (lanes 0..7 of a group of 16 carry the high plane of Q
+//       rows 0..7, lanes 8..15 the low plane: the planes are stacked in the MFMA rows), kh / kl
+//       are the planes of the Kmat piece; acc takes q x kh and acc2 takes q x kl.
+template <int PB>
+__device__ __forceinline__ void mma_step(v4i q, v4i k, v4i k2, v4i &acc, v4i &acc2)
+{
+    if (PB == 4) {
+        v4i qe, qo, ke, ko;
+        widen4(q, qe, qo);
+        widen4(k, ke, ko);
+        acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(qe, ke, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(qo, ko, acc, 0, 0, 0);
+    } else {
+        acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(q, k, acc, 0, 0, 0);
+        if (PB == 16) acc2 = __builtin_amdgcn_mfma_i32_16x16x64_i8(q, k2, acc2, 0, 0, 0);
+    }
+}
+
+// Finishes a tile's accumulators.  16 bit: rows 0..7 hold Qh.Kh (acc) and Qh.Kl (acc2), rows
+// 8..15 (32 lanes further up) hold Ql.Kh and Ql.Kl; S = (QhKh << 16) + ((QhKl + QlKh) << 8) + QlKl.
+template <int PB> __device__ __forceinline__ v4i finish_tile(v4i acc, v4i acc2)
+{
+    if (PB == 4) return acc >> 8; // both operands carried a factor 16
+    if (PB == 16) {
+        v4i up, up2;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            up[r] = __shfl_xor(acc[r], 32);
+            up2[r] = __shfl_xor(acc2[r], 32);
+        }
+        return (acc << 16) + ((acc2 + up) << 8) + up2; // meaningful in lanes 0..31 only
+    }
+    return acc;
+}
+
 __device__ __forceinline__ void store_scores(const SddmmArgs &a, int64_t out0, int slot, int n, int g, v4i acc)
 {
     // accumulator register r of lane (j, g) is row 4g + r of vector `slot`
@@ -45,11 +103,39 @@ __device__ __forceinline__ void store_scores(const SddmmArgs &a, int64_t out0, i
     }
 }
 
-// RB: bytes of a Kmat row (64, 128, 256).  WK: waves per workgroup.
-template <bool R4, int RB, int WK>
+// Bytes of a row that one MFMA step consumes (64 operand bytes per plane).
+template <int PB> struct StepBytes { static constexpr int value = (PB == 16) ? 128 : 64; };
+
+// The Q operand of step kc for this lane, straight from memory (zero outside the panel's rows
+// and beyond the row end).  j = lane % 16, g = lane / 16.
+template <int PB>
+__device__ __forceinline__ v4i load_q(const uint8_t *Qpanel, int64_t ldq_bytes, int V, int row_bytes, int kc, int j, int g)
+{
+    v4i q = {0, 0, 0, 0};
+    if (PB == 16) {
+        const int off = kc * 128 + g * 32;
+        if ((j & 7) < V && off < row_bytes) {
+            const uint8_t *p = Qpanel + (int64_t)(j & 7) * ldq_bytes + off;
+            const v4i x = *reinterpret_cast<const v4i *>(p);
+            v4i y = {0, 0, 0, 0};
+            if (off + 16 < row_bytes) y = *reinterpret_cast<const v4i *>(p + 16);
+            v4i hi, lo;
+            split16(x, y, hi, lo);
+            q = (j < 8) ? hi : lo;
+        }
+    } else {
+        const int off = kc * 64 + g * 16;
+        if (j < V && off < row_bytes) q = *reinterpret_cast<const v4i *>(Qpanel + (int64_t)j * ldq_bytes + off);
+    }
+    return q;
+}
+
+// RB: bytes of a Kmat row (64, 128, 256; 16-bit operands: 128, 256).  WK: waves per workgroup.
+template <int PB, int RB, int WK>
 __global__ __launch_bounds__(64 * WK) void sddmm_lds_kernel(SddmmArgs a)
 {
-    constexpr int LPR = RB / 16, NI = LPR, RPI = 64 / LPR, KC = RB / 64;
+    constexpr int LPR = RB / 16, NI = LPR, RPI = 64 / LPR, KC = RB / StepBytes<PB>::value;
+    static_assert(KC >= 1, "a row must fill at least one MFMA step");
     __shared__ __attribute__((aligned(16))) char lds[WK * 64 * RB];
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int j = lane & 15, g = lane >> 4;
@@ -63,13 +149,9 @@ __global__ __launch_bounds__(64 * WK) void sddmm_lds_kernel(SddmmArgs a)
     char *stage = lds + w * (64 * RB);
 
     v4i qf[KC];
+    const uint8_t *Qpanel = a.Q + (int64_t)batch * a.Q_batch_stride + (int64_t)panel * a.V * a.ldq_bytes;
 #pragma unroll
-    for (int kc = 0; kc < KC; ++kc) {
-        qf[kc] = (v4i){0, 0, 0, 0};
-        if (j < a.V)
-            qf[kc] = *reinterpret_cast<const v4i *>(a.Q + (int64_t)batch * a.Q_batch_stride +
-                                                    (int64_t)(panel * a.V + j) * a.ldq_bytes + kc * 64 + g * 16);
-    }
+    for (int kc = 0; kc < KC; ++kc) qf[kc] = load_q<PB>(Qpanel, a.ldq_bytes, a.V, RB, kc, j, g);
     // load instruction i: lane (rg, seg) copies segment seg ^ i of the row in slot rg*NI + i
     // to LDS row i*RPI + rg (byte i*1024 + lane*16 of the stage)
     const int nmy = (nch > w) ? (nch - w + WK - 1) / WK : 0;
@@ -93,95 +175,83 @@ __global__ __launch_bounds__(64 * WK) void sddmm_lds_kernel(SddmmArgs a)
             const int s = tl * 16 + j;              // slot within the chunk
             const int i = s % NI, r = s / NI;       // its load instruction and row group
             const char *rowp = stage + i * 1024 + r * RB;
-            v4i acc = {0, 0, 0, 0};
+            v4i acc = {0, 0, 0, 0}, acc2 = {0, 0, 0, 0};
 #pragma unroll
             for (int kc = 0; kc < KC; ++kc) {
-                const v4i kf = *reinterpret_cast<const v4i *>(rowp + (((kc * 4 + g) ^ i) * 16));
-                if (R4) {
-                    v4i qe, qo, ke, ko;
-                    widen4(qf[kc], qe, qo);
-                    widen4(kf, ke, ko);
-                    acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(qe, ke, acc, 0, 0, 0);
-                    acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(qo, ko, acc, 0, 0, 0);
+                if (PB == 16) {
+                    const v4i x = *reinterpret_cast<const v4i *>(rowp + (((kc * 8 + 2 * g) ^ i) * 16));
+                    const v4i y = *reinterpret_cast<const v4i *>(rowp + (((kc * 8 + 2 * g + 1) ^ i) * 16));
+                    v4i kh, kl;
+                    split16(x, y, kh, kl);
+                    mma_step<PB>(qf[kc], kh, kl, acc, acc2);
                 } else {
-                    acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(qf[kc], kf, acc, 0, 0, 0);
+                    const v4i kf = *reinterpret_cast<const v4i *>(rowp + (((kc * 4 + g) ^ i) * 16));
+                    mma_step<PB>(qf[kc], kf, kf, acc, acc2);
                 }
             }
-            if (R4) acc = acc >> 8; // both operands carried a factor 16
-            store_scores(a, out0, c * MC_CHUNK + s, n, g, acc);
+            store_scores(a, out0, c * MC_CHUNK + s, n, g, finish_tile<PB>(acc, acc2));
         }
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); // reads done before the rows are overwritten
     }
 }
 
-// KC = number of 64-byte steps along a row kept in registers (0: any length, Q re-read).
-template <bool R4, int KC>
+// KC = number of MFMA steps along a row kept in registers (0: any length, Q re-read).
+template <int PB, int KC>
 __global__ __launch_bounds__(64 * SDDMM_WAVES) void sddmm_direct_kernel(SddmmArgs a)
 {
+    constexpr int STEP = StepBytes<PB>::value, LANEB = STEP / 4; // bytes per step / per lane and step
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int j = lane & 15, g = lane >> 4;
     const int panel = blockIdx.x, batch = blockIdx.y;
     const int s0 = a.panel_ptr[2 * panel], n = a.panel_ptr[2 * panel + 1] - s0;
     const int ntile = (n + 15) / 16;
     const int64_t out0 = (int64_t)batch * a.S_batch_stride + (int64_t)a.row_ptr[panel] * a.V;
-    const uint8_t *Q = a.Q + (int64_t)batch * a.Q_batch_stride + (int64_t)(panel * a.V + j) * a.ldq_bytes + g * 16;
-    const uint8_t *Km = a.Kmat + (int64_t)batch * a.K_batch_stride + g * 16;
-    const int kc_n = (a.row_bytes + 63) / 64;
-    const bool qrow = j < a.V;
+    const uint8_t *Qpanel = a.Q + (int64_t)batch * a.Q_batch_stride + (int64_t)panel * a.V * a.ldq_bytes;
+    const uint8_t *Km = a.Kmat + (int64_t)batch * a.K_batch_stride + g * LANEB;
+    const int kc_n = (a.row_bytes + STEP - 1) / STEP;
+
+    // this lane's piece of step kc of a Kmat row: (k, k2) = the operand (8 / 4 bit) or its planes
+    auto load_k = [&](const uint8_t *kr, int kc, v4i &k, v4i &k2) {
+        k = k2 = (v4i){0, 0, 0, 0};
+        const int off = kc * STEP + g * LANEB;
+        if (off < a.row_bytes) {
+            const v4i x = *reinterpret_cast<const v4i *>(kr + kc * STEP);
+            if (PB == 16) {
+                v4i y = {0, 0, 0, 0};
+                if (off + 16 < a.row_bytes) y = *reinterpret_cast<const v4i *>(kr + kc * STEP + 16);
+                split16(x, y, k, k2);
+            } else {
+                k = x;
+            }
+        }
+    };
 
     v4i qf[KC > 0 ? KC : 1];
     if (KC > 0) {
 #pragma unroll
-        for (int kc = 0; kc < KC; ++kc) {
-            qf[kc] = (v4i){0, 0, 0, 0};
-            if (qrow && kc * 64 + g * 16 < a.row_bytes) qf[kc] = *reinterpret_cast<const v4i *>(Q + kc * 64);
-        }
+        for (int kc = 0; kc < KC; ++kc) qf[kc] = load_q<PB>(Qpanel, a.ldq_bytes, a.V, a.row_bytes, kc, j, g);
     }
 
     for (int t = w; t < ntile; t += SDDMM_WAVES) {
         const int slot = t * 16 + j;
         const int row = a.slot_idx[s0 + slot]; // padded slots name a valid row
         const uint8_t *kr = Km + (int64_t)row * a.ldk_bytes;
-        v4i acc = {0, 0, 0, 0};
+        v4i acc = {0, 0, 0, 0}, acc2 = {0, 0, 0, 0};
         if (KC > 0) {
-            v4i kf[KC > 0 ? KC : 1];
+            v4i kf[KC > 0 ? KC : 1], kf2[KC > 0 ? KC : 1];
 #pragma unroll
-            for (int kc = 0; kc < KC; ++kc) {
-                kf[kc] = (v4i){0, 0, 0, 0};
-                if (kc * 64 + g * 16 < a.row_bytes) kf[kc] = *reinterpret_cast<const v4i *>(kr + kc * 64);
-            }
+            for (int kc = 0; kc < KC; ++kc) load_k(kr, kc, kf[kc], kf2[kc]);
 #pragma unroll
-            for (int kc = 0; kc < KC; ++kc) {
-                if (R4) {
-                    v4i qe, qo, ke, ko;
-                    widen4(qf[kc], qe, qo);
-                    widen4(kf[kc], ke, ko);
-                    acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(qe, ke, acc, 0, 0, 0);
-                    acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(qo, ko, acc, 0, 0, 0);
-                } else {
-                    acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(qf[kc], kf[kc], acc, 0, 0, 0);
-                }
-            }
+            for (int kc = 0; kc < KC; ++kc) mma_step<PB>(qf[kc], kf[kc], kf2[kc], acc, acc2);
         } else {
             for (int kc = 0; kc < kc_n; ++kc) {
-                v4i q = {0, 0, 0, 0}, k = {0, 0, 0, 0};
-                if (kc * 64 + g * 16 < a.row_bytes) {
-                    k = *reinterpret_cast<const v4i *>(kr + kc * 64);
-                    if (qrow) q = *reinterpret_cast<const v4i *>(Q + kc * 64);
-                }
-                if (R4) {
-                    v4i qe, qo, ke, ko;
-                    widen4(q, qe, qo);
-                    widen4(k, ke, ko);
-                    acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(qe, ke, acc, 0, 0, 0);
-                    acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(qo, ko, acc, 0, 0, 0);
-                } else {
-                    acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(q, k, acc, 0, 0, 0);
-                }
+                v4i k, k2;
+                load_k(kr, kc, k, k2);
+                const v4i q = load_q<PB>(Qpanel, a.ldq_bytes, a.V, a.row_bytes, kc, j, g);
+                mma_step<PB>(q, k, k2, acc, acc2);
             }
         }
-        if (R4) acc = acc >> 8; // both operands carried a factor 16
-        store_scores(a, out0, slot, n, g, acc);
+        store_scores(a, out0, slot, n, g, finish_tile<PB>(acc, acc2));
     }
 }
 
@@ -274,49 +344,42 @@ __global__ __launch_bounds__(256) void repack_kernel(RepackArgs a)
 
 } // namespace
 
-template <bool R4, int RB> hipError_t launch_sddmm_lds(const SddmmArgs &a, int waves, hipStream_t s)
+template <int PB, int RB> hipError_t launch_sddmm_lds(const SddmmArgs &a, int waves, hipStream_t s)
 {
     dim3 grid((unsigned)a.P, (unsigned)a.batch);
     constexpr int MAXW = (64 * RB * 8 <= 65536) ? 8 : 4;
     if (waves > MAXW) waves = MAXW;
     switch (waves) {
-    case 1: hipLaunchKernelGGL((sddmm_lds_kernel<R4, RB, 1>), grid, dim3(64), 0, s, a); break;
-    case 2: hipLaunchKernelGGL((sddmm_lds_kernel<R4, RB, 2>), grid, dim3(128), 0, s, a); break;
-    case 4: hipLaunchKernelGGL((sddmm_lds_kernel<R4, RB, 4>), grid, dim3(256), 0, s, a); break;
-    default: hipLaunchKernelGGL((sddmm_lds_kernel<R4, RB, MAXW>), grid, dim3(64 * MAXW), 0, s, a); break;
+    case 1: hipLaunchKernelGGL((sddmm_lds_kernel<PB, RB, 1>), grid, dim3(64), 0, s, a); break;
+    case 2: hipLaunchKernelGGL((sddmm_lds_kernel<PB, RB, 2>), grid, dim3(128), 0, s, a); break;
+    case 4: hipLaunchKernelGGL((sddmm_lds_kernel<PB, RB, 4>), grid, dim3(256), 0, s, a); break;
+    default: hipLaunchKernelGGL((sddmm_lds_kernel<PB, RB, MAXW>), grid, dim3(64 * MAXW), 0, s, a); break;
     }
     return hipGetLastError();
 }
 
-hipError_t launch_sddmm(bool int4, const SddmmArgs &a, int waves, hipStream_t s)
+template <int PB> hipError_t launch_sddmm_bits(const SddmmArgs &a, int waves, hipStream_t s)
 {
-    if (a.P == 0 || a.batch == 0) return hipSuccess;
-    if (waves > 0 && (a.row_bytes == 64 || a.row_bytes == 128 || a.row_bytes == 256)) {
-        if (int4) {
-            if (a.row_bytes == 64) return launch_sddmm_lds<true, 64>(a, waves, s);
-            if (a.row_bytes == 128) return launch_sddmm_lds<true, 128>(a, waves, s);
-            return launch_sddmm_lds<true, 256>(a, waves, s);
-        }
-        if (a.row_bytes == 64) return launch_sddmm_lds<false, 64>(a, waves, s);
-        if (a.row_bytes == 128) return launch_sddmm_lds<false, 128>(a, waves, s);
-        return launch_sddmm_lds<false, 256>(a, waves, s);
+    if (waves > 0) {
+        if (a.row_bytes == 64 && PB != 16) return launch_sddmm_lds<(PB == 16 ? 8 : PB), 64>(a, waves, s);
+        if (a.row_bytes == 128) return launch_sddmm_lds<PB, 128>(a, waves, s);
+        if (a.row_bytes == 256) return launch_sddmm_lds<PB, 256>(a, waves, s);
     }
     dim3 grid((unsigned)a.P, (unsigned)a.batch), block(64 * SDDMM_WAVES);
-    const int kc = (a.row_bytes + 63) / 64;
-#define MC_SDDMM(R4, KC) hipLaunchKernelGGL((sddmm_direct_kernel<R4, KC>), grid, block, 0, s, a)
-    if (int4) {
-        if (kc == 1) MC_SDDMM(true, 1);
-        else if (kc == 2) MC_SDDMM(true, 2);
-        else if (kc <= 4) MC_SDDMM(true, 4);
-        else MC_SDDMM(true, 0);
-    } else {
-        if (kc == 1) MC_SDDMM(false, 1);
-        else if (kc == 2) MC_SDDMM(false, 2);
-        else if (kc <= 4) MC_SDDMM(false, 4);
-        else MC_SDDMM(false, 0);
-    }
-#undef MC_SDDMM
+    const int kc = (a.row_bytes + StepBytes<PB>::value - 1) / StepBytes<PB>::value;
+    if (kc == 1) hipLaunchKernelGGL((sddmm_direct_kernel<PB, 1>), grid, block, 0, s, a);
+    else if (kc == 2) hipLaunchKernelGGL((sddmm_direct_kernel<PB, 2>), grid, block, 0, s, a);
+    else if (kc <= 4) hipLaunchKernelGGL((sddmm_direct_kernel<PB, 4>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((sddmm_direct_kernel<PB, 0>), grid, block, 0, s, a);
     return hipGetLastError();
+}
+
+hipError_t launch_sddmm(int bits, const SddmmArgs &a, int waves, hipStream_t s)
+{
+    if (a.P == 0 || a.batch == 0) return hipSuccess;
+    if (bits == 4) return launch_sddmm_bits<4>(a, waves, s);
+    if (bits == 16) return launch_sddmm_bits<16>(a, waves, s);
+    return launch_sddmm_bits<8>(a, waves, s);
 }
 
 hipError_t launch_softmax(const SoftmaxArgs &a, hipStream_t s)

@@ -23,7 +23,12 @@
 //      16 x the signed nibble, so (x << 4) & 0xF0F0F0F0 and x & 0xF0F0F0F0 are valid int8
 //      operands and the int32 sums are shifted right by 4 (or 8) at the end;
 //   4. 16-bit A travels as two signed int8 planes in rows 0..7 (high) and 8..15 (low) of
-//      the same MFMA (the "stacking" of Section 4.4) and is recombined as (hi<<8)+lo.
+//      the same MFMA (the "stacking" of Section 4.4) and is recombined as (hi<<8)+lo;
+//   5. a 16-bit B row is gathered as it is and treated as a byte matrix of twice the width:
+//      even byte columns hold the low (unsigned) bytes, odd ones the high (signed) bytes.
+//      The MFMA is signed x signed, so a low byte u enters as u ^ 0x80 = u - 128 and the
+//      missing 128 * sum_k A[m][k] comes from one extra MFMA per chunk against an all-ones
+//      operand; the byte-column pairs are recombined as (hi<<8)+lo in the epilogue.
 // The sum over a chunk does not depend on the order of its terms; slot s of a chunk is
 // reduction byte (s % 16) of lane group (s / 16) on both the A and the B side.
 #include "internal.h"
@@ -37,18 +42,17 @@ typedef __attribute__((address_space(3))) v2i lds_v2i;
 typedef __attribute__((address_space(1))) const void gptr_t;
 typedef __attribute__((address_space(3))) void lptr_t;
 
-enum { PREC_L8R8 = 0, PREC_L8R4 = 1, PREC_L4R4 = 2, PREC_L16R8 = 3 };
-
 // A operand of one chunk for this lane (row = lane % 16, lane group = lane / 16).
-template <int MODE>
+// LB: stored width of A (4, 8 or 16 bits; a 12-bit operand is stored as 16).
+template <int LB>
 __device__ __forceinline__ v4i load_a(const uint8_t *vals, int64_t chunk, int V, int row, int g)
 {
     v4i a = {0, 0, 0, 0};
-    if (MODE == PREC_L16R8) {
+    if (LB == 16) {
         // [chunk][g][plane hi, lo][v][16]; high plane in rows 0..V-1, low plane in rows 8..8+V-1
         const int v = row & 7;
         if (v < V) a = *reinterpret_cast<const v4i *>(vals + chunk * (128 * V) + g * (32 * V) + (row >> 3) * (16 * V) + v * 16);
-    } else if (MODE == PREC_L4R4) {
+    } else if (LB == 4) {
         // [chunk][g][v][8 bytes]: byte b = slot b (low nibble), slot b+8 (high nibble)
         if (row < V) {
             const v2i x = *reinterpret_cast<const v2i *>(vals + chunk * (32 * V) + g * (8 * V) + row * 8);
@@ -63,28 +67,30 @@ __device__ __forceinline__ v4i load_a(const uint8_t *vals, int64_t chunk, int V,
     return a;
 }
 
-template <int BNB, int WK, int MODE> struct SpmmCfg {
-    static constexpr bool R4 = (MODE == PREC_L8R4 || MODE == PREC_L4R4);
+template <int BNB, int WK, int LB, int RB> struct SpmmCfg {
+    static constexpr bool R4 = (RB == 4), R16 = (RB == 16), L16 = (LB == 16);
     static constexpr int LPR = BNB / 16;                 // lanes (16-byte segments) per row
     static constexpr int NI = LPR;                       // load instructions per chunk
     static constexpr int RPI = 64 / LPR;                 // rows per load instruction
     static constexpr int SWZ = (LPR == 4) ? 3 : 7;       // bits of the instruction number used as swizzle
-    static constexpr int NACC = LPR * (R4 ? 2 : 1);      // MFMA accumulators per lane (v4i each)
+    static constexpr int NACC = LPR * (R4 ? 2 : 1) + (R16 ? 1 : 0); // MFMA accumulators per lane (v4i each); R16: + row sums of A
     static constexpr int STAGE = 64 * BNB;               // LDS bytes of one staged chunk
-    static constexpr int COLS = BNB * (R4 ? 2 : 1);      // output columns of the tile
-    static constexpr int OROWS = (MODE == PREC_L16R8) ? 16 : 8;
+    static constexpr int COLS = BNB * (R4 ? 2 : 1);      // columns of the partial tile (byte columns for R16)
+    static constexpr int OUTC = R16 ? BNB / 2 : COLS;    // output columns of the tile
+    static constexpr int OROWS = L16 ? 16 : 8;
     static constexpr int TST = COLS + 4;                 // row stride (ints) of a partial tile: +4 keeps rows 4 apart in different banks
     static constexpr int OTILE = OROWS * TST * 4;        // bytes of one wave's partial tile
     static constexpr int PERWAVE = (STAGE > OTILE) ? STAGE : OTILE;
     static constexpr int LDS = WK * PERWAVE;
 };
 
-template <int BNB, int WK, int MODE>
+template <int BNB, int WK, int LB, int RB>
 __global__ __launch_bounds__(64 * WK) void spmm_kernel(SpmmArgs a)
 {
-    using Cfg = SpmmCfg<BNB, WK, MODE>;
+    using Cfg = SpmmCfg<BNB, WK, LB, RB>;
     constexpr int LPR = Cfg::LPR, NI = Cfg::NI, RPI = Cfg::RPI, NACC = Cfg::NACC, COLS = Cfg::COLS, TST = Cfg::TST;
-    constexpr bool R4 = Cfg::R4;
+    constexpr int OUTC = Cfg::OUTC;
+    constexpr bool R4 = Cfg::R4, R16 = Cfg::R16, L16 = Cfg::L16;
     __shared__ __attribute__((aligned(16))) char lds[Cfg::LDS];
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -134,6 +140,8 @@ __global__ __launch_bounds__(64 * WK) void spmm_kernel(SpmmArgs a)
         const int i = s % NI, r = s / NI;
         rd_base[h] = i * 1024 + r * BNB + ((i & Cfg::SWZ) * 16) + 8 * (src & 1);
     }
+    // R16: lanes that own an even byte column (low bytes) flip the top bit of every byte
+    const int lowflip = (R16 && !(j & 1)) ? (int)0x80808080 : 0;
     v4i idxv[NI / 4];
     if (nmy > 0) load_idx(w, idxv);
     for (int k = 0; k < nmy; ++k) {
@@ -142,14 +150,15 @@ __global__ __launch_bounds__(64 * WK) void spmm_kernel(SpmmArgs a)
         for (int i = 0; i < NI; ++i)
             __builtin_amdgcn_global_load_lds((gptr_t *)(Bb + (int64_t)idxv[i >> 2][i & 3] * a.ldb_bytes + segoff[i]),
                                              (lptr_t *)(stage + i * 1024), 16, 0, 0);
-        const v4i a_cur = load_a<MODE>(vals, chunk0 + c, a.V, j, g);
+        const v4i a_cur = load_a<LB>(vals, chunk0 + c, a.V, j, g);
         if (k + 1 < nmy) load_idx(c + WK, idxv); // the copies above have consumed the old indices
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #pragma unroll
         for (int ct = 0; ct < LPR; ++ct) {
             const v2i d0 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(stage + (rd_base[0] ^ (ct * 16))));
             const v2i d1 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(stage + (rd_base[1] ^ (ct * 16))));
-            const v4i bop = {d0.x, d0.y, d1.x, d1.y};
+            v4i bop = {d0.x, d0.y, d1.x, d1.y};
+            if (R16) bop ^= (v4i){lowflip, lowflip, lowflip, lowflip};
             if (!R4) {
                 acc[ct] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a_cur, bop, acc[ct], 0, 0, 0);
             } else {
@@ -157,6 +166,10 @@ __global__ __launch_bounds__(64 * WK) void spmm_kernel(SpmmArgs a)
                 acc[2 * ct] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a_cur, (bop << 4) & msk, acc[2 * ct], 0, 0, 0);
                 acc[2 * ct + 1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a_cur, bop & msk, acc[2 * ct + 1], 0, 0, 0);
             }
+        }
+        if (R16) {
+            const v4i ones = {0x01010101, 0x01010101, 0x01010101, 0x01010101};
+            acc[LPR] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a_cur, ones, acc[LPR], 0, 0, 0); // every column: sum over the chunk of A's row
         }
         // the reads of the staged rows are complete before the next chunk overwrites them
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -179,26 +192,46 @@ __global__ __launch_bounds__(64 * WK) void spmm_kernel(SpmmArgs a)
                     *reinterpret_cast<v2i *>(&tile_w[(4 * g + r) * TST + ct * 32 + 2 * j]) = (v2i){acc[2 * ct][r], acc[2 * ct + 1][r]};
                 }
             }
+        if (R16 && j == 0) { // the row sums ride in the padding column of the tile
+#pragma unroll
+            for (int r = 0; r < 4; ++r) tile_w[(4 * g + r) * TST + COLS] = acc[LPR][r];
+        }
     }
     __syncthreads();
 
     // ---- sum over the waves, finish the arithmetic, store 16 bytes per thread -------------
-    const int ncols = a.row_bytes * (R4 ? 2 : 1);
-    constexpr int PIECES = 8 * (COLS / 4);
+    // Every plane sum is exact in int32 (R4: after its shift); the recombinations wrap.
+    const int ncols = R4 ? a.row_bytes * 2 : (R16 ? a.row_bytes / 2 : a.row_bytes);
+    constexpr int PIECES = 8 * (OUTC / 4);
+    constexpr int SH = R4 ? (LB == 4 ? 8 : 4) : 0;       // scale carried by widened nibbles
     for (int pc = tid; pc < PIECES; pc += 64 * WK) {
-        const int row = pc / (COLS / 4), col = (pc % (COLS / 4)) * 4;
-        const int gcol = nb0 * (R4 ? 2 : 1) + col;
+        const int row = pc / (OUTC / 4), col = (pc % (OUTC / 4)) * 4;
+        const int gcol = tile * OUTC + col;
         if (row >= a.V || gcol >= ncols) continue;
-        v4i s = {0, 0, 0, 0}, lo = {0, 0, 0, 0};
+        const int tcol = R16 ? 2 * col : col;            // first column in the partial tile
+        v4i s = {0, 0, 0, 0}, lo = {0, 0, 0, 0}, s2 = {0, 0, 0, 0}, lo2 = {0, 0, 0, 0};
+        int rs = 0, rs_lo = 0;
 #pragma unroll
         for (int ww = 0; ww < WK; ++ww) {
             const int *t = reinterpret_cast<const int *>(lds + ww * Cfg::PERWAVE);
-            s += *reinterpret_cast<const v4i *>(&t[row * TST + col]);
-            if (MODE == PREC_L16R8) lo += *reinterpret_cast<const v4i *>(&t[(row + 8) * TST + col]);
+            s += *reinterpret_cast<const v4i *>(&t[row * TST + tcol]);
+            if (L16) lo += *reinterpret_cast<const v4i *>(&t[(row + 8) * TST + tcol]);
+            if (R16) {
+                s2 += *reinterpret_cast<const v4i *>(&t[row * TST + tcol + 4]);
+                rs += t[row * TST + COLS];
+                if (L16) {
+                    lo2 += *reinterpret_cast<const v4i *>(&t[(row + 8) * TST + tcol + 4]);
+                    rs_lo += t[(row + 8) * TST + COLS];
+                }
+            }
         }
-        if (MODE == PREC_L16R8) s = (s << 8) + lo;      // wrapping 32-bit arithmetic
-        else if (MODE == PREC_L8R4) s = s >> 4;
-        else if (MODE == PREC_L4R4) s = s >> 8;
+        if (R4) { s = s >> SH; lo = lo >> SH; }
+        if (L16) { s = (s << 8) + lo; s2 = (s2 << 8) + lo2; rs = (rs << 8) + rs_lo; }
+        if (R16) {
+            // byte columns (low, high) of four B elements: A*b = (A*hi << 8) + A*(low ^ 0x80) + 128 * rowsum(A)
+            const int fix = rs << 7;
+            s = (v4i){(s.y << 8) + s.x + fix, (s.w << 8) + s.z + fix, (s2.y << 8) + s2.x + fix, (s2.w << 8) + s2.z + fix};
+        }
         const int64_t off = (int64_t)batch * a.C_batch_stride + (int64_t)(panel * a.V + row) * a.ldc + gcol;
         if (a.float_out) {
             const v4f f = {s.x * a.out_scale, s.y * a.out_scale, s.z * a.out_scale, s.w * a.out_scale};
@@ -209,33 +242,32 @@ __global__ __launch_bounds__(64 * WK) void spmm_kernel(SpmmArgs a)
     }
 }
 
-template <int BNB, int WK, int MODE> hipError_t launch_one(const SpmmArgs &a, hipStream_t s)
+template <int BNB, int WK, int LB, int RB> hipError_t launch_one(const SpmmArgs &a, hipStream_t s)
 {
     const int ntiles = (a.row_bytes + BNB - 1) / BNB;
     dim3 grid((unsigned)(a.P * ntiles), (unsigned)a.batch), block(64 * WK);
-    hipLaunchKernelGGL((spmm_kernel<BNB, WK, MODE>), grid, block, 0, s, a);
+    hipLaunchKernelGGL((spmm_kernel<BNB, WK, LB, RB>), grid, block, 0, s, a);
     return hipGetLastError();
 }
 
-template <int BNB, int MODE> hipError_t launch_wk(const SpmmArgs &a, int waves, hipStream_t s)
+template <int BNB, int LB, int RB> hipError_t launch_wk(const SpmmArgs &a, int waves, hipStream_t s)
 {
     // the per-wave LDS regions of a workgroup must fit 64 KB
-    constexpr int MAXW = (SpmmCfg<BNB, 8, MODE>::LDS <= 65536) ? 8 : ((SpmmCfg<BNB, 4, MODE>::LDS <= 65536) ? 4 : 2);
+    constexpr int MAXW = (SpmmCfg<BNB, 8, LB, RB>::LDS <= 65536) ? 8 : ((SpmmCfg<BNB, 4, LB, RB>::LDS <= 65536) ? 4 : 2);
     if (waves > MAXW) waves = MAXW;
     switch (waves) {
-    case 1: return launch_one<BNB, 1, MODE>(a, s);
-    case 2: return launch_one<BNB, 2, MODE>(a, s);
-    case 4: return launch_one<BNB, (MAXW < 4 ? MAXW : 4), MODE>(a, s);
-    default: return launch_one<BNB, MAXW, MODE>(a, s);
+    case 1: return launch_one<BNB, 1, LB, RB>(a, s);
+    case 2: return launch_one<BNB, 2, LB, RB>(a, s);
+    case 4: return launch_one<BNB, (MAXW < 4 ? MAXW : 4), LB, RB>(a, s);
+    default: return launch_one<BNB, MAXW, LB, RB>(a, s);
     }
 }
 
-template <int MODE> hipError_t launch_mode(const SpmmArgs &a, int bnb, int waves, hipStream_t s)
+template <int LB, int RB> hipError_t launch_mode(const SpmmArgs &a, int bnb, int waves, hipStream_t s)
 {
-    constexpr bool R4 = (MODE == PREC_L8R4 || MODE == PREC_L4R4);
-    if (bnb == 64) return launch_wk<64, MODE>(a, waves, s);
-    if (bnb == 256 && !R4) return launch_wk<256, (R4 ? PREC_L8R8 : MODE)>(a, waves, s);
-    return launch_wk<128, MODE>(a, waves, s);
+    if (bnb == 64) return launch_wk<64, LB, RB>(a, waves, s);
+    if (bnb == 256 && RB != 4) return launch_wk<256, (RB == 4 ? 8 : LB), (RB == 4 ? 8 : RB)>(a, waves, s);
+    return launch_wk<128, LB, RB>(a, waves, s);
 }
 
 } // namespace
@@ -244,10 +276,13 @@ hipError_t launch_spmm(mc_prec prec, const SpmmArgs &a, int bnb, int waves, hipS
 {
     if (a.P == 0 || a.batch == 0 || a.row_bytes == 0) return hipSuccess;
     switch (prec) {
-    case MC_L8R8: return launch_mode<PREC_L8R8>(a, bnb, waves, s);
-    case MC_L8R4: return launch_mode<PREC_L8R4>(a, bnb, waves, s);
-    case MC_L4R4: return launch_mode<PREC_L4R4>(a, bnb, waves, s);
-    case MC_L16R8: return launch_mode<PREC_L16R8>(a, bnb, waves, s);
+    case MC_L8R8: return launch_mode<8, 8>(a, bnb, waves, s);
+    case MC_L8R4: return launch_mode<8, 4>(a, bnb, waves, s);
+    case MC_L4R4: return launch_mode<4, 4>(a, bnb, waves, s);
+    case MC_L16R8: return launch_mode<16, 8>(a, bnb, waves, s);
+    case MC_L16R16: return launch_mode<16, 16>(a, bnb, waves, s);
+    case MC_L16R4:
+    case MC_L12R4: return launch_mode<16, 4>(a, bnb, waves, s); // a 12-bit A is stored as two byte planes too
     }
     return hipErrorInvalidValue;
 }

@@ -1,0 +1,160 @@
+"""GPU parity of the emulated wide precisions (table of supported precisions, Section 4.4):
+SpMM L16-R16 / L16-R4 / L12-R4 and SDDMM L16-R16, bit-exact against the CPU oracle."""
+import numpy as np
+import pytest
+
+from paper_2209_06979_amd import workloads as wl
+from gpu_util import run_spmm_gpu, run_spmm_oracle, run_sddmm_gpu, run_sddmm_oracle
+
+pytestmark = pytest.mark.gpu
+
+WIDE = ["L16R16", "L16R4", "L12R4"]
+
+
+def _spmm(case, variant=(0, 0)):
+    print(f"spmm case M={case['M']} K={case['K']} N={case['N']} V={case['V']} {case['prec']} variant={variant}",
+          flush=True)
+    got, want = run_spmm_gpu(case, variant), run_spmm_oracle(case)
+    assert got.dtype == np.int32 and got.shape == want.shape
+    bad = np.argwhere(got != want)
+    assert bad.size == 0, f"{len(bad)} mismatches, first at {bad[0]}: got {got[tuple(bad[0])]} want {want[tuple(bad[0])]}"
+
+
+def _sddmm(case, variants=(-1,)):
+    want = run_sddmm_oracle(case)
+    for waves in variants:
+        print(f"sddmm case M={case['M']} Nc={case['Nc']} Kd={case['Kd']} V={case['V']} {case['prec']} waves={waves}",
+              flush=True)
+        got = run_sddmm_gpu(case, waves)
+        assert got.shape == want.shape
+        bad = np.flatnonzero(got != want)
+        assert bad.size == 0, f"{len(bad)} mismatches, first at {bad[0]}: got {got[bad[0]]} want {want[bad[0]]}"
+
+
+def _rhs(prec, K, N, seed, lo=-2048, hi=2047):
+    if prec == "L16R16":
+        return wl.uniform_int16((K, N), seed, lo, hi)
+    return wl.uniform_packed_int4((K, N // 2), seed)
+
+
+# --------------------------------------------------------------------- SpMM ----
+@pytest.mark.parametrize("prec", WIDE)
+@pytest.mark.parametrize("V", [2, 4, 8])
+def test_spmm_small(prec, V):
+    _spmm(wl.spmm_case(16 * V, 640, 256, V, 0.75, prec, 2000 + V))
+
+
+@pytest.mark.parametrize("bnb", [64, 128, 256])
+@pytest.mark.parametrize("waves", [1, 2, 4, 8])
+@pytest.mark.parametrize("prec", WIDE)
+def test_spmm_every_tile_variant(bnb, waves, prec):
+    N = 168 if prec == "L16R16" else 384    # 336- / 192-byte rows: ragged last tile for 128- and 256-byte tiles
+    _spmm(wl.spmm_case(64, 1024, N, 8, 0.7, prec, 2100 + bnb + waves), (bnb, waves))
+
+
+@pytest.mark.parametrize("prec", WIDE)
+def test_spmm_ragged_and_empty_panels(prec):
+    V, K, N = 8, 700, 192
+    counts = [0, 1, 15, 16, 17, 63, 64, 65, 127, 128, 129, 0, 300, 700, 2, 0]
+    M = V * len(counts)
+    rp, ci = wl.ragged_pattern(M, K, V, counts, 2201)
+    case = dict(M=M, K=K, N=N, V=V, prec=prec, row_ptr=rp, col_idx=ci,
+                values=wl.uniform_int16((len(ci), V), 2202), B=_rhs(prec, K, N, 2203))
+    for variant in [(0, 0), (64, 4), (128, 2)]:
+        _spmm(case, variant)
+
+
+@pytest.mark.parametrize("N", [8, 24, 40, 136])
+def test_spmm_l16r16_narrow_widths(N):
+    _spmm(wl.spmm_case(32, 256, N, 8, 0.5, "L16R16", 2300 + N))
+    _spmm(wl.spmm_case(16, 256, N, 4, 0.5, "L16R16", 2350 + N))
+
+
+def test_spmm_l16r16_full_int16_range():
+    """B takes every int16 value (its low byte is used unsigned); A up to the split's limit."""
+    V, K, N = 8, 512, 64
+    counts = [1] * 8 + [3] * 4 + [16] * 4
+    M = V * len(counts)
+    rp, ci = wl.ragged_pattern(M, K, V, counts, 2401)
+    nvec = len(ci)
+    B = wl.uniform_int16((K, N), 2402, -32768, 32767)
+    B[ci[0], :4] = [-32768, 32767, -1, 255]
+    vals = wl.uniform_int16((nvec, V), 2403, -2048, 2047)
+    vals[:8] = wl.uniform_int16((8, V), 2404, -32768, 32639)       # panels with a single vector: no overflow
+    vals[0, :4] = [-32768, 32639, -129, 128]
+    _spmm(dict(M=M, K=K, N=N, V=V, prec="L16R16", row_ptr=rp, col_idx=ci, values=vals, B=B))
+
+
+def test_spmm_r4_large_plane_sums():
+    """Most negative operands everywhere: each plane sum is shifted before the planes are combined."""
+    V, M, K, N = 8, 16, 2048, 64
+    rp, ci = wl.vector_sparse_pattern(M, K, V, 0.0, 5)
+    vals = np.full((len(ci), V), -2048, np.int16)
+    B4 = np.full((K, N // 2), 0x88, np.uint8)
+    for prec in ("L16R4", "L12R4"):
+        _spmm(dict(M=M, K=K, N=N, V=V, prec=prec, row_ptr=rp, col_idx=ci, values=vals, B=B4))
+    vals[:] = 16000                          # C = 16000 * 7 * 2048 = 2.3e8 fits int32, 16 * C would not
+    _spmm(dict(M=M, K=K, N=N, V=V, prec="L16R4", row_ptr=rp, col_idx=ci, values=vals, B=np.full_like(B4, 0x77)))
+
+
+def test_l12_values_are_range_checked():
+    from paper_2209_06979_amd import binding as mc
+    c = wl.spmm_case(16, 64, 32, 8, 0.5, "L12R4", 2501)
+    bad = c["values"].copy()
+    bad[0, 0] = -2049
+    with pytest.raises(mc.MagicubeError) as e:
+        mc.SparseMatrix(c["M"], c["K"], c["V"], c["row_ptr"], c["col_idx"], bad, 12)
+    assert e.value.status == mc.MC_ERANGE
+    A = mc.SparseMatrix(c["M"], c["K"], c["V"], c["row_ptr"], c["col_idx"], c["values"], 12)
+    import torch
+    B = torch.from_numpy(c["B"]).cuda()
+    with pytest.raises(mc.MagicubeError):      # a 12-bit matrix is not a 16-bit one
+        mc.spmm(A, B, "L16R4")
+    A.close()
+
+
+@pytest.mark.parametrize("prec", WIDE)
+def test_spmm_full_size_4096(prec):
+    _spmm(wl.spmm_case(4096, 4096, 256, 8, 0.9, prec, wl.seed_for(4, 7)))
+
+
+def test_set_values_device_16bit_then_l16r16():
+    import torch
+    import oracle
+    from paper_2209_06979_amd import binding as mc
+    c = wl.spmm_case(64, 512, 64, 8, 0.6, "L16R16", 2601)
+    A = mc.SparseMatrix(c["M"], c["K"], c["V"], c["row_ptr"], c["col_idx"], np.zeros_like(c["values"]), 16)
+    A.set_values(torch.from_numpy(c["values"]).cuda())
+    got = mc.spmm(A, torch.from_numpy(c["B"]).cuda(), "L16R16").cpu().numpy()
+    A.close()
+    assert np.array_equal(got, oracle.spmm(c["M"], c["K"], c["V"], c["row_ptr"], c["col_idx"], c["values"], c["B"], "L16R16"))
+
+
+# -------------------------------------------------------------------- SDDMM ----
+@pytest.mark.parametrize("V", [2, 4, 8])
+@pytest.mark.parametrize("Kd", [32, 64, 128, 256])
+def test_sddmm_l16r16_small(V, Kd):
+    _sddmm(wl.sddmm_case(16 * V, 300, Kd, V, 0.7, "L16R16", 3000 + V + Kd), variants=(-1, 0, 1, 2, 4, 8))
+
+
+@pytest.mark.parametrize("Kd", [8, 24, 72, 200, 520])
+def test_sddmm_l16r16_odd_reduction_lengths(Kd):
+    _sddmm(wl.sddmm_case(64, 200, Kd, 8, 0.5, "L16R16", 3100 + Kd))
+
+
+def test_sddmm_l16r16_ragged_and_extreme_values():
+    V, Nc, Kd = 8, 500, 64
+    counts = [0, 1, 15, 16, 17, 63, 64, 65, 0, 129, 500, 3]
+    M = V * len(counts)
+    rp, ci = wl.ragged_pattern(M, Nc, V, counts, 3201)
+    Q = wl.uniform_int16((M, Kd), 3202)
+    Km = wl.uniform_int16((Nc, Kd), 3203, -16, 15)
+    # one extreme element per row: the products stay below 2**30 + small
+    Q[:, 5] = np.where(np.arange(M) % 2 == 0, -32768, 32639)
+    Km[:, 5] = np.where(np.arange(Nc) % 3 == 0, 32639, -32768)
+    _sddmm(dict(M=M, Nc=Nc, Kd=Kd, V=V, prec="L16R16", row_ptr=rp, col_idx=ci, Q=Q, Kmat=Km), variants=(-1, 0, 2, 8))
+
+
+@pytest.mark.parametrize("Kd,s", [(64, 0.9), (256, 0.9), (128, 0.7)])
+def test_sddmm_l16r16_full_size_4096(Kd, s):
+    _sddmm(wl.sddmm_case(4096, 4096, Kd, 8, s, "L16R16", wl.seed_for(3, 500 + Kd)))
