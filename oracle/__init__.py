@@ -249,11 +249,13 @@ def split_balanced(a, low_bits: int):
 # --------------------------------------------------------------------------- #
 # Quantized sparse attention (Section 5.3)                                     #
 # --------------------------------------------------------------------------- #
-def quantize_per_tensor(x):
-    """Symmetric int8 quantisation with one scale: s = max|x|/127, q = rint(x/s)."""
+def quantize_per_tensor(x, bits: int = 8):
+    """Symmetric quantisation with one scale: qmax = 2**(bits-1) - 1, s = max|x|/qmax,
+    q = rint(x/s) in [-qmax, qmax] (returned as int8, one value per element, not packed)."""
     x = np.asarray(x, dtype=np.float64)
-    s = np.float32(np.max(np.abs(x)) / 127.0)
-    q = np.clip(np.rint(x / np.float64(s)), -127, 127).astype(np.int8)
+    qmax = (1 << (bits - 1)) - 1
+    s = np.float32(np.max(np.abs(x)) / qmax)
+    q = np.clip(np.rint(x / np.float64(s)), -qmax, qmax).astype(np.int8)
     return q, s
 
 
@@ -277,20 +279,33 @@ def sparse_softmax(S, row_ptr, V: int, scale: float) -> np.ndarray:
     return out
 
 
-def requantize_probabilities(p, s_p: float) -> np.ndarray:
-    """int8 codes of softmax outputs: clamp(rint(p / s_p), 0, 127), ties to even."""
-    return np.clip(np.rint(np.asarray(p, dtype=np.float64) / np.float64(s_p)), 0, 127).astype(np.int8)
+# Largest code of the re-quantised softmax output.  8 bits: the int8 maximum.  16 bits: the
+# largest value whose split into two SIGNED bytes (hi = (c + 128) >> 8) still fits, which is
+# what a signed x signed matrix unit can take as a two-plane operand.
+P_CODE_MAX = {8: 127, 16: 32639}
 
 
-def attention(Q8, K8, V8, row_ptr, col_idx, V: int, s_q, s_k, s_v, s_p):
+def requantize_probabilities(p, s_p: float, bits: int = 8) -> np.ndarray:
+    """Integer codes of softmax outputs: clamp(rint(p / s_p), 0, P_CODE_MAX[bits]), ties to even."""
+    q = np.clip(np.rint(np.asarray(p, dtype=np.float64) / np.float64(s_p)), 0, P_CODE_MAX[bits])
+    return q.astype(np.int8 if bits == 8 else np.int16)
+
+
+def attention(Q8, K8, V8, row_ptr, col_idx, V: int, s_q, s_k, s_v, s_p, p_bits: int = 8, qkv_bits: int = 8):
     """Quantized self-attention with a vector-sparse mask shared by all heads.
 
-    Q8, K8, V8: (heads, L, dk) int8.  Per head: int8 SDDMM(Q, K^T) at the mask ->
-    dequantise with s_q*s_k/sqrt(dk) -> softmax over the stored entries -> int8
-    re-quantisation with the static scale s_p -> int8 SpMM with V -> scale s_p*s_v.
-    Returns (O fp64 (heads, L, dk), scores int32, probabilities fp64, codes int8),
+    Q8, K8, V8: (heads, L, dk) int8, or for qkv_bits=4 (heads, L, dk/2) bytes with two
+    4-bit values each.  Per head: integer SDDMM(Q, K^T) at the mask -> dequantise with
+    s_q*s_k/sqrt(dk) -> softmax over the stored entries -> re-quantisation to p_bits-bit
+    codes with the static scale s_p -> integer SpMM with V -> scale s_p*s_v.  The paper's
+    "xb-yb" variants (Section 5.3 / end-to-end latency figure) are p_bits=x, qkv_bits=y.
+    Returns (O fp64 (heads, L, dk), scores int32, probabilities fp64, integer codes),
     the last three as (heads, nvec*V) in SDDMM output order.
     """
+    if qkv_bits == 4:
+        Q8, K8, V8 = (unpack_int4(np.asarray(t).view(np.uint8)) for t in (Q8, K8, V8))
+    elif qkv_bits != 8:
+        raise ValueError("qkv_bits must be 4 or 8")
     Q8 = np.asarray(Q8)
     heads, L, dk = Q8.shape
     flags = stored_flags(L, L, V, row_ptr, col_idx)
@@ -299,11 +314,11 @@ def attention(Q8, K8, V8, row_ptr, col_idx, V: int, s_q, s_k, s_v, s_p):
     O = np.empty((heads, L, dk), dtype=np.float64)
     scores = np.empty((heads, nvec * V), dtype=np.int32)
     probs = np.empty((heads, nvec * V), dtype=np.float64)
-    codes = np.empty((heads, nvec * V), dtype=np.int8)
+    codes = np.empty((heads, nvec * V), dtype=np.int8 if p_bits == 8 else np.int16)
     for h in range(heads):
         scores[h] = sddmm_dense(Q8[h].astype(np.int32), np.asarray(K8[h]).astype(np.int32), flags, V)
         probs[h] = sparse_softmax(scores[h], row_ptr, V, scale)
-        codes[h] = requantize_probabilities(probs[h], s_p)
+        codes[h] = requantize_probabilities(probs[h], s_p, p_bits)
         A, _ = bcrs_to_dense(L, L, V, row_ptr, col_idx, codes[h].reshape(nvec, V))
         C = spmm_dense(A, flags, np.asarray(V8[h]).astype(np.int32), V)
         O[h] = C.astype(np.float64) * (np.float64(np.float32(s_p)) * np.float64(np.float32(s_v)))

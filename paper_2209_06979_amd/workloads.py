@@ -145,3 +145,13 @@ def quantize_inputs_int8(x: np.ndarray):
     s = np.float32(np.max(np.abs(x.astype(np.float64))) / 127.0)
     q = np.clip(np.rint(x.astype(np.float64) / np.float64(s)), -127, 127).astype(np.int8)
     return q, s
+
+
+def quantize_inputs_int4(x: np.ndarray):
+    """As quantize_inputs_int8 with 4-bit codes: s = max|x| / 7, codes in [-7, 7], packed two
+    per byte along the last axis (element 2j in bits 3:0, element 2j+1 in bits 7:4).
+    Returns (packed uint8 array with half the last dimension, fp32 scale)."""
+    s = np.float32(np.max(np.abs(x.astype(np.float64))) / 7.0)
+    q = np.clip(np.rint(x.astype(np.float64) / np.float64(s)), -7, 7).astype(np.int64)
+    packed = (q[..., 0::2] & 15) | ((q[..., 1::2] & 15) << 4)
+    return packed.astype(np.uint8), s

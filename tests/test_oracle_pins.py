@@ -384,6 +384,56 @@ def test_attention_against_dense_torch_reference():
         assert np.max(np.abs(O[h] - ref.numpy())) < 0.15
 
 
+def test_requantize_16_bit_codes():
+    q = oracle.requantize_probabilities(np.array([0.0, 1.0, 2.0, 100.4 / 32639, 100.6 / 32639]), 1 / 32639, 16)
+    assert q.dtype == np.int16 and q.tolist() == [0, 32639, 32639, 100, 101]
+    lo, hi = oracle.split_balanced(np.array([32639]), 8)      # the largest code still splits into signed bytes
+    assert hi[0] == 127 and lo[0] == 127
+    lo, hi = oracle.split_balanced(np.array([32640]), 8)
+    assert hi[0] == 128                                        # ... and the next one does not
+
+
+@pytest.mark.parametrize("p_bits,qkv_bits", [(16, 8), (8, 4)])
+def test_attention_variants_against_dense_torch_reference(p_bits, qkv_bits):
+    """The 16b-8b and 8b-4b variants of the layer, by the dense masked route in torch."""
+    heads, L, dk, V = 2, 64, 16, 8
+    c = wl.attention_case(heads, L, dk, V, 0.75, 901)
+    if qkv_bits == 4:
+        (q, s_q), (k, s_k), (v, s_v) = (wl.quantize_inputs_int4(c[n]) for n in "qkv")
+        # unpack by an independent formula: sign-extend nibbles with int8 shifts
+        def widen(p):
+            lo = (np.left_shift(p, 4).astype(np.uint8).view(np.int8) >> 4)
+            hi = (p.view(np.int8) >> 4)
+            return np.stack([lo, hi], axis=-1).reshape(p.shape[:-1] + (-1,)).astype(np.int8)
+        qi, ki, vi = widen(q), widen(k), widen(v)
+        for t, (tq, ts) in zip("qkv", ((qi, s_q), (ki, s_k), (vi, s_v))):
+            oq, os_ = oracle.quantize_per_tensor(c[t], 4)
+            assert os_ == ts and np.array_equal(oq, tq) and np.abs(tq).max() == 7
+    else:
+        (q, s_q), (k, s_k), (v, s_v) = (wl.quantize_inputs_int8(c[n]) for n in "qkv")
+        qi, ki, vi = q, k, v
+    pmax = {8: 127, 16: 32639}[p_bits]
+    s_p = np.float32(1.0 / pmax)
+    O, scores, probs, codes = oracle.attention(q, k, v, c["row_ptr"], c["col_idx"], V, s_q, s_k, s_v, s_p,
+                                               p_bits=p_bits, qkv_bits=qkv_bits)
+    assert codes.dtype == (np.int8 if p_bits == 8 else np.int16) and codes.max() <= pmax and codes.min() >= 0
+    flags = oracle.stored_flags(L, L, V, c["row_ptr"], c["col_idx"])
+    keep = torch.from_numpy(np.repeat(flags, V, axis=0).astype(bool))
+    for h in range(heads):
+        Sd = torch.from_numpy(qi[h]).double() @ torch.from_numpy(ki[h]).double().T
+        x = (Sd * (float(s_q) * float(s_k) / np.sqrt(dk))).masked_fill(~keep, float("-inf"))
+        Pq = torch.clamp(torch.round(torch.softmax(x, dim=1) / float(s_p)), 0, pmax)
+        Od = (Pq @ torch.from_numpy(vi[h]).double()) * (float(s_p) * float(s_v))
+        assert np.allclose(O[h], Od.numpy(), rtol=0, atol=1e-12)
+    if p_bits == 16:   # finer codes: closer to the layer with unquantised probabilities than the 8-bit codes are
+        O8 = oracle.attention(q, k, v, c["row_ptr"], c["col_idx"], V, s_q, s_k, s_v, np.float32(1 / 127))[0]
+        for h in range(heads):
+            Sd = torch.from_numpy(qi[h]).double() @ torch.from_numpy(ki[h]).double().T
+            x = (Sd * (float(s_q) * float(s_k) / np.sqrt(dk))).masked_fill(~keep, float("-inf"))
+            ref = (torch.softmax(x, dim=1) @ torch.from_numpy(vi[h]).double()).numpy() * float(s_v)
+            assert np.abs(O[h] - ref).max() < 0.05 * np.abs(O8[h] - ref).max()
+
+
 # ------------------------------------------------------------ generators ----
 def test_generators_are_seeded_and_exact():
     rp, ci = wl.vector_sparse_pattern(64, 512, 8, 0.8, wl.seed_for(1))
