@@ -168,6 +168,11 @@ int mc_sddmm(const void *Q_dev, int ldq, const void *Kmat_dev, int ldk, int Kd, 
  * ---------------------------------------------------------------------------------- */
 int mc_sparse_softmax(const mc_mat *mask, int batch, const int32_t *S_dev, float score_scale,
                       float inv_s_p, int8_t *codes_dev, void *stream);
+/* The same with code_bits = 8 (int8 codes, as above) or 16: int16 codes clamped to
+ * [0, 32639], the largest value that still splits into two signed bytes (Section 4.4) and
+ * can therefore feed a 16-bit SpMM operand.  Other widths: MC_EUNSUPPORTED. */
+int mc_sparse_softmax_bits(const mc_mat *mask, int batch, const int32_t *S_dev, float score_scale,
+                           float inv_s_p, int code_bits, void *codes_dev, void *stream);
 
 /* ------------------------------------------------------------------------------------
  * Quantized sparse self-attention layer (Section 5.3), one mask shared by all heads:
@@ -196,6 +201,21 @@ int mc_sparse_attention_strided(const int8_t *Q_dev, const int8_t *Km_dev, const
 int mc_sparse_attention(const int8_t *Q_dev, const int8_t *Km_dev, const int8_t *Vm_dev, int heads, int L,
                         int dk, const mc_mat *mask, float s_q, float s_k, float s_v, float s_p,
                         float *O_dev, void *workspace_dev, size_t workspace_bytes, void *stream);
+
+/* The "xb-yb" variants of the layer (Section 5.3 and the end-to-end latency figure): the
+ * softmax output is quantised to p_bits = x (8 or 16; 16-bit codes are clamped to 32639 and
+ * multiplied as two signed byte planes) and Q, Km, Vm hold qkv_bits = y bit integers (8, or 4
+ * packed two per byte along dk).  Strides are in ELEMENTS for all four tensors and must make
+ * whole 16-byte pieces (multiples of 16 for 8-bit, of 32 for 4-bit inputs); dk likewise.
+ * p_bits = 8, qkv_bits = 8 is mc_sparse_attention_strided.  The other combinations run the
+ * four-kernel pipeline SDDMM -> softmax -> repack -> SpMM and need
+ * mc_attention_workspace_bytes_bits(heads, mask, p_bits) bytes of workspace.
+ * Unsupported widths: MC_EUNSUPPORTED. */
+size_t mc_attention_workspace_bytes_bits(int heads, const mc_mat *mask, int p_bits);
+int mc_sparse_attention_bits(const void *Q_dev, const void *Km_dev, const void *Vm_dev, int heads, int L, int dk,
+                             int64_t head_stride, int64_t token_stride, const mc_mat *mask, int p_bits,
+                             int qkv_bits, float s_q, float s_k, float s_v, float s_p, float *O_dev,
+                             void *workspace_dev, size_t workspace_bytes, void *stream);
 
 /* ------------------------------------------------------------------------------------
  * Tuning knob (not needed for correctness): selects the SpMM tile variant.

@@ -66,11 +66,18 @@ def _load() -> ctypes.CDLL:
     L.mc_sparse_attention_strided.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int64, c_int64,
                                               c_void_p, c_float, c_float, c_float, c_float, c_void_p, c_void_p,
                                               c_size_t, c_void_p]
+    L.mc_sparse_softmax_bits.argtypes = [c_void_p, c_int, c_void_p, c_float, c_float, c_int, c_void_p, c_void_p]
+    L.mc_attention_workspace_bytes_bits.argtypes = [c_int, c_void_p, c_int]
+    L.mc_attention_workspace_bytes_bits.restype = c_size_t
+    L.mc_sparse_attention_bits.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int64, c_int64,
+                                           c_void_p, c_int, c_int, c_float, c_float, c_float, c_float, c_void_p,
+                                           c_void_p, c_size_t, c_void_p]
     L.mc_set_spmm_variant.argtypes = [c_int, c_int]
     L.mc_set_attention_mode.argtypes = [c_int]
     L.mc_set_sddmm_variant.argtypes = [c_int]
     for name in ("mc_layout_query", "mc_pack_host", "mc_unpack_host", "mc_mat_create", "mc_mat_set_values_device",
-                 "mc_mat_info", "mc_spmm", "mc_sddmm", "mc_sparse_softmax", "mc_sparse_attention", "mc_sparse_attention_strided",
+                 "mc_mat_info", "mc_spmm", "mc_sddmm", "mc_sparse_softmax", "mc_sparse_softmax_bits", "mc_sparse_attention",
+                 "mc_sparse_attention_strided", "mc_sparse_attention_bits",
                  "mc_set_spmm_variant", "mc_set_attention_mode", "mc_set_sddmm_variant"):
         getattr(L, name).restype = c_int
     return L
@@ -217,47 +224,56 @@ def sddmm(Q, Kmat, mask: SparseMatrix, prec: str, out=None):
     return out
 
 
-def sparse_softmax(mask: SparseMatrix, S, score_scale: float, inv_s_p: float, out=None):
-    """int8 codes of the row softmax over the stored entries; S: (batch, nvec*V) int32."""
+def sparse_softmax(mask: SparseMatrix, S, score_scale: float, inv_s_p: float, out=None, code_bits: int = 8):
+    """Integer codes (int8, or int16 for code_bits=16) of the row softmax over the stored
+    entries; S: (batch, nvec*V) int32."""
     assert S.is_cuda and S.dtype == torch.int32 and S.is_contiguous()
     S2 = S.reshape(-1, mask.nvec * mask.V)
+    dt = torch.int16 if code_bits == 16 else torch.int8
     if out is None:
-        out = torch.empty(S2.shape, dtype=torch.int8, device=S.device)
-    assert out.is_cuda and out.dtype == torch.int8 and out.is_contiguous() and out.numel() == S2.numel()
-    _check(lib.mc_sparse_softmax(mask.handle, S2.shape[0], S2.data_ptr(), score_scale, inv_s_p, out.data_ptr(),
-                                 _stream()), "mc_sparse_softmax")
+        out = torch.empty(S2.shape, dtype=dt, device=S.device)
+    assert out.is_cuda and out.dtype == dt and out.is_contiguous() and out.numel() == S2.numel()
+    _check(lib.mc_sparse_softmax_bits(mask.handle, S2.shape[0], S2.data_ptr(), score_scale, inv_s_p, code_bits,
+                                      out.data_ptr(), _stream()), "mc_sparse_softmax_bits")
     return out.reshape(S.shape)
 
 
-def attention_workspace_bytes(heads: int, mask: SparseMatrix) -> int:
-    return int(lib.mc_attention_workspace_bytes(heads, mask.handle))
+def attention_workspace_bytes(heads: int, mask: SparseMatrix, p_bits: int = 8) -> int:
+    return int(lib.mc_attention_workspace_bytes_bits(heads, mask.handle, p_bits))
 
 
-def sparse_attention(Q8, K8, V8, mask: SparseMatrix, s_q, s_k, s_v, s_p, out=None, workspace=None):
-    """Quantized sparse self-attention; Q8/K8/V8: (heads, L, dk) int8 device tensors.
+def sparse_attention(Q8, K8, V8, mask: SparseMatrix, s_q, s_k, s_v, s_p, out=None, workspace=None,
+                     p_bits: int = 8, qkv_bits: int = 8):
+    """Quantized sparse self-attention; Q8/K8/V8: (heads, L, dk) int8 device tensors, or for
+    qkv_bits=4 (heads, L, dk/2) uint8 tensors with two 4-bit values per byte.  p_bits is the
+    width of the re-quantised softmax output (8 or 16).
 
     Any layout with unit stride along dk is accepted as long as the three tensors (and
     ``out``) share it; a (heads, L, dk) view of a token-major (L, heads, dk) buffer, i.e.
     ``x.permute(1, 0, 2)``, selects the fast two-heads-per-request path.
     """
-    heads, L, dk = Q8.shape
-    hs, ts = Q8.stride(0), Q8.stride(1)
+    epb = 8 // qkv_bits                       # elements per byte
+    heads, L, dkb = Q8.shape
+    dk = dkb * epb
+    hs, ts = Q8.stride(0) * epb, Q8.stride(1) * epb   # strides in elements
     for t in (Q8, K8, V8):
-        assert t.is_cuda and t.dtype == torch.int8 and t.shape == Q8.shape and t.stride() == (hs, ts, 1)
+        assert t.is_cuda and t.element_size() == 1 and t.shape == Q8.shape and t.stride() == Q8.stride() and t.stride(2) == 1
     if out is None:
-        # same layout as the inputs
-        if hs < ts:
+        # same layout as the inputs (the two dense ones; anything else needs an explicit ``out``)
+        if (hs, ts) == (dk, heads * dk):
             out = torch.empty((L, heads, dk), dtype=torch.float32, device=Q8.device).permute(1, 0, 2)
-        else:
+        elif (hs, ts) == (L * dk, dk):
             out = torch.empty((heads, L, dk), dtype=torch.float32, device=Q8.device)
-    assert out.is_cuda and out.dtype == torch.float32 and out.shape == Q8.shape and out.stride() == (hs, ts, 1)
-    need = attention_workspace_bytes(heads, mask)
+        else:
+            raise MagicubeError(MC_EINVAL, "sparse_attention(out is required for this layout)")
+    assert out.is_cuda and out.dtype == torch.float32 and out.shape == (heads, L, dk) and out.stride() == (hs, ts, 1)
+    need = attention_workspace_bytes(heads, mask, p_bits)
     if workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=Q8.device)
     assert workspace.is_cuda and workspace.is_contiguous()
-    _check(lib.mc_sparse_attention_strided(Q8.data_ptr(), K8.data_ptr(), V8.data_ptr(), heads, L, dk, hs, ts,
-                                           mask.handle, float(s_q), float(s_k), float(s_v), float(s_p),
-                                           out.data_ptr(), workspace.data_ptr(),
-                                           workspace.numel() * workspace.element_size(), _stream()),
-           "mc_sparse_attention_strided")
+    _check(lib.mc_sparse_attention_bits(Q8.data_ptr(), K8.data_ptr(), V8.data_ptr(), heads, L, dk, hs, ts,
+                                        mask.handle, p_bits, qkv_bits, float(s_q), float(s_k), float(s_v), float(s_p),
+                                        out.data_ptr(), workspace.data_ptr(),
+                                        workspace.numel() * workspace.element_size(), _stream()),
+           "mc_sparse_attention_bits")
     return out

@@ -275,39 +275,100 @@ extern "C" int mc_sddmm(const void *Q_dev, int ldq, const void *Kmat_dev, int ld
     return MC_OK;
 }
 
-extern "C" int mc_sparse_softmax(const mc_mat *mask, int batch, const int32_t *S_dev, float score_scale,
-                                 float inv_s_p, int8_t *codes_dev, void *stream)
+extern "C" int mc_sparse_softmax_bits(const mc_mat *mask, int batch, const int32_t *S_dev, float score_scale,
+                                      float inv_s_p, int code_bits, void *codes_dev, void *stream)
 {
     if (!mask || !S_dev || !codes_dev || batch <= 0) return MC_EINVAL;
+    if (code_bits != 8 && code_bits != 16) return MC_EUNSUPPORTED;
     if (!std::isfinite(score_scale) || !std::isfinite(inv_s_p)) return MC_EINVAL;
     SoftmaxArgs a;
     a.row_ptr = mask->d_row_ptr; a.S = S_dev; a.codes = codes_dev;
     a.batch_stride = mask->nvec * mask->V;
     a.score_scale = score_scale; a.inv_s_p = inv_s_p;
-    a.P = mask->P; a.V = mask->V; a.batch = batch;
+    a.P = mask->P; a.V = mask->V; a.batch = batch; a.code_bits = code_bits;
     MC_HIP(launch_softmax(a, static_cast<hipStream_t>(stream)));
     return MC_OK;
+}
+
+extern "C" int mc_sparse_softmax(const mc_mat *mask, int batch, const int32_t *S_dev, float score_scale,
+                                 float inv_s_p, int8_t *codes_dev, void *stream)
+{
+    return mc_sparse_softmax_bits(mask, batch, S_dev, score_scale, inv_s_p, 8, codes_dev, stream);
 }
 
 namespace {
 inline size_t round256(size_t x) { return (x + 255) / 256 * 256; }
 struct AttnWs { size_t scores, codes, vals, total; };
-AttnWs attn_layout(int heads, const mc_mat *mask)
+AttnWs attn_layout(int heads, const mc_mat *mask, int p_bits)
 {
     AttnWs w;
-    const size_t nnz = (size_t)mask->nvec * mask->V;
+    const size_t nnz = (size_t)mask->nvec * mask->V, pb = (size_t)p_bits / 8;
     w.scores = 0;
     w.codes = w.scores + round256((size_t)heads * nnz * sizeof(int32_t));
-    w.vals = w.codes + round256((size_t)heads * nnz);
-    w.total = w.vals + round256((size_t)heads * (size_t)mask->nslots * mask->V);
+    w.vals = w.codes + round256((size_t)heads * nnz * pb);
+    w.total = w.vals + round256((size_t)heads * (size_t)mask->nslots * mask->V * pb);
     return w;
+}
+
+// SDDMM -> softmax -> repack -> SpMM, every step a kernel of its own; intermediates in the
+// workspace.  Strides of Q/Km/Vm in bytes, of O in elements.
+int attention_pipeline(const uint8_t *Q, const uint8_t *Km, const uint8_t *Vm, int heads, int dk, int qkv_bits,
+                       int p_bits, int64_t head_stride_bytes, int64_t token_stride_bytes, int64_t o_head_stride,
+                       int64_t o_token_stride, const mc_mat *mask, float s_q, float s_k, float s_v, float s_p,
+                       float *O, void *workspace_dev, hipStream_t s)
+{
+    const AttnWs ws = attn_layout(heads, mask, p_bits);
+    const int64_t nnz = mask->nvec * mask->V;
+    uint8_t *wsb = static_cast<uint8_t *>(workspace_dev);
+    int32_t *scores = reinterpret_cast<int32_t *>(wsb + ws.scores);
+    uint8_t *codes = wsb + ws.codes;
+    uint8_t *pvals = wsb + ws.vals;
+    const int row_bytes = dk * qkv_bits / 8, pb = p_bits / 8;
+
+    SddmmArgs d;
+    d.panel_ptr = mask->d_panel_ptr; d.row_ptr = mask->d_row_ptr; d.slot_idx = mask->d_slot_idx;
+    d.Q = Q; d.ldq_bytes = token_stride_bytes; d.Q_batch_stride = head_stride_bytes;
+    d.Kmat = Km; d.ldk_bytes = token_stride_bytes; d.K_batch_stride = head_stride_bytes;
+    d.row_bytes = row_bytes; d.S = scores; d.S_batch_stride = nnz;
+    d.P = mask->P; d.V = 8; d.batch = heads;
+    MC_HIP(launch_sddmm(qkv_bits, d, choose_sddmm_waves(mask, heads), s));
+
+    SoftmaxArgs f;
+    f.row_ptr = mask->d_row_ptr; f.S = scores; f.codes = codes; f.batch_stride = nnz;
+    f.score_scale = s_q * s_k / std::sqrt((float)dk); f.inv_s_p = 1.f / s_p;
+    f.P = mask->P; f.V = 8; f.batch = heads; f.code_bits = p_bits;
+    MC_HIP(launch_softmax(f, s));
+
+    RepackArgs r;
+    r.panel_ptr = mask->d_panel_ptr; r.row_ptr = mask->d_row_ptr;
+    r.src = codes; r.src_batch_stride = nnz * pb;
+    r.dst = pvals; r.dst_batch_stride = mask->nslots * 8 * pb;
+    r.P = mask->P; r.V = 8; r.bits = p_bits; r.batch = heads;
+    MC_HIP(launch_repack(r, s));
+
+    SpmmArgs m;
+    m.panel_ptr = mask->d_panel_ptr; m.slot_idx = mask->d_slot_idx;
+    m.vals = pvals; m.vals_batch_stride = mask->nslots * 8 * pb;
+    m.B = Vm; m.ldb_bytes = token_stride_bytes; m.B_batch_stride = head_stride_bytes;
+    m.row_bytes = row_bytes; m.C = O; m.ldc = o_token_stride; m.C_batch_stride = o_head_stride;
+    m.P = mask->P; m.V = 8; m.batch = heads; m.float_out = 1; m.out_scale = s_p * s_v;
+    int bnb, waves;
+    choose_variant(mask, m.row_bytes, qkv_bits == 4, heads, &bnb, &waves);
+    const mc_prec prec = (p_bits == 16) ? (qkv_bits == 4 ? MC_L16R4 : MC_L16R8) : (qkv_bits == 4 ? MC_L8R4 : MC_L8R8);
+    MC_HIP(launch_spmm(prec, m, bnb, waves, s));
+    return MC_OK;
 }
 } // namespace
 
+extern "C" size_t mc_attention_workspace_bytes_bits(int heads, const mc_mat *mask, int p_bits)
+{
+    if (!mask || heads <= 0 || (p_bits != 8 && p_bits != 16)) return 0;
+    return attn_layout(heads, mask, p_bits).total;
+}
+
 extern "C" size_t mc_attention_workspace_bytes(int heads, const mc_mat *mask)
 {
-    if (!mask || heads <= 0) return 0;
-    return attn_layout(heads, mask).total;
+    return mc_attention_workspace_bytes_bits(heads, mask, 8);
 }
 
 extern "C" int mc_sparse_attention(const int8_t *Q_dev, const int8_t *Km_dev, const int8_t *Vm_dev, int heads, int L,
@@ -323,26 +384,36 @@ extern "C" int mc_sparse_attention_strided(const int8_t *Q_dev, const int8_t *Km
                                            const mc_mat *mask, float s_q, float s_k, float s_v, float s_p,
                                            float *O_dev, void *workspace_dev, size_t workspace_bytes, void *stream)
 {
+    return mc_sparse_attention_bits(Q_dev, Km_dev, Vm_dev, heads, L, dk, head_stride, token_stride, mask, 8, 8, s_q,
+                                    s_k, s_v, s_p, O_dev, workspace_dev, workspace_bytes, stream);
+}
+
+extern "C" int mc_sparse_attention_bits(const void *Q_dev, const void *Km_dev, const void *Vm_dev, int heads, int L,
+                                        int dk, int64_t head_stride, int64_t token_stride, const mc_mat *mask,
+                                        int p_bits, int qkv_bits, float s_q, float s_k, float s_v, float s_p,
+                                        float *O_dev, void *workspace_dev, size_t workspace_bytes, void *stream)
+{
     if (!Q_dev || !Km_dev || !Vm_dev || !mask || !O_dev || !workspace_dev) return MC_EINVAL;
-    if (heads <= 0 || L <= 0 || dk <= 0 || dk % 16 != 0) return MC_EINVAL;
+    if ((p_bits != 8 && p_bits != 16) || (qkv_bits != 8 && qkv_bits != 4)) return MC_EUNSUPPORTED;
+    const int epp = 128 / qkv_bits; // elements per 16-byte piece
+    if (heads <= 0 || L <= 0 || dk <= 0 || dk % epp != 0) return MC_EINVAL;
     if (mask->M != L || mask->K != L || mask->V != 8) return MC_EINVAL;
     if (!(s_p > 0.f) || !std::isfinite(s_q * s_k * s_v / s_p)) return MC_EINVAL;
     if (token_stride < dk || head_stride < dk) return MC_EINVAL;
     if ((int64_t)(L - 1) * token_stride + (int64_t)(heads - 1) * head_stride + dk > (int64_t)INT32_MAX) return MC_EINVAL;
     if (L > (1 << 24) || token_stride >= (1 << 24)) return MC_EINVAL; // kernels use 24-bit multiplies
-    if (token_stride % 16 != 0 || head_stride % 16 != 0) return MC_EALIGN;
+    if (token_stride % epp != 0 || head_stride % epp != 0) return MC_EALIGN;
     if (!aligned16(Q_dev) || !aligned16(Km_dev) || !aligned16(Vm_dev) || !aligned16(O_dev)) return MC_EALIGN;
     if ((reinterpret_cast<uintptr_t>(workspace_dev) & 255u) != 0) return MC_EALIGN;
-    const AttnWs ws = attn_layout(heads, mask);
-    if (workspace_bytes < ws.total) return MC_ENOMEM;
+    if (workspace_bytes < attn_layout(heads, mask, p_bits).total) return MC_ENOMEM;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const int64_t nnz = mask->nvec * mask->V;
 
-    if (g_attention_mode != 1 && dk == 64 && mask->max_panel_chunks * MC_CHUNK <= attention_fused_max_vectors()) {
+    if (p_bits == 8 && qkv_bits == 8 && g_attention_mode != 1 && dk == 64 &&
+        mask->max_panel_chunks * MC_CHUNK <= attention_fused_max_vectors()) {
         AttnArgs f;
         f.panel_ptr = mask->d_panel_ptr; f.slot_idx = mask->d_slot_idx;
-        f.Q = reinterpret_cast<const uint8_t *>(Q_dev); f.Km = reinterpret_cast<const uint8_t *>(Km_dev);
-        f.Vm = reinterpret_cast<const uint8_t *>(Vm_dev); f.O = O_dev;
+        f.Q = static_cast<const uint8_t *>(Q_dev); f.Km = static_cast<const uint8_t *>(Km_dev);
+        f.Vm = static_cast<const uint8_t *>(Vm_dev); f.O = O_dev;
         f.head_stride = head_stride; f.token_stride = token_stride;
         f.score_scale = s_q * s_k / std::sqrt((float)dk); f.inv_s_p = 1.f / s_p; f.out_scale = s_p * s_v;
         f.P = mask->P; f.heads = heads;
@@ -351,41 +422,8 @@ extern "C" int mc_sparse_attention_strided(const int8_t *Q_dev, const int8_t *Km
         MC_HIP(launch_attention_fused(f, hpg, s));
         return MC_OK;
     }
-
-    uint8_t *wsb = static_cast<uint8_t *>(workspace_dev);
-    int32_t *scores = reinterpret_cast<int32_t *>(wsb + ws.scores);
-    int8_t *codes = reinterpret_cast<int8_t *>(wsb + ws.codes);
-    uint8_t *pvals = wsb + ws.vals;
-
-    SddmmArgs d;
-    d.panel_ptr = mask->d_panel_ptr; d.row_ptr = mask->d_row_ptr; d.slot_idx = mask->d_slot_idx;
-    d.Q = reinterpret_cast<const uint8_t *>(Q_dev); d.ldq_bytes = token_stride; d.Q_batch_stride = head_stride;
-    d.Kmat = reinterpret_cast<const uint8_t *>(Km_dev); d.ldk_bytes = token_stride; d.K_batch_stride = head_stride;
-    d.row_bytes = dk; d.S = scores; d.S_batch_stride = nnz;
-    d.P = mask->P; d.V = 8; d.batch = heads;
-    MC_HIP(launch_sddmm(8, d, choose_sddmm_waves(mask, heads), s));
-
-    SoftmaxArgs f;
-    f.row_ptr = mask->d_row_ptr; f.S = scores; f.codes = codes; f.batch_stride = nnz;
-    f.score_scale = s_q * s_k / std::sqrt((float)dk); f.inv_s_p = 1.f / s_p;
-    f.P = mask->P; f.V = 8; f.batch = heads;
-    MC_HIP(launch_softmax(f, s));
-
-    RepackArgs r;
-    r.panel_ptr = mask->d_panel_ptr; r.row_ptr = mask->d_row_ptr;
-    r.src = reinterpret_cast<const uint8_t *>(codes); r.src_batch_stride = nnz;
-    r.dst = pvals; r.dst_batch_stride = mask->nslots * 8;
-    r.P = mask->P; r.V = 8; r.bits = 8; r.batch = heads;
-    MC_HIP(launch_repack(r, s));
-
-    SpmmArgs m;
-    m.panel_ptr = mask->d_panel_ptr; m.slot_idx = mask->d_slot_idx;
-    m.vals = pvals; m.vals_batch_stride = mask->nslots * 8;
-    m.B = reinterpret_cast<const uint8_t *>(Vm_dev); m.ldb_bytes = token_stride; m.B_batch_stride = head_stride;
-    m.row_bytes = dk; m.C = O_dev; m.ldc = token_stride; m.C_batch_stride = head_stride;
-    m.P = mask->P; m.V = 8; m.batch = heads; m.float_out = 1; m.out_scale = s_p * s_v;
-    int bnb, waves;
-    choose_variant(mask, m.row_bytes, false, heads, &bnb, &waves);
-    MC_HIP(launch_spmm(MC_L8R8, m, bnb, waves, s));
-    return MC_OK;
+    return attention_pipeline(static_cast<const uint8_t *>(Q_dev), static_cast<const uint8_t *>(Km_dev),
+                              static_cast<const uint8_t *>(Vm_dev), heads, dk, qkv_bits, p_bits,
+                              head_stride * qkv_bits / 8, token_stride * qkv_bits / 8, head_stride, token_stride, mask,
+                              s_q, s_k, s_v, s_p, O_dev, workspace_dev, s);
 }

@@ -52,10 +52,10 @@ struct SddmmArgs {
 struct SoftmaxArgs {
     const int32_t *row_ptr;
     const int32_t *S;
-    int8_t *codes;
+    void *codes;               // int8 (code_bits 8) or int16 (code_bits 16)
     int64_t batch_stride;      // elements (nvec * V)
     float score_scale, inv_s_p;
-    int P, V, batch;
+    int P, V, batch, code_bits;
 };
 
 struct RepackArgs {

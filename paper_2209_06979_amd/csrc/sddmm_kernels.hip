@@ -284,11 +284,13 @@ __global__ __launch_bounds__(256) void softmax_kernel(SoftmaxArgs a)
     sum = 0.f;
     for (int t = v; t < 256; t += V) sum += red[t];
 
-    int8_t *codes = a.codes + base;
     const float rinv = a.inv_s_p / sum; // p / s_p = e * (1 / (sum * s_p)): one division per row
+    // largest code: int8 maximum, or the largest 16-bit value that splits into two signed bytes
+    const float qmax = (a.code_bits == 16) ? 32639.f : 127.f;
     for (int e = tid; e < cnt; e += 256) {
-        const float q = fminf(fmaxf(rintf(__builtin_amdgcn_exp2f((float)S[e] * scale2 - m) * rinv), 0.f), 127.f);
-        codes[e] = (int8_t)(int)q;
+        const float q = fminf(fmaxf(rintf(__builtin_amdgcn_exp2f((float)S[e] * scale2 - m) * rinv), 0.f), qmax);
+        if (a.code_bits == 16) static_cast<int16_t *>(a.codes)[base + e] = (int16_t)(int)q;
+        else static_cast<int8_t *>(a.codes)[base + e] = (int8_t)(int)q;
     }
 }
 

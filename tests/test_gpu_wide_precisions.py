@@ -158,3 +158,87 @@ def test_sddmm_l16r16_ragged_and_extreme_values():
 @pytest.mark.parametrize("Kd,s", [(64, 0.9), (256, 0.9), (128, 0.7)])
 def test_sddmm_l16r16_full_size_4096(Kd, s):
     _sddmm(wl.sddmm_case(4096, 4096, Kd, 8, s, "L16R16", wl.seed_for(3, 500 + Kd)))
+
+
+# ------------------------------------------------- attention "xb-yb" variants ----
+def _attention_variant_check(heads, L, dk, sparsity, seed, p_bits, qkv_bits, token_major=False):
+    """The layer with p_bits-bit softmax codes and qkv_bits-bit Q/K/V against the oracle, with the
+    same tie protocol as the 8b-8b layer: 1e-3, plus one code step for every entry whose
+    re-quantisation sits on a rounding boundary within fp32 accuracy."""
+    import torch
+    import oracle
+    from paper_2209_06979_amd import binding as mc
+    from test_gpu_sddmm import _tie_ambiguous, _layout
+    V = 8
+    c = wl.attention_case(heads, L, dk, V, sparsity, seed)
+    quant = wl.quantize_inputs_int4 if qkv_bits == 4 else wl.quantize_inputs_int8
+    (q, s_q), (k, s_k), (v, s_v) = (quant(c[n]) for n in "qkv")
+    s_p = np.float32(1.0 / oracle.P_CODE_MAX[p_bits])
+    vmax = 7 if qkv_bits == 4 else 127
+    print(f"attention {p_bits}b-{qkv_bits}b heads={heads} L={L} dk={dk} s={sparsity} token_major={token_major}", flush=True)
+    mask = mc.SparseMatrix(L, L, V, c["row_ptr"], c["col_idx"])
+    out = _layout(np.full((heads, L, dk), np.nan, np.float32), token_major)
+    O = mc.sparse_attention(_layout(q, token_major), _layout(k, token_major), _layout(v, token_major), mask,
+                            s_q, s_k, s_v, s_p, out=out, p_bits=p_bits, qkv_bits=qkv_bits)
+    torch.cuda.synchronize()
+    O = O.cpu().numpy().astype(np.float64)
+    mask.close()
+    want, scores, probs, codes = oracle.attention(q, k, v, c["row_ptr"], c["col_idx"], V, s_q, s_k, s_v, s_p,
+                                                  p_bits=p_bits, qkv_bits=qkv_bits)
+    amb = _tie_ambiguous(probs, s_p).reshape(heads, -1, V)
+    rp = c["row_ptr"]
+    n_amb_rows = np.zeros((heads, L), np.int64)
+    for p in range(L // V):
+        n_amb_rows[:, p * V:(p + 1) * V] = amb[:, rp[p]:rp[p + 1], :].sum(axis=1)
+    tol = 1e-3 + n_amb_rows[:, :, None] * float(s_p) * float(s_v) * vmax
+    err = np.abs(O - want)
+    assert (err <= tol).all(), f"max err {err.max()} (ambiguous entries: {int(amb.sum())})"
+    clean = n_amb_rows == 0
+    if p_bits == 8:
+        assert clean.mean() > 0.9
+    else:
+        # a 16-bit code step is worth s_p * s_v * 127 ~ 1e-7 .. 1e-6 of output: many rows hold an entry
+        # near a rounding boundary, but the plain bound must then hold without any allowance
+        assert err.max() < 1e-3
+    print(f"  max abs err {err.max():.3e}; clean rows {clean.mean():.3f} max err {err[clean].max():.3e}", flush=True)
+
+
+@pytest.mark.parametrize("p_bits,qkv_bits", [(16, 8), (8, 4), (16, 4)])
+@pytest.mark.parametrize("token_major", [False, True])
+def test_attention_variants_small(p_bits, qkv_bits, token_major):
+    _attention_variant_check(2, 256, 64, 0.75, 4000, p_bits, qkv_bits, token_major)
+    _attention_variant_check(3, 512, 32, 0.9, 4001, p_bits, qkv_bits, token_major)
+    _attention_variant_check(2, 1024, 64, 0.6, 4002, p_bits, qkv_bits, token_major)
+    _attention_variant_check(1, 2048, 128, 0.7, 4003, p_bits, qkv_bits, token_major)
+
+
+@pytest.mark.parametrize("p_bits,qkv_bits", [(16, 8), (8, 4)])
+def test_attention_variants_config5_shape(p_bits, qkv_bits):
+    """The 16b-8b and 8b-4b variants at 8 heads, L=4096, dk=64, 90 % vector sparsity."""
+    _attention_variant_check(8, 4096, 64, 0.9, wl.seed_for(5, 1), p_bits, qkv_bits)
+
+
+def test_sparse_softmax_16_bit_codes():
+    import torch
+    import oracle
+    from paper_2209_06979_amd import binding as mc
+    from test_gpu_sddmm import _tie_ambiguous
+    V, L = 8, 512
+    rp, ci = wl.ragged_pattern(L, L, V, np.r_[[1, 2, 0, 64, 300], np.full(L // V - 5, 51)], 4101)
+    nnz = len(ci) * V
+    S = np.random.default_rng(4102).integers(-60000, 60000, size=(3, nnz)).astype(np.int32)
+    scale = np.float32(2.5e-4)
+    mask = mc.SparseMatrix(L, L, V, rp, ci)
+    codes = mc.sparse_softmax(mask, torch.from_numpy(S).cuda(), float(scale), 32639.0, code_bits=16)
+    torch.cuda.synchronize()
+    codes = codes.cpu().numpy()
+    assert codes.dtype == np.int16 and codes.max() == 32639     # the single-entry rows: p = 1
+    for b in range(3):
+        p = oracle.sparse_softmax(S[b], rp, V, scale)
+        want = oracle.requantize_probabilities(p, 1 / 32639, 16)
+        amb = _tie_ambiguous(p, 1 / 32639)
+        diff = codes[b].astype(np.int32) - want.astype(np.int32)
+        assert (diff[~amb] == 0).all(), f"{np.count_nonzero(diff[~amb])} code mismatches away from ties"
+        assert (np.abs(diff[amb]) <= 1).all()
+        assert amb.mean() < 0.05
+    mask.close()
