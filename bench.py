@@ -86,6 +86,9 @@ def main():
     ap.add_argument("--attention-layout", choices=["token", "head"], default="head",
                     help="Q/K/V buffers token-major (L, heads, dk) as a projection writes them, or head-major (heads, L, dk)")
     ap.add_argument("--no-per-kernel", action="store_true", help="skip the per-kernel timing runs (counter collection)")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the measurements beside the step: cold-cache and gather-only timings of the headline "
+                         "SpMM and the wider precisions that are not part of the step")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 64 MiB device copy, the known-size kernel that scales FETCH_SIZE / WRITE_SIZE")
     args = ap.parse_args()
@@ -213,6 +216,7 @@ def main():
                 samples.append(e0.elapsed_time(e1) * 1e3 / args.reps)   # microseconds per launch
             k["us"] = float(np.median(samples))
             del g
+        extras = None if (args.no_extras or args.only) else measure_extras(mc, torch, prob, stream, args.reps, up)
     ms_per_step = elapsed / args.steps * 1e3
     total_ops = sum(k["ops"] for k in kernels)
     value = total_ops / (elapsed / args.steps) / 1e12
@@ -243,13 +247,106 @@ def main():
         "config": {"workload": "4096x4096 V=8 s=0.9: SpMM L8-R8/L8-R4/L4-R4/L16-R8 N=256 + SDDMM L8-R8/L4-R4 K=256 "
                                "+ sparse attention 8 heads L=4096 dk=64",
                    "launch": "eager" if args.eager else f"hip_graph x{spg} steps", "kernels_in_step": [k["name"] for k in kernels]},
-        "headline_spmm_l8r8": per_kernel.get("spmm_L8R8"),
+        "headline_spmm_l8r8": dict(per_kernel.get("spmm_L8R8") or {}, **((extras or {}).get("headline") or {})),
+        "beyond_the_step": (extras or {}).get("wider_precisions"),
         "per_kernel": per_kernel,
         "format_build_s": round(format_build_s, 3),
         "roofline": roofline,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))
+
+
+def time_graph(torch, stream, launches, rounds=5):
+    """Microseconds per launch: the launches captured once into a HIP graph, replayed between two
+    events on the launch stream; median over `rounds` replays."""
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=stream):
+        for f in launches:
+            f()
+    g.replay()
+    stream.synchronize()
+    samples = []
+    for _ in range(rounds):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        g.replay()
+        e1.record(stream)
+        e1.synchronize()
+        samples.append(e0.elapsed_time(e1) * 1e3 / len(launches))
+    return float(np.median(samples))
+
+
+def measure_extras(mc, torch, prob, stream, reps, up):
+    """Measurements beside the step (called on the launch stream).
+
+    headline: the L8-R8 SpMM (a) with cold caches -- 80 copies of all its operands (about 620 MB,
+    more than L2 plus the 256 MB memory-side cache) visited in turn, so every launch finds its
+    operands in HBM only; (b) its gather alone (mc_probe_gather, same indices and launch shape).
+    wider_precisions: the emulated precisions and layer variants that are not rows of the step.
+    """
+    from paper_2209_06979_amd import workloads as wl
+    out = {}
+    c = prob["spmm_L8R8"]
+    nsets = 80
+    sets = []
+    for _ in range(nsets):
+        A = mc.SparseMatrix(M, K, V, c["row_ptr"], c["col_idx"], c["values"], 8)
+        sets.append((A, up(c["B"]), torch.empty((M, N_SPMM), dtype=torch.int32, device="cuda")))
+    cold = time_graph(torch, stream, [(lambda A=A, B=B, C=C: mc.spmm(A, B, "L8R8", out=C)) for A, B, C in sets])
+    A, B, C = sets[0]
+    sink = mc.probe_gather(A, B, "L8R8")
+    gather = time_graph(torch, stream, [lambda: mc.probe_gather(A, B, "L8R8", sink=sink)] * reps)
+    warm = time_graph(torch, stream, [lambda: mc.spmm(A, B, "L8R8", out=C)] * reps)
+    nvec = A.nvec
+    alg = spmm_alg_bytes(nvec, M // V, 8, 8, N_SPMM)
+    out["headline"] = dict(cold_us=round(cold, 2), cold_alg_gbs=round(alg / cold / 1e3, 1),
+                           cold_hbm_frac=round(alg / cold / 1e3 / HBM_PEAK_GBS, 4),
+                           gather_only_us=round(gather, 2), time_over_gather_only=round(warm / gather, 2),
+                           gathered_bytes=int(nvec * N_SPMM),
+                           gather_only_tbs=round(nvec * N_SPMM / gather / 1e6, 2))
+    for A, _, _ in sets:
+        A.close()
+    del sets
+
+    wide = {}
+    for i, prec in enumerate(["L16R16", "L16R4", "L12R4"]):
+        cc = wl.spmm_case(M, K, N_SPMM, V, SPARSITY, prec, wl.seed_for(2, 100 + 10 * i))
+        A = mc.SparseMatrix(M, K, V, cc["row_ptr"], cc["col_idx"], cc["values"], mc.LHS_BITS[prec])
+        B = up(cc["B"])
+        C = torch.empty((M, N_SPMM), dtype=torch.int32, device="cuda")
+        us = time_graph(torch, stream, [lambda: mc.spmm(A, B, prec, out=C)] * reps)
+        ops = 2 * A.nvec * V * N_SPMM
+        b = spmm_alg_bytes(A.nvec, M // V, 16, mc.RHS_BITS[prec], N_SPMM)
+        wide["spmm_" + prec] = dict(us=round(us, 2), eff_tops=round(ops / us / 1e6, 1), alg_gbs=round(b / us / 1e3, 1))
+        A.close()
+    cc = wl.sddmm_case(M, K, KD_SDDMM, V, SPARSITY, "L16R16", wl.seed_for(3, 100))
+    mask = mc.SparseMatrix(M, K, V, cc["row_ptr"], cc["col_idx"])
+    Q, Km = up(cc["Q"]), up(cc["Kmat"])
+    S = torch.empty(mask.nvec * V, dtype=torch.int32, device="cuda")
+    us = time_graph(torch, stream, [lambda: mc.sddmm(Q, Km, mask, "L16R16", out=S)] * reps)
+    ops = 2 * mask.nvec * V * KD_SDDMM
+    wide["sddmm_L16R16"] = dict(us=round(us, 2), eff_tops=round(ops / us / 1e6, 1),
+                                alg_gbs=round(sddmm_alg_bytes(mask.nvec, M // V, 16, KD_SDDMM) / us / 1e3, 1))
+    mask.close()
+    att = prob["attention"]
+    amask = mc.SparseMatrix(L_ATT, L_ATT, V, att["row_ptr"], att["col_idx"])
+    O = torch.empty((HEADS, L_ATT, DK), dtype=torch.float32, device="cuda")
+    for name, p_bits, qkv_bits in (("attention_16b8b", 16, 8), ("attention_8b4b", 8, 4)):
+        if qkv_bits == 4:
+            (q, s_q), (k, s_k), (v, s_v) = (wl.quantize_inputs_int4(att[n]) for n in "qkv")
+        else:
+            q, k, v, s_q, s_k, s_v = att["q8"], att["k8"], att["v8"], att["s_q"], att["s_k"], att["s_v"]
+        q, k, v = up(q), up(k), up(v)
+        ws = torch.empty(mc.attention_workspace_bytes(HEADS, amask, p_bits), dtype=torch.uint8, device="cuda")
+        s_p = np.float32(1.0 / (32639.0 if p_bits == 16 else 127.0))
+        us = time_graph(torch, stream, [lambda: mc.sparse_attention(q, k, v, amask, s_q, s_k, s_v, s_p, out=O, workspace=ws,
+                                                                    p_bits=p_bits, qkv_bits=qkv_bits)] * max(1, reps // 4))
+        ops = HEADS * 2 * (2 * amask.nvec * V * DK)
+        wide[name] = dict(us=round(us, 2), eff_tops=round(ops / us / 1e6, 1), path="four-kernel pipeline")
+    amask.close()
+    out["wider_precisions"] = wide
+    return out
 
 
 def cpu_baseline(prob):
@@ -273,8 +370,19 @@ def cpu_baseline(prob):
         ops += HEADS * 2 * (2 * len(a["col_idx"]) * V * DK)
         dt = time.perf_counter() - t0
         best = dt if best is None else min(best, dt)
-    return dict(value=round(ops / best / 1e12, 5), unit="TOPS", cores=oracle.num_threads(), kind="oracle",
+    # the headline SpMM alone on one core, for scale
+    c = prob["spmm_L8R8"]
+    nthreads = oracle.num_threads()
+    oracle.set_num_threads(1)
+    try:
+        t0 = time.perf_counter()
+        oracle.spmm(M, K, V, c["row_ptr"], c["col_idx"], c["values"], c["B"], "L8R8")
+        single = time.perf_counter() - t0
+    finally:
+        oracle.set_num_threads(nthreads)
+    return dict(value=round(ops / best / 1e12, 5), unit="TOPS", cores=nthreads, kind="oracle",
                 seconds=round(best, 3),
+                headline_spmm_one_core_tops=round(2 * len(c["col_idx"]) * V * N_SPMM / single / 1e12, 5),
                 sample="the operations of one whole step (4 SpMM precisions, 2 SDDMM precisions, 8 attention heads), "
                        "best of 3 passes, including the oracle's dense/int32 operand preparation")
 

@@ -144,6 +144,17 @@ int mc_mat_info(const mc_mat *A, int *M, int *K, int *V, int *lhs_bits, int64_t 
 int mc_spmm(const mc_mat *A, const void *B_dev, int N, int ldb, mc_prec prec, int32_t *C_dev, int ldc,
             void *stream);
 
+/* Measurement aid (Section 4.2.1 names the gather of B rows by column index as the step the
+ * kernel is built around): performs ONLY the gather of mc_spmm(A, B_dev, N, ldb, prec, ...) --
+ * same tile variant, index loads and row copies into on-chip memory, no arithmetic, no C.
+ * Its time is the floor the memory system sets for that launch shape.
+ *   sink_dev   int32 array, at least mc_probe_gather_sink_len(A, N, prec) entries; entry
+ *              w receives bytes 0..3 of workgroup w's first staged row piece (0 for an empty panel)
+ * Same argument checks as mc_spmm. */
+int64_t mc_probe_gather_sink_len(const mc_mat *A, int N, mc_prec prec);
+int mc_probe_gather(const mc_mat *A, const void *B_dev, int N, int ldb, mc_prec prec, int32_t *sink_dev,
+                    void *stream);
+
 /* ------------------------------------------------------------------------------------
  * SDDMM (Section 4.3): for every stored vector i of the mask (panel p, column c):
  *   S[i*V + v] = sum_k Q[p*V + v][k] * Kmat[c][k],  v = 0..V-1

@@ -72,12 +72,14 @@ def _load() -> ctypes.CDLL:
     L.mc_sparse_attention_bits.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int64, c_int64,
                                            c_void_p, c_int, c_int, c_float, c_float, c_float, c_float, c_void_p,
                                            c_void_p, c_size_t, c_void_p]
+    L.mc_probe_gather_sink_len.argtypes = [c_void_p, c_int, c_int]; L.mc_probe_gather_sink_len.restype = c_int64
+    L.mc_probe_gather.argtypes = [c_void_p, c_void_p, c_int, c_int, c_int, c_void_p, c_void_p]
     L.mc_set_spmm_variant.argtypes = [c_int, c_int]
     L.mc_set_attention_mode.argtypes = [c_int]
     L.mc_set_sddmm_variant.argtypes = [c_int]
     for name in ("mc_layout_query", "mc_pack_host", "mc_unpack_host", "mc_mat_create", "mc_mat_set_values_device",
                  "mc_mat_info", "mc_spmm", "mc_sddmm", "mc_sparse_softmax", "mc_sparse_softmax_bits", "mc_sparse_attention",
-                 "mc_sparse_attention_strided", "mc_sparse_attention_bits",
+                 "mc_sparse_attention_strided", "mc_sparse_attention_bits", "mc_probe_gather",
                  "mc_set_spmm_variant", "mc_set_attention_mode", "mc_set_sddmm_variant"):
         getattr(L, name).restype = c_int
     return L
@@ -206,6 +208,18 @@ def spmm(A: SparseMatrix, B, prec: str, out=None):
     assert out.is_cuda and out.dtype == torch.int32 and out.shape == (A.M, N) and out.stride(1) == 1
     _check(lib.mc_spmm(A.handle, B.data_ptr(), N, ldb, PREC[prec], out.data_ptr(), out.stride(0), _stream()), "mc_spmm")
     return out
+
+
+def probe_gather(A: SparseMatrix, B, prec: str, sink=None):
+    """Only the gather of spmm(A, B, prec) (a measurement aid); returns the per-workgroup sink."""
+    assert B.is_cuda and B.dim() == 2 and B.stride(1) == 1
+    rbits = RHS_BITS[prec]
+    N = B.shape[1] * B.element_size() * 8 // rbits
+    if sink is None:
+        sink = torch.zeros(int(lib.mc_probe_gather_sink_len(A.handle, N, PREC[prec])), dtype=torch.int32, device=B.device)
+    _check(lib.mc_probe_gather(A.handle, B.data_ptr(), N, B.stride(0) * B.element_size() * 8 // rbits, PREC[prec],
+                               sink.data_ptr(), _stream()), "mc_probe_gather")
+    return sink
 
 
 def sddmm(Q, Kmat, mask: SparseMatrix, prec: str, out=None):

@@ -253,6 +253,34 @@ extern "C" int mc_spmm(const mc_mat *A, const void *B_dev, int N, int ldb, mc_pr
     return MC_OK;
 }
 
+extern "C" int64_t mc_probe_gather_sink_len(const mc_mat *A, int N, mc_prec prec)
+{
+    if (!A || N <= 0 || !valid_prec((int)prec)) return 0;
+    // the widest tiling (64-byte tiles) bounds the number of workgroups
+    return (int64_t)A->P * (((int64_t)N * rhs_bits_of(prec) / 8 + 63) / 64);
+}
+
+extern "C" int mc_probe_gather(const mc_mat *A, const void *B_dev, int N, int ldb, mc_prec prec, int32_t *sink_dev,
+                               void *stream)
+{
+    if (!A || !B_dev || !sink_dev) return MC_EINVAL;
+    if (!valid_prec((int)prec)) return MC_EUNSUPPORTED;
+    const int rb = rhs_bits_of(prec);
+    if (N <= 0 || N % (128 / rb) != 0 || ldb < N) return MC_EINVAL;
+    if (((int64_t)ldb * rb / 8) % 16 != 0 || !aligned16(B_dev)) return MC_EALIGN;
+    SpmmArgs a;
+    a.panel_ptr = A->d_panel_ptr; a.slot_idx = A->d_slot_idx;
+    a.vals = nullptr; a.vals_batch_stride = 0;
+    a.B = static_cast<const uint8_t *>(B_dev); a.ldb_bytes = (int64_t)ldb * rb / 8; a.B_batch_stride = 0;
+    a.row_bytes = N * rb / 8;
+    a.C = nullptr; a.ldc = 0; a.C_batch_stride = 0;
+    a.P = A->P; a.V = A->V; a.batch = 1; a.float_out = 0; a.out_scale = 1.f;
+    int bnb, waves;
+    choose_variant(A, a.row_bytes, rb == 4, 1, &bnb, &waves);
+    MC_HIP(launch_gather_probe(a, bnb, waves, sink_dev, static_cast<hipStream_t>(stream)));
+    return MC_OK;
+}
+
 extern "C" int mc_sddmm(const void *Q_dev, int ldq, const void *Kmat_dev, int ldk, int Kd, const mc_mat *mask,
                         mc_prec prec, int32_t *S_dev, void *stream)
 {
@@ -408,7 +436,7 @@ extern "C" int mc_sparse_attention_bits(const void *Q_dev, const void *Km_dev, c
     if (workspace_bytes < attn_layout(heads, mask, p_bits).total) return MC_ENOMEM;
     hipStream_t s = static_cast<hipStream_t>(stream);
 
-    if (p_bits == 8 && qkv_bits == 8 && g_attention_mode != 1 && dk == 64 &&
+    if (qkv_bits == 8 && g_attention_mode != 1 && dk == 64 &&
         mask->max_panel_chunks * MC_CHUNK <= attention_fused_max_vectors()) {
         AttnArgs f;
         f.panel_ptr = mask->d_panel_ptr; f.slot_idx = mask->d_slot_idx;
@@ -419,7 +447,7 @@ extern "C" int mc_sparse_attention_bits(const void *Q_dev, const void *Km_dev, c
         f.P = mask->P; f.heads = heads;
         // neighbouring heads contiguous inside a token: two heads per workgroup, 128-byte gathers
         const int hpg = (g_attention_mode == 0 && head_stride == 64 && heads % 2 == 0) ? 2 : 1;
-        MC_HIP(launch_attention_fused(f, hpg, s));
+        MC_HIP(launch_attention_fused(f, hpg, p_bits, s));
         return MC_OK;
     }
     return attention_pipeline(static_cast<const uint8_t *>(Q_dev), static_cast<const uint8_t *>(Km_dev),

@@ -68,9 +68,14 @@ __device__ __forceinline__ float row16_sum(float v)
 }
 
 // MAXCH: longest panel in chunks of 64 vectors.  HPW: heads (= waves) per workgroup.
-template <int MAXCH, int HPW>
-__global__ __launch_bounds__(64 * HPW, (HPW == 1 ? 4 : 3)) void attention_fused_kernel(AttnArgs a)
+// PB: bits of the re-quantised softmax output.  16 ("16b-8b" layer): the code c <= 32639 is split
+// into signed bytes c = 256*hi + lo (Section 4.4); the hi codes feed MFMA rows 0..7 and the lo
+// codes rows 8..15 of the same instruction, and the output is (O_hi << 8) + O_lo.
+template <int MAXCH, int HPW, int PB>
+__global__ __launch_bounds__(64 * HPW, ((HPW == 1 && PB == 8) ? 4 : 3)) void attention_fused_kernel(AttnArgs a)
 {
+    static_assert(PB == 8 || (PB == 16 && HPW == 1), "16-bit codes: one head per workgroup");
+    constexpr int PLANE = MAXCH * 512;   // bytes of one plane of codes, [slot][8 rows]
     constexpr int DK = 64;
     constexpr int NPR = MAXCH * 2;   // pairs of score tiles
     constexpr int ROWB = DK * HPW;   // bytes of a gathered row
@@ -80,7 +85,7 @@ __global__ __launch_bounds__(64 * HPW, (HPW == 1 ? 4 : 3)) void attention_fused_
     constexpr int STG = 64 * ROWB;   // bytes of one stage
     constexpr int NST = HPW;         // stages: one for a lone wave, two when two waves share the chunks
     __shared__ __attribute__((aligned(16))) char stage[NST * STG];         // chunks of gathered rows
-    __shared__ __attribute__((aligned(16))) char Pl_all[HPW * MAXCH * 512]; // codes, [slot][8 rows], per wave
+    __shared__ __attribute__((aligned(16))) char Pl_all[HPW * PLANE * (PB / 8)]; // codes, [plane][slot][8 rows], per wave
 
     const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int j = lane & 15, g = lane >> 4;
@@ -98,7 +103,7 @@ __global__ __launch_bounds__(64 * HPW, (HPW == 1 ? 4 : 3)) void attention_fused_
     const int64_t hoff = (int64_t)head * a.head_stride;
     const uint8_t *Kg = a.Km + goff, *Vg = a.Vm + goff;
     float *Oh = a.O + hoff + (int64_t)panel * 8 * a.token_stride;
-    char *Pl = Pl_all + w * (MAXCH * 512);
+    char *Pl = Pl_all + w * (PLANE * (PB / 8));
 
     // Q rows twice: in MFMA rows 0..7 (q_lo) and in rows 8..15 (q_hi)
     v4i q_lo = {0, 0, 0, 0}, q_hi = {0, 0, 0, 0};
@@ -235,7 +240,9 @@ __global__ __launch_bounds__(64 * HPW, (HPW == 1 ? 4 : 3)) void attention_fused_
         const int s = g * 16 + 8 * h + ii;   // slot within the chunk supplied by this lane
         const int i = s % NIT, r = s / NIT;
         vbase[h] = i * 1024 + r * ROWB + (((4 * w) ^ i) * 16) + 8 * (src & 1);
-        paddr[h] = Pl + s * 8;
+        // lanes 2t and 2t+1 supply the 8-byte pieces that end up in MFMA rows 0..7 and 8..15:
+        // the same piece twice (rows 8..15 are zeroed below) or the high and the low plane
+        paddr[h] = Pl + s * 8 + ((PB == 16) ? (src & 1) * PLANE : 0);
     }
     static_for<MAXCH>([&](auto C) {
         constexpr int c = C;
@@ -246,11 +253,25 @@ __global__ __launch_bounds__(64 * HPW, (HPW == 1 ? 4 : 3)) void attention_fused_
             // Done here, chunk by chunk, so that this ALU work overlaps the V copies in flight.
 #pragma unroll
             for (int pr = 0; pr < 2; ++pr) {
-                unsigned packed = 0;
-#pragma unroll
-                for (int r = 0; r < 4; ++r) packed = __builtin_amdgcn_cvt_pk_u8_f32(x[2 * c + pr][r] * rinv[r], r, packed);
                 const int slot = c * MC_CHUNK + (2 * pr + (g >> 1)) * 16 + j;
-                *reinterpret_cast<unsigned *>(Pl + slot * 8 + 4 * (g & 1)) = packed;
+                if (PB == 8) {
+                    unsigned packed = 0;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) packed = __builtin_amdgcn_cvt_pk_u8_f32(x[2 * c + pr][r] * rinv[r], r, packed);
+                    *reinterpret_cast<unsigned *>(Pl + slot * 8 + 4 * (g & 1)) = packed;
+                } else {
+                    // code = clamp(rint(e * rinv), 0, 32639) (ties to even), hi = (code + 128) >> 8 in
+                    // [0, 127], lo = code - 256 * hi in [-128, 127]: its low byte as it is
+                    unsigned hi = 0, lo = 0;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const int code = (int)__builtin_rintf(fminf(x[2 * c + pr][r] * rinv[r], 32639.f));
+                        hi |= (unsigned)((code + 128) >> 8) << (8 * r);
+                        lo |= (unsigned)(code & 255) << (8 * r);
+                    }
+                    *reinterpret_cast<unsigned *>(Pl + slot * 8 + 4 * (g & 1)) = hi;
+                    *reinterpret_cast<unsigned *>(Pl + PLANE + slot * 8 + 4 * (g & 1)) = lo;
+                }
             }
             acquire(Vg, c);
             // the codes, transposed to the MFMA row operand: row j < 8, slots g*16 .. +15
@@ -263,7 +284,7 @@ __global__ __launch_bounds__(64 * HPW, (HPW == 1 ? 4 : 3)) void attention_fused_
             }
             release(Vg, c);
             v4i aop = {p0.x, p0.y, p1.x, p1.y};
-            if (j >= 8) aop = (v4i){0, 0, 0, 0};
+            if (PB == 8 && j >= 8) aop = (v4i){0, 0, 0, 0};
 #pragma unroll
             for (int ct = 0; ct < 4; ++ct) {
                 const v4i bop = {d[ct][0].x, d[ct][0].y, d[ct][1].x, d[ct][1].y};
@@ -275,7 +296,7 @@ __global__ __launch_bounds__(64 * HPW, (HPW == 1 ? 4 : 3)) void attention_fused_
     // ---- output: 8 x 64 tile through this wave's code area, scaled, 16-byte stores -------------
     vm_wait<0>();
     int *Ol = reinterpret_cast<int *>(Pl);
-    if (g < 2) {
+    if (g < 2 || PB == 16) {
 #pragma unroll
         for (int ct = 0; ct < 4; ++ct)
 #pragma unroll
@@ -286,7 +307,8 @@ __global__ __launch_bounds__(64 * HPW, (HPW == 1 ? 4 : 3)) void attention_fused_
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
         const int piece = h * 64 + lane, row = piece >> 4, col = (piece & 15) * 4;
-        const v4i sres = *reinterpret_cast<const v4i *>(&Ol[row * (DK + 4) + col]);
+        v4i sres = *reinterpret_cast<const v4i *>(&Ol[row * (DK + 4) + col]);
+        if (PB == 16) sres = (sres << 8) + *reinterpret_cast<const v4i *>(&Ol[(row + 8) * (DK + 4) + col]);
         const v4f f = {sres.x * a.out_scale, sres.y * a.out_scale, sres.z * a.out_scale, sres.w * a.out_scale};
         *reinterpret_cast<v4f *>(Oh + (int64_t)row * a.token_stride + col) = f;
     }
@@ -296,15 +318,18 @@ __global__ __launch_bounds__(64 * HPW, (HPW == 1 ? 4 : 3)) void attention_fused_
 
 int attention_fused_max_vectors() { return 8 * 64; }
 
-hipError_t launch_attention_fused(const AttnArgs &a, int heads_per_group, hipStream_t s)
+hipError_t launch_attention_fused(const AttnArgs &a, int heads_per_group, int p_bits, hipStream_t s)
 {
     if (a.P == 0 || a.heads == 0) return hipSuccess;
-    if (heads_per_group == 2) {
+    if (p_bits == 16) {
+        dim3 grid((unsigned)a.P * (unsigned)a.heads), block(64);
+        hipLaunchKernelGGL((attention_fused_kernel<8, 1, 16>), grid, block, 0, s, a);
+    } else if (heads_per_group == 2) {
         dim3 grid((unsigned)a.P * (unsigned)(a.heads / 2)), block(128);
-        hipLaunchKernelGGL((attention_fused_kernel<8, 2>), grid, block, 0, s, a);
+        hipLaunchKernelGGL((attention_fused_kernel<8, 2, 8>), grid, block, 0, s, a);
     } else {
         dim3 grid((unsigned)a.P * (unsigned)a.heads), block(64);
-        hipLaunchKernelGGL((attention_fused_kernel<8, 1>), grid, block, 0, s, a);
+        hipLaunchKernelGGL((attention_fused_kernel<8, 1, 8>), grid, block, 0, s, a);
     }
     return hipGetLastError();
 }

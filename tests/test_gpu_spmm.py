@@ -148,3 +148,35 @@ def test_ablation_shape_and_tall_matrix():
         _check(wl.spmm_case(256, 2304, 512, 8, 0.7, prec, 77))
     _check(wl.spmm_case(32768, 8192, 64, 8, 0.99, "L8R8", 78))
     _check(wl.spmm_case(16384, 1024, 1024, 4, 0.9, "L8R4", 79))
+
+
+@pytest.mark.parametrize("bnb,waves", [(64, 1), (128, 2), (256, 4)])
+def test_gather_probe_fetches_the_rows_spmm_would(bnb, waves):
+    """The gather-only measurement kernel: every workgroup reports the first word of its staged rows."""
+    import torch
+    from paper_2209_06979_amd import binding as mc
+    V, K, N = 8, 700, 320
+    counts = [0, 1, 63, 64, 65, 129, 300, 700]
+    M = V * len(counts)
+    rp, ci = wl.ragged_pattern(M, K, V, counts, 171)
+    B = wl.uniform_int8((K, N), 172)
+    A = mc.SparseMatrix(M, K, V, rp, ci, wl.uniform_int8((len(ci), V), 173), 8)
+    mc.set_spmm_variant(bnb, waves)
+    try:
+        sink = mc.probe_gather(A, torch.from_numpy(B).cuda(), "L8R8")
+        torch.cuda.synchronize()
+    finally:
+        mc.set_spmm_variant(0, 0)
+        A.close()
+    sink = sink.cpu().numpy()
+    ntiles = (N + bnb - 1) // bnb
+    for p, n in enumerate(counts):
+        for t in range(ntiles):
+            if n == 0:
+                want = 0
+            else:
+                nch = (n + 63) // 64
+                c_last = (nch - 1) // waves * waves            # last chunk of wave 0
+                col = ci[rp[p] + c_last * 64]
+                want = int(B[col, t * bnb:t * bnb + 4].copy().view(np.int32)[0])
+            assert sink[p * ntiles + t] == want, (p, t)

@@ -161,7 +161,7 @@ def test_sddmm_l16r16_full_size_4096(Kd, s):
 
 
 # ------------------------------------------------- attention "xb-yb" variants ----
-def _attention_variant_check(heads, L, dk, sparsity, seed, p_bits, qkv_bits, token_major=False):
+def _attention_variant_check(heads, L, dk, sparsity, seed, p_bits, qkv_bits, token_major=False, mode=0):
     """The layer with p_bits-bit softmax codes and qkv_bits-bit Q/K/V against the oracle, with the
     same tie protocol as the 8b-8b layer: 1e-3, plus one code step for every entry whose
     re-quantisation sits on a rounding boundary within fp32 accuracy."""
@@ -175,12 +175,17 @@ def _attention_variant_check(heads, L, dk, sparsity, seed, p_bits, qkv_bits, tok
     (q, s_q), (k, s_k), (v, s_v) = (quant(c[n]) for n in "qkv")
     s_p = np.float32(1.0 / oracle.P_CODE_MAX[p_bits])
     vmax = 7 if qkv_bits == 4 else 127
-    print(f"attention {p_bits}b-{qkv_bits}b heads={heads} L={L} dk={dk} s={sparsity} token_major={token_major}", flush=True)
+    print(f"attention {p_bits}b-{qkv_bits}b heads={heads} L={L} dk={dk} s={sparsity} token_major={token_major} mode={mode}",
+          flush=True)
     mask = mc.SparseMatrix(L, L, V, c["row_ptr"], c["col_idx"])
     out = _layout(np.full((heads, L, dk), np.nan, np.float32), token_major)
-    O = mc.sparse_attention(_layout(q, token_major), _layout(k, token_major), _layout(v, token_major), mask,
-                            s_q, s_k, s_v, s_p, out=out, p_bits=p_bits, qkv_bits=qkv_bits)
-    torch.cuda.synchronize()
+    mc.set_attention_mode(mode)
+    try:
+        O = mc.sparse_attention(_layout(q, token_major), _layout(k, token_major), _layout(v, token_major), mask,
+                                s_q, s_k, s_v, s_p, out=out, p_bits=p_bits, qkv_bits=qkv_bits)
+        torch.cuda.synchronize()
+    finally:
+        mc.set_attention_mode(0)
     O = O.cpu().numpy().astype(np.float64)
     mask.close()
     want, scores, probs, codes = oracle.attention(q, k, v, c["row_ptr"], c["col_idx"], V, s_q, s_k, s_v, s_p,
@@ -205,17 +210,41 @@ def _attention_variant_check(heads, L, dk, sparsity, seed, p_bits, qkv_bits, tok
 
 @pytest.mark.parametrize("p_bits,qkv_bits", [(16, 8), (8, 4), (16, 4)])
 @pytest.mark.parametrize("token_major", [False, True])
-def test_attention_variants_small(p_bits, qkv_bits, token_major):
-    _attention_variant_check(2, 256, 64, 0.75, 4000, p_bits, qkv_bits, token_major)
-    _attention_variant_check(3, 512, 32, 0.9, 4001, p_bits, qkv_bits, token_major)
-    _attention_variant_check(2, 1024, 64, 0.6, 4002, p_bits, qkv_bits, token_major)
-    _attention_variant_check(1, 2048, 128, 0.7, 4003, p_bits, qkv_bits, token_major)
+@pytest.mark.parametrize("mode", [0, 1])                      # fused kernel where there is one / kernel pipeline
+def test_attention_variants_small(p_bits, qkv_bits, token_major, mode):
+    _attention_variant_check(2, 256, 64, 0.75, 4000, p_bits, qkv_bits, token_major, mode)   # one chunk per panel
+    _attention_variant_check(3, 512, 32, 0.9, 4001, p_bits, qkv_bits, token_major, mode)    # dk != 64: pipeline
+    _attention_variant_check(2, 1024, 64, 0.6, 4002, p_bits, qkv_bits, token_major, mode)   # 7 chunks, ragged tail
+    _attention_variant_check(2, 2048, 64, 0.75, 4004, p_bits, qkv_bits, token_major, mode)  # 512 vectors: longest fused panel
+    _attention_variant_check(1, 2048, 128, 0.7, 4003, p_bits, qkv_bits, token_major, mode)  # 614 vectors, dk 128: pipeline
 
 
 @pytest.mark.parametrize("p_bits,qkv_bits", [(16, 8), (8, 4)])
-def test_attention_variants_config5_shape(p_bits, qkv_bits):
+@pytest.mark.parametrize("mode", [0, 1])
+def test_attention_variants_config5_shape(p_bits, qkv_bits, mode):
     """The 16b-8b and 8b-4b variants at 8 heads, L=4096, dk=64, 90 % vector sparsity."""
-    _attention_variant_check(8, 4096, 64, 0.9, wl.seed_for(5, 1), p_bits, qkv_bits)
+    _attention_variant_check(8, 4096, 64, 0.9, wl.seed_for(5, 1), p_bits, qkv_bits, mode=mode)
+
+
+def test_attention_16b8b_ragged_rows():
+    """16-bit codes in the fused kernel with panels of very different lengths (empty ones give zeros)."""
+    import torch
+    import oracle
+    from paper_2209_06979_amd import binding as mc
+    V, L, dk, heads = 8, 512, 64, 2
+    counts = np.r_[[0, 1, 2, 15, 16, 17, 63, 64, 65, 127, 128, 129, 300, 511, 512, 0], np.full(L // V - 16, 40)]
+    rp, ci = wl.ragged_pattern(L, L, V, counts, 4200)
+    (q, s_q), (k, s_k), (v, s_v) = (wl.quantize_inputs_int8(wl.normal_fp32((heads, L, dk), 4201 + i)) for i in range(3))
+    s_p = np.float32(1 / 32639)
+    want = oracle.attention(q, k, v, rp, ci, V, s_q, s_k, s_v, s_p, p_bits=16)[0]
+    mask = mc.SparseMatrix(L, L, V, rp, ci)
+    O = mc.sparse_attention(torch.from_numpy(q).cuda(), torch.from_numpy(k).cuda(), torch.from_numpy(v).cuda(), mask,
+                            s_q, s_k, s_v, s_p, p_bits=16)
+    torch.cuda.synchronize()
+    O = O.cpu().numpy().astype(np.float64)
+    mask.close()
+    assert np.abs(O - want).max() < 1e-3
+    assert not O[:, :8].any() and not O[:, 15 * 8:16 * 8].any()
 
 
 def test_sparse_softmax_16_bit_codes():
