@@ -343,7 +343,7 @@ def measure_extras(mc, torch, prob, stream, reps, up):
         us = time_graph(torch, stream, [lambda: mc.sparse_attention(q, k, v, amask, s_q, s_k, s_v, s_p, out=O, workspace=ws,
                                                                     p_bits=p_bits, qkv_bits=qkv_bits)] * max(1, reps // 4))
         ops = HEADS * 2 * (2 * amask.nvec * V * DK)
-        wide[name] = dict(us=round(us, 2), eff_tops=round(ops / us / 1e6, 1), path="four-kernel pipeline")
+        wide[name] = dict(us=round(us, 2), eff_tops=round(ops / us / 1e6, 1))
     amask.close()
     out["wider_precisions"] = wide
     return out

@@ -218,9 +218,10 @@ int mc_sparse_attention(const int8_t *Q_dev, const int8_t *Km_dev, const int8_t 
  * multiplied as two signed byte planes) and Q, Km, Vm hold qkv_bits = y bit integers (8, or 4
  * packed two per byte along dk).  Strides are in ELEMENTS for all four tensors and must make
  * whole 16-byte pieces (multiples of 16 for 8-bit, of 32 for 4-bit inputs); dk likewise.
- * p_bits = 8, qkv_bits = 8 is mc_sparse_attention_strided.  The other combinations run the
- * four-kernel pipeline SDDMM -> softmax -> repack -> SpMM and need
- * mc_attention_workspace_bytes_bits(heads, mask, p_bits) bytes of workspace.
+ * p_bits = 8, qkv_bits = 8 is mc_sparse_attention_strided.  Every combination has the fused
+ * kernel (dk == 64, panels of at most 512 vectors) and the four-kernel pipeline behind it, as
+ * selected by mc_set_attention_mode; the workspace must hold
+ * mc_attention_workspace_bytes_bits(heads, mask, p_bits) bytes.
  * Unsupported widths: MC_EUNSUPPORTED. */
 size_t mc_attention_workspace_bytes_bits(int heads, const mc_mat *mask, int p_bits);
 int mc_sparse_attention_bits(const void *Q_dev, const void *Km_dev, const void *Vm_dev, int heads, int L, int dk,

@@ -436,18 +436,19 @@ extern "C" int mc_sparse_attention_bits(const void *Q_dev, const void *Km_dev, c
     if (workspace_bytes < attn_layout(heads, mask, p_bits).total) return MC_ENOMEM;
     hipStream_t s = static_cast<hipStream_t>(stream);
 
-    if (qkv_bits == 8 && g_attention_mode != 1 && dk == 64 &&
+    if (g_attention_mode != 1 && dk == 64 &&
         mask->max_panel_chunks * MC_CHUNK <= attention_fused_max_vectors()) {
         AttnArgs f;
         f.panel_ptr = mask->d_panel_ptr; f.slot_idx = mask->d_slot_idx;
         f.Q = static_cast<const uint8_t *>(Q_dev); f.Km = static_cast<const uint8_t *>(Km_dev);
         f.Vm = static_cast<const uint8_t *>(Vm_dev); f.O = O_dev;
         f.head_stride = head_stride; f.token_stride = token_stride;
+        f.in_head_stride = head_stride * qkv_bits / 8; f.in_token_stride = token_stride * qkv_bits / 8;
         f.score_scale = s_q * s_k / std::sqrt((float)dk); f.inv_s_p = 1.f / s_p; f.out_scale = s_p * s_v;
         f.P = mask->P; f.heads = heads;
         // neighbouring heads contiguous inside a token: two heads per workgroup, 128-byte gathers
-        const int hpg = (g_attention_mode == 0 && head_stride == 64 && heads % 2 == 0) ? 2 : 1;
-        MC_HIP(launch_attention_fused(f, hpg, p_bits, s));
+        const int hpg = (g_attention_mode == 0 && p_bits == 8 && head_stride == 64 && heads % 2 == 0) ? 2 : 1;
+        MC_HIP(launch_attention_fused(f, hpg, p_bits, qkv_bits, s));
         return MC_OK;
     }
     return attention_pipeline(static_cast<const uint8_t *>(Q_dev), static_cast<const uint8_t *>(Km_dev),

@@ -71,17 +71,25 @@ __device__ __forceinline__ float row16_sum(float v)
 // PB: bits of the re-quantised softmax output.  16 ("16b-8b" layer): the code c <= 32639 is split
 // into signed bytes c = 256*hi + lo (Section 4.4); the hi codes feed MFMA rows 0..7 and the lo
 // codes rows 8..15 of the same instruction, and the output is (O_hi << 8) + O_lo.
-template <int MAXCH, int HPW, int PB>
+// QB: bits of Q, Kmat and V.  4 ("8b-4b" layer): rows are 32 bytes of packed nibbles.  A nibble is
+// widened in registers to an int8 worth 16 x its value (Section 4.4 without an int4 matrix unit):
+// the even elements of a 16-byte piece in lane groups 0 and 1, the odd ones in groups 2 and 3, so
+// the scores carry a factor 256 and the output a factor 16, removed by exact shifts.
+template <int MAXCH, int HPW, int PB, int QB>
 __global__ __launch_bounds__(64 * HPW, ((HPW == 1 && PB == 8) ? 4 : 3)) void attention_fused_kernel(AttnArgs a)
 {
     static_assert(PB == 8 || (PB == 16 && HPW == 1), "16-bit codes: one head per workgroup");
+    static_assert(QB == 8 || QB == 4, "Q, K, V are 8-bit or packed 4-bit");
     constexpr int PLANE = MAXCH * 512;   // bytes of one plane of codes, [slot][8 rows]
     constexpr int DK = 64;
+    constexpr int DKB = DK * QB / 8; // bytes of one head's row
     constexpr int NPR = MAXCH * 2;   // pairs of score tiles
-    constexpr int ROWB = DK * HPW;   // bytes of a gathered row
+    constexpr int ROWB = DKB * HPW;  // bytes of a gathered row
     constexpr int LPR = ROWB / 16;   // lanes per row
-    constexpr int NIT = LPR;         // copy instructions per chunk (4 of them per wave)
+    constexpr int NIT = LPR;         // copy instructions per chunk
+    constexpr int NITW = DKB / 16;   // ... of which each wave issues this many (4, or 2 for nibbles)
     constexpr int SWZ = LPR - 1;
+    constexpr int NIB = (int)0xF0F0F0F0;
     constexpr int STG = 64 * ROWB;   // bytes of one stage
     constexpr int NST = HPW;         // stages: one for a lone wave, two when two waves share the chunks
     __shared__ __attribute__((aligned(16))) char stage[NST * STG];         // chunks of gathered rows
@@ -99,41 +107,48 @@ __global__ __launch_bounds__(64 * HPW, ((HPW == 1 && PB == 8) ? 4 : 3)) void att
     const int s0 = a.panel_ptr[2 * panel], n = a.panel_ptr[2 * panel + 1] - s0;
     const int nch = (n + MC_CHUNK - 1) / MC_CHUNK;
     const int32_t *idx = a.slot_idx + s0;
-    const int64_t goff = (int64_t)hgrp * HPW * a.head_stride; // first head of the group
-    const int64_t hoff = (int64_t)head * a.head_stride;
+    const int64_t goff = (int64_t)hgrp * HPW * a.in_head_stride; // first head of the group
     const uint8_t *Kg = a.Km + goff, *Vg = a.Vm + goff;
-    float *Oh = a.O + hoff + (int64_t)panel * 8 * a.token_stride;
+    float *Oh = a.O + (int64_t)head * a.head_stride + (int64_t)panel * 8 * a.token_stride;
     char *Pl = Pl_all + w * (PLANE * (PB / 8));
 
     // Q rows twice: in MFMA rows 0..7 (q_lo) and in rows 8..15 (q_hi)
     v4i q_lo = {0, 0, 0, 0}, q_hi = {0, 0, 0, 0};
     {
-        const v4i qv = *reinterpret_cast<const v4i *>(a.Q + hoff + (int64_t)(panel * 8 + (j & 7)) * a.token_stride + g * 16);
+        const uint8_t *qrow = a.Q + (int64_t)head * a.in_head_stride + (int64_t)(panel * 8 + (j & 7)) * a.in_token_stride;
+        v4i qv;
+        if (QB == 8) {
+            qv = *reinterpret_cast<const v4i *>(qrow + g * 16);
+        } else {
+            const v4i raw = *reinterpret_cast<const v4i *>(qrow + (g & 1) * 16);
+            qv = (g < 2) ? ((raw << 4) & NIB) : (raw & NIB);
+        }
         if (j < 8) q_lo = qv; else q_hi = qv;
     }
     // Copy instruction i of a chunk: lane (rg, seg) fetches segment seg ^ i of the row in slot
-    // rg*NIT + i; it lands in LDS row i*(64/NIT) + rg.  Wave w issues instructions 4w .. 4w+3,
-    // whose 4 column indices are consecutive slots: one 128-bit index load per chunk.
-    unsigned segoff[4];
+    // rg*NIT + i; it lands in LDS row i*(64/NIT) + rg.  Wave w issues instructions NITW*w .. +NITW-1,
+    // whose column indices are consecutive slots: one 128-bit (64-bit) index load per chunk.
+    typedef int ixv_t __attribute__((ext_vector_type(NITW)));
+    unsigned segoff[NITW];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) segoff[i] = (seg ^ ((4 * w + i) & SWZ)) * 16;
+    for (int i = 0; i < NITW; ++i) segoff[i] = (seg ^ ((NITW * w + i) & SWZ)) * 16;
     const unsigned stage_u = lds_addr_uniform(stage);
-    const int32_t *myidx = idx + rg * NIT + 4 * w;
-    const unsigned tstride = (unsigned)a.token_stride;
+    const int32_t *myidx = idx + rg * NIT + NITW * w;
+    const unsigned tstride = (unsigned)a.in_token_stride;
     // issue(c): this wave's copies of chunk c into stage c % NST, from the column indices held
     // in ixn; then the indices of the following chunk are requested (an ordinary load that has
     // long arrived by the time they are needed: a vm_wait<0>() lies in between).
-    v4i ixn = {0, 0, 0, 0};
+    ixv_t ixn = {};
     auto issue = [&](const uint8_t *base, int c) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-            copy16_to_lds(base, __umul24(ixn[i], tstride) + segoff[i], stage_u + (c % NST) * STG + (4 * w + i) * 1024);
-        ixn = *reinterpret_cast<const v4i *>(myidx + ((c + 1 < nch) ? c + 1 : c) * MC_CHUNK);
+        for (int i = 0; i < NITW; ++i)
+            copy16_to_lds(base, __umul24(ixn[i], tstride) + segoff[i], stage_u + (c % NST) * STG + (NITW * w + i) * 1024);
+        ixn = *reinterpret_cast<const ixv_t *>(myidx + ((c + 1 < nch) ? c + 1 : c) * MC_CHUNK);
     };
     auto start_pipeline = [&](const uint8_t *base) {
         if (HPW > 1) __builtin_amdgcn_s_barrier(); // both waves are done with the stages
         if (nch > 0) {
-            ixn = *reinterpret_cast<const v4i *>(myidx);
+            ixn = *reinterpret_cast<const ixv_t *>(myidx);
             issue(base, 0);
         }
     };
@@ -158,8 +173,14 @@ __global__ __launch_bounds__(64 * HPW, ((HPW == 1 && PB == 8) ? 4 : 3)) void att
     // The integer scores stay in registers; only the last chunk can hold padded slots, which
     // are kept out of the row maximum here and out of the row sum below.
     // K operand of tile tl: slot s = tl*16 + j sits in LDS row (s % NIT)*(64/NIT) + s/NIT,
-    // i.e. byte (j % NIT)*1024 + (j / NIT)*ROWB + tl*256; segment (4w + g) ^ (j % NIT)
-    const char *kaddr = stage + (j % NIT) * 1024 + (j / NIT) * ROWB + (((4 * w + g) ^ (j % NIT)) * 16);
+    // i.e. byte (j % NIT)*1024 + (j / NIT)*ROWB + tl*256; segment (NITW*w + piece) ^ (j % NIT), where
+    // lane group g reads piece g of its head's row (8 bit) or piece g % 2 (4 bit: even elements of
+    // the piece for g < 2, odd elements for g >= 2, as on the Q side)
+    const char *kaddr = stage + (j % NIT) * 1024 + (j / NIT) * ROWB + (((NITW * w + (QB == 8 ? g : (g & 1))) ^ (j % NIT)) * 16);
+    auto kop = [&](v4i raw) -> v4i {
+        if (QB == 8) return raw;
+        return (g < 2) ? ((raw << 4) & NIB) : (raw & NIB);
+    };
     v4i sc[NPR];
     int imax[4] = {INT32_MIN, INT32_MIN, INT32_MIN, INT32_MIN};
     const int tail = n - (nch - 1) * MC_CHUNK; // real vectors in the last chunk
@@ -176,10 +197,14 @@ __global__ __launch_bounds__(64 * HPW, ((HPW == 1 && PB == 8) ? 4 : 3)) void att
             const v4i kA0 = *reinterpret_cast<const v4i *>(kaddr + ST), kB0 = *reinterpret_cast<const v4i *>(kaddr + ST + 256);
             const v4i kA1 = *reinterpret_cast<const v4i *>(kaddr + ST + 512), kB1 = *reinterpret_cast<const v4i *>(kaddr + ST + 768);
             release(Kg, c);
-            sc[2 * c] = __builtin_amdgcn_mfma_i32_16x16x64_i8(q_lo, kA0, sc[2 * c], 0, 0, 0);
-            sc[2 * c] = __builtin_amdgcn_mfma_i32_16x16x64_i8(q_hi, kB0, sc[2 * c], 0, 0, 0);
-            sc[2 * c + 1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(q_lo, kA1, sc[2 * c + 1], 0, 0, 0);
-            sc[2 * c + 1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(q_hi, kB1, sc[2 * c + 1], 0, 0, 0);
+            sc[2 * c] = __builtin_amdgcn_mfma_i32_16x16x64_i8(q_lo, kop(kA0), sc[2 * c], 0, 0, 0);
+            sc[2 * c] = __builtin_amdgcn_mfma_i32_16x16x64_i8(q_hi, kop(kB0), sc[2 * c], 0, 0, 0);
+            sc[2 * c + 1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(q_lo, kop(kA1), sc[2 * c + 1], 0, 0, 0);
+            sc[2 * c + 1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(q_hi, kop(kB1), sc[2 * c + 1], 0, 0, 0);
+            if (QB == 4) { // both operands carried a factor 16
+                sc[2 * c] = sc[2 * c] >> 8;
+                sc[2 * c + 1] = sc[2 * c + 1] >> 8;
+            }
             if (c == nch - 1) {
 #pragma unroll
                 for (int pr = 0; pr < 2; ++pr)
@@ -239,7 +264,7 @@ __global__ __launch_bounds__(64 * HPW, ((HPW == 1 && PB == 8) ? 4 : 3)) void att
     for (int h = 0; h < 2; ++h) {
         const int s = g * 16 + 8 * h + ii;   // slot within the chunk supplied by this lane
         const int i = s % NIT, r = s / NIT;
-        vbase[h] = i * 1024 + r * ROWB + (((4 * w) ^ i) * 16) + 8 * (src & 1);
+        vbase[h] = i * 1024 + r * ROWB + (((NITW * w) ^ i) * 16) + 8 * (src & 1);
         // lanes 2t and 2t+1 supply the 8-byte pieces that end up in MFMA rows 0..7 and 8..15:
         // the same piece twice (rows 8..15 are zeroed below) or the high and the low plane
         paddr[h] = Pl + s * 8 + ((PB == 16) ? (src & 1) * PLANE : 0);
@@ -276,9 +301,9 @@ __global__ __launch_bounds__(64 * HPW, ((HPW == 1 && PB == 8) ? 4 : 3)) void att
             acquire(Vg, c);
             // the codes, transposed to the MFMA row operand: row j < 8, slots g*16 .. +15
             const v2i p0 = lds_read_tr8(paddr[0] + c * 512), p1 = lds_read_tr8(paddr[1] + c * 512);
-            v2i d[4][2];
+            v2i d[NITW][2];
 #pragma unroll
-            for (int ct = 0; ct < 4; ++ct) {
+            for (int ct = 0; ct < NITW; ++ct) {
                 d[ct][0] = lds_read_tr8(stage + (c % NST) * STG + (vbase[0] ^ (ct * 16)));
                 d[ct][1] = lds_read_tr8(stage + (c % NST) * STG + (vbase[1] ^ (ct * 16)));
             }
@@ -286,9 +311,15 @@ __global__ __launch_bounds__(64 * HPW, ((HPW == 1 && PB == 8) ? 4 : 3)) void att
             v4i aop = {p0.x, p0.y, p1.x, p1.y};
             if (PB == 8 && j >= 8) aop = (v4i){0, 0, 0, 0};
 #pragma unroll
-            for (int ct = 0; ct < 4; ++ct) {
+            for (int ct = 0; ct < NITW; ++ct) {
                 const v4i bop = {d[ct][0].x, d[ct][0].y, d[ct][1].x, d[ct][1].y};
-                o[ct] = __builtin_amdgcn_mfma_i32_16x16x64_i8(aop, bop, o[ct], 0, 0, 0);
+                if (QB == 8) {
+                    o[ct] = __builtin_amdgcn_mfma_i32_16x16x64_i8(aop, bop, o[ct], 0, 0, 0);
+                } else { // byte j of the piece holds columns 32*ct + 2j (low nibble) and 2j + 1 (high nibble)
+                    const v4i msk = {NIB, NIB, NIB, NIB};
+                    o[2 * ct] = __builtin_amdgcn_mfma_i32_16x16x64_i8(aop, (bop << 4) & msk, o[2 * ct], 0, 0, 0);
+                    o[2 * ct + 1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(aop, bop & msk, o[2 * ct + 1], 0, 0, 0);
+                }
             }
         }
     });
@@ -300,7 +331,11 @@ __global__ __launch_bounds__(64 * HPW, ((HPW == 1 && PB == 8) ? 4 : 3)) void att
 #pragma unroll
         for (int ct = 0; ct < 4; ++ct)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) Ol[(4 * g + r) * (DK + 4) + ct * 16 + j] = o[ct][r];
+            for (int r = 0; r < 4; ++r) {
+                // the nibble products carry a factor 16; each plane's sum is shifted on its own
+                if (QB == 8) Ol[(4 * g + r) * (DK + 4) + ct * 16 + j] = o[ct][r];
+                else Ol[(4 * g + r) * (DK + 4) + (ct >> 1) * 32 + 2 * j + (ct & 1)] = o[ct][r] >> 4;
+            }
     }
     lgkm_wait();
     __builtin_amdgcn_wave_barrier();
@@ -318,18 +353,21 @@ __global__ __launch_bounds__(64 * HPW, ((HPW == 1 && PB == 8) ? 4 : 3)) void att
 
 int attention_fused_max_vectors() { return 8 * 64; }
 
-hipError_t launch_attention_fused(const AttnArgs &a, int heads_per_group, int p_bits, hipStream_t s)
+hipError_t launch_attention_fused(const AttnArgs &a, int heads_per_group, int p_bits, int qkv_bits, hipStream_t s)
 {
     if (a.P == 0 || a.heads == 0) return hipSuccess;
     if (p_bits == 16) {
         dim3 grid((unsigned)a.P * (unsigned)a.heads), block(64);
-        hipLaunchKernelGGL((attention_fused_kernel<8, 1, 16>), grid, block, 0, s, a);
+        if (qkv_bits == 4) hipLaunchKernelGGL((attention_fused_kernel<8, 1, 16, 4>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((attention_fused_kernel<8, 1, 16, 8>), grid, block, 0, s, a);
     } else if (heads_per_group == 2) {
         dim3 grid((unsigned)a.P * (unsigned)(a.heads / 2)), block(128);
-        hipLaunchKernelGGL((attention_fused_kernel<8, 2, 8>), grid, block, 0, s, a);
+        if (qkv_bits == 4) hipLaunchKernelGGL((attention_fused_kernel<8, 2, 8, 4>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((attention_fused_kernel<8, 2, 8, 8>), grid, block, 0, s, a);
     } else {
         dim3 grid((unsigned)a.P * (unsigned)a.heads), block(64);
-        hipLaunchKernelGGL((attention_fused_kernel<8, 1, 8>), grid, block, 0, s, a);
+        if (qkv_bits == 4) hipLaunchKernelGGL((attention_fused_kernel<8, 1, 8, 4>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((attention_fused_kernel<8, 1, 8, 8>), grid, block, 0, s, a);
     }
     return hipGetLastError();
 }

@@ -75,7 +75,8 @@ struct AttnArgs {
     const int32_t *slot_idx;
     const uint8_t *Q, *Km, *Vm;
     float *O;
-    int64_t head_stride, token_stride; // elements
+    int64_t head_stride, token_stride;       // elements of O
+    int64_t in_head_stride, in_token_stride; // bytes of Q, Km, Vm
     float score_scale, inv_s_p, out_scale;
     int P, heads;
 };
@@ -89,5 +90,5 @@ hipError_t launch_sddmm(int bits, const SddmmArgs &a, int waves, hipStream_t s);
 hipError_t launch_softmax(const SoftmaxArgs &a, hipStream_t s);
 hipError_t launch_repack(const RepackArgs &a, hipStream_t s);
 // heads_per_group 2 needs head_stride == 64 (token-major layout) and an even head count
-hipError_t launch_attention_fused(const AttnArgs &a, int heads_per_group, int p_bits, hipStream_t s);
+hipError_t launch_attention_fused(const AttnArgs &a, int heads_per_group, int p_bits, int qkv_bits, hipStream_t s);
 int attention_fused_max_vectors(); // longest panel (in vectors) the fused kernel accepts
