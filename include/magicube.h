@@ -238,7 +238,7 @@ int mc_sparse_attention_bits(const void *Q_dev, const void *Km_dev, const void *
 int mc_set_spmm_variant(int bytes_per_row_tile, int waves);
 /* SDDMM variant: -1 = automatic, 0 = the kernel that loads operands straight from memory
  * (any row length), 1, 2, 4 or 8 = waves per panel of the kernel that stages Kmat rows in
- * LDS (used when a row has 64, 128 or 256 bytes, else ignored).  Process-wide. */
+ * LDS (used when a row has 64, 128, 256 or 512 bytes, else ignored).  Process-wide. */
 int mc_set_sddmm_variant(int waves);
 /* Attention path: 0 = automatic (a single fused kernel when dk == 64 and no panel holds
  * more than 512 vectors, else the four-kernel pipeline), 1 = always the four-kernel

@@ -9,7 +9,7 @@
 // both sides.  The waves of a workgroup take the panel's chunks of 64 vectors round-robin
 // and never have to meet: every chunk produces its own outputs.
 // Two kernels:
-//   sddmm_lds_kernel   rows of 64, 128 or 256 bytes: the 64 Kmat rows of a chunk are copied
+//   sddmm_lds_kernel   rows of 64, 128, 256 or 512 bytes: the 64 Kmat rows of a chunk are copied
 //                      from global memory straight into LDS with coalesced 16-byte pieces
 //                      (global_load_lds), then read as 128-bit MFMA operands; the
 //                      16-byte segments are XOR-swizzled against bank conflicts.
@@ -130,7 +130,7 @@ __device__ __forceinline__ v4i load_q(const uint8_t *Qpanel, int64_t ldq_bytes, 
     return q;
 }
 
-// RB: bytes of a Kmat row (64, 128, 256; 16-bit operands: 128, 256).  WK: waves per workgroup.
+// RB: bytes of a Kmat row (64, 128, 256, 512; 16-bit operands: from 128).  WK: waves per workgroup.
 template <int PB, int RB, int WK>
 __global__ __launch_bounds__(64 * WK) void sddmm_lds_kernel(SddmmArgs a)
 {
@@ -349,12 +349,12 @@ __global__ __launch_bounds__(256) void repack_kernel(RepackArgs a)
 template <int PB, int RB> hipError_t launch_sddmm_lds(const SddmmArgs &a, int waves, hipStream_t s)
 {
     dim3 grid((unsigned)a.P, (unsigned)a.batch);
-    constexpr int MAXW = (64 * RB * 8 <= 65536) ? 8 : 4;
+    constexpr int MAXW = (64 * RB * 8 <= 65536) ? 8 : ((64 * RB * 4 <= 65536) ? 4 : 2); // 64 KB of stages per workgroup
     if (waves > MAXW) waves = MAXW;
     switch (waves) {
     case 1: hipLaunchKernelGGL((sddmm_lds_kernel<PB, RB, 1>), grid, dim3(64), 0, s, a); break;
     case 2: hipLaunchKernelGGL((sddmm_lds_kernel<PB, RB, 2>), grid, dim3(128), 0, s, a); break;
-    case 4: hipLaunchKernelGGL((sddmm_lds_kernel<PB, RB, 4>), grid, dim3(256), 0, s, a); break;
+    case 4: hipLaunchKernelGGL((sddmm_lds_kernel<PB, RB, (MAXW < 4 ? MAXW : 4)>), grid, dim3(64 * (MAXW < 4 ? MAXW : 4)), 0, s, a); break;
     default: hipLaunchKernelGGL((sddmm_lds_kernel<PB, RB, MAXW>), grid, dim3(64 * MAXW), 0, s, a); break;
     }
     return hipGetLastError();
@@ -366,6 +366,7 @@ template <int PB> hipError_t launch_sddmm_bits(const SddmmArgs &a, int waves, hi
         if (a.row_bytes == 64 && PB != 16) return launch_sddmm_lds<(PB == 16 ? 8 : PB), 64>(a, waves, s);
         if (a.row_bytes == 128) return launch_sddmm_lds<PB, 128>(a, waves, s);
         if (a.row_bytes == 256) return launch_sddmm_lds<PB, 256>(a, waves, s);
+        if (a.row_bytes == 512) return launch_sddmm_lds<PB, 512>(a, waves, s);
     }
     dim3 grid((unsigned)a.P, (unsigned)a.batch), block(64 * SDDMM_WAVES);
     const int kc = (a.row_bytes + StepBytes<PB>::value - 1) / StepBytes<PB>::value;

@@ -26,6 +26,11 @@ def test_small(prec, V, Kd):
     _check(wl.sddmm_case(16 * V, 300, Kd, V, 0.7, prec, 1000 + V + Kd), variants=(-1, 0, 1, 2, 4, 8))
 
 
+@pytest.mark.parametrize("prec,Kd", [("L8R8", 512), ("L4R4", 1024)])
+def test_rows_of_512_bytes(prec, Kd):
+    _check(wl.sddmm_case(64, 300, Kd, 8, 0.5, prec, 1150 + Kd), variants=(-1, 0, 1, 2, 4, 8))
+
+
 @pytest.mark.parametrize("prec,Kd", [("L8R8", 16), ("L8R8", 48), ("L8R8", 320), ("L8R8", 1024), ("L4R4", 32),
                                      ("L4R4", 96), ("L4R4", 1056)])
 def test_odd_reduction_lengths(prec, Kd):
