@@ -241,9 +241,11 @@ int mc_set_spmm_variant(int bytes_per_row_tile, int waves);
  * LDS (used when a row has 64, 128, 256 or 512 bytes, else ignored).  Process-wide. */
 int mc_set_sddmm_variant(int waves);
 /* Attention path: 0 = automatic (a single fused kernel when dk == 64 and no panel holds
- * more than 512 vectors, else the four-kernel pipeline), 1 = always the four-kernel
+ * more than 2048 vectors -- one, two or four waves per (panel, head) for panels of up to 512,
+ * 1024, 2048 vectors -- else the four-kernel pipeline), 1 = always the four-kernel
  * pipeline SDDMM -> softmax -> repack -> SpMM, 2 = the fused kernel with one head per
- * workgroup even for token-major tensors.  All give the same result up to fp32 summation
+ * workgroup even for token-major tensors, 3 / 4 = the fused kernel with at least two / with
+ * four waves per (panel, head) whatever the panel length.  All give the same result up to fp32 summation
  * order in the softmax.  Process-wide; MC_EINVAL for other values. */
 int mc_set_attention_mode(int mode);
 

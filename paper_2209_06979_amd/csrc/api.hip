@@ -130,7 +130,7 @@ extern "C" int mc_set_sddmm_variant(int waves)
 
 extern "C" int mc_set_attention_mode(int mode)
 {
-    if (mode < 0 || mode > 2) return MC_EINVAL;
+    if (mode < 0 || mode > 4) return MC_EINVAL;
     g_attention_mode = mode;
     return MC_OK;
 }
@@ -447,8 +447,12 @@ extern "C" int mc_sparse_attention_bits(const void *Q_dev, const void *Km_dev, c
         f.score_scale = s_q * s_k / std::sqrt((float)dk); f.inv_s_p = 1.f / s_p; f.out_scale = s_p * s_v;
         f.P = mask->P; f.heads = heads;
         // neighbouring heads contiguous inside a token: two heads per workgroup, 128-byte gathers
-        const int hpg = (g_attention_mode == 0 && p_bits == 8 && head_stride == 64 && heads % 2 == 0) ? 2 : 1;
-        MC_HIP(launch_attention_fused(f, hpg, p_bits, qkv_bits, s));
+        // a wave keeps at most 8 chunks of scores in registers: longer panels are shared by 2 or 4 waves
+        int wpp = (mask->max_panel_chunks > 16) ? 4 : (mask->max_panel_chunks > 8 ? 2 : 1);
+        if (g_attention_mode == 3 && wpp < 2) wpp = 2;
+        if (g_attention_mode == 4) wpp = 4;
+        const int hpg = (g_attention_mode == 0 && wpp == 1 && p_bits == 8 && head_stride == 64 && heads % 2 == 0) ? 2 : 1;
+        MC_HIP(launch_attention_fused(f, hpg, wpp, p_bits, qkv_bits, s));
         return MC_OK;
     }
     return attention_pipeline(static_cast<const uint8_t *>(Q_dev), static_cast<const uint8_t *>(Km_dev),

@@ -75,11 +75,17 @@ __device__ __forceinline__ float row16_sum(float v)
 // widened in registers to an int8 worth 16 x its value (Section 4.4 without an int4 matrix unit):
 // the even elements of a 16-byte piece in lane groups 0 and 1, the odd ones in groups 2 and 3, so
 // the scores carry a factor 256 and the output a factor 16, removed by exact shifts.
-template <int MAXCH, int HPW, int PB, int QB>
-__global__ __launch_bounds__(64 * HPW, ((HPW == 1 && PB == 8) ? 4 : 3)) void attention_fused_kernel(AttnArgs a)
+// KS: waves that share one (panel, head) when a panel is longer than MAXCH chunks (HPW 1 only): wave
+// ks takes chunks ks, ks + KS, ...; the waves exchange their row maxima and row sums through LDS
+// and add up their partial output tiles at the end (three workgroup barriers in total).
+template <int MAXCH, int HPW, int PB, int QB, int KS>
+__global__ __launch_bounds__(64 * HPW * KS, ((HPW == 1 && PB == 8 && KS == 1) ? 4 : 3))
+void attention_fused_kernel(AttnArgs a)
 {
     static_assert(PB == 8 || (PB == 16 && HPW == 1), "16-bit codes: one head per workgroup");
     static_assert(QB == 8 || QB == 4, "Q, K, V are 8-bit or packed 4-bit");
+    static_assert(KS == 1 || HPW == 1, "chunks are shared between waves only in the one-head-per-workgroup form");
+    constexpr int NW = HPW * KS;         // waves per workgroup
     constexpr int PLANE = MAXCH * 512;   // bytes of one plane of codes, [slot][8 rows]
     constexpr int DK = 64;
     constexpr int DKB = DK * QB / 8; // bytes of one head's row
@@ -92,10 +98,14 @@ __global__ __launch_bounds__(64 * HPW, ((HPW == 1 && PB == 8) ? 4 : 3)) void att
     constexpr int NIB = (int)0xF0F0F0F0;
     constexpr int STG = 64 * ROWB;   // bytes of one stage
     constexpr int NST = HPW;         // stages: one for a lone wave, two when two waves share the chunks
-    __shared__ __attribute__((aligned(16))) char stage[NST * STG];         // chunks of gathered rows
-    __shared__ __attribute__((aligned(16))) char Pl_all[HPW * PLANE * (PB / 8)]; // codes, [plane][slot][8 rows], per wave
+    __shared__ __attribute__((aligned(16))) char stage_all[NST * STG * KS];  // chunks of gathered rows (KS > 1: one stage per wave)
+    __shared__ __attribute__((aligned(16))) char Pl_all[NW * PLANE * (PB / 8)]; // codes, [plane][slot][8 rows], per wave
+    __shared__ int xch[2][KS][8];                                             // row maxima / row sums of the KS waves
 
-    const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int w = (HPW > 1) ? wave : 0;   // head within the workgroup
+    const int ks = (KS > 1) ? wave : 0;   // share of the panel's chunks
+    char *stage = stage_all + ks * (NST * STG);
     const int j = lane & 15, g = lane >> 4;
     const int rg = lane / LPR, seg = lane % LPR;
     // Workgroups are handed to the 8 XCDs round-robin by linear id.  With id = panel * groups +
@@ -110,7 +120,8 @@ __global__ __launch_bounds__(64 * HPW, ((HPW == 1 && PB == 8) ? 4 : 3)) void att
     const int64_t goff = (int64_t)hgrp * HPW * a.in_head_stride; // first head of the group
     const uint8_t *Kg = a.Km + goff, *Vg = a.Vm + goff;
     float *Oh = a.O + (int64_t)head * a.head_stride + (int64_t)panel * 8 * a.token_stride;
-    char *Pl = Pl_all + w * (PLANE * (PB / 8));
+    char *Pl = Pl_all + wave * (PLANE * (PB / 8));
+    const int nloc = (nch > ks) ? (nch - ks + KS - 1) / KS : 0; // chunks of this wave: ks, ks + KS, ...
 
     // Q rows twice: in MFMA rows 0..7 (q_lo) and in rows 8..15 (q_hi)
     v4i q_lo = {0, 0, 0, 0}, q_hi = {0, 0, 0, 0};
@@ -132,7 +143,7 @@ __global__ __launch_bounds__(64 * HPW, ((HPW == 1 && PB == 8) ? 4 : 3)) void att
     unsigned segoff[NITW];
 #pragma unroll
     for (int i = 0; i < NITW; ++i) segoff[i] = (seg ^ ((NITW * w + i) & SWZ)) * 16;
-    const unsigned stage_u = lds_addr_uniform(stage);
+    const unsigned stage_u = lds_addr_uniform(stage);  // this wave's stage(s)
     const int32_t *myidx = idx + rg * NIT + NITW * w;
     const unsigned tstride = (unsigned)a.in_token_stride;
     // issue(c): this wave's copies of chunk c into stage c % NST, from the column indices held
@@ -143,13 +154,13 @@ __global__ __launch_bounds__(64 * HPW, ((HPW == 1 && PB == 8) ? 4 : 3)) void att
 #pragma unroll
         for (int i = 0; i < NITW; ++i)
             copy16_to_lds(base, __umul24(ixn[i], tstride) + segoff[i], stage_u + (c % NST) * STG + (NITW * w + i) * 1024);
-        ixn = *reinterpret_cast<const ixv_t *>(myidx + ((c + 1 < nch) ? c + 1 : c) * MC_CHUNK);
+        ixn = *reinterpret_cast<const ixv_t *>(myidx + ((c + KS < nch) ? c + KS : c) * MC_CHUNK);
     };
     auto start_pipeline = [&](const uint8_t *base) {
         if (HPW > 1) __builtin_amdgcn_s_barrier(); // both waves are done with the stages
-        if (nch > 0) {
-            ixn = *reinterpret_cast<const ixv_t *>(myidx);
-            issue(base, 0);
+        if (nloc > 0) {
+            ixn = *reinterpret_cast<const ixv_t *>(myidx + ks * MC_CHUNK);
+            issue(base, ks);
         }
     };
     // Makes chunk c readable.  HPW 1: the next chunk is issued by release() once this one has
@@ -163,9 +174,9 @@ __global__ __launch_bounds__(64 * HPW, ((HPW == 1 && PB == 8) ? 4 : 3)) void att
         }
     };
     auto release = [&](const uint8_t *base, int c) { // the reads of chunk c have been issued
-        if (HPW == 1 && c + 1 < nch) {
+        if (HPW == 1 && c + KS < nch) {
             lgkm_wait(); // ... and have returned: the one stage may be overwritten
-            issue(base, c + 1);
+            issue(base, c + KS);
         }
     };
 
@@ -188,15 +199,17 @@ __global__ __launch_bounds__(64 * HPW, ((HPW == 1 && PB == 8) ? 4 : 3)) void att
 #pragma unroll
     for (int pr = 0; pr < 2; ++pr) keep[pr] = (2 * pr + (g >> 1)) * 16 + j < tail;
     start_pipeline(Kg);
+    // (from here on c counts this wave's chunks; gc is the chunk's number in the panel)
     static_for<MAXCH>([&](auto C) {
-        constexpr int c = C, ST = (c % NST) * STG;
+        constexpr int c = C, ST = (KS > 1) ? 0 : (c % NST) * STG;
+        const int gc = ks + c * KS;
         sc[2 * c] = (v4i){0, 0, 0, 0};
         sc[2 * c + 1] = (v4i){0, 0, 0, 0};
-        if (c < nch) {
-            acquire(Kg, c);
+        if (c < nloc) {
+            acquire(Kg, gc);
             const v4i kA0 = *reinterpret_cast<const v4i *>(kaddr + ST), kB0 = *reinterpret_cast<const v4i *>(kaddr + ST + 256);
             const v4i kA1 = *reinterpret_cast<const v4i *>(kaddr + ST + 512), kB1 = *reinterpret_cast<const v4i *>(kaddr + ST + 768);
-            release(Kg, c);
+            release(Kg, gc);
             sc[2 * c] = __builtin_amdgcn_mfma_i32_16x16x64_i8(q_lo, kop(kA0), sc[2 * c], 0, 0, 0);
             sc[2 * c] = __builtin_amdgcn_mfma_i32_16x16x64_i8(q_hi, kop(kB0), sc[2 * c], 0, 0, 0);
             sc[2 * c + 1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(q_lo, kop(kA1), sc[2 * c + 1], 0, 0, 0);
@@ -205,7 +218,7 @@ __global__ __launch_bounds__(64 * HPW, ((HPW == 1 && PB == 8) ? 4 : 3)) void att
                 sc[2 * c] = sc[2 * c] >> 8;
                 sc[2 * c + 1] = sc[2 * c + 1] >> 8;
             }
-            if (c == nch - 1) {
+            if (gc == nch - 1) {
 #pragma unroll
                 for (int pr = 0; pr < 2; ++pr)
 #pragma unroll
@@ -229,18 +242,30 @@ __global__ __launch_bounds__(64 * HPW, ((HPW == 1 && PB == 8) ? 4 : 3)) void att
     for (int r = 0; r < 4; ++r) {
         imax[r] = row16_imax(imax[r]);
         imax[r] = max(imax[r], __shfl_xor(imax[r], 32, 64));
-        m2[r] = (float)imax[r] * scale2;
     }
+    if (KS > 1) { // row 4*(g&1) + r: lanes 0 and 16 publish, everybody reads all waves
+        if (lane == 0 || lane == 16) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) xch[0][ks][4 * (g & 1) + r] = imax[r];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int k = 0; k < KS; ++k) imax[r] = max(imax[r], xch[0][k][4 * (g & 1) + r]);
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) m2[r] = (float)imax[r] * scale2;
     float x[NPR][4];
     static_for<MAXCH>([&](auto C) {
         constexpr int c = C;
-        if (c < nch) {
+        if (c < nloc) {
 #pragma unroll
             for (int pr = 0; pr < 2; ++pr)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     float e = __builtin_amdgcn_exp2f(__builtin_fmaf((float)sc[2 * c + pr][r], scale2, -m2[r]));
-                    if (c == nch - 1) e = keep[pr] ? e : 0.f;
+                    if (ks + c * KS == nch - 1) e = keep[pr] ? e : 0.f;
                     x[2 * c + pr][r] = e;
                     srow[r] += e;
                 }
@@ -251,8 +276,22 @@ __global__ __launch_bounds__(64 * HPW, ((HPW == 1 && PB == 8) ? 4 : 3)) void att
     for (int r = 0; r < 4; ++r) {
         srow[r] = row16_sum(srow[r]);
         srow[r] += __shfl_xor(srow[r], 32, 64);
-        rinv[r] = a.inv_s_p / srow[r];
     }
+    if (KS > 1) { // every wave adds the partial sums in the same order: identical totals everywhere
+        if (lane == 0 || lane == 16) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) xch[1][ks][4 * (g & 1) + r] = __builtin_bit_cast(int, srow[r]);
+        }
+        __syncthreads();
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            srow[r] = 0.f;
+#pragma unroll
+            for (int k = 0; k < KS; ++k) srow[r] += __builtin_bit_cast(float, xch[1][k][4 * (g & 1) + r]);
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) rinv[r] = a.inv_s_p / srow[r];
     // ---- phase V: O = codes * V ------------------------------------------------------------------
     v4i o[4];
 #pragma unroll
@@ -271,7 +310,8 @@ __global__ __launch_bounds__(64 * HPW, ((HPW == 1 && PB == 8) ? 4 : 3)) void att
     }
     static_for<MAXCH>([&](auto C) {
         constexpr int c = C;
-        if (c < nch) {
+        const int gc = ks + c * KS;
+        if (c < nloc) {
             // Codes of this chunk's slots (tile*16 + j), rows 4*(g&1) .. +3: one 32-bit LDS write
             // per tile.  v_cvt_pk_u8_f32 rounds to nearest even, saturates to [0, 255] and drops
             // the byte into place; e * rinv cannot exceed 127 by more than rounding noise.
@@ -298,16 +338,16 @@ __global__ __launch_bounds__(64 * HPW, ((HPW == 1 && PB == 8) ? 4 : 3)) void att
                     *reinterpret_cast<unsigned *>(Pl + PLANE + slot * 8 + 4 * (g & 1)) = lo;
                 }
             }
-            acquire(Vg, c);
+            acquire(Vg, gc);
             // the codes, transposed to the MFMA row operand: row j < 8, slots g*16 .. +15
             const v2i p0 = lds_read_tr8(paddr[0] + c * 512), p1 = lds_read_tr8(paddr[1] + c * 512);
             v2i d[NITW][2];
 #pragma unroll
             for (int ct = 0; ct < NITW; ++ct) {
-                d[ct][0] = lds_read_tr8(stage + (c % NST) * STG + (vbase[0] ^ (ct * 16)));
-                d[ct][1] = lds_read_tr8(stage + (c % NST) * STG + (vbase[1] ^ (ct * 16)));
+                d[ct][0] = lds_read_tr8(stage + (KS > 1 ? 0 : (c % NST) * STG) + (vbase[0] ^ (ct * 16)));
+                d[ct][1] = lds_read_tr8(stage + (KS > 1 ? 0 : (c % NST) * STG) + (vbase[1] ^ (ct * 16)));
             }
-            release(Vg, c);
+            release(Vg, gc);
             v4i aop = {p0.x, p0.y, p1.x, p1.y};
             if (PB == 8 && j >= 8) aop = (v4i){0, 0, 0, 0};
 #pragma unroll
@@ -338,12 +378,21 @@ __global__ __launch_bounds__(64 * HPW, ((HPW == 1 && PB == 8) ? 4 : 3)) void att
             }
     }
     lgkm_wait();
-    __builtin_amdgcn_wave_barrier();
+    if (KS > 1) __syncthreads(); else __builtin_amdgcn_wave_barrier();
+    // 8 rows x 16 pieces of 4 columns; with KS waves the first 128 threads add up the partial tiles
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
-        const int piece = h * 64 + lane, row = piece >> 4, col = (piece & 15) * 4;
-        v4i sres = *reinterpret_cast<const v4i *>(&Ol[row * (DK + 4) + col]);
-        if (PB == 16) sres = (sres << 8) + *reinterpret_cast<const v4i *>(&Ol[(row + 8) * (DK + 4) + col]);
+        const int piece = (KS > 1) ? (int)threadIdx.x + h * 64 * KS : h * 64 + lane;
+        if (piece >= 128) continue;
+        const int row = piece >> 4, col = (piece & 15) * 4;
+        v4i sres = {0, 0, 0, 0}, slo = {0, 0, 0, 0};
+#pragma unroll
+        for (int k = 0; k < KS; ++k) {
+            const int *Ok = (KS > 1) ? reinterpret_cast<const int *>(Pl_all + k * (PLANE * (PB / 8))) : Ol;
+            sres += *reinterpret_cast<const v4i *>(&Ok[row * (DK + 4) + col]);
+            if (PB == 16) slo += *reinterpret_cast<const v4i *>(&Ok[(row + 8) * (DK + 4) + col]);
+        }
+        if (PB == 16) sres = (sres << 8) + slo;
         const v4f f = {sres.x * a.out_scale, sres.y * a.out_scale, sres.z * a.out_scale, sres.w * a.out_scale};
         *reinterpret_cast<v4f *>(Oh + (int64_t)row * a.token_stride + col) = f;
     }
@@ -351,23 +400,29 @@ __global__ __launch_bounds__(64 * HPW, ((HPW == 1 && PB == 8) ? 4 : 3)) void att
 
 } // namespace
 
-int attention_fused_max_vectors() { return 8 * 64; }
+int attention_fused_max_vectors() { return 4 * 8 * 64; }
 
-hipError_t launch_attention_fused(const AttnArgs &a, int heads_per_group, int p_bits, int qkv_bits, hipStream_t s)
+template <int PB, int QB> hipError_t launch_pq(const AttnArgs &a, int heads_per_group, int waves_per_panel, hipStream_t s)
 {
-    if (a.P == 0 || a.heads == 0) return hipSuccess;
-    if (p_bits == 16) {
-        dim3 grid((unsigned)a.P * (unsigned)a.heads), block(64);
-        if (qkv_bits == 4) hipLaunchKernelGGL((attention_fused_kernel<8, 1, 16, 4>), grid, block, 0, s, a);
-        else hipLaunchKernelGGL((attention_fused_kernel<8, 1, 16, 8>), grid, block, 0, s, a);
-    } else if (heads_per_group == 2) {
-        dim3 grid((unsigned)a.P * (unsigned)(a.heads / 2)), block(128);
-        if (qkv_bits == 4) hipLaunchKernelGGL((attention_fused_kernel<8, 2, 8, 4>), grid, block, 0, s, a);
-        else hipLaunchKernelGGL((attention_fused_kernel<8, 2, 8, 8>), grid, block, 0, s, a);
+    if (waves_per_panel == 4) {
+        hipLaunchKernelGGL((attention_fused_kernel<8, 1, PB, QB, 4>), dim3((unsigned)a.P * (unsigned)a.heads), dim3(256), 0, s, a);
+    } else if (waves_per_panel == 2) {
+        hipLaunchKernelGGL((attention_fused_kernel<8, 1, PB, QB, 2>), dim3((unsigned)a.P * (unsigned)a.heads), dim3(128), 0, s, a);
+    } else if (heads_per_group == 2 && PB == 8) {
+        hipLaunchKernelGGL((attention_fused_kernel<8, 2, 8, QB, 1>), dim3((unsigned)a.P * (unsigned)(a.heads / 2)), dim3(128), 0, s, a);
     } else {
-        dim3 grid((unsigned)a.P * (unsigned)a.heads), block(64);
-        if (qkv_bits == 4) hipLaunchKernelGGL((attention_fused_kernel<8, 1, 8, 4>), grid, block, 0, s, a);
-        else hipLaunchKernelGGL((attention_fused_kernel<8, 1, 8, 8>), grid, block, 0, s, a);
+        hipLaunchKernelGGL((attention_fused_kernel<8, 1, PB, QB, 1>), dim3((unsigned)a.P * (unsigned)a.heads), dim3(64), 0, s, a);
     }
     return hipGetLastError();
+}
+
+// waves_per_panel: 1, 2 or 4 waves share the chunks of one (panel, head); a wave holds at most 8 chunks
+// of scores in registers, so a panel may have up to 512 * waves_per_panel vectors.
+hipError_t launch_attention_fused(const AttnArgs &a, int heads_per_group, int waves_per_panel, int p_bits, int qkv_bits,
+                                  hipStream_t s)
+{
+    if (a.P == 0 || a.heads == 0) return hipSuccess;
+    if (p_bits == 16) return (qkv_bits == 4) ? launch_pq<16, 4>(a, 1, waves_per_panel, s) : launch_pq<16, 8>(a, 1, waves_per_panel, s);
+    return (qkv_bits == 4) ? launch_pq<8, 4>(a, heads_per_group, waves_per_panel, s)
+                           : launch_pq<8, 8>(a, heads_per_group, waves_per_panel, s);
 }

@@ -90,5 +90,6 @@ hipError_t launch_sddmm(int bits, const SddmmArgs &a, int waves, hipStream_t s);
 hipError_t launch_softmax(const SoftmaxArgs &a, hipStream_t s);
 hipError_t launch_repack(const RepackArgs &a, hipStream_t s);
 // heads_per_group 2 needs head_stride == 64 (token-major layout) and an even head count
-hipError_t launch_attention_fused(const AttnArgs &a, int heads_per_group, int p_bits, int qkv_bits, hipStream_t s);
+hipError_t launch_attention_fused(const AttnArgs &a, int heads_per_group, int waves_per_panel, int p_bits, int qkv_bits,
+                                  hipStream_t s);
 int attention_fused_max_vectors(); // longest panel (in vectors) the fused kernel accepts

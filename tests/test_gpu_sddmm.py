@@ -158,7 +158,24 @@ def test_attention_small(mode, token_major):
     _attention_check(2, 1024, 64, 0.6, 1202, mode, token_major)   # 410 vectors per panel: 7 chunks, ragged tail
     _attention_check(3, 1024, 64, 0.8, 1205, mode, token_major)   # odd head count: one head per workgroup
     _attention_check(2, 2048, 64, 0.75, 1203, mode, token_major)  # 512 vectors: the longest panel the fused kernel takes
-    _attention_check(1, 2048, 64, 0.7, 1204, mode, token_major)   # 614 vectors: falls back to the pipeline
+    _attention_check(1, 2048, 64, 0.7, 1204, mode, token_major)   # 614 vectors: two waves share a (panel, head)
+
+
+@pytest.mark.parametrize("token_major", [False, True])
+@pytest.mark.parametrize("mode", [2, 3, 4])
+def test_attention_forced_fused_variants(mode, token_major):
+    """One head per workgroup (2) and two / four waves per (panel, head) (3, 4) on short and long panels."""
+    _attention_check(2, 256, 64, 0.75, 1210, mode, token_major)   # one chunk: most waves of a panel have nothing to do
+    _attention_check(3, 1024, 64, 0.6, 1211, mode, token_major)   # 7 chunks, ragged tail
+    _attention_check(2, 2048, 64, 0.75, 1212, mode, token_major)  # 8 chunks
+
+
+@pytest.mark.parametrize("token_major", [False, True])
+def test_attention_long_panels(token_major):
+    _attention_check(2, 2048, 64, 0.6, 1220, 0, token_major)      # 819 vectors (13 chunks): two waves per (panel, head)
+    _attention_check(1, 2048, 64, 0.4, 1221, 0, token_major)      # 1229 vectors (20 chunks): four waves
+    _attention_check(1, 2048, 64, 0.0, 1222, 0, token_major)      # 2048 vectors (32 chunks): the longest fused panel
+    _attention_check(1, 4096, 64, 0.45, 1223, 0, token_major)     # 2253 vectors: the kernel pipeline
 
 
 @pytest.mark.parametrize("token_major", [False, True])

@@ -226,6 +226,14 @@ def test_attention_variants_config5_shape(p_bits, qkv_bits, mode):
     _attention_variant_check(8, 4096, 64, 0.9, wl.seed_for(5, 1), p_bits, qkv_bits, mode=mode)
 
 
+@pytest.mark.parametrize("p_bits,qkv_bits", [(16, 8), (8, 4), (16, 4)])
+def test_attention_variants_long_panels_and_forced_wave_counts(p_bits, qkv_bits):
+    _attention_variant_check(2, 2048, 64, 0.6, 4300, p_bits, qkv_bits)            # 13 chunks: two waves per (panel, head)
+    _attention_variant_check(1, 2048, 64, 0.3, 4301, p_bits, qkv_bits)            # 23 chunks: four waves
+    _attention_variant_check(2, 1024, 64, 0.6, 4302, p_bits, qkv_bits, mode=3)    # 7 chunks on two waves
+    _attention_variant_check(2, 256, 64, 0.75, 4303, p_bits, qkv_bits, True, 4)   # one chunk on four waves
+
+
 def test_attention_16b8b_ragged_rows():
     """16-bit codes in the fused kernel with panels of very different lengths (empty ones give zeros)."""
     import torch
