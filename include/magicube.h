@@ -229,6 +229,16 @@ int mc_sparse_attention_bits(const void *Q_dev, const void *Km_dev, const void *
                              int qkv_bits, float s_q, float s_k, float s_v, float s_p, float *O_dev,
                              void *workspace_dev, size_t workspace_bytes, void *stream);
 
+/* The layer for a batch of inputs that share the mask (the end-to-end runs of Section 5.3 use
+ * batches of 2 and 8): element (b, h, l, d) sits at b*batch_stride + h*head_stride +
+ * l*token_stride + d in all four tensors (strides in elements, whole 16-byte pieces), batch
+ * <= 65535.  One launch of the fused kernel covers the whole batch; the kernel pipeline runs
+ * the items one after the other through the same workspace (sized for ONE item). */
+int mc_sparse_attention_batched(const void *Q_dev, const void *Km_dev, const void *Vm_dev, int batch, int heads, int L,
+                                int dk, int64_t batch_stride, int64_t head_stride, int64_t token_stride,
+                                const mc_mat *mask, int p_bits, int qkv_bits, float s_q, float s_k, float s_v,
+                                float s_p, float *O_dev, void *workspace_dev, size_t workspace_bytes, void *stream);
+
 /* ------------------------------------------------------------------------------------
  * Tuning knob (not needed for correctness): selects the SpMM tile variant.
  *   bytes_per_row_tile  0 = automatic, else 64, 128 or 256 bytes of a B row per workgroup

@@ -74,12 +74,15 @@ def _load() -> ctypes.CDLL:
                                            c_void_p, c_size_t, c_void_p]
     L.mc_probe_gather_sink_len.argtypes = [c_void_p, c_int, c_int]; L.mc_probe_gather_sink_len.restype = c_int64
     L.mc_probe_gather.argtypes = [c_void_p, c_void_p, c_int, c_int, c_int, c_void_p, c_void_p]
+    L.mc_sparse_attention_batched.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int64, c_int64,
+                                              c_int64, c_void_p, c_int, c_int, c_float, c_float, c_float, c_float,
+                                              c_void_p, c_void_p, c_size_t, c_void_p]
     L.mc_set_spmm_variant.argtypes = [c_int, c_int]
     L.mc_set_attention_mode.argtypes = [c_int]
     L.mc_set_sddmm_variant.argtypes = [c_int]
     for name in ("mc_layout_query", "mc_pack_host", "mc_unpack_host", "mc_mat_create", "mc_mat_set_values_device",
                  "mc_mat_info", "mc_spmm", "mc_sddmm", "mc_sparse_softmax", "mc_sparse_softmax_bits", "mc_sparse_attention",
-                 "mc_sparse_attention_strided", "mc_sparse_attention_bits", "mc_probe_gather",
+                 "mc_sparse_attention_strided", "mc_sparse_attention_bits", "mc_sparse_attention_batched", "mc_probe_gather",
                  "mc_set_spmm_variant", "mc_set_attention_mode", "mc_set_sddmm_variant"):
         getattr(L, name).restype = c_int
     return L
@@ -258,36 +261,34 @@ def attention_workspace_bytes(heads: int, mask: SparseMatrix, p_bits: int = 8) -
 
 def sparse_attention(Q8, K8, V8, mask: SparseMatrix, s_q, s_k, s_v, s_p, out=None, workspace=None,
                      p_bits: int = 8, qkv_bits: int = 8):
-    """Quantized sparse self-attention; Q8/K8/V8: (heads, L, dk) int8 device tensors, or for
-    qkv_bits=4 (heads, L, dk/2) uint8 tensors with two 4-bit values per byte.  p_bits is the
-    width of the re-quantised softmax output (8 or 16).
+    """Quantized sparse self-attention; Q8/K8/V8: (heads, L, dk) or (batch, heads, L, dk) int8
+    device tensors, or for qkv_bits=4 uint8 tensors of half the last dimension with two 4-bit
+    values per byte.  p_bits is the width of the re-quantised softmax output (8 or 16).
 
     Any layout with unit stride along dk is accepted as long as the three tensors (and
     ``out``) share it; a (heads, L, dk) view of a token-major (L, heads, dk) buffer, i.e.
     ``x.permute(1, 0, 2)``, selects the fast two-heads-per-request path.
     """
     epb = 8 // qkv_bits                       # elements per byte
-    heads, L, dkb = Q8.shape
+    batched = Q8.dim() == 4
+    batch = Q8.shape[0] if batched else 1
+    heads, L, dkb = Q8.shape[-3:]
     dk = dkb * epb
-    hs, ts = Q8.stride(0) * epb, Q8.stride(1) * epb   # strides in elements
+    st = tuple(x * epb for x in Q8.stride()[:-1])     # strides in elements
+    bs, hs, ts = (st if batched else (0,) + st)
     for t in (Q8, K8, V8):
-        assert t.is_cuda and t.element_size() == 1 and t.shape == Q8.shape and t.stride() == Q8.stride() and t.stride(2) == 1
+        assert t.is_cuda and t.element_size() == 1 and t.shape == Q8.shape and t.stride() == Q8.stride() and t.stride(-1) == 1
+    oshape = tuple(Q8.shape[:-1]) + (dk,)
     if out is None:
-        # same layout as the inputs (the two dense ones; anything else needs an explicit ``out``)
-        if (hs, ts) == (dk, heads * dk):
-            out = torch.empty((L, heads, dk), dtype=torch.float32, device=Q8.device).permute(1, 0, 2)
-        elif (hs, ts) == (L * dk, dk):
-            out = torch.empty((heads, L, dk), dtype=torch.float32, device=Q8.device)
-        else:
-            raise MagicubeError(MC_EINVAL, "sparse_attention(out is required for this layout)")
-    assert out.is_cuda and out.dtype == torch.float32 and out.shape == (heads, L, dk) and out.stride() == (hs, ts, 1)
+        out = torch.empty_strided(oshape, st + (1,), dtype=torch.float32, device=Q8.device)   # the inputs' layout
+    assert out.is_cuda and out.dtype == torch.float32 and out.shape == oshape and out.stride() == st + (1,)
     need = attention_workspace_bytes(heads, mask, p_bits)
     if workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=Q8.device)
     assert workspace.is_cuda and workspace.is_contiguous()
-    _check(lib.mc_sparse_attention_bits(Q8.data_ptr(), K8.data_ptr(), V8.data_ptr(), heads, L, dk, hs, ts,
-                                        mask.handle, p_bits, qkv_bits, float(s_q), float(s_k), float(s_v), float(s_p),
-                                        out.data_ptr(), workspace.data_ptr(),
-                                        workspace.numel() * workspace.element_size(), _stream()),
-           "mc_sparse_attention_bits")
+    _check(lib.mc_sparse_attention_batched(Q8.data_ptr(), K8.data_ptr(), V8.data_ptr(), batch, heads, L, dk, bs, hs, ts,
+                                           mask.handle, p_bits, qkv_bits, float(s_q), float(s_k), float(s_v), float(s_p),
+                                           out.data_ptr(), workspace.data_ptr(),
+                                           workspace.numel() * workspace.element_size(), _stream()),
+           "mc_sparse_attention_batched")
     return out

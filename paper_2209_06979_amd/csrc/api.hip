@@ -421,16 +421,27 @@ extern "C" int mc_sparse_attention_bits(const void *Q_dev, const void *Km_dev, c
                                         int p_bits, int qkv_bits, float s_q, float s_k, float s_v, float s_p,
                                         float *O_dev, void *workspace_dev, size_t workspace_bytes, void *stream)
 {
+    return mc_sparse_attention_batched(Q_dev, Km_dev, Vm_dev, 1, heads, L, dk, 0, head_stride, token_stride, mask,
+                                       p_bits, qkv_bits, s_q, s_k, s_v, s_p, O_dev, workspace_dev, workspace_bytes,
+                                       stream);
+}
+
+extern "C" int mc_sparse_attention_batched(const void *Q_dev, const void *Km_dev, const void *Vm_dev, int batch,
+                                           int heads, int L, int dk, int64_t batch_stride, int64_t head_stride,
+                                           int64_t token_stride, const mc_mat *mask, int p_bits, int qkv_bits,
+                                           float s_q, float s_k, float s_v, float s_p, float *O_dev,
+                                           void *workspace_dev, size_t workspace_bytes, void *stream)
+{
     if (!Q_dev || !Km_dev || !Vm_dev || !mask || !O_dev || !workspace_dev) return MC_EINVAL;
     if ((p_bits != 8 && p_bits != 16) || (qkv_bits != 8 && qkv_bits != 4)) return MC_EUNSUPPORTED;
     const int epp = 128 / qkv_bits; // elements per 16-byte piece
-    if (heads <= 0 || L <= 0 || dk <= 0 || dk % epp != 0) return MC_EINVAL;
+    if (batch <= 0 || batch > 65535 || heads <= 0 || L <= 0 || dk <= 0 || dk % epp != 0) return MC_EINVAL;
     if (mask->M != L || mask->K != L || mask->V != 8) return MC_EINVAL;
     if (!(s_p > 0.f) || !std::isfinite(s_q * s_k * s_v / s_p)) return MC_EINVAL;
-    if (token_stride < dk || head_stride < dk) return MC_EINVAL;
+    if (token_stride < dk || head_stride < dk || (batch > 1 && batch_stride < dk)) return MC_EINVAL;
     if ((int64_t)(L - 1) * token_stride + (int64_t)(heads - 1) * head_stride + dk > (int64_t)INT32_MAX) return MC_EINVAL;
     if (L > (1 << 24) || token_stride >= (1 << 24)) return MC_EINVAL; // kernels use 24-bit multiplies
-    if (token_stride % epp != 0 || head_stride % epp != 0) return MC_EALIGN;
+    if (token_stride % epp != 0 || head_stride % epp != 0 || batch_stride % epp != 0) return MC_EALIGN;
     if (!aligned16(Q_dev) || !aligned16(Km_dev) || !aligned16(Vm_dev) || !aligned16(O_dev)) return MC_EALIGN;
     if ((reinterpret_cast<uintptr_t>(workspace_dev) & 255u) != 0) return MC_EALIGN;
     if (workspace_bytes < attn_layout(heads, mask, p_bits).total) return MC_ENOMEM;
@@ -442,21 +453,29 @@ extern "C" int mc_sparse_attention_bits(const void *Q_dev, const void *Km_dev, c
         f.panel_ptr = mask->d_panel_ptr; f.slot_idx = mask->d_slot_idx;
         f.Q = static_cast<const uint8_t *>(Q_dev); f.Km = static_cast<const uint8_t *>(Km_dev);
         f.Vm = static_cast<const uint8_t *>(Vm_dev); f.O = O_dev;
-        f.head_stride = head_stride; f.token_stride = token_stride;
+        f.head_stride = head_stride; f.token_stride = token_stride; f.batch_stride = batch_stride;
         f.in_head_stride = head_stride * qkv_bits / 8; f.in_token_stride = token_stride * qkv_bits / 8;
+        f.in_batch_stride = batch_stride * qkv_bits / 8;
         f.score_scale = s_q * s_k / std::sqrt((float)dk); f.inv_s_p = 1.f / s_p; f.out_scale = s_p * s_v;
-        f.P = mask->P; f.heads = heads;
-        // neighbouring heads contiguous inside a token: two heads per workgroup, 128-byte gathers
+        f.P = mask->P; f.heads = heads; f.batch = batch;
         // a wave keeps at most 8 chunks of scores in registers: longer panels are shared by 2 or 4 waves
         int wpp = (mask->max_panel_chunks > 16) ? 4 : (mask->max_panel_chunks > 8 ? 2 : 1);
         if (g_attention_mode == 3 && wpp < 2) wpp = 2;
         if (g_attention_mode == 4) wpp = 4;
+        // neighbouring heads contiguous inside a token: two heads per workgroup, 128-byte gathers
         const int hpg = (g_attention_mode == 0 && wpp == 1 && p_bits == 8 && head_stride == 64 && heads % 2 == 0) ? 2 : 1;
         MC_HIP(launch_attention_fused(f, hpg, wpp, p_bits, qkv_bits, s));
         return MC_OK;
     }
-    return attention_pipeline(static_cast<const uint8_t *>(Q_dev), static_cast<const uint8_t *>(Km_dev),
-                              static_cast<const uint8_t *>(Vm_dev), heads, dk, qkv_bits, p_bits,
-                              head_stride * qkv_bits / 8, token_stride * qkv_bits / 8, head_stride, token_stride, mask,
-                              s_q, s_k, s_v, s_p, O_dev, workspace_dev, s);
+    // the kernel pipeline runs the batch items one after the other through the same workspace
+    for (int b = 0; b < batch; ++b) {
+        const int64_t ib = (int64_t)b * batch_stride * qkv_bits / 8;
+        const int rc = attention_pipeline(static_cast<const uint8_t *>(Q_dev) + ib, static_cast<const uint8_t *>(Km_dev) + ib,
+                                          static_cast<const uint8_t *>(Vm_dev) + ib, heads, dk, qkv_bits, p_bits,
+                                          head_stride * qkv_bits / 8, token_stride * qkv_bits / 8, head_stride,
+                                          token_stride, mask, s_q, s_k, s_v, s_p, O_dev + (int64_t)b * batch_stride,
+                                          workspace_dev, s);
+        if (rc != MC_OK) return rc;
+    }
+    return MC_OK;
 }

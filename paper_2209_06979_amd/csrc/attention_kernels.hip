@@ -118,15 +118,16 @@ void attention_fused_kernel(AttnArgs a)
     const int nch = (n + MC_CHUNK - 1) / MC_CHUNK;
     const int32_t *idx = a.slot_idx + s0;
     const int64_t goff = (int64_t)hgrp * HPW * a.in_head_stride; // first head of the group
-    const uint8_t *Kg = a.Km + goff, *Vg = a.Vm + goff;
-    float *Oh = a.O + (int64_t)head * a.head_stride + (int64_t)panel * 8 * a.token_stride;
+    const int64_t boff = (int64_t)blockIdx.y * a.in_batch_stride; // batch item
+    const uint8_t *Kg = a.Km + boff + goff, *Vg = a.Vm + boff + goff;
+    float *Oh = a.O + (int64_t)blockIdx.y * a.batch_stride + (int64_t)head * a.head_stride + (int64_t)panel * 8 * a.token_stride;
     char *Pl = Pl_all + wave * (PLANE * (PB / 8));
     const int nloc = (nch > ks) ? (nch - ks + KS - 1) / KS : 0; // chunks of this wave: ks, ks + KS, ...
 
     // Q rows twice: in MFMA rows 0..7 (q_lo) and in rows 8..15 (q_hi)
     v4i q_lo = {0, 0, 0, 0}, q_hi = {0, 0, 0, 0};
     {
-        const uint8_t *qrow = a.Q + (int64_t)head * a.in_head_stride + (int64_t)(panel * 8 + (j & 7)) * a.in_token_stride;
+        const uint8_t *qrow = a.Q + boff + (int64_t)head * a.in_head_stride + (int64_t)(panel * 8 + (j & 7)) * a.in_token_stride;
         v4i qv;
         if (QB == 8) {
             qv = *reinterpret_cast<const v4i *>(qrow + g * 16);
@@ -405,13 +406,13 @@ int attention_fused_max_vectors() { return 4 * 8 * 64; }
 template <int PB, int QB> hipError_t launch_pq(const AttnArgs &a, int heads_per_group, int waves_per_panel, hipStream_t s)
 {
     if (waves_per_panel == 4) {
-        hipLaunchKernelGGL((attention_fused_kernel<8, 1, PB, QB, 4>), dim3((unsigned)a.P * (unsigned)a.heads), dim3(256), 0, s, a);
+        hipLaunchKernelGGL((attention_fused_kernel<8, 1, PB, QB, 4>), dim3((unsigned)a.P * (unsigned)a.heads, (unsigned)a.batch), dim3(256), 0, s, a);
     } else if (waves_per_panel == 2) {
-        hipLaunchKernelGGL((attention_fused_kernel<8, 1, PB, QB, 2>), dim3((unsigned)a.P * (unsigned)a.heads), dim3(128), 0, s, a);
+        hipLaunchKernelGGL((attention_fused_kernel<8, 1, PB, QB, 2>), dim3((unsigned)a.P * (unsigned)a.heads, (unsigned)a.batch), dim3(128), 0, s, a);
     } else if (heads_per_group == 2 && PB == 8) {
-        hipLaunchKernelGGL((attention_fused_kernel<8, 2, 8, QB, 1>), dim3((unsigned)a.P * (unsigned)(a.heads / 2)), dim3(128), 0, s, a);
+        hipLaunchKernelGGL((attention_fused_kernel<8, 2, 8, QB, 1>), dim3((unsigned)a.P * (unsigned)(a.heads / 2), (unsigned)a.batch), dim3(128), 0, s, a);
     } else {
-        hipLaunchKernelGGL((attention_fused_kernel<8, 1, PB, QB, 1>), dim3((unsigned)a.P * (unsigned)a.heads), dim3(64), 0, s, a);
+        hipLaunchKernelGGL((attention_fused_kernel<8, 1, PB, QB, 1>), dim3((unsigned)a.P * (unsigned)a.heads, (unsigned)a.batch), dim3(64), 0, s, a);
     }
     return hipGetLastError();
 }
@@ -421,7 +422,7 @@ template <int PB, int QB> hipError_t launch_pq(const AttnArgs &a, int heads_per_
 hipError_t launch_attention_fused(const AttnArgs &a, int heads_per_group, int waves_per_panel, int p_bits, int qkv_bits,
                                   hipStream_t s)
 {
-    if (a.P == 0 || a.heads == 0) return hipSuccess;
+    if (a.P == 0 || a.heads == 0 || a.batch == 0) return hipSuccess;
     if (p_bits == 16) return (qkv_bits == 4) ? launch_pq<16, 4>(a, 1, waves_per_panel, s) : launch_pq<16, 8>(a, 1, waves_per_panel, s);
     return (qkv_bits == 4) ? launch_pq<8, 4>(a, heads_per_group, waves_per_panel, s)
                            : launch_pq<8, 8>(a, heads_per_group, waves_per_panel, s);

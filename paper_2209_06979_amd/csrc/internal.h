@@ -77,8 +77,9 @@ struct AttnArgs {
     float *O;
     int64_t head_stride, token_stride;       // elements of O
     int64_t in_head_stride, in_token_stride; // bytes of Q, Km, Vm
+    int64_t batch_stride, in_batch_stride;   // between batch items: elements of O, bytes of Q, Km, Vm
     float score_scale, inv_s_p, out_scale;
-    int P, heads;
+    int P, heads, batch;
 };
 
 hipError_t launch_spmm(mc_prec prec, const SpmmArgs &a, int bnb, int waves, hipStream_t s);

@@ -279,3 +279,36 @@ def test_sparse_softmax_16_bit_codes():
         assert (np.abs(diff[amb]) <= 1).all()
         assert amb.mean() < 0.05
     mask.close()
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("p_bits,qkv_bits", [(8, 8), (16, 8), (8, 4)])
+def test_attention_batched_equals_item_by_item(p_bits, qkv_bits, mode):
+    """A batch sharing one mask, in the (batch, L, heads, dk) layout of a projection's output and in the
+    contiguous (batch, heads, L, dk) one: every item must equal the single-item call bit for bit."""
+    import torch
+    from paper_2209_06979_amd import binding as mc
+    B, heads, L, dk, V = 3, 4, 512, 64, 8
+    c = wl.attention_case(B * heads, L, dk, V, 0.8, 4400)
+    quant = wl.quantize_inputs_int4 if qkv_bits == 4 else wl.quantize_inputs_int8
+    (q, s_q), (k, s_k), (v, s_v) = (quant(c[n]) for n in "qkv")
+    s_p = np.float32(1.0 / (32639.0 if p_bits == 16 else 127.0))
+    mask = mc.SparseMatrix(L, L, V, c["row_ptr"], c["col_idx"])
+    mc.set_attention_mode(mode)
+    try:
+        for token_major in (False, True):
+            def dev(t):
+                x = torch.from_numpy(np.ascontiguousarray(t)).cuda().reshape(B, heads, L, -1)
+                return x.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3) if token_major else x
+            qd, kd, vd = dev(q), dev(k), dev(v)
+            print(f"batched attention {p_bits}b-{qkv_bits}b mode={mode} token_major={token_major}", flush=True)
+            O = mc.sparse_attention(qd, kd, vd, mask, s_q, s_k, s_v, s_p, p_bits=p_bits, qkv_bits=qkv_bits)
+            torch.cuda.synchronize()
+            assert O.shape == (B, heads, L, dk) and bool(torch.isfinite(O).all())
+            for b in range(B):
+                Ob = mc.sparse_attention(qd[b], kd[b], vd[b], mask, s_q, s_k, s_v, s_p, p_bits=p_bits, qkv_bits=qkv_bits)
+                torch.cuda.synchronize()
+                assert torch.equal(O[b], Ob), b
+    finally:
+        mc.set_attention_mode(0)
+        mask.close()
