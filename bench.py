@@ -249,6 +249,7 @@ def main():
                    "launch": "eager" if args.eager else f"hip_graph x{spg} steps", "kernels_in_step": [k["name"] for k in kernels]},
         "headline_spmm_l8r8": dict(per_kernel.get("spmm_L8R8") or {}, **((extras or {}).get("headline") or {})),
         "beyond_the_step": (extras or {}).get("wider_precisions"),
+        "layer_at_inference_shapes": (extras or {}).get("layer_at_inference_shapes"),
         "per_kernel": per_kernel,
         "format_build_s": round(format_build_s, 3),
         "roofline": roofline,
@@ -346,6 +347,26 @@ def measure_extras(mc, torch, prob, stream, reps, up):
         wide[name] = dict(us=round(us, 2), eff_tops=round(ops / us / 1e6, 1))
     amask.close()
     out["wider_precisions"] = wide
+
+    # The layer at the shapes of the paper's end-to-end latency figure (Section 5.3: 4 / 8 heads, sequence
+    # 4096 / 8192, batch 2 / 8, sparsity 0.9 / 0.95, head dimension 64), one launch per batch.
+    shapes = {}
+    for L, heads, batch, sp in ((4096, 8, 8, 0.9), (8192, 4, 8, 0.9), (8192, 4, 2, 0.95)):
+        c = wl.attention_case(1, L, DK, V, sp, wl.seed_for(5, L + heads + batch))
+        m = mc.SparseMatrix(L, L, V, c["row_ptr"], c["col_idx"])
+        x = wl.normal_fp32((batch, heads, L, DK), wl.seed_for(5, 7))
+        O = torch.empty((batch, heads, L, DK), dtype=torch.float32, device="cuda")
+        for name, p_bits, qkv_bits in (("8b-8b", 8, 8), ("16b-8b", 16, 8), ("8b-4b", 8, 4)):
+            xq, sx = (wl.quantize_inputs_int4 if qkv_bits == 4 else wl.quantize_inputs_int8)(x)
+            q = up(xq)                                  # the same tensor serves as Q, K and V: timing only
+            ws = torch.empty(mc.attention_workspace_bytes(heads, m, p_bits), dtype=torch.uint8, device="cuda")
+            s_p = np.float32(1.0 / (32639.0 if p_bits == 16 else 127.0))
+            us = time_graph(torch, stream, [lambda: mc.sparse_attention(q, q, q, m, sx, sx, sx, s_p, out=O, workspace=ws,
+                                                                        p_bits=p_bits, qkv_bits=qkv_bits)] * 20)
+            ops = batch * heads * 2 * (2 * m.nvec * V * DK)
+            shapes[f"L{L}_h{heads}_b{batch}_s{sp}_{name}"] = dict(us=round(us, 1), eff_tops=round(ops / us / 1e6, 1))
+        m.close()
+    out["layer_at_inference_shapes"] = shapes
     return out
 
 
