@@ -87,6 +87,8 @@ void attention_fused_kernel(AttnArgs a)
     static_assert(KS == 1 || HPW == 1, "chunks are shared between waves only in the one-head-per-workgroup form");
     constexpr int NW = HPW * KS;         // waves per workgroup
     constexpr int PLANE = MAXCH * 512;   // bytes of one plane of codes, [slot][8 rows]
+    constexpr int OTILE = (PB == 16 ? 16 : 8) * (64 + 4) * 4;                       // a wave's output tile, staged in the same area
+    constexpr int PLB = (PLANE * (PB / 8) > OTILE) ? PLANE * (PB / 8) : OTILE;      // bytes of that area
     constexpr int DK = 64;
     constexpr int DKB = DK * QB / 8; // bytes of one head's row
     constexpr int NPR = MAXCH * 2;   // pairs of score tiles
@@ -99,7 +101,8 @@ void attention_fused_kernel(AttnArgs a)
     constexpr int STG = 64 * ROWB;   // bytes of one stage
     constexpr int NST = HPW;         // stages: one for a lone wave, two when two waves share the chunks
     __shared__ __attribute__((aligned(16))) char stage_all[NST * STG * KS];  // chunks of gathered rows (KS > 1: one stage per wave)
-    __shared__ __attribute__((aligned(16))) char Pl_all[NW * PLANE * (PB / 8)]; // codes, [plane][slot][8 rows], per wave
+    __shared__ __attribute__((aligned(16))) char Pl_all[NW * PLB]; // codes, [plane][slot][8 rows], per wave
+    __shared__ __attribute__((aligned(8))) char zeros[8];                      // row operand of the MFMA rows that carry no codes
     __shared__ int xch[2][KS][8];                                             // row maxima / row sums of the KS waves
 
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -121,8 +124,9 @@ void attention_fused_kernel(AttnArgs a)
     const int64_t boff = (int64_t)blockIdx.y * a.in_batch_stride; // batch item
     const uint8_t *Kg = a.Km + boff + goff, *Vg = a.Vm + boff + goff;
     float *Oh = a.O + (int64_t)blockIdx.y * a.batch_stride + (int64_t)head * a.head_stride + (int64_t)panel * 8 * a.token_stride;
-    char *Pl = Pl_all + wave * (PLANE * (PB / 8));
+    char *Pl = Pl_all + wave * PLB;
     const int nloc = (nch > ks) ? (nch - ks + KS - 1) / KS : 0; // chunks of this wave: ks, ks + KS, ...
+    if (PB == 8 && lane < 2) reinterpret_cast<int *>(zeros)[lane] = 0; // every wave writes the same zeros: no race that matters
 
     // Q rows twice: in MFMA rows 0..7 (q_lo) and in rows 8..15 (q_hi)
     v4i q_lo = {0, 0, 0, 0}, q_hi = {0, 0, 0, 0};
@@ -183,7 +187,7 @@ void attention_fused_kernel(AttnArgs a)
 
     // ---- phase K: scores; lane (j, g) owns row 4*(g&1) + r of tile 2*pr + (g >> 1) -----
     // The integer scores stay in registers; only the last chunk can hold padded slots, which
-    // are kept out of the row maximum here and out of the row sum below.
+    // are kept out of the row sum (and so out of the codes) below.
     // K operand of tile tl: slot s = tl*16 + j sits in LDS row (s % NIT)*(64/NIT) + s/NIT,
     // i.e. byte (j % NIT)*1024 + (j / NIT)*ROWB + tl*256; segment (NITW*w + piece) ^ (j % NIT), where
     // lane group g reads piece g of its head's row (8 bit) or piece g % 2 (4 bit: even elements of
@@ -204,32 +208,24 @@ void attention_fused_kernel(AttnArgs a)
     static_for<MAXCH>([&](auto C) {
         constexpr int c = C, ST = (KS > 1) ? 0 : (c % NST) * STG;
         const int gc = ks + c * KS;
-        sc[2 * c] = (v4i){0, 0, 0, 0};
-        sc[2 * c + 1] = (v4i){0, 0, 0, 0};
         if (c < nloc) {
             acquire(Kg, gc);
             const v4i kA0 = *reinterpret_cast<const v4i *>(kaddr + ST), kB0 = *reinterpret_cast<const v4i *>(kaddr + ST + 256);
             const v4i kA1 = *reinterpret_cast<const v4i *>(kaddr + ST + 512), kB1 = *reinterpret_cast<const v4i *>(kaddr + ST + 768);
             release(Kg, gc);
-            sc[2 * c] = __builtin_amdgcn_mfma_i32_16x16x64_i8(q_lo, kop(kA0), sc[2 * c], 0, 0, 0);
+            const v4i zero = {0, 0, 0, 0};
+            sc[2 * c] = __builtin_amdgcn_mfma_i32_16x16x64_i8(q_lo, kop(kA0), zero, 0, 0, 0);
             sc[2 * c] = __builtin_amdgcn_mfma_i32_16x16x64_i8(q_hi, kop(kB0), sc[2 * c], 0, 0, 0);
-            sc[2 * c + 1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(q_lo, kop(kA1), sc[2 * c + 1], 0, 0, 0);
+            sc[2 * c + 1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(q_lo, kop(kA1), zero, 0, 0, 0);
             sc[2 * c + 1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(q_hi, kop(kB1), sc[2 * c + 1], 0, 0, 0);
             if (QB == 4) { // both operands carried a factor 16
                 sc[2 * c] = sc[2 * c] >> 8;
                 sc[2 * c + 1] = sc[2 * c + 1] >> 8;
             }
-            if (gc == nch - 1) {
+            // a padded slot repeats the panel's last real column, so its score duplicates a real
+            // one and cannot change the row maximum: no masking here
 #pragma unroll
-                for (int pr = 0; pr < 2; ++pr)
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) imax[r] = max(imax[r], keep[pr] ? sc[2 * c + pr][r] : INT32_MIN);
-            } else {
-#pragma unroll
-                for (int pr = 0; pr < 2; ++pr)
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) imax[r] = max(imax[r], sc[2 * c + pr][r]);
-            }
+            for (int r = 0; r < 4; ++r) imax[r] = max(imax[r], max(sc[2 * c][r], sc[2 * c + 1][r]));
         }
     });
     // all Kmat rows are consumed: start copying V rows while the softmax runs
@@ -264,12 +260,21 @@ void attention_fused_kernel(AttnArgs a)
 #pragma unroll
             for (int pr = 0; pr < 2; ++pr)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    float e = __builtin_amdgcn_exp2f(__builtin_fmaf((float)sc[2 * c + pr][r], scale2, -m2[r]));
-                    if (ks + c * KS == nch - 1) e = keep[pr] ? e : 0.f;
-                    x[2 * c + pr][r] = e;
-                    srow[r] += e;
-                }
+                for (int r = 0; r < 4; ++r)
+                    x[2 * c + pr][r] = __builtin_amdgcn_exp2f(__builtin_fmaf((float)sc[2 * c + pr][r], scale2, -m2[r]));
+            if (ks + c * KS == nch - 1) {
+                // the panel's last chunk: padded slots count for nothing.  (The empty statement keeps
+                // this a branch taken once per wave instead of selects in every chunk.)
+                asm volatile("" ::: "memory");
+#pragma unroll
+                for (int pr = 0; pr < 2; ++pr)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) x[2 * c + pr][r] = keep[pr] ? x[2 * c + pr][r] : 0.f;
+            }
+#pragma unroll
+            for (int pr = 0; pr < 2; ++pr)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) srow[r] += x[2 * c + pr][r];
         }
     });
     float rinv[4]; // p / s_p = e * (1 / (sum * s_p)): one division per row instead of one per entry
@@ -305,9 +310,10 @@ void attention_fused_kernel(AttnArgs a)
         const int s = g * 16 + 8 * h + ii;   // slot within the chunk supplied by this lane
         const int i = s % NIT, r = s / NIT;
         vbase[h] = i * 1024 + r * ROWB + (((NITW * w) ^ i) * 16) + 8 * (src & 1);
-        // lanes 2t and 2t+1 supply the 8-byte pieces that end up in MFMA rows 0..7 and 8..15:
-        // the same piece twice (rows 8..15 are zeroed below) or the high and the low plane
-        paddr[h] = Pl + s * 8 + ((PB == 16) ? (src & 1) * PLANE : 0);
+        // lanes 2t and 2t+1 supply the 8-byte pieces that end up in MFMA rows 0..7 and 8..15: the
+        // codes and 8 zero bytes (PB 8), or the high and the low plane of the codes (PB 16)
+        if (PB == 16) paddr[h] = Pl + s * 8 + (src & 1) * PLANE;
+        else paddr[h] = (src & 1) ? zeros : Pl + s * 8;
     }
     static_for<MAXCH>([&](auto C) {
         constexpr int c = C;
@@ -341,7 +347,8 @@ void attention_fused_kernel(AttnArgs a)
             }
             acquire(Vg, gc);
             // the codes, transposed to the MFMA row operand: row j < 8, slots g*16 .. +15
-            const v2i p0 = lds_read_tr8(paddr[0] + c * 512), p1 = lds_read_tr8(paddr[1] + c * 512);
+            const int pstep = (PB == 8 && (src & 1)) ? 0 : c * 512; // the zero bytes do not move
+            const v2i p0 = lds_read_tr8(paddr[0] + pstep), p1 = lds_read_tr8(paddr[1] + pstep);
             v2i d[NITW][2];
 #pragma unroll
             for (int ct = 0; ct < NITW; ++ct) {
@@ -349,8 +356,7 @@ void attention_fused_kernel(AttnArgs a)
                 d[ct][1] = lds_read_tr8(stage + (KS > 1 ? 0 : (c % NST) * STG) + (vbase[1] ^ (ct * 16)));
             }
             release(Vg, gc);
-            v4i aop = {p0.x, p0.y, p1.x, p1.y};
-            if (PB == 8 && j >= 8) aop = (v4i){0, 0, 0, 0};
+            const v4i aop = {p0.x, p0.y, p1.x, p1.y};
 #pragma unroll
             for (int ct = 0; ct < NITW; ++ct) {
                 const v4i bop = {d[ct][0].x, d[ct][0].y, d[ct][1].x, d[ct][1].y};
@@ -389,7 +395,7 @@ void attention_fused_kernel(AttnArgs a)
         v4i sres = {0, 0, 0, 0}, slo = {0, 0, 0, 0};
 #pragma unroll
         for (int k = 0; k < KS; ++k) {
-            const int *Ok = (KS > 1) ? reinterpret_cast<const int *>(Pl_all + k * (PLANE * (PB / 8))) : Ol;
+            const int *Ok = (KS > 1) ? reinterpret_cast<const int *>(Pl_all + k * PLB) : Ol;
             sres += *reinterpret_cast<const v4i *>(&Ok[row * (DK + 4) + col]);
             if (PB == 16) slo += *reinterpret_cast<const v4i *>(&Ok[(row + 8) * (DK + 4) + col]);
         }
