@@ -58,8 +58,8 @@ void free_device(mc_mat *A)
     if (A->d_vals) (void)hipFree(A->d_vals);
 }
 
-// Tile variant for a problem (measured on MI355X).  Rows of 256 bytes or more are cut into
-// 128-byte tiles (256-byte tiles when panels are long), shorter rows into 64-byte tiles;
+// Tile variant for a problem (measured on MI355X).  Rows are cut into 128-byte tiles, into
+// 256-byte tiles when panels are long, into 64-byte tiles when rows or panels are short;
 // the chunks of a panel are shared by as many waves as it takes to put about 2048 waves
 // on the chip, but never more waves than a panel has chunks.
 // Waves per panel for SDDMM: enough to put about 2048 waves on the chip, at most one per chunk.
@@ -78,8 +78,15 @@ void choose_variant(const mc_mat *A, int row_bytes, bool r4, int batch, int *bnb
     int b = g_variant_bnb, w = g_variant_waves;
     const double avg = A->P ? (double)(A->nslots / MC_CHUNK) / A->P : 0.0;
     if (b == 0) {
-        b = (row_bytes >= 256) ? 128 : 64;
-        if (!r4 && row_bytes >= 256 && avg >= 16.0) b = 256;
+        if (r4) {
+            // a 64-byte tile of nibbles already yields 128 output columns
+            b = ((row_bytes >= 256 && avg >= 2.0) || (row_bytes >= 128 && avg >= 16.0)) ? 128 : 64;
+        } else {
+            b = 128;
+            if (row_bytes < 128 || (row_bytes == 128 && avg < 4.0) || (row_bytes < 512 && avg < 2.0)) b = 64;
+            // wide tiles for long panels; with a two-plane A (16 output rows per tile) only for long rows
+            if (row_bytes >= 256 && avg >= 16.0 && (row_bytes >= 512 || A->lhs_bits == 8)) b = 256;
+        }
     }
     if (b == 256 && r4) b = 128;
     if (w == 0) {
