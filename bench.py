@@ -229,6 +229,13 @@ def main():
                     frac=round(achieved / HBM_PEAK_GBS, 4),
                     traffic=(MEASURED_TRAFFIC_BYTES.get(dom["name"]) if args.attention_layout == "head" else None),
                     us_per_launch=round(dom["us"], 2), algorithmic_bytes=int(dom["bytes"]))
+    if extras is not None and dom["name"] == "attention":
+        # the practical bound of the dominant kernel: its K and V rows (64 bytes each, padded slots
+        # included) at the gather rate measured above
+        gb = HEADS * 2 * amask.nslots * DK
+        roofline["gathered_bytes"] = int(gb)
+        roofline["gather_peak_tbs_measured"] = extras["gather_peak_tbs"]["rows_64B"]
+        roofline["frac_of_gather_peak"] = round(gb / extras["gather_peak_tbs"]["rows_64B"] / 1e6 / dom["us"], 3)
     per_kernel = {k["name"]: dict(us=round(k["us"], 2), eff_tops=round(k["ops"] / k["us"] / 1e6, 1),
                                   alg_gbs=round(k["bytes"] / k["us"] / 1e3, 1),
                                   hbm_frac=round(k["bytes"] / k["us"] / 1e3 / HBM_PEAK_GBS, 4),
@@ -248,6 +255,7 @@ def main():
                                "+ sparse attention 8 heads L=4096 dk=64",
                    "launch": "eager" if args.eager else f"hip_graph x{spg} steps", "kernels_in_step": [k["name"] for k in kernels]},
         "headline_spmm_l8r8": dict(per_kernel.get("spmm_L8R8") or {}, **((extras or {}).get("headline") or {})),
+        "gather_peak_tbs_measured": (extras or {}).get("gather_peak_tbs"),
         "beyond_the_step": (extras or {}).get("wider_precisions"),
         "layer_at_inference_shapes": (extras or {}).get("layer_at_inference_shapes"),
         "per_kernel": per_kernel,
@@ -310,6 +318,26 @@ def measure_extras(mc, torch, prob, stream, reps, up):
         A.close()
     del sets
 
+    # What the memory system sustains for this access pattern: the gather alone on 32x the panels
+    # (launch and tail amortised), rows of 64 bytes (the attention kernel's K / V rows) and of 128
+    # bytes (the SpMM's row pieces), from a table that stays in L2 like B, K and V do.
+    peak = {}
+    for rb in (64, 128):
+        cg = wl.spmm_case(32 * M, K, rb, V, SPARSITY, "L8R8", wl.seed_for(2, 900 + rb))
+        Ag = mc.SparseMatrix(32 * M, K, V, cg["row_ptr"], cg["col_idx"], cg["values"], 8)
+        Bg = up(cg["B"])
+        sg = mc.probe_gather(Ag, Bg, "L8R8")
+        best = None
+        for waves in (1, 2, 4):       # the best launch shape counts
+            mc.set_spmm_variant(rb, waves)
+            us = time_graph(torch, stream, [lambda: mc.probe_gather(Ag, Bg, "L8R8", sink=sg)] * 20)
+            best = us if best is None else min(best, us)
+        mc.set_spmm_variant(0, 0)
+        peak[rb] = Ag.nvec * rb / best / 1e6   # TB/s
+        Ag.close()
+    out["gather_peak_tbs"] = {"rows_64B": round(peak[64], 2), "rows_128B": round(peak[128], 2)}
+    out["headline"]["frac_of_gather_peak"] = round(nvec * N_SPMM / peak[128] / 1e6 / warm, 3)
+
     wide = {}
     for i, prec in enumerate(["L16R16", "L16R4", "L12R4"]):
         cc = wl.spmm_case(M, K, N_SPMM, V, SPARSITY, prec, wl.seed_for(2, 100 + 10 * i))
@@ -349,22 +377,28 @@ def measure_extras(mc, torch, prob, stream, reps, up):
     out["wider_precisions"] = wide
 
     # The layer at the shapes of the paper's end-to-end latency figure (Section 5.3: 4 / 8 heads, sequence
-    # 4096 / 8192, batch 2 / 8, sparsity 0.9 / 0.95, head dimension 64), one launch per batch.
+    # 4096 / 8192, batch 2 / 8, sparsity 0.9 / 0.95, head dimension 64), one launch per batch, tensors as
+    # (batch, head, token, d) and in the (batch, token, head, d) order a QKV projection writes.
     shapes = {}
     for L, heads, batch, sp in ((4096, 8, 8, 0.9), (8192, 4, 8, 0.9), (8192, 4, 2, 0.95)):
         c = wl.attention_case(1, L, DK, V, sp, wl.seed_for(5, L + heads + batch))
         m = mc.SparseMatrix(L, L, V, c["row_ptr"], c["col_idx"])
         x = wl.normal_fp32((batch, heads, L, DK), wl.seed_for(5, 7))
-        O = torch.empty((batch, heads, L, DK), dtype=torch.float32, device="cuda")
-        for name, p_bits, qkv_bits in (("8b-8b", 8, 8), ("16b-8b", 16, 8), ("8b-4b", 8, 4)):
-            xq, sx = (wl.quantize_inputs_int4 if qkv_bits == 4 else wl.quantize_inputs_int8)(x)
-            q = up(xq)                                  # the same tensor serves as Q, K and V: timing only
-            ws = torch.empty(mc.attention_workspace_bytes(heads, m, p_bits), dtype=torch.uint8, device="cuda")
-            s_p = np.float32(1.0 / (32639.0 if p_bits == 16 else 127.0))
-            us = time_graph(torch, stream, [lambda: mc.sparse_attention(q, q, q, m, sx, sx, sx, s_p, out=O, workspace=ws,
-                                                                        p_bits=p_bits, qkv_bits=qkv_bits)] * 20)
-            ops = batch * heads * 2 * (2 * m.nvec * V * DK)
-            shapes[f"L{L}_h{heads}_b{batch}_s{sp}_{name}"] = dict(us=round(us, 1), eff_tops=round(ops / us / 1e6, 1))
+        for layout in ("head", "token"):
+            if layout == "token":
+                O = torch.empty((batch, L, heads, DK), dtype=torch.float32, device="cuda").permute(0, 2, 1, 3)
+            else:
+                O = torch.empty((batch, heads, L, DK), dtype=torch.float32, device="cuda")
+            for name, p_bits, qkv_bits in (("8b-8b", 8, 8), ("16b-8b", 16, 8), ("8b-4b", 8, 4)):
+                xq, sx = (wl.quantize_inputs_int4 if qkv_bits == 4 else wl.quantize_inputs_int8)(x)
+                # the same tensor serves as Q, K and V: timing only
+                q = up(np.ascontiguousarray(np.transpose(xq, (0, 2, 1, 3)))).permute(0, 2, 1, 3) if layout == "token" else up(xq)
+                ws = torch.empty(mc.attention_workspace_bytes(heads, m, p_bits), dtype=torch.uint8, device="cuda")
+                s_p = np.float32(1.0 / (32639.0 if p_bits == 16 else 127.0))
+                us = time_graph(torch, stream, [lambda: mc.sparse_attention(q, q, q, m, sx, sx, sx, s_p, out=O, workspace=ws,
+                                                                            p_bits=p_bits, qkv_bits=qkv_bits)] * 20)
+                ops = batch * heads * 2 * (2 * m.nvec * V * DK)
+                shapes[f"L{L}_h{heads}_b{batch}_s{sp}_{name}_{layout}-major"] = dict(us=round(us, 1), eff_tops=round(ops / us / 1e6, 1))
         m.close()
     out["layer_at_inference_shapes"] = shapes
     return out

@@ -162,6 +162,7 @@ void attention_fused_kernel(AttnArgs a)
         ixn = *reinterpret_cast<const ixv_t *>(myidx + ((c + KS < nch) ? c + KS : c) * MC_CHUNK);
     };
     auto start_pipeline = [&](const uint8_t *base) {
+        lgkm_wait();                               // no read of the stage is still in flight
         if (HPW > 1) __builtin_amdgcn_s_barrier(); // both waves are done with the stages
         if (nloc > 0) {
             ixn = *reinterpret_cast<const ixv_t *>(myidx + ks * MC_CHUNK);
@@ -404,6 +405,7 @@ void attention_fused_kernel(AttnArgs a)
         *reinterpret_cast<v4f *>(Oh + (int64_t)row * a.token_stride + col) = f;
     }
 }
+
 
 } // namespace
 
