@@ -122,17 +122,19 @@ def sddmm_dense(Q, Kmat, stored, V: int) -> np.ndarray:
 # --------------------------------------------------------------------------- #
 # Interchange data -> dense operands                                           #
 # --------------------------------------------------------------------------- #
-def unpack_int4(packed) -> np.ndarray:
-    """Signed 4-bit values from bytes, along the last axis.
+def unpack_int4(packed, unsigned: bool = False) -> np.ndarray:
+    """4-bit values from bytes, along the last axis.
 
     Byte j holds element 2j in bits 3:0 and element 2j+1 in bits 7:4, each a
-    two's-complement value in [-8, 7].  Returns int32 with the last axis doubled.
+    two's-complement value in [-8, 7] (or, with ``unsigned``, a value in [0, 15]).
+    Returns int32 with the last axis doubled.
     """
     p = np.asarray(packed).view(np.uint8).astype(np.int32)
     lo = p & 15
     hi = (p >> 4) & 15
-    lo = np.where(lo >= 8, lo - 16, lo)
-    hi = np.where(hi >= 8, hi - 16, hi)
+    if not unsigned:
+        lo = np.where(lo >= 8, lo - 16, lo)
+        hi = np.where(hi >= 8, hi - 16, hi)
     out = np.empty(p.shape[:-1] + (p.shape[-1] * 2,), dtype=np.int32)
     out[..., 0::2] = lo
     out[..., 1::2] = hi
@@ -151,21 +153,23 @@ def stored_flags(M: int, K: int, V: int, row_ptr, col_idx) -> np.ndarray:
     return flags
 
 
-def vector_values_as_int(values, nvec: int, V: int, bits: int) -> np.ndarray:
+def vector_values_as_int(values, nvec: int, V: int, bits: int, unsigned: bool = False) -> np.ndarray:
     """(nvec, V) int32 from vector-major stored values of the given width.
 
     bits=8: int8; bits=16: int16; bits=12: int16 container restricted to 12-bit values;
     bits=4: two elements per byte along the V axis.
     """
+    if unsigned and bits not in (4, 8):
+        raise ValueError("unsigned operands are defined here for 4 and 8 bits")
     if bits == 8:
-        return np.asarray(values).view(np.int8).reshape(nvec, V).astype(np.int32)
+        return np.asarray(values).view(np.uint8 if unsigned else np.int8).reshape(nvec, V).astype(np.int32)
     if bits == 16 or bits == 12:
         vv = np.asarray(values).view(np.int16).reshape(nvec, V).astype(np.int32)
         if bits == 12 and vv.size and (vv.min() < -2048 or vv.max() > 2047):
             raise ValueError("12-bit operand outside [-2048, 2047]")
         return vv
     if bits == 4:
-        return unpack_int4(np.asarray(values).view(np.uint8).reshape(nvec, V // 2))
+        return unpack_int4(np.asarray(values).view(np.uint8).reshape(nvec, V // 2), unsigned)
     raise ValueError("bits must be 4, 8, 12 or 16")
 
 
@@ -190,37 +194,42 @@ _LHS_BITS = {"L8R8": 8, "L8R4": 8, "L4R4": 4, "L16R8": 16, "L16R16": 16, "L16R4"
 _RHS_BITS = {"L8R8": 8, "L8R4": 4, "L4R4": 4, "L16R8": 8, "L16R16": 16, "L16R4": 4, "L12R4": 4}
 
 
-def dense_rhs_as_int(B, bits: int) -> np.ndarray:
+def dense_rhs_as_int(B, bits: int, unsigned: bool = False) -> np.ndarray:
     """Row-major dense operand as int32; bits=4 means two elements per byte along a row,
     bits=16 little-endian int16 elements."""
+    if unsigned and bits not in (4, 8):
+        raise ValueError("unsigned operands are defined here for 4 and 8 bits")
     if bits == 8:
-        return np.asarray(B).view(np.int8).astype(np.int32)
+        return np.asarray(B).view(np.uint8 if unsigned else np.int8).astype(np.int32)
     if bits == 16:
         return np.asarray(B).view(np.int16).astype(np.int32)
     if bits == 4:
-        return unpack_int4(np.asarray(B).view(np.uint8))
+        return unpack_int4(np.asarray(B).view(np.uint8), unsigned)
     raise ValueError("bits must be 4, 8 or 16")
 
 
-def spmm(M, K, V, row_ptr, col_idx, values, B, prec: str) -> np.ndarray:
+def spmm(M, K, V, row_ptr, col_idx, values, B, prec: str, lhs_unsigned: bool = False,
+         rhs_unsigned: bool = False) -> np.ndarray:
     """SpMM from interchange data: widen every operand to int, then ``spmm_dense``.
 
     Lx-Ry names the operand widths (Table "precision supported" of the paper); the
-    oracle never splits planes -- mixed precision is just integers of other ranges.
+    oracle never splits planes -- mixed precision is just integers of other ranges, and an
+    unsigned operand (Section 4.4.1) is the same bytes read as non-negative values.
     """
     nvec = len(col_idx)
-    vv = vector_values_as_int(values, nvec, V, _LHS_BITS[prec])
+    vv = vector_values_as_int(values, nvec, V, _LHS_BITS[prec], lhs_unsigned)
     A, flags = bcrs_to_dense(M, K, V, row_ptr, col_idx, vv)
-    return spmm_dense(A, flags, dense_rhs_as_int(B, _RHS_BITS[prec]), V)
+    return spmm_dense(A, flags, dense_rhs_as_int(B, _RHS_BITS[prec], rhs_unsigned), V)
 
 
-def sddmm(M, Nc, V, row_ptr, col_idx, Q, Kmat, prec: str) -> np.ndarray:
+def sddmm(M, Nc, V, row_ptr, col_idx, Q, Kmat, prec: str, lhs_unsigned: bool = False,
+          rhs_unsigned: bool = False) -> np.ndarray:
     """SDDMM from interchange data; Q and Kmat are row-major (packed along Kd for int4)."""
     bits = _LHS_BITS[prec]
     if bits not in (4, 8, 16) or _RHS_BITS[prec] != bits:
         raise ValueError("SDDMM is defined here for L8R8, L4R4 and L16R16")
     flags = stored_flags(M, Nc, V, row_ptr, col_idx)
-    return sddmm_dense(dense_rhs_as_int(Q, bits), dense_rhs_as_int(Kmat, bits), flags, V)
+    return sddmm_dense(dense_rhs_as_int(Q, bits, lhs_unsigned), dense_rhs_as_int(Kmat, bits, rhs_unsigned), flags, V)
 
 
 # --------------------------------------------------------------------------- #

@@ -319,6 +319,70 @@ def test_sddmm_l16r16_against_library_matmul_and_loops():
     assert got[i * V + 2] == sum(a * b for a, b in zip(q[V + 2], k[int(c["col_idx"][i])]))
 
 
+@pytest.mark.parametrize("prec", ["L8R8", "L8R4", "L4R4"])
+@pytest.mark.parametrize("lu,ru", [(True, True), (True, False), (False, True)])
+def test_unsigned_operands_by_integer_loops(prec, lu, ru):
+    """Section 4.4.1: the same bytes read as non-negative values; loops over the stored vectors."""
+    V, M, K, N = 4, 8, 12, 32
+    c = wl.spmm_case(M, K, N, V, 0.5, prec, 47)
+    def lhs(i, v):
+        if prec == "L4R4":
+            b = int(c["values"][i, v // 2]); x = (b >> (4 * (v % 2))) & 15
+            return x if lu else (x ^ 8) - 8
+        x = int(c["values"].view(np.uint8)[i, v])
+        return x if lu else (x ^ 128) - 128
+    def rhs(k, n):
+        if prec in ("L8R4", "L4R4"):
+            b = int(c["B"][k, n // 2]); x = (b >> (4 * (n % 2))) & 15
+            return x if ru else (x ^ 8) - 8
+        x = int(c["B"].view(np.uint8)[k, n])
+        return x if ru else (x ^ 128) - 128
+    want = [[0] * N for _ in range(M)]
+    for p in range(M // V):
+        for i in range(c["row_ptr"][p], c["row_ptr"][p + 1]):
+            for v in range(V):
+                for n in range(N):
+                    want[p * V + v][n] += lhs(i, v) * rhs(int(c["col_idx"][i]), n)
+    got = oracle.spmm(M, K, V, c["row_ptr"], c["col_idx"], c["values"], c["B"], prec, lhs_unsigned=lu, rhs_unsigned=ru)
+    assert got.tolist() == want
+    if lu and ru:
+        assert got.min() >= 0
+
+
+def test_unsigned_plane_emulation_identity():
+    """The paper's unsigned example (Section 4.4.1): an unsigned 8-bit A as two unsigned 4-bit planes,
+    C = C0 + 16 * C1, planes multiplied by the library matmul; 237 = 13 + 16 * 14."""
+    lo, hi = oracle.split_unsigned(np.array([237]), 4)
+    assert (int(lo[0]), int(hi[0])) == (13, 14)
+    V, M, K, N = 8, 16, 24, 32
+    c = wl.spmm_case(M, K, N, V, 0.5, "L8R4", 48)
+    A, flags = oracle.bcrs_to_dense(M, K, V, c["row_ptr"], c["col_idx"], c["values"].view(np.uint8).astype(np.int32))
+    Bu = oracle.unpack_int4(c["B"], unsigned=True)
+    a0, a1 = oracle.split_unsigned(A, 4)
+    want = (a0 @ Bu.astype(np.int64)) + 16 * (a1 @ Bu.astype(np.int64))
+    got = oracle.spmm(M, K, V, c["row_ptr"], c["col_idx"], c["values"], c["B"], "L8R4", lhs_unsigned=True, rhs_unsigned=True)
+    assert np.array_equal(got, want)
+
+
+@pytest.mark.parametrize("prec", ["L8R8", "L4R4"])
+def test_unsigned_sddmm_against_library_matmul(prec):
+    V, M, Nc, Kd = 4, 8, 12, 32
+    c = wl.sddmm_case(M, Nc, Kd, V, 0.5, prec, 49)
+    if prec == "L4R4":
+        Qu, Ku = oracle.unpack_int4(c["Q"], True), oracle.unpack_int4(c["Kmat"], True)
+        assert Qu.min() >= 0 and Qu.max() == 15
+    else:
+        Qu, Ku = c["Q"].view(np.uint8).astype(np.int64), c["Kmat"].view(np.uint8).astype(np.int64)
+    full = torch.from_numpy(Qu.astype(np.int64)) @ torch.from_numpy(Ku.astype(np.int64)).T
+    want = []
+    for p in range(M // V):
+        for i in range(c["row_ptr"][p], c["row_ptr"][p + 1]):
+            for v in range(V):
+                want.append(int(full[p * V + v, int(c["col_idx"][i])]))
+    got = oracle.sddmm(M, Nc, V, c["row_ptr"], c["col_idx"], c["Q"], c["Kmat"], prec, lhs_unsigned=True, rhs_unsigned=True)
+    assert got.tolist() == want
+
+
 # ------------------------------------------------------------ attention ----
 def test_softmax_rows_sum_to_one_and_uniform_case():
     V = 8
