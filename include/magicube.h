@@ -144,6 +144,17 @@ int mc_mat_info(const mc_mat *A, int *M, int *K, int *V, int *lhs_bits, int64_t 
 int mc_spmm(const mc_mat *A, const void *B_dev, int N, int ldb, mc_prec prec, int32_t *C_dev, int ldc,
             void *stream);
 
+/* Operand signedness (Section 4.4.1, unsigned integers): with a flag set, the bytes (nibbles) of
+ * that operand are read as values in [0, 255] ([0, 15]) instead of two's complement.  The matrix
+ * unit multiplies signed bytes, so an unsigned value enters as u - 128 (u - 8) and the difference
+ * is put back exactly from row sums of A and column sums of the gathered B rows.
+ * Supported for MC_L8R8, MC_L8R4 and MC_L4R4 (other precisions: MC_EUNSUPPORTED); the 4-bit
+ * right operand then requires K <= 32768.  flags = 0 is mc_spmm / mc_sddmm. */
+#define MC_LHS_UNSIGNED 1u
+#define MC_RHS_UNSIGNED 2u
+int mc_spmm_flags(const mc_mat *A, const void *B_dev, int N, int ldb, mc_prec prec, unsigned flags, int32_t *C_dev,
+                  int ldc, void *stream);
+
 /* Measurement aid (Section 4.2.1 names the gather of B rows by column index as the step the
  * kernel is built around): performs ONLY the gather of mc_spmm(A, B_dev, N, ldb, prec, ...) --
  * same tile variant, index loads and row copies into on-chip memory, no arithmetic, no C.

@@ -58,6 +58,7 @@ def _load() -> ctypes.CDLL:
     L.mc_mat_info.argtypes = [c_void_p, POINTER(c_int), POINTER(c_int), POINTER(c_int), POINTER(c_int),
                               POINTER(c_int64), POINTER(c_int64)]
     L.mc_spmm.argtypes = [c_void_p, c_void_p, c_int, c_int, c_int, c_void_p, c_int, c_void_p]
+    L.mc_spmm_flags.argtypes = [c_void_p, c_void_p, c_int, c_int, c_int, ctypes.c_uint, c_void_p, c_int, c_void_p]
     L.mc_sddmm.argtypes = [c_void_p, c_int, c_void_p, c_int, c_int, c_void_p, c_int, c_void_p, c_void_p]
     L.mc_sparse_softmax.argtypes = [c_void_p, c_int, c_void_p, c_float, c_float, c_void_p, c_void_p]
     L.mc_attention_workspace_bytes.argtypes = [c_int, c_void_p]; L.mc_attention_workspace_bytes.restype = c_size_t
@@ -81,7 +82,7 @@ def _load() -> ctypes.CDLL:
     L.mc_set_attention_mode.argtypes = [c_int]
     L.mc_set_sddmm_variant.argtypes = [c_int]
     for name in ("mc_layout_query", "mc_pack_host", "mc_unpack_host", "mc_mat_create", "mc_mat_set_values_device",
-                 "mc_mat_info", "mc_spmm", "mc_sddmm", "mc_sparse_softmax", "mc_sparse_softmax_bits", "mc_sparse_attention",
+                 "mc_mat_info", "mc_spmm", "mc_spmm_flags", "mc_sddmm", "mc_sparse_softmax", "mc_sparse_softmax_bits", "mc_sparse_attention",
                  "mc_sparse_attention_strided", "mc_sparse_attention_bits", "mc_sparse_attention_batched", "mc_probe_gather",
                  "mc_set_spmm_variant", "mc_set_attention_mode", "mc_set_sddmm_variant"):
         getattr(L, name).restype = c_int
@@ -200,8 +201,9 @@ def set_attention_mode(mode: int = 0) -> None:
     _check(lib.mc_set_attention_mode(mode), "mc_set_attention_mode")
 
 
-def spmm(A: SparseMatrix, B, prec: str, out=None):
-    """C = A * B (int32, M x N).  B: device tensor (K, N) int8, (K, N/2) uint8 for R4, (K, N) int16 for R16."""
+def spmm(A: SparseMatrix, B, prec: str, out=None, lhs_unsigned: bool = False, rhs_unsigned: bool = False):
+    """C = A * B (int32, M x N).  B: device tensor (K, N) int8, (K, N/2) uint8 for R4, (K, N) int16 for R16.
+    lhs_unsigned / rhs_unsigned: read the 8- or 4-bit operand as non-negative values."""
     assert B.is_cuda and B.dim() == 2 and B.stride(1) == 1
     rbits = RHS_BITS[prec]
     N = B.shape[1] * B.element_size() * 8 // rbits
@@ -209,7 +211,9 @@ def spmm(A: SparseMatrix, B, prec: str, out=None):
     if out is None:
         out = torch.empty((A.M, N), dtype=torch.int32, device=B.device)
     assert out.is_cuda and out.dtype == torch.int32 and out.shape == (A.M, N) and out.stride(1) == 1
-    _check(lib.mc_spmm(A.handle, B.data_ptr(), N, ldb, PREC[prec], out.data_ptr(), out.stride(0), _stream()), "mc_spmm")
+    flags = (1 if lhs_unsigned else 0) | (2 if rhs_unsigned else 0)
+    _check(lib.mc_spmm_flags(A.handle, B.data_ptr(), N, ldb, PREC[prec], flags, out.data_ptr(), out.stride(0), _stream()),
+           "mc_spmm_flags")
     return out
 
 

@@ -237,17 +237,26 @@ extern "C" int mc_mat_set_values_device(mc_mat *A, const void *values_dev, void 
 extern "C" int mc_spmm(const mc_mat *A, const void *B_dev, int N, int ldb, mc_prec prec, int32_t *C_dev, int ldc,
                        void *stream)
 {
+    return mc_spmm_flags(A, B_dev, N, ldb, prec, 0u, C_dev, ldc, stream);
+}
+
+extern "C" int mc_spmm_flags(const mc_mat *A, const void *B_dev, int N, int ldb, mc_prec prec, unsigned flags,
+                             int32_t *C_dev, int ldc, void *stream)
+{
     if (!A || !B_dev || !C_dev) return MC_EINVAL;
     if (!valid_prec((int)prec)) return MC_EUNSUPPORTED;
+    if (flags & ~(unsigned)(MC_LHS_UNSIGNED | MC_RHS_UNSIGNED)) return MC_EINVAL;
+    if (flags && prec != MC_L8R8 && prec != MC_L8R4 && prec != MC_L4R4) return MC_EUNSUPPORTED;
     if (!A->d_vals || A->lhs_bits != lhs_bits_of(prec)) return MC_EINVAL;
     const int rb = rhs_bits_of(prec);
     if (N <= 0 || N % (128 / rb) != 0) return MC_EINVAL; // whole 16-byte pieces of a row
     if (ldb < N || ldc < N) return MC_EINVAL;
     if (((int64_t)ldb * rb / 8) % 16 != 0 || ldc % 4 != 0) return MC_EALIGN;
     if (!aligned16(B_dev) || !aligned16(C_dev)) return MC_EALIGN;
-    if (rb == 4 && A->K > 131072) return MC_EUNSUPPORTED;
+    if (rb == 4 && A->K > ((flags != 0) ? 32768 : 131072)) return MC_EUNSUPPORTED;
 
-    SpmmArgs a;
+    SpmmArgs a = {};
+    a.lhs_unsigned = (flags & MC_LHS_UNSIGNED) ? 1 : 0; a.rhs_unsigned = (flags & MC_RHS_UNSIGNED) ? 1 : 0;
     a.panel_ptr = A->d_panel_ptr; a.slot_idx = A->d_slot_idx;
     a.vals = A->d_vals; a.vals_batch_stride = 0;
     a.B = static_cast<const uint8_t *>(B_dev); a.ldb_bytes = (int64_t)ldb * rb / 8; a.B_batch_stride = 0;
@@ -275,7 +284,7 @@ extern "C" int mc_probe_gather(const mc_mat *A, const void *B_dev, int N, int ld
     const int rb = rhs_bits_of(prec);
     if (N <= 0 || N % (128 / rb) != 0 || ldb < N) return MC_EINVAL;
     if (((int64_t)ldb * rb / 8) % 16 != 0 || !aligned16(B_dev)) return MC_EALIGN;
-    SpmmArgs a;
+    SpmmArgs a = {};
     a.panel_ptr = A->d_panel_ptr; a.slot_idx = A->d_slot_idx;
     a.vals = nullptr; a.vals_batch_stride = 0;
     a.B = static_cast<const uint8_t *>(B_dev); a.ldb_bytes = (int64_t)ldb * rb / 8; a.B_batch_stride = 0;
@@ -381,7 +390,7 @@ int attention_pipeline(const uint8_t *Q, const uint8_t *Km, const uint8_t *Vm, i
     r.P = mask->P; r.V = 8; r.bits = p_bits; r.batch = heads;
     MC_HIP(launch_repack(r, s));
 
-    SpmmArgs m;
+    SpmmArgs m = {};
     m.panel_ptr = mask->d_panel_ptr; m.slot_idx = mask->d_slot_idx;
     m.vals = pvals; m.vals_batch_stride = mask->nslots * 8 * pb;
     m.B = Vm; m.ldb_bytes = token_stride_bytes; m.B_batch_stride = head_stride_bytes;

@@ -33,6 +33,7 @@ struct SpmmArgs {
     int P, V, batch;
     int float_out;             // 1: write float(acc) * out_scale
     float out_scale;
+    int lhs_unsigned, rhs_unsigned; // 4- and 8-bit operands read as non-negative values
 };
 
 struct SddmmArgs {

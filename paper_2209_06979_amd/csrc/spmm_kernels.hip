@@ -28,7 +28,13 @@
 //      even byte columns hold the low (unsigned) bytes, odd ones the high (signed) bytes.
 //      The MFMA is signed x signed, so a low byte u enters as u ^ 0x80 = u - 128 and the
 //      missing 128 * sum_k A[m][k] comes from one extra MFMA per chunk against an all-ones
-//      operand; the byte-column pairs are recombined as (hi<<8)+lo in the epilogue.
+//      operand; the byte-column pairs are recombined as (hi<<8)+lo in the epilogue;
+//   6. unsigned 8- or 4-bit operands (Section 4.4.1; kernels with U = true) use the same trick on
+//      either side: an unsigned value u enters the signed MFMA as u - c (c = 128, or 8 for a
+//      nibble, i.e. one XOR of the top bit of the operand byte), and
+//      sum (a'+ca)(b'+cb) = sum a'b' + cb * sum a' + ca * sum b' + ca*cb*n.  The row sums of A come
+//      from the all-ones MFMA of 5., the column sums of the gathered B rows from MFMA row 8,
+//      which is free when A has one plane and is fed an all-ones row operand.
 // The sum over a chunk does not depend on the order of its terms; slot s of a chunk is
 // reduction byte (s % 16) of lane group (s / 16) on both the A and the B side.
 #include "internal.h"
@@ -67,30 +73,34 @@ __device__ __forceinline__ v4i load_a(const uint8_t *vals, int64_t chunk, int V,
     return a;
 }
 
-template <int BNB, int WK, int LB, int RB> struct SpmmCfg {
+template <int BNB, int WK, int LB, int RB, bool U = false> struct SpmmCfg {
     static constexpr bool R4 = (RB == 4), R16 = (RB == 16), L16 = (LB == 16);
+    static_assert(!U || (!R16 && !L16), "unsigned operands: 4 and 8 bits");
     static constexpr int LPR = BNB / 16;                 // lanes (16-byte segments) per row
     static constexpr int NI = LPR;                       // load instructions per chunk
     static constexpr int RPI = 64 / LPR;                 // rows per load instruction
     static constexpr int SWZ = (LPR == 4) ? 3 : 7;       // bits of the instruction number used as swizzle
-    static constexpr int NACC = LPR * (R4 ? 2 : 1) + (R16 ? 1 : 0); // MFMA accumulators per lane (v4i each); R16: + row sums of A
+    static constexpr int XACC = LPR * (R4 ? 2 : 1);      // index of the accumulator of the all-ones MFMA (row sums of A)
+    static constexpr int NACC = XACC + ((R16 || U) ? 1 : 0); // MFMA accumulators per lane (v4i each)
     static constexpr int STAGE = 64 * BNB;               // LDS bytes of one staged chunk
     static constexpr int COLS = BNB * (R4 ? 2 : 1);      // columns of the partial tile (byte columns for R16)
     static constexpr int OUTC = R16 ? BNB / 2 : COLS;    // output columns of the tile
-    static constexpr int OROWS = L16 ? 16 : 8;
+    static constexpr int OROWS = L16 ? 16 : (U ? 12 : 8); // rows of a partial tile (U: row 8 holds column sums of B)
     static constexpr int TST = COLS + 4;                 // row stride (ints) of a partial tile: +4 keeps rows 4 apart in different banks
     static constexpr int OTILE = OROWS * TST * 4;        // bytes of one wave's partial tile
     static constexpr int PERWAVE = (STAGE > OTILE) ? STAGE : OTILE;
     static constexpr int LDS = WK * PERWAVE;
 };
 
-template <int BNB, int WK, int LB, int RB>
+template <int BNB, int WK, int LB, int RB, bool U = false>
 __global__ __launch_bounds__(64 * WK) void spmm_kernel(SpmmArgs a)
 {
-    using Cfg = SpmmCfg<BNB, WK, LB, RB>;
+    using Cfg = SpmmCfg<BNB, WK, LB, RB, U>;
     constexpr int LPR = Cfg::LPR, NI = Cfg::NI, RPI = Cfg::RPI, NACC = Cfg::NACC, COLS = Cfg::COLS, TST = Cfg::TST;
     constexpr int OUTC = Cfg::OUTC;
     constexpr bool R4 = Cfg::R4, R16 = Cfg::R16, L16 = Cfg::L16;
+    constexpr int XACC = Cfg::XACC;
+    const int axor = (U && a.lhs_unsigned) ? (int)0x80808080 : 0, bxor = (U && a.rhs_unsigned) ? (int)0x80808080 : 0;
     __shared__ __attribute__((aligned(16))) char lds[Cfg::LDS];
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -150,7 +160,11 @@ __global__ __launch_bounds__(64 * WK) void spmm_kernel(SpmmArgs a)
         for (int i = 0; i < NI; ++i)
             __builtin_amdgcn_global_load_lds((gptr_t *)(Bb + (int64_t)idxv[i >> 2][i & 3] * a.ldb_bytes + segoff[i]),
                                              (lptr_t *)(stage + i * 1024), 16, 0, 0);
-        const v4i a_cur = load_a<LB>(vals, chunk0 + c, a.V, j, g);
+        v4i a_cur = load_a<LB>(vals, chunk0 + c, a.V, j, g);
+        if (U) {
+            if (j < a.V) a_cur ^= (v4i){axor, axor, axor, axor};
+            if (j == 8) a_cur = (v4i){0x01010101, 0x01010101, 0x01010101, 0x01010101}; // row 8 collects the column sums of B
+        }
         if (k + 1 < nmy) load_idx(c + WK, idxv); // the copies above have consumed the old indices
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #pragma unroll
@@ -159,17 +173,21 @@ __global__ __launch_bounds__(64 * WK) void spmm_kernel(SpmmArgs a)
             const v2i d1 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(stage + (rd_base[1] ^ (ct * 16))));
             v4i bop = {d0.x, d0.y, d1.x, d1.y};
             if (R16) bop ^= (v4i){lowflip, lowflip, lowflip, lowflip};
+            const v4i bx = {bxor, bxor, bxor, bxor};
             if (!R4) {
+                if (U) bop ^= bx;
                 acc[ct] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a_cur, bop, acc[ct], 0, 0, 0);
             } else {
                 const v4i msk = {(int)0xF0F0F0F0, (int)0xF0F0F0F0, (int)0xF0F0F0F0, (int)0xF0F0F0F0};
-                acc[2 * ct] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a_cur, (bop << 4) & msk, acc[2 * ct], 0, 0, 0);
-                acc[2 * ct + 1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a_cur, bop & msk, acc[2 * ct + 1], 0, 0, 0);
+                v4i be = (bop << 4) & msk, bo = bop & msk;
+                if (U) { be ^= bx; bo ^= bx; }
+                acc[2 * ct] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a_cur, be, acc[2 * ct], 0, 0, 0);
+                acc[2 * ct + 1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a_cur, bo, acc[2 * ct + 1], 0, 0, 0);
             }
         }
-        if (R16) {
+        if (R16 || U) {
             const v4i ones = {0x01010101, 0x01010101, 0x01010101, 0x01010101};
-            acc[LPR] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a_cur, ones, acc[LPR], 0, 0, 0); // every column: sum over the chunk of A's row
+            acc[XACC] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a_cur, ones, acc[XACC], 0, 0, 0); // every column: sum over the chunk of A's row
         }
         // the reads of the staged rows are complete before the next chunk overwrites them
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -192,9 +210,9 @@ __global__ __launch_bounds__(64 * WK) void spmm_kernel(SpmmArgs a)
                     *reinterpret_cast<v2i *>(&tile_w[(4 * g + r) * TST + ct * 32 + 2 * j]) = (v2i){acc[2 * ct][r], acc[2 * ct + 1][r]};
                 }
             }
-        if (R16 && j == 0) { // the row sums ride in the padding column of the tile
+        if ((R16 || U) && j == 0) { // the row sums ride in the padding column of the tile
 #pragma unroll
-            for (int r = 0; r < 4; ++r) tile_w[(4 * g + r) * TST + COLS] = acc[LPR][r];
+            for (int r = 0; r < 4; ++r) tile_w[(4 * g + r) * TST + COLS] = acc[XACC][r];
         }
     }
     __syncthreads();
@@ -209,13 +227,17 @@ __global__ __launch_bounds__(64 * WK) void spmm_kernel(SpmmArgs a)
         const int gcol = tile * OUTC + col;
         if (row >= a.V || gcol >= ncols) continue;
         const int tcol = R16 ? 2 * col : col;            // first column in the partial tile
-        v4i s = {0, 0, 0, 0}, lo = {0, 0, 0, 0}, s2 = {0, 0, 0, 0}, lo2 = {0, 0, 0, 0};
+        v4i s = {0, 0, 0, 0}, lo = {0, 0, 0, 0}, s2 = {0, 0, 0, 0}, lo2 = {0, 0, 0, 0}, cs = {0, 0, 0, 0};
         int rs = 0, rs_lo = 0;
 #pragma unroll
         for (int ww = 0; ww < WK; ++ww) {
             const int *t = reinterpret_cast<const int *>(lds + ww * Cfg::PERWAVE);
             s += *reinterpret_cast<const v4i *>(&t[row * TST + tcol]);
             if (L16) lo += *reinterpret_cast<const v4i *>(&t[(row + 8) * TST + tcol]);
+            if (U) {
+                cs += *reinterpret_cast<const v4i *>(&t[8 * TST + tcol]);
+                rs += t[row * TST + COLS];
+            }
             if (R16) {
                 s2 += *reinterpret_cast<const v4i *>(&t[row * TST + tcol + 4]);
                 rs += t[row * TST + COLS];
@@ -225,7 +247,17 @@ __global__ __launch_bounds__(64 * WK) void spmm_kernel(SpmmArgs a)
                 }
             }
         }
+        if (U) {
+            // sum (a'+ca)(b'+cb): the operand bytes carry a' and b' (times 16 for nibbles), and
+            // cb * 16^[R4] = ca * 16^[L4] = 128, so both corrections are the sums shifted by 7
+            if (a.rhs_unsigned) s += (v4i){rs << 7, rs << 7, rs << 7, rs << 7};
+            if (a.lhs_unsigned) s += cs << 7;
+        }
         if (R4) { s = s >> SH; lo = lo >> SH; }
+        if (U && a.lhs_unsigned && a.rhs_unsigned) {
+            const int cc = (LB == 4 ? 8 : 128) * (RB == 4 ? 8 : 128) * (nch * MC_CHUNK); // ca * cb * slots (padded ones included: their a' is -ca)
+            s += (v4i){cc, cc, cc, cc};
+        }
         if (L16) { s = (s << 8) + lo; s2 = (s2 << 8) + lo2; rs = (rs << 8) + rs_lo; }
         if (R16) {
             // byte columns (low, high) of four B elements: A*b = (A*hi << 8) + A*(low ^ 0x80) + 128 * rowsum(A)
@@ -242,25 +274,32 @@ __global__ __launch_bounds__(64 * WK) void spmm_kernel(SpmmArgs a)
     }
 }
 
-template <int BNB, int WK, int LB, int RB> hipError_t launch_one(const SpmmArgs &a, hipStream_t s)
+template <int BNB, int WK, int LB, int RB, bool U> hipError_t launch_one(const SpmmArgs &a, hipStream_t s)
 {
     const int ntiles = (a.row_bytes + BNB - 1) / BNB;
     dim3 grid((unsigned)(a.P * ntiles), (unsigned)a.batch), block(64 * WK);
-    hipLaunchKernelGGL((spmm_kernel<BNB, WK, LB, RB>), grid, block, 0, s, a);
+    hipLaunchKernelGGL((spmm_kernel<BNB, WK, LB, RB, U>), grid, block, 0, s, a);
     return hipGetLastError();
 }
 
-template <int BNB, int LB, int RB> hipError_t launch_wk(const SpmmArgs &a, int waves, hipStream_t s)
+template <int BNB, int LB, int RB, bool U = false> hipError_t launch_wk(const SpmmArgs &a, int waves, hipStream_t s)
 {
     // the per-wave LDS regions of a workgroup must fit 64 KB
-    constexpr int MAXW = (SpmmCfg<BNB, 8, LB, RB>::LDS <= 65536) ? 8 : ((SpmmCfg<BNB, 4, LB, RB>::LDS <= 65536) ? 4 : 2);
+    constexpr int MAXW = (SpmmCfg<BNB, 8, LB, RB, U>::LDS <= 65536) ? 8 : ((SpmmCfg<BNB, 4, LB, RB, U>::LDS <= 65536) ? 4 : 2);
     if (waves > MAXW) waves = MAXW;
     switch (waves) {
-    case 1: return launch_one<BNB, 1, LB, RB>(a, s);
-    case 2: return launch_one<BNB, 2, LB, RB>(a, s);
-    case 4: return launch_one<BNB, (MAXW < 4 ? MAXW : 4), LB, RB>(a, s);
-    default: return launch_one<BNB, MAXW, LB, RB>(a, s);
+    case 1: return launch_one<BNB, 1, LB, RB, U>(a, s);
+    case 2: return launch_one<BNB, 2, LB, RB, U>(a, s);
+    case 4: return launch_one<BNB, (MAXW < 4 ? MAXW : 4), LB, RB, U>(a, s);
+    default: return launch_one<BNB, MAXW, LB, RB, U>(a, s);
     }
+}
+
+// unsigned operands: tiles of 64 or 128 bytes
+template <int LB, int RB> hipError_t launch_unsigned(const SpmmArgs &a, int bnb, int waves, hipStream_t s)
+{
+    if (bnb == 64) return launch_wk<64, LB, RB, true>(a, waves, s);
+    return launch_wk<128, LB, RB, true>(a, waves, s);
 }
 
 template <int LB, int RB> hipError_t launch_mode(const SpmmArgs &a, int bnb, int waves, hipStream_t s)
@@ -275,6 +314,14 @@ template <int LB, int RB> hipError_t launch_mode(const SpmmArgs &a, int bnb, int
 hipError_t launch_spmm(mc_prec prec, const SpmmArgs &a, int bnb, int waves, hipStream_t s)
 {
     if (a.P == 0 || a.batch == 0 || a.row_bytes == 0) return hipSuccess;
+    if (a.lhs_unsigned || a.rhs_unsigned) {
+        switch (prec) {
+        case MC_L8R8: return launch_unsigned<8, 8>(a, bnb, waves, s);
+        case MC_L8R4: return launch_unsigned<8, 4>(a, bnb, waves, s);
+        case MC_L4R4: return launch_unsigned<4, 4>(a, bnb, waves, s);
+        default: return hipErrorInvalidValue;
+        }
+    }
     switch (prec) {
     case MC_L8R8: return launch_mode<8, 8>(a, bnb, waves, s);
     case MC_L8R4: return launch_mode<8, 4>(a, bnb, waves, s);

@@ -18,7 +18,8 @@ def run_spmm_gpu(case, variant=(0, 0)):
         B = torch_dev(case["B"])
         # poison the output so that unwritten elements are caught
         out = torch.full((case["M"], case["N"]), -7777777, dtype=torch.int32, device="cuda")
-        C = mc.spmm(A, B, case["prec"], out=out)
+        C = mc.spmm(A, B, case["prec"], out=out, lhs_unsigned=case.get("lhs_unsigned", False),
+                    rhs_unsigned=case.get("rhs_unsigned", False))
         torch.cuda.synchronize()
         return C.cpu().numpy()
     finally:
@@ -29,7 +30,8 @@ def run_spmm_gpu(case, variant=(0, 0)):
 def run_spmm_oracle(case):
     import oracle
     return oracle.spmm(case["M"], case["K"], case["V"], case["row_ptr"], case["col_idx"], case["values"],
-                       case["B"], case["prec"])
+                       case["B"], case["prec"], lhs_unsigned=case.get("lhs_unsigned", False),
+                       rhs_unsigned=case.get("rhs_unsigned", False))
 
 
 def run_sddmm_gpu(case, waves=-1):
