@@ -180,6 +180,10 @@ int mc_probe_gather(const mc_mat *A, const void *B_dev, int N, int ldb, mc_prec 
  * ---------------------------------------------------------------------------------- */
 int mc_sddmm(const void *Q_dev, int ldq, const void *Kmat_dev, int ldk, int Kd, const mc_mat *mask,
              mc_prec prec, int32_t *S_dev, void *stream);
+/* The same with operand signedness flags (MC_LHS_UNSIGNED: Q, MC_RHS_UNSIGNED: Kmat; see
+ * mc_spmm_flags).  Supported for MC_L8R8 and MC_L4R4 (the latter with Kd <= 32768). */
+int mc_sddmm_flags(const void *Q_dev, int ldq, const void *Kmat_dev, int ldk, int Kd, const mc_mat *mask,
+                   mc_prec prec, unsigned flags, int32_t *S_dev, void *stream);
 
 /* ------------------------------------------------------------------------------------
  * Sparse softmax with fused (de)quantisation (Section 5.3): for each row (p, v) over its

@@ -60,6 +60,7 @@ def _load() -> ctypes.CDLL:
     L.mc_spmm.argtypes = [c_void_p, c_void_p, c_int, c_int, c_int, c_void_p, c_int, c_void_p]
     L.mc_spmm_flags.argtypes = [c_void_p, c_void_p, c_int, c_int, c_int, ctypes.c_uint, c_void_p, c_int, c_void_p]
     L.mc_sddmm.argtypes = [c_void_p, c_int, c_void_p, c_int, c_int, c_void_p, c_int, c_void_p, c_void_p]
+    L.mc_sddmm_flags.argtypes = [c_void_p, c_int, c_void_p, c_int, c_int, c_void_p, c_int, ctypes.c_uint, c_void_p, c_void_p]
     L.mc_sparse_softmax.argtypes = [c_void_p, c_int, c_void_p, c_float, c_float, c_void_p, c_void_p]
     L.mc_attention_workspace_bytes.argtypes = [c_int, c_void_p]; L.mc_attention_workspace_bytes.restype = c_size_t
     L.mc_sparse_attention.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_void_p,
@@ -82,7 +83,7 @@ def _load() -> ctypes.CDLL:
     L.mc_set_attention_mode.argtypes = [c_int]
     L.mc_set_sddmm_variant.argtypes = [c_int]
     for name in ("mc_layout_query", "mc_pack_host", "mc_unpack_host", "mc_mat_create", "mc_mat_set_values_device",
-                 "mc_mat_info", "mc_spmm", "mc_spmm_flags", "mc_sddmm", "mc_sparse_softmax", "mc_sparse_softmax_bits", "mc_sparse_attention",
+                 "mc_mat_info", "mc_spmm", "mc_spmm_flags", "mc_sddmm", "mc_sddmm_flags", "mc_sparse_softmax", "mc_sparse_softmax_bits", "mc_sparse_attention",
                  "mc_sparse_attention_strided", "mc_sparse_attention_bits", "mc_sparse_attention_batched", "mc_probe_gather",
                  "mc_set_spmm_variant", "mc_set_attention_mode", "mc_set_sddmm_variant"):
         getattr(L, name).restype = c_int
@@ -229,7 +230,7 @@ def probe_gather(A: SparseMatrix, B, prec: str, sink=None):
     return sink
 
 
-def sddmm(Q, Kmat, mask: SparseMatrix, prec: str, out=None):
+def sddmm(Q, Kmat, mask: SparseMatrix, prec: str, out=None, lhs_unsigned: bool = False, rhs_unsigned: bool = False):
     """S (nvec*V int32, interchange order) = (Q * Kmat^T) at the mask's stored vectors."""
     assert Q.is_cuda and Kmat.is_cuda and Q.dim() == 2 and Kmat.dim() == 2
     assert Q.stride(1) == 1 and Kmat.stride(1) == 1 and Q.shape[1] == Kmat.shape[1]
@@ -239,9 +240,10 @@ def sddmm(Q, Kmat, mask: SparseMatrix, prec: str, out=None):
     if out is None:
         out = torch.empty(mask.nvec * mask.V, dtype=torch.int32, device=Q.device)
     assert out.is_cuda and out.dtype == torch.int32 and out.numel() == mask.nvec * mask.V and out.is_contiguous()
-    _check(lib.mc_sddmm(Q.data_ptr(), Q.stride(0) * Q.element_size() * 8 // bits, Kmat.data_ptr(),
-                        Kmat.stride(0) * Kmat.element_size() * 8 // bits, Kd,
-                        mask.handle, PREC[prec], out.data_ptr(), _stream()), "mc_sddmm")
+    flags = (1 if lhs_unsigned else 0) | (2 if rhs_unsigned else 0)
+    _check(lib.mc_sddmm_flags(Q.data_ptr(), Q.stride(0) * Q.element_size() * 8 // bits, Kmat.data_ptr(),
+                              Kmat.stride(0) * Kmat.element_size() * 8 // bits, Kd,
+                              mask.handle, PREC[prec], flags, out.data_ptr(), _stream()), "mc_sddmm_flags")
     return out
 
 

@@ -300,21 +300,31 @@ extern "C" int mc_probe_gather(const mc_mat *A, const void *B_dev, int N, int ld
 extern "C" int mc_sddmm(const void *Q_dev, int ldq, const void *Kmat_dev, int ldk, int Kd, const mc_mat *mask,
                         mc_prec prec, int32_t *S_dev, void *stream)
 {
+    return mc_sddmm_flags(Q_dev, ldq, Kmat_dev, ldk, Kd, mask, prec, 0u, S_dev, stream);
+}
+
+extern "C" int mc_sddmm_flags(const void *Q_dev, int ldq, const void *Kmat_dev, int ldk, int Kd, const mc_mat *mask,
+                              mc_prec prec, unsigned flags, int32_t *S_dev, void *stream)
+{
     if (!Q_dev || !Kmat_dev || !mask || !S_dev) return MC_EINVAL;
     if (!valid_prec((int)prec)) return MC_EUNSUPPORTED;
+    if (flags & ~(unsigned)(MC_LHS_UNSIGNED | MC_RHS_UNSIGNED)) return MC_EINVAL;
+    if (flags && prec != MC_L8R8 && prec != MC_L4R4) return MC_EUNSUPPORTED;
+    if (flags && prec == MC_L4R4 && Kd > 32768) return MC_EUNSUPPORTED; // 256x scaled sums stay inside int32
     if (prec != MC_L8R8 && prec != MC_L4R4 && prec != MC_L16R16) return MC_EUNSUPPORTED;
     const int bits = lhs_bits_of(prec);
     if (Kd <= 0 || Kd % (128 / bits) != 0 || ldq < Kd || ldk < Kd) return MC_EINVAL;
     if (((int64_t)ldq * bits / 8) % 16 != 0 || ((int64_t)ldk * bits / 8) % 16 != 0) return MC_EALIGN;
     if (!aligned16(Q_dev) || !aligned16(Kmat_dev) || !aligned16(S_dev)) return MC_EALIGN;
 
-    SddmmArgs a;
+    SddmmArgs a = {};
     a.panel_ptr = mask->d_panel_ptr; a.row_ptr = mask->d_row_ptr; a.slot_idx = mask->d_slot_idx;
     a.Q = static_cast<const uint8_t *>(Q_dev); a.ldq_bytes = (int64_t)ldq * bits / 8; a.Q_batch_stride = 0;
     a.Kmat = static_cast<const uint8_t *>(Kmat_dev); a.ldk_bytes = (int64_t)ldk * bits / 8; a.K_batch_stride = 0;
     a.row_bytes = Kd * bits / 8;
     a.S = S_dev; a.S_batch_stride = 0;
     a.P = mask->P; a.V = mask->V; a.batch = 1;
+    a.lhs_unsigned = (flags & MC_LHS_UNSIGNED) ? 1 : 0; a.rhs_unsigned = (flags & MC_RHS_UNSIGNED) ? 1 : 0;
     MC_HIP(launch_sddmm(bits, a, choose_sddmm_waves(mask, 1), static_cast<hipStream_t>(stream)));
     return MC_OK;
 }
@@ -369,7 +379,7 @@ int attention_pipeline(const uint8_t *Q, const uint8_t *Km, const uint8_t *Vm, i
     uint8_t *pvals = wsb + ws.vals;
     const int row_bytes = dk * qkv_bits / 8, pb = p_bits / 8;
 
-    SddmmArgs d;
+    SddmmArgs d = {};
     d.panel_ptr = mask->d_panel_ptr; d.row_ptr = mask->d_row_ptr; d.slot_idx = mask->d_slot_idx;
     d.Q = Q; d.ldq_bytes = token_stride_bytes; d.Q_batch_stride = head_stride_bytes;
     d.Kmat = Km; d.ldk_bytes = token_stride_bytes; d.K_batch_stride = head_stride_bytes;

@@ -48,6 +48,7 @@ struct SddmmArgs {
     int32_t *S;
     int64_t S_batch_stride;    // elements
     int P, V, batch;
+    int lhs_unsigned, rhs_unsigned; // 4- and 8-bit operands read as non-negative values
 };
 
 struct SoftmaxArgs {

@@ -255,6 +255,78 @@ __global__ __launch_bounds__(64 * SDDMM_WAVES) void sddmm_direct_kernel(SddmmArg
     }
 }
 
+// ---- unsigned 8- and 4-bit operands (Section 4.4.1), any row length ---------------------------
+// The signed MFMA takes an unsigned value u as u - c (c = 128, or 8 for a nibble: one XOR of the
+// top bit of the operand byte); sum (q'+cq)(k'+ck) = sum q'k' + ck sum q' + cq sum k' + cq ck n.
+// sum q' per Q row comes from an MFMA against an all-ones column operand (once per wave), sum k'
+// per gathered Kmat row from MFMA row 8, which is free (V <= 8) and is fed an all-ones row operand.
+// Reduction bytes beyond the row end are zero on both sides before the XOR, so they take part in
+// every term consistently and n counts them.
+template <int PB>
+__global__ __launch_bounds__(64 * SDDMM_WAVES) void sddmm_unsigned_kernel(SddmmArgs a)
+{
+    static_assert(PB == 8 || PB == 4, "unsigned operands: 4 and 8 bits");
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int j = lane & 15, g = lane >> 4;
+    const int panel = blockIdx.x, batch = blockIdx.y;
+    const int s0 = a.panel_ptr[2 * panel], n = a.panel_ptr[2 * panel + 1] - s0;
+    const int ntile = (n + 15) / 16;
+    const int64_t out0 = (int64_t)batch * a.S_batch_stride + (int64_t)a.row_ptr[panel] * a.V;
+    const uint8_t *Qrow = a.Q + (int64_t)batch * a.Q_batch_stride + (int64_t)(panel * a.V + (j < a.V ? j : 0)) * a.ldq_bytes + g * 16;
+    const uint8_t *Km = a.Kmat + (int64_t)batch * a.K_batch_stride + g * 16;
+    const int kc_n = (a.row_bytes + 63) / 64;
+    const int qx = a.lhs_unsigned ? (int)0x80808080 : 0, kx = a.rhs_unsigned ? (int)0x80808080 : 0;
+    const v4i ones = {0x01010101, 0x01010101, 0x01010101, 0x01010101};
+    const v4i nib = {NIBBLE_HI, NIBBLE_HI, NIBBLE_HI, NIBBLE_HI};
+
+    // operands of step kc: (q0, q1) row operands and (k0, k1) column operands; 8 bit uses the first of each
+    auto q_ops = [&](int kc, v4i &q0, v4i &q1) {
+        v4i raw = {0, 0, 0, 0};
+        if (kc * 64 + g * 16 < a.row_bytes) raw = *reinterpret_cast<const v4i *>(Qrow + kc * 64);
+        const v4i x = {qx, qx, qx, qx};
+        if (PB == 8) { q0 = raw ^ x; q1 = q0; }
+        else { q0 = ((raw << 4) & nib) ^ x; q1 = (raw & nib) ^ x; }
+        if (j >= a.V) q0 = q1 = (j == 8) ? ones : (v4i){0, 0, 0, 0};
+    };
+    auto k_ops = [&](const uint8_t *kr, int kc, v4i &k0, v4i &k1) {
+        v4i raw = {0, 0, 0, 0};
+        if (kc * 64 + g * 16 < a.row_bytes) raw = *reinterpret_cast<const v4i *>(kr + kc * 64);
+        const v4i x = {kx, kx, kx, kx};
+        if (PB == 8) { k0 = raw ^ x; k1 = k0; }
+        else { k0 = ((raw << 4) & nib) ^ x; k1 = (raw & nib) ^ x; }
+    };
+
+    v4i rq = {0, 0, 0, 0}; // rows 4g .. 4g+3: sum over the reduction of the Q operand bytes
+    for (int kc = 0; kc < kc_n; ++kc) {
+        v4i q0, q1;
+        q_ops(kc, q0, q1);
+        rq = __builtin_amdgcn_mfma_i32_16x16x64_i8(q0, ones, rq, 0, 0, 0);
+        if (PB == 4) rq = __builtin_amdgcn_mfma_i32_16x16x64_i8(q1, ones, rq, 0, 0, 0);
+    }
+    const int nred = kc_n * (PB == 4 ? 128 : 64);                       // reduction elements, padding included
+    const int cqck = (a.lhs_unsigned && a.rhs_unsigned) ? (PB == 4 ? 64 : 16384) * nred : 0;
+
+    for (int t = w; t < ntile; t += SDDMM_WAVES) {
+        const int slot = t * 16 + j;
+        const int row = a.slot_idx[s0 + slot]; // padded slots name a valid row
+        const uint8_t *kr = Km + (int64_t)row * a.ldk_bytes;
+        v4i acc = {0, 0, 0, 0};
+        for (int kc = 0; kc < kc_n; ++kc) {
+            v4i q0, q1, k0, k1;
+            q_ops(kc, q0, q1);
+            k_ops(kr, kc, k0, k1);
+            acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(q0, k0, acc, 0, 0, 0);
+            if (PB == 4) acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(q1, k1, acc, 0, 0, 0);
+        }
+        const int cs = __shfl(acc[0], 32 + j); // MFMA row 8 (lane group 2, register 0) of this lane's column
+        if (a.rhs_unsigned) acc += rq << 7;
+        if (a.lhs_unsigned) acc += (v4i){cs << 7, cs << 7, cs << 7, cs << 7};
+        if (PB == 4) acc = acc >> 8;
+        acc += (v4i){cqck, cqck, cqck, cqck};
+        store_scores(a, out0, slot, n, g, acc);
+    }
+}
+
 // ---- sparse softmax + int8 re-quantisation (Section 5.3) ---------------------------
 // One workgroup per (panel, batch).  Thread t owns elements t, t+256, ... of the panel's
 // contiguous score block; 256 % V == 0, so a thread always stays in row v = t % V.
@@ -380,6 +452,13 @@ template <int PB> hipError_t launch_sddmm_bits(const SddmmArgs &a, int waves, hi
 hipError_t launch_sddmm(int bits, const SddmmArgs &a, int waves, hipStream_t s)
 {
     if (a.P == 0 || a.batch == 0) return hipSuccess;
+    if (a.lhs_unsigned || a.rhs_unsigned) {
+        dim3 grid((unsigned)a.P, (unsigned)a.batch), block(64 * SDDMM_WAVES);
+        if (bits == 8) hipLaunchKernelGGL((sddmm_unsigned_kernel<8>), grid, block, 0, s, a);
+        else if (bits == 4) hipLaunchKernelGGL((sddmm_unsigned_kernel<4>), grid, block, 0, s, a);
+        else return hipErrorInvalidValue;
+        return hipGetLastError();
+    }
     if (bits == 4) return launch_sddmm_bits<4>(a, waves, s);
     if (bits == 16) return launch_sddmm_bits<16>(a, waves, s);
     return launch_sddmm_bits<8>(a, waves, s);

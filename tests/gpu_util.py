@@ -41,7 +41,8 @@ def run_sddmm_gpu(case, waves=-1):
     mc.set_sddmm_variant(waves)
     try:
         out = torch.full((mask.nvec * mask.V,), -7777777, dtype=torch.int32, device="cuda")
-        S = mc.sddmm(torch_dev(case["Q"]), torch_dev(case["Kmat"]), mask, case["prec"], out=out)
+        S = mc.sddmm(torch_dev(case["Q"]), torch_dev(case["Kmat"]), mask, case["prec"], out=out,
+                     lhs_unsigned=case.get("lhs_unsigned", False), rhs_unsigned=case.get("rhs_unsigned", False))
         torch.cuda.synchronize()
         return S.cpu().numpy()
     finally:
@@ -52,4 +53,5 @@ def run_sddmm_gpu(case, waves=-1):
 def run_sddmm_oracle(case):
     import oracle
     return oracle.sddmm(case["M"], case["Nc"], case["V"], case["row_ptr"], case["col_idx"], case["Q"],
-                        case["Kmat"], case["prec"])
+                        case["Kmat"], case["prec"], lhs_unsigned=case.get("lhs_unsigned", False),
+                        rhs_unsigned=case.get("rhs_unsigned", False))

@@ -83,3 +83,43 @@ def test_unsigned_is_refused_for_wide_operands():
         mc.spmm(A, torch.from_numpy(c["B"]).cuda(), "L16R8", lhs_unsigned=True)
     assert e.value.status == mc.MC_EUNSUPPORTED
     A.close()
+
+
+# -------------------------------------------------------------------- SDDMM ----
+def _sddmm(case):
+    from gpu_util import run_sddmm_gpu, run_sddmm_oracle
+    print(f"sddmm case M={case['M']} Nc={case['Nc']} Kd={case['Kd']} V={case['V']} {case['prec']} "
+          f"unsigned=({case.get('lhs_unsigned')}, {case.get('rhs_unsigned')})", flush=True)
+    got, want = run_sddmm_gpu(case), run_sddmm_oracle(case)
+    assert got.shape == want.shape
+    bad = np.flatnonzero(got != want)
+    assert bad.size == 0, f"{len(bad)} mismatches, first at {bad[0]}: got {got[bad[0]]} want {want[bad[0]]}"
+
+
+@pytest.mark.parametrize("prec", ["L8R8", "L4R4"])
+@pytest.mark.parametrize("lu,ru", SIGNS)
+@pytest.mark.parametrize("V", [2, 4, 8])
+@pytest.mark.parametrize("Kd", [64, 96, 256, 1056])
+def test_sddmm_unsigned(prec, lu, ru, V, Kd):
+    c = wl.sddmm_case(16 * V, 300, Kd, V, 0.7, prec, 5400 + V + Kd)
+    c["lhs_unsigned"], c["rhs_unsigned"] = lu, ru
+    _sddmm(c)
+
+
+@pytest.mark.parametrize("prec", ["L8R8", "L4R4"])
+def test_sddmm_unsigned_ragged_and_extremes(prec):
+    V, Nc, Kd = 8, 500, 128
+    counts = [0, 1, 15, 16, 17, 63, 64, 65, 0, 129, 500, 3]
+    M = V * len(counts)
+    rp, ci = wl.ragged_pattern(M, Nc, V, counts, 5501)
+    nb = Kd // 2 if prec == "L4R4" else Kd
+    Q, Km = np.full((M, nb), 0xFF, np.uint8), np.full((Nc, nb), 0xFF, np.uint8)     # every operand at its maximum
+    Q[::3] = wl.uniform_packed_int4((len(Q[::3]), nb), 5502)
+    _sddmm(dict(M=M, Nc=Nc, Kd=Kd, V=V, prec=prec, row_ptr=rp, col_idx=ci, Q=Q, Kmat=Km, lhs_unsigned=True, rhs_unsigned=True))
+
+
+@pytest.mark.parametrize("prec", ["L8R8", "L4R4"])
+def test_sddmm_unsigned_full_size_4096(prec):
+    c = wl.sddmm_case(4096, 4096, 256, 8, 0.9, prec, wl.seed_for(3, 77))
+    c["lhs_unsigned"], c["rhs_unsigned"] = True, True
+    _sddmm(c)
