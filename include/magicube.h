@@ -261,6 +261,12 @@ int mc_sparse_attention_batched(const void *Q_dev, const void *Km_dev, const voi
  * Returns MC_EINVAL for other values.  Process-wide.
  * ---------------------------------------------------------------------------------- */
 int mc_set_spmm_variant(int bytes_per_row_tile, int waves);
+/* Matrices whose longest panel is far above the average (more than four times the larger of the
+ * average and 4 chunks) get, at mc_mat_create, a list of work items that cuts long panels into
+ * pieces; mc_spmm then lets several workgroups add their exact int32 partial results into the
+ * (first cleared) rows of such panels.  enable = 0 turns this off (one workgroup per panel and
+ * row tile, as for regular matrices); the result is the same either way.  Process-wide. */
+int mc_set_spmm_splitting(int enable);
 /* SDDMM variant: -1 = automatic, 0 = the kernel that loads operands straight from memory
  * (any row length), 1, 2, 4 or 8 = waves per panel of the kernel that stages Kmat rows in
  * LDS (used when a row has 64, 128, 256 or 512 bytes, else ignored).  Process-wide. */

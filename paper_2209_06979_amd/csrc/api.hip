@@ -2,6 +2,7 @@
 // stream.  See include/magicube.h for the contract of every function.
 #include "internal.h"
 
+#include <algorithm>
 #include <cmath>
 #include <cstdio>
 #include <cstdlib>
@@ -13,6 +14,7 @@ namespace {
 int g_variant_bnb = 0, g_variant_waves = 0;
 int g_sddmm_waves = -1;   // -1 automatic, 0 direct-load kernel, 1/2/4/8 waves of the LDS-staged kernel
 int g_attention_mode = 0; // 0 automatic, 1 always the unfused four-kernel pipeline
+int g_spmm_items = 1;     // 1: matrices with very unequal panels run through their work items
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline int lhs_bits_of(mc_prec p)
@@ -56,6 +58,8 @@ void free_device(mc_mat *A)
     if (A->d_row_ptr) (void)hipFree(A->d_row_ptr);
     if (A->d_slot_idx) (void)hipFree(A->d_slot_idx);
     if (A->d_vals) (void)hipFree(A->d_vals);
+    if (A->d_items) (void)hipFree(A->d_items);
+    if (A->d_split_panels) (void)hipFree(A->d_split_panels);
 }
 
 // Tile variant for a problem (measured on MI355X).  Rows are cut into 128-byte tiles, into
@@ -128,6 +132,12 @@ extern "C" int mc_set_spmm_variant(int bytes_per_row_tile, int waves)
     return MC_OK;
 }
 
+extern "C" int mc_set_spmm_splitting(int enable)
+{
+    g_spmm_items = enable ? 1 : 0;
+    return MC_OK;
+}
+
 extern "C" int mc_set_sddmm_variant(int waves)
 {
     if (waves != -1 && waves != 0 && waves != 1 && waves != 2 && waves != 4 && waves != 8) return MC_EINVAL;
@@ -176,6 +186,35 @@ extern "C" int mc_mat_create(int M, int K, int V, int lhs_bits, const int32_t *r
     }
     A->d_panel_ptr = A->d_row_ptr = A->d_slot_idx = nullptr;
     A->d_vals = nullptr;
+    A->d_items = A->d_split_panels = nullptr;
+    A->n_items = A->n_split = 0;
+    // Work items: only when the longest panel is far above the average; a panel is then cut into
+    // pieces of at most `cap` chunks (cap = twice the average, at least 8).
+    std::vector<int32_t> items, split_panels;
+    {
+        const double avg = lay.P ? (double)(lay.nslots / MC_CHUNK) / lay.P : 0.0;
+        const int cap = std::max(8, (int)std::ceil(2.0 * avg));
+        if (A->max_panel_chunks > 2 * cap) {
+            try {
+                for (int p = 0; p < lay.P; ++p) {
+                    const int c = (row_ptr[p + 1] - row_ptr[p] + MC_CHUNK - 1) / MC_CHUNK;
+                    const int pieces = (c + cap - 1) / cap;
+                    if (pieces > 1) split_panels.push_back(p);
+                    if (pieces <= 1) {
+                        items.insert(items.end(), {p, 0, c, 0});
+                    } else {
+                        const int per = (c + pieces - 1) / pieces;
+                        for (int b = 0; b < c; b += per) items.insert(items.end(), {p, b, std::min(c, b + per), 1});
+                    }
+                }
+            } catch (const std::bad_alloc &) {
+                delete A;
+                return MC_ENOMEM;
+            }
+            A->n_items = (int)(items.size() / 4);
+            A->n_split = (int)split_panels.size();
+        }
+    }
     hipStream_t s = static_cast<hipStream_t>(stream);
 #define MC_TRY(call) (ok = ok && hip_ok((call), #call))
     bool ok = true;
@@ -191,6 +230,13 @@ extern "C" int mc_mat_create(int M, int K, int V, int lhs_bits, const int32_t *r
         MC_TRY(hipMemcpyAsync(A->d_slot_idx, slot_idx.data(), sizeof(int32_t) * (size_t)lay.nslots, hipMemcpyHostToDevice, s));
     if (lay.vals_bytes)
         MC_TRY(hipMemcpyAsync(A->d_vals, vals.data(), (size_t)lay.vals_bytes, hipMemcpyHostToDevice, s));
+    if (A->n_items) {
+        MC_TRY(hipMalloc(&A->d_items, sizeof(int32_t) * items.size()));
+        MC_TRY(hipMalloc(&A->d_split_panels, sizeof(int32_t) * split_panels.size()));
+        MC_TRY(hipMemcpyAsync(A->d_items, items.data(), sizeof(int32_t) * items.size(), hipMemcpyHostToDevice, s));
+        MC_TRY(hipMemcpyAsync(A->d_split_panels, split_panels.data(), sizeof(int32_t) * split_panels.size(),
+                              hipMemcpyHostToDevice, s));
+    }
     MC_TRY(hipStreamSynchronize(s)); // host staging buffers die at return
 #undef MC_TRY
     if (!ok) {
@@ -265,6 +311,11 @@ extern "C" int mc_spmm_flags(const mc_mat *A, const void *B_dev, int N, int ldb,
     a.P = A->P; a.V = A->V; a.batch = 1; a.float_out = 0; a.out_scale = 1.f;
     int bnb, waves;
     choose_variant(A, a.row_bytes, rb == 4, 1, &bnb, &waves);
+    if (A->n_items && g_spmm_items) {
+        // very unequal panels: long ones are shared by several workgroups that add into cleared rows
+        a.items = A->d_items; a.n_units = A->n_items;
+        MC_HIP(launch_zero_rows(C_dev, ldc, N, A->V, A->d_split_panels, A->n_split, static_cast<hipStream_t>(stream)));
+    }
     MC_HIP(launch_spmm(prec, a, bnb, waves, static_cast<hipStream_t>(stream)));
     return MC_OK;
 }

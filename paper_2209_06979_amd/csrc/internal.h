@@ -15,6 +15,12 @@ struct mc_mat {
     int32_t *d_row_ptr;        // P+1: interchange row pointers (vector offsets)
     int32_t *d_slot_idx;       // nslots
     uint8_t *d_vals;           // vals_bytes (null for a pattern-only mask)
+    // Work items for matrices with very unequal panel lengths (null / 0 otherwise): panels longer
+    // than a cap are cut into several items of at most `cap` chunks, so that no single
+    // workgroup is left with a tail many times the average.
+    int32_t *d_items;          // n_items x 4: panel, first chunk, end chunk, 1 if the panel has several items
+    int32_t *d_split_panels;   // n_split: the panels that have several items
+    int n_items, n_split;
 };
 
 // One SpMM launch (optionally a batch of problems sharing the sparsity pattern).
@@ -34,6 +40,10 @@ struct SpmmArgs {
     int float_out;             // 1: write float(acc) * out_scale
     float out_scale;
     int lhs_unsigned, rhs_unsigned; // 4- and 8-bit operands read as non-negative values
+    // optional work items (see mc_mat): null = one unit of work per panel.  Items of a split panel
+    // add their int32 results into C with atomics; C's rows of those panels are cleared first.
+    const int32_t *items;
+    int n_units;               // items, or P
 };
 
 struct SddmmArgs {
@@ -85,6 +95,8 @@ struct AttnArgs {
 };
 
 hipError_t launch_spmm(mc_prec prec, const SpmmArgs &a, int bnb, int waves, hipStream_t s);
+// clears the C rows (int32, n columns) of the listed panels
+hipError_t launch_zero_rows(int32_t *C, int64_t ldc, int n, int V, const int32_t *panels, int n_panels, hipStream_t s);
 // the gather of launch_spmm alone (same tile variant); sink: one int32 per workgroup (P * row tiles)
 hipError_t launch_gather_probe(const SpmmArgs &a, int bnb, int waves, int32_t *sink, hipStream_t s);
 // waves: 0 = the direct-load kernel; 1, 2, 4, 8 = waves per panel of the LDS-staged kernel

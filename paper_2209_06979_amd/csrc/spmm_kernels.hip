@@ -107,14 +107,21 @@ __global__ __launch_bounds__(64 * WK) void spmm_kernel(SpmmArgs a)
     const int j = lane & 15, g = lane >> 4;
     const int rg = lane / LPR, seg = lane % LPR;
     const int ntiles = (a.row_bytes + BNB - 1) / BNB;
-    const int panel = blockIdx.x / ntiles, tile = blockIdx.x % ntiles;
+    const int unit = blockIdx.x / ntiles, tile = blockIdx.x % ntiles;
     const int batch = blockIdx.y;
     const int nb0 = tile * BNB;
 
+    // a unit of work: a whole panel, or (matrices with very unequal panels) a range of its chunks
+    int panel = unit, cb = 0, ce = -1, split = 0;
+    if (a.items) {
+        const v4i it = *reinterpret_cast<const v4i *>(a.items + 4 * unit);
+        panel = it.x; cb = it.y; ce = it.z; split = it.w;
+    }
     const int s0 = a.panel_ptr[2 * panel], s1 = a.panel_ptr[2 * panel + 1];
-    const int nch = (s1 - s0 + MC_CHUNK - 1) / MC_CHUNK;
-    const int64_t chunk0 = s0 / MC_CHUNK;
-    const int32_t *idx = a.slot_idx + s0;
+    if (ce < 0) ce = (s1 - s0 + MC_CHUNK - 1) / MC_CHUNK;
+    const int nch = ce - cb;                       // chunks of this unit: cb .. ce-1
+    const int64_t chunk0 = s0 / MC_CHUNK + cb;
+    const int32_t *idx = a.slot_idx + s0 + cb * MC_CHUNK;
     const uint8_t *vals = a.vals + (int64_t)batch * a.vals_batch_stride;
     const uint8_t *Bb = a.B + (int64_t)batch * a.B_batch_stride + nb0;
     char *stage = lds + w * Cfg::PERWAVE;
@@ -268,6 +275,11 @@ __global__ __launch_bounds__(64 * WK) void spmm_kernel(SpmmArgs a)
         if (a.float_out) {
             const v4f f = {s.x * a.out_scale, s.y * a.out_scale, s.z * a.out_scale, s.w * a.out_scale};
             *reinterpret_cast<v4f *>(static_cast<float *>(a.C) + off) = f;
+        } else if (split) {
+            // several units own this panel: exact, order-independent integer accumulation into rows
+            // that were cleared before the launch
+            int32_t *c = static_cast<int32_t *>(a.C) + off;
+            atomicAdd(c, s.x); atomicAdd(c + 1, s.y); atomicAdd(c + 2, s.z); atomicAdd(c + 3, s.w);
         } else {
             *reinterpret_cast<v4i *>(static_cast<int32_t *>(a.C) + off) = s;
         }
@@ -277,7 +289,7 @@ __global__ __launch_bounds__(64 * WK) void spmm_kernel(SpmmArgs a)
 template <int BNB, int WK, int LB, int RB, bool U> hipError_t launch_one(const SpmmArgs &a, hipStream_t s)
 {
     const int ntiles = (a.row_bytes + BNB - 1) / BNB;
-    dim3 grid((unsigned)(a.P * ntiles), (unsigned)a.batch), block(64 * WK);
+    dim3 grid((unsigned)((a.items ? a.n_units : a.P) * ntiles), (unsigned)a.batch), block(64 * WK);
     hipLaunchKernelGGL((spmm_kernel<BNB, WK, LB, RB, U>), grid, block, 0, s, a);
     return hipGetLastError();
 }
@@ -309,7 +321,24 @@ template <int LB, int RB> hipError_t launch_mode(const SpmmArgs &a, int bnb, int
     return launch_wk<128, LB, RB>(a, waves, s);
 }
 
+__global__ __launch_bounds__(256) void zero_rows_kernel(int32_t *C, int64_t ldc, int n, int V, const int32_t *panels)
+{
+    const int panel = panels[blockIdx.x];
+    const int per_row = n / 4; // n is a multiple of 4 (16-byte pieces of int32)
+    for (int p = threadIdx.x; p < V * per_row; p += 256) {
+        const int row = p / per_row, col = (p % per_row) * 4;
+        *reinterpret_cast<v4i *>(C + (int64_t)(panel * V + row) * ldc + col) = (v4i){0, 0, 0, 0};
+    }
+}
+
 } // namespace
+
+hipError_t launch_zero_rows(int32_t *C, int64_t ldc, int n, int V, const int32_t *panels, int n_panels, hipStream_t s)
+{
+    if (n_panels == 0 || n == 0) return hipSuccess;
+    hipLaunchKernelGGL(zero_rows_kernel, dim3((unsigned)n_panels), dim3(256), 0, s, C, ldc, n, V, panels);
+    return hipGetLastError();
+}
 
 hipError_t launch_spmm(mc_prec prec, const SpmmArgs &a, int bnb, int waves, hipStream_t s)
 {

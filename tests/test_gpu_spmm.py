@@ -180,3 +180,38 @@ def test_gather_probe_fetches_the_rows_spmm_would(bnb, waves):
                 col = ci[rp[p] + c_last * 64]
                 want = int(B[col, t * bnb:t * bnb + 4].copy().view(np.int32)[0])
             assert sink[p * ntiles + t] == want, (p, t)
+
+
+@pytest.mark.parametrize("prec", PRECS + ["L16R16", "L16R4"])
+def test_very_unequal_panels_are_split_into_work_items(prec):
+    """A few panels many times longer than the rest: the library cuts them into several work items whose
+    partial results are added with integer atomics.  Same result with the splitting turned off."""
+    from paper_2209_06979_amd import binding as mc
+    V, K, N = 8, 2048, 192
+    counts = [30] * 40 + [2048, 1500, 0, 1] + [50] * 20
+    M = V * len(counts)
+    rp, ci = wl.ragged_pattern(M, K, V, counts, 181)
+    nvec = len(ci)
+    if prec == "L4R4":
+        vals = wl.uniform_packed_int4((nvec, V // 2), 182)
+    elif prec.startswith("L16"):
+        vals = wl.uniform_int16((nvec, V), 182, -512, 511)
+    else:
+        vals = wl.uniform_int8((nvec, V), 182)
+    if prec.endswith("R4"):
+        B = wl.uniform_packed_int4((K, N // 2), 183)
+    elif prec.endswith("R16"):
+        B = wl.uniform_int16((K, N), 183, -512, 511)
+    else:
+        B = wl.uniform_int8((K, N), 183)
+    case = dict(M=M, K=K, N=N, V=V, prec=prec, row_ptr=rp, col_idx=ci, values=vals, B=B)
+    for variant in [(0, 0), (64, 1), (128, 4)]:
+        _check(case, variant)
+    mc.set_spmm_splitting(False)
+    try:
+        _check(case)
+    finally:
+        mc.set_spmm_splitting(True)
+    if prec == "L8R8":
+        case["lhs_unsigned"] = case["rhs_unsigned"] = True
+        _check(case)
