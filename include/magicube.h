@@ -266,7 +266,7 @@ int mc_set_spmm_variant(int bytes_per_row_tile, int waves);
  * pieces; mc_spmm then lets several workgroups add their exact int32 partial results into the
  * (first cleared) rows of such panels.  enable = 0 turns this off (one workgroup per panel and
  * row tile, as for regular matrices); the result is the same either way.  Process-wide. */
-int mc_set_spmm_splitting(int enable);
+int mc_set_spmm_splitting(int enable); /* also governs the work items of mc_sddmm (no atomics there) */
 /* SDDMM variant: -1 = automatic, 0 = the kernel that loads operands straight from memory
  * (any row length), 1, 2, 4 or 8 = waves per panel of the kernel that stages Kmat rows in
  * LDS (used when a row has 64, 128, 256 or 512 bytes, else ignored).  Process-wide. */

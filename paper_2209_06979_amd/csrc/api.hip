@@ -376,6 +376,7 @@ extern "C" int mc_sddmm_flags(const void *Q_dev, int ldq, const void *Kmat_dev, 
     a.S = S_dev; a.S_batch_stride = 0;
     a.P = mask->P; a.V = mask->V; a.batch = 1;
     a.lhs_unsigned = (flags & MC_LHS_UNSIGNED) ? 1 : 0; a.rhs_unsigned = (flags & MC_RHS_UNSIGNED) ? 1 : 0;
+    if (mask->n_items && g_spmm_items) { a.items = mask->d_items; a.n_units = mask->n_items; } // very unequal panels
     MC_HIP(launch_sddmm(bits, a, choose_sddmm_waves(mask, 1), static_cast<hipStream_t>(stream)));
     return MC_OK;
 }

@@ -59,6 +59,8 @@ struct SddmmArgs {
     int64_t S_batch_stride;    // elements
     int P, V, batch;
     int lhs_unsigned, rhs_unsigned; // 4- and 8-bit operands read as non-negative values
+    const int32_t *items;      // optional work items (see mc_mat): null = one workgroup per panel
+    int n_units;               // items, or P
 };
 
 struct SoftmaxArgs {

@@ -140,10 +140,17 @@ __global__ __launch_bounds__(64 * WK) void sddmm_lds_kernel(SddmmArgs a)
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int j = lane & 15, g = lane >> 4;
     const int rg = lane / LPR, seg = lane % LPR;
-    const int panel = blockIdx.x, batch = blockIdx.y;
+    const int batch = blockIdx.y;
+    // a unit of work: a whole panel, or (masks with very unequal panels) a range of its chunks
+    int panel = blockIdx.x, cb = 0, ce = -1;
+    if (a.items) {
+        const v4i it = *reinterpret_cast<const v4i *>(a.items + 4 * blockIdx.x);
+        panel = it.x; cb = it.y; ce = it.z;
+    }
     const int s0 = a.panel_ptr[2 * panel], n = a.panel_ptr[2 * panel + 1] - s0;
-    const int nch = (n + MC_CHUNK - 1) / MC_CHUNK;
-    const int32_t *idx = a.slot_idx + s0;
+    if (ce < 0) ce = (n + MC_CHUNK - 1) / MC_CHUNK;
+    const int nch = ce - cb;
+    const int32_t *idx = a.slot_idx + s0 + cb * MC_CHUNK;
     const int64_t out0 = (int64_t)batch * a.S_batch_stride + (int64_t)a.row_ptr[panel] * a.V;
     const uint8_t *Km = a.Kmat + (int64_t)batch * a.K_batch_stride;
     char *stage = lds + w * (64 * RB);
@@ -189,7 +196,7 @@ __global__ __launch_bounds__(64 * WK) void sddmm_lds_kernel(SddmmArgs a)
                     mma_step<PB>(qf[kc], kf, kf, acc, acc2);
                 }
             }
-            store_scores(a, out0, c * MC_CHUNK + s, n, g, finish_tile<PB>(acc, acc2));
+            store_scores(a, out0, (cb + c) * MC_CHUNK + s, n, g, finish_tile<PB>(acc, acc2));
         }
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); // reads done before the rows are overwritten
     }
@@ -202,9 +209,14 @@ __global__ __launch_bounds__(64 * SDDMM_WAVES) void sddmm_direct_kernel(SddmmArg
     constexpr int STEP = StepBytes<PB>::value, LANEB = STEP / 4; // bytes per step / per lane and step
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int j = lane & 15, g = lane >> 4;
-    const int panel = blockIdx.x, batch = blockIdx.y;
+    const int batch = blockIdx.y;
+    int panel = blockIdx.x, cb = 0, ce = -1; // unit of work: a panel or a range of its chunks
+    if (a.items) {
+        const v4i it = *reinterpret_cast<const v4i *>(a.items + 4 * blockIdx.x);
+        panel = it.x; cb = it.y; ce = it.z;
+    }
     const int s0 = a.panel_ptr[2 * panel], n = a.panel_ptr[2 * panel + 1] - s0;
-    const int ntile = (n + 15) / 16;
+    const int tile0 = 4 * cb, ntile = (ce < 0) ? (n + 15) / 16 : min((n + 15) / 16, 4 * ce);
     const int64_t out0 = (int64_t)batch * a.S_batch_stride + (int64_t)a.row_ptr[panel] * a.V;
     const uint8_t *Qpanel = a.Q + (int64_t)batch * a.Q_batch_stride + (int64_t)panel * a.V * a.ldq_bytes;
     const uint8_t *Km = a.Kmat + (int64_t)batch * a.K_batch_stride + g * LANEB;
@@ -232,7 +244,7 @@ __global__ __launch_bounds__(64 * SDDMM_WAVES) void sddmm_direct_kernel(SddmmArg
         for (int kc = 0; kc < KC; ++kc) qf[kc] = load_q<PB>(Qpanel, a.ldq_bytes, a.V, a.row_bytes, kc, j, g);
     }
 
-    for (int t = w; t < ntile; t += SDDMM_WAVES) {
+    for (int t = tile0 + w; t < ntile; t += SDDMM_WAVES) {
         const int slot = t * 16 + j;
         const int row = a.slot_idx[s0 + slot]; // padded slots name a valid row
         const uint8_t *kr = Km + (int64_t)row * a.ldk_bytes;
@@ -268,9 +280,14 @@ __global__ __launch_bounds__(64 * SDDMM_WAVES) void sddmm_unsigned_kernel(SddmmA
     static_assert(PB == 8 || PB == 4, "unsigned operands: 4 and 8 bits");
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int j = lane & 15, g = lane >> 4;
-    const int panel = blockIdx.x, batch = blockIdx.y;
+    const int batch = blockIdx.y;
+    int panel = blockIdx.x, cb = 0, ce = -1; // unit of work: a panel or a range of its chunks
+    if (a.items) {
+        const v4i it = *reinterpret_cast<const v4i *>(a.items + 4 * blockIdx.x);
+        panel = it.x; cb = it.y; ce = it.z;
+    }
     const int s0 = a.panel_ptr[2 * panel], n = a.panel_ptr[2 * panel + 1] - s0;
-    const int ntile = (n + 15) / 16;
+    const int tile0 = 4 * cb, ntile = (ce < 0) ? (n + 15) / 16 : min((n + 15) / 16, 4 * ce);
     const int64_t out0 = (int64_t)batch * a.S_batch_stride + (int64_t)a.row_ptr[panel] * a.V;
     const uint8_t *Qrow = a.Q + (int64_t)batch * a.Q_batch_stride + (int64_t)(panel * a.V + (j < a.V ? j : 0)) * a.ldq_bytes + g * 16;
     const uint8_t *Km = a.Kmat + (int64_t)batch * a.K_batch_stride + g * 16;
@@ -306,7 +323,7 @@ __global__ __launch_bounds__(64 * SDDMM_WAVES) void sddmm_unsigned_kernel(SddmmA
     const int nred = kc_n * (PB == 4 ? 128 : 64);                       // reduction elements, padding included
     const int cqck = (a.lhs_unsigned && a.rhs_unsigned) ? (PB == 4 ? 64 : 16384) * nred : 0;
 
-    for (int t = w; t < ntile; t += SDDMM_WAVES) {
+    for (int t = tile0 + w; t < ntile; t += SDDMM_WAVES) {
         const int slot = t * 16 + j;
         const int row = a.slot_idx[s0 + slot]; // padded slots name a valid row
         const uint8_t *kr = Km + (int64_t)row * a.ldk_bytes;
@@ -420,7 +437,7 @@ __global__ __launch_bounds__(256) void repack_kernel(RepackArgs a)
 
 template <int PB, int RB> hipError_t launch_sddmm_lds(const SddmmArgs &a, int waves, hipStream_t s)
 {
-    dim3 grid((unsigned)a.P, (unsigned)a.batch);
+    dim3 grid((unsigned)(a.items ? a.n_units : a.P), (unsigned)a.batch);
     constexpr int MAXW = (64 * RB * 8 <= 65536) ? 8 : ((64 * RB * 4 <= 65536) ? 4 : 2); // 64 KB of stages per workgroup
     if (waves > MAXW) waves = MAXW;
     switch (waves) {
@@ -440,7 +457,7 @@ template <int PB> hipError_t launch_sddmm_bits(const SddmmArgs &a, int waves, hi
         if (a.row_bytes == 256) return launch_sddmm_lds<PB, 256>(a, waves, s);
         if (a.row_bytes == 512) return launch_sddmm_lds<PB, 512>(a, waves, s);
     }
-    dim3 grid((unsigned)a.P, (unsigned)a.batch), block(64 * SDDMM_WAVES);
+    dim3 grid((unsigned)(a.items ? a.n_units : a.P), (unsigned)a.batch), block(64 * SDDMM_WAVES);
     const int kc = (a.row_bytes + StepBytes<PB>::value - 1) / StepBytes<PB>::value;
     if (kc == 1) hipLaunchKernelGGL((sddmm_direct_kernel<PB, 1>), grid, block, 0, s, a);
     else if (kc == 2) hipLaunchKernelGGL((sddmm_direct_kernel<PB, 2>), grid, block, 0, s, a);
@@ -453,7 +470,7 @@ hipError_t launch_sddmm(int bits, const SddmmArgs &a, int waves, hipStream_t s)
 {
     if (a.P == 0 || a.batch == 0) return hipSuccess;
     if (a.lhs_unsigned || a.rhs_unsigned) {
-        dim3 grid((unsigned)a.P, (unsigned)a.batch), block(64 * SDDMM_WAVES);
+        dim3 grid((unsigned)(a.items ? a.n_units : a.P), (unsigned)a.batch), block(64 * SDDMM_WAVES);
         if (bits == 8) hipLaunchKernelGGL((sddmm_unsigned_kernel<8>), grid, block, 0, s, a);
         else if (bits == 4) hipLaunchKernelGGL((sddmm_unsigned_kernel<4>), grid, block, 0, s, a);
         else return hipErrorInvalidValue;

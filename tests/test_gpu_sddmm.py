@@ -220,3 +220,29 @@ def test_attention_ragged_rows():
                                           ("L8R8", 256, 0.95, 2), ("L4R4", 64, 0.95, 4)])
 def test_config3_more_points_full_size(prec, Kd, s, V):
     _check(wl.sddmm_case(4096, 4096, Kd, V, s, prec, wl.seed_for(3, 500 + Kd + int(100 * s) + V)))
+
+
+@pytest.mark.parametrize("prec", ["L8R8", "L4R4", "L16R16"])
+def test_very_unequal_panels_use_work_items(prec):
+    """A few panels many times longer than the rest are cut into several work items (one workgroup each)."""
+    from paper_2209_06979_amd import binding as mc
+    V, Nc, Kd = 8, 2048, 128
+    counts = [30] * 40 + [2048, 1500, 0, 1] + [50] * 20
+    M = V * len(counts)
+    rp, ci = wl.ragged_pattern(M, Nc, V, counts, 191)
+    if prec == "L4R4":
+        Q, Km = wl.uniform_packed_int4((M, Kd // 2), 192), wl.uniform_packed_int4((Nc, Kd // 2), 193)
+    elif prec == "L16R16":
+        Q, Km = wl.uniform_int16((M, Kd), 192), wl.uniform_int16((Nc, Kd), 193)
+    else:
+        Q, Km = wl.uniform_int8((M, Kd), 192), wl.uniform_int8((Nc, Kd), 193)
+    case = dict(M=M, Nc=Nc, Kd=Kd, V=V, prec=prec, row_ptr=rp, col_idx=ci, Q=Q, Kmat=Km)
+    _check(case, variants=(-1, 0, 1, 4))
+    mc.set_spmm_splitting(False)
+    try:
+        _check(case)
+    finally:
+        mc.set_spmm_splitting(True)
+    if prec != "L16R16":
+        case["lhs_unsigned"] = case["rhs_unsigned"] = True
+        _check(case)
