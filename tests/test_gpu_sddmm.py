@@ -246,3 +246,12 @@ def test_very_unequal_panels_use_work_items(prec):
     if prec != "L16R16":
         case["lhs_unsigned"] = case["rhs_unsigned"] = True
         _check(case)
+
+
+def test_config3_whole_grid_full_size():
+    """Every point of BASELINE config 3: Kd in {64,128,256} x sparsity in {0.7,0.9,0.95} x {L8-R8, L4-R4} at
+    4096 x 4096, V = 8, whole outputs compared (18 points)."""
+    for prec in ("L8R8", "L4R4"):
+        for s in (0.7, 0.9, 0.95):
+            for Kd in (64, 128, 256):
+                _check(wl.sddmm_case(4096, 4096, Kd, 8, s, prec, wl.seed_for(3, 3000 + Kd + int(100 * s))))

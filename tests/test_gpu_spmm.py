@@ -215,3 +215,24 @@ def test_very_unequal_panels_are_split_into_work_items(prec):
     if prec == "L8R8":
         case["lhs_unsigned"] = case["rhs_unsigned"] = True
         _check(case)
+
+
+@pytest.mark.parametrize("prec", ["L8R8", "L8R4", "L4R4"])
+def test_config2_whole_grid_full_size(prec):
+    """Every point of BASELINE config 2 for one precision: V in {2,4,8} x sparsity in {0.5 .. 0.98} x
+    N in {128,256,512} at 4096 x 4096, whole outputs compared (54 points per precision)."""
+    import torch
+    from paper_2209_06979_amd import binding as mc
+    for V in (2, 4, 8):
+        for s in (0.5, 0.7, 0.8, 0.9, 0.95, 0.98):
+            # one pattern and one set of A values per (V, s); B per N
+            base = wl.spmm_case(4096, 4096, 512, V, s, prec, wl.seed_for(2, 2000 + int(s * 100) + 10 * V))
+            A = mc.SparseMatrix(4096, 4096, V, base["row_ptr"], base["col_idx"], base["values"], mc.LHS_BITS[prec])
+            for N in (128, 256, 512):
+                nb = N // 2 if prec != "L8R8" else N
+                Bh = np.ascontiguousarray(base["B"][:, :nb])
+                print(f"config 2: {prec} V={V} s={s} N={N}", flush=True)
+                got = mc.spmm(A, torch.from_numpy(Bh).cuda(), prec).cpu().numpy()
+                want = run_spmm_oracle(dict(base, N=N, B=Bh))
+                assert np.array_equal(got, want), (prec, V, s, N)
+            A.close()
