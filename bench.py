@@ -258,6 +258,7 @@ def main():
         "gather_peak_tbs_measured": (extras or {}).get("gather_peak_tbs"),
         "beyond_the_step": (extras or {}).get("wider_precisions"),
         "layer_at_inference_shapes": (extras or {}).get("layer_at_inference_shapes"),
+        "quantisation_streaming": (extras or {}).get("quantisation_streaming"),
         "per_kernel": per_kernel,
         "format_build_s": round(format_build_s, 3),
         "roofline": roofline,
@@ -401,6 +402,19 @@ def measure_extras(mc, torch, prob, stream, reps, up):
                 shapes[f"L{L}_h{heads}_b{batch}_s{sp}_{name}_{layout}-major"] = dict(us=round(us, 1), eff_tops=round(ops / us / 1e6, 1))
         m.close()
     out["layer_at_inference_shapes"] = shapes
+
+    # The layer's first step, quantisation of fp32 projections (a pure streaming kernel): a batch
+    # of 64 layers' worth of one tensor, 128 Mi elements, far beyond every cache.
+    xs = torch.empty(64 * HEADS * L_ATT * DK, dtype=torch.float32, device="cuda").normal_()
+    qs = torch.empty(xs.numel(), dtype=torch.int8, device="cuda")
+    mx = torch.empty(1, dtype=torch.float32, device="cuda")
+    quant = {}
+    for name, fn, nbytes in (("absmax", lambda: mc.absmax(xs, out=mx), 4 * xs.numel()),
+                             ("quantize_int8", lambda: mc.quantize(xs, 0.03, 8, out=qs), 5 * xs.numel())):
+        us = time_graph(torch, stream, [fn] * 5)
+        quant[name] = dict(us=round(us, 1), gbs=round(nbytes / us / 1e3, 1), hbm_frac=round(nbytes / us / 1e3 / HBM_PEAK_GBS, 3))
+    out["quantisation_streaming"] = quant
+    del xs, qs
     return out
 
 

@@ -201,6 +201,18 @@ int mc_sparse_softmax_bits(const mc_mat *mask, int batch, const int32_t *S_dev, 
                            float inv_s_p, int code_bits, void *codes_dev, void *stream);
 
 /* ------------------------------------------------------------------------------------
+ * Quantisation of the layer's inputs (Section 5.3, first step): symmetric, one scale per tensor.
+ *   mc_absmax    *result_dev (device float) = max |x_dev[i]|, i < n; the caller takes
+ *                scale = max / 127 (8 bits) or max / 7 (4 bits), or uses a calibrated constant
+ *   mc_quantize  q[i] = clamp(rint(x[i] / scale), -qmax, qmax), ties to even, decided as in double
+ *                precision; bits = 8: int8 codes; bits = 4: two codes per byte (element 2j in bits
+ *                3:0 of byte j), n even.  x_dev 16-byte aligned, q_dev 8-byte aligned.
+ * Other widths: MC_EUNSUPPORTED; scale must be finite and positive.
+ * ---------------------------------------------------------------------------------- */
+int mc_absmax(const float *x_dev, int64_t n, float *result_dev, void *stream);
+int mc_quantize(const float *x_dev, int64_t n, float scale, int bits, void *q_dev, void *stream);
+
+/* ------------------------------------------------------------------------------------
  * Quantized sparse self-attention layer (Section 5.3), one mask shared by all heads:
  *   O[h] = ( P_q[h] * Vm[h] ) * (s_p * s_v),
  *   P_q[h] = int8( softmax( SDDMM(Q[h], Km[h]; mask) * s_q*s_k/sqrt(dk) ) / s_p )

@@ -79,6 +79,8 @@ def _load() -> ctypes.CDLL:
     L.mc_sparse_attention_batched.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int64, c_int64,
                                               c_int64, c_void_p, c_int, c_int, c_float, c_float, c_float, c_float,
                                               c_void_p, c_void_p, c_size_t, c_void_p]
+    L.mc_absmax.argtypes = [c_void_p, c_int64, c_void_p, c_void_p]
+    L.mc_quantize.argtypes = [c_void_p, c_int64, c_float, c_int, c_void_p, c_void_p]
     L.mc_set_spmm_variant.argtypes = [c_int, c_int]
     L.mc_set_attention_mode.argtypes = [c_int]
     L.mc_set_spmm_splitting.argtypes = [c_int]
@@ -86,6 +88,7 @@ def _load() -> ctypes.CDLL:
     for name in ("mc_layout_query", "mc_pack_host", "mc_unpack_host", "mc_mat_create", "mc_mat_set_values_device",
                  "mc_mat_info", "mc_spmm", "mc_spmm_flags", "mc_sddmm", "mc_sddmm_flags", "mc_sparse_softmax", "mc_sparse_softmax_bits", "mc_sparse_attention",
                  "mc_sparse_attention_strided", "mc_sparse_attention_bits", "mc_sparse_attention_batched", "mc_probe_gather",
+                 "mc_absmax", "mc_quantize",
                  "mc_set_spmm_variant", "mc_set_attention_mode", "mc_set_sddmm_variant", "mc_set_spmm_splitting"):
         getattr(L, name).restype = c_int
     return L
@@ -249,6 +252,31 @@ def sddmm(Q, Kmat, mask: SparseMatrix, prec: str, out=None, lhs_unsigned: bool =
     _check(lib.mc_sddmm_flags(Q.data_ptr(), Q.stride(0) * Q.element_size() * 8 // bits, Kmat.data_ptr(),
                               Kmat.stride(0) * Kmat.element_size() * 8 // bits, Kd,
                               mask.handle, PREC[prec], flags, out.data_ptr(), _stream()), "mc_sddmm_flags")
+    return out
+
+
+def absmax(x, out=None):
+    """max |x| of a contiguous fp32 device tensor, as a one-element device tensor."""
+    assert x.is_cuda and x.dtype == torch.float32 and x.is_contiguous()
+    if out is None:
+        out = torch.empty(1, dtype=torch.float32, device=x.device)
+    _check(lib.mc_absmax(x.data_ptr(), x.numel(), out.data_ptr(), _stream()), "mc_absmax")
+    return out
+
+
+def quantize(x, scale: float, bits: int = 8, out=None):
+    """Symmetric quantisation of a contiguous fp32 device tensor: int8 codes of the same shape, or
+    (bits=4) uint8 with half the last dimension, two codes per byte."""
+    assert x.is_cuda and x.dtype == torch.float32 and x.is_contiguous()
+    if out is None:
+        if bits == 4:
+            out = torch.empty(x.shape[:-1] + (x.shape[-1] // 2,), dtype=torch.uint8, device=x.device)
+        else:
+            out = torch.empty(x.shape, dtype=torch.int8, device=x.device)
+    assert out.is_cuda and out.is_contiguous()
+    if out.numel() * (2 if bits == 4 else 1) != x.numel() and bits in (4, 8):
+        raise MagicubeError(MC_EINVAL, "quantize(out size)")
+    _check(lib.mc_quantize(x.data_ptr(), x.numel(), float(scale), bits, out.data_ptr(), _stream()), "mc_quantize")
     return out
 
 

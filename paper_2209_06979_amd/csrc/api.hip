@@ -381,6 +381,24 @@ extern "C" int mc_sddmm_flags(const void *Q_dev, int ldq, const void *Kmat_dev, 
     return MC_OK;
 }
 
+extern "C" int mc_absmax(const float *x_dev, int64_t n, float *result_dev, void *stream)
+{
+    if (!x_dev || !result_dev || n < 0) return MC_EINVAL;
+    if (!aligned16(x_dev)) return MC_EALIGN;
+    MC_HIP(launch_absmax(x_dev, n, result_dev, static_cast<hipStream_t>(stream)));
+    return MC_OK;
+}
+
+extern "C" int mc_quantize(const float *x_dev, int64_t n, float scale, int bits, void *q_dev, void *stream)
+{
+    if (!x_dev || !q_dev || n < 0) return MC_EINVAL;
+    if (bits != 8 && bits != 4) return MC_EUNSUPPORTED;
+    if (!(scale > 0.f) || !std::isfinite(scale) || (bits == 4 && n % 2 != 0)) return MC_EINVAL;
+    if (!aligned16(x_dev) || (reinterpret_cast<uintptr_t>(q_dev) & 7u) != 0) return MC_EALIGN;
+    MC_HIP(launch_quantize(x_dev, n, scale, bits, static_cast<uint8_t *>(q_dev), static_cast<hipStream_t>(stream)));
+    return MC_OK;
+}
+
 extern "C" int mc_sparse_softmax_bits(const mc_mat *mask, int batch, const int32_t *S_dev, float score_scale,
                                       float inv_s_p, int code_bits, void *codes_dev, void *stream)
 {

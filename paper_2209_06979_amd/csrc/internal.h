@@ -105,6 +105,8 @@ hipError_t launch_gather_probe(const SpmmArgs &a, int bnb, int waves, int32_t *s
 // (used when a row has 64, 128, 256 or 512 bytes)
 hipError_t launch_sddmm(int bits, const SddmmArgs &a, int waves, hipStream_t s);
 hipError_t launch_softmax(const SoftmaxArgs &a, hipStream_t s);
+hipError_t launch_absmax(const float *x, int64_t n, float *result, hipStream_t s);
+hipError_t launch_quantize(const float *x, int64_t n, float scale, int bits, uint8_t *q, hipStream_t s);
 hipError_t launch_repack(const RepackArgs &a, hipStream_t s);
 // heads_per_group 2 needs head_stride == 64 (token-major layout) and an even head count
 hipError_t launch_attention_fused(const AttnArgs &a, int heads_per_group, int waves_per_panel, int p_bits, int qkv_bits,
