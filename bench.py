@@ -4,7 +4,8 @@
 A *step* is one pass of every kernel row of the path at the headline shape
 (4096 x 4096, V = 8, 90 % of the vectors zero): SpMM L8-R8 / L8-R4 / L4-R4 / L16-R8
 with N = 256, SDDMM L8-R8 / L4-R4 with K = 256, and the quantized sparse-attention
-layer (8 heads, L = 4096, d_k = 64, Q/K/V as (heads, L, d_k): SDDMM -> softmax -> int8 -> SpMM).  Inputs are
+layer (8 heads, L = 4096, d_k = 64, Q/K/V as a QKV projection writes them, (L, heads, d_k): SDDMM -> softmax ->
+int8 -> SpMM).  Inputs are
 seeded synthetic data already resident in HBM; the sparse operands were converted to
 the device format beforehand (the paper builds its format offline as well).
 
@@ -36,8 +37,8 @@ I8_MFMA_PEAK_TOPS = 5000.0  # MI355X dense int8, published
 # x1.999 and x1.000).  Counters cannot be read from inside the benchmark; refresh these
 # together with profiles/bench_step_counters.txt.
 MEASURED_TRAFFIC_BYTES = {
-    "spmm_L8R8": 14.03e6, "spmm_L8R4": 14.02e6, "spmm_L4R4": 12.19e6, "spmm_L16R8": 17.69e6,
-    "sddmm_L8R8": 17.23e6, "sddmm_L4R4": 12.51e6, "attention": 22.28e6,
+    "spmm_L8R8": 14.03e6, "spmm_L8R4": 14.02e6, "spmm_L4R4": 12.19e6, "spmm_L16R8": 17.70e6,
+    "sddmm_L8R8": 17.23e6, "sddmm_L4R4": 12.51e6, "attention": 22.79e6,
 }
 
 M = K = 4096
@@ -83,7 +84,7 @@ def main():
     ap.add_argument("--reps", type=int, default=200, help="back-to-back launches for the per-kernel timings")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--only", default="", help="comma-separated kernel names: run only these in the step")
-    ap.add_argument("--attention-layout", choices=["token", "head"], default="head",
+    ap.add_argument("--attention-layout", choices=["token", "head"], default="token",
                     help="Q/K/V buffers token-major (L, heads, dk) as a projection writes them, or head-major (heads, L, dk)")
     ap.add_argument("--no-per-kernel", action="store_true", help="skip the per-kernel timing runs (counter collection)")
     ap.add_argument("--no-extras", action="store_true",
@@ -227,15 +228,17 @@ def main():
     achieved = dom["bytes"] / (dom["us"] * 1e-6) / 1e9
     roofline = dict(bound="hbm", kernel=dom["name"], achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s",
                     frac=round(achieved / HBM_PEAK_GBS, 4),
-                    traffic=(MEASURED_TRAFFIC_BYTES.get(dom["name"]) if args.attention_layout == "head" else None),
+                    traffic=(MEASURED_TRAFFIC_BYTES.get(dom["name"]) if args.attention_layout == "token" else None),
                     us_per_launch=round(dom["us"], 2), algorithmic_bytes=int(dom["bytes"]))
     if extras is not None and dom["name"] == "attention":
         # the practical bound of the dominant kernel: its K and V rows (64 bytes each, padded slots
         # included) at the gather rate measured above
+        # (token-major: the rows of two neighbouring heads are fetched as one 128-byte piece)
         gb = HEADS * 2 * amask.nslots * DK
+        pk = extras["gather_peak_tbs"]["rows_128B" if args.attention_layout == "token" else "rows_64B"]
         roofline["gathered_bytes"] = int(gb)
-        roofline["gather_peak_tbs_measured"] = extras["gather_peak_tbs"]["rows_64B"]
-        roofline["frac_of_gather_peak"] = round(gb / extras["gather_peak_tbs"]["rows_64B"] / 1e6 / dom["us"], 3)
+        roofline["gather_peak_tbs_measured"] = pk
+        roofline["frac_of_gather_peak"] = round(gb / pk / 1e6 / dom["us"], 3)
     per_kernel = {k["name"]: dict(us=round(k["us"], 2), eff_tops=round(k["ops"] / k["us"] / 1e6, 1),
                                   alg_gbs=round(k["bytes"] / k["us"] / 1e3, 1),
                                   hbm_frac=round(k["bytes"] / k["us"] / 1e3 / HBM_PEAK_GBS, 4),

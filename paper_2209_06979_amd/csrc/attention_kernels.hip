@@ -88,7 +88,11 @@ void attention_fused_kernel(AttnArgs a)
     constexpr int NW = HPW * KS;         // waves per workgroup
     constexpr int PLANE = MAXCH * 512;   // bytes of one plane of codes, [slot][8 rows]
     constexpr int OTILE = (PB == 16 ? 16 : 8) * (64 + 4) * 4;                       // a wave's output tile, staged in the same area
-    constexpr int PLB = (PLANE * (PB / 8) > OTILE) ? PLANE * (PB / 8) : OTILE;      // bytes of that area
+    // HPW 2: the code area holds ONE chunk (codes are written right before they are read) and the
+    // output tile is staged in the gather stages, which keeps a workgroup below 20 KB of LDS:
+    // eight of them, i.e. all 2048 of a 8 x 4096 layer, are resident at once.
+    constexpr bool SMALLP = (HPW == 2);
+    constexpr int PLB = SMALLP ? 512 : ((PLANE * (PB / 8) > OTILE) ? PLANE * (PB / 8) : OTILE); // bytes of that area
     constexpr int DK = 64;
     constexpr int DKB = DK * QB / 8; // bytes of one head's row
     constexpr int NPR = MAXCH * 2;   // pairs of score tiles
@@ -326,7 +330,7 @@ void attention_fused_kernel(AttnArgs a)
             // Done here, chunk by chunk, so that this ALU work overlaps the V copies in flight.
 #pragma unroll
             for (int pr = 0; pr < 2; ++pr) {
-                const int slot = c * MC_CHUNK + (2 * pr + (g >> 1)) * 16 + j;
+                const int slot = (SMALLP ? 0 : c * MC_CHUNK) + (2 * pr + (g >> 1)) * 16 + j;
                 if (PB == 8) {
                     unsigned packed = 0;
 #pragma unroll
@@ -348,7 +352,7 @@ void attention_fused_kernel(AttnArgs a)
             }
             acquire(Vg, gc);
             // the codes, transposed to the MFMA row operand: row j < 8, slots g*16 .. +15
-            const int pstep = (PB == 8 && (src & 1)) ? 0 : c * 512; // the zero bytes do not move
+            const int pstep = (SMALLP || (PB == 8 && (src & 1))) ? 0 : c * 512; // the zero bytes do not move
             const v2i p0 = lds_read_tr8(paddr[0] + pstep), p1 = lds_read_tr8(paddr[1] + pstep);
             v2i d[NITW][2];
 #pragma unroll
@@ -374,7 +378,11 @@ void attention_fused_kernel(AttnArgs a)
 
     // ---- output: 8 x 64 tile through this wave's code area, scaled, 16-byte stores -------------
     vm_wait<0>();
-    int *Ol = reinterpret_cast<int *>(Pl);
+    if (SMALLP) {
+        lgkm_wait();
+        __builtin_amdgcn_s_barrier(); // nobody reads the stages any more: each wave takes one for its tile
+    }
+    int *Ol = reinterpret_cast<int *>(SMALLP ? stage_all + w * STG : Pl);
     if (g < 2 || PB == 16) {
 #pragma unroll
         for (int ct = 0; ct < 4; ++ct)
