@@ -126,3 +126,41 @@ def test_compute_entry_points_reject_null_handles_without_a_gpu():
     assert mc.lib.mc_set_spmm_variant(96, 0) == mc.MC_EINVAL and mc.lib.mc_set_spmm_variant(0, 3) == mc.MC_EINVAL
     assert mc.lib.mc_set_spmm_variant(0, 0) == mc.MC_OK
     mc.lib.mc_mat_destroy(None)
+
+
+def test_12_bit_values_are_stored_like_16_and_range_checked():
+    counts = [3, 0, 70]
+    M, K, rp, ci, _ = _case(8, 16, counts, seed=99)
+    vals = wl.uniform_int16((len(ci), 8), 100, -2048, 2047)
+    pp, si, sv = mc.pack_host(M, K, 8, 12, rp, ci, vals)
+    pp16, si16, sv16 = mc.pack_host(M, K, 8, 16, rp, ci, vals)
+    assert np.array_equal(sv, sv16) and np.array_equal(si, si16)
+    rp2, ci2, v2 = mc.unpack_host(M, K, 8, 12, pp, si, sv)
+    assert np.array_equal(v2.view(np.int16).reshape(-1, 8), vals)
+    bad = vals.copy()
+    bad[1, 2] = 2048
+    with pytest.raises(mc.MagicubeError) as e:
+        mc.pack_host(M, K, 8, 12, rp, ci, bad)
+    assert e.value.status == mc.MC_ERANGE
+
+
+def test_entry_points_reject_bad_arguments_before_touching_the_gpu():
+    """Null handles / pointers and unknown knob values come back as status codes (no GPU needed)."""
+    L = mc.lib
+    assert L.mc_spmm(None, None, 16, 16, 0, None, 16, None) == mc.MC_EINVAL
+    assert L.mc_spmm_flags(None, None, 16, 16, 0, 0, None, 16, None) == mc.MC_EINVAL
+    assert L.mc_sddmm(None, 64, None, 64, 64, None, 0, None, None) == mc.MC_EINVAL
+    assert L.mc_sddmm_flags(None, 64, None, 64, 64, None, 0, 3, None, None) == mc.MC_EINVAL
+    assert L.mc_sparse_softmax_bits(None, 1, None, 1.0, 1.0, 8, None, None) == mc.MC_EINVAL
+    assert L.mc_sparse_attention_batched(None, None, None, 1, 1, 8, 64, 0, 512, 64, None, 8, 8, 1.0, 1.0, 1.0, 1.0,
+                                         None, None, 0, None) == mc.MC_EINVAL
+    assert L.mc_absmax(None, 4, None, None) == mc.MC_EINVAL
+    assert L.mc_quantize(None, 4, 1.0, 8, None, None) == mc.MC_EINVAL
+    assert L.mc_probe_gather(None, None, 16, 16, 0, None, None) == mc.MC_EINVAL
+    assert L.mc_mat_info(None, None, None, None, None, None, None) == mc.MC_EINVAL
+    assert L.mc_mat_set_values_device(None, None, None) == mc.MC_EINVAL
+    assert L.mc_set_attention_mode(9) == mc.MC_EINVAL and L.mc_set_attention_mode(0) == mc.MC_OK
+    assert L.mc_set_spmm_variant(100, 1) == mc.MC_EINVAL and L.mc_set_spmm_variant(0, 0) == mc.MC_OK
+    assert L.mc_set_sddmm_variant(3) == mc.MC_EINVAL and L.mc_set_sddmm_variant(-1) == mc.MC_OK
+    assert L.mc_attention_workspace_bytes_bits(4, None, 8) == 0
+    assert L.mc_probe_gather_sink_len(None, 16, 0) == 0
