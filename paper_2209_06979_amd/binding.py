@@ -84,12 +84,13 @@ def _load() -> ctypes.CDLL:
     L.mc_set_spmm_variant.argtypes = [c_int, c_int]
     L.mc_set_attention_mode.argtypes = [c_int]
     L.mc_set_spmm_splitting.argtypes = [c_int]
+    L.mc_set_spmm_stages.argtypes = [c_int]
     L.mc_set_sddmm_variant.argtypes = [c_int]
     for name in ("mc_layout_query", "mc_pack_host", "mc_unpack_host", "mc_mat_create", "mc_mat_set_values_device",
                  "mc_mat_info", "mc_spmm", "mc_spmm_flags", "mc_sddmm", "mc_sddmm_flags", "mc_sparse_softmax", "mc_sparse_softmax_bits", "mc_sparse_attention",
                  "mc_sparse_attention_strided", "mc_sparse_attention_bits", "mc_sparse_attention_batched", "mc_probe_gather",
                  "mc_absmax", "mc_quantize",
-                 "mc_set_spmm_variant", "mc_set_attention_mode", "mc_set_sddmm_variant", "mc_set_spmm_splitting"):
+                 "mc_set_spmm_variant", "mc_set_attention_mode", "mc_set_sddmm_variant", "mc_set_spmm_splitting", "mc_set_spmm_stages"):
         getattr(L, name).restype = c_int
     return L
 
@@ -196,6 +197,10 @@ class SparseMatrix:
 
 def set_spmm_variant(bytes_per_row_tile: int = 0, waves: int = 0) -> None:
     _check(lib.mc_set_spmm_variant(bytes_per_row_tile, waves), "mc_set_spmm_variant")
+
+
+def set_spmm_stages(stages: int = 2) -> None:
+    _check(lib.mc_set_spmm_stages(stages), "mc_set_spmm_stages")
 
 
 def set_spmm_splitting(enable: bool = True) -> None:

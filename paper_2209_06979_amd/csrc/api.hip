@@ -15,6 +15,7 @@ int g_variant_bnb = 0, g_variant_waves = 0;
 int g_sddmm_waves = -1;   // -1 automatic, 0 direct-load kernel, 1/2/4/8 waves of the LDS-staged kernel
 int g_attention_mode = 0; // 0 automatic, 1 always the unfused four-kernel pipeline
 int g_spmm_items = 1;     // 1: matrices with very unequal panels run through their work items
+int g_spmm_stages = 2;    // chunks in flight per wave of the SpMM kernel (1 or 2)
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline int lhs_bits_of(mc_prec p)
@@ -132,6 +133,13 @@ extern "C" int mc_set_spmm_variant(int bytes_per_row_tile, int waves)
     return MC_OK;
 }
 
+extern "C" int mc_set_spmm_stages(int stages)
+{
+    if (stages != 1 && stages != 2) return MC_EINVAL;
+    g_spmm_stages = stages;
+    return MC_OK;
+}
+
 extern "C" int mc_set_spmm_splitting(int enable)
 {
     g_spmm_items = enable ? 1 : 0;
@@ -188,6 +196,7 @@ extern "C" int mc_mat_create(int M, int K, int V, int lhs_bits, const int32_t *r
     A->d_vals = nullptr;
     A->d_items = A->d_split_panels = nullptr;
     A->n_items = A->n_split = 0;
+    A->max_item_chunks = 0;
     // Work items: only when the longest panel is far above the average; a panel is then cut into
     // pieces of at most `cap` chunks (cap = twice the average, at least 8).
     std::vector<int32_t> items, split_panels;
@@ -213,6 +222,8 @@ extern "C" int mc_mat_create(int M, int K, int V, int lhs_bits, const int32_t *r
             }
             A->n_items = (int)(items.size() / 4);
             A->n_split = (int)split_panels.size();
+            A->max_item_chunks = 0;
+            for (size_t i = 0; i < items.size(); i += 4) A->max_item_chunks = std::max(A->max_item_chunks, items[i + 2] - items[i + 1]);
         }
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -311,7 +322,10 @@ extern "C" int mc_spmm_flags(const mc_mat *A, const void *B_dev, int N, int ldb,
     a.P = A->P; a.V = A->V; a.batch = 1; a.float_out = 0; a.out_scale = 1.f;
     int bnb, waves;
     choose_variant(A, a.row_bytes, rb == 4, 1, &bnb, &waves);
+    a.stages = (g_spmm_stages == 2 && (int64_t)(A->K - 1) * a.ldb_bytes + a.row_bytes < ((int64_t)1 << 32)) ? 2 : 1;
+    a.max_unit_chunks = A->max_panel_chunks;
     if (A->n_items && g_spmm_items) {
+        a.max_unit_chunks = A->max_item_chunks;
         // very unequal panels: long ones are shared by several workgroups that add into cleared rows
         a.items = A->d_items; a.n_units = A->n_items;
         MC_HIP(launch_zero_rows(C_dev, ldc, N, A->V, A->d_split_panels, A->n_split, static_cast<hipStream_t>(stream)));
@@ -476,6 +490,8 @@ int attention_pipeline(const uint8_t *Q, const uint8_t *Km, const uint8_t *Vm, i
     m.B = Vm; m.ldb_bytes = token_stride_bytes; m.B_batch_stride = head_stride_bytes;
     m.row_bytes = row_bytes; m.C = O; m.ldc = o_token_stride; m.C_batch_stride = o_head_stride;
     m.P = mask->P; m.V = 8; m.batch = heads; m.float_out = 1; m.out_scale = s_p * s_v;
+    m.stages = (g_spmm_stages == 2 && (int64_t)(mask->K - 1) * m.ldb_bytes + m.row_bytes < ((int64_t)1 << 32)) ? 2 : 1;
+    m.max_unit_chunks = mask->max_panel_chunks;
     int bnb, waves;
     choose_variant(mask, m.row_bytes, qkv_bits == 4, heads, &bnb, &waves);
     const mc_prec prec = (p_bits == 16) ? (qkv_bits == 4 ? MC_L16R4 : MC_L16R8) : (qkv_bits == 4 ? MC_L8R4 : MC_L8R8);

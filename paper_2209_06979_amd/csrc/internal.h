@@ -21,6 +21,7 @@ struct mc_mat {
     int32_t *d_items;          // n_items x 4: panel, first chunk, end chunk, 1 if the panel has several items
     int32_t *d_split_panels;   // n_split: the panels that have several items
     int n_items, n_split;
+    int max_item_chunks;       // chunks of the longest item
 };
 
 // One SpMM launch (optionally a batch of problems sharing the sparsity pattern).
@@ -44,6 +45,8 @@ struct SpmmArgs {
     // add their int32 results into C with atomics; C's rows of those panels are cleared first.
     const int32_t *items;
     int n_units;               // items, or P
+    int stages;                // chunks in flight per wave: 1 or 2 (2 needs B to span less than 4 GiB)
+    int max_unit_chunks;       // chunks of the longest unit of work (panel or work item)
 };
 
 struct SddmmArgs {

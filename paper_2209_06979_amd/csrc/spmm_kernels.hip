@@ -38,6 +38,7 @@
 // The sum over a chunk does not depend on the order of its terms; slot s of a chunk is
 // reduction byte (s % 16) of lane group (s / 16) on both the A and the B side.
 #include "internal.h"
+#include "lds_async.h"
 
 namespace {
 
@@ -73,7 +74,17 @@ __device__ __forceinline__ v4i load_a(const uint8_t *vals, int64_t chunk, int V,
     return a;
 }
 
-template <int BNB, int WK, int LB, int RB, bool U = false> struct SpmmCfg {
+// NS: chunks in flight per wave.  1: the copies are issued through the compiler's builtin, which
+// makes it wait for all of them before the first LDS read (any extent of B, any panel length).
+// 2: the copies are issued from inline assembly into two alternating stages and only the older
+// chunk is waited for (counted s_waitcnt); for waves with at most SPMM_PIPE_CHUNKS chunks; lane
+// offsets are 32 bits, so B must span less than 4 GiB.
+constexpr int SPMM_PIPE_CHUNKS = 4;
+
+// Makes the compiler treat x as used and redefined here: a load into x that is still in flight is
+// waited for at this point (and at no later one).
+__device__ __forceinline__ void pin(v4i &x) { asm volatile("" : "+v"(x)); }
+template <int BNB, int WK, int LB, int RB, bool U = false, int NS = 1> struct SpmmCfg {
     static constexpr bool R4 = (RB == 4), R16 = (RB == 16), L16 = (LB == 16);
     static_assert(!U || (!R16 && !L16), "unsigned operands: 4 and 8 bits");
     static constexpr int LPR = BNB / 16;                 // lanes (16-byte segments) per row
@@ -88,14 +99,14 @@ template <int BNB, int WK, int LB, int RB, bool U = false> struct SpmmCfg {
     static constexpr int OROWS = L16 ? 16 : (U ? 12 : 8); // rows of a partial tile (U: row 8 holds column sums of B)
     static constexpr int TST = COLS + 4;                 // row stride (ints) of a partial tile: +4 keeps rows 4 apart in different banks
     static constexpr int OTILE = OROWS * TST * 4;        // bytes of one wave's partial tile
-    static constexpr int PERWAVE = (STAGE > OTILE) ? STAGE : OTILE;
+    static constexpr int PERWAVE = (NS * STAGE > OTILE) ? NS * STAGE : OTILE;
     static constexpr int LDS = WK * PERWAVE;
 };
 
-template <int BNB, int WK, int LB, int RB, bool U = false>
+template <int BNB, int WK, int LB, int RB, bool U = false, int NS = 1>
 __global__ __launch_bounds__(64 * WK) void spmm_kernel(SpmmArgs a)
 {
-    using Cfg = SpmmCfg<BNB, WK, LB, RB, U>;
+    using Cfg = SpmmCfg<BNB, WK, LB, RB, U, NS>;
     constexpr int LPR = Cfg::LPR, NI = Cfg::NI, RPI = Cfg::RPI, NACC = Cfg::NACC, COLS = Cfg::COLS, TST = Cfg::TST;
     constexpr int OUTC = Cfg::OUTC;
     constexpr bool R4 = Cfg::R4, R16 = Cfg::R16, L16 = Cfg::L16;
@@ -159,25 +170,21 @@ __global__ __launch_bounds__(64 * WK) void spmm_kernel(SpmmArgs a)
     }
     // R16: lanes that own an even byte column (low bytes) flip the top bit of every byte
     const int lowflip = (R16 && !(j & 1)) ? (int)0x80808080 : 0;
-    v4i idxv[NI / 4];
-    if (nmy > 0) load_idx(w, idxv);
-    for (int k = 0; k < nmy; ++k) {
-        const int c = w + k * WK;
-#pragma unroll
-        for (int i = 0; i < NI; ++i)
-            __builtin_amdgcn_global_load_lds((gptr_t *)(Bb + (int64_t)idxv[i >> 2][i & 3] * a.ldb_bytes + segoff[i]),
-                                             (lptr_t *)(stage + i * 1024), 16, 0, 0);
-        v4i a_cur = load_a<LB>(vals, chunk0 + c, a.V, j, g);
+    // the A operand of chunk c of this wave's share, ready for the MFMA
+    auto load_a_op = [&](int c) -> v4i {
+        v4i av = load_a<LB>(vals, chunk0 + c, a.V, j, g);
         if (U) {
-            if (j < a.V) a_cur ^= (v4i){axor, axor, axor, axor};
-            if (j == 8) a_cur = (v4i){0x01010101, 0x01010101, 0x01010101, 0x01010101}; // row 8 collects the column sums of B
+            if (j < a.V) av ^= (v4i){axor, axor, axor, axor};
+            if (j == 8) av = (v4i){0x01010101, 0x01010101, 0x01010101, 0x01010101}; // row 8 collects the column sums of B
         }
-        if (k + 1 < nmy) load_idx(c + WK, idxv); // the copies above have consumed the old indices
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        return av;
+    };
+    // all MFMAs of one chunk whose rows sit in the stage at st
+    auto compute = [&](const char *st, v4i a_cur) {
 #pragma unroll
         for (int ct = 0; ct < LPR; ++ct) {
-            const v2i d0 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(stage + (rd_base[0] ^ (ct * 16))));
-            const v2i d1 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(stage + (rd_base[1] ^ (ct * 16))));
+            const v2i d0 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(st + (rd_base[0] ^ (ct * 16))));
+            const v2i d1 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(st + (rd_base[1] ^ (ct * 16))));
             v4i bop = {d0.x, d0.y, d1.x, d1.y};
             if (R16) bop ^= (v4i){lowflip, lowflip, lowflip, lowflip};
             const v4i bx = {bxor, bxor, bxor, bxor};
@@ -196,8 +203,73 @@ __global__ __launch_bounds__(64 * WK) void spmm_kernel(SpmmArgs a)
             const v4i ones = {0x01010101, 0x01010101, 0x01010101, 0x01010101};
             acc[XACC] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a_cur, ones, acc[XACC], 0, 0, 0); // every column: sum over the chunk of A's row
         }
-        // the reads of the staged rows are complete before the next chunk overwrites them
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    };
+    if (NS == 1) {
+        v4i idxv[NI / 4];
+        if (nmy > 0) load_idx(w, idxv);
+        for (int k = 0; k < nmy; ++k) {
+            const int c = w + k * WK;
+#pragma unroll
+            for (int i = 0; i < NI; ++i)
+                __builtin_amdgcn_global_load_lds((gptr_t *)(Bb + (int64_t)idxv[i >> 2][i & 3] * a.ldb_bytes + segoff[i]),
+                                                 (lptr_t *)(stage + i * 1024), 16, 0, 0);
+            const v4i a_cur = load_a_op(c);
+            if (k + 1 < nmy) load_idx(c + WK, idxv); // the copies above have consumed the old indices
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            compute(stage, a_cur);
+            // the reads of the staged rows are complete before the next chunk overwrites them
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        }
+    } else {
+        // Two chunks in flight (waves with at most MAXL chunks; the launcher guarantees it).
+        // Every load that returns data in registers -- the column indices and A operands of ALL
+        // the wave's chunks -- is issued up front and completed before the first copy: the
+        // compiler schedules its own waits for such loads by counting the loads it knows of, and
+        // such a wait in the middle of the loop would also wait for the copies it does not know
+        // of.  The empty assembly statements below make the loaded registers "used" at this
+        // point, so that the compiler's waits land here, where nothing else is in flight.  The
+        // loop then contains copies (assembly, no register destination) and LDS reads only, and
+        // vector-memory operations complete in issue order: "at most NI outstanding" right after
+        // the NI copies of chunk k+1 means that chunk k has arrived.
+        constexpr int MAXL = SPMM_PIPE_CHUNKS;
+        const unsigned stage_u = mcu::lds_addr_uniform(stage);
+        const unsigned ldb32 = (unsigned)a.ldb_bytes;
+        v4i ix[MAXL][NI / 4], av[MAXL];
+        mcu::static_for<MAXL>([&](auto Lc) {
+            constexpr int l = decltype(Lc)::value;
+#pragma unroll
+            for (int t = 0; t < NI / 4; ++t) ix[l][t] = (v4i){0, 0, 0, 0};
+            av[l] = (v4i){0, 0, 0, 0};
+            if (l < nmy) {
+                load_idx(w + l * WK, ix[l]);
+                av[l] = load_a_op(w + l * WK);
+            }
+        });
+        mcu::static_for<MAXL>([&](auto Lc) {
+            constexpr int l = decltype(Lc)::value;
+#pragma unroll
+            for (int t = 0; t < NI / 4; ++t) pin(ix[l][t]);
+            pin(av[l]);
+        });
+        auto issue = [&](int st, const v4i (&ixs)[NI / 4]) {
+#pragma unroll
+            for (int i = 0; i < NI; ++i)
+                mcu::copy16_to_lds(Bb, (unsigned)ixs[i >> 2][i & 3] * ldb32 + (unsigned)segoff[i], stage_u + st * Cfg::STAGE + i * 1024);
+        };
+        if (nmy > 0) issue(0, ix[0]);
+        mcu::static_for<MAXL>([&](auto Lc) {
+            constexpr int l = decltype(Lc)::value;
+            if (l < nmy) {
+                if (l + 1 < MAXL && l + 1 < nmy) {
+                    issue((l + 1) & 1, ix[(l + 1 < MAXL) ? l + 1 : l]);
+                    mcu::vm_wait<NI>();
+                } else {
+                    mcu::vm_wait<0>();
+                }
+                compute(stage + (l & 1) * Cfg::STAGE, av[l]);
+                mcu::lgkm_wait(); // the reads of this stage have returned before it is refilled
+            }
+        });
     }
 
     // ---- partial tiles -> LDS (each wave into its own region), row-major int32 ----------
@@ -286,25 +358,38 @@ __global__ __launch_bounds__(64 * WK) void spmm_kernel(SpmmArgs a)
     }
 }
 
-template <int BNB, int WK, int LB, int RB, bool U> hipError_t launch_one(const SpmmArgs &a, hipStream_t s)
+template <int BNB, int WK, int LB, int RB, bool U, int NS> hipError_t launch_one(const SpmmArgs &a, hipStream_t s)
 {
     const int ntiles = (a.row_bytes + BNB - 1) / BNB;
     dim3 grid((unsigned)((a.items ? a.n_units : a.P) * ntiles), (unsigned)a.batch), block(64 * WK);
-    hipLaunchKernelGGL((spmm_kernel<BNB, WK, LB, RB, U>), grid, block, 0, s, a);
+    hipLaunchKernelGGL((spmm_kernel<BNB, WK, LB, RB, U, NS>), grid, block, 0, s, a);
     return hipGetLastError();
+}
+
+template <int BNB, int LB, int RB, bool U, int NS> hipError_t launch_ns(const SpmmArgs &a, int waves, hipStream_t s)
+{
+    // the per-wave LDS regions of a workgroup must fit 64 KB
+    constexpr int MAXW = (SpmmCfg<BNB, 8, LB, RB, U, NS>::LDS <= 65536) ? 8 : ((SpmmCfg<BNB, 4, LB, RB, U, NS>::LDS <= 65536) ? 4 : ((SpmmCfg<BNB, 2, LB, RB, U, NS>::LDS <= 65536) ? 2 : 1));
+    if (waves > MAXW) waves = MAXW;
+    switch (waves) {
+    case 1: return launch_one<BNB, 1, LB, RB, U, NS>(a, s);
+    case 2: return launch_one<BNB, 2, LB, RB, U, NS>(a, s);
+    case 4: return launch_one<BNB, (MAXW < 4 ? MAXW : 4), LB, RB, U, NS>(a, s);
+    default: return launch_one<BNB, MAXW, LB, RB, U, NS>(a, s);
+    }
 }
 
 template <int BNB, int LB, int RB, bool U = false> hipError_t launch_wk(const SpmmArgs &a, int waves, hipStream_t s)
 {
-    // the per-wave LDS regions of a workgroup must fit 64 KB
-    constexpr int MAXW = (SpmmCfg<BNB, 8, LB, RB, U>::LDS <= 65536) ? 8 : ((SpmmCfg<BNB, 4, LB, RB, U>::LDS <= 65536) ? 4 : 2);
-    if (waves > MAXW) waves = MAXW;
-    switch (waves) {
-    case 1: return launch_one<BNB, 1, LB, RB, U>(a, s);
-    case 2: return launch_one<BNB, 2, LB, RB, U>(a, s);
-    case 4: return launch_one<BNB, (MAXW < 4 ? MAXW : 4), LB, RB, U>(a, s);
-    default: return launch_one<BNB, MAXW, LB, RB, U>(a, s);
+    // two chunks in flight per wave whenever the lane offsets into B fit 32 bits (unsigned
+    // operands keep to the one-chunk form to bound the number of kernels)
+    // ... and no wave has more than SPMM_PIPE_CHUNKS chunks
+    if constexpr (!U) if (a.stages == 2) {
+        constexpr int MAXW2 = (SpmmCfg<BNB, 8, LB, RB, U, 2>::LDS <= 65536) ? 8 : ((SpmmCfg<BNB, 4, LB, RB, U, 2>::LDS <= 65536) ? 4 : ((SpmmCfg<BNB, 2, LB, RB, U, 2>::LDS <= 65536) ? 2 : 1));
+        const int wv = waves > MAXW2 ? MAXW2 : (waves == 4 && MAXW2 < 4 ? MAXW2 : waves);
+        if ((a.max_unit_chunks + wv - 1) / wv <= SPMM_PIPE_CHUNKS) return launch_ns<BNB, LB, RB, U, 2>(a, waves, s);
     }
+    return launch_ns<BNB, LB, RB, U, 1>(a, waves, s);
 }
 
 // unsigned operands: tiles of 64 or 128 bytes

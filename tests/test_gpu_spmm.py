@@ -236,3 +236,19 @@ def test_config2_whole_grid_full_size(prec):
                 want = run_spmm_oracle(dict(base, N=N, B=Bh))
                 assert np.array_equal(got, want), (prec, V, s, N)
             A.close()
+
+
+@pytest.mark.parametrize("prec", PRECS + ["L16R16", "L16R4"])
+def test_one_and_two_chunks_in_flight_agree(prec):
+    """The kernel form with two chunks of gathered rows in flight per wave (default where it applies) and the
+    one-chunk form, on panels short enough for the former and on longer ones."""
+    from paper_2209_06979_amd import binding as mc
+    for s, N in ((0.9, 256), (0.97, 128), (0.6, 256)):
+        case = wl.spmm_case(256, 2048, N, 8, s, prec, 195)
+        for stages in (1, 2):
+            mc.set_spmm_stages(stages)
+            try:
+                for variant in [(0, 0), (64, 1), (128, 2), (256, 8)]:
+                    _check(case, variant)
+            finally:
+                mc.set_spmm_stages(2)
