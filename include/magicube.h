@@ -274,7 +274,8 @@ int mc_sparse_attention_batched(const void *Q_dev, const void *Km_dev, const voi
  * ---------------------------------------------------------------------------------- */
 int mc_set_spmm_variant(int bytes_per_row_tile, int waves);
 /* Chunks of gathered rows in flight per wave of the SpMM kernel: 2 (default; used when B spans
- * less than 4 GiB) or 1.  Same results.  MC_EINVAL for other values.  Process-wide. */
+ * less than 4 GiB and no wave has more than 4 chunks) or 1.  Same results.  MC_EINVAL for other
+ * values.  Process-wide. */
 int mc_set_spmm_stages(int stages);
 /* Matrices whose longest panel is far above the average (more than four times the larger of the
  * average and 4 chunks) get, at mc_mat_create, a list of work items that cuts long panels into
