@@ -288,6 +288,17 @@ def sparse_softmax(S, row_ptr, V: int, scale: float) -> np.ndarray:
     return out
 
 
+def dequantize(acc, scale, out_bits: int = 32) -> np.ndarray:
+    """Fused dequantisation of an integer result (Section 5.3): the exact integer times the real
+    scale (an fp32 number), computed in fp64 and rounded ONCE, to nearest even, to the output
+    type: fp32 (out_bits 32) or fp16 (out_bits 16; magnitudes of 65520 and above become inf)."""
+    if out_bits not in (16, 32):
+        raise ValueError("out_bits must be 16 or 32")
+    x = np.asarray(acc).astype(np.float64) * np.float64(np.float32(scale))
+    with np.errstate(over="ignore"):
+        return x.astype(np.float32 if out_bits == 32 else np.float16)
+
+
 # Largest code of the re-quantised softmax output.  8 bits: the int8 maximum.  16 bits: the
 # largest value whose split into two SIGNED bytes (hi = (c + 128) >> 8) still fits, which is
 # what a signed x signed matrix unit can take as a two-plane operand.
@@ -300,7 +311,8 @@ def requantize_probabilities(p, s_p: float, bits: int = 8) -> np.ndarray:
     return q.astype(np.int8 if bits == 8 else np.int16)
 
 
-def attention(Q8, K8, V8, row_ptr, col_idx, V: int, s_q, s_k, s_v, s_p, p_bits: int = 8, qkv_bits: int = 8):
+def attention(Q8, K8, V8, row_ptr, col_idx, V: int, s_q, s_k, s_v, s_p, p_bits: int = 8, qkv_bits: int = 8,
+              out_bits: int = 64):
     """Quantized self-attention with a vector-sparse mask shared by all heads.
 
     Q8, K8, V8: (heads, L, dk) int8, or for qkv_bits=4 (heads, L, dk/2) bytes with two
@@ -308,8 +320,9 @@ def attention(Q8, K8, V8, row_ptr, col_idx, V: int, s_q, s_k, s_v, s_p, p_bits: 
     s_q*s_k/sqrt(dk) -> softmax over the stored entries -> re-quantisation to p_bits-bit
     codes with the static scale s_p -> integer SpMM with V -> scale s_p*s_v.  The paper's
     "xb-yb" variants (Section 5.3 / end-to-end latency figure) are p_bits=x, qkv_bits=y.
-    Returns (O fp64 (heads, L, dk), scores int32, probabilities fp64, integer codes),
-    the last three as (heads, nvec*V) in SDDMM output order.
+    Returns (O (heads, L, dk), scores int32, probabilities fp64, integer codes), the last
+    three as (heads, nvec*V) in SDDMM output order.  O is fp64, or with out_bits 32 / 16 the
+    fp64 value rounded once to fp32 / fp16 (the paper's output type).
     """
     if qkv_bits == 4:
         Q8, K8, V8 = (unpack_int4(np.asarray(t).view(np.uint8)) for t in (Q8, K8, V8))
@@ -331,4 +344,7 @@ def attention(Q8, K8, V8, row_ptr, col_idx, V: int, s_q, s_k, s_v, s_p, p_bits: 
         A, _ = bcrs_to_dense(L, L, V, row_ptr, col_idx, codes[h].reshape(nvec, V))
         C = spmm_dense(A, flags, np.asarray(V8[h]).astype(np.int32), V)
         O[h] = C.astype(np.float64) * (np.float64(np.float32(s_p)) * np.float64(np.float32(s_v)))
+    if out_bits != 64:
+        with np.errstate(over="ignore"):
+            O = O.astype({32: np.float32, 16: np.float16}[out_bits])
     return O, scores, probs, codes

@@ -448,6 +448,74 @@ def test_attention_against_dense_torch_reference():
         assert np.max(np.abs(O[h] - ref.numpy())) < 0.15
 
 
+def _half_bits_by_hand(x) -> int:
+    """IEEE binary16 bit pattern of a finite double or exact Fraction, rounded to nearest even,
+    by integer arithmetic on exact fractions (no library conversion)."""
+    from fractions import Fraction
+    import math
+    x = Fraction(x)
+    sign = 0x8000 if x < 0 else 0
+    f = abs(x)
+    if f >= Fraction(65520):                                 # half-way between 65504 and 2^16 rounds to inf
+        return sign | 0x7c00
+    if f == 0:
+        return sign
+    e = max(math.floor(math.log2(f)) if f >= Fraction(1, 1 << 14) else -14, -14)
+    while f >= Fraction(2) ** (e + 1):                       # guard against log2 rounding
+        e += 1
+    while e > -14 and f < Fraction(2) ** e:
+        e -= 1
+    ulp = Fraction(2) ** (e - 10)
+    n, r = divmod(f, ulp)
+    n = int(n)
+    if r > ulp / 2 or (r == ulp / 2 and n % 2 == 1):
+        n += 1
+    # n counts ulps: normal numbers have n in [1024, 2048]; 2048 carries into the next exponent
+    if e == -14 and n < 1024:
+        return sign | n                                      # subnormal (or zero)
+    if n == 2048:
+        n, e = 1024, e + 1
+    return sign | ((e + 15) << 10) | (n - 1024)
+
+
+def test_dequantize_rounds_once_to_nearest_even():
+    """fp16 and fp32 outputs of the fused dequantisation: bit patterns against a by-hand
+    rounding of the exact product, and against struct's 'e' / 'f' packers."""
+    import struct
+    from fractions import Fraction
+    rng = np.random.default_rng(77)
+    acc = np.concatenate([rng.integers(-2**31, 2**31, 400), rng.integers(-70000, 70000, 400),
+                          [0, 1, -1, 2049, 2051, -2049, 4098, 65519, 65520, -65520, 2**31 - 1, -2**31]]).astype(np.int64)
+    for scale in (1.0, np.float32(0.001), np.float32(1 / 127 / 127), np.float32(2.0 ** -24), np.float32(3e-8)):
+        h = oracle.dequantize(acc, scale, 16)
+        f = oracle.dequantize(acc, scale, 32)
+        assert h.dtype == np.float16 and f.dtype == np.float32
+        for a_, hb, fb in zip(acc.tolist(), h.view(np.uint16).tolist(), f.view(np.uint32).tolist()):
+            exact = Fraction(a_) * Fraction(float(np.float32(scale)))   # no rounding at all
+            assert hb == _half_bits_by_hand(exact), (a_, scale)
+            if abs(exact) < 65520:
+                assert hb == struct.unpack("<H", struct.pack("<e", float(exact)))[0]
+            assert fb == struct.unpack("<I", struct.pack("<f", float(exact)))[0]
+    # ties: 2049 is half-way between 2048 and 2050 -> even mantissa (2048); 2051 -> 2052
+    assert oracle.dequantize(np.array([2049, 2051, 4098]), 1.0, 16).tolist() == [2048.0, 2052.0, 4096.0]
+    assert np.isinf(oracle.dequantize(np.array([65520]), 1.0, 16)[0]) and oracle.dequantize(np.array([65519]), 1.0, 16)[0] == 65504
+
+
+def test_attention_output_types_are_single_roundings():
+    heads, L, dk, V = 2, 64, 16, 8
+    c = wl.attention_case(heads, L, dk, V, 0.75, 902)
+    (q, s_q), (k, s_k), (v, s_v) = (wl.quantize_inputs_int8(c[n]) for n in "qkv")
+    args = (q, k, v, c["row_ptr"], c["col_idx"], V, s_q, s_k, s_v, np.float32(1 / 127))
+    O64 = oracle.attention(*args)[0]
+    O16 = oracle.attention(*args, out_bits=16)[0]
+    O32 = oracle.attention(*args, out_bits=32)[0]
+    assert O64.dtype == np.float64 and O16.dtype == np.float16 and O32.dtype == np.float32
+    hb = [_half_bits_by_hand(x) for x in O64.reshape(-1).tolist()]
+    assert O16.reshape(-1).view(np.uint16).tolist() == hb
+    assert np.array_equal(O32, O64.astype(np.float32))
+    assert np.abs(O16.astype(np.float64) - O64).max() <= 2.0 ** -11 * np.abs(O64).max()
+
+
 def test_requantize_16_bit_codes():
     q = oracle.requantize_probabilities(np.array([0.0, 1.0, 2.0, 100.4 / 32639, 100.6 / 32639]), 1 / 32639, 16)
     assert q.dtype == np.int16 and q.tolist() == [0, 32639, 32639, 100, 101]
