@@ -60,6 +60,9 @@ typedef enum {
     MC_L16R16 = 4, MC_L16R4 = 5, MC_L12R4 = 6
 } mc_prec;
 
+/* Type of a dequantised (real-valued) output: IEEE binary32 or binary16. */
+typedef enum { MC_OUT_F32 = 0, MC_OUT_F16 = 1 } mc_out_type;
+
 /* Vectors per chunk of the device format (= reduction depth of v_mfma_i32_16x16x64_i8). */
 #define MC_CHUNK 64
 
@@ -155,6 +158,15 @@ int mc_spmm(const mc_mat *A, const void *B_dev, int N, int ldb, mc_prec prec, in
 int mc_spmm_flags(const mc_mat *A, const void *B_dev, int N, int ldb, mc_prec prec, unsigned flags, int32_t *C_dev,
                   int ldc, void *stream);
 
+/* SpMM with fused dequantisation (Section 5.3: the integer product is turned into real values
+ * in the kernel's epilogue): C = scale * (A * B), each element computed as float(int32 result) *
+ * scale in fp32 and, for MC_OUT_F16, rounded to nearest even (magnitudes beyond the fp16 range
+ * become infinity).  C_dev: M x N row-major float or half, 16-byte aligned, ldc a multiple of 4.
+ * scale must be finite.  Other arguments and limits as mc_spmm_flags.  Panels of very unequal
+ * length are not shared between workgroups here (a rounded result cannot be added up piecewise). */
+int mc_spmm_dequant(const mc_mat *A, const void *B_dev, int N, int ldb, mc_prec prec, unsigned flags, float scale,
+                    mc_out_type out_type, void *C_dev, int ldc, void *stream);
+
 /* Measurement aid (Section 4.2.1 names the gather of B rows by column index as the step the
  * kernel is built around): performs ONLY the gather of mc_spmm(A, B_dev, N, ldb, prec, ...) --
  * same tile variant, index loads and row copies into on-chip memory, no arithmetic, no C.
@@ -184,6 +196,11 @@ int mc_sddmm(const void *Q_dev, int ldq, const void *Kmat_dev, int ldk, int Kd, 
  * mc_spmm_flags).  Supported for MC_L8R8 and MC_L4R4 (the latter with Kd <= 32768). */
 int mc_sddmm_flags(const void *Q_dev, int ldq, const void *Kmat_dev, int ldk, int Kd, const mc_mat *mask,
                    mc_prec prec, unsigned flags, int32_t *S_dev, void *stream);
+
+/* SDDMM with fused dequantisation (Section 5.3): S_dev receives scale * score as nvec*V floats
+ * or halves (rounded as in mc_spmm_dequant) in the same order.  Other arguments as mc_sddmm_flags. */
+int mc_sddmm_dequant(const void *Q_dev, int ldq, const void *Kmat_dev, int ldk, int Kd, const mc_mat *mask,
+                     mc_prec prec, unsigned flags, float scale, mc_out_type out_type, void *S_dev, void *stream);
 
 /* ------------------------------------------------------------------------------------
  * Sparse softmax with fused (de)quantisation (Section 5.3): for each row (p, v) over its
@@ -265,6 +282,15 @@ int mc_sparse_attention_batched(const void *Q_dev, const void *Km_dev, const voi
                                 int dk, int64_t batch_stride, int64_t head_stride, int64_t token_stride,
                                 const mc_mat *mask, int p_bits, int qkv_bits, float s_q, float s_k, float s_v,
                                 float s_p, float *O_dev, void *workspace_dev, size_t workspace_bytes, void *stream);
+
+/* The batched layer with a typed output (Section 5.3 dequantises the layer's result to fp16):
+ * O_dev holds floats (MC_OUT_F32: identical to mc_sparse_attention_batched) or halves
+ * (MC_OUT_F16: the same fp32 results rounded to nearest even); strides stay in elements. */
+int mc_sparse_attention_out(const void *Q_dev, const void *Km_dev, const void *Vm_dev, int batch, int heads, int L,
+                            int dk, int64_t batch_stride, int64_t head_stride, int64_t token_stride,
+                            const mc_mat *mask, int p_bits, int qkv_bits, float s_q, float s_k, float s_v, float s_p,
+                            mc_out_type out_type, void *O_dev, void *workspace_dev, size_t workspace_bytes,
+                            void *stream);
 
 /* ------------------------------------------------------------------------------------
  * Tuning knob (not needed for correctness): selects the SpMM tile variant.

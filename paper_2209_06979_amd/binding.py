@@ -79,6 +79,13 @@ def _load() -> ctypes.CDLL:
     L.mc_sparse_attention_batched.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int64, c_int64,
                                               c_int64, c_void_p, c_int, c_int, c_float, c_float, c_float, c_float,
                                               c_void_p, c_void_p, c_size_t, c_void_p]
+    L.mc_sparse_attention_out.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int64, c_int64,
+                                          c_int64, c_void_p, c_int, c_int, c_float, c_float, c_float, c_float, c_int,
+                                          c_void_p, c_void_p, c_size_t, c_void_p]
+    L.mc_spmm_dequant.argtypes = [c_void_p, c_void_p, c_int, c_int, c_int, ctypes.c_uint, c_float, c_int, c_void_p, c_int,
+                                  c_void_p]
+    L.mc_sddmm_dequant.argtypes = [c_void_p, c_int, c_void_p, c_int, c_int, c_void_p, c_int, ctypes.c_uint, c_float, c_int,
+                                   c_void_p, c_void_p]
     L.mc_absmax.argtypes = [c_void_p, c_int64, c_void_p, c_void_p]
     L.mc_quantize.argtypes = [c_void_p, c_int64, c_float, c_int, c_void_p, c_void_p]
     L.mc_set_spmm_variant.argtypes = [c_int, c_int]
@@ -89,7 +96,7 @@ def _load() -> ctypes.CDLL:
     for name in ("mc_layout_query", "mc_pack_host", "mc_unpack_host", "mc_mat_create", "mc_mat_set_values_device",
                  "mc_mat_info", "mc_spmm", "mc_spmm_flags", "mc_sddmm", "mc_sddmm_flags", "mc_sparse_softmax", "mc_sparse_softmax_bits", "mc_sparse_attention",
                  "mc_sparse_attention_strided", "mc_sparse_attention_bits", "mc_sparse_attention_batched", "mc_probe_gather",
-                 "mc_absmax", "mc_quantize",
+                 "mc_absmax", "mc_quantize", "mc_sparse_attention_out", "mc_spmm_dequant", "mc_sddmm_dequant",
                  "mc_set_spmm_variant", "mc_set_attention_mode", "mc_set_sddmm_variant", "mc_set_spmm_splitting", "mc_set_spmm_stages"):
         getattr(L, name).restype = c_int
     return L
@@ -231,6 +238,25 @@ def spmm(A: SparseMatrix, B, prec: str, out=None, lhs_unsigned: bool = False, rh
     return out
 
 
+OUT_TYPE = {torch.float32: 0, torch.float16: 1}
+
+
+def spmm_dequant(A: SparseMatrix, B, prec: str, scale: float, out_dtype=torch.float32, out=None,
+                 lhs_unsigned: bool = False, rhs_unsigned: bool = False):
+    """C = scale * (A * B) as fp32 or fp16 (M x N): SpMM with the dequantisation fused into the kernel."""
+    assert B.is_cuda and B.dim() == 2 and B.stride(1) == 1
+    rbits = RHS_BITS[prec]
+    N = B.shape[1] * B.element_size() * 8 // rbits
+    ldb = B.stride(0) * B.element_size() * 8 // rbits
+    if out is None:
+        out = torch.empty((A.M, N), dtype=out_dtype, device=B.device)
+    assert out.is_cuda and out.dtype == out_dtype and out.shape == (A.M, N) and out.stride(1) == 1
+    flags = (1 if lhs_unsigned else 0) | (2 if rhs_unsigned else 0)
+    _check(lib.mc_spmm_dequant(A.handle, B.data_ptr(), N, ldb, PREC[prec], flags, float(scale), OUT_TYPE[out_dtype],
+                               out.data_ptr(), out.stride(0), _stream()), "mc_spmm_dequant")
+    return out
+
+
 def probe_gather(A: SparseMatrix, B, prec: str, sink=None):
     """Only the gather of spmm(A, B, prec) (a measurement aid); returns the per-workgroup sink."""
     assert B.is_cuda and B.dim() == 2 and B.stride(1) == 1
@@ -257,6 +283,24 @@ def sddmm(Q, Kmat, mask: SparseMatrix, prec: str, out=None, lhs_unsigned: bool =
     _check(lib.mc_sddmm_flags(Q.data_ptr(), Q.stride(0) * Q.element_size() * 8 // bits, Kmat.data_ptr(),
                               Kmat.stride(0) * Kmat.element_size() * 8 // bits, Kd,
                               mask.handle, PREC[prec], flags, out.data_ptr(), _stream()), "mc_sddmm_flags")
+    return out
+
+
+def sddmm_dequant(Q, Kmat, mask: SparseMatrix, prec: str, scale: float, out_dtype=torch.float32, out=None,
+                  lhs_unsigned: bool = False, rhs_unsigned: bool = False):
+    """scale * (Q * Kmat^T) at the mask's stored vectors as nvec*V fp32 or fp16 values (interchange order)."""
+    assert Q.is_cuda and Kmat.is_cuda and Q.dim() == 2 and Kmat.dim() == 2
+    assert Q.stride(1) == 1 and Kmat.stride(1) == 1 and Q.shape[1] == Kmat.shape[1]
+    bits = LHS_BITS[prec]
+    Kd = Q.shape[1] * Q.element_size() * 8 // bits
+    assert Q.element_size() == Kmat.element_size()
+    if out is None:
+        out = torch.empty(mask.nvec * mask.V, dtype=out_dtype, device=Q.device)
+    assert out.is_cuda and out.dtype == out_dtype and out.numel() == mask.nvec * mask.V and out.is_contiguous()
+    flags = (1 if lhs_unsigned else 0) | (2 if rhs_unsigned else 0)
+    _check(lib.mc_sddmm_dequant(Q.data_ptr(), Q.stride(0) * Q.element_size() * 8 // bits, Kmat.data_ptr(),
+                                Kmat.stride(0) * Kmat.element_size() * 8 // bits, Kd, mask.handle, PREC[prec], flags,
+                                float(scale), OUT_TYPE[out_dtype], out.data_ptr(), _stream()), "mc_sddmm_dequant")
     return out
 
 
@@ -304,10 +348,11 @@ def attention_workspace_bytes(heads: int, mask: SparseMatrix, p_bits: int = 8) -
 
 
 def sparse_attention(Q8, K8, V8, mask: SparseMatrix, s_q, s_k, s_v, s_p, out=None, workspace=None,
-                     p_bits: int = 8, qkv_bits: int = 8):
+                     p_bits: int = 8, qkv_bits: int = 8, out_dtype=torch.float32):
     """Quantized sparse self-attention; Q8/K8/V8: (heads, L, dk) or (batch, heads, L, dk) int8
     device tensors, or for qkv_bits=4 uint8 tensors of half the last dimension with two 4-bit
-    values per byte.  p_bits is the width of the re-quantised softmax output (8 or 16).
+    values per byte.  p_bits is the width of the re-quantised softmax output (8 or 16);
+    out_dtype is torch.float32 or torch.float16.
 
     Any layout with unit stride along dk is accepted as long as the three tensors (and
     ``out``) share it; a (heads, L, dk) view of a token-major (L, heads, dk) buffer, i.e.
@@ -324,15 +369,15 @@ def sparse_attention(Q8, K8, V8, mask: SparseMatrix, s_q, s_k, s_v, s_p, out=Non
         assert t.is_cuda and t.element_size() == 1 and t.shape == Q8.shape and t.stride() == Q8.stride() and t.stride(-1) == 1
     oshape = tuple(Q8.shape[:-1]) + (dk,)
     if out is None:
-        out = torch.empty_strided(oshape, st + (1,), dtype=torch.float32, device=Q8.device)   # the inputs' layout
-    assert out.is_cuda and out.dtype == torch.float32 and out.shape == oshape and out.stride() == st + (1,)
+        out = torch.empty_strided(oshape, st + (1,), dtype=out_dtype, device=Q8.device)   # the inputs' layout
+    assert out.is_cuda and out.dtype == out_dtype and out.shape == oshape and out.stride() == st + (1,)
     need = attention_workspace_bytes(heads, mask, p_bits)
     if workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=Q8.device)
     assert workspace.is_cuda and workspace.is_contiguous()
-    _check(lib.mc_sparse_attention_batched(Q8.data_ptr(), K8.data_ptr(), V8.data_ptr(), batch, heads, L, dk, bs, hs, ts,
-                                           mask.handle, p_bits, qkv_bits, float(s_q), float(s_k), float(s_v), float(s_p),
-                                           out.data_ptr(), workspace.data_ptr(),
-                                           workspace.numel() * workspace.element_size(), _stream()),
-           "mc_sparse_attention_batched")
+    _check(lib.mc_sparse_attention_out(Q8.data_ptr(), K8.data_ptr(), V8.data_ptr(), batch, heads, L, dk, bs, hs, ts,
+                                       mask.handle, p_bits, qkv_bits, float(s_q), float(s_k), float(s_v), float(s_p),
+                                       OUT_TYPE[out_dtype], out.data_ptr(), workspace.data_ptr(),
+                                       workspace.numel() * workspace.element_size(), _stream()),
+           "mc_sparse_attention_out")
     return out

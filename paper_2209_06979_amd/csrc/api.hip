@@ -297,8 +297,10 @@ extern "C" int mc_spmm(const mc_mat *A, const void *B_dev, int N, int ldb, mc_pr
     return mc_spmm_flags(A, B_dev, N, ldb, prec, 0u, C_dev, ldc, stream);
 }
 
-extern "C" int mc_spmm_flags(const mc_mat *A, const void *B_dev, int N, int ldb, mc_prec prec, unsigned flags,
-                             int32_t *C_dev, int ldc, void *stream)
+namespace {
+// out_mode 0: int32 results; 1 / 2: scale * result as fp32 / fp16 (fused dequantisation)
+int spmm_impl(const mc_mat *A, const void *B_dev, int N, int ldb, mc_prec prec, unsigned flags, int out_mode,
+              float scale, void *C_dev, int ldc, void *stream)
 {
     if (!A || !B_dev || !C_dev) return MC_EINVAL;
     if (!valid_prec((int)prec)) return MC_EUNSUPPORTED;
@@ -311,6 +313,7 @@ extern "C" int mc_spmm_flags(const mc_mat *A, const void *B_dev, int N, int ldb,
     if (((int64_t)ldb * rb / 8) % 16 != 0 || ldc % 4 != 0) return MC_EALIGN;
     if (!aligned16(B_dev) || !aligned16(C_dev)) return MC_EALIGN;
     if (rb == 4 && A->K > ((flags != 0) ? 32768 : 131072)) return MC_EUNSUPPORTED;
+    if (out_mode && !std::isfinite(scale)) return MC_EINVAL;
 
     SpmmArgs a = {};
     a.lhs_unsigned = (flags & MC_LHS_UNSIGNED) ? 1 : 0; a.rhs_unsigned = (flags & MC_RHS_UNSIGNED) ? 1 : 0;
@@ -319,19 +322,35 @@ extern "C" int mc_spmm_flags(const mc_mat *A, const void *B_dev, int N, int ldb,
     a.B = static_cast<const uint8_t *>(B_dev); a.ldb_bytes = (int64_t)ldb * rb / 8; a.B_batch_stride = 0;
     a.row_bytes = N * rb / 8;
     a.C = C_dev; a.ldc = ldc; a.C_batch_stride = 0;
-    a.P = A->P; a.V = A->V; a.batch = 1; a.float_out = 0; a.out_scale = 1.f;
+    a.P = A->P; a.V = A->V; a.batch = 1; a.float_out = out_mode; a.out_scale = out_mode ? scale : 1.f;
     int bnb, waves;
     choose_variant(A, a.row_bytes, rb == 4, 1, &bnb, &waves);
     a.stages = (g_spmm_stages == 2 && (int64_t)(A->K - 1) * a.ldb_bytes + a.row_bytes < ((int64_t)1 << 32)) ? 2 : 1;
     a.max_unit_chunks = A->max_panel_chunks;
-    if (A->n_items && g_spmm_items) {
+    if (A->n_items && g_spmm_items && out_mode == 0) {
         a.max_unit_chunks = A->max_item_chunks;
         // very unequal panels: long ones are shared by several workgroups that add into cleared rows
+        // (integer results only: a scaled, rounded result cannot be accumulated piecewise)
         a.items = A->d_items; a.n_units = A->n_items;
-        MC_HIP(launch_zero_rows(C_dev, ldc, N, A->V, A->d_split_panels, A->n_split, static_cast<hipStream_t>(stream)));
+        MC_HIP(launch_zero_rows(static_cast<int32_t *>(C_dev), ldc, N, A->V, A->d_split_panels, A->n_split,
+                                static_cast<hipStream_t>(stream)));
     }
     MC_HIP(launch_spmm(prec, a, bnb, waves, static_cast<hipStream_t>(stream)));
     return MC_OK;
+}
+} // namespace
+
+extern "C" int mc_spmm_flags(const mc_mat *A, const void *B_dev, int N, int ldb, mc_prec prec, unsigned flags,
+                             int32_t *C_dev, int ldc, void *stream)
+{
+    return spmm_impl(A, B_dev, N, ldb, prec, flags, 0, 1.f, C_dev, ldc, stream);
+}
+
+extern "C" int mc_spmm_dequant(const mc_mat *A, const void *B_dev, int N, int ldb, mc_prec prec, unsigned flags,
+                               float scale, mc_out_type out_type, void *C_dev, int ldc, void *stream)
+{
+    if (out_type != MC_OUT_F32 && out_type != MC_OUT_F16) return MC_EUNSUPPORTED;
+    return spmm_impl(A, B_dev, N, ldb, prec, flags, out_type == MC_OUT_F16 ? 2 : 1, scale, C_dev, ldc, stream);
 }
 
 extern "C" int64_t mc_probe_gather_sink_len(const mc_mat *A, int N, mc_prec prec)
@@ -368,8 +387,9 @@ extern "C" int mc_sddmm(const void *Q_dev, int ldq, const void *Kmat_dev, int ld
     return mc_sddmm_flags(Q_dev, ldq, Kmat_dev, ldk, Kd, mask, prec, 0u, S_dev, stream);
 }
 
-extern "C" int mc_sddmm_flags(const void *Q_dev, int ldq, const void *Kmat_dev, int ldk, int Kd, const mc_mat *mask,
-                              mc_prec prec, unsigned flags, int32_t *S_dev, void *stream)
+namespace {
+int sddmm_impl(const void *Q_dev, int ldq, const void *Kmat_dev, int ldk, int Kd, const mc_mat *mask, mc_prec prec,
+               unsigned flags, int out_mode, float scale, void *S_dev, void *stream)
 {
     if (!Q_dev || !Kmat_dev || !mask || !S_dev) return MC_EINVAL;
     if (!valid_prec((int)prec)) return MC_EUNSUPPORTED;
@@ -381,8 +401,10 @@ extern "C" int mc_sddmm_flags(const void *Q_dev, int ldq, const void *Kmat_dev, 
     if (Kd <= 0 || Kd % (128 / bits) != 0 || ldq < Kd || ldk < Kd) return MC_EINVAL;
     if (((int64_t)ldq * bits / 8) % 16 != 0 || ((int64_t)ldk * bits / 8) % 16 != 0) return MC_EALIGN;
     if (!aligned16(Q_dev) || !aligned16(Kmat_dev) || !aligned16(S_dev)) return MC_EALIGN;
+    if (out_mode && !std::isfinite(scale)) return MC_EINVAL;
 
     SddmmArgs a = {};
+    a.float_out = out_mode; a.out_scale = out_mode ? scale : 1.f;
     a.panel_ptr = mask->d_panel_ptr; a.row_ptr = mask->d_row_ptr; a.slot_idx = mask->d_slot_idx;
     a.Q = static_cast<const uint8_t *>(Q_dev); a.ldq_bytes = (int64_t)ldq * bits / 8; a.Q_batch_stride = 0;
     a.Kmat = static_cast<const uint8_t *>(Kmat_dev); a.ldk_bytes = (int64_t)ldk * bits / 8; a.K_batch_stride = 0;
@@ -393,6 +415,22 @@ extern "C" int mc_sddmm_flags(const void *Q_dev, int ldq, const void *Kmat_dev, 
     if (mask->n_items && g_spmm_items) { a.items = mask->d_items; a.n_units = mask->n_items; } // very unequal panels
     MC_HIP(launch_sddmm(bits, a, choose_sddmm_waves(mask, 1), static_cast<hipStream_t>(stream)));
     return MC_OK;
+}
+} // namespace
+
+extern "C" int mc_sddmm_flags(const void *Q_dev, int ldq, const void *Kmat_dev, int ldk, int Kd, const mc_mat *mask,
+                              mc_prec prec, unsigned flags, int32_t *S_dev, void *stream)
+{
+    return sddmm_impl(Q_dev, ldq, Kmat_dev, ldk, Kd, mask, prec, flags, 0, 1.f, S_dev, stream);
+}
+
+extern "C" int mc_sddmm_dequant(const void *Q_dev, int ldq, const void *Kmat_dev, int ldk, int Kd, const mc_mat *mask,
+                                mc_prec prec, unsigned flags, float scale, mc_out_type out_type, void *S_dev,
+                                void *stream)
+{
+    if (out_type != MC_OUT_F32 && out_type != MC_OUT_F16) return MC_EUNSUPPORTED;
+    return sddmm_impl(Q_dev, ldq, Kmat_dev, ldk, Kd, mask, prec, flags, out_type == MC_OUT_F16 ? 2 : 1, scale, S_dev,
+                      stream);
 }
 
 extern "C" int mc_absmax(const float *x_dev, int64_t n, float *result_dev, void *stream)
@@ -453,7 +491,7 @@ AttnWs attn_layout(int heads, const mc_mat *mask, int p_bits)
 int attention_pipeline(const uint8_t *Q, const uint8_t *Km, const uint8_t *Vm, int heads, int dk, int qkv_bits,
                        int p_bits, int64_t head_stride_bytes, int64_t token_stride_bytes, int64_t o_head_stride,
                        int64_t o_token_stride, const mc_mat *mask, float s_q, float s_k, float s_v, float s_p,
-                       float *O, void *workspace_dev, hipStream_t s)
+                       void *O, int out_f16, void *workspace_dev, hipStream_t s)
 {
     const AttnWs ws = attn_layout(heads, mask, p_bits);
     const int64_t nnz = mask->nvec * mask->V;
@@ -489,7 +527,7 @@ int attention_pipeline(const uint8_t *Q, const uint8_t *Km, const uint8_t *Vm, i
     m.vals = pvals; m.vals_batch_stride = mask->nslots * 8 * pb;
     m.B = Vm; m.ldb_bytes = token_stride_bytes; m.B_batch_stride = head_stride_bytes;
     m.row_bytes = row_bytes; m.C = O; m.ldc = o_token_stride; m.C_batch_stride = o_head_stride;
-    m.P = mask->P; m.V = 8; m.batch = heads; m.float_out = 1; m.out_scale = s_p * s_v;
+    m.P = mask->P; m.V = 8; m.batch = heads; m.float_out = out_f16 ? 2 : 1; m.out_scale = s_p * s_v;
     m.stages = (g_spmm_stages == 2 && (int64_t)(mask->K - 1) * m.ldb_bytes + m.row_bytes < ((int64_t)1 << 32)) ? 2 : 1;
     m.max_unit_chunks = mask->max_panel_chunks;
     int bnb, waves;
@@ -544,6 +582,19 @@ extern "C" int mc_sparse_attention_batched(const void *Q_dev, const void *Km_dev
                                            float s_q, float s_k, float s_v, float s_p, float *O_dev,
                                            void *workspace_dev, size_t workspace_bytes, void *stream)
 {
+    return mc_sparse_attention_out(Q_dev, Km_dev, Vm_dev, batch, heads, L, dk, batch_stride, head_stride, token_stride,
+                                   mask, p_bits, qkv_bits, s_q, s_k, s_v, s_p, MC_OUT_F32, O_dev, workspace_dev,
+                                   workspace_bytes, stream);
+}
+
+extern "C" int mc_sparse_attention_out(const void *Q_dev, const void *Km_dev, const void *Vm_dev, int batch, int heads,
+                                       int L, int dk, int64_t batch_stride, int64_t head_stride, int64_t token_stride,
+                                       const mc_mat *mask, int p_bits, int qkv_bits, float s_q, float s_k, float s_v,
+                                       float s_p, mc_out_type out_type, void *O_dev, void *workspace_dev,
+                                       size_t workspace_bytes, void *stream)
+{
+    if (out_type != MC_OUT_F32 && out_type != MC_OUT_F16) return MC_EUNSUPPORTED;
+    const int out_f16 = (out_type == MC_OUT_F16) ? 1 : 0;
     if (!Q_dev || !Km_dev || !Vm_dev || !mask || !O_dev || !workspace_dev) return MC_EINVAL;
     if ((p_bits != 8 && p_bits != 16) || (qkv_bits != 8 && qkv_bits != 4)) return MC_EUNSUPPORTED;
     const int epp = 128 / qkv_bits; // elements per 16-byte piece
@@ -564,7 +615,7 @@ extern "C" int mc_sparse_attention_batched(const void *Q_dev, const void *Km_dev
         AttnArgs f;
         f.panel_ptr = mask->d_panel_ptr; f.slot_idx = mask->d_slot_idx;
         f.Q = static_cast<const uint8_t *>(Q_dev); f.Km = static_cast<const uint8_t *>(Km_dev);
-        f.Vm = static_cast<const uint8_t *>(Vm_dev); f.O = O_dev;
+        f.Vm = static_cast<const uint8_t *>(Vm_dev); f.O = static_cast<float *>(O_dev); f.out_f16 = out_f16;
         f.head_stride = head_stride; f.token_stride = token_stride; f.batch_stride = batch_stride;
         f.in_head_stride = head_stride * qkv_bits / 8; f.in_token_stride = token_stride * qkv_bits / 8;
         f.in_batch_stride = batch_stride * qkv_bits / 8;
@@ -585,8 +636,9 @@ extern "C" int mc_sparse_attention_batched(const void *Q_dev, const void *Km_dev
         const int rc = attention_pipeline(static_cast<const uint8_t *>(Q_dev) + ib, static_cast<const uint8_t *>(Km_dev) + ib,
                                           static_cast<const uint8_t *>(Vm_dev) + ib, heads, dk, qkv_bits, p_bits,
                                           head_stride * qkv_bits / 8, token_stride * qkv_bits / 8, head_stride,
-                                          token_stride, mask, s_q, s_k, s_v, s_p, O_dev + (int64_t)b * batch_stride,
-                                          workspace_dev, s);
+                                          token_stride, mask, s_q, s_k, s_v, s_p,
+                                          static_cast<uint8_t *>(O_dev) + (int64_t)b * batch_stride * (out_f16 ? 2 : 4),
+                                          out_f16, workspace_dev, s);
         if (rc != MC_OK) return rc;
     }
     return MC_OK;

@@ -410,7 +410,9 @@ void attention_fused_kernel(AttnArgs a)
         }
         if (PB == 16) sres = (sres << 8) + slo;
         const v4f f = {sres.x * a.out_scale, sres.y * a.out_scale, sres.z * a.out_scale, sres.w * a.out_scale};
-        *reinterpret_cast<v4f *>(Oh + (int64_t)row * a.token_stride + col) = f;
+        const int64_t off = (Oh - a.O) + (int64_t)row * a.token_stride + col;
+        if (a.out_f16) *reinterpret_cast<v4h *>(reinterpret_cast<_Float16 *>(a.O) + off) = to_half4(f);
+        else *reinterpret_cast<v4f *>(a.O + off) = f;
     }
 }
 

@@ -34,11 +34,11 @@ struct SpmmArgs {
     int64_t ldb_bytes;
     int64_t B_batch_stride;    // bytes
     int row_bytes;             // bytes of one B row that take part (N * bits / 8)
-    void *C;                   // int32 or float
+    void *C;                   // int32, float or half (see float_out)
     int64_t ldc;               // elements
     int64_t C_batch_stride;    // elements
     int P, V, batch;
-    int float_out;             // 1: write float(acc) * out_scale
+    int float_out;             // 0: int32; 1: float(acc) * out_scale as fp32; 2: the same rounded to fp16
     float out_scale;
     int lhs_unsigned, rhs_unsigned; // 4- and 8-bit operands read as non-negative values
     // optional work items (see mc_mat): null = one unit of work per panel.  Items of a split panel
@@ -58,8 +58,10 @@ struct SddmmArgs {
     const uint8_t *Kmat;
     int64_t ldk_bytes, K_batch_stride;
     int row_bytes;             // Kd * bits / 8
-    int32_t *S;
+    void *S;                   // int32, float or half (see float_out)
     int64_t S_batch_stride;    // elements
+    int float_out;             // 0: int32; 1: float(score) * out_scale as fp32; 2: the same rounded to fp16
+    float out_scale;
     int P, V, batch;
     int lhs_unsigned, rhs_unsigned; // 4- and 8-bit operands read as non-negative values
     const int32_t *items;      // optional work items (see mc_mat): null = one workgroup per panel
@@ -91,12 +93,13 @@ struct AttnArgs {
     const int32_t *panel_ptr;
     const int32_t *slot_idx;
     const uint8_t *Q, *Km, *Vm;
-    float *O;
+    float *O;                                // fp32, or half when out_f16 is set
     int64_t head_stride, token_stride;       // elements of O
     int64_t in_head_stride, in_token_stride; // bytes of Q, Km, Vm
     int64_t batch_stride, in_batch_stride;   // between batch items: elements of O, bytes of Q, Km, Vm
     float score_scale, inv_s_p, out_scale;
     int P, heads, batch;
+    int out_f16;                             // 1: O holds fp16 (the fp32 result rounded to nearest even)
 };
 
 hipError_t launch_spmm(mc_prec prec, const SpmmArgs &a, int bnb, int waves, hipStream_t s);

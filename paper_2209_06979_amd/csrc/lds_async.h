@@ -25,6 +25,11 @@ namespace mcu {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v2i __attribute__((ext_vector_type(2)));
 typedef float v4f __attribute__((ext_vector_type(4)));
+typedef _Float16 v4h __attribute__((ext_vector_type(4)));
+typedef _Float16 v2h __attribute__((ext_vector_type(2)));
+
+// four fp32 values rounded to fp16 (to nearest even; beyond the fp16 range: infinity)
+__device__ __forceinline__ v4h to_half4(v4f f) { return (v4h){(_Float16)f.x, (_Float16)f.y, (_Float16)f.z, (_Float16)f.w}; }
 typedef __attribute__((address_space(3))) v2i lds_v2i;
 
 // 32-bit LDS address of a pointer into a __shared__ array

@@ -16,13 +16,17 @@
 //   sddmm_direct_kernel any row length: each lane loads its 16 operand bytes from memory.
 // int4 operands are widened in registers; int16 operands (L16-R16, Section 4.4) are split in
 // registers into signed byte planes, the two Q planes stacked in the MFMA rows 0..7 / 8..15.
-// The output is written in interchange (BCRS) order: V consecutive int32 per vector.
+// The output is written in interchange (BCRS) order: V consecutive int32 per vector, or with the
+// fused dequantisation of Section 5.3 V consecutive fp32 / fp16 values.
 #include "internal.h"
 
 namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v2i __attribute__((ext_vector_type(2)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef _Float16 v4h __attribute__((ext_vector_type(4)));
+typedef _Float16 v2h __attribute__((ext_vector_type(2)));
 typedef __attribute__((address_space(1))) const void gptr_t;
 typedef __attribute__((address_space(3))) void lptr_t;
 
@@ -93,13 +97,32 @@ template <int PB> __device__ __forceinline__ v4i finish_tile(v4i acc, v4i acc2)
     return acc;
 }
 
+// four fp32 values rounded to fp16 (to nearest even; beyond the fp16 range: infinity)
+__device__ __forceinline__ v4h to_half4(v4f f) { return (v4h){(_Float16)f.x, (_Float16)f.y, (_Float16)f.z, (_Float16)f.w}; }
+
 __device__ __forceinline__ void store_scores(const SddmmArgs &a, int64_t out0, int slot, int n, int g, v4i acc)
 {
     // accumulator register r of lane (j, g) is row 4g + r of vector `slot`
     if (slot < n && 4 * g < a.V) {
-        int32_t *o = a.S + out0 + (int64_t)slot * a.V + 4 * g;
-        if (a.V >= 4) *reinterpret_cast<v4i *>(o) = acc;
-        else *reinterpret_cast<v2i *>(o) = (v2i){acc.x, acc.y};
+        const int64_t off = out0 + (int64_t)slot * a.V + 4 * g;
+        if (a.float_out == 0) {
+            int32_t *o = static_cast<int32_t *>(a.S) + off;
+            if (a.V >= 4) *reinterpret_cast<v4i *>(o) = acc;
+            else *reinterpret_cast<v2i *>(o) = (v2i){acc.x, acc.y};
+        } else {
+            // fused dequantisation (Section 5.3)
+            const v4f f = {acc.x * a.out_scale, acc.y * a.out_scale, acc.z * a.out_scale, acc.w * a.out_scale};
+            if (a.float_out == 1) {
+                float *o = static_cast<float *>(a.S) + off;
+                if (a.V >= 4) *reinterpret_cast<v4f *>(o) = f;
+                else { o[0] = f.x; o[1] = f.y; }
+            } else {
+                _Float16 *o = static_cast<_Float16 *>(a.S) + off;
+                const v4h h = to_half4(f);
+                if (a.V >= 4) *reinterpret_cast<v4h *>(o) = h;
+                else *reinterpret_cast<v2h *>(o) = (v2h){h.x, h.y};
+            }
+        }
     }
 }
 
