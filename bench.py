@@ -415,7 +415,28 @@ def measure_extras(mc, torch, prob, stream, reps, up):
                                                                     p_bits=p_bits, qkv_bits=qkv_bits)] * max(1, reps // 4))
         ops = HEADS * 2 * (2 * amask.nvec * V * DK)
         wide[name] = dict(us=round(us, 2), eff_tops=round(ops / us / 1e6, 1))
+    # the paper's output type: fp16 written by the fused dequantisation (the step's rows write int32 / fp32)
+    tmaj = lambda x: up(np.ascontiguousarray(np.transpose(x, (1, 0, 2)))).permute(1, 0, 2)
+    q, k, v = tmaj(att["q8"]), tmaj(att["k8"]), tmaj(att["v8"])
+    O16 = torch.empty((L_ATT, HEADS, DK), dtype=torch.float16, device="cuda").permute(1, 0, 2)
+    ws = torch.empty(mc.attention_workspace_bytes(HEADS, amask), dtype=torch.uint8, device="cuda")
+    us = time_graph(torch, stream, [lambda: mc.sparse_attention(q, k, v, amask, att["s_q"], att["s_k"], att["s_v"], att["s_p"],
+                                                                out=O16, workspace=ws, out_dtype=torch.float16)] * max(1, reps // 4))
+    wide["attention_8b8b_fp16_out"] = dict(us=round(us, 2), eff_tops=round(HEADS * 2 * (2 * amask.nvec * V * DK) / us / 1e6, 1))
     amask.close()
+    cc = prob["spmm_L8R8"]
+    A = mc.SparseMatrix(M, K, V, cc["row_ptr"], cc["col_idx"], cc["values"], 8)
+    B, C16 = up(cc["B"]), torch.empty((M, N_SPMM), dtype=torch.float16, device="cuda")
+    us = time_graph(torch, stream, [lambda: mc.spmm_dequant(A, B, "L8R8", 1e-4, torch.float16, out=C16)] * reps)
+    wide["spmm_L8R8_fp16_out"] = dict(us=round(us, 2), eff_tops=round(2 * A.nvec * V * N_SPMM / us / 1e6, 1))
+    A.close()
+    cc = prob["sddmm_L8R8"]
+    mask = mc.SparseMatrix(M, K, V, cc["row_ptr"], cc["col_idx"])
+    Q, Km = up(cc["Q"]), up(cc["Kmat"])
+    S16 = torch.empty(mask.nvec * V, dtype=torch.float16, device="cuda")
+    us = time_graph(torch, stream, [lambda: mc.sddmm_dequant(Q, Km, mask, "L8R8", 1e-4, torch.float16, out=S16)] * reps)
+    wide["sddmm_L8R8_fp16_out"] = dict(us=round(us, 2), eff_tops=round(2 * mask.nvec * V * KD_SDDMM / us / 1e6, 1))
+    mask.close()
     out["wider_precisions"] = wide
 
     # The layer at the shapes of the paper's end-to-end latency figure (Section 5.3: 4 / 8 heads, sequence

@@ -100,17 +100,19 @@ template <int PB> __device__ __forceinline__ v4i finish_tile(v4i acc, v4i acc2)
 // four fp32 values rounded to fp16 (to nearest even; beyond the fp16 range: infinity)
 __device__ __forceinline__ v4h to_half4(v4f f) { return (v4h){(_Float16)f.x, (_Float16)f.y, (_Float16)f.z, (_Float16)f.w}; }
 
+// DQ: fused dequantisation (Section 5.3).  A compile-time switch: the integer path keeps its
+// straight-line stores, which the scheduler interleaves with the next tile's MFMAs.
+template <bool DQ>
 __device__ __forceinline__ void store_scores(const SddmmArgs &a, int64_t out0, int slot, int n, int g, v4i acc)
 {
     // accumulator register r of lane (j, g) is row 4g + r of vector `slot`
     if (slot < n && 4 * g < a.V) {
         const int64_t off = out0 + (int64_t)slot * a.V + 4 * g;
-        if (a.float_out == 0) {
+        if (!DQ) {
             int32_t *o = static_cast<int32_t *>(a.S) + off;
             if (a.V >= 4) *reinterpret_cast<v4i *>(o) = acc;
             else *reinterpret_cast<v2i *>(o) = (v2i){acc.x, acc.y};
         } else {
-            // fused dequantisation (Section 5.3)
             const v4f f = {acc.x * a.out_scale, acc.y * a.out_scale, acc.z * a.out_scale, acc.w * a.out_scale};
             if (a.float_out == 1) {
                 float *o = static_cast<float *>(a.S) + off;
@@ -154,7 +156,7 @@ __device__ __forceinline__ v4i load_q(const uint8_t *Qpanel, int64_t ldq_bytes, 
 }
 
 // RB: bytes of a Kmat row (64, 128, 256, 512; 16-bit operands: from 128).  WK: waves per workgroup.
-template <int PB, int RB, int WK>
+template <int PB, int RB, int WK, bool DQ>
 __global__ __launch_bounds__(64 * WK) void sddmm_lds_kernel(SddmmArgs a)
 {
     constexpr int LPR = RB / 16, NI = LPR, RPI = 64 / LPR, KC = RB / StepBytes<PB>::value;
@@ -219,14 +221,14 @@ __global__ __launch_bounds__(64 * WK) void sddmm_lds_kernel(SddmmArgs a)
                     mma_step<PB>(qf[kc], kf, kf, acc, acc2);
                 }
             }
-            store_scores(a, out0, (cb + c) * MC_CHUNK + s, n, g, finish_tile<PB>(acc, acc2));
+            store_scores<DQ>(a, out0, (cb + c) * MC_CHUNK + s, n, g, finish_tile<PB>(acc, acc2));
         }
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); // reads done before the rows are overwritten
     }
 }
 
 // KC = number of MFMA steps along a row kept in registers (0: any length, Q re-read).
-template <int PB, int KC>
+template <int PB, int KC, bool DQ>
 __global__ __launch_bounds__(64 * SDDMM_WAVES) void sddmm_direct_kernel(SddmmArgs a)
 {
     constexpr int STEP = StepBytes<PB>::value, LANEB = STEP / 4; // bytes per step / per lane and step
@@ -286,7 +288,7 @@ __global__ __launch_bounds__(64 * SDDMM_WAVES) void sddmm_direct_kernel(SddmmArg
                 mma_step<PB>(q, k, k2, acc, acc2);
             }
         }
-        store_scores(a, out0, slot, n, g, finish_tile<PB>(acc, acc2));
+        store_scores<DQ>(a, out0, slot, n, g, finish_tile<PB>(acc, acc2));
     }
 }
 
@@ -297,7 +299,7 @@ __global__ __launch_bounds__(64 * SDDMM_WAVES) void sddmm_direct_kernel(SddmmArg
 // per gathered Kmat row from MFMA row 8, which is free (V <= 8) and is fed an all-ones row operand.
 // Reduction bytes beyond the row end are zero on both sides before the XOR, so they take part in
 // every term consistently and n counts them.
-template <int PB>
+template <int PB, bool DQ>
 __global__ __launch_bounds__(64 * SDDMM_WAVES) void sddmm_unsigned_kernel(SddmmArgs a)
 {
     static_assert(PB == 8 || PB == 4, "unsigned operands: 4 and 8 bits");
@@ -363,7 +365,7 @@ __global__ __launch_bounds__(64 * SDDMM_WAVES) void sddmm_unsigned_kernel(SddmmA
         if (a.lhs_unsigned) acc += (v4i){cs << 7, cs << 7, cs << 7, cs << 7};
         if (PB == 4) acc = acc >> 8;
         acc += (v4i){cqck, cqck, cqck, cqck};
-        store_scores(a, out0, slot, n, g, acc);
+        store_scores<DQ>(a, out0, slot, n, g, acc);
     }
 }
 
@@ -458,50 +460,55 @@ __global__ __launch_bounds__(256) void repack_kernel(RepackArgs a)
 
 } // namespace
 
-template <int PB, int RB> hipError_t launch_sddmm_lds(const SddmmArgs &a, int waves, hipStream_t s)
+template <int PB, int RB, bool DQ> hipError_t launch_sddmm_lds(const SddmmArgs &a, int waves, hipStream_t s)
 {
     dim3 grid((unsigned)(a.items ? a.n_units : a.P), (unsigned)a.batch);
     constexpr int MAXW = (64 * RB * 8 <= 65536) ? 8 : ((64 * RB * 4 <= 65536) ? 4 : 2); // 64 KB of stages per workgroup
     if (waves > MAXW) waves = MAXW;
     switch (waves) {
-    case 1: hipLaunchKernelGGL((sddmm_lds_kernel<PB, RB, 1>), grid, dim3(64), 0, s, a); break;
-    case 2: hipLaunchKernelGGL((sddmm_lds_kernel<PB, RB, 2>), grid, dim3(128), 0, s, a); break;
-    case 4: hipLaunchKernelGGL((sddmm_lds_kernel<PB, RB, (MAXW < 4 ? MAXW : 4)>), grid, dim3(64 * (MAXW < 4 ? MAXW : 4)), 0, s, a); break;
-    default: hipLaunchKernelGGL((sddmm_lds_kernel<PB, RB, MAXW>), grid, dim3(64 * MAXW), 0, s, a); break;
+    case 1: hipLaunchKernelGGL((sddmm_lds_kernel<PB, RB, 1, DQ>), grid, dim3(64), 0, s, a); break;
+    case 2: hipLaunchKernelGGL((sddmm_lds_kernel<PB, RB, 2, DQ>), grid, dim3(128), 0, s, a); break;
+    case 4: hipLaunchKernelGGL((sddmm_lds_kernel<PB, RB, (MAXW < 4 ? MAXW : 4), DQ>), grid, dim3(64 * (MAXW < 4 ? MAXW : 4)), 0, s, a); break;
+    default: hipLaunchKernelGGL((sddmm_lds_kernel<PB, RB, MAXW, DQ>), grid, dim3(64 * MAXW), 0, s, a); break;
     }
     return hipGetLastError();
 }
 
-template <int PB> hipError_t launch_sddmm_bits(const SddmmArgs &a, int waves, hipStream_t s)
+template <int PB, bool DQ> hipError_t launch_sddmm_bits(const SddmmArgs &a, int waves, hipStream_t s)
 {
     if (waves > 0) {
-        if (a.row_bytes == 64 && PB != 16) return launch_sddmm_lds<(PB == 16 ? 8 : PB), 64>(a, waves, s);
-        if (a.row_bytes == 128) return launch_sddmm_lds<PB, 128>(a, waves, s);
-        if (a.row_bytes == 256) return launch_sddmm_lds<PB, 256>(a, waves, s);
-        if (a.row_bytes == 512) return launch_sddmm_lds<PB, 512>(a, waves, s);
+        if (a.row_bytes == 64 && PB != 16) return launch_sddmm_lds<(PB == 16 ? 8 : PB), 64, DQ>(a, waves, s);
+        if (a.row_bytes == 128) return launch_sddmm_lds<PB, 128, DQ>(a, waves, s);
+        if (a.row_bytes == 256) return launch_sddmm_lds<PB, 256, DQ>(a, waves, s);
+        if (a.row_bytes == 512) return launch_sddmm_lds<PB, 512, DQ>(a, waves, s);
     }
     dim3 grid((unsigned)(a.items ? a.n_units : a.P), (unsigned)a.batch), block(64 * SDDMM_WAVES);
     const int kc = (a.row_bytes + StepBytes<PB>::value - 1) / StepBytes<PB>::value;
-    if (kc == 1) hipLaunchKernelGGL((sddmm_direct_kernel<PB, 1>), grid, block, 0, s, a);
-    else if (kc == 2) hipLaunchKernelGGL((sddmm_direct_kernel<PB, 2>), grid, block, 0, s, a);
-    else if (kc <= 4) hipLaunchKernelGGL((sddmm_direct_kernel<PB, 4>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((sddmm_direct_kernel<PB, 0>), grid, block, 0, s, a);
+    if (kc == 1) hipLaunchKernelGGL((sddmm_direct_kernel<PB, 1, DQ>), grid, block, 0, s, a);
+    else if (kc == 2) hipLaunchKernelGGL((sddmm_direct_kernel<PB, 2, DQ>), grid, block, 0, s, a);
+    else if (kc <= 4) hipLaunchKernelGGL((sddmm_direct_kernel<PB, 4, DQ>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((sddmm_direct_kernel<PB, 0, DQ>), grid, block, 0, s, a);
     return hipGetLastError();
+}
+
+template <bool DQ> hipError_t launch_sddmm_out(int bits, const SddmmArgs &a, int waves, hipStream_t s)
+{
+    if (a.lhs_unsigned || a.rhs_unsigned) {
+        dim3 grid((unsigned)(a.items ? a.n_units : a.P), (unsigned)a.batch), block(64 * SDDMM_WAVES);
+        if (bits == 8) hipLaunchKernelGGL((sddmm_unsigned_kernel<8, DQ>), grid, block, 0, s, a);
+        else if (bits == 4) hipLaunchKernelGGL((sddmm_unsigned_kernel<4, DQ>), grid, block, 0, s, a);
+        else return hipErrorInvalidValue;
+        return hipGetLastError();
+    }
+    if (bits == 4) return launch_sddmm_bits<4, DQ>(a, waves, s);
+    if (bits == 16) return launch_sddmm_bits<16, DQ>(a, waves, s);
+    return launch_sddmm_bits<8, DQ>(a, waves, s);
 }
 
 hipError_t launch_sddmm(int bits, const SddmmArgs &a, int waves, hipStream_t s)
 {
     if (a.P == 0 || a.batch == 0) return hipSuccess;
-    if (a.lhs_unsigned || a.rhs_unsigned) {
-        dim3 grid((unsigned)(a.items ? a.n_units : a.P), (unsigned)a.batch), block(64 * SDDMM_WAVES);
-        if (bits == 8) hipLaunchKernelGGL((sddmm_unsigned_kernel<8>), grid, block, 0, s, a);
-        else if (bits == 4) hipLaunchKernelGGL((sddmm_unsigned_kernel<4>), grid, block, 0, s, a);
-        else return hipErrorInvalidValue;
-        return hipGetLastError();
-    }
-    if (bits == 4) return launch_sddmm_bits<4>(a, waves, s);
-    if (bits == 16) return launch_sddmm_bits<16>(a, waves, s);
-    return launch_sddmm_bits<8>(a, waves, s);
+    return a.float_out ? launch_sddmm_out<true>(bits, a, waves, s) : launch_sddmm_out<false>(bits, a, waves, s);
 }
 
 hipError_t launch_softmax(const SoftmaxArgs &a, hipStream_t s)
