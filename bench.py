@@ -423,6 +423,13 @@ def measure_extras(mc, torch, prob, stream, reps, up):
     us = time_graph(torch, stream, [lambda: mc.sparse_attention(q, k, v, amask, att["s_q"], att["s_k"], att["s_v"], att["s_p"],
                                                                 out=O16, workspace=ws, out_dtype=torch.float16)] * max(1, reps // 4))
     wide["attention_8b8b_fp16_out"] = dict(us=round(us, 2), eff_tops=round(HEADS * 2 * (2 * amask.nvec * V * DK) / us / 1e6, 1))
+    # the general path (any head dimension, any panel length): SDDMM, softmax and SpMM as three kernels
+    mc.set_attention_mode(1)
+    O32 = torch.empty((L_ATT, HEADS, DK), dtype=torch.float32, device="cuda").permute(1, 0, 2)
+    us = time_graph(torch, stream, [lambda: mc.sparse_attention(q, k, v, amask, att["s_q"], att["s_k"], att["s_v"], att["s_p"],
+                                                                out=O32, workspace=ws)] * max(1, reps // 4))
+    mc.set_attention_mode(0)
+    wide["attention_8b8b_three_kernels"] = dict(us=round(us, 2), eff_tops=round(HEADS * 2 * (2 * amask.nvec * V * DK) / us / 1e6, 1))
     amask.close()
     cc = prob["spmm_L8R8"]
     A = mc.SparseMatrix(M, K, V, cc["row_ptr"], cc["col_idx"], cc["values"], 8)

@@ -229,6 +229,14 @@ int mc_sparse_softmax_bits(const mc_mat *mask, int batch, const int32_t *S_dev, 
 int mc_absmax(const float *x_dev, int64_t n, float *result_dev, void *stream);
 int mc_quantize(const float *x_dev, int64_t n, float scale, int bits, void *q_dev, void *stream);
 
+/* The sparse softmax for ONE score set, written straight into the device-resident values of a
+ * sparse operand (Section 4.3: the producer writes the format its consumer reads), so that
+ * mc_spmm(P, ...) can follow without mc_mat_set_values_device:
+ *   P   a matrix with the mask's pattern that holds 8- or 16-bit values (created with values,
+ *       e.g. zeros; a pattern-only mask: MC_EINVAL; other widths: MC_EUNSUPPORTED).  Its width
+ *       selects the code range as in mc_sparse_softmax_bits; all its values are replaced. */
+int mc_sparse_softmax_to_mat(mc_mat *P, const int32_t *S_dev, float score_scale, float inv_s_p, void *stream);
+
 /* ------------------------------------------------------------------------------------
  * Quantized sparse self-attention layer (Section 5.3), one mask shared by all heads:
  *   O[h] = ( P_q[h] * Vm[h] ) * (s_p * s_v),
@@ -239,7 +247,7 @@ int mc_quantize(const float *x_dev, int64_t n, float scale, int bits, void *q_de
  *   workspace_dev           at least mc_attention_workspace_bytes(heads, mask) bytes,
  *                           256-byte aligned, caller-owned; contents undefined after
  * Requirements: dk a multiple of 16.  Entries excluded by the mask do not take part in
- * the softmax.  Empty rows give zeros.  The workspace is only touched by the four-kernel
+ * the softmax.  Empty rows give zeros.  The workspace is only touched by the kernel
  * pipeline (see mc_set_attention_mode) but must always be supplied.
  * ---------------------------------------------------------------------------------- */
 size_t mc_attention_workspace_bytes(int heads, const mc_mat *mask);
@@ -263,7 +271,7 @@ int mc_sparse_attention(const int8_t *Q_dev, const int8_t *Km_dev, const int8_t 
  * packed two per byte along dk).  Strides are in ELEMENTS for all four tensors and must make
  * whole 16-byte pieces (multiples of 16 for 8-bit, of 32 for 4-bit inputs); dk likewise.
  * p_bits = 8, qkv_bits = 8 is mc_sparse_attention_strided.  Every combination has the fused
- * kernel (dk == 64, panels of at most 512 vectors) and the four-kernel pipeline behind it, as
+ * kernel (dk == 64, panels of at most 512 vectors) and the kernel pipeline behind it, as
  * selected by mc_set_attention_mode; the workspace must hold
  * mc_attention_workspace_bytes_bits(heads, mask, p_bits) bytes.
  * Unsupported widths: MC_EUNSUPPORTED. */
@@ -313,10 +321,14 @@ int mc_set_spmm_splitting(int enable); /* also governs the work items of mc_sddm
  * (any row length), 1, 2, 4 or 8 = waves per panel of the kernel that stages Kmat rows in
  * LDS (used when a row has 64, 128, 256 or 512 bytes, else ignored).  Process-wide. */
 int mc_set_sddmm_variant(int waves);
+/* Softmax variant: 0 = automatic (panels of up to 16384 scores, padding included, are kept in
+ * registers: one pass over the scores), 2 = always the kernel for panels of any length (three
+ * passes).  Same codes up to fp32 summation order.  Process-wide. */
+int mc_set_softmax_variant(int variant);
 /* Attention path: 0 = automatic (a single fused kernel when dk == 64 and no panel holds
  * more than 2048 vectors -- one, two or four waves per (panel, head) for panels of up to 512,
- * 1024, 2048 vectors -- else the four-kernel pipeline), 1 = always the four-kernel
- * pipeline SDDMM -> softmax -> repack -> SpMM, 2 = the fused kernel with one head per
+ * 1024, 2048 vectors -- else the pipeline of separate kernels), 1 = always the
+ * pipeline SDDMM -> softmax -> SpMM of separate kernels, 2 = the fused kernel with one head per
  * workgroup even for token-major tensors, 3 / 4 = the fused kernel with at least two / with
  * four waves per (panel, head) whatever the panel length.  All give the same result up to fp32 summation
  * order in the softmax.  Process-wide; MC_EINVAL for other values. */

@@ -86,6 +86,7 @@ def _load() -> ctypes.CDLL:
                                   c_void_p]
     L.mc_sddmm_dequant.argtypes = [c_void_p, c_int, c_void_p, c_int, c_int, c_void_p, c_int, ctypes.c_uint, c_float, c_int,
                                    c_void_p, c_void_p]
+    L.mc_sparse_softmax_to_mat.argtypes = [c_void_p, c_void_p, c_float, c_float, c_void_p]
     L.mc_absmax.argtypes = [c_void_p, c_int64, c_void_p, c_void_p]
     L.mc_quantize.argtypes = [c_void_p, c_int64, c_float, c_int, c_void_p, c_void_p]
     L.mc_set_spmm_variant.argtypes = [c_int, c_int]
@@ -93,11 +94,13 @@ def _load() -> ctypes.CDLL:
     L.mc_set_spmm_splitting.argtypes = [c_int]
     L.mc_set_spmm_stages.argtypes = [c_int]
     L.mc_set_sddmm_variant.argtypes = [c_int]
+    L.mc_set_softmax_variant.argtypes = [c_int]
     for name in ("mc_layout_query", "mc_pack_host", "mc_unpack_host", "mc_mat_create", "mc_mat_set_values_device",
                  "mc_mat_info", "mc_spmm", "mc_spmm_flags", "mc_sddmm", "mc_sddmm_flags", "mc_sparse_softmax", "mc_sparse_softmax_bits", "mc_sparse_attention",
                  "mc_sparse_attention_strided", "mc_sparse_attention_bits", "mc_sparse_attention_batched", "mc_probe_gather",
-                 "mc_absmax", "mc_quantize", "mc_sparse_attention_out", "mc_spmm_dequant", "mc_sddmm_dequant",
-                 "mc_set_spmm_variant", "mc_set_attention_mode", "mc_set_sddmm_variant", "mc_set_spmm_splitting", "mc_set_spmm_stages"):
+                 "mc_absmax", "mc_quantize", "mc_sparse_attention_out", "mc_spmm_dequant", "mc_sddmm_dequant", "mc_sparse_softmax_to_mat",
+                 "mc_set_spmm_variant", "mc_set_attention_mode", "mc_set_sddmm_variant", "mc_set_spmm_splitting", "mc_set_spmm_stages",
+                 "mc_set_softmax_variant"):
         getattr(L, name).restype = c_int
     return L
 
@@ -216,6 +219,10 @@ def set_spmm_splitting(enable: bool = True) -> None:
 
 def set_sddmm_variant(waves: int = -1) -> None:
     _check(lib.mc_set_sddmm_variant(waves), "mc_set_sddmm_variant")
+
+
+def set_softmax_variant(variant: int = 0) -> None:
+    _check(lib.mc_set_softmax_variant(variant), "mc_set_softmax_variant")
 
 
 def set_attention_mode(mode: int = 0) -> None:
@@ -341,6 +348,13 @@ def sparse_softmax(mask: SparseMatrix, S, score_scale: float, inv_s_p: float, ou
     _check(lib.mc_sparse_softmax_bits(mask.handle, S2.shape[0], S2.data_ptr(), score_scale, inv_s_p, code_bits,
                                       out.data_ptr(), _stream()), "mc_sparse_softmax_bits")
     return out.reshape(S.shape)
+
+
+def sparse_softmax_to_mat(P: SparseMatrix, S, score_scale: float, inv_s_p: float) -> None:
+    """Softmax of one score set (nvec*V int32) written as integer codes straight into P's device values."""
+    assert S.is_cuda and S.dtype == torch.int32 and S.is_contiguous() and S.numel() == P.nvec * P.V
+    _check(lib.mc_sparse_softmax_to_mat(P.handle, S.data_ptr(), float(score_scale), float(inv_s_p), _stream()),
+           "mc_sparse_softmax_to_mat")
 
 
 def attention_workspace_bytes(heads: int, mask: SparseMatrix, p_bits: int = 8) -> int:

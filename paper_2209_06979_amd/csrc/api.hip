@@ -15,6 +15,7 @@ int g_variant_bnb = 0, g_variant_waves = 0;
 int g_sddmm_waves = -1;   // -1 automatic, 0 direct-load kernel, 1/2/4/8 waves of the LDS-staged kernel
 int g_attention_mode = 0; // 0 automatic, 1 always the unfused four-kernel pipeline
 int g_spmm_items = 1;     // 1: matrices with very unequal panels run through their work items
+int g_softmax_variant = 0; // 0: automatic; 2: the any-length softmax kernel always
 int g_spmm_stages = 2;    // chunks in flight per wave of the SpMM kernel (1 or 2)
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -150,6 +151,13 @@ extern "C" int mc_set_sddmm_variant(int waves)
 {
     if (waves != -1 && waves != 0 && waves != 1 && waves != 2 && waves != 4 && waves != 8) return MC_EINVAL;
     g_sddmm_waves = waves;
+    return MC_OK;
+}
+
+extern "C" int mc_set_softmax_variant(int variant)
+{
+    if (variant != 0 && variant != 2) return MC_EINVAL;
+    g_softmax_variant = variant;
     return MC_OK;
 }
 
@@ -457,11 +465,29 @@ extern "C" int mc_sparse_softmax_bits(const mc_mat *mask, int batch, const int32
     if (!mask || !S_dev || !codes_dev || batch <= 0) return MC_EINVAL;
     if (code_bits != 8 && code_bits != 16) return MC_EUNSUPPORTED;
     if (!std::isfinite(score_scale) || !std::isfinite(inv_s_p)) return MC_EINVAL;
-    SoftmaxArgs a;
+    SoftmaxArgs a = {};
     a.row_ptr = mask->d_row_ptr; a.S = S_dev; a.codes = codes_dev;
     a.batch_stride = mask->nvec * mask->V;
     a.score_scale = score_scale; a.inv_s_p = inv_s_p;
     a.P = mask->P; a.V = mask->V; a.batch = batch; a.code_bits = code_bits;
+    a.max_panel_chunks = mask->max_panel_chunks; a.variant = g_softmax_variant;
+    MC_HIP(launch_softmax(a, static_cast<hipStream_t>(stream)));
+    return MC_OK;
+}
+
+extern "C" int mc_sparse_softmax_to_mat(mc_mat *P, const int32_t *S_dev, float score_scale, float inv_s_p, void *stream)
+{
+    if (!P || !S_dev) return MC_EINVAL;
+    if (!P->d_vals) return MC_EINVAL;
+    if (P->lhs_bits != 8 && P->lhs_bits != 16) return MC_EUNSUPPORTED;
+    if (!std::isfinite(score_scale) || !std::isfinite(inv_s_p)) return MC_EINVAL;
+    SoftmaxArgs a = {};
+    a.row_ptr = P->d_row_ptr; a.S = S_dev; a.codes = nullptr;
+    a.panel_ptr = P->d_panel_ptr; a.dev_vals = P->d_vals; a.dev_batch_stride = 0;
+    a.batch_stride = P->nvec * P->V;
+    a.score_scale = score_scale; a.inv_s_p = inv_s_p;
+    a.P = P->P; a.V = P->V; a.batch = 1; a.code_bits = P->lhs_bits;
+    a.max_panel_chunks = P->max_panel_chunks; a.variant = g_softmax_variant;
     MC_HIP(launch_softmax(a, static_cast<hipStream_t>(stream)));
     return MC_OK;
 }
@@ -474,19 +500,18 @@ extern "C" int mc_sparse_softmax(const mc_mat *mask, int batch, const int32_t *S
 
 namespace {
 inline size_t round256(size_t x) { return (x + 255) / 256 * 256; }
-struct AttnWs { size_t scores, codes, vals, total; };
+struct AttnWs { size_t scores, vals, total; };
 AttnWs attn_layout(int heads, const mc_mat *mask, int p_bits)
 {
     AttnWs w;
     const size_t nnz = (size_t)mask->nvec * mask->V, pb = (size_t)p_bits / 8;
     w.scores = 0;
-    w.codes = w.scores + round256((size_t)heads * nnz * sizeof(int32_t));
-    w.vals = w.codes + round256((size_t)heads * nnz * pb);
+    w.vals = w.scores + round256((size_t)heads * nnz * sizeof(int32_t));
     w.total = w.vals + round256((size_t)heads * (size_t)mask->nslots * mask->V * pb);
     return w;
 }
 
-// SDDMM -> softmax -> repack -> SpMM, every step a kernel of its own; intermediates in the
+// SDDMM -> softmax (writing the SpMM's operand format) -> SpMM, every step a kernel of its own; intermediates in the
 // workspace.  Strides of Q/Km/Vm in bytes, of O in elements.
 int attention_pipeline(const uint8_t *Q, const uint8_t *Km, const uint8_t *Vm, int heads, int dk, int qkv_bits,
                        int p_bits, int64_t head_stride_bytes, int64_t token_stride_bytes, int64_t o_head_stride,
@@ -497,7 +522,6 @@ int attention_pipeline(const uint8_t *Q, const uint8_t *Km, const uint8_t *Vm, i
     const int64_t nnz = mask->nvec * mask->V;
     uint8_t *wsb = static_cast<uint8_t *>(workspace_dev);
     int32_t *scores = reinterpret_cast<int32_t *>(wsb + ws.scores);
-    uint8_t *codes = wsb + ws.codes;
     uint8_t *pvals = wsb + ws.vals;
     const int row_bytes = dk * qkv_bits / 8, pb = p_bits / 8;
 
@@ -509,18 +533,15 @@ int attention_pipeline(const uint8_t *Q, const uint8_t *Km, const uint8_t *Vm, i
     d.P = mask->P; d.V = 8; d.batch = heads;
     MC_HIP(launch_sddmm(qkv_bits, d, choose_sddmm_waves(mask, heads), s));
 
-    SoftmaxArgs f;
-    f.row_ptr = mask->d_row_ptr; f.S = scores; f.codes = codes; f.batch_stride = nnz;
+    // the softmax writes its codes in the layout the SpMM reads (Section 4.3 lets the producer
+    // pick the output format by the consumer)
+    SoftmaxArgs f = {};
+    f.row_ptr = mask->d_row_ptr; f.S = scores; f.batch_stride = nnz;
+    f.codes = nullptr; f.panel_ptr = mask->d_panel_ptr; f.dev_vals = pvals; f.dev_batch_stride = mask->nslots * 8 * pb;
     f.score_scale = s_q * s_k / std::sqrt((float)dk); f.inv_s_p = 1.f / s_p;
     f.P = mask->P; f.V = 8; f.batch = heads; f.code_bits = p_bits;
+    f.max_panel_chunks = mask->max_panel_chunks; f.variant = g_softmax_variant;
     MC_HIP(launch_softmax(f, s));
-
-    RepackArgs r;
-    r.panel_ptr = mask->d_panel_ptr; r.row_ptr = mask->d_row_ptr;
-    r.src = codes; r.src_batch_stride = nnz * pb;
-    r.dst = pvals; r.dst_batch_stride = mask->nslots * 8 * pb;
-    r.P = mask->P; r.V = 8; r.bits = p_bits; r.batch = heads;
-    MC_HIP(launch_repack(r, s));
 
     SpmmArgs m = {};
     m.panel_ptr = mask->d_panel_ptr; m.slot_idx = mask->d_slot_idx;

@@ -71,10 +71,16 @@ struct SddmmArgs {
 struct SoftmaxArgs {
     const int32_t *row_ptr;
     const int32_t *S;
-    void *codes;               // int8 (code_bits 8) or int16 (code_bits 16)
+    void *codes;               // int8 (code_bits 8) or int16 (code_bits 16), interchange order; or null:
+    // the codes go straight into the device panel format of a sparse operand (padded slots zeroed)
+    const int32_t *panel_ptr;
+    uint8_t *dev_vals;
+    int64_t dev_batch_stride;  // bytes
     int64_t batch_stride;      // elements (nvec * V)
     float score_scale, inv_s_p;
     int P, V, batch, code_bits;
+    int max_panel_chunks;      // longest panel of the mask, in chunks of 64 vectors
+    int variant;               // 0: automatic; 2: the any-length kernel even for short panels
 };
 
 struct RepackArgs {

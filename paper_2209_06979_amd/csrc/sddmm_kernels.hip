@@ -1,4 +1,4 @@
-// SDDMM, sparse softmax and value-repack kernels for gfx950.
+// SDDMM and value-repack kernels for gfx950 (the sparse softmax lives in softmax_kernels.hip).
 //
 // SDDMM (paper, Section 4.3): a workgroup owns one row panel of the mask.  The panel's
 // V rows of Q are the row operand of v_mfma_i32_16x16x64_i8 and stay in registers for
@@ -369,45 +369,6 @@ __global__ __launch_bounds__(64 * SDDMM_WAVES) void sddmm_unsigned_kernel(SddmmA
     }
 }
 
-// ---- sparse softmax + int8 re-quantisation (Section 5.3) ---------------------------
-// One workgroup per (panel, batch).  Thread t owns elements t, t+256, ... of the panel's
-// contiguous score block; 256 % V == 0, so a thread always stays in row v = t % V.
-__global__ __launch_bounds__(256) void softmax_kernel(SoftmaxArgs a)
-{
-    __shared__ float red[256];
-    const int tid = threadIdx.x, panel = blockIdx.x, batch = blockIdx.y;
-    const int V = a.V, v = tid % V;
-    const int64_t base = (int64_t)batch * a.batch_stride + (int64_t)a.row_ptr[panel] * V;
-    const int cnt = (a.row_ptr[panel + 1] - a.row_ptr[panel]) * V;
-    const int32_t *S = a.S + base;
-
-    // softmax in base 2: exp(x - max) = 2^(x*log2(e) - max2), one v_exp_f32 per element
-    const float scale2 = a.score_scale * 1.4426950408889634f;
-    float m = -INFINITY;
-    for (int e = tid; e < cnt; e += 256) m = fmaxf(m, (float)S[e] * scale2);
-    red[tid] = m;
-    __syncthreads();
-    m = -INFINITY;
-    for (int t = v; t < 256; t += V) m = fmaxf(m, red[t]);
-    __syncthreads();
-
-    float sum = 0.f;
-    for (int e = tid; e < cnt; e += 256) sum += __builtin_amdgcn_exp2f((float)S[e] * scale2 - m);
-    red[tid] = sum;
-    __syncthreads();
-    sum = 0.f;
-    for (int t = v; t < 256; t += V) sum += red[t];
-
-    const float rinv = a.inv_s_p / sum; // p / s_p = e * (1 / (sum * s_p)): one division per row
-    // largest code: int8 maximum, or the largest 16-bit value that splits into two signed bytes
-    const float qmax = (a.code_bits == 16) ? 32639.f : 127.f;
-    for (int e = tid; e < cnt; e += 256) {
-        const float q = fminf(fmaxf(rintf(__builtin_amdgcn_exp2f((float)S[e] * scale2 - m) * rinv), 0.f), qmax);
-        if (a.code_bits == 16) static_cast<int16_t *>(a.codes)[base + e] = (int16_t)(int)q;
-        else static_cast<int8_t *>(a.codes)[base + e] = (int8_t)(int)q;
-    }
-}
-
 // ---- interchange-order values -> device panel format -------------------------------
 // One workgroup per (panel, batch); a thread handles one padded slot (8/16 bit) or the
 // slot pair (b, b+8) that shares bytes (4 bit).
@@ -509,14 +470,6 @@ hipError_t launch_sddmm(int bits, const SddmmArgs &a, int waves, hipStream_t s)
 {
     if (a.P == 0 || a.batch == 0) return hipSuccess;
     return a.float_out ? launch_sddmm_out<true>(bits, a, waves, s) : launch_sddmm_out<false>(bits, a, waves, s);
-}
-
-hipError_t launch_softmax(const SoftmaxArgs &a, hipStream_t s)
-{
-    if (a.P == 0 || a.batch == 0) return hipSuccess;
-    dim3 grid((unsigned)a.P, (unsigned)a.batch), block(256);
-    hipLaunchKernelGGL(softmax_kernel, grid, block, 0, s, a);
-    return hipGetLastError();
 }
 
 hipError_t launch_repack(const RepackArgs &a, hipStream_t s)

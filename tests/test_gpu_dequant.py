@@ -211,3 +211,47 @@ def test_attention_fp16_output_batched_and_config5():
     _attention_f16(4, 512, 64, 0.8, 6620, batch=3, token_major=True)
     _attention_f16(4, 512, 64, 0.8, 6621, batch=2, mode=1)
     _attention_f16(8, 4096, 64, 0.9, wl.seed_for(5, 2), token_major=True)
+
+
+# ------------------------------------------- softmax writing the SpMM operand format ----
+@pytest.mark.parametrize("variant", [0, 2])                    # scores kept in registers / the any-length kernel
+@pytest.mark.parametrize("V", [2, 4, 8])
+@pytest.mark.parametrize("bits", [8, 16])
+def test_softmax_codes_written_in_the_device_format(V, bits, variant):
+    """mc_sparse_softmax_to_mat puts the codes where the SpMM kernels read them: the product of
+    that matrix with the identity is the dense matrix of the oracle's codes (same tie protocol
+    as the interchange-order softmax: exact away from rounding boundaries, one step at them)."""
+    import torch
+    import oracle
+    from paper_2209_06979_amd import binding as mc
+    from test_gpu_sddmm import _tie_ambiguous
+    L = 256
+    P_ = L // V
+    counts = np.full(P_, 37)
+    counts[:8] = [0, 1, 2, 63, 64, 65, 128, 256]                 # empty, short, around chunk ends, full row
+    rp, ci = wl.ragged_pattern(L, L, V, counts, 6700 + V)
+    nvec = len(ci)
+    print(f"softmax_to_mat V={V} bits={bits} nvec={nvec}", flush=True)
+    S = np.random.default_rng(6701).integers(-30000, 30000, size=nvec * V).astype(np.int32)
+    scale, pmax = np.float32(3e-4), oracle.P_CODE_MAX[bits]
+    stale = np.full((nvec, V), 77, np.int8 if bits == 8 else np.int16)   # must be overwritten everywhere
+    Pm = mc.SparseMatrix(L, L, V, rp, ci, stale, bits)
+    mc.set_softmax_variant(variant)
+    try:
+        mc.sparse_softmax_to_mat(Pm, torch.from_numpy(S).cuda(), float(scale), float(pmax))
+    finally:
+        mc.set_softmax_variant(0)
+    eye = torch.eye(L, dtype=torch.int8, device="cuda")
+    got = mc.spmm(Pm, eye, "L8R8" if bits == 8 else "L16R8")
+    torch.cuda.synchronize()
+    got = got.cpu().numpy()
+    Pm.close()
+    p = oracle.sparse_softmax(S, rp, V, scale)
+    want_codes = oracle.requantize_probabilities(p, 1.0 / pmax, bits)
+    want, _ = oracle.bcrs_to_dense(L, L, V, rp, ci, want_codes.reshape(nvec, V))
+    amb_dense, _ = oracle.bcrs_to_dense(L, L, V, rp, ci, _tie_ambiguous(p, 1.0 / pmax).reshape(nvec, V).astype(np.int32))
+    amb = amb_dense.astype(bool)
+    diff = got.astype(np.int64) - want.astype(np.int64)
+    assert (diff[~amb] == 0).all(), f"{np.count_nonzero(diff[~amb])} mismatches away from ties"
+    assert (np.abs(diff[amb]) <= 1).all() and amb.mean() < 0.05
+    assert got.max() == pmax                                       # the single-entry rows: p = 1

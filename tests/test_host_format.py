@@ -162,6 +162,7 @@ def test_entry_points_reject_bad_arguments_before_touching_the_gpu():
     assert L.mc_spmm_dequant(None, None, 16, 16, 0, 0, 1.0, 7, None, 16, None) == mc.MC_EUNSUPPORTED
     assert L.mc_sddmm_dequant(None, 64, None, 64, 64, None, 0, 0, 1.0, 1, None, None) == mc.MC_EINVAL
     assert L.mc_sddmm_dequant(None, 64, None, 64, 64, None, 0, 0, 1.0, -1, None, None) == mc.MC_EUNSUPPORTED
+    assert L.mc_sparse_softmax_to_mat(None, None, 1.0, 1.0, None) == mc.MC_EINVAL
     assert L.mc_absmax(None, 4, None, None) == mc.MC_EINVAL
     assert L.mc_quantize(None, 4, 1.0, 8, None, None) == mc.MC_EINVAL
     assert L.mc_probe_gather(None, None, 16, 16, 0, None, None) == mc.MC_EINVAL
