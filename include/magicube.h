@@ -321,9 +321,10 @@ int mc_set_spmm_splitting(int enable); /* also governs the work items of mc_sddm
  * (any row length), 1, 2, 4 or 8 = waves per panel of the kernel that stages Kmat rows in
  * LDS (used when a row has 64, 128, 256 or 512 bytes, else ignored).  Process-wide. */
 int mc_set_sddmm_variant(int waves);
-/* Softmax variant: 0 = automatic (panels of up to 16384 scores, padding included, are kept in
- * registers: one pass over the scores), 2 = always the kernel for panels of any length (three
- * passes).  Same codes up to fp32 summation order.  Process-wide. */
+/* Softmax variant: 0 = automatic (panels of up to 4096 scores, padding included, are kept in
+ * the registers of one wave, up to 16384 in those of a workgroup: one pass over the scores),
+ * 1 = a workgroup per panel also for short panels, 2 = always the kernel for panels of any
+ * length (three passes).  Same codes up to fp32 summation order.  Process-wide. */
 int mc_set_softmax_variant(int variant);
 /* Attention path: 0 = automatic (a single fused kernel when dk == 64 and no panel holds
  * more than 2048 vectors -- one, two or four waves per (panel, head) for panels of up to 512,

@@ -15,7 +15,7 @@ int g_variant_bnb = 0, g_variant_waves = 0;
 int g_sddmm_waves = -1;   // -1 automatic, 0 direct-load kernel, 1/2/4/8 waves of the LDS-staged kernel
 int g_attention_mode = 0; // 0 automatic, 1 always the unfused four-kernel pipeline
 int g_spmm_items = 1;     // 1: matrices with very unequal panels run through their work items
-int g_softmax_variant = 0; // 0: automatic; 2: the any-length softmax kernel always
+int g_softmax_variant = 0; // 0: automatic; 1: a workgroup per panel; 2: the any-length softmax kernel always
 int g_spmm_stages = 2;    // chunks in flight per wave of the SpMM kernel (1 or 2)
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -156,7 +156,7 @@ extern "C" int mc_set_sddmm_variant(int waves)
 
 extern "C" int mc_set_softmax_variant(int variant)
 {
-    if (variant != 0 && variant != 2) return MC_EINVAL;
+    if (variant != 0 && variant != 1 && variant != 2) return MC_EINVAL;
     g_softmax_variant = variant;
     return MC_OK;
 }

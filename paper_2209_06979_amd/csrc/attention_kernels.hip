@@ -325,8 +325,8 @@ void attention_fused_kernel(AttnArgs a)
         const int gc = ks + c * KS;
         if (c < nloc) {
             // Codes of this chunk's slots (tile*16 + j), rows 4*(g&1) .. +3: one 32-bit LDS write
-            // per tile.  v_cvt_pk_u8_f32 rounds to nearest even, saturates to [0, 255] and drops
-            // the byte into place; e * rinv cannot exceed 127 by more than rounding noise.
+            // per tile.  v_cvt_pk_u8_f32 rounds to nearest even and drops the byte into place; the
+            // largest code is 127 (p / s_p exceeds it when s_p < 1/127), hence the minimum.
             // Done here, chunk by chunk, so that this ALU work overlaps the V copies in flight.
 #pragma unroll
             for (int pr = 0; pr < 2; ++pr) {
@@ -334,7 +334,7 @@ void attention_fused_kernel(AttnArgs a)
                 if (PB == 8) {
                     unsigned packed = 0;
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) packed = __builtin_amdgcn_cvt_pk_u8_f32(x[2 * c + pr][r] * rinv[r], r, packed);
+                    for (int r = 0; r < 4; ++r) packed = __builtin_amdgcn_cvt_pk_u8_f32(fminf(x[2 * c + pr][r] * rinv[r], 127.f), r, packed);
                     *reinterpret_cast<unsigned *>(Pl + slot * 8 + 4 * (g & 1)) = packed;
                 } else {
                     // code = clamp(rint(e * rinv), 0, 32639) (ties to even), hi = (code + 128) >> 8 in

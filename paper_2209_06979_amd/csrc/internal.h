@@ -80,7 +80,7 @@ struct SoftmaxArgs {
     float score_scale, inv_s_p;
     int P, V, batch, code_bits;
     int max_panel_chunks;      // longest panel of the mask, in chunks of 64 vectors
-    int variant;               // 0: automatic; 2: the any-length kernel even for short panels
+    int variant;               // 0: automatic; 1: a workgroup per panel even for short panels; 2: the any-length kernel
 };
 
 struct RepackArgs {

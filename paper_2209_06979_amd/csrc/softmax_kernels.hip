@@ -5,9 +5,12 @@
 // of nvec_p * V int32 in interchange order (V consecutive values per stored vector), and every
 // row of the panel has the same number of entries, so the rows of a panel are reduced together.
 //
-//   softmax_cached_kernel<R>  panels of up to R * 1024 scores: each thread keeps R pieces of four
-//                             consecutive scores in registers; one read of the scores, one
-//                             exponential per score, row reductions by lane exchanges.
+//   softmax_wave_kernel<R>    panels of up to R * 256 scores: ONE WAVE per panel (four panels per
+//                             workgroup), each lane keeps R pieces of four consecutive scores in
+//                             registers; one read of the scores, one exponential per score, row
+//                             reductions by lane exchanges, no barrier anywhere.
+//   softmax_cached_kernel<R>  panels of up to R * 1024 scores: the same with the four waves of a
+//                             workgroup sharing one panel (reductions finish through LDS).
 //   softmax_general_kernel    any panel length: three passes over the scores in memory.
 //
 // The integer codes go out either in interchange order (int8 / int16) or straight in the device
@@ -15,6 +18,8 @@
 // consumer): per chunk of 64 slots and group of 16 slots, [row v][16 slots] bytes; 16-bit codes as
 // a high and a low signed-byte plane; padded slots zero.
 #include "internal.h"
+
+#include <type_traits>
 
 namespace {
 
@@ -26,11 +31,13 @@ constexpr float LOG2E = 1.4426950408889634f;
 // largest code: int8 maximum, or the largest 16-bit value that splits into two signed bytes
 __device__ __forceinline__ float code_max(int code_bits) { return (code_bits == 16) ? 32639.f : 127.f; }
 
-// byte offset of (vector i of the panel, row v) in the panel's device-format values; 16-bit
-// codes: offset of the high plane, the low plane follows 16 * V bytes later
-__device__ __forceinline__ int dev_offset(int i, int v, int V, int pb)
+// byte offset of element e = i * V + v (vector i of the panel, row v; V = 1 << vs) in the panel's
+// device-format values; 16-bit codes (pb = 2): offset of the high plane, the low plane follows
+// 16 * V bytes later
+__device__ __forceinline__ int dev_offset(int e, int vs, int pb)
 {
-    return (i / MC_CHUNK) * (MC_CHUNK * V * pb) + ((i % MC_CHUNK) / 16) * (16 * V * pb) + v * 16 + (i % 16);
+    const int i = e >> vs, v = e & ((1 << vs) - 1);
+    return (((i >> 6) * MC_CHUNK + ((i >> 4) & 3) * 16) << vs) * pb + v * 16 + (i & 15);
 }
 
 // Combines the four per-lane values of every lane that holds the same rows: a lane's piece e0 =
@@ -38,7 +45,7 @@ __device__ __forceinline__ int dev_offset(int i, int v, int V, int pb)
 // r % 2 for V = 2 (then components 0/2 and 1/3 belong together).  MAX: maximum, else sum.
 template <bool MAX> __device__ __forceinline__ float comb(float x, float y) { return MAX ? fmaxf(x, y) : x + y; }
 
-template <bool MAX> __device__ __forceinline__ v4f reduce_rows(v4f x, int V, float (*red)[8], int lane, int w)
+template <bool MAX> __device__ __forceinline__ v4f reduce_lanes(v4f x, int V)
 {
     if (V == 2) {
         x.x = x.z = comb<MAX>(x.x, x.z);
@@ -52,7 +59,13 @@ template <bool MAX> __device__ __forceinline__ v4f reduce_rows(v4f x, int V, flo
         for (int d = 2; d < 64; d <<= 1) v = comb<MAX>(v, __shfl_xor(v, d, 64));
         x[r] = v;
     }
-    // across the four waves: lanes 0 and 1 of each wave publish their rows
+    return x;
+}
+
+// ... and across the four waves of a workgroup: lanes 0 and 1 of each wave publish their rows
+template <bool MAX> __device__ __forceinline__ v4f reduce_rows(v4f x, int V, float (*red)[8], int lane, int w)
+{
+    x = reduce_lanes<MAX>(x, V);
     const int c = (V == 8) ? (lane & 1) : 0;
     if (lane < 2) {
 #pragma unroll
@@ -66,39 +79,47 @@ template <bool MAX> __device__ __forceinline__ v4f reduce_rows(v4f x, int V, flo
     return x;
 }
 
-template <int R> __global__ __launch_bounds__(256) void softmax_cached_kernel(SoftmaxArgs a)
+// Scores -> codes for a panel handled by NT threads (one wave: NT = 64; a workgroup: NT = 256);
+// thread t of them owns the pieces 4 * (t + NT * k), k < R.  reduce(x, is_max) finishes a row
+// reduction over those threads; sync() orders the staged codes before they are copied out.
+// C16: 16-bit codes (else 8-bit); DEV: device panel format (else interchange order) -- compile-time,
+// so that the unrolled per-piece code carries no branches on the mode.
+template <int R, int NT, bool C16, bool DEV, class Reduce, class Sync>
+__device__ __forceinline__ void softmax_panel(const SoftmaxArgs &a, int panel, int batch, int t, uint8_t *stage,
+                                              Reduce &&reduce, Sync &&sync)
 {
-    __shared__ float red_max[4][8], red_sum[4][8];
-    __shared__ __attribute__((aligned(16))) uint8_t stage[R * 1024 * 2]; // device-format codes of the panel
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    const int panel = blockIdx.x, batch = blockIdx.y, V = a.V;
+    const int V = a.V, vs = (V == 8) ? 3 : (V == 4 ? 2 : 1);
     const int64_t base = (int64_t)batch * a.batch_stride + (int64_t)a.row_ptr[panel] * V;
     const int cnt = (a.row_ptr[panel + 1] - a.row_ptr[panel]) * V;
-    if (cnt == 0) return;
     const int32_t *S = a.S + base;
 
     // softmax in base 2: exp(x - max) = 2^(x * log2(e) - max2)
     const float scale2 = a.score_scale * LOG2E;
+    const v4f absent = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
     v4f x[R];
 #pragma unroll
     for (int k = 0; k < R; ++k) {
-        const int e0 = 4 * (tid + 256 * k);
-        v4f f = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+        const int e0 = 4 * (t + NT * k);
+        v4f f = absent;
         if (e0 + 4 <= cnt) {
             v4i s;
-            __builtin_memcpy(&s, S + e0, 16);   // only 4-byte alignment is known (V = 2 panels start anywhere)
+            __builtin_memcpy(&s, S + e0, 16);   // only 8-byte alignment is known (V = 2 panels start at any vector)
             f = (v4f){(float)s.x * scale2, (float)s.y * scale2, (float)s.z * scale2, (float)s.w * scale2};
-        } else {
-#pragma unroll
-            for (int r = 0; r < 4; ++r)
-                if (e0 + r < cnt) f[r] = (float)S[e0 + r] * scale2;
         }
         x[k] = f;
     }
-    v4f m = x[0];
+    // V = 2 with an odd number of vectors leaves half a piece: thread 0 keeps it beside its pieces
+    // (components 0, 1 = rows 0, 1 of the last vector)
+    const bool tail = (cnt & 3) != 0;
+    v4f xt = absent;
+    if (tail && t == 0) {
+        xt.x = (float)S[cnt - 2] * scale2;
+        xt.y = (float)S[cnt - 1] * scale2;
+    }
+    v4f m = {fmaxf(x[0].x, xt.x), fmaxf(x[0].y, xt.y), x[0].z, x[0].w};
 #pragma unroll
     for (int k = 1; k < R; ++k) m = (v4f){fmaxf(m.x, x[k].x), fmaxf(m.y, x[k].y), fmaxf(m.z, x[k].z), fmaxf(m.w, x[k].w)};
-    m = reduce_rows<true>(m, V, red_max, lane, w);
+    m = reduce(m, std::true_type{});
 
     v4f sum = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -107,63 +128,137 @@ template <int R> __global__ __launch_bounds__(256) void softmax_cached_kernel(So
         for (int r = 0; r < 4; ++r) x[k][r] = __builtin_amdgcn_exp2f(x[k][r] - m[r]); // absent entries: 2^-inf = 0
         sum += x[k];
     }
-    sum = reduce_rows<false>(sum, V, red_sum, lane, w);
+    xt.x = __builtin_amdgcn_exp2f(xt.x - m.x);
+    xt.y = __builtin_amdgcn_exp2f(xt.y - m.y);
+    sum.x += xt.x;
+    sum.y += xt.y;
+    sum = reduce(sum, std::false_type{});
 
-    // p / s_p = e * (1 / (sum * s_p)): one division per row
+    // p / s_p = e * (1 / (sum * s_p)): one division per row.  e * rinv is never negative, so the
+    // code is min(., largest code) rounded to nearest even (v_cvt_pk_u8_f32 rounds that way and
+    // drops the byte into place).
     const v4f rinv = {a.inv_s_p / sum.x, a.inv_s_p / sum.y, a.inv_s_p / sum.z, a.inv_s_p / sum.w};
-    const float qmax = code_max(a.code_bits);
-    const int pb = a.code_bits / 8;
-    const bool aligned = (base & 3) == 0;  // interchange order: whole pieces can go out as one store
-    const int cpad = (cnt / V + MC_CHUNK - 1) / MC_CHUNK * MC_CHUNK * V;
+    const float qmax = code_max(C16 ? 16 : 8);
+    constexpr int pb = C16 ? 2 : 1;
+    auto codes_of = [&](v4f e, unsigned &lo, unsigned &hi) {
+        // 8 bit: lo = the four codes as bytes; 16 bit: lo, hi = codes 0, 1 and 2, 3 as halfwords
+        lo = hi = 0;
+        if (!C16) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) lo = __builtin_amdgcn_cvt_pk_u8_f32(fminf(e[r] * rinv[r], qmax), r, lo);
+        } else {
+            const unsigned q0 = (unsigned)rintf(fminf(e.x * rinv.x, qmax)), q1 = (unsigned)rintf(fminf(e.y * rinv.y, qmax));
+            const unsigned q2 = (unsigned)rintf(fminf(e.z * rinv.z, qmax)), q3 = (unsigned)rintf(fminf(e.w * rinv.w, qmax));
+            lo = q0 | (q1 << 16);
+            hi = q2 | (q3 << 16);
+        }
+    };
+    // one code into the staged device format
+    auto stage_code = [&](int off, unsigned q) {
+        if (C16) {
+            const unsigned h = (q + 128) >> 8; // balanced split into two signed bytes
+            stage[off] = (uint8_t)h;
+            stage[off + 16 * V] = (uint8_t)(q - h * 256);
+        } else {
+            stage[off] = (uint8_t)q;
+        }
+    };
+    auto code_at = [&](unsigned lo, unsigned hi, int r) -> unsigned {
+        return C16 ? ((r < 2 ? lo : hi) >> (16 * (r & 1))) & 0xffffu : (lo >> (8 * r)) & 0xffu;
+    };
+    const bool aligned = (base & 3) == 0;  // else (V = 2 only) the block starts half a piece off
+    const int cpad = (((cnt >> vs) + MC_CHUNK - 1) / MC_CHUNK * MC_CHUNK) << vs;
 #pragma unroll
     for (int k = 0; k < R; ++k) {
-        const int e0 = 4 * (tid + 256 * k);
-        int q[4];
-#pragma unroll
-        for (int r = 0; r < 4; ++r) q[r] = (int)fminf(fmaxf(rintf(x[k][r] * rinv[r]), 0.f), qmax);
-        if (a.codes) {
-            if (e0 >= cnt) continue;
-            if (a.code_bits == 8) {
+        const int e0 = 4 * (t + NT * k);
+        const bool full = e0 + 4 <= cnt;
+        unsigned lo, hi;
+        codes_of(x[k], lo, hi);
+        if (!DEV) {
+            if (!full) continue;
+            if (!C16) {
                 int8_t *o = static_cast<int8_t *>(a.codes) + base + e0;
-                if (aligned && e0 + 4 <= cnt) {
-                    *reinterpret_cast<int *>(o) = q[0] | (q[1] << 8) | (q[2] << 16) | (q[3] << 24);
+                if (aligned) {
+                    *reinterpret_cast<unsigned *>(o) = lo;
                 } else {
-#pragma unroll
-                    for (int r = 0; r < 4; ++r)
-                        if (e0 + r < cnt) o[r] = (int8_t)q[r];
+                    reinterpret_cast<uint16_t *>(o)[0] = (uint16_t)lo;
+                    reinterpret_cast<uint16_t *>(o)[1] = (uint16_t)(lo >> 16);
                 }
             } else {
                 int16_t *o = static_cast<int16_t *>(a.codes) + base + e0;
-                if (aligned && e0 + 4 <= cnt) {
-                    *reinterpret_cast<int2 *>(o) = make_int2(q[0] | (q[1] << 16), q[2] | (q[3] << 16));
+                if (aligned) {
+                    *reinterpret_cast<uint2 *>(o) = make_uint2(lo, hi);
                 } else {
-#pragma unroll
-                    for (int r = 0; r < 4; ++r)
-                        if (e0 + r < cnt) o[r] = (int16_t)q[r];
+                    reinterpret_cast<unsigned *>(o)[0] = lo;
+                    reinterpret_cast<unsigned *>(o)[1] = hi;
                 }
             }
         } else if (e0 < cpad) {
-            // the padded slots of the last chunk take part with code 0 (their e is 0)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int e = e0 + r, off = dev_offset(e / V, e % V, V, pb);
-                if (a.code_bits == 16) {
-                    const int hi = (q[r] + 128) >> 8;
-                    stage[off] = (uint8_t)hi;
-                    stage[off + 16 * V] = (uint8_t)(q[r] - hi * 256);
-                } else {
-                    stage[off] = (uint8_t)q[r];
-                }
+            // a piece holds rows v .. v+3 of one vector (V >= 4: 16 bytes apart) or two vectors (V = 2);
+            // beyond the panel's end the padded slots of the last chunk get code 0 (their e is 0), and the
+            // half piece at the end is left to thread 0
+            const int offa = dev_offset(e0, vs, pb), offb = (V == 2) ? dev_offset(e0 + 2, vs, pb) : offa + 32;
+            if (full || e0 >= cnt) {
+                stage_code(offa, code_at(lo, hi, 0));
+                stage_code(offa + 16, code_at(lo, hi, 1));
             }
+            stage_code(offb, code_at(lo, hi, 2));
+            stage_code(offb + 16, code_at(lo, hi, 3));
         }
     }
-    if (!a.codes) {
-        __syncthreads();
+    if (tail && t == 0) {
+        unsigned lo, hi;
+        codes_of(xt, lo, hi);
+        if (!DEV) {
+            if (!C16) *reinterpret_cast<uint16_t *>(static_cast<int8_t *>(a.codes) + base + cnt - 2) = (uint16_t)lo;
+            else *reinterpret_cast<unsigned *>(static_cast<int16_t *>(a.codes) + base + cnt - 2) = lo;
+        } else {
+            const int off = dev_offset(cnt - 2, vs, pb);
+            stage_code(off, code_at(lo, hi, 0));
+            stage_code(off + 16, code_at(lo, hi, 1));
+        }
+    }
+    if (DEV) {
+        sync();
         const int s0 = a.panel_ptr[2 * panel]; // chunk-aligned first slot of the panel
         uint8_t *dst = a.dev_vals + (int64_t)batch * a.dev_batch_stride + (int64_t)(s0 / MC_CHUNK) * (MC_CHUNK * V * pb);
-        for (int o = tid * 16; o < cpad * pb; o += 256 * 16)
+        for (int o = t * 16; o < cpad * pb; o += NT * 16)
             *reinterpret_cast<v4i *>(dst + o) = *reinterpret_cast<const v4i *>(stage + o);
     }
+}
+
+// four waves per SIMD: every panel of a 4096-panel launch is resident at once
+template <int R, bool C16, bool DEV>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) void softmax_wave_kernel(SoftmaxArgs a)
+{
+    __shared__ __attribute__((aligned(16))) uint8_t stage[4][DEV ? R * 256 * (C16 ? 2 : 1) : 16]; // device-format codes, per wave
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int panel = blockIdx.x * 4 + w, batch = blockIdx.y, V = a.V;
+    if (panel >= a.P || a.row_ptr[panel + 1] == a.row_ptr[panel]) return; // waves never meet in this kernel
+    softmax_panel<R, 64, C16, DEV>(
+        a, panel, batch, lane, stage[w],
+        [&](v4f x, auto is_max) { return reduce_lanes<decltype(is_max)::value>(x, V); },
+        [&]() {
+            // LDS executes a wave's instructions in order; keep the compiler from moving the reads up
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            __builtin_amdgcn_wave_barrier();
+        });
+}
+
+template <int R, bool C16, bool DEV> __global__ __launch_bounds__(256) void softmax_cached_kernel(SoftmaxArgs a)
+{
+    __shared__ float red_max[4][8], red_sum[4][8];
+    __shared__ __attribute__((aligned(16))) uint8_t stage[DEV ? R * 1024 * (C16 ? 2 : 1) : 16]; // device-format codes of the panel
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int panel = blockIdx.x, batch = blockIdx.y, V = a.V;
+    if (a.row_ptr[panel + 1] == a.row_ptr[panel]) return;                 // uniform: before any barrier
+    softmax_panel<R, 256, C16, DEV>(
+        a, panel, batch, tid, stage,
+        [&](v4f x, auto is_max) {
+            constexpr bool MAX = decltype(is_max)::value;
+            return reduce_rows<MAX>(x, V, MAX ? red_max : red_sum, lane, w);
+        },
+        [&]() { __syncthreads(); });
 }
 
 // Thread t owns elements t, t+256, ... of the panel's score block; 256 % V == 0, so a thread
@@ -205,12 +300,12 @@ __global__ __launch_bounds__(256) void softmax_general_kernel(SoftmaxArgs a)
     }
     const int s0 = a.panel_ptr[2 * panel];
     const int cpad = (cnt / V + MC_CHUNK - 1) / MC_CHUNK * MC_CHUNK * V;
-    const int pb = a.code_bits / 8;
+    const int pb = a.code_bits / 8, vs = (V == 8) ? 3 : (V == 4 ? 2 : 1);
     uint8_t *dst = a.dev_vals + (int64_t)batch * a.dev_batch_stride + (int64_t)(s0 / MC_CHUNK) * (MC_CHUNK * V * pb);
     for (int e = tid; e < cpad; e += 256) {
         int x = 0; // padded slots hold zeros
         if (e < cnt) x = (int)fminf(fmaxf(rintf(__builtin_amdgcn_exp2f((float)S[e] * scale2 - m) * rinv), 0.f), qmax);
-        uint8_t *o = dst + dev_offset(e / V, v, V, pb);
+        uint8_t *o = dst + dev_offset(e, vs, pb);
         if (a.code_bits == 16) {
             const int hi = (x + 128) >> 8;
             o[0] = (uint8_t)hi;
@@ -223,13 +318,19 @@ __global__ __launch_bounds__(256) void softmax_general_kernel(SoftmaxArgs a)
 
 } // namespace
 
+template <bool C16, bool DEV> hipError_t launch_softmax_mode(const SoftmaxArgs &a, hipStream_t s)
+{
+    dim3 grid((unsigned)a.P, (unsigned)a.batch), grid4((unsigned)((a.P + 3) / 4), (unsigned)a.batch), block(256);
+    const int64_t longest = (int64_t)a.max_panel_chunks * MC_CHUNK * a.V; // scores of the longest panel, padding included
+    if (a.variant == 0 && longest <= 16 * 256) hipLaunchKernelGGL((softmax_wave_kernel<16, C16, DEV>), grid4, block, 0, s, a);
+    else if (a.variant != 2 && longest <= 16 * 1024) hipLaunchKernelGGL((softmax_cached_kernel<16, C16, DEV>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL(softmax_general_kernel, grid, block, 0, s, a);
+    return hipGetLastError();
+}
+
 hipError_t launch_softmax(const SoftmaxArgs &a, hipStream_t s)
 {
     if (a.P == 0 || a.batch == 0) return hipSuccess;
-    dim3 grid((unsigned)a.P, (unsigned)a.batch), block(256);
-    const int64_t longest = (int64_t)a.max_panel_chunks * MC_CHUNK * a.V; // scores of the longest panel, padding included
-    if (a.variant != 2 && longest <= 4 * 1024) hipLaunchKernelGGL(softmax_cached_kernel<4>, grid, block, 0, s, a);
-    else if (a.variant != 2 && longest <= 16 * 1024) hipLaunchKernelGGL(softmax_cached_kernel<16>, grid, block, 0, s, a);
-    else hipLaunchKernelGGL(softmax_general_kernel, grid, block, 0, s, a);
-    return hipGetLastError();
+    if (a.codes) return (a.code_bits == 16) ? launch_softmax_mode<true, false>(a, s) : launch_softmax_mode<false, false>(a, s);
+    return (a.code_bits == 16) ? launch_softmax_mode<true, true>(a, s) : launch_softmax_mode<false, true>(a, s);
 }

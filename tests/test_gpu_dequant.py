@@ -214,7 +214,7 @@ def test_attention_fp16_output_batched_and_config5():
 
 
 # ------------------------------------------- softmax writing the SpMM operand format ----
-@pytest.mark.parametrize("variant", [0, 2])                    # scores kept in registers / the any-length kernel
+@pytest.mark.parametrize("variant", [0, 1, 2])                 # a wave / a workgroup per panel, the any-length kernel
 @pytest.mark.parametrize("V", [2, 4, 8])
 @pytest.mark.parametrize("bits", [8, 16])
 def test_softmax_codes_written_in_the_device_format(V, bits, variant):

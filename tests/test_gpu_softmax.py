@@ -50,7 +50,7 @@ def _counts(P, head, fill):
     return c
 
 
-@pytest.mark.parametrize("variant", [0, 2])
+@pytest.mark.parametrize("variant", [0, 1, 2])     # a wave per panel / a workgroup per panel / the any-length kernel
 @pytest.mark.parametrize("bits", [8, 16])
 @pytest.mark.parametrize("V", [2, 4, 8])
 def test_softmax_ragged_panels(V, bits, variant):
@@ -63,13 +63,13 @@ def test_softmax_ragged_panels(V, bits, variant):
 @pytest.mark.parametrize("bits", [8, 16])
 @pytest.mark.parametrize("V", [2, 4, 8])
 def test_softmax_panel_lengths_around_the_register_limits(V, bits):
-    """4096 and 16384 scores per panel (padding included) are the limits of the two register-cached
-    variants; the panels here sit just below, at and above them."""
+    """4096 and 16384 scores per panel (padding included) are the limits of the kernels that keep a
+    panel in the registers of a wave / of a workgroup; the panels here sit just below, at and above them."""
     L = 4096
     per = lambda scores: scores // V            # vectors for a number of scores
     head = [per(4096) - 1, per(4096), per(4096) + 1]
-    _check(V, L, _counts(L // V, head, 5), 7100 + V, bits)                     # longest > 4096 scores: 16-piece variant
-    _check(V, L, _counts(L // V, [per(4096)], 5), 7110 + V, bits)              # exactly 4096: 4-piece variant
+    _check(V, L, _counts(L // V, head, 5), 7100 + V, bits)                     # longest > 4096 scores: a workgroup per panel
+    _check(V, L, _counts(L // V, [per(4096)], 5), 7110 + V, bits)              # exactly 4096: a wave per panel
     if per(16384) <= L:
         _check(V, L, _counts(L // V, [per(16384)], 5), 7120 + V, bits)         # exactly 16384
     if per(16384) + 1 <= L:
@@ -84,7 +84,7 @@ def test_softmax_extreme_scores_and_single_entries():
     _check(4, 256, _counts(64, [1], 9), 7202, 8, score_range=3, scale=1e-3)    # nearly uniform rows
 
 
-@pytest.mark.parametrize("variant", [0, 2])
+@pytest.mark.parametrize("variant", [0, 1, 2])
 def test_softmax_config5_shape(variant):
     c = wl.attention_case(1, 4096, 64, 8, 0.9, wl.seed_for(5, 3))
     counts = np.diff(c["row_ptr"])
