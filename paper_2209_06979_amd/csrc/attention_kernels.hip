@@ -395,6 +395,31 @@ void attention_fused_kernel(AttnArgs a)
     }
     lgkm_wait();
     if (KS > 1) __syncthreads(); else __builtin_amdgcn_wave_barrier();
+    if (a.out_f16) {
+        // fp16: 8 rows x 8 pieces of 8 columns, one 16-byte store per thread
+        const int piece = (KS > 1) ? (int)threadIdx.x : lane;
+        if (piece < 64) {
+            const int row = piece >> 3, col = (piece & 7) * 8;
+            v4h hv[2];
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                v4i sres = {0, 0, 0, 0}, slo = {0, 0, 0, 0};
+#pragma unroll
+                for (int k = 0; k < KS; ++k) {
+                    const int *Ok = (KS > 1) ? reinterpret_cast<const int *>(Pl_all + k * PLB) : Ol;
+                    sres += *reinterpret_cast<const v4i *>(&Ok[row * (DK + 4) + col + 4 * q]);
+                    if (PB == 16) slo += *reinterpret_cast<const v4i *>(&Ok[(row + 8) * (DK + 4) + col + 4 * q]);
+                }
+                if (PB == 16) sres = (sres << 8) + slo;
+                hv[q] = to_half4((v4f){sres.x * a.out_scale, sres.y * a.out_scale, sres.z * a.out_scale, sres.w * a.out_scale});
+            }
+            typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+            const int64_t off = (Oh - a.O) + (int64_t)row * a.token_stride + col;
+            *reinterpret_cast<v8h *>(reinterpret_cast<_Float16 *>(a.O) + off) =
+                (v8h){hv[0].x, hv[0].y, hv[0].z, hv[0].w, hv[1].x, hv[1].y, hv[1].z, hv[1].w};
+        }
+        return;
+    }
     // 8 rows x 16 pieces of 4 columns; with KS waves the first 128 threads add up the partial tiles
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
@@ -410,9 +435,7 @@ void attention_fused_kernel(AttnArgs a)
         }
         if (PB == 16) sres = (sres << 8) + slo;
         const v4f f = {sres.x * a.out_scale, sres.y * a.out_scale, sres.z * a.out_scale, sres.w * a.out_scale};
-        const int64_t off = (Oh - a.O) + (int64_t)row * a.token_stride + col;
-        if (a.out_f16) *reinterpret_cast<v4h *>(reinterpret_cast<_Float16 *>(a.O) + off) = to_half4(f);
-        else *reinterpret_cast<v4f *>(a.O + off) = f;
+        *reinterpret_cast<v4f *>(Oh + (int64_t)row * a.token_stride + col) = f;
     }
 }
 
