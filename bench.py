@@ -86,6 +86,9 @@ def main():
     ap.add_argument("--only", default="", help="comma-separated kernel names: run only these in the step")
     ap.add_argument("--attention-layout", choices=["token", "head"], default="token",
                     help="Q/K/V buffers token-major (L, heads, dk) as a projection writes them, or head-major (heads, L, dk)")
+    ap.add_argument("--attention-mode", type=int, default=0,
+                    help="0: automatic (the fused kernel); 1: the pipeline of separate SDDMM / softmax / SpMM kernels "
+                         "(for profiling them; the value is then not the headline number)")
     ap.add_argument("--no-per-kernel", action="store_true", help="skip the per-kernel timing runs (counter collection)")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the measurements beside the step: cold-cache and gather-only timings of the headline "
@@ -160,6 +163,7 @@ def main():
     torch.cuda.synchronize()
     format_build_s = time.perf_counter() - t0
 
+    mc.set_attention_mode(args.attention_mode)
     if args.only:
         names = set(args.only.split(","))
         kernels = [k for k in kernels if k["name"] in names]
@@ -217,7 +221,7 @@ def main():
                 samples.append(e0.elapsed_time(e1) * 1e3 / args.reps)   # microseconds per launch
             k["us"] = float(np.median(samples))
             del g
-        extras = None if (args.no_extras or args.only) else measure_extras(mc, torch, prob, stream, args.reps, up)
+        extras = None if (args.no_extras or args.only or args.attention_mode) else measure_extras(mc, torch, prob, stream, args.reps, up)
     ms_per_step = elapsed / args.steps * 1e3
     total_ops = sum(k["ops"] for k in kernels)
     value = total_ops / (elapsed / args.steps) / 1e12
@@ -256,7 +260,8 @@ def main():
         "dtype": "int8", "data": "synthetic",
         "config": {"workload": "4096x4096 V=8 s=0.9: SpMM L8-R8/L8-R4/L4-R4/L16-R8 N=256 + SDDMM L8-R8/L4-R4 K=256 "
                                "+ sparse attention 8 heads L=4096 dk=64",
-                   "launch": "eager" if args.eager else f"hip_graph x{spg} steps", "kernels_in_step": [k["name"] for k in kernels]},
+                   "launch": "eager" if args.eager else f"hip_graph x{spg} steps", "kernels_in_step": [k["name"] for k in kernels],
+                   **({"attention_mode": args.attention_mode} if args.attention_mode else {})},
         "headline_spmm_l8r8": dict(per_kernel.get("spmm_L8R8") or {}, **((extras or {}).get("headline") or {})),
         "cold_cache_us": (extras or {}).get("cold_us"),
         "gather_peak_tbs_measured": (extras or {}).get("gather_peak_tbs"),
