@@ -435,7 +435,7 @@ void attention_fused_kernel(AttnArgs a)
         }
         if (PB == 16) sres = (sres << 8) + slo;
         const v4f f = {sres.x * a.out_scale, sres.y * a.out_scale, sres.z * a.out_scale, sres.w * a.out_scale};
-        *reinterpret_cast<v4f *>(Oh + (int64_t)row * a.token_stride + col) = f;
+        __builtin_nontemporal_store(f, reinterpret_cast<v4f *>(Oh + (int64_t)row * a.token_stride + col));
     }
 }
 

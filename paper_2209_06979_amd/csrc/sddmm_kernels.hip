@@ -110,8 +110,8 @@ __device__ __forceinline__ void store_scores(const SddmmArgs &a, int64_t out0, i
         const int64_t off = out0 + (int64_t)slot * a.V + 4 * g;
         if (!DQ) {
             int32_t *o = static_cast<int32_t *>(a.S) + off;
-            if (a.V >= 4) *reinterpret_cast<v4i *>(o) = acc;
-            else *reinterpret_cast<v2i *>(o) = (v2i){acc.x, acc.y};
+            if (a.V >= 4) __builtin_nontemporal_store(acc, reinterpret_cast<v4i *>(o));
+            else __builtin_nontemporal_store((v2i){acc.x, acc.y}, reinterpret_cast<v2i *>(o));
         } else {
             const v4f f = {acc.x * a.out_scale, acc.y * a.out_scale, acc.z * a.out_scale, acc.w * a.out_scale};
             if (a.float_out == 1) {

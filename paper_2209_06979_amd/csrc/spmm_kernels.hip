@@ -354,7 +354,7 @@ __global__ __launch_bounds__(64 * WK) void spmm_kernel(SpmmArgs a)
             int32_t *c = static_cast<int32_t *>(a.C) + off;
             atomicAdd(c, s.x); atomicAdd(c + 1, s.y); atomicAdd(c + 2, s.z); atomicAdd(c + 3, s.w);
         } else {
-            *reinterpret_cast<v4i *>(static_cast<int32_t *>(a.C) + off) = s;
+            __builtin_nontemporal_store(s, reinterpret_cast<v4i *>(static_cast<int32_t *>(a.C) + off));
         }
     }
 }
