@@ -417,7 +417,7 @@ def measure_extras(mc, torch, prob, stream, reps, up):
         ws = torch.empty(mc.attention_workspace_bytes(HEADS, amask, p_bits), dtype=torch.uint8, device="cuda")
         s_p = np.float32(1.0 / (32639.0 if p_bits == 16 else 127.0))
         us = time_graph(torch, stream, [lambda: mc.sparse_attention(q, k, v, amask, s_q, s_k, s_v, s_p, out=O, workspace=ws,
-                                                                    p_bits=p_bits, qkv_bits=qkv_bits)] * max(1, reps // 4))
+                                                                    p_bits=p_bits, qkv_bits=qkv_bits)] * reps)
         ops = HEADS * 2 * (2 * amask.nvec * V * DK)
         wide[name] = dict(us=round(us, 2), eff_tops=round(ops / us / 1e6, 1))
     # the paper's output type: fp16 written by the fused dequantisation (the step's rows write int32 / fp32)
@@ -426,13 +426,13 @@ def measure_extras(mc, torch, prob, stream, reps, up):
     O16 = torch.empty((L_ATT, HEADS, DK), dtype=torch.float16, device="cuda").permute(1, 0, 2)
     ws = torch.empty(mc.attention_workspace_bytes(HEADS, amask), dtype=torch.uint8, device="cuda")
     us = time_graph(torch, stream, [lambda: mc.sparse_attention(q, k, v, amask, att["s_q"], att["s_k"], att["s_v"], att["s_p"],
-                                                                out=O16, workspace=ws, out_dtype=torch.float16)] * max(1, reps // 4))
+                                                                out=O16, workspace=ws, out_dtype=torch.float16)] * reps)
     wide["attention_8b8b_fp16_out"] = dict(us=round(us, 2), eff_tops=round(HEADS * 2 * (2 * amask.nvec * V * DK) / us / 1e6, 1))
     # the general path (any head dimension, any panel length): SDDMM, softmax and SpMM as three kernels
     mc.set_attention_mode(1)
     O32 = torch.empty((L_ATT, HEADS, DK), dtype=torch.float32, device="cuda").permute(1, 0, 2)
     us = time_graph(torch, stream, [lambda: mc.sparse_attention(q, k, v, amask, att["s_q"], att["s_k"], att["s_v"], att["s_p"],
-                                                                out=O32, workspace=ws)] * max(1, reps // 4))
+                                                                out=O32, workspace=ws)] * reps)
     mc.set_attention_mode(0)
     wide["attention_8b8b_three_kernels"] = dict(us=round(us, 2), eff_tops=round(HEADS * 2 * (2 * amask.nvec * V * DK) / us / 1e6, 1))
     amask.close()

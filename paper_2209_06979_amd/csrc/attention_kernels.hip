@@ -415,8 +415,8 @@ void attention_fused_kernel(AttnArgs a)
             }
             typedef _Float16 v8h __attribute__((ext_vector_type(8)));
             const int64_t off = (Oh - a.O) + (int64_t)row * a.token_stride + col;
-            *reinterpret_cast<v8h *>(reinterpret_cast<_Float16 *>(a.O) + off) =
-                (v8h){hv[0].x, hv[0].y, hv[0].z, hv[0].w, hv[1].x, hv[1].y, hv[1].z, hv[1].w};
+            __builtin_nontemporal_store((v8h){hv[0].x, hv[0].y, hv[0].z, hv[0].w, hv[1].x, hv[1].y, hv[1].z, hv[1].w},
+                                        reinterpret_cast<v8h *>(reinterpret_cast<_Float16 *>(a.O) + off));
         }
         return;
     }

@@ -116,12 +116,12 @@ __device__ __forceinline__ void store_scores(const SddmmArgs &a, int64_t out0, i
             const v4f f = {acc.x * a.out_scale, acc.y * a.out_scale, acc.z * a.out_scale, acc.w * a.out_scale};
             if (a.float_out == 1) {
                 float *o = static_cast<float *>(a.S) + off;
-                if (a.V >= 4) *reinterpret_cast<v4f *>(o) = f;
+                if (a.V >= 4) __builtin_nontemporal_store(f, reinterpret_cast<v4f *>(o));
                 else { o[0] = f.x; o[1] = f.y; }
             } else {
                 _Float16 *o = static_cast<_Float16 *>(a.S) + off;
                 const v4h h = to_half4(f);
-                if (a.V >= 4) *reinterpret_cast<v4h *>(o) = h;
+                if (a.V >= 4) __builtin_nontemporal_store(h, reinterpret_cast<v4h *>(o));
                 else *reinterpret_cast<v2h *>(o) = (v2h){h.x, h.y};
             }
         }

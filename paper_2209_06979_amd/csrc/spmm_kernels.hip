@@ -346,8 +346,8 @@ __global__ __launch_bounds__(64 * WK) void spmm_kernel(SpmmArgs a)
         const int64_t off = (int64_t)batch * a.C_batch_stride + (int64_t)(panel * a.V + row) * a.ldc + gcol;
         if (a.float_out) {
             const v4f f = {s.x * a.out_scale, s.y * a.out_scale, s.z * a.out_scale, s.w * a.out_scale};
-            if (a.float_out == 2) *reinterpret_cast<mcu::v4h *>(static_cast<_Float16 *>(a.C) + off) = mcu::to_half4(f);
-            else *reinterpret_cast<v4f *>(static_cast<float *>(a.C) + off) = f;
+            if (a.float_out == 2) __builtin_nontemporal_store(mcu::to_half4(f), reinterpret_cast<mcu::v4h *>(static_cast<_Float16 *>(a.C) + off));
+            else __builtin_nontemporal_store(f, reinterpret_cast<v4f *>(static_cast<float *>(a.C) + off));
         } else if (split) {
             // several units own this panel: exact, order-independent integer accumulation into rows
             // that were cleared before the launch
