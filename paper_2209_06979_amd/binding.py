@@ -340,7 +340,8 @@ def sparse_softmax(mask: SparseMatrix, S, score_scale: float, inv_s_p: float, ou
     """Integer codes (int8, or int16 for code_bits=16) of the row softmax over the stored
     entries; S: (batch, nvec*V) int32."""
     assert S.is_cuda and S.dtype == torch.int32 and S.is_contiguous()
-    S2 = S.reshape(-1, mask.nvec * mask.V)
+    n = mask.nvec * mask.V
+    S2 = S.reshape(-1, n) if n else S.reshape(S.shape[0] if S.dim() > 1 else 1, 0)
     dt = torch.int16 if code_bits == 16 else torch.int8
     if out is None:
         out = torch.empty(S2.shape, dtype=dt, device=S.device)

@@ -288,8 +288,10 @@ extern "C" int mc_mat_info(const mc_mat *A, int *M, int *K, int *V, int *lhs_bit
 
 extern "C" int mc_mat_set_values_device(mc_mat *A, const void *values_dev, void *stream)
 {
-    if (!A || !values_dev) return MC_EINVAL;
-    if (A->lhs_bits == 0 || !A->d_vals) return MC_EINVAL;
+    if (!A) return MC_EINVAL;
+    if (A->lhs_bits == 0) return MC_EINVAL;        // a pattern-only mask holds no values
+    if (A->nslots == 0) return MC_OK;              // no stored vector: nothing to replace
+    if (!values_dev) return MC_EINVAL;
     RepackArgs r;
     r.panel_ptr = A->d_panel_ptr; r.row_ptr = A->d_row_ptr;
     r.src = static_cast<const uint8_t *>(values_dev); r.src_batch_stride = 0;
@@ -314,7 +316,8 @@ int spmm_impl(const mc_mat *A, const void *B_dev, int N, int ldb, mc_prec prec, 
     if (!valid_prec((int)prec)) return MC_EUNSUPPORTED;
     if (flags & ~(unsigned)(MC_LHS_UNSIGNED | MC_RHS_UNSIGNED)) return MC_EINVAL;
     if (flags && prec != MC_L8R8 && prec != MC_L8R4 && prec != MC_L4R4) return MC_EUNSUPPORTED;
-    if (!A->d_vals || A->lhs_bits != lhs_bits_of(prec)) return MC_EINVAL;
+    // (a matrix without any stored vector has no value buffer and is a valid all-zero operand)
+    if ((!A->d_vals && A->nslots > 0) || A->lhs_bits != lhs_bits_of(prec)) return MC_EINVAL;
     const int rb = rhs_bits_of(prec);
     if (N <= 0 || N % (128 / rb) != 0) return MC_EINVAL; // whole 16-byte pieces of a row
     if (ldb < N || ldc < N) return MC_EINVAL;
@@ -399,7 +402,8 @@ namespace {
 int sddmm_impl(const void *Q_dev, int ldq, const void *Kmat_dev, int ldk, int Kd, const mc_mat *mask, mc_prec prec,
                unsigned flags, int out_mode, float scale, void *S_dev, void *stream)
 {
-    if (!Q_dev || !Kmat_dev || !mask || !S_dev) return MC_EINVAL;
+    if (!Q_dev || !Kmat_dev || !mask) return MC_EINVAL;
+    if (!S_dev && mask->nvec > 0) return MC_EINVAL; // (a mask without any vector has an empty output)
     if (!valid_prec((int)prec)) return MC_EUNSUPPORTED;
     if (flags & ~(unsigned)(MC_LHS_UNSIGNED | MC_RHS_UNSIGNED)) return MC_EINVAL;
     if (flags && prec != MC_L8R8 && prec != MC_L4R4) return MC_EUNSUPPORTED;
@@ -410,6 +414,7 @@ int sddmm_impl(const void *Q_dev, int ldq, const void *Kmat_dev, int ldk, int Kd
     if (((int64_t)ldq * bits / 8) % 16 != 0 || ((int64_t)ldk * bits / 8) % 16 != 0) return MC_EALIGN;
     if (!aligned16(Q_dev) || !aligned16(Kmat_dev) || !aligned16(S_dev)) return MC_EALIGN;
     if (out_mode && !std::isfinite(scale)) return MC_EINVAL;
+    if (mask->nvec == 0) return MC_OK;
 
     SddmmArgs a = {};
     a.float_out = out_mode; a.out_scale = out_mode ? scale : 1.f;
@@ -462,9 +467,11 @@ extern "C" int mc_quantize(const float *x_dev, int64_t n, float scale, int bits,
 extern "C" int mc_sparse_softmax_bits(const mc_mat *mask, int batch, const int32_t *S_dev, float score_scale,
                                       float inv_s_p, int code_bits, void *codes_dev, void *stream)
 {
-    if (!mask || !S_dev || !codes_dev || batch <= 0) return MC_EINVAL;
+    if (!mask || batch <= 0) return MC_EINVAL;
+    if ((!S_dev || !codes_dev) && mask->nvec > 0) return MC_EINVAL;
     if (code_bits != 8 && code_bits != 16) return MC_EUNSUPPORTED;
     if (!std::isfinite(score_scale) || !std::isfinite(inv_s_p)) return MC_EINVAL;
+    if (mask->nvec == 0) return MC_OK; // nothing stored: empty input and output
     SoftmaxArgs a = {};
     a.row_ptr = mask->d_row_ptr; a.S = S_dev; a.codes = codes_dev;
     a.batch_stride = mask->nvec * mask->V;
@@ -478,7 +485,8 @@ extern "C" int mc_sparse_softmax_bits(const mc_mat *mask, int batch, const int32
 extern "C" int mc_sparse_softmax_to_mat(mc_mat *P, const int32_t *S_dev, float score_scale, float inv_s_p, void *stream)
 {
     if (!P || !S_dev) return MC_EINVAL;
-    if (!P->d_vals) return MC_EINVAL;
+    if (P->lhs_bits == 0) return MC_EINVAL;
+    if (P->nslots == 0) return MC_OK;
     if (P->lhs_bits != 8 && P->lhs_bits != 16) return MC_EUNSUPPORTED;
     if (!std::isfinite(score_scale) || !std::isfinite(inv_s_p)) return MC_EINVAL;
     SoftmaxArgs a = {};

@@ -255,3 +255,19 @@ def test_config3_whole_grid_full_size():
         for s in (0.7, 0.9, 0.95):
             for Kd in (64, 128, 256):
                 _check(wl.sddmm_case(4096, 4096, Kd, 8, s, prec, wl.seed_for(3, 3000 + Kd + int(100 * s))))
+
+
+def test_mask_without_any_stored_vector():
+    """A mask that stores nothing is valid: SDDMM and the softmax have empty outputs and succeed."""
+    import torch
+    from paper_2209_06979_amd import binding as mc
+    M, Nc, Kd, V = 32, 64, 64, 8
+    rp, ci = wl.ragged_pattern(M, Nc, V, np.zeros(M // V, np.int64), 95)
+    mask = mc.SparseMatrix(M, Nc, V, rp, ci)
+    Q, Km = torch_dev(wl.uniform_int8((M, Kd), 96)), torch_dev(wl.uniform_int8((Nc, Kd), 97))
+    S = mc.sddmm(Q, Km, mask, "L8R8")
+    assert S.numel() == 0
+    assert mc.sddmm_dequant(Q, Km, mask, "L8R8", 0.5, torch.float16).numel() == 0
+    assert mc.sparse_softmax(mask, S.reshape(1, 0), 1.0, 127.0).numel() == 0
+    torch.cuda.synchronize()
+    mask.close()

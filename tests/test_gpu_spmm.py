@@ -252,3 +252,24 @@ def test_one_and_two_chunks_in_flight_agree(prec):
                     _check(case, variant)
             finally:
                 mc.set_spmm_stages(2)
+
+
+@pytest.mark.parametrize("prec", PRECS)
+@pytest.mark.parametrize("V", [2, 8])
+def test_matrix_without_any_stored_vector(prec, V):
+    """Every panel empty (a valid, all-zero sparse operand with no value buffer at all): C must be
+    written as zeros, and replacing the (zero) values from the device is a no-op."""
+    import torch
+    from paper_2209_06979_amd import binding as mc
+    M, K, N = 8 * V, 64, 64
+    rp, ci = wl.ragged_pattern(M, K, V, np.zeros(M // V, np.int64), 75)
+    vals = np.zeros((0, V // 2 if prec == "L4R4" else V), {"L16R8": np.int16, "L4R4": np.uint8}.get(prec, np.int8))
+    B = wl.uniform_packed_int4((K, N // 2), 76) if prec in ("L8R4", "L4R4") else wl.uniform_int8((K, N), 76)
+    case = dict(M=M, K=K, N=N, V=V, prec=prec, row_ptr=rp, col_idx=ci, values=vals, B=B)
+    _check(case)
+    A = mc.SparseMatrix(M, K, V, rp, ci, vals, mc.LHS_BITS[prec])
+    A.set_values(torch.zeros(0, dtype=torch.int8, device="cuda"))
+    out = mc.spmm_dequant(A, torch.from_numpy(B).cuda(), prec, 0.5, torch.float16)
+    torch.cuda.synchronize()
+    assert out.shape == (M, N) and not out.any()
+    A.close()
