@@ -97,8 +97,10 @@ void choose_variant(const mc_mat *A, int row_bytes, bool r4, int batch, int *bnb
     if (b == 256 && r4) b = 128;
     if (w == 0) {
         const double groups = (double)A->P * ((row_bytes + b - 1) / b) * (batch > 0 ? batch : 1);
+        // about 2048 waves on the chip; 4096 of the lighter ones that gather 64-byte pieces of nibbles
+        const double target = (r4 && b == 64) ? 4096.0 : 2048.0;
         w = 1;
-        while (w < 8 && groups * w * 2 <= 2048.0 && w * 2 <= avg) w *= 2;
+        while (w < 8 && groups * w * 2 <= target && w * 2 <= avg) w *= 2;
     }
     *bnb = b;
     *waves = w;
