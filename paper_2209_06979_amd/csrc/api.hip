@@ -13,7 +13,7 @@ namespace {
 
 int g_variant_bnb = 0, g_variant_waves = 0;
 int g_sddmm_waves = -1;   // -1 automatic, 0 direct-load kernel, 1/2/4/8 waves of the LDS-staged kernel
-int g_attention_mode = 0; // 0 automatic, 1 always the unfused four-kernel pipeline
+int g_attention_mode = 0; // 0 automatic, 1 always the pipeline of separate kernels, 2..4 see mc_set_attention_mode
 int g_spmm_items = 1;     // 1: matrices with very unequal panels run through their work items
 int g_softmax_variant = 0; // 0: automatic; 1: a workgroup per panel; 2: the any-length softmax kernel always
 int g_spmm_stages = 2;    // chunks in flight per wave of the SpMM kernel (1 or 2)
@@ -64,10 +64,6 @@ void free_device(mc_mat *A)
     if (A->d_split_panels) (void)hipFree(A->d_split_panels);
 }
 
-// Tile variant for a problem (measured on MI355X).  Rows are cut into 128-byte tiles, into
-// 256-byte tiles when panels are long, into 64-byte tiles when rows or panels are short;
-// the chunks of a panel are shared by as many waves as it takes to put about 2048 waves
-// on the chip, but never more waves than a panel has chunks.
 // Waves per panel for SDDMM: enough to put about 2048 waves on the chip, at most one per chunk.
 int choose_sddmm_waves(const mc_mat *mask, int batch)
 {
@@ -79,6 +75,10 @@ int choose_sddmm_waves(const mc_mat *mask, int batch)
     return w;
 }
 
+// SpMM tile variant for a problem (from sweeps on MI355X).  Rows are cut into 128-byte tiles, into
+// 256-byte tiles when panels are long, into 64-byte tiles when rows or panels are short; the chunks
+// of a panel are shared by as many waves as it takes to put about 2048 waves on the chip, but
+// never more waves than a panel has chunks.
 void choose_variant(const mc_mat *A, int row_bytes, bool r4, int batch, int *bnb, int *waves)
 {
     int b = g_variant_bnb, w = g_variant_waves;
