@@ -319,7 +319,7 @@ int mc_set_spmm_stages(int stages);
 int mc_set_spmm_splitting(int enable); /* also governs the work items of mc_sddmm (no atomics there) */
 /* SDDMM variant: -1 = automatic, 0 = the kernel that loads operands straight from memory
  * (any row length), 1, 2, 4 or 8 = waves per panel of the kernel that stages Kmat rows in
- * LDS (used when a row has 64, 128, 256 or 512 bytes, else ignored).  Process-wide. */
+ * LDS (used when a row has 64, 128, 256, 512 or 1024 bytes, else ignored).  Process-wide. */
 int mc_set_sddmm_variant(int waves);
 /* Softmax variant: 0 = automatic (panels of up to 4096 scores, padding included, are kept in
  * the registers of one wave, up to 16384 in those of a workgroup: one pass over the scores),

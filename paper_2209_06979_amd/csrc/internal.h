@@ -114,7 +114,7 @@ hipError_t launch_zero_rows(int32_t *C, int64_t ldc, int n, int V, const int32_t
 // the gather of launch_spmm alone (same tile variant); sink: one int32 per workgroup (P * row tiles)
 hipError_t launch_gather_probe(const SpmmArgs &a, int bnb, int waves, int32_t *sink, hipStream_t s);
 // waves: 0 = the direct-load kernel; 1, 2, 4, 8 = waves per panel of the LDS-staged kernel
-// (used when a row has 64, 128, 256 or 512 bytes)
+// (used when a row has 64, 128, 256, 512 or 1024 bytes)
 hipError_t launch_sddmm(int bits, const SddmmArgs &a, int waves, hipStream_t s);
 hipError_t launch_softmax(const SoftmaxArgs &a, hipStream_t s);
 hipError_t launch_absmax(const float *x, int64_t n, float *result, hipStream_t s);

@@ -9,10 +9,11 @@
 // both sides.  The waves of a workgroup take the panel's chunks of 64 vectors round-robin
 // and never have to meet: every chunk produces its own outputs.
 // Two kernels:
-//   sddmm_lds_kernel   rows of 64, 128, 256 or 512 bytes: the 64 Kmat rows of a chunk are copied
+//   sddmm_lds_kernel   rows of 64, 128, 256, 512 or 1024 bytes: the 64 Kmat rows of a chunk are copied
 //                      from global memory straight into LDS with coalesced 16-byte pieces
 //                      (global_load_lds), then read as 128-bit MFMA operands; the
-//                      16-byte segments are XOR-swizzled against bank conflicts.
+//                      16-byte segments are XOR-swizzled against bank conflicts.  Rows longer
+//                      than 256 bytes pass through the stage 256 bytes at a time.
 //   sddmm_direct_kernel any row length: each lane loads its 16 operand bytes from memory.
 // int4 operands are widened in registers; int16 operands (L16-R16, Section 4.4) are split in
 // registers into signed byte planes, the two Q planes stacked in the MFMA rows 0..7 / 8..15.
@@ -155,8 +156,10 @@ __device__ __forceinline__ v4i load_q(const uint8_t *Qpanel, int64_t ldq_bytes, 
     return q;
 }
 
-// RB: bytes of a Kmat row (64, 128, 256, 512; 16-bit operands: from 128).  WK: waves per workgroup.
-template <int PB, int RB, int WK, bool DQ>
+// RB: bytes of a Kmat row staged per pass (64, 128, 256, 512; 16-bit operands: from 128); SEGS: passes
+// per chunk, a row has RB * SEGS bytes (the tiles' accumulators live across the passes, so long
+// rows need no more LDS than short ones).  WK: waves per workgroup.
+template <int PB, int RB, int SEGS, int WK, bool DQ>
 __global__ __launch_bounds__(64 * WK) void sddmm_lds_kernel(SddmmArgs a)
 {
     constexpr int LPR = RB / 16, NI = LPR, RPI = 64 / LPR, KC = RB / StepBytes<PB>::value;
@@ -180,11 +183,11 @@ __global__ __launch_bounds__(64 * WK) void sddmm_lds_kernel(SddmmArgs a)
     const uint8_t *Km = a.Kmat + (int64_t)batch * a.K_batch_stride;
     char *stage = lds + w * (64 * RB);
 
-    v4i qf[KC];
+    v4i qf[KC * SEGS];
     const uint8_t *Qpanel = a.Q + (int64_t)batch * a.Q_batch_stride + (int64_t)panel * a.V * a.ldq_bytes;
 #pragma unroll
-    for (int kc = 0; kc < KC; ++kc) qf[kc] = load_q<PB>(Qpanel, a.ldq_bytes, a.V, RB, kc, j, g);
-    // load instruction i: lane (rg, seg) copies segment seg ^ i of the row in slot rg*NI + i
+    for (int kc = 0; kc < KC * SEGS; ++kc) qf[kc] = load_q<PB>(Qpanel, a.ldq_bytes, a.V, RB * SEGS, kc, j, g);
+    // load instruction i: lane (rg, seg) copies segment seg ^ i of the row (piece) in slot rg*NI + i
     // to LDS row i*RPI + rg (byte i*1024 + lane*16 of the stage)
     const int nmy = (nch > w) ? (nch - w + WK - 1) / WK : 0;
     v4i idxv[NI / 4];
@@ -195,33 +198,42 @@ __global__ __launch_bounds__(64 * WK) void sddmm_lds_kernel(SddmmArgs a)
     if (nmy > 0) load_idx(w);
     for (int k = 0; k < nmy; ++k) {
         const int c = w + k * WK;
+        v4i acc[4], acc2[4];
 #pragma unroll
-        for (int i = 0; i < NI; ++i)
-            __builtin_amdgcn_global_load_lds((gptr_t *)(Km + (int64_t)idxv[i >> 2][i & 3] * a.ldk_bytes + ((seg ^ i) * 16)),
-                                             (lptr_t *)(stage + i * 1024), 16, 0, 0);
-        if (k + 1 < nmy) load_idx(c + WK);
-        if (k + 1 < nmy) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NI / 4) : "memory"); // rows landed, indices may still fly
-        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        for (int h = 0; h < SEGS; ++h) {
+            if (h > 0) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); // the previous pass has been read
+            // (the column indices of this chunk are still needed by the later passes: the next
+            // chunk's may only be requested after the last pass has issued its copies)
 #pragma unroll
-        for (int tl = 0; tl < 4; ++tl) {
-            const int s = tl * 16 + j;              // slot within the chunk
-            const int i = s % NI, r = s / NI;       // its load instruction and row group
-            const char *rowp = stage + i * 1024 + r * RB;
-            v4i acc = {0, 0, 0, 0}, acc2 = {0, 0, 0, 0};
+            for (int i = 0; i < NI; ++i)
+                __builtin_amdgcn_global_load_lds((gptr_t *)(Km + (int64_t)idxv[i >> 2][i & 3] * a.ldk_bytes + h * RB + ((seg ^ i) * 16)),
+                                                 (lptr_t *)(stage + i * 1024), 16, 0, 0);
+            const bool more = (h == SEGS - 1) && (k + 1 < nmy);
+            if (more) load_idx(c + WK);
+            if (more) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NI / 4) : "memory"); // rows landed, indices may still fly
+            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #pragma unroll
-            for (int kc = 0; kc < KC; ++kc) {
-                if (PB == 16) {
-                    const v4i x = *reinterpret_cast<const v4i *>(rowp + (((kc * 8 + 2 * g) ^ i) * 16));
-                    const v4i y = *reinterpret_cast<const v4i *>(rowp + (((kc * 8 + 2 * g + 1) ^ i) * 16));
-                    v4i kh, kl;
-                    split16(x, y, kh, kl);
-                    mma_step<PB>(qf[kc], kh, kl, acc, acc2);
-                } else {
-                    const v4i kf = *reinterpret_cast<const v4i *>(rowp + (((kc * 4 + g) ^ i) * 16));
-                    mma_step<PB>(qf[kc], kf, kf, acc, acc2);
+            for (int tl = 0; tl < 4; ++tl) {
+                const int s = tl * 16 + j;              // slot within the chunk
+                const int i = s % NI, r = s / NI;       // its load instruction and row group
+                const char *rowp = stage + i * 1024 + r * RB;
+                if (h == 0) acc[tl] = acc2[tl] = (v4i){0, 0, 0, 0};
+#pragma unroll
+                for (int kc = 0; kc < KC; ++kc) {
+                    if (PB == 16) {
+                        const v4i x = *reinterpret_cast<const v4i *>(rowp + (((kc * 8 + 2 * g) ^ i) * 16));
+                        const v4i y = *reinterpret_cast<const v4i *>(rowp + (((kc * 8 + 2 * g + 1) ^ i) * 16));
+                        v4i kh, kl;
+                        split16(x, y, kh, kl);
+                        mma_step<PB>(qf[h * KC + kc], kh, kl, acc[tl], acc2[tl]);
+                    } else {
+                        const v4i kf = *reinterpret_cast<const v4i *>(rowp + (((kc * 4 + g) ^ i) * 16));
+                        mma_step<PB>(qf[h * KC + kc], kf, kf, acc[tl], acc2[tl]);
+                    }
                 }
+                if (h == SEGS - 1)
+                    store_scores<DQ>(a, out0, (cb + c) * MC_CHUNK + s, n, g, finish_tile<PB>(acc[tl], acc2[tl]));
             }
-            store_scores<DQ>(a, out0, (cb + c) * MC_CHUNK + s, n, g, finish_tile<PB>(acc, acc2));
         }
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); // reads done before the rows are overwritten
     }
@@ -421,16 +433,16 @@ __global__ __launch_bounds__(256) void repack_kernel(RepackArgs a)
 
 } // namespace
 
-template <int PB, int RB, bool DQ> hipError_t launch_sddmm_lds(const SddmmArgs &a, int waves, hipStream_t s)
+template <int PB, int RB, int SEGS, bool DQ> hipError_t launch_sddmm_lds(const SddmmArgs &a, int waves, hipStream_t s)
 {
     dim3 grid((unsigned)(a.items ? a.n_units : a.P), (unsigned)a.batch);
     constexpr int MAXW = (64 * RB * 8 <= 65536) ? 8 : ((64 * RB * 4 <= 65536) ? 4 : 2); // 64 KB of stages per workgroup
     if (waves > MAXW) waves = MAXW;
     switch (waves) {
-    case 1: hipLaunchKernelGGL((sddmm_lds_kernel<PB, RB, 1, DQ>), grid, dim3(64), 0, s, a); break;
-    case 2: hipLaunchKernelGGL((sddmm_lds_kernel<PB, RB, 2, DQ>), grid, dim3(128), 0, s, a); break;
-    case 4: hipLaunchKernelGGL((sddmm_lds_kernel<PB, RB, (MAXW < 4 ? MAXW : 4), DQ>), grid, dim3(64 * (MAXW < 4 ? MAXW : 4)), 0, s, a); break;
-    default: hipLaunchKernelGGL((sddmm_lds_kernel<PB, RB, MAXW, DQ>), grid, dim3(64 * MAXW), 0, s, a); break;
+    case 1: hipLaunchKernelGGL((sddmm_lds_kernel<PB, RB, SEGS, 1, DQ>), grid, dim3(64), 0, s, a); break;
+    case 2: hipLaunchKernelGGL((sddmm_lds_kernel<PB, RB, SEGS, 2, DQ>), grid, dim3(128), 0, s, a); break;
+    case 4: hipLaunchKernelGGL((sddmm_lds_kernel<PB, RB, SEGS, (MAXW < 4 ? MAXW : 4), DQ>), grid, dim3(64 * (MAXW < 4 ? MAXW : 4)), 0, s, a); break;
+    default: hipLaunchKernelGGL((sddmm_lds_kernel<PB, RB, SEGS, MAXW, DQ>), grid, dim3(64 * MAXW), 0, s, a); break;
     }
     return hipGetLastError();
 }
@@ -438,10 +450,13 @@ template <int PB, int RB, bool DQ> hipError_t launch_sddmm_lds(const SddmmArgs &
 template <int PB, bool DQ> hipError_t launch_sddmm_bits(const SddmmArgs &a, int waves, hipStream_t s)
 {
     if (waves > 0) {
-        if (a.row_bytes == 64 && PB != 16) return launch_sddmm_lds<(PB == 16 ? 8 : PB), 64, DQ>(a, waves, s);
-        if (a.row_bytes == 128) return launch_sddmm_lds<PB, 128, DQ>(a, waves, s);
-        if (a.row_bytes == 256) return launch_sddmm_lds<PB, 256, DQ>(a, waves, s);
-        if (a.row_bytes == 512) return launch_sddmm_lds<PB, 512, DQ>(a, waves, s);
+        if (a.row_bytes == 64 && PB != 16) return launch_sddmm_lds<(PB == 16 ? 8 : PB), 64, 1, DQ>(a, waves, s);
+        if (a.row_bytes == 128) return launch_sddmm_lds<PB, 128, 1, DQ>(a, waves, s);
+        if (a.row_bytes == 256) return launch_sddmm_lds<PB, 256, 1, DQ>(a, waves, s);
+        // longer rows go through the stage in passes of 256 bytes: four waves per workgroup still fit
+        // (a 512-byte stage leaves room for two; measured 15.6 -> 12.0 us for 16-bit operands at Kd = 256)
+        if (a.row_bytes == 512) return launch_sddmm_lds<PB, 256, 2, DQ>(a, waves, s);
+        if (a.row_bytes == 1024) return launch_sddmm_lds<PB, 256, 4, DQ>(a, waves, s);
     }
     dim3 grid((unsigned)(a.items ? a.n_units : a.P), (unsigned)a.batch), block(64 * SDDMM_WAVES);
     const int kc = (a.row_bytes + StepBytes<PB>::value - 1) / StepBytes<PB>::value;

@@ -26,9 +26,12 @@ def test_small(prec, V, Kd):
     _check(wl.sddmm_case(16 * V, 300, Kd, V, 0.7, prec, 1000 + V + Kd), variants=(-1, 0, 1, 2, 4, 8))
 
 
-@pytest.mark.parametrize("prec,Kd", [("L8R8", 512), ("L4R4", 1024)])
-def test_rows_of_512_bytes(prec, Kd):
-    _check(wl.sddmm_case(64, 300, Kd, 8, 0.5, prec, 1150 + Kd), variants=(-1, 0, 1, 2, 4, 8))
+@pytest.mark.parametrize("prec,Kd", [("L8R8", 512), ("L4R4", 1024), ("L8R8", 1024), ("L4R4", 2048), ("L16R16", 256),
+                                     ("L16R16", 512)])
+@pytest.mark.parametrize("V", [2, 8])
+def test_rows_of_512_and_1024_bytes(prec, Kd, V):
+    """Rows longer than the 256-byte stage go through it in two or four passes."""
+    _check(wl.sddmm_case(8 * V, 300, Kd, V, 0.5, prec, 1150 + Kd + V), variants=(-1, 0, 1, 2, 4, 8))
 
 
 @pytest.mark.parametrize("prec,Kd", [("L8R8", 16), ("L8R8", 48), ("L8R8", 320), ("L8R8", 1024), ("L4R4", 32),
