@@ -657,7 +657,9 @@ extern "C" int mc_sparse_attention_out(const void *Q_dev, const void *Km_dev, co
         if (g_attention_mode == 3 && wpp < 2) wpp = 2;
         if (g_attention_mode == 4) wpp = 4;
         // neighbouring heads contiguous inside a token: two heads per workgroup, 128-byte gathers
-        const int hpg = (g_attention_mode == 0 && wpp == 1 && p_bits == 8 && head_stride == 64 && heads % 2 == 0) ? 2 : 1;
+        // (not for 16-bit codes with 4-bit inputs, whose output tile does not fit that kernel's stages)
+        const int hpg = (g_attention_mode == 0 && wpp == 1 && head_stride == 64 && heads % 2 == 0 &&
+                         !(p_bits == 16 && qkv_bits == 4)) ? 2 : 1;
         MC_HIP(launch_attention_fused(f, hpg, wpp, p_bits, qkv_bits, s));
         return MC_OK;
     }

@@ -82,7 +82,7 @@ template <int MAXCH, int HPW, int PB, int QB, int KS>
 __global__ __launch_bounds__(64 * HPW * KS, ((HPW == 1 && PB == 8 && KS == 1) ? 4 : 3))
 void attention_fused_kernel(AttnArgs a)
 {
-    static_assert(PB == 8 || (PB == 16 && HPW == 1), "16-bit codes: one head per workgroup");
+    static_assert(PB == 8 || PB == 16, "8- or 16-bit codes");
     static_assert(QB == 8 || QB == 4, "Q, K, V are 8-bit or packed 4-bit");
     static_assert(KS == 1 || HPW == 1, "chunks are shared between waves only in the one-head-per-workgroup form");
     constexpr int NW = HPW * KS;         // waves per workgroup
@@ -92,7 +92,8 @@ void attention_fused_kernel(AttnArgs a)
     // output tile is staged in the gather stages, which keeps a workgroup below 20 KB of LDS:
     // eight of them, i.e. all 2048 of a 8 x 4096 layer, are resident at once.
     constexpr bool SMALLP = (HPW == 2);
-    constexpr int PLB = SMALLP ? 512 : ((PLANE * (PB / 8) > OTILE) ? PLANE * (PB / 8) : OTILE); // bytes of that area
+    constexpr int PSTRIDE = SMALLP ? 512 : PLANE;                                   // from the high to the low plane of the codes
+    constexpr int PLB = SMALLP ? 512 * (PB / 8) : ((PLANE * (PB / 8) > OTILE) ? PLANE * (PB / 8) : OTILE); // bytes of that area
     constexpr int DK = 64;
     constexpr int DKB = DK * QB / 8; // bytes of one head's row
     constexpr int NPR = MAXCH * 2;   // pairs of score tiles
@@ -104,6 +105,7 @@ void attention_fused_kernel(AttnArgs a)
     constexpr int NIB = (int)0xF0F0F0F0;
     constexpr int STG = 64 * ROWB;   // bytes of one stage
     constexpr int NST = HPW;         // stages: one for a lone wave, two when two waves share the chunks
+    static_assert(!SMALLP || OTILE <= STG, "with two heads per workgroup a wave's output tile is staged in one gather stage");
     __shared__ __attribute__((aligned(16))) char stage_all[NST * STG * KS];  // chunks of gathered rows (KS > 1: one stage per wave)
     __shared__ __attribute__((aligned(16))) char Pl_all[NW * PLB]; // codes, [plane][slot][8 rows], per wave
     __shared__ __attribute__((aligned(8))) char zeros[8];                      // row operand of the MFMA rows that carry no codes
@@ -317,7 +319,7 @@ void attention_fused_kernel(AttnArgs a)
         vbase[h] = i * 1024 + r * ROWB + (((NITW * w) ^ i) * 16) + 8 * (src & 1);
         // lanes 2t and 2t+1 supply the 8-byte pieces that end up in MFMA rows 0..7 and 8..15: the
         // codes and 8 zero bytes (PB 8), or the high and the low plane of the codes (PB 16)
-        if (PB == 16) paddr[h] = Pl + s * 8 + (src & 1) * PLANE;
+        if (PB == 16) paddr[h] = Pl + s * 8 + (src & 1) * PSTRIDE;
         else paddr[h] = (src & 1) ? zeros : Pl + s * 8;
     }
     static_for<MAXCH>([&](auto C) {
@@ -347,7 +349,7 @@ void attention_fused_kernel(AttnArgs a)
                         lo |= (unsigned)(code & 255) << (8 * r);
                     }
                     *reinterpret_cast<unsigned *>(Pl + slot * 8 + 4 * (g & 1)) = hi;
-                    *reinterpret_cast<unsigned *>(Pl + PLANE + slot * 8 + 4 * (g & 1)) = lo;
+                    *reinterpret_cast<unsigned *>(Pl + PSTRIDE + slot * 8 + 4 * (g & 1)) = lo;
                 }
             }
             acquire(Vg, gc);
@@ -450,8 +452,10 @@ template <int PB, int QB> hipError_t launch_pq(const AttnArgs &a, int heads_per_
         hipLaunchKernelGGL((attention_fused_kernel<8, 1, PB, QB, 4>), dim3((unsigned)a.P * (unsigned)a.heads, (unsigned)a.batch), dim3(256), 0, s, a);
     } else if (waves_per_panel == 2) {
         hipLaunchKernelGGL((attention_fused_kernel<8, 1, PB, QB, 2>), dim3((unsigned)a.P * (unsigned)a.heads, (unsigned)a.batch), dim3(128), 0, s, a);
-    } else if (heads_per_group == 2 && PB == 8) {
-        hipLaunchKernelGGL((attention_fused_kernel<8, 2, 8, QB, 1>), dim3((unsigned)a.P * (unsigned)(a.heads / 2), (unsigned)a.batch), dim3(128), 0, s, a);
+    } else if (heads_per_group == 2) {
+        // (16-bit codes with 4-bit Q/K/V: the two-plane output tile does not fit a stage of 32-byte rows)
+        if constexpr (PB == 16 && QB == 4) return hipErrorInvalidValue;
+        else hipLaunchKernelGGL((attention_fused_kernel<8, 2, PB, QB, 1>), dim3((unsigned)a.P * (unsigned)(a.heads / 2), (unsigned)a.batch), dim3(128), 0, s, a);
     } else {
         hipLaunchKernelGGL((attention_fused_kernel<8, 1, PB, QB, 1>), dim3((unsigned)a.P * (unsigned)a.heads, (unsigned)a.batch), dim3(64), 0, s, a);
     }
@@ -464,7 +468,8 @@ hipError_t launch_attention_fused(const AttnArgs &a, int heads_per_group, int wa
                                   hipStream_t s)
 {
     if (a.P == 0 || a.heads == 0 || a.batch == 0) return hipSuccess;
-    if (p_bits == 16) return (qkv_bits == 4) ? launch_pq<16, 4>(a, 1, waves_per_panel, s) : launch_pq<16, 8>(a, 1, waves_per_panel, s);
+    if (p_bits == 16) return (qkv_bits == 4) ? launch_pq<16, 4>(a, heads_per_group, waves_per_panel, s)
+                                             : launch_pq<16, 8>(a, heads_per_group, waves_per_panel, s);
     return (qkv_bits == 4) ? launch_pq<8, 4>(a, heads_per_group, waves_per_panel, s)
                            : launch_pq<8, 8>(a, heads_per_group, waves_per_panel, s);
 }
