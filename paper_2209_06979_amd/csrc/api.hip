@@ -230,6 +230,18 @@ extern "C" int mc_mat_create(int M, int K, int V, int lhs_bits, const int32_t *r
                 delete A;
                 return MC_ENOMEM;
             }
+            // longest first: workgroups start in this order, so the long items do not form the tail
+            {
+                const size_t ni = items.size() / 4;
+                std::vector<size_t> order(ni);
+                for (size_t i = 0; i < ni; ++i) order[i] = i;
+                std::stable_sort(order.begin(), order.end(), [&](size_t x, size_t y) {
+                    return items[4 * x + 2] - items[4 * x + 1] > items[4 * y + 2] - items[4 * y + 1];
+                });
+                std::vector<int32_t> sorted(items.size());
+                for (size_t i = 0; i < ni; ++i) std::copy(items.begin() + 4 * order[i], items.begin() + 4 * order[i] + 4, sorted.begin() + 4 * i);
+                items.swap(sorted);
+            }
             A->n_items = (int)(items.size() / 4);
             A->n_split = (int)split_panels.size();
             A->max_item_chunks = 0;
