@@ -79,7 +79,8 @@ int choose_sddmm_waves(const mc_mat *mask, int batch)
 // 256-byte tiles when panels are long, into 64-byte tiles when rows or panels are short; the chunks
 // of a panel are shared by as many waves as it takes to put about 2048 waves on the chip, but
 // never more waves than a panel has chunks.
-void choose_variant(const mc_mat *A, int row_bytes, bool r4, int batch, int *bnb, int *waves)
+// max_unit: chunks of the longest unit of work (panel or work item) of this launch.
+void choose_variant(const mc_mat *A, int row_bytes, bool r4, int batch, int max_unit, int *bnb, int *waves)
 {
     int b = g_variant_bnb, w = g_variant_waves;
     const double avg = A->P ? (double)(A->nslots / MC_CHUNK) / A->P : 0.0;
@@ -101,6 +102,9 @@ void choose_variant(const mc_mat *A, int row_bytes, bool r4, int batch, int *bnb
         const double target = (r4 && b == 64) ? 4096.0 : 2048.0;
         w = 1;
         while (w < 8 && groups * w * 2 <= target && w * 2 <= avg) w *= 2;
+        // unequal panels (longest unit above twice the average): the longest unit sets the time of the
+        // launch; no wave gets more than 8 chunks of it
+        while (w < 8 && max_unit > 2.0 * avg && max_unit > 8 * w) w *= 2;
     }
     *bnb = b;
     *waves = w;
@@ -208,11 +212,12 @@ extern "C" int mc_mat_create(int M, int K, int V, int lhs_bits, const int32_t *r
     A->n_items = A->n_split = 0;
     A->max_item_chunks = 0;
     // Work items: only when the longest panel is far above the average; a panel is then cut into
-    // pieces of at most `cap` chunks (cap = twice the average, at least 8).
+    // pieces of at most `cap` chunks (cap = three times the average, at least 8: smaller pieces
+    // balance better but cost more in atomics than they gain; measured).
     std::vector<int32_t> items, split_panels;
     {
         const double avg = lay.P ? (double)(lay.nslots / MC_CHUNK) / lay.P : 0.0;
-        const int cap = std::max(8, (int)std::ceil(2.0 * avg));
+        const int cap = std::max(8, (int)std::ceil(3.0 * avg));
         if (A->max_panel_chunks > 2 * cap) {
             try {
                 for (int p = 0; p < lay.P; ++p) {
@@ -348,12 +353,13 @@ int spmm_impl(const mc_mat *A, const void *B_dev, int N, int ldb, mc_prec prec, 
     a.row_bytes = N * rb / 8;
     a.C = C_dev; a.ldc = ldc; a.C_batch_stride = 0;
     a.P = A->P; a.V = A->V; a.batch = 1; a.float_out = out_mode; a.out_scale = out_mode ? scale : 1.f;
-    int bnb, waves;
-    choose_variant(A, a.row_bytes, rb == 4, 1, &bnb, &waves);
     a.stages = (g_spmm_stages == 2 && (int64_t)(A->K - 1) * a.ldb_bytes + a.row_bytes < ((int64_t)1 << 32)) ? 2 : 1;
     a.max_unit_chunks = A->max_panel_chunks;
-    if (A->n_items && g_spmm_items && out_mode == 0) {
-        a.max_unit_chunks = A->max_item_chunks;
+    const bool use_items = A->n_items && g_spmm_items && out_mode == 0;
+    if (use_items) a.max_unit_chunks = A->max_item_chunks;
+    int bnb, waves;
+    choose_variant(A, a.row_bytes, rb == 4, 1, a.max_unit_chunks, &bnb, &waves);
+    if (use_items) {
         // very unequal panels: long ones are shared by several workgroups that add into cleared rows
         // (integer results only: a scaled, rounded result cannot be accumulated piecewise)
         a.items = A->d_items; a.n_units = A->n_items;
@@ -401,7 +407,7 @@ extern "C" int mc_probe_gather(const mc_mat *A, const void *B_dev, int N, int ld
     a.C = nullptr; a.ldc = 0; a.C_batch_stride = 0;
     a.P = A->P; a.V = A->V; a.batch = 1; a.float_out = 0; a.out_scale = 1.f;
     int bnb, waves;
-    choose_variant(A, a.row_bytes, rb == 4, 1, &bnb, &waves);
+    choose_variant(A, a.row_bytes, rb == 4, 1, A->max_panel_chunks, &bnb, &waves);
     MC_HIP(launch_gather_probe(a, bnb, waves, sink_dev, static_cast<hipStream_t>(stream)));
     return MC_OK;
 }
@@ -574,7 +580,7 @@ int attention_pipeline(const uint8_t *Q, const uint8_t *Km, const uint8_t *Vm, i
     m.stages = (g_spmm_stages == 2 && (int64_t)(mask->K - 1) * m.ldb_bytes + m.row_bytes < ((int64_t)1 << 32)) ? 2 : 1;
     m.max_unit_chunks = mask->max_panel_chunks;
     int bnb, waves;
-    choose_variant(mask, m.row_bytes, qkv_bits == 4, heads, &bnb, &waves);
+    choose_variant(mask, m.row_bytes, qkv_bits == 4, heads, mask->max_panel_chunks, &bnb, &waves);
     const mc_prec prec = (p_bits == 16) ? (qkv_bits == 4 ? MC_L16R4 : MC_L16R8) : (qkv_bits == 4 ? MC_L8R4 : MC_L8R8);
     MC_HIP(launch_spmm(prec, m, bnb, waves, s));
     return MC_OK;
