@@ -311,9 +311,9 @@ int mc_set_spmm_variant(int bytes_per_row_tile, int waves);
  * less than 4 GiB and no wave has more than 4 chunks) or 1.  Same results.  MC_EINVAL for other
  * values.  Process-wide. */
 int mc_set_spmm_stages(int stages);
-/* Matrices whose longest panel is far above the average (more than four times the larger of the
- * average and 4 chunks) get, at mc_mat_create, a list of work items that cuts long panels into
- * pieces; mc_spmm then lets several workgroups add their exact int32 partial results into the
+/* Matrices whose longest panel is far above the average (more than six times the average and
+ * more than 16 chunks) get, at mc_mat_create, a list of work items that cuts long panels into
+ * pieces of at most three times the average (at least 8 chunks); mc_spmm then lets several workgroups add their exact int32 partial results into the
  * (first cleared) rows of such panels.  enable = 0 turns this off (one workgroup per panel and
  * row tile, as for regular matrices); the result is the same either way.  Process-wide. */
 int mc_set_spmm_splitting(int enable); /* also governs the work items of mc_sddmm (no atomics there) */
