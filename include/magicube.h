@@ -316,7 +316,10 @@ int mc_set_spmm_stages(int stages);
  * pieces of at most three times the average (at least 8 chunks); mc_spmm then lets several workgroups add their exact int32 partial results into the
  * (first cleared) rows of such panels.  enable = 0 turns this off (one workgroup per panel and
  * row tile, as for regular matrices); the result is the same either way.  Process-wide. */
-int mc_set_spmm_splitting(int enable); /* also governs the work items of mc_sddmm (no atomics there) */
+int mc_set_spmm_splitting(int enable);
+/* (The switch also governs the work items of mc_sddmm.  There every item writes its own outputs,
+ * so a pattern-only mask is cut finer: into pieces of at most the average panel length, at least
+ * 8 chunks, as soon as one panel is longer than that.) */
 /* SDDMM variant: -1 = automatic, 0 = the kernel that loads operands straight from memory
  * (any row length), 1, 2, 4 or 8 = waves per panel of the kernel that stages Kmat rows in
  * LDS (used when a row has 64, 128, 256, 512 or 1024 bytes, else ignored).  Process-wide. */

@@ -213,12 +213,15 @@ extern "C" int mc_mat_create(int M, int K, int V, int lhs_bits, const int32_t *r
     A->max_item_chunks = 0;
     // Work items: only when the longest panel is far above the average; a panel is then cut into
     // pieces of at most `cap` chunks (cap = three times the average, at least 8: smaller pieces
-    // balance better but cost more in atomics than they gain; measured).
+    // balance better but cost the SpMM more in atomics than they gain; measured).
     std::vector<int32_t> items, split_panels;
     {
         const double avg = lay.P ? (double)(lay.nslots / MC_CHUNK) / lay.P : 0.0;
-        const int cap = std::max(8, (int)std::ceil(3.0 * avg));
-        if (A->max_panel_chunks > 2 * cap) {
+        // A pattern-only mask (SDDMM: every item writes its own outputs, nothing to add up) is cut
+        // as soon as a panel exceeds the average rounded up to 8 chunks.
+        const bool mask_only = (lhs_bits == 0);
+        const int cap = std::max(8, (int)std::ceil((mask_only ? 1.0 : 3.0) * avg));
+        if (A->max_panel_chunks > (mask_only ? cap : 2 * cap)) {
             try {
                 for (int p = 0; p < lay.P; ++p) {
                     const int c = (row_ptr[p + 1] - row_ptr[p] + MC_CHUNK - 1) / MC_CHUNK;
@@ -559,6 +562,7 @@ int attention_pipeline(const uint8_t *Q, const uint8_t *Km, const uint8_t *Vm, i
     d.Kmat = Km; d.ldk_bytes = token_stride_bytes; d.K_batch_stride = head_stride_bytes;
     d.row_bytes = row_bytes; d.S = scores; d.S_batch_stride = nnz;
     d.P = mask->P; d.V = 8; d.batch = heads;
+    if (mask->n_items && g_spmm_items) { d.items = mask->d_items; d.n_units = mask->n_items; } // very unequal panels
     MC_HIP(launch_sddmm(qkv_bits, d, choose_sddmm_waves(mask, heads), s));
 
     // the softmax writes its codes in the layout the SpMM reads (Section 4.3 lets the producer
