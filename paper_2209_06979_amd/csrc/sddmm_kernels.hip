@@ -159,11 +159,15 @@ __device__ __forceinline__ v4i load_q(const uint8_t *Qpanel, int64_t ldq_bytes, 
 // RB: bytes of a Kmat row staged per pass (64, 128, 256, 512; 16-bit operands: from 128); SEGS: passes
 // per chunk, a row has RB * SEGS bytes (the tiles' accumulators live across the passes, so long
 // rows need no more LDS than short ones).  WK: waves per workgroup.
-template <int PB, int RB, int SEGS, int WK, bool DQ>
+// U: 8- or 4-bit operands of which one or both are read as non-negative values (Section 4.4.1); the
+// scheme is the one described at sddmm_unsigned_kernel below, here on rows staged in LDS.
+template <int PB, int RB, int SEGS, int WK, bool DQ, bool U>
 __global__ __launch_bounds__(64 * WK) void sddmm_lds_kernel(SddmmArgs a)
 {
     constexpr int LPR = RB / 16, NI = LPR, RPI = 64 / LPR, KC = RB / StepBytes<PB>::value;
     static_assert(KC >= 1, "a row must fill at least one MFMA step");
+    static_assert(!U || PB == 8 || PB == 4, "unsigned operands: 4 and 8 bits");
+    constexpr int QR = (U && PB == 4) ? 2 : 1; // registers per step of the Q operand (unsigned nibbles are widened once, up front)
     __shared__ __attribute__((aligned(16))) char lds[WK * 64 * RB];
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int j = lane & 15, g = lane >> 4;
@@ -183,10 +187,32 @@ __global__ __launch_bounds__(64 * WK) void sddmm_lds_kernel(SddmmArgs a)
     const uint8_t *Km = a.Kmat + (int64_t)batch * a.K_batch_stride;
     char *stage = lds + w * (64 * RB);
 
-    v4i qf[KC * SEGS];
+    v4i qf[KC * SEGS * QR];
     const uint8_t *Qpanel = a.Q + (int64_t)batch * a.Q_batch_stride + (int64_t)panel * a.V * a.ldq_bytes;
+    const v4i ones = {0x01010101, 0x01010101, 0x01010101, 0x01010101};
+    const v4i nib = {NIBBLE_HI, NIBBLE_HI, NIBBLE_HI, NIBBLE_HI};
+    const int qx1 = (U && a.lhs_unsigned) ? (int)0x80808080 : 0, kx1 = (U && a.rhs_unsigned) ? (int)0x80808080 : 0;
+    const v4i qx = {qx1, qx1, qx1, qx1}, kx = {kx1, kx1, kx1, kx1};
+    v4i rq = {0, 0, 0, 0}; // U: rows 4g .. 4g+3: sum over the reduction of the Q operand bytes
 #pragma unroll
-    for (int kc = 0; kc < KC * SEGS; ++kc) qf[kc] = load_q<PB>(Qpanel, a.ldq_bytes, a.V, RB * SEGS, kc, j, g);
+    for (int kc = 0; kc < KC * SEGS; ++kc) {
+        const v4i raw = load_q<PB>(Qpanel, a.ldq_bytes, a.V, RB * SEGS, kc, j, g);
+        if (!U) {
+            qf[kc] = raw;
+        } else {
+            // rows of the panel: the operand bytes; MFMA row 8: all ones (it collects the sums of the Kmat
+            // operand bytes of every output column); other rows: zero
+#pragma unroll
+            for (int t = 0; t < QR; ++t) {
+                v4i q = (PB == 8) ? (raw ^ qx) : (((t == 0 ? (raw << 4) : raw) & nib) ^ qx);
+                if (j >= a.V) q = (j == 8) ? ones : (v4i){0, 0, 0, 0};
+                qf[kc * QR + t] = q;
+                rq = __builtin_amdgcn_mfma_i32_16x16x64_i8(q, ones, rq, 0, 0, 0);
+            }
+        }
+    }
+    const int nred = RB * SEGS * (PB == 4 ? 2 : 1);                      // reduction elements
+    const int cqck = (U && a.lhs_unsigned && a.rhs_unsigned) ? (PB == 4 ? 64 : 16384) * nred : 0;
     // load instruction i: lane (rg, seg) copies segment seg ^ i of the row (piece) in slot rg*NI + i
     // to LDS row i*RPI + rg (byte i*1024 + lane*16 of the stage)
     const int nmy = (nch > w) ? (nch - w + WK - 1) / WK : 0;
@@ -228,11 +254,31 @@ __global__ __launch_bounds__(64 * WK) void sddmm_lds_kernel(SddmmArgs a)
                         mma_step<PB>(qf[h * KC + kc], kh, kl, acc[tl], acc2[tl]);
                     } else {
                         const v4i kf = *reinterpret_cast<const v4i *>(rowp + (((kc * 4 + g) ^ i) * 16));
-                        mma_step<PB>(qf[h * KC + kc], kf, kf, acc[tl], acc2[tl]);
+                        if (!U) {
+                            mma_step<PB>(qf[h * KC + kc], kf, kf, acc[tl], acc2[tl]);
+                        } else if (PB == 8) {
+                            acc[tl] = __builtin_amdgcn_mfma_i32_16x16x64_i8(qf[h * KC + kc], kf ^ kx, acc[tl], 0, 0, 0);
+                        } else {
+                            acc[tl] = __builtin_amdgcn_mfma_i32_16x16x64_i8(qf[(h * KC + kc) * 2], ((kf << 4) & nib) ^ kx, acc[tl], 0, 0, 0);
+                            acc[tl] = __builtin_amdgcn_mfma_i32_16x16x64_i8(qf[(h * KC + kc) * 2 + 1], (kf & nib) ^ kx, acc[tl], 0, 0, 0);
+                        }
                     }
                 }
-                if (h == SEGS - 1)
-                    store_scores<DQ>(a, out0, (cb + c) * MC_CHUNK + s, n, g, finish_tile<PB>(acc[tl], acc2[tl]));
+                if (h == SEGS - 1) {
+                    if (!U) {
+                        store_scores<DQ>(a, out0, (cb + c) * MC_CHUNK + s, n, g, finish_tile<PB>(acc[tl], acc2[tl]));
+                    } else {
+                        // sum (q'+cq)(k'+ck) = sum q'k' + ck sum q' + cq sum k' + cq ck n, with cq = ck = 128 in the
+                        // scale the operand bytes carry (nibbles: 16 x their value)
+                        v4i r = acc[tl];
+                        const int cs = __shfl(r[0], 32 + j); // MFMA row 8 (lane group 2, register 0) of this lane's column
+                        if (a.rhs_unsigned) r += rq << 7;
+                        if (a.lhs_unsigned) r += (v4i){cs << 7, cs << 7, cs << 7, cs << 7};
+                        if (PB == 4) r = r >> 8;
+                        r += (v4i){cqck, cqck, cqck, cqck};
+                        store_scores<DQ>(a, out0, (cb + c) * MC_CHUNK + s, n, g, r);
+                    }
+                }
             }
         }
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); // reads done before the rows are overwritten
@@ -433,52 +479,54 @@ __global__ __launch_bounds__(256) void repack_kernel(RepackArgs a)
 
 } // namespace
 
-template <int PB, int RB, int SEGS, bool DQ> hipError_t launch_sddmm_lds(const SddmmArgs &a, int waves, hipStream_t s)
+template <int PB, int RB, int SEGS, bool DQ, bool U> hipError_t launch_sddmm_lds(const SddmmArgs &a, int waves, hipStream_t s)
 {
     dim3 grid((unsigned)(a.items ? a.n_units : a.P), (unsigned)a.batch);
     constexpr int MAXW = (64 * RB * 8 <= 65536) ? 8 : ((64 * RB * 4 <= 65536) ? 4 : 2); // 64 KB of stages per workgroup
     if (waves > MAXW) waves = MAXW;
     switch (waves) {
-    case 1: hipLaunchKernelGGL((sddmm_lds_kernel<PB, RB, SEGS, 1, DQ>), grid, dim3(64), 0, s, a); break;
-    case 2: hipLaunchKernelGGL((sddmm_lds_kernel<PB, RB, SEGS, 2, DQ>), grid, dim3(128), 0, s, a); break;
-    case 4: hipLaunchKernelGGL((sddmm_lds_kernel<PB, RB, SEGS, (MAXW < 4 ? MAXW : 4), DQ>), grid, dim3(64 * (MAXW < 4 ? MAXW : 4)), 0, s, a); break;
-    default: hipLaunchKernelGGL((sddmm_lds_kernel<PB, RB, SEGS, MAXW, DQ>), grid, dim3(64 * MAXW), 0, s, a); break;
+    case 1: hipLaunchKernelGGL((sddmm_lds_kernel<PB, RB, SEGS, 1, DQ, U>), grid, dim3(64), 0, s, a); break;
+    case 2: hipLaunchKernelGGL((sddmm_lds_kernel<PB, RB, SEGS, 2, DQ, U>), grid, dim3(128), 0, s, a); break;
+    case 4: hipLaunchKernelGGL((sddmm_lds_kernel<PB, RB, SEGS, (MAXW < 4 ? MAXW : 4), DQ, U>), grid, dim3(64 * (MAXW < 4 ? MAXW : 4)), 0, s, a); break;
+    default: hipLaunchKernelGGL((sddmm_lds_kernel<PB, RB, SEGS, MAXW, DQ, U>), grid, dim3(64 * MAXW), 0, s, a); break;
     }
     return hipGetLastError();
 }
 
-template <int PB, bool DQ> hipError_t launch_sddmm_bits(const SddmmArgs &a, int waves, hipStream_t s)
+template <int PB, bool DQ, bool U> hipError_t launch_sddmm_bits(const SddmmArgs &a, int waves, hipStream_t s)
 {
     if (waves > 0) {
-        if (a.row_bytes == 64 && PB != 16) return launch_sddmm_lds<(PB == 16 ? 8 : PB), 64, 1, DQ>(a, waves, s);
-        if (a.row_bytes == 128) return launch_sddmm_lds<PB, 128, 1, DQ>(a, waves, s);
-        if (a.row_bytes == 256) return launch_sddmm_lds<PB, 256, 1, DQ>(a, waves, s);
+        if (a.row_bytes == 64 && PB != 16) return launch_sddmm_lds<(PB == 16 ? 8 : PB), 64, 1, DQ, U>(a, waves, s);
+        if (a.row_bytes == 128) return launch_sddmm_lds<PB, 128, 1, DQ, U>(a, waves, s);
+        if (a.row_bytes == 256) return launch_sddmm_lds<PB, 256, 1, DQ, U>(a, waves, s);
         // longer rows go through the stage in passes of 256 bytes: four waves per workgroup still fit
         // (a 512-byte stage leaves room for two; measured 15.6 -> 12.0 us for 16-bit operands at Kd = 256)
-        if (a.row_bytes == 512) return launch_sddmm_lds<PB, 256, 2, DQ>(a, waves, s);
-        if (a.row_bytes == 1024) return launch_sddmm_lds<PB, 256, 4, DQ>(a, waves, s);
+        if (a.row_bytes == 512) return launch_sddmm_lds<PB, 256, 2, DQ, U>(a, waves, s);
+        if (a.row_bytes == 1024) return launch_sddmm_lds<PB, 256, 4, DQ, U>(a, waves, s);
     }
     dim3 grid((unsigned)(a.items ? a.n_units : a.P), (unsigned)a.batch), block(64 * SDDMM_WAVES);
-    const int kc = (a.row_bytes + StepBytes<PB>::value - 1) / StepBytes<PB>::value;
-    if (kc == 1) hipLaunchKernelGGL((sddmm_direct_kernel<PB, 1, DQ>), grid, block, 0, s, a);
-    else if (kc == 2) hipLaunchKernelGGL((sddmm_direct_kernel<PB, 2, DQ>), grid, block, 0, s, a);
-    else if (kc <= 4) hipLaunchKernelGGL((sddmm_direct_kernel<PB, 4, DQ>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((sddmm_direct_kernel<PB, 0, DQ>), grid, block, 0, s, a);
+    if constexpr (U) {
+        hipLaunchKernelGGL((sddmm_unsigned_kernel<PB, DQ>), grid, block, 0, s, a); // any row length, operands straight from memory
+    } else {
+        const int kc = (a.row_bytes + StepBytes<PB>::value - 1) / StepBytes<PB>::value;
+        if (kc == 1) hipLaunchKernelGGL((sddmm_direct_kernel<PB, 1, DQ>), grid, block, 0, s, a);
+        else if (kc == 2) hipLaunchKernelGGL((sddmm_direct_kernel<PB, 2, DQ>), grid, block, 0, s, a);
+        else if (kc <= 4) hipLaunchKernelGGL((sddmm_direct_kernel<PB, 4, DQ>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((sddmm_direct_kernel<PB, 0, DQ>), grid, block, 0, s, a);
+    }
     return hipGetLastError();
 }
 
 template <bool DQ> hipError_t launch_sddmm_out(int bits, const SddmmArgs &a, int waves, hipStream_t s)
 {
     if (a.lhs_unsigned || a.rhs_unsigned) {
-        dim3 grid((unsigned)(a.items ? a.n_units : a.P), (unsigned)a.batch), block(64 * SDDMM_WAVES);
-        if (bits == 8) hipLaunchKernelGGL((sddmm_unsigned_kernel<8, DQ>), grid, block, 0, s, a);
-        else if (bits == 4) hipLaunchKernelGGL((sddmm_unsigned_kernel<4, DQ>), grid, block, 0, s, a);
-        else return hipErrorInvalidValue;
-        return hipGetLastError();
+        if (bits == 8) return launch_sddmm_bits<8, DQ, true>(a, waves, s);
+        if (bits == 4) return launch_sddmm_bits<4, DQ, true>(a, waves, s);
+        return hipErrorInvalidValue;
     }
-    if (bits == 4) return launch_sddmm_bits<4, DQ>(a, waves, s);
-    if (bits == 16) return launch_sddmm_bits<16, DQ>(a, waves, s);
-    return launch_sddmm_bits<8, DQ>(a, waves, s);
+    if (bits == 4) return launch_sddmm_bits<4, DQ, false>(a, waves, s);
+    if (bits == 16) return launch_sddmm_bits<16, DQ, false>(a, waves, s);
+    return launch_sddmm_bits<8, DQ, false>(a, waves, s);
 }
 
 hipError_t launch_sddmm(int bits, const SddmmArgs &a, int waves, hipStream_t s)

@@ -86,14 +86,16 @@ def test_unsigned_is_refused_for_wide_operands():
 
 
 # -------------------------------------------------------------------- SDDMM ----
-def _sddmm(case):
+def _sddmm(case, variants=(-1,)):
     from gpu_util import run_sddmm_gpu, run_sddmm_oracle
-    print(f"sddmm case M={case['M']} Nc={case['Nc']} Kd={case['Kd']} V={case['V']} {case['prec']} "
-          f"unsigned=({case.get('lhs_unsigned')}, {case.get('rhs_unsigned')})", flush=True)
-    got, want = run_sddmm_gpu(case), run_sddmm_oracle(case)
-    assert got.shape == want.shape
-    bad = np.flatnonzero(got != want)
-    assert bad.size == 0, f"{len(bad)} mismatches, first at {bad[0]}: got {got[bad[0]]} want {want[bad[0]]}"
+    want = run_sddmm_oracle(case)
+    for waves in variants:      # -1: automatic; 0: operands straight from memory; 1..8: waves of the LDS-staged kernel
+        print(f"sddmm case M={case['M']} Nc={case['Nc']} Kd={case['Kd']} V={case['V']} {case['prec']} "
+              f"unsigned=({case.get('lhs_unsigned')}, {case.get('rhs_unsigned')}) waves={waves}", flush=True)
+        got = run_sddmm_gpu(case, waves)
+        assert got.shape == want.shape
+        bad = np.flatnonzero(got != want)
+        assert bad.size == 0, f"{len(bad)} mismatches, first at {bad[0]}: got {got[bad[0]]} want {want[bad[0]]}"
 
 
 @pytest.mark.parametrize("prec", ["L8R8", "L4R4"])
@@ -103,7 +105,17 @@ def _sddmm(case):
 def test_sddmm_unsigned(prec, lu, ru, V, Kd):
     c = wl.sddmm_case(16 * V, 300, Kd, V, 0.7, prec, 5400 + V + Kd)
     c["lhs_unsigned"], c["rhs_unsigned"] = lu, ru
-    _sddmm(c)
+    _sddmm(c, variants=(-1, 0, 1, 2, 4, 8))
+
+
+@pytest.mark.parametrize("prec,Kd", [("L8R8", 128), ("L8R8", 512), ("L8R8", 1024), ("L4R4", 128), ("L4R4", 512), ("L4R4", 1024),
+                                     ("L4R4", 2048)])
+@pytest.mark.parametrize("lu,ru", SIGNS)
+def test_sddmm_unsigned_every_staged_row_length(prec, Kd, lu, ru):
+    """Rows of 64 .. 1024 bytes run on the LDS-staged kernel (512 and 1024 in passes), also with unsigned operands."""
+    c = wl.sddmm_case(64, 300, Kd, 8, 0.5, prec, 5450 + Kd)
+    c["lhs_unsigned"], c["rhs_unsigned"] = lu, ru
+    _sddmm(c, variants=(-1, 0, 2, 8))
 
 
 @pytest.mark.parametrize("prec", ["L8R8", "L4R4"])
