@@ -37,8 +37,8 @@ I8_MFMA_PEAK_TOPS = 5000.0  # MI355X dense int8, published
 # x1.999 and x1.000).  Counters cannot be read from inside the benchmark; refresh these
 # together with profiles/bench_step_counters.txt.
 MEASURED_TRAFFIC_BYTES = {
-    "spmm_L8R8": 14.06e6, "spmm_L8R4": 14.07e6, "spmm_L4R4": 12.23e6, "spmm_L16R8": 17.73e6,
-    "sddmm_L8R8": 17.34e6, "sddmm_L4R4": 12.56e6, "attention": 22.81e6,
+    "spmm_L8R8": 14.06e6, "spmm_L8R4": 14.05e6, "spmm_L4R4": 12.22e6, "spmm_L16R8": 17.73e6,
+    "sddmm_L8R8": 17.36e6, "sddmm_L4R4": 12.55e6, "attention": 22.80e6,
 }
 
 M = K = 4096
