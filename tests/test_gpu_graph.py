@@ -53,3 +53,59 @@ def test_graph_replays_match_eager():
         mc.set_attention_mode(0)
     for h in (A, mask, amask):
         h.close()
+
+
+def test_graph_replays_of_the_other_entry_points():
+    """Captured once, replayed with eager work in between: the SpMM over work items (a row-clearing
+    kernel plus atomics), the dequantising SpMM / SDDMM, the softmax writing a matrix's values, and
+    absmax (its result cell is reset by a kernel, not by a memset) / quantize."""
+    import torch
+    from paper_2209_06979_amd import binding as mc
+    dev = torch.device("cuda:0")
+    V, K, N = 8, 2048, 128
+    counts = np.r_[[2048, 1500, 0, 1], np.full(60, 30)]
+    M = V * len(counts)
+    rp, ci = wl.ragged_pattern(M, K, V, counts, 21)
+    A = mc.SparseMatrix(M, K, V, rp, ci, wl.uniform_int8((len(ci), V), 22), 8)      # long panels: work items
+    B = torch.from_numpy(wl.uniform_int8((K, N), 23)).to(dev)
+    Q = torch.from_numpy(wl.uniform_int8((M, 64), 24)).to(dev)
+    Km = torch.from_numpy(wl.uniform_int8((K, 64), 25)).to(dev)
+    P = mc.SparseMatrix(M, K, V, rp, ci, np.zeros((len(ci), V), np.int8), 8)
+    x = torch.from_numpy(wl.normal_fp32((1 << 16,), 26)).to(dev)
+    C = torch.empty((M, N), dtype=torch.int32, device=dev)
+    Ch = torch.empty((M, N), dtype=torch.float16, device=dev)
+    Sf = torch.empty(A.nvec * V, dtype=torch.float32, device=dev)
+    Si = torch.empty(A.nvec * V, dtype=torch.int32, device=dev)
+    Cp = torch.empty((M, N), dtype=torch.int32, device=dev)
+    mx = torch.empty(1, dtype=torch.float32, device=dev)
+    xq = torch.empty(x.numel(), dtype=torch.int8, device=dev)
+    outs = (C, Ch, Sf, Si, Cp, mx, xq)
+
+    def step():
+        mc.spmm(A, B, "L8R8", out=C)
+        mc.spmm_dequant(A, B, "L8R8", 1e-3, torch.float16, out=Ch)
+        mc.sddmm_dequant(Q, Km, A, "L8R8", 1e-3, torch.float32, out=Sf)
+        mc.sddmm(Q, Km, A, "L8R8", out=Si)
+        mc.sparse_softmax_to_mat(P, Si, 1e-3, 127.0)
+        mc.spmm(P, B, "L8R8", out=Cp)
+        mc.absmax(x, out=mx)
+        mc.quantize(x, 0.03, 8, out=xq)
+
+    step()
+    torch.cuda.synchronize()
+    want = [t.clone() for t in outs]
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=stream):
+            step()
+        for _ in range(4):
+            for t in outs:
+                t.fill_(3)                          # eager work between the replays; C is NOT left cleared
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            for got, ref in zip(outs, want):
+                assert torch.equal(got, ref)
+    A.close()
+    P.close()
