@@ -93,6 +93,10 @@ def main():
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the measurements beside the step: cold-cache and gather-only timings of the headline "
                          "SpMM and the wider precisions that are not part of the step")
+    ap.add_argument("--sweep", action="store_true",
+                    help="instead of the step: time every point of the SpMM grid (V x sparsity x N x precision, 162 points, "
+                         "plus L16-R8) and of the SDDMM grid (Kd x sparsity x precision, 18 points) at 4096 x 4096 and print "
+                         "one JSON object with the table")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 64 MiB device copy, the known-size kernel that scales FETCH_SIZE / WRITE_SIZE")
     args = ap.parse_args()
@@ -108,6 +112,10 @@ def main():
         sys.exit(1)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+
+    if args.sweep:
+        run_sweep(mc, torch)
+        return
 
     prob = build_problem()
     t0 = time.perf_counter()
@@ -274,6 +282,41 @@ def main():
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))
+
+
+def run_sweep(mc, torch):
+    """The grids of the SpMM and SDDMM precision sweeps (Section 5.2 figures' shapes: vector lengths, sparsities,
+    widths of the dense operand, precisions) on seeded synthetic 4096 x 4096 patterns, warm caches, automatic variants."""
+    from paper_2209_06979_amd import workloads as wl
+    stream = torch.cuda.Stream()
+    spmm, sddmm = [], []
+    with torch.cuda.stream(stream):
+        for prec in ("L8R8", "L8R4", "L4R4", "L16R8"):
+            for Vv in (2, 4, 8):
+                for s in (0.5, 0.7, 0.8, 0.9, 0.95, 0.98):
+                    for N in (128, 256, 512):
+                        c = wl.spmm_case(M, K, N, Vv, s, prec, wl.seed_for(2, 1))
+                        A = mc.SparseMatrix(M, K, Vv, c["row_ptr"], c["col_idx"], c["values"], mc.LHS_BITS[prec])
+                        B = torch.from_numpy(c["B"]).cuda()
+                        C = torch.empty((M, N), dtype=torch.int32, device="cuda")
+                        us = time_graph(torch, stream, [lambda: mc.spmm(A, B, prec, out=C)] * 50, rounds=3)
+                        gathered = A.nvec * N * mc.RHS_BITS[prec] / 8
+                        spmm.append(dict(prec=prec, V=Vv, s=s, N=N, us=round(us, 2), eff_tops=round(2 * A.nvec * Vv * N / us / 1e6, 1),
+                                         gather_tbs=round(gathered / us / 1e6, 2)))
+                        A.close()
+        for prec in ("L8R8", "L4R4", "L16R16"):
+            for Kd in (64, 128, 256):
+                for s in (0.7, 0.9, 0.95):
+                    c = wl.sddmm_case(M, K, Kd, V, s, prec, wl.seed_for(3, 1))
+                    m = mc.SparseMatrix(M, K, V, c["row_ptr"], c["col_idx"])
+                    Q, Km = torch.from_numpy(c["Q"]).cuda(), torch.from_numpy(c["Kmat"]).cuda()
+                    S = torch.empty(m.nvec * V, dtype=torch.int32, device="cuda")
+                    us = time_graph(torch, stream, [lambda: mc.sddmm(Q, Km, m, prec, out=S)] * 50, rounds=3)
+                    gathered = m.nvec * Kd * mc.LHS_BITS[prec] / 8
+                    sddmm.append(dict(prec=prec, Kd=Kd, s=s, us=round(us, 2), eff_tops=round(2 * m.nvec * V * Kd / us / 1e6, 1),
+                                      gather_tbs=round(gathered / us / 1e6, 2)))
+                    m.close()
+    print(json.dumps({"sweep": "4096x4096, warm caches, 50 back-to-back launches per point (median of 3)", "spmm": spmm, "sddmm": sddmm}))
 
 
 def time_graph(torch, stream, launches, rounds=5):

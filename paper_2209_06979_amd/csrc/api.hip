@@ -80,7 +80,8 @@ int choose_sddmm_waves(const mc_mat *mask, int batch)
 // of a panel are shared by as many waves as it takes to put about 2048 waves on the chip, but
 // never more waves than a panel has chunks.
 // max_unit: chunks of the longest unit of work (panel or work item) of this launch.
-void choose_variant(const mc_mat *A, int row_bytes, bool r4, int batch, int max_unit, int *bnb, int *waves)
+// lhs_bits: width of the sparse operand's values in this launch (a mask carries none of its own).
+void choose_variant(const mc_mat *A, int lhs_bits, int row_bytes, bool r4, int batch, int max_unit, int *bnb, int *waves)
 {
     int b = g_variant_bnb, w = g_variant_waves;
     const double avg = A->P ? (double)(A->nslots / MC_CHUNK) / A->P : 0.0;
@@ -90,9 +91,10 @@ void choose_variant(const mc_mat *A, int row_bytes, bool r4, int batch, int max_
             b = ((row_bytes >= 256 && avg >= 2.0) || (row_bytes >= 128 && avg >= 16.0)) ? 128 : 64;
         } else {
             b = 128;
-            if (row_bytes < 128 || (row_bytes == 128 && avg < 4.0) || (row_bytes < 512 && avg < 2.0)) b = 64;
-            // wide tiles for long panels; with a two-plane A (16 output rows per tile) only for long rows
-            if (row_bytes >= 256 && avg >= 16.0 && (row_bytes >= 512 || A->lhs_bits == 8)) b = 256;
+            if (row_bytes < 128 || (row_bytes == 128 && avg < 4.0) || (row_bytes < 512 && avg < 2.0) || avg < 3.0) b = 64;
+            // wide tiles for panels of 8 chunks and more; with a two-plane A and V = 8 (16 output rows per
+            // tile) only for long rows
+            if (row_bytes >= 256 && avg >= 8.0 && (lhs_bits == 8 || A->V < 8 || row_bytes >= 512)) b = 256;
         }
     }
     if (b == 256 && r4) b = 128;
@@ -102,6 +104,11 @@ void choose_variant(const mc_mat *A, int row_bytes, bool r4, int batch, int max_
         const double target = (r4 && b == 64) ? 4096.0 : 2048.0;
         w = 1;
         while (w < 8 && groups * w * 2 <= target && w * 2 <= avg) w *= 2;
+        // long panels on the narrower tiles: at most 16 chunks per wave (8 with a two-plane A and V = 8)
+        if (!r4 && b != 256) {
+            const double per_wave = (lhs_bits != 8 && A->V == 8) ? 8.0 : 16.0;
+            while (w < 8 && avg > per_wave * w) w *= 2;
+        }
         // unequal panels (longest unit above twice the average): the longest unit sets the time of the
         // launch; no wave gets more than 8 chunks of it
         while (w < 8 && max_unit > 2.0 * avg && max_unit > 8 * w) w *= 2;
@@ -361,7 +368,7 @@ int spmm_impl(const mc_mat *A, const void *B_dev, int N, int ldb, mc_prec prec, 
     const bool use_items = A->n_items && g_spmm_items && out_mode == 0;
     if (use_items) a.max_unit_chunks = A->max_item_chunks;
     int bnb, waves;
-    choose_variant(A, a.row_bytes, rb == 4, 1, a.max_unit_chunks, &bnb, &waves);
+    choose_variant(A, A->lhs_bits, a.row_bytes, rb == 4, 1, a.max_unit_chunks, &bnb, &waves);
     if (use_items) {
         // very unequal panels: long ones are shared by several workgroups that add into cleared rows
         // (integer results only: a scaled, rounded result cannot be accumulated piecewise)
@@ -410,7 +417,7 @@ extern "C" int mc_probe_gather(const mc_mat *A, const void *B_dev, int N, int ld
     a.C = nullptr; a.ldc = 0; a.C_batch_stride = 0;
     a.P = A->P; a.V = A->V; a.batch = 1; a.float_out = 0; a.out_scale = 1.f;
     int bnb, waves;
-    choose_variant(A, a.row_bytes, rb == 4, 1, A->max_panel_chunks, &bnb, &waves);
+    choose_variant(A, A->lhs_bits, a.row_bytes, rb == 4, 1, A->max_panel_chunks, &bnb, &waves);
     MC_HIP(launch_gather_probe(a, bnb, waves, sink_dev, static_cast<hipStream_t>(stream)));
     return MC_OK;
 }
@@ -584,7 +591,7 @@ int attention_pipeline(const uint8_t *Q, const uint8_t *Km, const uint8_t *Vm, i
     m.stages = (g_spmm_stages == 2 && (int64_t)(mask->K - 1) * m.ldb_bytes + m.row_bytes < ((int64_t)1 << 32)) ? 2 : 1;
     m.max_unit_chunks = mask->max_panel_chunks;
     int bnb, waves;
-    choose_variant(mask, m.row_bytes, qkv_bits == 4, heads, mask->max_panel_chunks, &bnb, &waves);
+    choose_variant(mask, p_bits, m.row_bytes, qkv_bits == 4, heads, mask->max_panel_chunks, &bnb, &waves);
     const mc_prec prec = (p_bits == 16) ? (qkv_bits == 4 ? MC_L16R4 : MC_L16R8) : (qkv_bits == 4 ? MC_L8R4 : MC_L8R8);
     MC_HIP(launch_spmm(prec, m, bnb, waves, s));
     return MC_OK;
