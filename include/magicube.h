@@ -322,7 +322,8 @@ int mc_set_spmm_splitting(int enable);
  * 8 chunks, as soon as one panel is longer than that.) */
 /* SDDMM variant: -1 = automatic, 0 = the kernel that loads operands straight from memory
  * (any row length), 1, 2, 4 or 8 = waves per panel of the kernel that stages Kmat rows in
- * LDS (used when a row has 64, 128, 256, 512 or 1024 bytes, else ignored).  Process-wide. */
+ * LDS (used when a row has 64, 128, 256, 512 or 1024 bytes, or 32 bytes of 4-bit values, else
+ * ignored).  Process-wide. */
 int mc_set_sddmm_variant(int waves);
 /* Softmax variant: 0 = automatic (panels of up to 4096 scores, padding included, are kept in
  * the registers of one wave, up to 16384 in those of a workgroup: one pass over the scores),

@@ -9,7 +9,7 @@
 // both sides.  The waves of a workgroup take the panel's chunks of 64 vectors round-robin
 // and never have to meet: every chunk produces its own outputs.
 // Two kernels:
-//   sddmm_lds_kernel   rows of 64, 128, 256, 512 or 1024 bytes: the 64 Kmat rows of a chunk are copied
+//   sddmm_lds_kernel   rows of 64, 128, 256, 512 or 1024 bytes (sddmm_nib32_kernel: 32 bytes of nibbles): the 64 Kmat rows of a chunk are copied
 //                      from global memory straight into LDS with coalesced 16-byte pieces
 //                      (global_load_lds), then read as 128-bit MFMA operands; the
 //                      16-byte segments are XOR-swizzled against bank conflicts.  Rows longer
@@ -285,6 +285,87 @@ __global__ __launch_bounds__(64 * WK) void sddmm_lds_kernel(SddmmArgs a)
     }
 }
 
+// Rows of 32 bytes of packed nibbles (Kd = 64 with 4-bit operands): one MFMA step per tile.  The 64
+// reduction elements of a row fill the step exactly when lane groups 0 and 1 take the even elements
+// of the two 16-byte pieces (low nibbles, shifted up) and groups 2 and 3 the odd ones (high nibbles),
+// on both operand sides: sums do not depend on the order of their terms.  Both operands carry a
+// factor 16.  Staging as in sddmm_lds_kernel: copy instruction i (of 2) brings the rows of the
+// slots 2*rg + i, rg = lane / 2, into LDS rows i*32 + rg, pieces XOR-swizzled with i.
+template <int WK, bool DQ, bool U>
+__global__ __launch_bounds__(64 * WK) void sddmm_nib32_kernel(SddmmArgs a)
+{
+    constexpr int RB = 32;
+    __shared__ __attribute__((aligned(16))) char lds[WK * 64 * RB];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int j = lane & 15, g = lane >> 4;
+    const int rg = lane >> 1, seg = lane & 1;
+    const int batch = blockIdx.y;
+    int panel = blockIdx.x, cb = 0, ce = -1;
+    if (a.items) {
+        const v4i it = *reinterpret_cast<const v4i *>(a.items + 4 * blockIdx.x);
+        panel = it.x; cb = it.y; ce = it.z;
+    }
+    const int s0 = a.panel_ptr[2 * panel], n = a.panel_ptr[2 * panel + 1] - s0;
+    if (ce < 0) ce = (n + MC_CHUNK - 1) / MC_CHUNK;
+    const int nch = ce - cb;
+    const int32_t *idx = a.slot_idx + s0 + cb * MC_CHUNK;
+    const int64_t out0 = (int64_t)batch * a.S_batch_stride + (int64_t)a.row_ptr[panel] * a.V;
+    const uint8_t *Km = a.Kmat + (int64_t)batch * a.K_batch_stride;
+    char *stage = lds + w * (64 * RB);
+
+    const v4i ones = {0x01010101, 0x01010101, 0x01010101, 0x01010101};
+    const v4i nib = {NIBBLE_HI, NIBBLE_HI, NIBBLE_HI, NIBBLE_HI};
+    const int qx1 = (U && a.lhs_unsigned) ? (int)0x80808080 : 0, kx1 = (U && a.rhs_unsigned) ? (int)0x80808080 : 0;
+    const v4i qx = {qx1, qx1, qx1, qx1}, kx = {kx1, kx1, kx1, kx1};
+    // this lane's operand from 16 raw bytes: even elements (groups 0, 1) or odd elements (groups 2, 3)
+    auto widen = [&](v4i raw) -> v4i { return ((g < 2) ? (raw << 4) : raw) & nib; };
+
+    v4i qop = {0, 0, 0, 0};
+    if (j < a.V) {
+        const uint8_t *qrow = a.Q + (int64_t)batch * a.Q_batch_stride + (int64_t)(panel * a.V + j) * a.ldq_bytes;
+        qop = widen(*reinterpret_cast<const v4i *>(qrow + (g & 1) * 16)) ^ qx;
+    } else if (U && j == 8) {
+        qop = ones; // MFMA row 8 collects the sums of the Kmat operand bytes of every output column
+    }
+    v4i rq = {0, 0, 0, 0}; // U: rows 4g .. 4g+3: sum over the reduction of the Q operand bytes
+    if (U) rq = __builtin_amdgcn_mfma_i32_16x16x64_i8(qop, ones, rq, 0, 0, 0);
+    const int cqck = (U && a.lhs_unsigned && a.rhs_unsigned) ? 64 * 64 : 0; // cq * ck per element, 64 elements
+
+    const int nmy = (nch > w) ? (nch - w + WK - 1) / WK : 0;
+    v2i idxv = {0, 0};
+    if (nmy > 0) idxv = *reinterpret_cast<const v2i *>(idx + w * MC_CHUNK + rg * 2);
+    for (int k = 0; k < nmy; ++k) {
+        const int c = w + k * WK;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+            __builtin_amdgcn_global_load_lds((gptr_t *)(Km + (int64_t)idxv[i] * a.ldk_bytes + ((seg ^ i) * 16)),
+                                             (lptr_t *)(stage + i * 1024), 16, 0, 0);
+        if (k + 1 < nmy) {
+            idxv = *reinterpret_cast<const v2i *>(idx + (c + WK) * MC_CHUNK + rg * 2);
+            asm volatile("s_waitcnt vmcnt(1)" ::: "memory"); // rows landed, indices may still fly
+        } else {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        }
+#pragma unroll
+        for (int tl = 0; tl < 4; ++tl) {
+            const int s = tl * 16 + j;              // slot within the chunk
+            const int i = s & 1, r = s >> 1;        // its copy instruction and row group
+            const v4i kf = *reinterpret_cast<const v4i *>(stage + i * 1024 + r * RB + (((g & 1) ^ i) * 16));
+            v4i acc = {0, 0, 0, 0};
+            acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(qop, widen(kf) ^ kx, acc, 0, 0, 0);
+            if (U) {
+                const int cs = __shfl(acc[0], 32 + j); // MFMA row 8 (lane group 2, register 0) of this lane's column
+                if (a.rhs_unsigned) acc += rq << 7;
+                if (a.lhs_unsigned) acc += (v4i){cs << 7, cs << 7, cs << 7, cs << 7};
+            }
+            acc = acc >> 8; // both operands carried a factor 16
+            if (U) acc += (v4i){cqck, cqck, cqck, cqck};
+            store_scores<DQ>(a, out0, (cb + c) * MC_CHUNK + s, n, g, acc);
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); // reads done before the rows are overwritten
+    }
+}
+
 // KC = number of MFMA steps along a row kept in registers (0: any length, Q re-read).
 template <int PB, int KC, bool DQ>
 __global__ __launch_bounds__(64 * SDDMM_WAVES) void sddmm_direct_kernel(SddmmArgs a)
@@ -496,6 +577,18 @@ template <int PB, int RB, int SEGS, bool DQ, bool U> hipError_t launch_sddmm_lds
 template <int PB, bool DQ, bool U> hipError_t launch_sddmm_bits(const SddmmArgs &a, int waves, hipStream_t s)
 {
     if (waves > 0) {
+        if constexpr (PB == 4) {
+            if (a.row_bytes == 32) { // 64 nibbles: one MFMA step
+                dim3 grid((unsigned)(a.items ? a.n_units : a.P), (unsigned)a.batch);
+                switch (waves) {
+                case 1: hipLaunchKernelGGL((sddmm_nib32_kernel<1, DQ, U>), grid, dim3(64), 0, s, a); break;
+                case 2: hipLaunchKernelGGL((sddmm_nib32_kernel<2, DQ, U>), grid, dim3(128), 0, s, a); break;
+                case 4: hipLaunchKernelGGL((sddmm_nib32_kernel<4, DQ, U>), grid, dim3(256), 0, s, a); break;
+                default: hipLaunchKernelGGL((sddmm_nib32_kernel<8, DQ, U>), grid, dim3(512), 0, s, a); break;
+                }
+                return hipGetLastError();
+            }
+        }
         if (a.row_bytes == 64 && PB != 16) return launch_sddmm_lds<(PB == 16 ? 8 : PB), 64, 1, DQ, U>(a, waves, s);
         if (a.row_bytes == 128) return launch_sddmm_lds<PB, 128, 1, DQ, U>(a, waves, s);
         if (a.row_bytes == 256) return launch_sddmm_lds<PB, 256, 1, DQ, U>(a, waves, s);
