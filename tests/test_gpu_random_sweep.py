@@ -30,15 +30,25 @@ def test_random_spmm(seed):
         case = wl.spmm_case(M, K, N, V, max(s, 0.5) if big else s, prec, int(rng.integers(1 << 30)))
         if prec in ("L8R8", "L8R4", "L4R4") and rng.random() < 0.3:
             case["lhs_unsigned"], case["rhs_unsigned"] = bool(rng.integers(2)), bool(rng.integers(2))
+        splitting = True
+        if rng.random() < 0.3:      # panels of very unequal length, with and without work items
+            cnt = np.clip(np.rint(rng.lognormal(0, float(rng.choice([0.5, 1.0, 2.0])), M // V) * max(1, (1 - s) * K)), 0, K)
+            rp, ci = wl.ragged_pattern(M, K, V, cnt.astype(np.int64), int(rng.integers(1 << 30)))
+            vb = case["values"]
+            vals = rng.integers(-7, 8, size=(len(ci), vb.shape[1])).astype(vb.dtype)
+            case.update(row_ptr=rp, col_idx=ci, values=vals)
+            splitting = bool(rng.integers(2))
         variant = (int(rng.choice([0, 64, 128, 256])), int(rng.choice([0, 1, 2, 4, 8])))
         stages = int(rng.choice([1, 2]))
         print(f"#{n} spmm {prec} M={M} K={K} N={N} V={V} s={s} variant={variant} stages={stages} "
               f"unsigned={case.get('lhs_unsigned', False)},{case.get('rhs_unsigned', False)}", flush=True)
         mc.set_spmm_stages(stages)
+        mc.set_spmm_splitting(splitting)
         try:
             got = run_spmm_gpu(case, variant)
         finally:
             mc.set_spmm_stages(2)
+            mc.set_spmm_splitting(True)
         assert np.array_equal(got, run_spmm_oracle(case))
 
 
@@ -57,10 +67,21 @@ def test_random_sddmm(seed):
         case = wl.sddmm_case(M, Nc, Kd, V, max(s, 0.5) if big else s, prec, int(rng.integers(1 << 30)))
         if prec != "L16R16" and rng.random() < 0.3:
             case["lhs_unsigned"], case["rhs_unsigned"] = bool(rng.integers(2)), bool(rng.integers(2))
+        splitting = True
+        if rng.random() < 0.3:
+            cnt = np.clip(np.rint(rng.lognormal(0, float(rng.choice([0.5, 1.0, 2.0])), M // V) * max(1, (1 - s) * Nc)), 0, Nc)
+            rp, ci = wl.ragged_pattern(M, Nc, V, cnt.astype(np.int64), int(rng.integers(1 << 30)))
+            case.update(row_ptr=rp, col_idx=ci)
+            splitting = bool(rng.integers(2))
         waves = int(rng.choice([-1, 0, 1, 2, 4, 8]))
         print(f"#{n} sddmm {prec} M={M} Nc={Nc} Kd={Kd} V={V} s={s} waves={waves} "
               f"unsigned={case.get('lhs_unsigned', False)},{case.get('rhs_unsigned', False)}", flush=True)
-        assert np.array_equal(run_sddmm_gpu(case, waves), run_sddmm_oracle(case))
+        mc.set_spmm_splitting(splitting)
+        try:
+            got = run_sddmm_gpu(case, waves)
+        finally:
+            mc.set_spmm_splitting(True)
+        assert np.array_equal(got, run_sddmm_oracle(case))
 
 
 @pytest.mark.parametrize("seed", [1, 2])
