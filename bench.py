@@ -262,7 +262,7 @@ def main():
         cpu = cpu_baseline(prob)
 
     out = {
-        "metric": "SpMM/SDDMM effective TOPS (2*nnz*N/s), 90% sparse, V=8, L8-R8; % roofline",
+        "metric": "SpMM/SDDMM effective TOPS (2\u00b7nnz\u00b7N/s), 90% sparse, V=8, L8-R8; % roofline",
         "value": round(value, 2), "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int8", "data": "synthetic",
