@@ -88,4 +88,5 @@ def test_softmax_extreme_scores_and_single_entries():
 def test_softmax_config5_shape(variant):
     c = wl.attention_case(1, 4096, 64, 8, 0.9, wl.seed_for(5, 3))
     counts = np.diff(c["row_ptr"])
-    _check(8, 4096, counts, 7300, 8, variant, batch=2)
+    _check(8, 4096, counts, 7300, 8, variant, batch=2)     # 1024 (panel, score set) units: two waves per panel
+    _check(8, 4096, counts, 7301, 16, variant, batch=3)    # 1536 units: one wave per panel
