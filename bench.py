@@ -478,6 +478,16 @@ def measure_extras(mc, torch, prob, stream, reps, up):
                                                                 out=O32, workspace=ws)] * reps)
     mc.set_attention_mode(0)
     wide["attention_8b8b_three_kernels"] = dict(us=round(us, 2), eff_tops=round(HEADS * 2 * (2 * amask.nvec * V * DK) / us / 1e6, 1))
+    # the same layer with head dimension 128 (rows of 128 bytes): the fused kernel and the three kernels
+    x128, s128 = wl.quantize_inputs_int8(wl.normal_fp32((HEADS, L_ATT, 128), wl.seed_for(5, 9)))
+    q128 = tmaj(x128) # serves as Q, K and V: timing only
+    O128 = torch.empty((L_ATT, HEADS, 128), dtype=torch.float32, device="cuda").permute(1, 0, 2)
+    for name, mode in (("attention_8b8b_dk128", 0), ("attention_8b8b_dk128_three_kernels", 1)):
+        mc.set_attention_mode(mode)
+        us = time_graph(torch, stream, [lambda: mc.sparse_attention(q128, q128, q128, amask, s128, s128, s128, att["s_p"],
+                                                                    out=O128, workspace=ws)] * reps)
+        mc.set_attention_mode(0)
+        wide[name] = dict(us=round(us, 2), eff_tops=round(HEADS * 2 * (2 * amask.nvec * V * 128) / us / 1e6, 1))
     amask.close()
     cc = prob["spmm_L8R8"]
     A = mc.SparseMatrix(M, K, V, cc["row_ptr"], cc["col_idx"], cc["values"], 8)

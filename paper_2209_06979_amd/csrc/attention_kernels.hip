@@ -5,8 +5,9 @@
 //
 //   phase K  per chunk of 64 mask vectors: the Kmat rows named by the column indices are
 //            copied from global memory straight into LDS (global_load_lds, no registers in
-//            between); one v_mfma_i32_16x16x64_i8 per 16 vectors gives the scores (head dim
-//            64 = one MFMA; both operands are contiguous along the reduction, Section 4.3).
+//            between); one v_mfma_i32_16x16x64_i8 per 16 vectors and 64 elements of the head
+//            dimension gives the scores (head dim 64 = one MFMA, 128 = two; both operands are
+//            contiguous along the reduction, Section 4.3).
 //            The 8 Q rows sit in MFMA rows 0..7 for even tiles and in rows 8..15 for odd
 //            tiles, so two tiles share one accumulator and all 64 lanes carry real scores.
 //   softmax  fp32, base 2, over the panel's stored entries: in-lane over the tiles, DPP
@@ -16,19 +17,20 @@
 //   phase V  SpMM (Section 4.2) per chunk: V rows are copied into the same LDS stages;
 //            ds_read_b64_tr_b8 delivers both MFMA operands in place: the codes transposed
 //            to [row][16 slots] and the V rows transposed to [column][16 slots].
-//   output   the 8 x 64 tile goes through LDS once to be stored as fp32 with 16-byte stores.
+//   output   the 8 x dk tile goes through LDS once to be stored as fp32 with 16-byte stores.
 //
 // Two variants (HPW = heads per workgroup):
-//   HPW 1  any layout: the wave gathers the 64-byte rows of its own head into its one LDS
-//          stage (8 KB of LDS per wave, so 16 waves fit a CU).
+//   HPW 1  any layout: the wave gathers the rows of its own head (64 bytes; 128 bytes for head
+//          dimension 128, 8-bit inputs only) into its one LDS stage (8 KB of LDS per wave and
+//          16 waves per CU for 64-byte rows).
 //   HPW 2  token-major layout (the heads of a token are contiguous, as a QKV projection
 //          writes them): two waves own two neighbouring heads and gather their 128 bytes of
 //          a token with ONE request.  The L2 serves a 128-byte line at the cost of a 64-byte
 //          half, so this halves the number of gather requests, which is what bounds the
 //          kernel.  Each wave copies half of a chunk's rows; one s_barrier per chunk.
-// LDS rows are 64*HPW bytes; slot s of a chunk lives in row (s % NIT) * (64/NIT) + s / NIT
-// (NIT = 4*HPW copy instructions per chunk, so that a lane's 4 column indices are
-// consecutive) and its 16-byte segments are XOR-swizzled with s % NIT so that rows read
+// LDS rows are as long as a gathered row (ROWB = 64*HPW bytes, 128 for head dimension 128); slot s
+// of a chunk lives in row (s % NIT) * (64/NIT) + s / NIT (NIT = ROWB/16 copy instructions per
+// chunk, so that the column indices a lane needs are consecutive) and its 16-byte segments are XOR-swizzled with s % NIT so that rows read
 // together fall into different banks.
 #include "internal.h"
 #include "lds_async.h"
@@ -78,29 +80,32 @@ __device__ __forceinline__ float row16_sum(float v)
 // KS: waves that share one (panel, head) when a panel is longer than MAXCH chunks (HPW 1 only): wave
 // ks takes chunks ks, ks + KS, ...; the waves exchange their row maxima and row sums through LDS
 // and add up their partial output tiles at the end (three workgroup barriers in total).
-template <int MAXCH, int HPW, int PB, int QB, int KS>
-__global__ __launch_bounds__(64 * HPW * KS, ((HPW == 1 && PB == 8 && KS == 1) ? 4 : 3))
+// DK: head dimension, 64 or 128 (128: 8-bit inputs, one head per workgroup).
+template <int MAXCH, int HPW, int PB, int QB, int KS, int DK>
+__global__ __launch_bounds__(64 * HPW * KS, ((HPW == 1 && PB == 8 && KS == 1 && DK == 64) ? 4 : 3))
 void attention_fused_kernel(AttnArgs a)
 {
     static_assert(PB == 8 || PB == 16, "8- or 16-bit codes");
     static_assert(QB == 8 || QB == 4, "Q, K, V are 8-bit or packed 4-bit");
     static_assert(KS == 1 || HPW == 1, "chunks are shared between waves only in the one-head-per-workgroup form");
+    static_assert(DK == 64 || (DK == 128 && QB == 8 && HPW == 1), "head dimension 128: 8-bit inputs, one head per workgroup");
     constexpr int NW = HPW * KS;         // waves per workgroup
     constexpr int PLANE = MAXCH * 512;   // bytes of one plane of codes, [slot][8 rows]
-    constexpr int OTILE = (PB == 16 ? 16 : 8) * (64 + 4) * 4;                       // a wave's output tile, staged in the same area
+    constexpr int OTILE = (PB == 16 ? 16 : 8) * (DK + 4) * 4;                       // a wave's output tile, staged in the same area
     // HPW 2: the code area holds ONE chunk (codes are written right before they are read) and the
     // output tile is staged in the gather stages, which keeps a workgroup below 20 KB of LDS:
     // eight of them, i.e. all 2048 of a 8 x 4096 layer, are resident at once.
     constexpr bool SMALLP = (HPW == 2);
     constexpr int PSTRIDE = SMALLP ? 512 : PLANE;                                   // from the high to the low plane of the codes
     constexpr int PLB = SMALLP ? 512 * (PB / 8) : ((PLANE * (PB / 8) > OTILE) ? PLANE * (PB / 8) : OTILE); // bytes of that area
-    constexpr int DK = 64;
     constexpr int DKB = DK * QB / 8; // bytes of one head's row
+    constexpr int KK = DK / 64;      // MFMA steps along the head dimension
+    constexpr int NO = DK / 16;      // column tiles of the output
     constexpr int NPR = MAXCH * 2;   // pairs of score tiles
     constexpr int ROWB = DKB * HPW;  // bytes of a gathered row
     constexpr int LPR = ROWB / 16;   // lanes per row
     constexpr int NIT = LPR;         // copy instructions per chunk
-    constexpr int NITW = DKB / 16;   // ... of which each wave issues this many (4, or 2 for nibbles)
+    constexpr int NITW = DKB / 16;   // ... of which each wave issues this many (4; 2 for nibbles; 8 for head dimension 128)
     constexpr int SWZ = LPR - 1;
     constexpr int NIB = (int)0xF0F0F0F0;
     constexpr int STG = 64 * ROWB;   // bytes of one stage
@@ -135,17 +140,19 @@ void attention_fused_kernel(AttnArgs a)
     if (PB == 8 && lane < 2) reinterpret_cast<int *>(zeros)[lane] = 0; // every wave writes the same zeros: no race that matters
 
     // Q rows twice: in MFMA rows 0..7 (q_lo) and in rows 8..15 (q_hi)
-    v4i q_lo = {0, 0, 0, 0}, q_hi = {0, 0, 0, 0};
-    {
+    v4i q_lo[KK], q_hi[KK];
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
         const uint8_t *qrow = a.Q + boff + (int64_t)head * a.in_head_stride + (int64_t)(panel * 8 + (j & 7)) * a.in_token_stride;
         v4i qv;
         if (QB == 8) {
-            qv = *reinterpret_cast<const v4i *>(qrow + g * 16);
+            qv = *reinterpret_cast<const v4i *>(qrow + kk * 64 + g * 16);
         } else {
             const v4i raw = *reinterpret_cast<const v4i *>(qrow + (g & 1) * 16);
             qv = (g < 2) ? ((raw << 4) & NIB) : (raw & NIB);
         }
-        if (j < 8) q_lo = qv; else q_hi = qv;
+        q_lo[kk] = (j < 8) ? qv : (v4i){0, 0, 0, 0};
+        q_hi[kk] = (j < 8) ? (v4i){0, 0, 0, 0} : qv;
     }
     // Copy instruction i of a chunk: lane (rg, seg) fetches segment seg ^ i of the row in slot
     // rg*NIT + i; it lands in LDS row i*(64/NIT) + rg.  Wave w issues instructions NITW*w .. +NITW-1,
@@ -197,9 +204,12 @@ void attention_fused_kernel(AttnArgs a)
     // are kept out of the row sum (and so out of the codes) below.
     // K operand of tile tl: slot s = tl*16 + j sits in LDS row (s % NIT)*(64/NIT) + s/NIT,
     // i.e. byte (j % NIT)*1024 + (j / NIT)*ROWB + tl*256; segment (NITW*w + piece) ^ (j % NIT), where
-    // lane group g reads piece g of its head's row (8 bit) or piece g % 2 (4 bit: even elements of
-    // the piece for g < 2, odd elements for g >= 2, as on the Q side)
-    const char *kaddr = stage + (j % NIT) * 1024 + (j / NIT) * ROWB + (((NITW * w + (QB == 8 ? g : (g & 1))) ^ (j % NIT)) * 16);
+    // lane group g reads piece 4*kk + g of its head's row in MFMA step kk (8 bit) or piece g % 2
+    // (4 bit: even elements of the piece for g < 2, odd elements for g >= 2, as on the Q side)
+    const char *kaddr[KK];
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk)
+        kaddr[kk] = stage + (j % NIT) * 1024 + (j / NIT) * ROWB + (((NITW * w + 4 * kk + (QB == 8 ? g : (g & 1))) ^ (j % NIT)) * 16);
     auto kop = [&](v4i raw) -> v4i {
         if (QB == 8) return raw;
         return (g < 2) ? ((raw << 4) & NIB) : (raw & NIB);
@@ -217,14 +227,21 @@ void attention_fused_kernel(AttnArgs a)
         const int gc = ks + c * KS;
         if (c < nloc) {
             acquire(Kg, gc);
-            const v4i kA0 = *reinterpret_cast<const v4i *>(kaddr + ST), kB0 = *reinterpret_cast<const v4i *>(kaddr + ST + 256);
-            const v4i kA1 = *reinterpret_cast<const v4i *>(kaddr + ST + 512), kB1 = *reinterpret_cast<const v4i *>(kaddr + ST + 768);
+            v4i kt[KK][4]; // tiles 0..3 of the chunk
+#pragma unroll
+            for (int kk = 0; kk < KK; ++kk)
+#pragma unroll
+                for (int tl = 0; tl < 4; ++tl) kt[kk][tl] = *reinterpret_cast<const v4i *>(kaddr[kk] + ST + tl * 256);
             release(Kg, gc);
-            const v4i zero = {0, 0, 0, 0};
-            sc[2 * c] = __builtin_amdgcn_mfma_i32_16x16x64_i8(q_lo, kop(kA0), zero, 0, 0, 0);
-            sc[2 * c] = __builtin_amdgcn_mfma_i32_16x16x64_i8(q_hi, kop(kB0), sc[2 * c], 0, 0, 0);
-            sc[2 * c + 1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(q_lo, kop(kA1), zero, 0, 0, 0);
-            sc[2 * c + 1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(q_hi, kop(kB1), sc[2 * c + 1], 0, 0, 0);
+            sc[2 * c] = (v4i){0, 0, 0, 0};
+            sc[2 * c + 1] = (v4i){0, 0, 0, 0};
+#pragma unroll
+            for (int kk = 0; kk < KK; ++kk) {
+                sc[2 * c] = __builtin_amdgcn_mfma_i32_16x16x64_i8(q_lo[kk], kop(kt[kk][0]), sc[2 * c], 0, 0, 0);
+                sc[2 * c] = __builtin_amdgcn_mfma_i32_16x16x64_i8(q_hi[kk], kop(kt[kk][1]), sc[2 * c], 0, 0, 0);
+                sc[2 * c + 1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(q_lo[kk], kop(kt[kk][2]), sc[2 * c + 1], 0, 0, 0);
+                sc[2 * c + 1] = __builtin_amdgcn_mfma_i32_16x16x64_i8(q_hi[kk], kop(kt[kk][3]), sc[2 * c + 1], 0, 0, 0);
+            }
             if (QB == 4) { // both operands carried a factor 16
                 sc[2 * c] = sc[2 * c] >> 8;
                 sc[2 * c + 1] = sc[2 * c + 1] >> 8;
@@ -306,9 +323,9 @@ void attention_fused_kernel(AttnArgs a)
 #pragma unroll
     for (int r = 0; r < 4; ++r) rinv[r] = a.inv_s_p / srow[r];
     // ---- phase V: O = codes * V ------------------------------------------------------------------
-    v4i o[4];
+    v4i o[NO];
 #pragma unroll
-    for (int ct = 0; ct < 4; ++ct) o[ct] = (v4i){0, 0, 0, 0};
+    for (int ct = 0; ct < NO; ++ct) o[ct] = (v4i){0, 0, 0, 0};
     const int src = lane & 15, ii = src >> 1;
     int vbase[2];
     const char *paddr[2];
@@ -378,7 +395,7 @@ void attention_fused_kernel(AttnArgs a)
         }
     });
 
-    // ---- output: 8 x 64 tile through this wave's code area, scaled, 16-byte stores -------------
+    // ---- output: 8 x DK tile through this wave's code area, scaled, 16-byte stores -------------
     vm_wait<0>();
     if (SMALLP) {
         lgkm_wait();
@@ -387,7 +404,7 @@ void attention_fused_kernel(AttnArgs a)
     int *Ol = reinterpret_cast<int *>(SMALLP ? stage_all + w * STG : Pl);
     if (g < 2 || PB == 16) {
 #pragma unroll
-        for (int ct = 0; ct < 4; ++ct)
+        for (int ct = 0; ct < NO; ++ct)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 // the nibble products carry a factor 16; each plane's sum is shifted on its own
@@ -398,10 +415,12 @@ void attention_fused_kernel(AttnArgs a)
     lgkm_wait();
     if (KS > 1) __syncthreads(); else __builtin_amdgcn_wave_barrier();
     if (a.out_f16) {
-        // fp16: 8 rows x 8 pieces of 8 columns, one 16-byte store per thread
-        const int piece = (KS > 1) ? (int)threadIdx.x : lane;
-        if (piece < 64) {
-            const int row = piece >> 3, col = (piece & 7) * 8;
+        // fp16: 8 rows x DK/8 pieces of 8 columns, one 16-byte store each
+#pragma unroll
+        for (int h = 0; h < (DK + 64 * KS - 1) / (64 * KS); ++h) {
+            const int piece = ((KS > 1) ? (int)threadIdx.x : lane) + h * 64 * KS;
+            if (piece >= DK) continue;
+            const int row = piece / (DK / 8), col = (piece % (DK / 8)) * 8;
             v4h hv[2];
 #pragma unroll
             for (int q = 0; q < 2; ++q) {
@@ -422,12 +441,12 @@ void attention_fused_kernel(AttnArgs a)
         }
         return;
     }
-    // 8 rows x 16 pieces of 4 columns; with KS waves the first 128 threads add up the partial tiles
+    // 8 rows x DK/4 pieces of 4 columns; with KS waves all threads share the adding up of the partial tiles
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-        const int piece = (KS > 1) ? (int)threadIdx.x + h * 64 * KS : h * 64 + lane;
-        if (piece >= 128) continue;
-        const int row = piece >> 4, col = (piece & 15) * 4;
+    for (int h = 0; h < (2 * DK + 64 * KS - 1) / (64 * KS); ++h) {
+        const int piece = ((KS > 1) ? (int)threadIdx.x : lane) + h * 64 * KS;
+        if (piece >= 2 * DK) continue;
+        const int row = piece / (DK / 4), col = (piece % (DK / 4)) * 4;
         v4i sres = {0, 0, 0, 0}, slo = {0, 0, 0, 0};
 #pragma unroll
         for (int k = 0; k < KS; ++k) {
@@ -446,30 +465,36 @@ void attention_fused_kernel(AttnArgs a)
 
 int attention_fused_max_vectors() { return 4 * 8 * 64; }
 
-template <int PB, int QB> hipError_t launch_pq(const AttnArgs &a, int heads_per_group, int waves_per_panel, hipStream_t s)
+template <int PB, int QB, int DK> hipError_t launch_pq(const AttnArgs &a, int heads_per_group, int waves_per_panel, hipStream_t s)
 {
     if (waves_per_panel == 4) {
-        hipLaunchKernelGGL((attention_fused_kernel<8, 1, PB, QB, 4>), dim3((unsigned)a.P * (unsigned)a.heads, (unsigned)a.batch), dim3(256), 0, s, a);
+        hipLaunchKernelGGL((attention_fused_kernel<8, 1, PB, QB, 4, DK>), dim3((unsigned)a.P * (unsigned)a.heads, (unsigned)a.batch), dim3(256), 0, s, a);
     } else if (waves_per_panel == 2) {
-        hipLaunchKernelGGL((attention_fused_kernel<8, 1, PB, QB, 2>), dim3((unsigned)a.P * (unsigned)a.heads, (unsigned)a.batch), dim3(128), 0, s, a);
+        hipLaunchKernelGGL((attention_fused_kernel<8, 1, PB, QB, 2, DK>), dim3((unsigned)a.P * (unsigned)a.heads, (unsigned)a.batch), dim3(128), 0, s, a);
     } else if (heads_per_group == 2) {
         // (16-bit codes with 4-bit Q/K/V: the two-plane output tile does not fit a stage of 32-byte rows)
-        if constexpr (PB == 16 && QB == 4) return hipErrorInvalidValue;
-        else hipLaunchKernelGGL((attention_fused_kernel<8, 2, PB, QB, 1>), dim3((unsigned)a.P * (unsigned)(a.heads / 2), (unsigned)a.batch), dim3(128), 0, s, a);
+        if constexpr ((PB == 16 && QB == 4) || DK != 64) return hipErrorInvalidValue;
+        else hipLaunchKernelGGL((attention_fused_kernel<8, 2, PB, QB, 1, DK>), dim3((unsigned)a.P * (unsigned)(a.heads / 2), (unsigned)a.batch), dim3(128), 0, s, a);
     } else {
-        hipLaunchKernelGGL((attention_fused_kernel<8, 1, PB, QB, 1>), dim3((unsigned)a.P * (unsigned)a.heads, (unsigned)a.batch), dim3(64), 0, s, a);
+        hipLaunchKernelGGL((attention_fused_kernel<8, 1, PB, QB, 1, DK>), dim3((unsigned)a.P * (unsigned)a.heads, (unsigned)a.batch), dim3(64), 0, s, a);
     }
     return hipGetLastError();
 }
 
 // waves_per_panel: 1, 2 or 4 waves share the chunks of one (panel, head); a wave holds at most 8 chunks
 // of scores in registers, so a panel may have up to 512 * waves_per_panel vectors.
+// dk: 64, or 128 with 8-bit inputs and heads_per_group 1
 hipError_t launch_attention_fused(const AttnArgs &a, int heads_per_group, int waves_per_panel, int p_bits, int qkv_bits,
-                                  hipStream_t s)
+                                  int dk, hipStream_t s)
 {
     if (a.P == 0 || a.heads == 0 || a.batch == 0) return hipSuccess;
-    if (p_bits == 16) return (qkv_bits == 4) ? launch_pq<16, 4>(a, heads_per_group, waves_per_panel, s)
-                                             : launch_pq<16, 8>(a, heads_per_group, waves_per_panel, s);
-    return (qkv_bits == 4) ? launch_pq<8, 4>(a, heads_per_group, waves_per_panel, s)
-                           : launch_pq<8, 8>(a, heads_per_group, waves_per_panel, s);
+    if (dk == 128) {
+        if (qkv_bits != 8 || heads_per_group != 1) return hipErrorInvalidValue;
+        return (p_bits == 16) ? launch_pq<16, 8, 128>(a, 1, waves_per_panel, s) : launch_pq<8, 8, 128>(a, 1, waves_per_panel, s);
+    }
+    if (dk != 64) return hipErrorInvalidValue;
+    if (p_bits == 16) return (qkv_bits == 4) ? launch_pq<16, 4, 64>(a, heads_per_group, waves_per_panel, s)
+                                             : launch_pq<16, 8, 64>(a, heads_per_group, waves_per_panel, s);
+    return (qkv_bits == 4) ? launch_pq<8, 4, 64>(a, heads_per_group, waves_per_panel, s)
+                           : launch_pq<8, 8, 64>(a, heads_per_group, waves_per_panel, s);
 }

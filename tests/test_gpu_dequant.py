@@ -207,6 +207,14 @@ def test_attention_fp16_output_variants(p_bits, qkv_bits):
     _attention_f16(2, 2048, 64, 0.6, 6612, p_bits, qkv_bits)                       # two waves per (panel, head)
 
 
+@pytest.mark.parametrize("p_bits", [8, 16])
+def test_attention_fp16_output_head_dimension_128(p_bits):
+    _attention_f16(2, 1024, 128, 0.6, 6630, p_bits, 8)
+    _attention_f16(2, 1024, 128, 0.6, 6631, p_bits, 8, token_major=True)
+    _attention_f16(2, 2048, 128, 0.6, 6632, p_bits, 8)                             # two waves per (panel, head)
+    _attention_f16(1, 2048, 128, 0.3, 6633, p_bits, 8, token_major=True)           # four waves
+
+
 def test_attention_fp16_output_batched_and_config5():
     _attention_f16(4, 512, 64, 0.8, 6620, batch=3, token_major=True)
     _attention_f16(4, 512, 64, 0.8, 6621, batch=2, mode=1)

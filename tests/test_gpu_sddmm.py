@@ -182,6 +182,22 @@ def test_attention_long_panels(token_major):
 
 
 @pytest.mark.parametrize("token_major", [False, True])
+@pytest.mark.parametrize("mode", [0, 1, 3, 4])
+def test_attention_head_dimension_128(mode, token_major):
+    """Rows of 128 bytes: two MFMA steps per score tile and eight column tiles of output in the fused kernel."""
+    _attention_check(2, 256, 128, 0.75, 1230, mode, token_major)   # one chunk per panel
+    _attention_check(3, 1024, 128, 0.6, 1231, mode, token_major)   # 7 chunks, ragged tail
+    _attention_check(2, 2048, 128, 0.75, 1232, mode, token_major)  # 8 chunks
+
+
+@pytest.mark.parametrize("token_major", [False, True])
+def test_attention_head_dimension_128_long_panels(token_major):
+    _attention_check(2, 2048, 128, 0.6, 1233, 0, token_major)      # 13 chunks: two waves per (panel, head)
+    _attention_check(1, 2048, 128, 0.0, 1234, 0, token_major)      # 32 chunks: four waves
+    _attention_check(4, 4096, 128, 0.9, 1235, 0, token_major)      # the bench layer's pattern at head dimension 128
+
+
+@pytest.mark.parametrize("token_major", [False, True])
 @pytest.mark.parametrize("mode", [0, 1])
 def test_attention_config5_full(mode, token_major):
     """BASELINE config 5: 8 heads, L=4096, dk=64, 90 % vector sparsity, diagonal kept."""

@@ -216,7 +216,16 @@ def test_attention_variants_small(p_bits, qkv_bits, token_major, mode):
     _attention_variant_check(3, 512, 32, 0.9, 4001, p_bits, qkv_bits, token_major, mode)    # dk != 64: pipeline
     _attention_variant_check(2, 1024, 64, 0.6, 4002, p_bits, qkv_bits, token_major, mode)   # 7 chunks, ragged tail
     _attention_variant_check(2, 2048, 64, 0.75, 4004, p_bits, qkv_bits, token_major, mode)  # 512 vectors: longest fused panel
-    _attention_variant_check(1, 2048, 128, 0.7, 4003, p_bits, qkv_bits, token_major, mode)  # 614 vectors, dk 128: pipeline
+    _attention_variant_check(1, 2048, 128, 0.7, 4003, p_bits, qkv_bits, token_major, mode)  # 614 vectors, dk 128
+
+
+@pytest.mark.parametrize("token_major", [False, True])
+@pytest.mark.parametrize("mode", [0, 3, 4])
+def test_attention_16bit_codes_head_dimension_128(token_major, mode):
+    """Two planes of codes with rows of 128 bytes (the fused kernel's largest LDS footprint)."""
+    _attention_variant_check(2, 256, 128, 0.75, 4010, 16, 8, token_major, mode)
+    _attention_variant_check(2, 1024, 128, 0.6, 4011, 16, 8, token_major, mode)
+    _attention_variant_check(1, 2048, 128, 0.4, 4012, 16, 8, token_major, mode)   # 20 chunks: four waves in every mode
 
 
 @pytest.mark.parametrize("p_bits,qkv_bits", [(16, 8), (8, 4)])
