@@ -255,8 +255,9 @@ size_t mc_attention_workspace_bytes(int heads, const mc_mat *mask);
  * and of O (fp32) sits at h*head_stride + l*token_stride + d (strides in elements, both
  * multiples of 16).  mc_sparse_attention is the case head_stride = L*dk, token_stride = dk.
  * The token-major layout a QKV projection produces (head_stride = dk, token_stride =
- * heads*dk) is the fast one: with dk = 64 and an even number of heads, two neighbouring
- * heads are gathered with one 128-byte request per token. */
+ * heads*dk) is the fast one: with rows of at most 64 bytes (dk = 64, or dk = 128 of 4-bit
+ * values in the variants below) and an even number of heads, two neighbouring heads are
+ * gathered with one 128-byte request per token. */
 int mc_sparse_attention_strided(const int8_t *Q_dev, const int8_t *Km_dev, const int8_t *Vm_dev, int heads, int L,
                                 int dk, int64_t head_stride, int64_t token_stride, const mc_mat *mask, float s_q,
                                 float s_k, float s_v, float s_p, float *O_dev, void *workspace_dev,
@@ -271,7 +272,7 @@ int mc_sparse_attention(const int8_t *Q_dev, const int8_t *Km_dev, const int8_t 
  * packed two per byte along dk).  Strides are in ELEMENTS for all four tensors and must make
  * whole 16-byte pieces (multiples of 16 for 8-bit, of 32 for 4-bit inputs); dk likewise.
  * p_bits = 8, qkv_bits = 8 is mc_sparse_attention_strided.  Every combination has the fused
- * kernel (dk == 64, and dk == 128 with 8-bit inputs; panels of at most 2048 vectors) and the
+ * kernel (dk == 64 or dk == 128; panels of at most 2048 vectors) and the
  * kernel pipeline behind it, as selected by mc_set_attention_mode; the workspace must hold
  * mc_attention_workspace_bytes_bits(heads, mask, p_bits) bytes.
  * Unsupported widths: MC_EUNSUPPORTED. */
@@ -330,8 +331,8 @@ int mc_set_sddmm_variant(int waves);
  * 1 = a workgroup per panel also for short panels, 2 = always the kernel for panels of any
  * length (three passes).  Same codes up to fp32 summation order.  Process-wide. */
 int mc_set_softmax_variant(int variant);
-/* Attention path: 0 = automatic (a single fused kernel when dk == 64, or dk == 128 with
- * qkv_bits == 8, and no panel holds more than 2048 vectors -- one, two or four waves per (panel, head) for panels of up to 512,
+/* Attention path: 0 = automatic (a single fused kernel when dk is 64 or 128
+ * and no panel holds more than 2048 vectors -- one, two or four waves per (panel, head) for panels of up to 512,
  * 1024, 2048 vectors -- else the pipeline of separate kernels), 1 = always the
  * pipeline SDDMM -> softmax -> SpMM of separate kernels, 2 = the fused kernel with one head per
  * workgroup even for token-major tensors, 3 / 4 = the fused kernel with at least two / with

@@ -672,8 +672,7 @@ extern "C" int mc_sparse_attention_out(const void *Q_dev, const void *Km_dev, co
     if (workspace_bytes < attn_layout(heads, mask, p_bits).total) return MC_ENOMEM;
     hipStream_t s = static_cast<hipStream_t>(stream);
 
-    // the fused kernel: head dimension 64, or 128 with 8-bit inputs
-    if (g_attention_mode != 1 && (dk == 64 || (dk == 128 && qkv_bits == 8)) &&
+    if (g_attention_mode != 1 && (dk == 64 || dk == 128) &&
         mask->max_panel_chunks * MC_CHUNK <= attention_fused_max_vectors()) {
         AttnArgs f;
         f.panel_ptr = mask->d_panel_ptr; f.slot_idx = mask->d_slot_idx;
@@ -688,9 +687,11 @@ extern "C" int mc_sparse_attention_out(const void *Q_dev, const void *Km_dev, co
         int wpp = (mask->max_panel_chunks > 16) ? 4 : (mask->max_panel_chunks > 8 ? 2 : 1);
         if (g_attention_mode == 3 && wpp < 2) wpp = 2;
         if (g_attention_mode == 4) wpp = 4;
-        // neighbouring heads contiguous inside a token: two heads per workgroup, 128-byte gathers
-        // (not for 16-bit codes with 4-bit inputs, whose output tile does not fit that kernel's stages)
-        const int hpg = (g_attention_mode == 0 && wpp == 1 && dk == 64 && head_stride == 64 && heads % 2 == 0 &&
+        // neighbouring heads contiguous inside a token, rows of at most 64 bytes: two heads per workgroup,
+        // 128-byte gathers (not for 16-bit codes with 4-bit inputs, whose output tile does not fit that
+        // kernel's stages)
+        const bool short_rows = dk == 64 || qkv_bits == 4;
+        const int hpg = (g_attention_mode == 0 && wpp == 1 && short_rows && head_stride == dk && heads % 2 == 0 &&
                          !(p_bits == 16 && qkv_bits == 4)) ? 2 : 1;
         MC_HIP(launch_attention_fused(f, hpg, wpp, p_bits, qkv_bits, dk, s));
         return MC_OK;

@@ -21,7 +21,7 @@
 //
 // Two variants (HPW = heads per workgroup):
 //   HPW 1  any layout: the wave gathers the rows of its own head (64 bytes; 128 bytes for head
-//          dimension 128, 8-bit inputs only) into its one LDS stage (8 KB of LDS per wave and
+//          dimension 128 with 8-bit inputs) into its one LDS stage (8 KB of LDS per wave and
 //          16 waves per CU for 64-byte rows).
 //   HPW 2  token-major layout (the heads of a token are contiguous, as a QKV projection
 //          writes them): two waves own two neighbouring heads and gather their 128 bytes of
@@ -80,7 +80,8 @@ __device__ __forceinline__ float row16_sum(float v)
 // KS: waves that share one (panel, head) when a panel is longer than MAXCH chunks (HPW 1 only): wave
 // ks takes chunks ks, ks + KS, ...; the waves exchange their row maxima and row sums through LDS
 // and add up their partial output tiles at the end (three workgroup barriers in total).
-// DK: head dimension, 64 or 128 (128: 8-bit inputs, one head per workgroup).
+// DK: head dimension, 64 or 128.  Rows of 128 bytes (DK 128, 8-bit inputs) are gathered by one head per
+// workgroup only; the 64-byte rows of DK 128 with 4-bit inputs behave like those of DK 64 with 8-bit ones.
 template <int MAXCH, int HPW, int PB, int QB, int KS, int DK>
 __global__ __launch_bounds__(64 * HPW * KS, ((HPW == 1 && PB == 8 && KS == 1 && DK == 64) ? 4 : 3))
 void attention_fused_kernel(AttnArgs a)
@@ -88,7 +89,7 @@ void attention_fused_kernel(AttnArgs a)
     static_assert(PB == 8 || PB == 16, "8- or 16-bit codes");
     static_assert(QB == 8 || QB == 4, "Q, K, V are 8-bit or packed 4-bit");
     static_assert(KS == 1 || HPW == 1, "chunks are shared between waves only in the one-head-per-workgroup form");
-    static_assert(DK == 64 || (DK == 128 && QB == 8 && HPW == 1), "head dimension 128: 8-bit inputs, one head per workgroup");
+    static_assert(DK == 64 || (DK == 128 && (QB == 4 || HPW == 1)), "rows of 128 bytes: one head per workgroup");
     constexpr int NW = HPW * KS;         // waves per workgroup
     constexpr int PLANE = MAXCH * 512;   // bytes of one plane of codes, [slot][8 rows]
     constexpr int OTILE = (PB == 16 ? 16 : 8) * (DK + 4) * 4;                       // a wave's output tile, staged in the same area
@@ -148,7 +149,7 @@ void attention_fused_kernel(AttnArgs a)
         if (QB == 8) {
             qv = *reinterpret_cast<const v4i *>(qrow + kk * 64 + g * 16);
         } else {
-            const v4i raw = *reinterpret_cast<const v4i *>(qrow + (g & 1) * 16);
+            const v4i raw = *reinterpret_cast<const v4i *>(qrow + kk * 32 + (g & 1) * 16);
             qv = (g < 2) ? ((raw << 4) & NIB) : (raw & NIB);
         }
         q_lo[kk] = (j < 8) ? qv : (v4i){0, 0, 0, 0};
@@ -204,12 +205,12 @@ void attention_fused_kernel(AttnArgs a)
     // are kept out of the row sum (and so out of the codes) below.
     // K operand of tile tl: slot s = tl*16 + j sits in LDS row (s % NIT)*(64/NIT) + s/NIT,
     // i.e. byte (j % NIT)*1024 + (j / NIT)*ROWB + tl*256; segment (NITW*w + piece) ^ (j % NIT), where
-    // lane group g reads piece 4*kk + g of its head's row in MFMA step kk (8 bit) or piece g % 2
+    // lane group g reads piece 4*kk + g of its head's row in MFMA step kk (8 bit) or piece 2*kk + g % 2
     // (4 bit: even elements of the piece for g < 2, odd elements for g >= 2, as on the Q side)
     const char *kaddr[KK];
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk)
-        kaddr[kk] = stage + (j % NIT) * 1024 + (j / NIT) * ROWB + (((NITW * w + 4 * kk + (QB == 8 ? g : (g & 1))) ^ (j % NIT)) * 16);
+        kaddr[kk] = stage + (j % NIT) * 1024 + (j / NIT) * ROWB + (((NITW * w + (QB == 8 ? 4 * kk + g : 2 * kk + (g & 1))) ^ (j % NIT)) * 16);
     auto kop = [&](v4i raw) -> v4i {
         if (QB == 8) return raw;
         return (g < 2) ? ((raw << 4) & NIB) : (raw & NIB);
@@ -472,8 +473,9 @@ template <int PB, int QB, int DK> hipError_t launch_pq(const AttnArgs &a, int he
     } else if (waves_per_panel == 2) {
         hipLaunchKernelGGL((attention_fused_kernel<8, 1, PB, QB, 2, DK>), dim3((unsigned)a.P * (unsigned)a.heads, (unsigned)a.batch), dim3(128), 0, s, a);
     } else if (heads_per_group == 2) {
-        // (16-bit codes with 4-bit Q/K/V: the two-plane output tile does not fit a stage of 32-byte rows)
-        if constexpr ((PB == 16 && QB == 4) || DK != 64) return hipErrorInvalidValue;
+        // (16-bit codes with 4-bit Q/K/V: the two-plane output tile does not fit the stage; rows of 128
+        // bytes: one head per workgroup)
+        if constexpr ((PB == 16 && QB == 4) || (DK == 128 && QB == 8)) return hipErrorInvalidValue;
         else hipLaunchKernelGGL((attention_fused_kernel<8, 2, PB, QB, 1, DK>), dim3((unsigned)a.P * (unsigned)(a.heads / 2), (unsigned)a.batch), dim3(128), 0, s, a);
     } else {
         hipLaunchKernelGGL((attention_fused_kernel<8, 1, PB, QB, 1, DK>), dim3((unsigned)a.P * (unsigned)a.heads, (unsigned)a.batch), dim3(64), 0, s, a);
@@ -483,14 +485,16 @@ template <int PB, int QB, int DK> hipError_t launch_pq(const AttnArgs &a, int he
 
 // waves_per_panel: 1, 2 or 4 waves share the chunks of one (panel, head); a wave holds at most 8 chunks
 // of scores in registers, so a panel may have up to 512 * waves_per_panel vectors.
-// dk: 64, or 128 with 8-bit inputs and heads_per_group 1
+// dk: 64 or 128
 hipError_t launch_attention_fused(const AttnArgs &a, int heads_per_group, int waves_per_panel, int p_bits, int qkv_bits,
                                   int dk, hipStream_t s)
 {
     if (a.P == 0 || a.heads == 0 || a.batch == 0) return hipSuccess;
     if (dk == 128) {
-        if (qkv_bits != 8 || heads_per_group != 1) return hipErrorInvalidValue;
-        return (p_bits == 16) ? launch_pq<16, 8, 128>(a, 1, waves_per_panel, s) : launch_pq<8, 8, 128>(a, 1, waves_per_panel, s);
+        if (p_bits == 16) return (qkv_bits == 4) ? launch_pq<16, 4, 128>(a, heads_per_group, waves_per_panel, s)
+                                                 : launch_pq<16, 8, 128>(a, heads_per_group, waves_per_panel, s);
+        return (qkv_bits == 4) ? launch_pq<8, 4, 128>(a, heads_per_group, waves_per_panel, s)
+                               : launch_pq<8, 8, 128>(a, heads_per_group, waves_per_panel, s);
     }
     if (dk != 64) return hipErrorInvalidValue;
     if (p_bits == 16) return (qkv_bits == 4) ? launch_pq<16, 4, 64>(a, heads_per_group, waves_per_panel, s)

@@ -120,8 +120,8 @@ hipError_t launch_softmax(const SoftmaxArgs &a, hipStream_t s);
 hipError_t launch_absmax(const float *x, int64_t n, float *result, hipStream_t s);
 hipError_t launch_quantize(const float *x, int64_t n, float scale, int bits, uint8_t *q, hipStream_t s);
 hipError_t launch_repack(const RepackArgs &a, hipStream_t s);
-// heads_per_group 2 needs dk == 64 == head_stride (token-major layout), an even head count, and is not
-// available for 16-bit codes with 4-bit inputs; dk is 64, or 128 with 8-bit inputs
+// dk is 64 or 128.  heads_per_group 2 needs head_stride == dk (token-major layout), rows of at most 64
+// bytes and an even head count, and is not available for 16-bit codes with 4-bit inputs
 hipError_t launch_attention_fused(const AttnArgs &a, int heads_per_group, int waves_per_panel, int p_bits, int qkv_bits,
                                   int dk, hipStream_t s);
 int attention_fused_max_vectors(); // longest panel (in vectors) the fused kernel accepts

@@ -197,7 +197,7 @@ def _attention_f16(heads, L, dk, sparsity, seed, p_bits=8, qkv_bits=8, token_maj
 def test_attention_fp16_output_small(token_major, mode):
     _attention_f16(2, 256, 64, 0.75, 6600, token_major=token_major, mode=mode)
     _attention_f16(2, 1024, 64, 0.6, 6601, token_major=token_major, mode=mode)     # 7 chunks, ragged tail
-    _attention_f16(3, 512, 32, 0.9, 6602, token_major=token_major, mode=mode)      # dk != 64: kernel pipeline
+    _attention_f16(3, 512, 32, 0.9, 6602, token_major=token_major, mode=mode)      # dk = 32: kernel pipeline
 
 
 @pytest.mark.parametrize("p_bits,qkv_bits", [(16, 8), (8, 4), (16, 4)])
@@ -213,6 +213,8 @@ def test_attention_fp16_output_head_dimension_128(p_bits):
     _attention_f16(2, 1024, 128, 0.6, 6631, p_bits, 8, token_major=True)
     _attention_f16(2, 2048, 128, 0.6, 6632, p_bits, 8)                             # two waves per (panel, head)
     _attention_f16(1, 2048, 128, 0.3, 6633, p_bits, 8, token_major=True)           # four waves
+    _attention_f16(2, 1024, 128, 0.6, 6634, p_bits, 4, token_major=True)           # nibbles; two heads per workgroup (8-bit codes)
+    _attention_f16(2, 2048, 128, 0.6, 6635, p_bits, 4)
 
 
 def test_attention_fp16_output_batched_and_config5():

@@ -157,7 +157,7 @@ def _attention_check(heads, L, dk, sparsity, seed, mode=0, token_major=False):
 @pytest.mark.parametrize("mode", [0, 1])
 def test_attention_small(mode, token_major):
     _attention_check(2, 256, 64, 0.75, 1200, mode, token_major)   # one chunk per panel
-    _attention_check(3, 512, 32, 0.9, 1201, mode, token_major)    # dk != 64: always the kernel pipeline
+    _attention_check(3, 512, 32, 0.9, 1201, mode, token_major)    # dk = 32: always the kernel pipeline
     _attention_check(2, 1024, 64, 0.6, 1202, mode, token_major)   # 410 vectors per panel: 7 chunks, ragged tail
     _attention_check(3, 1024, 64, 0.8, 1205, mode, token_major)   # odd head count: one head per workgroup
     _attention_check(2, 2048, 64, 0.75, 1203, mode, token_major)  # 512 vectors: the longest panel the fused kernel takes

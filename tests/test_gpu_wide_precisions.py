@@ -213,7 +213,7 @@ def _attention_variant_check(heads, L, dk, sparsity, seed, p_bits, qkv_bits, tok
 @pytest.mark.parametrize("mode", [0, 1])                      # fused kernel where there is one / kernel pipeline
 def test_attention_variants_small(p_bits, qkv_bits, token_major, mode):
     _attention_variant_check(2, 256, 64, 0.75, 4000, p_bits, qkv_bits, token_major, mode)   # one chunk per panel
-    _attention_variant_check(3, 512, 32, 0.9, 4001, p_bits, qkv_bits, token_major, mode)    # dk != 64: pipeline
+    _attention_variant_check(3, 512, 32, 0.9, 4001, p_bits, qkv_bits, token_major, mode)    # dk = 32: pipeline
     _attention_variant_check(2, 1024, 64, 0.6, 4002, p_bits, qkv_bits, token_major, mode)   # 7 chunks, ragged tail
     _attention_variant_check(2, 2048, 64, 0.75, 4004, p_bits, qkv_bits, token_major, mode)  # 512 vectors: longest fused panel
     _attention_variant_check(1, 2048, 128, 0.7, 4003, p_bits, qkv_bits, token_major, mode)  # 614 vectors, dk 128
@@ -226,6 +226,16 @@ def test_attention_16bit_codes_head_dimension_128(token_major, mode):
     _attention_variant_check(2, 256, 128, 0.75, 4010, 16, 8, token_major, mode)
     _attention_variant_check(2, 1024, 128, 0.6, 4011, 16, 8, token_major, mode)
     _attention_variant_check(1, 2048, 128, 0.4, 4012, 16, 8, token_major, mode)   # 20 chunks: four waves in every mode
+
+
+@pytest.mark.parametrize("p_bits", [8, 16])
+@pytest.mark.parametrize("token_major", [False, True])
+@pytest.mark.parametrize("mode", [0, 2, 3, 4])
+def test_attention_4bit_inputs_head_dimension_128(p_bits, token_major, mode):
+    """Rows of 64 bytes of nibbles: two MFMA steps per score tile, eight column tiles of output."""
+    _attention_variant_check(2, 256, 128, 0.75, 4020, p_bits, 4, token_major, mode)
+    _attention_variant_check(4, 1024, 128, 0.6, 4021, p_bits, 4, token_major, mode)   # 7 chunks, ragged tail
+    _attention_variant_check(1, 2048, 128, 0.4, 4022, p_bits, 4, token_major, mode)   # 20 chunks: four waves in every mode
 
 
 @pytest.mark.parametrize("p_bits,qkv_bits", [(16, 8), (8, 4)])
