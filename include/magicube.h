@@ -336,7 +336,7 @@ int mc_set_softmax_variant(int variant);
  * 1024, 2048 vectors -- else the pipeline of separate kernels), 1 = always the
  * pipeline SDDMM -> softmax -> SpMM of separate kernels, 2 = the fused kernel with one head per
  * workgroup even for token-major tensors, 3 / 4 = the fused kernel with at least two / with
- * four waves per (panel, head) whatever the panel length.  All give the same result up to fp32 summation
+ * four waves per (panel, head) whatever the panel length (heads per workgroup as in 0).  All give the same result up to fp32 summation
  * order in the softmax.  Process-wide; MC_EINVAL for other values. */
 int mc_set_attention_mode(int mode);
 

@@ -691,7 +691,7 @@ extern "C" int mc_sparse_attention_out(const void *Q_dev, const void *Km_dev, co
         // 128-byte gathers (not for 16-bit codes with 4-bit inputs, whose output tile does not fit that
         // kernel's stages)
         const bool short_rows = dk == 64 || qkv_bits == 4;
-        const int hpg = (g_attention_mode == 0 && wpp == 1 && short_rows && head_stride == dk && heads % 2 == 0 &&
+        const int hpg = (g_attention_mode != 2 && short_rows && head_stride == dk && heads % 2 == 0 &&
                          !(p_bits == 16 && qkv_bits == 4)) ? 2 : 1;
         MC_HIP(launch_attention_fused(f, hpg, wpp, p_bits, qkv_bits, dk, s));
         return MC_OK;

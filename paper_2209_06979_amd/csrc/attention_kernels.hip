@@ -77,9 +77,12 @@ __device__ __forceinline__ float row16_sum(float v)
 // widened in registers to an int8 worth 16 x its value (Section 4.4 without an int4 matrix unit):
 // the even elements of a 16-byte piece in lane groups 0 and 1, the odd ones in groups 2 and 3, so
 // the scores carry a factor 256 and the output a factor 16, removed by exact shifts.
-// KS: waves that share one (panel, head) when a panel is longer than MAXCH chunks (HPW 1 only): wave
-// ks takes chunks ks, ks + KS, ...; the waves exchange their row maxima and row sums through LDS
-// and add up their partial output tiles at the end (three workgroup barriers in total).
+// KS: waves that share one (panel, head) when a panel is longer than MAXCH chunks: wave ks takes
+// chunks ks, ks + KS, ...; the waves exchange their row maxima and row sums through LDS and add up
+// their partial output tiles at the end (three workgroup barriers in total).  With HPW 2 the
+// workgroup has 2 * KS waves: pair ks (one wave per head) gathers its chunks into its own two
+// stages, and since the per-chunk barrier is the workgroup's, every wave goes through the chunk
+// loops as often as the pair with the most chunks does.
 // DK: head dimension, 64 or 128.  Rows of 128 bytes (DK 128, 8-bit inputs) are gathered by one head per
 // workgroup only; the 64-byte rows of DK 128 with 4-bit inputs behave like those of DK 64 with 8-bit ones.
 template <int MAXCH, int HPW, int PB, int QB, int KS, int DK>
@@ -88,7 +91,6 @@ void attention_fused_kernel(AttnArgs a)
 {
     static_assert(PB == 8 || PB == 16, "8- or 16-bit codes");
     static_assert(QB == 8 || QB == 4, "Q, K, V are 8-bit or packed 4-bit");
-    static_assert(KS == 1 || HPW == 1, "chunks are shared between waves only in the one-head-per-workgroup form");
     static_assert(DK == 64 || (DK == 128 && (QB == 4 || HPW == 1)), "rows of 128 bytes: one head per workgroup");
     constexpr int NW = HPW * KS;         // waves per workgroup
     constexpr int PLANE = MAXCH * 512;   // bytes of one plane of codes, [slot][8 rows]
@@ -115,11 +117,11 @@ void attention_fused_kernel(AttnArgs a)
     __shared__ __attribute__((aligned(16))) char stage_all[NST * STG * KS];  // chunks of gathered rows (KS > 1: one stage per wave)
     __shared__ __attribute__((aligned(16))) char Pl_all[NW * PLB]; // codes, [plane][slot][8 rows], per wave
     __shared__ __attribute__((aligned(8))) char zeros[8];                      // row operand of the MFMA rows that carry no codes
-    __shared__ int xch[2][KS][8];                                             // row maxima / row sums of the KS waves
+    __shared__ int xch[2][HPW][KS][8];                                        // row maxima / row sums of the KS waves of a head
 
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int w = (HPW > 1) ? wave : 0;   // head within the workgroup
-    const int ks = (KS > 1) ? wave : 0;   // share of the panel's chunks
+    const int w = (HPW > 1) ? wave % HPW : 0;  // head within the workgroup
+    const int ks = (KS > 1) ? wave / HPW : 0;  // share of the panel's chunks
     char *stage = stage_all + ks * (NST * STG);
     const int j = lane & 15, g = lane >> 4;
     const int rg = lane / LPR, seg = lane % LPR;
@@ -138,6 +140,10 @@ void attention_fused_kernel(AttnArgs a)
     float *Oh = a.O + (int64_t)blockIdx.y * a.batch_stride + (int64_t)head * a.head_stride + (int64_t)panel * 8 * a.token_stride;
     char *Pl = Pl_all + wave * PLB;
     const int nloc = (nch > ks) ? (nch - ks + KS - 1) / KS : 0; // chunks of this wave: ks, ks + KS, ...
+    // Waves that meet at a workgroup barrier per chunk all make as many passes as the busiest of them
+    // (a pass without a chunk of its own is the barrier alone).
+    constexpr bool LOCKSTEP = (HPW > 1 && KS > 1);
+    const int npass = LOCKSTEP ? (nch + KS - 1) / KS : nloc;
     if (PB == 8 && lane < 2) reinterpret_cast<int *>(zeros)[lane] = 0; // every wave writes the same zeros: no race that matters
 
     // Q rows twice: in MFMA rows 0..7 (q_lo) and in rows 8..15 (q_hi)
@@ -172,7 +178,7 @@ void attention_fused_kernel(AttnArgs a)
     auto issue = [&](const uint8_t *base, int c) {
 #pragma unroll
         for (int i = 0; i < NITW; ++i)
-            copy16_to_lds(base, __umul24(ixn[i], tstride) + segoff[i], stage_u + (c % NST) * STG + (NITW * w + i) * 1024);
+            copy16_to_lds(base, __umul24(ixn[i], tstride) + segoff[i], stage_u + ((c / KS) % NST) * STG + (NITW * w + i) * 1024);
         ixn = *reinterpret_cast<const ixv_t *>(myidx + ((c + KS < nch) ? c + KS : c) * MC_CHUNK);
     };
     auto start_pipeline = [&](const uint8_t *base) {
@@ -185,12 +191,13 @@ void attention_fused_kernel(AttnArgs a)
     };
     // Makes chunk c readable.  HPW 1: the next chunk is issued by release() once this one has
     // been read.  HPW 2: both halves have landed after the barrier, which also tells that
-    // everybody is done reading chunk c-1, so the next chunk can go into the other stage now.
+    // everybody is done reading the pair's previous chunk, so its next chunk can go into the other
+    // stage now.  (c may lie beyond the panel's last chunk in a pass of waiting only.)
     auto acquire = [&](const uint8_t *base, int c) {
         vm_wait<0>();
         if (HPW > 1) {
             __builtin_amdgcn_s_barrier();
-            if (c + 1 < nch) issue(base, c + 1);
+            if (c + KS < nch) issue(base, c + KS);
         }
     };
     auto release = [&](const uint8_t *base, int c) { // the reads of chunk c have been issued
@@ -224,10 +231,11 @@ void attention_fused_kernel(AttnArgs a)
     start_pipeline(Kg);
     // (from here on c counts this wave's chunks; gc is the chunk's number in the panel)
     static_for<MAXCH>([&](auto C) {
-        constexpr int c = C, ST = (KS > 1) ? 0 : (c % NST) * STG;
+        constexpr int c = C, ST = (c % NST) * STG;
         const int gc = ks + c * KS;
-        if (c < nloc) {
+        if (c < npass) {
             acquire(Kg, gc);
+            if (LOCKSTEP && c >= nloc) return;
             v4i kt[KK][4]; // tiles 0..3 of the chunk
 #pragma unroll
             for (int kk = 0; kk < KK; ++kk)
@@ -268,13 +276,13 @@ void attention_fused_kernel(AttnArgs a)
     if (KS > 1) { // row 4*(g&1) + r: lanes 0 and 16 publish, everybody reads all waves
         if (lane == 0 || lane == 16) {
 #pragma unroll
-            for (int r = 0; r < 4; ++r) xch[0][ks][4 * (g & 1) + r] = imax[r];
+            for (int r = 0; r < 4; ++r) xch[0][w][ks][4 * (g & 1) + r] = imax[r];
         }
         __syncthreads();
 #pragma unroll
         for (int r = 0; r < 4; ++r)
 #pragma unroll
-            for (int k = 0; k < KS; ++k) imax[r] = max(imax[r], xch[0][k][4 * (g & 1) + r]);
+            for (int k = 0; k < KS; ++k) imax[r] = max(imax[r], xch[0][w][k][4 * (g & 1) + r]);
     }
 #pragma unroll
     for (int r = 0; r < 4; ++r) m2[r] = (float)imax[r] * scale2;
@@ -311,14 +319,14 @@ void attention_fused_kernel(AttnArgs a)
     if (KS > 1) { // every wave adds the partial sums in the same order: identical totals everywhere
         if (lane == 0 || lane == 16) {
 #pragma unroll
-            for (int r = 0; r < 4; ++r) xch[1][ks][4 * (g & 1) + r] = __builtin_bit_cast(int, srow[r]);
+            for (int r = 0; r < 4; ++r) xch[1][w][ks][4 * (g & 1) + r] = __builtin_bit_cast(int, srow[r]);
         }
         __syncthreads();
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             srow[r] = 0.f;
 #pragma unroll
-            for (int k = 0; k < KS; ++k) srow[r] += __builtin_bit_cast(float, xch[1][k][4 * (g & 1) + r]);
+            for (int k = 0; k < KS; ++k) srow[r] += __builtin_bit_cast(float, xch[1][w][k][4 * (g & 1) + r]);
         }
     }
 #pragma unroll
@@ -343,6 +351,10 @@ void attention_fused_kernel(AttnArgs a)
     static_for<MAXCH>([&](auto C) {
         constexpr int c = C;
         const int gc = ks + c * KS;
+        if (LOCKSTEP && c >= nloc) { // a pass of waiting only
+            if (c < npass) acquire(Vg, gc);
+            return;
+        }
         if (c < nloc) {
             // Codes of this chunk's slots (tile*16 + j), rows 4*(g&1) .. +3: one 32-bit LDS write
             // per tile.  v_cvt_pk_u8_f32 rounds to nearest even and drops the byte into place; the
@@ -377,8 +389,8 @@ void attention_fused_kernel(AttnArgs a)
             v2i d[NITW][2];
 #pragma unroll
             for (int ct = 0; ct < NITW; ++ct) {
-                d[ct][0] = lds_read_tr8(stage + (KS > 1 ? 0 : (c % NST) * STG) + (vbase[0] ^ (ct * 16)));
-                d[ct][1] = lds_read_tr8(stage + (KS > 1 ? 0 : (c % NST) * STG) + (vbase[1] ^ (ct * 16)));
+                d[ct][0] = lds_read_tr8(stage + (c % NST) * STG + (vbase[0] ^ (ct * 16)));
+                d[ct][1] = lds_read_tr8(stage + (c % NST) * STG + (vbase[1] ^ (ct * 16)));
             }
             release(Vg, gc);
             const v4i aop = {p0.x, p0.y, p1.x, p1.y};
@@ -402,7 +414,7 @@ void attention_fused_kernel(AttnArgs a)
         lgkm_wait();
         __builtin_amdgcn_s_barrier(); // nobody reads the stages any more: each wave takes one for its tile
     }
-    int *Ol = reinterpret_cast<int *>(SMALLP ? stage_all + w * STG : Pl);
+    int *Ol = reinterpret_cast<int *>(SMALLP ? stage_all + (ks * NST + w) * STG : Pl); // SMALLP: NST == HPW stages per pair
     if (g < 2 || PB == 16) {
 #pragma unroll
         for (int ct = 0; ct < NO; ++ct)
@@ -415,11 +427,16 @@ void attention_fused_kernel(AttnArgs a)
     }
     lgkm_wait();
     if (KS > 1) __syncthreads(); else __builtin_amdgcn_wave_barrier();
+    // the tile of wave k of this wave's head, and this thread's number among the 64 * KS threads of the head
+    auto partial_tile = [&](int k) -> const int * {
+        return reinterpret_cast<const int *>(SMALLP ? stage_all + (k * NST + w) * STG : Pl_all + k * PLB);
+    };
+    const int tih = ks * 64 + lane;
     if (a.out_f16) {
         // fp16: 8 rows x DK/8 pieces of 8 columns, one 16-byte store each
 #pragma unroll
         for (int h = 0; h < (DK + 64 * KS - 1) / (64 * KS); ++h) {
-            const int piece = ((KS > 1) ? (int)threadIdx.x : lane) + h * 64 * KS;
+            const int piece = tih + h * 64 * KS;
             if (piece >= DK) continue;
             const int row = piece / (DK / 8), col = (piece % (DK / 8)) * 8;
             v4h hv[2];
@@ -428,7 +445,7 @@ void attention_fused_kernel(AttnArgs a)
                 v4i sres = {0, 0, 0, 0}, slo = {0, 0, 0, 0};
 #pragma unroll
                 for (int k = 0; k < KS; ++k) {
-                    const int *Ok = (KS > 1) ? reinterpret_cast<const int *>(Pl_all + k * PLB) : Ol;
+                    const int *Ok = (KS > 1) ? partial_tile(k) : Ol;
                     sres += *reinterpret_cast<const v4i *>(&Ok[row * (DK + 4) + col + 4 * q]);
                     if (PB == 16) slo += *reinterpret_cast<const v4i *>(&Ok[(row + 8) * (DK + 4) + col + 4 * q]);
                 }
@@ -445,13 +462,13 @@ void attention_fused_kernel(AttnArgs a)
     // 8 rows x DK/4 pieces of 4 columns; with KS waves all threads share the adding up of the partial tiles
 #pragma unroll
     for (int h = 0; h < (2 * DK + 64 * KS - 1) / (64 * KS); ++h) {
-        const int piece = ((KS > 1) ? (int)threadIdx.x : lane) + h * 64 * KS;
+        const int piece = tih + h * 64 * KS;
         if (piece >= 2 * DK) continue;
         const int row = piece / (DK / 4), col = (piece % (DK / 4)) * 4;
         v4i sres = {0, 0, 0, 0}, slo = {0, 0, 0, 0};
 #pragma unroll
         for (int k = 0; k < KS; ++k) {
-            const int *Ok = (KS > 1) ? reinterpret_cast<const int *>(Pl_all + k * PLB) : Ol;
+            const int *Ok = (KS > 1) ? partial_tile(k) : Ol;
             sres += *reinterpret_cast<const v4i *>(&Ok[row * (DK + 4) + col]);
             if (PB == 16) slo += *reinterpret_cast<const v4i *>(&Ok[(row + 8) * (DK + 4) + col]);
         }
@@ -468,15 +485,20 @@ int attention_fused_max_vectors() { return 4 * 8 * 64; }
 
 template <int PB, int QB, int DK> hipError_t launch_pq(const AttnArgs &a, int heads_per_group, int waves_per_panel, hipStream_t s)
 {
-    if (waves_per_panel == 4) {
-        hipLaunchKernelGGL((attention_fused_kernel<8, 1, PB, QB, 4, DK>), dim3((unsigned)a.P * (unsigned)a.heads, (unsigned)a.batch), dim3(256), 0, s, a);
-    } else if (waves_per_panel == 2) {
-        hipLaunchKernelGGL((attention_fused_kernel<8, 1, PB, QB, 2, DK>), dim3((unsigned)a.P * (unsigned)a.heads, (unsigned)a.batch), dim3(128), 0, s, a);
-    } else if (heads_per_group == 2) {
+    if (heads_per_group == 2) {
         // (16-bit codes with 4-bit Q/K/V: the two-plane output tile does not fit the stage; rows of 128
         // bytes: one head per workgroup)
         if constexpr ((PB == 16 && QB == 4) || (DK == 128 && QB == 8)) return hipErrorInvalidValue;
-        else hipLaunchKernelGGL((attention_fused_kernel<8, 2, PB, QB, 1, DK>), dim3((unsigned)a.P * (unsigned)(a.heads / 2), (unsigned)a.batch), dim3(128), 0, s, a);
+        else {
+            const dim3 grid((unsigned)a.P * (unsigned)(a.heads / 2), (unsigned)a.batch);
+            if (waves_per_panel == 4) hipLaunchKernelGGL((attention_fused_kernel<8, 2, PB, QB, 4, DK>), grid, dim3(512), 0, s, a);
+            else if (waves_per_panel == 2) hipLaunchKernelGGL((attention_fused_kernel<8, 2, PB, QB, 2, DK>), grid, dim3(256), 0, s, a);
+            else hipLaunchKernelGGL((attention_fused_kernel<8, 2, PB, QB, 1, DK>), grid, dim3(128), 0, s, a);
+        }
+    } else if (waves_per_panel == 4) {
+        hipLaunchKernelGGL((attention_fused_kernel<8, 1, PB, QB, 4, DK>), dim3((unsigned)a.P * (unsigned)a.heads, (unsigned)a.batch), dim3(256), 0, s, a);
+    } else if (waves_per_panel == 2) {
+        hipLaunchKernelGGL((attention_fused_kernel<8, 1, PB, QB, 2, DK>), dim3((unsigned)a.P * (unsigned)a.heads, (unsigned)a.batch), dim3(128), 0, s, a);
     } else {
         hipLaunchKernelGGL((attention_fused_kernel<8, 1, PB, QB, 1, DK>), dim3((unsigned)a.P * (unsigned)a.heads, (unsigned)a.batch), dim3(64), 0, s, a);
     }

@@ -205,6 +205,8 @@ def test_attention_fp16_output_variants(p_bits, qkv_bits):
     _attention_f16(2, 512, 64, 0.8, 6610, p_bits, qkv_bits)
     _attention_f16(2, 512, 64, 0.8, 6611, p_bits, qkv_bits, token_major=True)
     _attention_f16(2, 2048, 64, 0.6, 6612, p_bits, qkv_bits)                       # two waves per (panel, head)
+    _attention_f16(2, 2048, 64, 0.6, 6613, p_bits, qkv_bits, token_major=True)
+    _attention_f16(2, 2048, 64, 0.3, 6614, p_bits, qkv_bits, token_major=True)     # four waves per (panel, head)
 
 
 @pytest.mark.parametrize("p_bits", [8, 16])

@@ -179,6 +179,8 @@ def test_attention_long_panels(token_major):
     _attention_check(1, 2048, 64, 0.4, 1221, 0, token_major)      # 1229 vectors (20 chunks): four waves
     _attention_check(1, 2048, 64, 0.0, 1222, 0, token_major)      # 2048 vectors (32 chunks): the longest fused panel
     _attention_check(1, 4096, 64, 0.45, 1223, 0, token_major)     # 2253 vectors: the kernel pipeline
+    _attention_check(4, 2048, 64, 0.4, 1224, 0, token_major)      # 20 chunks, an even number of heads
+    _attention_check(2, 2048, 64, 0.0, 1225, 0, token_major)      # 32 chunks, an even number of heads
 
 
 @pytest.mark.parametrize("token_major", [False, True])

@@ -238,6 +238,18 @@ def test_attention_4bit_inputs_head_dimension_128(p_bits, token_major, mode):
     _attention_variant_check(1, 2048, 128, 0.4, 4022, p_bits, 4, token_major, mode)   # 20 chunks: four waves in every mode
 
 
+@pytest.mark.parametrize("p_bits,qkv_bits,dk", [(8, 8, 64), (16, 8, 64), (8, 4, 64), (8, 4, 128)])
+def test_attention_two_heads_per_workgroup_sharing_long_panels(p_bits, qkv_bits, dk):
+    """Token-major tensors with panels of more than 512 vectors: pairs of waves (one wave per head) share the
+    chunks of a panel and every wave goes through the chunk loops as often as the busiest pair."""
+    for heads, L, sp, seed in ((2, 2048, 0.6, 4500),    # 13 chunks: pairs with 7 and 6
+                               (2, 1024, 0.45, 4503),   # 9 chunks: 5 and 4
+                               (4, 2048, 0.4, 4501),    # 20 chunks: four pairs with 5 each
+                               (2, 2048, 0.17, 4504),   # 27 chunks: 7, 7, 7, 6
+                               (2, 2048, 0.0, 4502)):   # 32 chunks: the longest fused panel
+        _attention_variant_check(heads, L, dk, sp, seed, p_bits, qkv_bits, True, 0)
+
+
 @pytest.mark.parametrize("p_bits,qkv_bits", [(16, 8), (8, 4)])
 @pytest.mark.parametrize("mode", [0, 1])
 def test_attention_variants_config5_shape(p_bits, qkv_bits, mode):
