@@ -86,7 +86,7 @@ __device__ __forceinline__ float row16_sum(float v)
 // DK: head dimension, 64 or 128.  Rows of 128 bytes (DK 128, 8-bit inputs) are gathered by one head per
 // workgroup only; the 64-byte rows of DK 128 with 4-bit inputs behave like those of DK 64 with 8-bit ones.
 template <int MAXCH, int HPW, int PB, int QB, int KS, int DK>
-__global__ __launch_bounds__(64 * HPW * KS, ((HPW == 1 && PB == 8 && KS == 1 && DK == 64) ? 4 : 3))
+__global__ __launch_bounds__(64 * HPW * KS, (((HPW == 1 && PB == 8 && KS == 1 && DK == 64) || (HPW == 2 && DK == 64 && QB == 8)) ? 4 : 3))
 void attention_fused_kernel(AttnArgs a)
 {
     static_assert(PB == 8 || PB == 16, "8- or 16-bit codes");
