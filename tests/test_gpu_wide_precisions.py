@@ -323,6 +323,42 @@ def test_sparse_softmax_16_bit_codes():
     mask.close()
 
 
+@pytest.mark.parametrize("L,dk,sparsity", [(1536, 64, 0.5), (2048, 64, 0.3), (1536, 128, 0.5)])
+def test_attention_batched_long_panels_equal_item_by_item(L, dk, sparsity):
+    """Batches whose panels need two or four waves per (panel, head), in both tensor orders."""
+    import torch
+    from paper_2209_06979_amd import binding as mc
+    B, heads, V = 2, 2, 8
+    c = wl.attention_case(B * heads, L, dk, V, sparsity, 4450 + dk)
+    (q, s_q), (k, s_k), (v, s_v) = (wl.quantize_inputs_int8(c[n]) for n in "qkv")
+    s_p = np.float32(1.0 / 127.0)
+    mask = mc.SparseMatrix(L, L, V, c["row_ptr"], c["col_idx"])
+    try:
+        for token_major in (False, True):
+            def dev(t):
+                x = torch.from_numpy(np.ascontiguousarray(t)).cuda().reshape(B, heads, L, -1)
+                return x.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3) if token_major else x
+            qd, kd, vd = dev(q), dev(k), dev(v)
+            print(f"batched attention L={L} dk={dk} s={sparsity} token_major={token_major}", flush=True)
+            O = mc.sparse_attention(qd, kd, vd, mask, s_q, s_k, s_v, s_p)
+            torch.cuda.synchronize()
+            assert O.shape == (B, heads, L, dk) and bool(torch.isfinite(O).all())
+            for b in range(B):
+                Ob = mc.sparse_attention(qd[b], kd[b], vd[b], mask, s_q, s_k, s_v, s_p)
+                torch.cuda.synchronize()
+                assert torch.equal(O[b], Ob), b
+            # and the single items against the kernel pipeline, up to the order of the fp32 sums
+            mc.set_attention_mode(1)
+            Op = mc.sparse_attention(qd[0], kd[0], vd[0], mask, s_q, s_k, s_v, s_p)
+            torch.cuda.synchronize()
+            mc.set_attention_mode(0)
+            d = (O[0] - Op).abs()
+            assert float((d > 1e-6).float().mean()) < 0.02 and float(d.max()) < 0.05
+    finally:
+        mc.set_attention_mode(0)
+        mask.close()
+
+
 @pytest.mark.parametrize("mode", [0, 1])
 @pytest.mark.parametrize("p_bits,qkv_bits", [(8, 8), (16, 8), (8, 4)])
 def test_attention_batched_equals_item_by_item(p_bits, qkv_bits, mode):
