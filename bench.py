@@ -275,6 +275,7 @@ def main():
         "gather_peak_tbs_measured": (extras or {}).get("gather_peak_tbs"),
         "beyond_the_step": (extras or {}).get("wider_precisions"),
         "layer_at_inference_shapes": (extras or {}).get("layer_at_inference_shapes"),
+        "spmm_design_steps": (extras or {}).get("spmm_design_steps"),
         "quantisation_streaming": (extras or {}).get("quantisation_streaming"),
         "per_kernel": per_kernel,
         "format_build_s": round(format_build_s, 3),
@@ -494,6 +495,25 @@ def measure_extras(mc, torch, prob, stream, reps, up):
     B, C16 = up(cc["B"]), torch.empty((M, N_SPMM), dtype=torch.float16, device="cuda")
     us = time_graph(torch, stream, [lambda: mc.spmm_dequant(A, B, "L8R8", 1e-4, torch.float16, out=C16)] * reps)
     wide["spmm_L8R8_fp16_out"] = dict(us=round(us, 2), eff_tops=round(2 * A.nvec * V * N_SPMM / us / 1e6, 1))
+    # What the pieces of the SpMM design are worth (the counterpart of the ablation in Section 5.1, on the
+    # headline matrix and on a matrix of that section's shape): one wave per panel on 64-byte row tiles with
+    # one chunk in flight; then the tile and wave count chosen from the shape; then two chunks in flight.
+    C32 = torch.empty((M, N_SPMM), dtype=torch.int32, device="cuda")
+    ca = wl.spmm_case(256, 2304, 512, V, 0.7, "L8R8", wl.seed_for(2, 900))
+    A2 = mc.SparseMatrix(256, 2304, V, ca["row_ptr"], ca["col_idx"], ca["values"], 8)
+    B2, C2 = up(ca["B"]), torch.empty((256, 512), dtype=torch.int32, device="cuda")
+    ablation = {}
+    for name, (Ax, Bx, Cx) in (("headline_4096x4096_s0.9_N256", (A, B, C32)), ("section5.1_shape_256x2304_s0.7_N512", (A2, B2, C2))):
+        row = {}
+        for step, (tile, waves, stages) in (("plain", (64, 1, 1)), ("tile_and_waves_chosen", (0, 0, 1)), ("two_chunks_in_flight", (0, 0, 2))):
+            mc.set_spmm_variant(tile, waves)
+            mc.set_spmm_stages(stages)
+            row[step + "_us"] = round(time_graph(torch, stream, [lambda: mc.spmm(Ax, Bx, "L8R8", out=Cx)] * reps), 2)
+        mc.set_spmm_variant(0, 0)
+        mc.set_spmm_stages(2)
+        ablation[name] = row
+    out["spmm_design_steps"] = ablation
+    A2.close()
     A.close()
     cc = prob["sddmm_L8R8"]
     mask = mc.SparseMatrix(M, K, V, cc["row_ptr"], cc["col_idx"])

@@ -320,7 +320,8 @@ int mc_set_spmm_stages(int stages);
 int mc_set_spmm_splitting(int enable);
 /* (The switch also governs the work items of mc_sddmm.  There every item writes its own outputs,
  * so a pattern-only mask is cut finer: into pieces of at most the average panel length, at least
- * 8 chunks, as soon as one panel is longer than that.) */
+ * 8 chunks, as soon as one panel is longer than that; a mask with fewer than 256 panels into
+ * pieces short enough to make 256 of them, again at least 8 chunks.) */
 /* SDDMM variant: -1 = automatic, 0 = the kernel that loads operands straight from memory
  * (any row length), 1, 2, 4 or 8 = waves per panel of the kernel that stages Kmat rows in
  * LDS (used when a row has 64, 128, 256, 512 or 1024 bytes, or 32 bytes of 4-bit values, else

@@ -73,7 +73,8 @@ int choose_sddmm_waves(const mc_mat *mask, int batch, int row_bytes)
     const double groups = (double)mask->P * (batch > 0 ? batch : 1);
     const double target = (row_bytes <= 32) ? 4096.0 : 2048.0;
     int w = 1;
-    while (w < 8 && groups * w * 2 <= target && w * 2 <= avg) w *= 2;
+    // (few panels: down to one chunk per wave, e.g. 32 panels of 7 chunks: 2.8 us with 4 waves, 2.4 us with 8)
+    while (w < 8 && groups * w * 2 <= target && (w * 2 <= avg || (groups * w * 2 <= 512.0 && w < avg))) w *= 2;
     return w;
 }
 
@@ -100,6 +101,10 @@ void choose_variant(const mc_mat *A, int lhs_bits, int row_bytes, bool r4, int b
         }
     }
     if (b == 256 && r4) b = 128;
+    // few panels: narrower tiles until there is a workgroup for every compute unit (a 256 x 2304 matrix
+    // with rows of 512 bytes: 5.7 us on 256-byte tiles, 3.3 us on 64-byte ones)
+    if (g_variant_bnb == 0)
+        while (b > 64 && (double)A->P * ((row_bytes + b - 1) / b) * (batch > 0 ? batch : 1) < 256.0) b /= 2;
     if (w == 0) {
         const double groups = (double)A->P * ((row_bytes + b - 1) / b) * (batch > 0 ? batch : 1);
         // about 2048 waves on the chip; 4096 of the lighter ones that gather 64-byte pieces of nibbles
@@ -228,8 +233,11 @@ extern "C" int mc_mat_create(int M, int K, int V, int lhs_bits, const int32_t *r
         const double avg = lay.P ? (double)(lay.nslots / MC_CHUNK) / lay.P : 0.0;
         // A pattern-only mask (SDDMM: every item writes its own outputs, nothing to add up) is cut
         // as soon as a panel exceeds the average rounded up to 8 chunks.
+        // With fewer than 256 panels the pieces also get short enough to make 256 of them.
         const bool mask_only = (lhs_bits == 0);
-        const int cap = std::max(8, (int)std::ceil((mask_only ? 1.0 : 3.0) * avg));
+        double piece = (mask_only ? 1.0 : 3.0) * avg;
+        if (mask_only && lay.P < 256) piece = std::min(piece, (double)(lay.nslots / MC_CHUNK) / 256.0);
+        const int cap = std::max(8, (int)std::ceil(piece));
         if (A->max_panel_chunks > (mask_only ? cap : 2 * cap)) {
             try {
                 for (int p = 0; p < lay.P; ++p) {

@@ -269,6 +269,21 @@ def test_very_unequal_panels_use_work_items(prec):
         _check(case)
 
 
+@pytest.mark.parametrize("prec", ["L8R8", "L4R4", "L16R16"])
+@pytest.mark.parametrize("M,Nc,s", [(128, 4096, 0.5), (256, 2304, 0.7), (1024, 4096, 0.7), (8, 4096, 0.0)])
+def test_few_long_panels_are_cut_into_work_items(prec, M, Nc, s):
+    """Masks with fewer than 256 panels: the panels are cut into pieces of 8 chunks and more so that the
+    launch has a workgroup for (about) every compute unit; with the cutting switched off: whole panels."""
+    from paper_2209_06979_amd import binding as mc
+    case = wl.sddmm_case(M, Nc, 128, 8, s, prec, 7000 + M)
+    _check(case, variants=(-1, 0, 2, 8))
+    mc.set_spmm_splitting(False)
+    try:
+        _check(case)
+    finally:
+        mc.set_spmm_splitting(True)
+
+
 def test_config3_whole_grid_full_size():
     """Every point of BASELINE config 3: Kd in {64,128,256} x sparsity in {0.7,0.9,0.95} x {L8-R8, L4-R4} at
     4096 x 4096, V = 8, whole outputs compared (18 points)."""

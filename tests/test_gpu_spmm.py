@@ -150,6 +150,13 @@ def test_ablation_shape_and_tall_matrix():
     _check(wl.spmm_case(16384, 1024, 1024, 4, 0.9, "L8R4", 79))
 
 
+@pytest.mark.parametrize("prec", PRECS)
+@pytest.mark.parametrize("M,K,N,s", [(128, 4096, 512, 0.5), (256, 2304, 512, 0.7), (1024, 4096, 256, 0.7), (8, 4096, 256, 0.0)])
+def test_few_panels_take_narrow_tiles(prec, M, K, N, s):
+    """Fewer panels than compute units: the automatic choice narrows the row tiles (same results)."""
+    _check(wl.spmm_case(M, K, N, 8, s, prec, 7100 + M))
+
+
 @pytest.mark.parametrize("bnb,waves", [(64, 1), (128, 2), (256, 4)])
 def test_gather_probe_fetches_the_rows_spmm_would(bnb, waves):
     """The gather-only measurement kernel: every workgroup reports the first word of its staged rows."""
