@@ -103,8 +103,13 @@ void choose_variant(const mc_mat *A, int lhs_bits, int row_bytes, bool r4, int b
     if (b == 256 && r4) b = 128;
     // few panels: narrower tiles until there is a workgroup for every compute unit (a 256 x 2304 matrix
     // with rows of 512 bytes: 5.7 us on 256-byte tiles, 3.3 us on 64-byte ones)
-    if (g_variant_bnb == 0)
-        while (b > 64 && (double)A->P * ((row_bytes + b - 1) / b) * (batch > 0 ? batch : 1) < 256.0) b /= 2;
+    // (rows of nibbles, fewer than 512 panels: until the panels' chunks can occupy 4096 of the light waves)
+    if (g_variant_bnb == 0) {
+        const double nb = (batch > 0 ? batch : 1), per_group = std::min(8.0, std::max(1.0, avg));
+        while (b > 64 && (double)A->P * ((row_bytes + b - 1) / b) * nb < 256.0) b /= 2;
+        if (r4 && A->P < 512)
+            while (b > 64 && (double)A->P * ((row_bytes + b - 1) / b) * nb * per_group < 4096.0) b /= 2;
+    }
     if (w == 0) {
         const double groups = (double)A->P * ((row_bytes + b - 1) / b) * (batch > 0 ? batch : 1);
         // about 2048 waves on the chip; 4096 of the lighter ones that gather 64-byte pieces of nibbles
