@@ -65,7 +65,7 @@ void free_device(mc_mat *A)
 }
 
 // Waves per panel for SDDMM: enough to put about 2048 waves on the chip (4096 of the light ones
-// that stage rows of 32 bytes), at most one per chunk.
+// that stage rows of 32 bytes), fewer than twice the chunks of an average panel.
 int choose_sddmm_waves(const mc_mat *mask, int batch, int row_bytes)
 {
     if (g_sddmm_waves >= 0) return g_sddmm_waves;
@@ -73,8 +73,8 @@ int choose_sddmm_waves(const mc_mat *mask, int batch, int row_bytes)
     const double groups = (double)mask->P * (batch > 0 ? batch : 1);
     const double target = (row_bytes <= 32) ? 4096.0 : 2048.0;
     int w = 1;
-    // (few panels: down to one chunk per wave, e.g. 32 panels of 7 chunks: 2.8 us with 4 waves, 2.4 us with 8)
-    while (w < 8 && groups * w * 2 <= target && (w * 2 <= avg || (groups * w * 2 <= 512.0 && w < avg))) w *= 2;
+    // (down to one chunk per wave, e.g. 32 panels of 7 chunks: 2.8 us with 4 waves, 2.4 us with 8)
+    while (w < 8 && groups * w * 2 <= target && w < avg) w *= 2;
     return w;
 }
 
