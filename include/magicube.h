@@ -332,13 +332,17 @@ int mc_set_sddmm_variant(int waves);
  * 1 = a workgroup per panel also for short panels, 2 = always the kernel for panels of any
  * length (three passes).  Same codes up to fp32 summation order.  Process-wide. */
 int mc_set_softmax_variant(int variant);
-/* Attention path: 0 = automatic (a single fused kernel when dk is 64 or 128
- * and no panel holds more than 2048 vectors -- one, two or four waves per (panel, head) for panels of up to 512,
- * 1024, 2048 vectors -- else the pipeline of separate kernels), 1 = always the
- * pipeline SDDMM -> softmax -> SpMM of separate kernels, 2 = the fused kernel with one head per
- * workgroup even for token-major tensors, 3 / 4 = the fused kernel with at least two / with
- * four waves per (panel, head) whatever the panel length (heads per workgroup as in 0).  All give the same result up to fp32 summation
- * order in the softmax.  Process-wide; MC_EINVAL for other values. */
+/* Attention path: 0 = automatic (a single fused kernel when dk is 64 or 128 and no panel holds
+ * more than 2048 vectors -- one, two or four waves per (panel, head) for panels of up to 512,
+ * 1024, 2048 vectors, more waves than that when the launch is small; two neighbouring heads per
+ * workgroup for token-major tensors once the launch has 2048 (panel, head) units -- else the
+ * pipeline of separate kernels), 1 = always the pipeline SDDMM -> softmax -> SpMM of separate
+ * kernels.  The remaining modes pin parts of the automatic choice (for tests and measurements):
+ * 2 = the fused kernel with one head per workgroup even for token-major tensors, waves by panel
+ * length alone; 3 / 4 = the fused kernel with at least two / with four waves per (panel, head)
+ * whatever the panel length, 5 = waves by panel length alone -- 3, 4 and 5 with two heads per
+ * workgroup wherever the layout allows it, whatever the size of the launch.  All give the same
+ * result up to fp32 summation order in the softmax.  Process-wide; MC_EINVAL for other values. */
 int mc_set_attention_mode(int mode);
 
 #ifdef __cplusplus

@@ -13,7 +13,7 @@ namespace {
 
 int g_variant_bnb = 0, g_variant_waves = 0;
 int g_sddmm_waves = -1;   // -1 automatic, 0 direct-load kernel, 1/2/4/8 waves of the LDS-staged kernel
-int g_attention_mode = 0; // 0 automatic, 1 always the pipeline of separate kernels, 2..4 see mc_set_attention_mode
+int g_attention_mode = 0; // 0 automatic, 1 always the pipeline of separate kernels, 2..5 see mc_set_attention_mode
 int g_spmm_items = 1;     // 1: matrices with very unequal panels run through their work items
 int g_softmax_variant = 0; // 0: automatic; 1: a workgroup per panel; 2: the any-length softmax kernel always
 int g_spmm_stages = 2;    // chunks in flight per wave of the SpMM kernel (1 or 2)
@@ -188,7 +188,7 @@ extern "C" int mc_set_softmax_variant(int variant)
 
 extern "C" int mc_set_attention_mode(int mode)
 {
-    if (mode < 0 || mode > 4) return MC_EINVAL;
+    if (mode < 0 || mode > 5) return MC_EINVAL;
     g_attention_mode = mode;
     return MC_OK;
 }
@@ -698,14 +698,26 @@ extern "C" int mc_sparse_attention_out(const void *Q_dev, const void *Km_dev, co
         f.P = mask->P; f.heads = heads; f.batch = batch;
         // a wave keeps at most 8 chunks of scores in registers: longer panels are shared by 2 or 4 waves
         int wpp = (mask->max_panel_chunks > 16) ? 4 : (mask->max_panel_chunks > 8 ? 2 : 1);
-        if (g_attention_mode == 3 && wpp < 2) wpp = 2;
-        if (g_attention_mode == 4) wpp = 4;
-        // neighbouring heads contiguous inside a token, rows of at most 64 bytes: two heads per workgroup,
-        // 128-byte gathers (not for 16-bit codes with 4-bit inputs, whose output tile does not fit that
-        // kernel's stages)
+        // neighbouring heads contiguous inside a token, rows of at most 64 bytes: two heads per workgroup can
+        // gather 128 bytes per token (not for 16-bit codes with 4-bit inputs, whose output tile does not fit
+        // that kernel's stages)
         const bool short_rows = dk == 64 || qkv_bits == 4;
-        const int hpg = (g_attention_mode != 2 && short_rows && head_stride == dk && heads % 2 == 0 &&
-                         !(p_bits == 16 && qkv_bits == 4)) ? 2 : 1;
+        const bool pairs = short_rows && head_stride == dk && heads % 2 == 0 && !(p_bits == 16 && qkv_bits == 4);
+        int hpg;
+        if (g_attention_mode == 0) {
+            // Halving the gather requests pays once the launch fills the chip (2048 (panel, head) units and
+            // more: 13.3 against 15.6 us for 4096 of them; 5.0 against 4.7 us for 128).  Smaller launches get
+            // more waves per unit instead, until about 2048 waves are in flight and while every wave still
+            // has a chunk (256 units of 7 chunks: 5.9 us with one wave each, 4.5 us with four).
+            const int64_t units = (int64_t)mask->P * heads * batch;
+            const double avg = mask->P ? (double)(mask->nslots / MC_CHUNK) / mask->P : 0.0;
+            hpg = (pairs && units >= 2048) ? 2 : 1;
+            if (hpg == 1) while (wpp < 4 && units * wpp * 2 <= 2048 && wpp * 2 <= avg) wpp *= 2;
+        } else {
+            if (g_attention_mode == 3 && wpp < 2) wpp = 2;
+            if (g_attention_mode == 4) wpp = 4;
+            hpg = (g_attention_mode != 2 && pairs) ? 2 : 1;
+        }
         MC_HIP(launch_attention_fused(f, hpg, wpp, p_bits, qkv_bits, dk, s));
         return MC_OK;
     }

@@ -193,7 +193,7 @@ def _attention_f16(heads, L, dk, sparsity, seed, p_bits=8, qkv_bits=8, token_maj
 
 
 @pytest.mark.parametrize("token_major", [False, True])
-@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("mode", [0, 1, 5])
 def test_attention_fp16_output_small(token_major, mode):
     _attention_f16(2, 256, 64, 0.75, 6600, token_major=token_major, mode=mode)
     _attention_f16(2, 1024, 64, 0.6, 6601, token_major=token_major, mode=mode)     # 7 chunks, ragged tail
@@ -203,10 +203,10 @@ def test_attention_fp16_output_small(token_major, mode):
 @pytest.mark.parametrize("p_bits,qkv_bits", [(16, 8), (8, 4), (16, 4)])
 def test_attention_fp16_output_variants(p_bits, qkv_bits):
     _attention_f16(2, 512, 64, 0.8, 6610, p_bits, qkv_bits)
-    _attention_f16(2, 512, 64, 0.8, 6611, p_bits, qkv_bits, token_major=True)
+    _attention_f16(2, 512, 64, 0.8, 6611, p_bits, qkv_bits, token_major=True, mode=5)      # two heads per workgroup
     _attention_f16(2, 2048, 64, 0.6, 6612, p_bits, qkv_bits)                       # two waves per (panel, head)
-    _attention_f16(2, 2048, 64, 0.6, 6613, p_bits, qkv_bits, token_major=True)
-    _attention_f16(2, 2048, 64, 0.3, 6614, p_bits, qkv_bits, token_major=True)     # four waves per (panel, head)
+    _attention_f16(2, 2048, 64, 0.6, 6613, p_bits, qkv_bits, token_major=True, mode=3)
+    _attention_f16(2, 2048, 64, 0.3, 6614, p_bits, qkv_bits, token_major=True, mode=4)     # four waves per (panel, head)
 
 
 @pytest.mark.parametrize("p_bits", [8, 16])
@@ -215,12 +215,12 @@ def test_attention_fp16_output_head_dimension_128(p_bits):
     _attention_f16(2, 1024, 128, 0.6, 6631, p_bits, 8, token_major=True)
     _attention_f16(2, 2048, 128, 0.6, 6632, p_bits, 8)                             # two waves per (panel, head)
     _attention_f16(1, 2048, 128, 0.3, 6633, p_bits, 8, token_major=True)           # four waves
-    _attention_f16(2, 1024, 128, 0.6, 6634, p_bits, 4, token_major=True)           # nibbles; two heads per workgroup (8-bit codes)
+    _attention_f16(2, 1024, 128, 0.6, 6634, p_bits, 4, token_major=True, mode=5)   # nibbles; two heads per workgroup (8-bit codes)
     _attention_f16(2, 2048, 128, 0.6, 6635, p_bits, 4)
 
 
 def test_attention_fp16_output_batched_and_config5():
-    _attention_f16(4, 512, 64, 0.8, 6620, batch=3, token_major=True)
+    _attention_f16(4, 512, 64, 0.8, 6620, batch=3, token_major=True, mode=5)
     _attention_f16(4, 512, 64, 0.8, 6621, batch=2, mode=1)
     _attention_f16(8, 4096, 64, 0.9, wl.seed_for(5, 2), token_major=True)
 

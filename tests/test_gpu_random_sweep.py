@@ -97,7 +97,7 @@ def test_random_attention(seed):
         dk = int(rng.choice([32, 64, 64, 64, 128]))
         s = float(rng.choice([0.3, 0.6, 0.9]))
         p_bits, qkv_bits = int(rng.choice([8, 16])), int(rng.choice([8, 4]))
-        mode, tmaj, f16 = int(rng.choice([0, 1, 2, 3, 4])), bool(rng.integers(2)), bool(rng.integers(2))
+        mode, tmaj, f16 = int(rng.choice([0, 1, 2, 3, 4, 5])), bool(rng.integers(2)), bool(rng.integers(2))
         c = wl.attention_case(heads, L, dk, 8, s, int(rng.integers(1 << 30)))
         quant = wl.quantize_inputs_int4 if qkv_bits == 4 else wl.quantize_inputs_int8
         (q, s_q), (k, s_k), (v, s_v) = (quant(c[nm]) for nm in "qkv")

@@ -154,7 +154,7 @@ def _attention_check(heads, L, dk, sparsity, seed, mode=0, token_major=False):
 
 
 @pytest.mark.parametrize("token_major", [False, True])
-@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("mode", [0, 1, 5])   # 5: two heads per workgroup on token-major tensors also in small launches
 def test_attention_small(mode, token_major):
     _attention_check(2, 256, 64, 0.75, 1200, mode, token_major)   # one chunk per panel
     _attention_check(3, 512, 32, 0.9, 1201, mode, token_major)    # dk = 32: always the kernel pipeline
@@ -221,7 +221,7 @@ def test_attention_ragged_rows():
     want, _, probs, _ = oracle.attention(q8, k8, v8, rp, ci, V, s_q, s_k, s_v, s_p)
     amb = _tie_ambiguous(probs, s_p).reshape(heads, -1, V)
     mask = mc.SparseMatrix(L, L, V, rp, ci)
-    for mode, token_major in ((0, False), (0, True), (1, False), (1, True)):
+    for mode, token_major in ((0, False), (0, True), (1, False), (1, True), (5, True), (3, True)):
         mc.set_attention_mode(mode)
         out = _layout(np.full((heads, L, dk), np.nan, np.float32), token_major)
         O = mc.sparse_attention(_layout(q8, token_major), _layout(k8, token_major), _layout(v8, token_major), mask,

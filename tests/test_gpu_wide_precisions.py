@@ -210,7 +210,7 @@ def _attention_variant_check(heads, L, dk, sparsity, seed, p_bits, qkv_bits, tok
 
 @pytest.mark.parametrize("p_bits,qkv_bits", [(16, 8), (8, 4), (16, 4)])
 @pytest.mark.parametrize("token_major", [False, True])
-@pytest.mark.parametrize("mode", [0, 1])                      # fused kernel where there is one / kernel pipeline
+@pytest.mark.parametrize("mode", [0, 1, 5])                   # automatic / kernel pipeline / two heads per workgroup
 def test_attention_variants_small(p_bits, qkv_bits, token_major, mode):
     _attention_variant_check(2, 256, 64, 0.75, 4000, p_bits, qkv_bits, token_major, mode)   # one chunk per panel
     _attention_variant_check(3, 512, 32, 0.9, 4001, p_bits, qkv_bits, token_major, mode)    # dk = 32: pipeline
@@ -238,8 +238,9 @@ def test_attention_4bit_inputs_head_dimension_128(p_bits, token_major, mode):
     _attention_variant_check(1, 2048, 128, 0.4, 4022, p_bits, 4, token_major, mode)   # 20 chunks: four waves in every mode
 
 
+@pytest.mark.parametrize("mode", [0, 3, 4])   # 3, 4: two heads per workgroup whatever the size of the launch
 @pytest.mark.parametrize("p_bits,qkv_bits,dk", [(8, 8, 64), (16, 8, 64), (8, 4, 64), (8, 4, 128)])
-def test_attention_two_heads_per_workgroup_sharing_long_panels(p_bits, qkv_bits, dk):
+def test_attention_two_heads_per_workgroup_sharing_long_panels(p_bits, qkv_bits, dk, mode):
     """Token-major tensors with panels of more than 512 vectors: pairs of waves (one wave per head) share the
     chunks of a panel and every wave goes through the chunk loops as often as the busiest pair."""
     for heads, L, sp, seed in ((2, 2048, 0.6, 4500),    # 13 chunks: pairs with 7 and 6
@@ -247,7 +248,7 @@ def test_attention_two_heads_per_workgroup_sharing_long_panels(p_bits, qkv_bits,
                                (4, 2048, 0.4, 4501),    # 20 chunks: four pairs with 5 each
                                (2, 2048, 0.17, 4504),   # 27 chunks: 7, 7, 7, 6
                                (2, 2048, 0.0, 4502)):   # 32 chunks: the longest fused panel
-        _attention_variant_check(heads, L, dk, sp, seed, p_bits, qkv_bits, True, 0)
+        _attention_variant_check(heads, L, dk, sp, seed, p_bits, qkv_bits, True, mode)
 
 
 @pytest.mark.parametrize("p_bits,qkv_bits", [(16, 8), (8, 4)])
@@ -259,7 +260,7 @@ def test_attention_variants_config5_shape(p_bits, qkv_bits, mode):
 
 @pytest.mark.parametrize("p_bits,qkv_bits", [(8, 8), (16, 8), (8, 4)])
 @pytest.mark.parametrize("token_major", [False, True])
-@pytest.mark.parametrize("mode", [0, 1, 3])
+@pytest.mark.parametrize("mode", [0, 1, 3, 5])
 def test_attention_codes_saturate_at_the_largest_code(p_bits, qkv_bits, token_major, mode):
     """A softmax scale finer than 1 / (largest code): every probability above code_max * s_p must
     become the largest code (127 or 32639), not wrap or run on to 255 / 65535."""
@@ -323,8 +324,9 @@ def test_sparse_softmax_16_bit_codes():
     mask.close()
 
 
+@pytest.mark.parametrize("mode", [0, 3])   # 3: two heads per workgroup on token-major tensors whatever the size of the launch
 @pytest.mark.parametrize("L,dk,sparsity", [(1536, 64, 0.5), (2048, 64, 0.3), (1536, 128, 0.5)])
-def test_attention_batched_long_panels_equal_item_by_item(L, dk, sparsity):
+def test_attention_batched_long_panels_equal_item_by_item(L, dk, sparsity, mode):
     """Batches whose panels need two or four waves per (panel, head), in both tensor orders."""
     import torch
     from paper_2209_06979_amd import binding as mc
@@ -339,14 +341,21 @@ def test_attention_batched_long_panels_equal_item_by_item(L, dk, sparsity):
                 x = torch.from_numpy(np.ascontiguousarray(t)).cuda().reshape(B, heads, L, -1)
                 return x.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3) if token_major else x
             qd, kd, vd = dev(q), dev(k), dev(v)
-            print(f"batched attention L={L} dk={dk} s={sparsity} token_major={token_major}", flush=True)
+            print(f"batched attention L={L} dk={dk} s={sparsity} token_major={token_major} mode={mode}", flush=True)
+            mc.set_attention_mode(mode)
             O = mc.sparse_attention(qd, kd, vd, mask, s_q, s_k, s_v, s_p)
             torch.cuda.synchronize()
             assert O.shape == (B, heads, L, dk) and bool(torch.isfinite(O).all())
             for b in range(B):
                 Ob = mc.sparse_attention(qd[b], kd[b], vd[b], mask, s_q, s_k, s_v, s_p)
                 torch.cuda.synchronize()
-                assert torch.equal(O[b], Ob), b
+                if mode == 0:
+                    # the automatic choice gives a smaller launch more waves per (panel, head): the softmax
+                    # sums may be added in another order, and a code next to a rounding boundary may move
+                    d = (O[b] - Ob).abs()
+                    assert float((d > 1e-6).float().mean()) < 0.02 and float(d.max()) < 0.05
+                else:
+                    assert torch.equal(O[b], Ob), b
             # and the single items against the kernel pipeline, up to the order of the fp32 sums
             mc.set_attention_mode(1)
             Op = mc.sparse_attention(qd[0], kd[0], vd[0], mask, s_q, s_k, s_v, s_p)
@@ -363,7 +372,8 @@ def test_attention_batched_long_panels_equal_item_by_item(L, dk, sparsity):
 @pytest.mark.parametrize("p_bits,qkv_bits", [(8, 8), (16, 8), (8, 4)])
 def test_attention_batched_equals_item_by_item(p_bits, qkv_bits, mode):
     """A batch sharing one mask, in the (batch, L, heads, dk) layout of a projection's output and in the
-    contiguous (batch, heads, L, dk) one: every item must equal the single-item call bit for bit."""
+    contiguous (batch, heads, L, dk) one: every item must equal the single-item call bit for bit (the
+    panels here have two chunks, which leaves the automatic choice nothing to vary with the launch size)."""
     import torch
     from paper_2209_06979_amd import binding as mc
     B, heads, L, dk, V = 3, 4, 512, 64, 8
