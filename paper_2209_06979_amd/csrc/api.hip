@@ -98,6 +98,7 @@ void choose_variant(const mc_mat *A, int lhs_bits, int row_bytes, bool r4, int b
             // wide tiles for panels of 8 chunks and more; with a two-plane A and V = 8 (16 output rows per
             // tile) only for long rows
             if (row_bytes >= 256 && avg >= 8.0 && (lhs_bits == 8 || A->V < 8 || row_bytes >= 512)) b = 256;
+            if (row_bytes >= 1024 && avg >= 6.0) b = 256; // eight and more 128-byte tiles would each re-read A
         }
     }
     if (b == 256 && r4) b = 128;
