@@ -65,13 +65,13 @@ void free_device(mc_mat *A)
 }
 
 // Waves per panel for SDDMM: enough to put about 2048 waves on the chip (4096 of the light ones
-// that stage rows of 32 bytes), fewer than twice the chunks of an average panel.
-int choose_sddmm_waves(const mc_mat *mask, int batch, int row_bytes)
+// that stage rows of 32 bytes, or 64 bytes of nibbles), fewer than twice the chunks of an average panel.
+int choose_sddmm_waves(const mc_mat *mask, int batch, int row_bytes, int bits)
 {
     if (g_sddmm_waves >= 0) return g_sddmm_waves;
     const double avg = mask->P ? (double)(mask->nslots / MC_CHUNK) / mask->P : 0.0;
     const double groups = (double)mask->P * (batch > 0 ? batch : 1);
-    const double target = (row_bytes <= 32) ? 4096.0 : 2048.0;
+    const double target = (row_bytes <= 32 || (bits == 4 && row_bytes <= 64)) ? 4096.0 : 2048.0;
     int w = 1;
     // (down to one chunk per wave, e.g. 32 panels of 7 chunks: 2.8 us with 4 waves, 2.4 us with 8)
     while (w < 8 && groups * w * 2 <= target && w < avg) w *= 2;
@@ -472,7 +472,7 @@ int sddmm_impl(const void *Q_dev, int ldq, const void *Kmat_dev, int ldk, int Kd
     a.P = mask->P; a.V = mask->V; a.batch = 1;
     a.lhs_unsigned = (flags & MC_LHS_UNSIGNED) ? 1 : 0; a.rhs_unsigned = (flags & MC_RHS_UNSIGNED) ? 1 : 0;
     if (mask->n_items && g_spmm_items) { a.items = mask->d_items; a.n_units = mask->n_items; } // very unequal panels
-    MC_HIP(launch_sddmm(bits, a, choose_sddmm_waves(mask, 1, a.row_bytes), static_cast<hipStream_t>(stream)));
+    MC_HIP(launch_sddmm(bits, a, choose_sddmm_waves(mask, 1, a.row_bytes, bits), static_cast<hipStream_t>(stream)));
     return MC_OK;
 }
 } // namespace
@@ -586,7 +586,7 @@ int attention_pipeline(const uint8_t *Q, const uint8_t *Km, const uint8_t *Vm, i
     d.row_bytes = row_bytes; d.S = scores; d.S_batch_stride = nnz;
     d.P = mask->P; d.V = 8; d.batch = heads;
     if (mask->n_items && g_spmm_items) { d.items = mask->d_items; d.n_units = mask->n_items; } // very unequal panels
-    MC_HIP(launch_sddmm(qkv_bits, d, choose_sddmm_waves(mask, heads, row_bytes), s));
+    MC_HIP(launch_sddmm(qkv_bits, d, choose_sddmm_waves(mask, heads, row_bytes, qkv_bits), s));
 
     // the softmax writes its codes in the layout the SpMM reads (Section 4.3 lets the producer
     // pick the output format by the consumer)
