@@ -28,10 +28,10 @@
 //          a token with ONE request.  The L2 serves a 128-byte line at the cost of a 64-byte
 //          half, so this halves the number of gather requests, which is what bounds the
 //          kernel.  Each wave copies half of a chunk's rows; one s_barrier per chunk.
-// LDS rows are as long as a gathered row (ROWB = 64*HPW bytes, 128 for head dimension 128); slot s
-// of a chunk lives in row (s % NIT) * (64/NIT) + s / NIT (NIT = ROWB/16 copy instructions per
-// chunk, so that the column indices a lane needs are consecutive) and its 16-byte segments are XOR-swizzled with s % NIT so that rows read
-// together fall into different banks.
+// LDS rows are as long as a gathered row (ROWB = HPW times the bytes of one head's row: 32 .. 128);
+// slot s of a chunk lives in row (s % NIT) * (64/NIT) + s / NIT (NIT = ROWB/16 copy instructions
+// per chunk, so that the column indices a lane needs are consecutive) and its 16-byte segments are
+// XOR-swizzled with s % NIT so that rows read together fall into different banks.
 #include "internal.h"
 #include "lds_async.h"
 
