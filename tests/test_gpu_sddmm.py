@@ -199,6 +199,14 @@ def test_attention_head_dimension_128_long_panels(token_major):
     _attention_check(4, 4096, 128, 0.9, 1235, 0, token_major)      # the bench layer's pattern at head dimension 128
 
 
+def test_attention_long_sequences():
+    """Sequences of 16384 and 32768 tokens (2048 and 4096 panels per head)."""
+    _attention_check(2, 16384, 64, 0.97, 1240, 0, True)      # 492 vectors per panel
+    _attention_check(2, 16384, 128, 0.95, 1241, 0, False)    # 819 vectors: two waves per (panel, head), 128-byte rows
+    _attention_check(1, 32768, 64, 0.98, 1242, 0, False)     # 655 vectors
+    _attention_check(2, 16384, 64, 0.9, 1243, 0, True)       # 1638 vectors: four waves
+
+
 @pytest.mark.parametrize("token_major", [False, True])
 @pytest.mark.parametrize("mode", [0, 1])
 def test_attention_config5_full(mode, token_major):
