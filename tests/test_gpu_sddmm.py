@@ -292,6 +292,13 @@ def test_few_long_panels_are_cut_into_work_items(prec, M, Nc, s):
         mc.set_spmm_splitting(True)
 
 
+@pytest.mark.parametrize("prec", ["L8R8", "L4R4", "L16R16"])
+def test_large_masks(prec):
+    """Masks of 16384 x 16384 (98 % sparse) and 8192 x 32768 (V = 4, 99 % sparse)."""
+    _check(wl.sddmm_case(16384, 16384, 64, 8, 0.98, prec, 7300))
+    _check(wl.sddmm_case(8192, 32768, 128, 4, 0.99, prec, 7301))
+
+
 def test_config3_whole_grid_full_size():
     """Every point of BASELINE config 3: Kd in {64,128,256} x sparsity in {0.7,0.9,0.95} x {L8-R8, L4-R4} at
     4096 x 4096, V = 8, whole outputs compared (18 points)."""

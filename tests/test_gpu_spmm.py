@@ -150,6 +150,13 @@ def test_ablation_shape_and_tall_matrix():
     _check(wl.spmm_case(16384, 1024, 1024, 4, 0.9, "L8R4", 79))
 
 
+@pytest.mark.parametrize("prec", ["L8R8", "L4R4", "L16R8"])
+def test_large_dimensions(prec):
+    """16384 x 16384 at 98 % sparsity (2048 panels, K four times the sweep's) and a tall 32768 x 4096 one with V = 2."""
+    _check(wl.spmm_case(16384, 16384, 128, 8, 0.98, prec, 7200))
+    _check(wl.spmm_case(32768, 4096, 64, 2, 0.95, prec, 7201))
+
+
 @pytest.mark.parametrize("prec", PRECS)
 @pytest.mark.parametrize("M,K,N,s", [(128, 4096, 512, 0.5), (256, 2304, 512, 0.7), (1024, 4096, 256, 0.7), (8, 4096, 256, 0.0)])
 def test_few_panels_take_narrow_tiles(prec, M, K, N, s):
