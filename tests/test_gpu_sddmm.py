@@ -292,6 +292,33 @@ def test_few_long_panels_are_cut_into_work_items(prec, M, Nc, s):
         mc.set_spmm_splitting(True)
 
 
+@pytest.mark.parametrize("waves", [-1, 0])
+@pytest.mark.parametrize("prec", ["L8R8", "L4R4"])
+def test_kmat_spanning_more_than_4_gib(prec, waves):
+    """Rows of Kmat a mebibyte apart: the last rows start beyond 2^32 bytes (64-bit row offsets)."""
+    import torch
+    from paper_2209_06979_amd import binding as mc
+    Nc, ld = 4128, (1 << 20) + 16
+    c = wl.sddmm_case(256, Nc, 128, 8, 0.9, prec, 7500)
+    want = run_sddmm_oracle(c)
+    Kh = torch.from_numpy(c["Kmat"])
+    big = torch.empty((Nc, ld), dtype=Kh.dtype, device="cuda")
+    assert big.element_size() == 1 and (Nc - 32) * ld > 1 << 32
+    Kv = big[:, :Kh.shape[1]]
+    Kv.copy_(Kh.cuda())
+    mask = mc.SparseMatrix(256, Nc, 8, c["row_ptr"], c["col_idx"])
+    print(f"sddmm {prec} waves={waves} with Kmat rows {ld} bytes apart", flush=True)
+    mc.set_sddmm_variant(waves)
+    try:
+        got = mc.sddmm(torch.from_numpy(c["Q"]).cuda(), Kv, mask, prec)
+        torch.cuda.synchronize()
+    finally:
+        mc.set_sddmm_variant(-1)
+        mask.close()
+    assert np.array_equal(got.cpu().numpy(), want)
+    del big
+
+
 @pytest.mark.parametrize("prec", ["L8R8", "L4R4", "L16R16"])
 def test_large_masks(prec):
     """Masks of 16384 x 16384 (98 % sparse) and 8192 x 32768 (V = 4, 99 % sparse)."""

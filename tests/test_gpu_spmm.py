@@ -150,6 +150,34 @@ def test_ablation_shape_and_tall_matrix():
     _check(wl.spmm_case(16384, 1024, 1024, 4, 0.9, "L8R4", 79))
 
 
+@pytest.mark.parametrize("prec", ["L8R8", "L8R4"])
+def test_dense_operand_spanning_more_than_4_gib(prec):
+    """Rows of B a mebibyte apart: the last row starts beyond 2^32 bytes, which takes the kernel form with
+    64-bit row offsets (one chunk in flight)."""
+    import torch
+    from paper_2209_06979_amd import binding as mc
+    K, ld = 4097, (1 << 20) + 16
+    c = wl.spmm_case(256, K - 1, 128, 8, 0.9, prec, 7400)
+    # the patterns of the generator address K - 1 columns; one more vector per panel names the last row
+    rp = c["row_ptr"] + np.arange(len(c["row_ptr"]), dtype=np.int32)
+    ci = np.concatenate([np.r_[c["col_idx"][a:b], K - 1] for a, b in zip(c["row_ptr"][:-1], c["row_ptr"][1:])]).astype(np.int32)
+    vals = np.concatenate([np.concatenate([c["values"][a:b], c["values"][a:a + 1]]) for a, b in zip(c["row_ptr"][:-1], c["row_ptr"][1:])])
+    Bh = np.concatenate([c["B"], c["B"][:1]])
+    case = dict(c, K=K, row_ptr=rp, col_idx=ci, values=np.ascontiguousarray(vals), B=Bh)
+    want = run_spmm_oracle(case)
+    A = mc.SparseMatrix(256, K, 8, rp, ci, case["values"], mc.LHS_BITS[prec])
+    big = torch.empty((K, ld), dtype=torch.from_numpy(Bh).dtype, device="cuda")
+    assert big.element_size() == 1 and (K - 1) * ld > 1 << 32
+    Bv = big[:, :Bh.shape[1]]
+    Bv.copy_(torch.from_numpy(Bh).cuda())
+    print(f"spmm {prec} with B rows {ld} bytes apart", flush=True)
+    got = mc.spmm(A, Bv, prec)
+    torch.cuda.synchronize()
+    assert np.array_equal(got.cpu().numpy(), want)
+    A.close()
+    del big
+
+
 @pytest.mark.parametrize("prec", ["L8R8", "L4R4", "L16R8"])
 def test_large_dimensions(prec):
     """16384 x 16384 at 98 % sparsity (2048 panels, K four times the sweep's) and a tall 32768 x 4096 one with V = 2."""
