@@ -479,6 +479,14 @@ def measure_extras(mc, torch, prob, stream, reps, up):
                                                                 out=O32, workspace=ws)] * reps)
     mc.set_attention_mode(0)
     wide["attention_8b8b_three_kernels"] = dict(us=round(us, 2), eff_tops=round(HEADS * 2 * (2 * amask.nvec * V * DK) / us / 1e6, 1))
+    # the softmax step on its own (8 heads of scores in, int8 codes out; 5 bytes per stored score)
+    nsc = amask.nvec * V
+    Ssm = torch.randint(-60000, 60000, (HEADS, nsc), dtype=torch.int32, device="cuda")
+    csm = torch.empty((HEADS, nsc), dtype=torch.int8, device="cuda")
+    us = time_graph(torch, stream, [lambda: mc.sparse_softmax(amask, Ssm, 2.5e-4, 127.0, out=csm)] * reps)
+    wide["sparse_softmax_8_heads"] = dict(us=round(us, 2), gbs=round(HEADS * nsc * 5 / us / 1e3, 1),
+                                          hbm_frac=round(HEADS * nsc * 5 / us / 1e3 / HBM_PEAK_GBS, 3))
+    del Ssm, csm
     # the same layer with head dimension 128 (rows of 128 bytes): the fused kernel and the three kernels
     x128, s128 = wl.quantize_inputs_int8(wl.normal_fp32((HEADS, L_ATT, 128), wl.seed_for(5, 9)))
     q128 = tmaj(x128) # serves as Q, K and V: timing only
