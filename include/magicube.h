@@ -33,6 +33,12 @@
  *     throws or aborts.  Argument checks are done on the host before any launch.
  *   - Dense operands are row-major.  int4 dense operands hold two elements per byte
  *     along a row (same nibble order as above); leading dimensions are in ELEMENTS.
+ *   - A compute call must be made with the device current on which its mc_mat was created
+ *     (MC_EINVAL otherwise; mc_last_error_detail() names both devices).
+ *   - The library keeps no process-wide mutable state.  Kernel-variant choices are automatic;
+ *     a caller that wants to pin them passes an mc_options to an ..._ex entry point, or sets
+ *     defaults for its own thread (mc_set_thread_options).  Calls from different host threads
+ *     never influence each other.
  */
 #ifndef MAGICUBE_H
 #define MAGICUBE_H
@@ -74,6 +80,32 @@ const char *mc_version(void);
 /* After a call returned MC_EHIP on this thread: which HIP call failed and its message
  * (empty string if none yet).  The pointer stays valid for the thread's lifetime. */
 const char *mc_last_error_detail(void);
+
+/* ------------------------------------------------------------------------------------
+ * Kernel-variant choices of one call.  All zero (mc_options_init) = automatic everywhere; the
+ * result of a computation never depends on them (softmax-based results: up to fp32 summation
+ * order).  They exist for tests and measurements.
+ * ---------------------------------------------------------------------------------- */
+typedef struct mc_options {
+    int spmm_row_tile_bytes; /* 0 automatic, else 64, 128 or 256 bytes of a B row per workgroup            */
+    int spmm_waves;          /* 0 automatic, else 1, 2, 4 or 8 wavefronts sharing a panel's chunks         */
+    int spmm_stages;         /* 0 automatic (two chunks of gathered rows in flight per wave when B spans
+                                less than 4 GiB and no wave has more than 4 chunks), 1 or 2               */
+    int spmm_splitting;      /* 0 automatic (very unequal panels are cut into work items, see
+                                mc_set_spmm_splitting), -1 never                                           */
+    int spmm_slab;           /* reserved, must be -1, 0 or 1                                               */
+    int sddmm_waves;         /* 0 automatic, -1 the kernel that loads operands straight from memory,
+                                1, 2, 4 or 8 waves per panel of the kernel that stages Kmat rows in LDS   */
+    int softmax_variant;     /* 0 automatic, 1 a workgroup per panel also for short panels, 2 always the
+                                any-length kernel                                                          */
+    int attention_mode;      /* 0 automatic, 1..5 as described at mc_set_attention_mode                    */
+} mc_options;
+/* Sets every field to automatic. */
+void mc_options_init(mc_options *o);
+/* Defaults of the CALLING THREAD for entry points that take no options argument (NULL: back to
+ * automatic).  MC_EINVAL if a field holds a value outside its list; nothing changes then. */
+int mc_set_thread_options(const mc_options *o);
+int mc_get_thread_options(mc_options *o);
 
 /* ------------------------------------------------------------------------------------
  * Host-side format builder (Section 4.1).  Pure host code: usable without a GPU.
@@ -124,7 +156,11 @@ int mc_unpack_host(int M, int K, int V, int lhs_bits, const int32_t *panel_ptr, 
 int mc_mat_create(int M, int K, int V, int lhs_bits, const int32_t *row_ptr, const int32_t *col_idx,
                   const void *values, void *stream, mc_mat **out);
 /* Replaces the values from a DEVICE array in interchange order (nvec*V elements of the
- * matrix's width; e.g. the output of a softmax).  Asynchronous on `stream`. */
+ * matrix's width; e.g. the output of a softmax).  Asynchronous on `stream`.
+ * Device data cannot be range-checked on the host: a 16-bit value must not exceed 32639 (it is
+ * split into two signed bytes) and a 12-bit operand must lie in [-2048, 2047]; values outside
+ * these ranges are not detected and give a wrong product (mc_mat_create returns MC_ERANGE for
+ * the same data on the host). */
 int mc_mat_set_values_device(mc_mat *A, const void *values_dev, void *stream);
 void mc_mat_destroy(mc_mat *A);
 /* Shape queries; return MC_EINVAL on a null handle. */
@@ -157,6 +193,10 @@ int mc_spmm(const mc_mat *A, const void *B_dev, int N, int ldb, mc_prec prec, in
 #define MC_RHS_UNSIGNED 2u
 int mc_spmm_flags(const mc_mat *A, const void *B_dev, int N, int ldb, mc_prec prec, unsigned flags, int32_t *C_dev,
                   int ldc, void *stream);
+/* mc_spmm_flags with the kernel variant given per call (options == NULL: automatic, whatever the
+ * thread's defaults are).  MC_EINVAL for an option value outside its list. */
+int mc_spmm_ex(const mc_mat *A, const void *B_dev, int N, int ldb, mc_prec prec, unsigned flags,
+               const mc_options *options, int32_t *C_dev, int ldc, void *stream);
 
 /* SpMM with fused dequantisation (Section 5.3: the integer product is turned into real values
  * in the kernel's epilogue): C = scale * (A * B), each element computed as float(int32 result) *
@@ -196,6 +236,9 @@ int mc_sddmm(const void *Q_dev, int ldq, const void *Kmat_dev, int ldk, int Kd, 
  * mc_spmm_flags).  Supported for MC_L8R8 and MC_L4R4 (the latter with Kd <= 32768). */
 int mc_sddmm_flags(const void *Q_dev, int ldq, const void *Kmat_dev, int ldk, int Kd, const mc_mat *mask,
                    mc_prec prec, unsigned flags, int32_t *S_dev, void *stream);
+/* mc_sddmm_flags with the kernel variant given per call (options == NULL: automatic). */
+int mc_sddmm_ex(const void *Q_dev, int ldq, const void *Kmat_dev, int ldk, int Kd, const mc_mat *mask,
+                mc_prec prec, unsigned flags, const mc_options *options, int32_t *S_dev, void *stream);
 
 /* SDDMM with fused dequantisation (Section 5.3): S_dev receives scale * score as nvec*V floats
  * or halves (rounded as in mc_spmm_dequant) in the same order.  Other arguments as mc_sddmm_flags. */
@@ -246,11 +289,18 @@ int mc_sparse_softmax_to_mat(mc_mat *P, const int32_t *S_dev, float score_scale,
  *   O_dev                   heads x L x dk fp32
  *   workspace_dev           at least mc_attention_workspace_bytes(heads, mask) bytes,
  *                           256-byte aligned, caller-owned; contents undefined after
- * Requirements: dk a multiple of 16.  Entries excluded by the mask do not take part in
- * the softmax.  Empty rows give zeros.  The workspace is only touched by the kernel
- * pipeline (see mc_set_attention_mode) but must always be supplied.
+ * Requirements: dk a multiple of 16; all four scales positive (symmetric quantisation scales
+ * are; MC_EINVAL otherwise).  Entries excluded by the mask do not take part in the softmax.
+ * Empty rows give zeros.  The workspace is only needed, checked and touched when the layer
+ * runs as the pipeline of separate kernels (see mc_set_attention_mode): NULL / 0 is accepted
+ * whenever mc_attention_workspace_needed(...) is 0 -- the fused kernel takes the layer, or the
+ * mask stores nothing.
  * ---------------------------------------------------------------------------------- */
 size_t mc_attention_workspace_bytes(int heads, const mc_mat *mask);
+/* Bytes of workspace the layer will really use for this head dimension and these options
+ * (NULL: the calling thread's defaults): 0 when the fused kernel runs, else
+ * mc_attention_workspace_bytes_bits(heads, mask, p_bits). */
+size_t mc_attention_workspace_needed(int heads, int dk, const mc_mat *mask, int p_bits, const mc_options *options);
 /* The same layer for any regular layout: element (head h, token l, d) of Q, Km, Vm (int8)
  * and of O (fp32) sits at h*head_stride + l*token_stride + d (strides in elements, both
  * multiples of 16).  mc_sparse_attention is the case head_stride = L*dk, token_stride = dk.
@@ -300,23 +350,31 @@ int mc_sparse_attention_out(const void *Q_dev, const void *Km_dev, const void *V
                             const mc_mat *mask, int p_bits, int qkv_bits, float s_q, float s_k, float s_v, float s_p,
                             mc_out_type out_type, void *O_dev, void *workspace_dev, size_t workspace_bytes,
                             void *stream);
+/* mc_sparse_attention_out with the kernel variants given per call (options == NULL: automatic). */
+int mc_sparse_attention_ex(const void *Q_dev, const void *Km_dev, const void *Vm_dev, int batch, int heads, int L,
+                           int dk, int64_t batch_stride, int64_t head_stride, int64_t token_stride,
+                           const mc_mat *mask, int p_bits, int qkv_bits, float s_q, float s_k, float s_v, float s_p,
+                           mc_out_type out_type, const mc_options *options, void *O_dev, void *workspace_dev,
+                           size_t workspace_bytes, void *stream);
 
 /* ------------------------------------------------------------------------------------
- * Tuning knob (not needed for correctness): selects the SpMM tile variant.
+ * One-knob setters kept for existing callers, tests and measurements.  Each changes one field of
+ * the CALLING THREAD's default options (see mc_set_thread_options); none is needed for
+ * correctness, and none affects other threads or the ..._ex entry points.
  *   bytes_per_row_tile  0 = automatic, else 64, 128 or 256 bytes of a B row per workgroup
  *   waves               0 = automatic, else 1, 2, 4 or 8 wavefronts sharing a panel's chunks
- * Returns MC_EINVAL for other values.  Process-wide.
+ * Returns MC_EINVAL for other values.
  * ---------------------------------------------------------------------------------- */
 int mc_set_spmm_variant(int bytes_per_row_tile, int waves);
 /* Chunks of gathered rows in flight per wave of the SpMM kernel: 2 (default; used when B spans
  * less than 4 GiB and no wave has more than 4 chunks) or 1.  Same results.  MC_EINVAL for other
- * values.  Process-wide. */
+ * values. */
 int mc_set_spmm_stages(int stages);
 /* Matrices whose longest panel is far above the average (more than six times the average and
  * more than 16 chunks) get, at mc_mat_create, a list of work items that cuts long panels into
  * pieces of at most three times the average (at least 8 chunks); mc_spmm then lets several workgroups add their exact int32 partial results into the
  * (first cleared) rows of such panels.  enable = 0 turns this off (one workgroup per panel and
- * row tile, as for regular matrices); the result is the same either way.  Process-wide. */
+ * row tile, as for regular matrices); the result is the same either way. */
 int mc_set_spmm_splitting(int enable);
 /* (The switch also governs the work items of mc_sddmm.  There every item writes its own outputs,
  * so a pattern-only mask is cut finer: into pieces of at most the average panel length, at least
@@ -325,12 +383,12 @@ int mc_set_spmm_splitting(int enable);
 /* SDDMM variant: -1 = automatic, 0 = the kernel that loads operands straight from memory
  * (any row length), 1, 2, 4 or 8 = waves per panel of the kernel that stages Kmat rows in
  * LDS (used when a row has 64, 128, 256, 512 or 1024 bytes, or 32 bytes of 4-bit values, else
- * ignored).  Process-wide. */
+ * ignored). */
 int mc_set_sddmm_variant(int waves);
 /* Softmax variant: 0 = automatic (panels of up to 4096 scores, padding included, are kept in
  * the registers of one wave, up to 16384 in those of a workgroup: one pass over the scores),
  * 1 = a workgroup per panel also for short panels, 2 = always the kernel for panels of any
- * length (three passes).  Same codes up to fp32 summation order.  Process-wide. */
+ * length (three passes).  Same codes up to fp32 summation order. */
 int mc_set_softmax_variant(int variant);
 /* Attention path: 0 = automatic (a single fused kernel when dk is 64 or 128 and no panel holds
  * more than 2048 vectors -- one, two or four waves per (panel, head) for panels of up to 512,
@@ -342,7 +400,7 @@ int mc_set_softmax_variant(int variant);
  * length alone; 3 / 4 = the fused kernel with at least two / with four waves per (panel, head)
  * whatever the panel length, 5 = waves by panel length alone -- 3, 4 and 5 with two heads per
  * workgroup wherever the layout allows it, whatever the size of the launch.  All give the same
- * result up to fp32 summation order in the softmax.  Process-wide; MC_EINVAL for other values. */
+ * result up to fp32 summation order in the softmax.  MC_EINVAL for other values. */
 int mc_set_attention_mode(int mode);
 
 #ifdef __cplusplus

@@ -32,6 +32,12 @@ class Layout(ctypes.Structure):
     _fields_ = [("P", c_int32), ("nvec", c_int64), ("nslots", c_int64), ("vals_bytes", c_int64)]
 
 
+class Options(ctypes.Structure):
+    """mc_options: kernel-variant choices of one call; all zero = automatic."""
+    _fields_ = [("spmm_row_tile_bytes", c_int), ("spmm_waves", c_int), ("spmm_stages", c_int), ("spmm_splitting", c_int),
+                ("spmm_slab", c_int), ("sddmm_waves", c_int), ("softmax_variant", c_int), ("attention_mode", c_int)]
+
+
 class MagicubeError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
@@ -89,6 +95,17 @@ def _load() -> ctypes.CDLL:
     L.mc_sparse_softmax_to_mat.argtypes = [c_void_p, c_void_p, c_float, c_float, c_void_p]
     L.mc_absmax.argtypes = [c_void_p, c_int64, c_void_p, c_void_p]
     L.mc_quantize.argtypes = [c_void_p, c_int64, c_float, c_int, c_void_p, c_void_p]
+    L.mc_options_init.argtypes = [POINTER(Options)]; L.mc_options_init.restype = None
+    L.mc_set_thread_options.argtypes = [POINTER(Options)]
+    L.mc_get_thread_options.argtypes = [POINTER(Options)]
+    L.mc_spmm_ex.argtypes = [c_void_p, c_void_p, c_int, c_int, c_int, ctypes.c_uint, POINTER(Options), c_void_p, c_int, c_void_p]
+    L.mc_sddmm_ex.argtypes = [c_void_p, c_int, c_void_p, c_int, c_int, c_void_p, c_int, ctypes.c_uint, POINTER(Options),
+                              c_void_p, c_void_p]
+    L.mc_sparse_attention_ex.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int64, c_int64,
+                                         c_int64, c_void_p, c_int, c_int, c_float, c_float, c_float, c_float, c_int,
+                                         POINTER(Options), c_void_p, c_void_p, c_size_t, c_void_p]
+    L.mc_attention_workspace_needed.argtypes = [c_int, c_int, c_void_p, c_int, POINTER(Options)]
+    L.mc_attention_workspace_needed.restype = c_size_t
     L.mc_set_spmm_variant.argtypes = [c_int, c_int]
     L.mc_set_attention_mode.argtypes = [c_int]
     L.mc_set_spmm_splitting.argtypes = [c_int]
@@ -100,7 +117,8 @@ def _load() -> ctypes.CDLL:
                  "mc_sparse_attention_strided", "mc_sparse_attention_bits", "mc_sparse_attention_batched", "mc_probe_gather",
                  "mc_absmax", "mc_quantize", "mc_sparse_attention_out", "mc_spmm_dequant", "mc_sddmm_dequant", "mc_sparse_softmax_to_mat",
                  "mc_set_spmm_variant", "mc_set_attention_mode", "mc_set_sddmm_variant", "mc_set_spmm_splitting", "mc_set_spmm_stages",
-                 "mc_set_softmax_variant"):
+                 "mc_set_softmax_variant", "mc_set_thread_options", "mc_get_thread_options", "mc_spmm_ex", "mc_sddmm_ex",
+                 "mc_sparse_attention_ex"):
         getattr(L, name).restype = c_int
     return L
 
@@ -205,6 +223,17 @@ class SparseMatrix:
             pass
 
 
+def set_thread_options(options: Options | None) -> None:
+    """Defaults of the calling thread for calls made without ``options=`` (None: automatic)."""
+    _check(lib.mc_set_thread_options(None if options is None else ctypes.byref(options)), "mc_set_thread_options")
+
+
+def get_thread_options() -> Options:
+    o = Options()
+    _check(lib.mc_get_thread_options(ctypes.byref(o)), "mc_get_thread_options")
+    return o
+
+
 def set_spmm_variant(bytes_per_row_tile: int = 0, waves: int = 0) -> None:
     _check(lib.mc_set_spmm_variant(bytes_per_row_tile, waves), "mc_set_spmm_variant")
 
@@ -229,9 +258,11 @@ def set_attention_mode(mode: int = 0) -> None:
     _check(lib.mc_set_attention_mode(mode), "mc_set_attention_mode")
 
 
-def spmm(A: SparseMatrix, B, prec: str, out=None, lhs_unsigned: bool = False, rhs_unsigned: bool = False):
+def spmm(A: SparseMatrix, B, prec: str, out=None, lhs_unsigned: bool = False, rhs_unsigned: bool = False,
+         options: Options | None = None):
     """C = A * B (int32, M x N).  B: device tensor (K, N) int8, (K, N/2) uint8 for R4, (K, N) int16 for R16.
-    lhs_unsigned / rhs_unsigned: read the 8- or 4-bit operand as non-negative values."""
+    lhs_unsigned / rhs_unsigned: read the 8- or 4-bit operand as non-negative values.
+    options: kernel-variant choices of this call (None: the calling thread's defaults)."""
     assert B.is_cuda and B.dim() == 2 and B.stride(1) == 1
     rbits = RHS_BITS[prec]
     N = B.shape[1] * B.element_size() * 8 // rbits
@@ -240,6 +271,10 @@ def spmm(A: SparseMatrix, B, prec: str, out=None, lhs_unsigned: bool = False, rh
         out = torch.empty((A.M, N), dtype=torch.int32, device=B.device)
     assert out.is_cuda and out.dtype == torch.int32 and out.shape == (A.M, N) and out.stride(1) == 1
     flags = (1 if lhs_unsigned else 0) | (2 if rhs_unsigned else 0)
+    if options is not None:
+        _check(lib.mc_spmm_ex(A.handle, B.data_ptr(), N, ldb, PREC[prec], flags, ctypes.byref(options), out.data_ptr(),
+                              out.stride(0), _stream()), "mc_spmm_ex")
+        return out
     _check(lib.mc_spmm_flags(A.handle, B.data_ptr(), N, ldb, PREC[prec], flags, out.data_ptr(), out.stride(0), _stream()),
            "mc_spmm_flags")
     return out
@@ -276,7 +311,8 @@ def probe_gather(A: SparseMatrix, B, prec: str, sink=None):
     return sink
 
 
-def sddmm(Q, Kmat, mask: SparseMatrix, prec: str, out=None, lhs_unsigned: bool = False, rhs_unsigned: bool = False):
+def sddmm(Q, Kmat, mask: SparseMatrix, prec: str, out=None, lhs_unsigned: bool = False, rhs_unsigned: bool = False,
+          options: Options | None = None):
     """S (nvec*V int32, interchange order) = (Q * Kmat^T) at the mask's stored vectors."""
     assert Q.is_cuda and Kmat.is_cuda and Q.dim() == 2 and Kmat.dim() == 2
     assert Q.stride(1) == 1 and Kmat.stride(1) == 1 and Q.shape[1] == Kmat.shape[1]
@@ -287,6 +323,11 @@ def sddmm(Q, Kmat, mask: SparseMatrix, prec: str, out=None, lhs_unsigned: bool =
         out = torch.empty(mask.nvec * mask.V, dtype=torch.int32, device=Q.device)
     assert out.is_cuda and out.dtype == torch.int32 and out.numel() == mask.nvec * mask.V and out.is_contiguous()
     flags = (1 if lhs_unsigned else 0) | (2 if rhs_unsigned else 0)
+    if options is not None:
+        _check(lib.mc_sddmm_ex(Q.data_ptr(), Q.stride(0) * Q.element_size() * 8 // bits, Kmat.data_ptr(),
+                               Kmat.stride(0) * Kmat.element_size() * 8 // bits, Kd, mask.handle, PREC[prec], flags,
+                               ctypes.byref(options), out.data_ptr(), _stream()), "mc_sddmm_ex")
+        return out
     _check(lib.mc_sddmm_flags(Q.data_ptr(), Q.stride(0) * Q.element_size() * 8 // bits, Kmat.data_ptr(),
                               Kmat.stride(0) * Kmat.element_size() * 8 // bits, Kd,
                               mask.handle, PREC[prec], flags, out.data_ptr(), _stream()), "mc_sddmm_flags")
@@ -362,8 +403,14 @@ def attention_workspace_bytes(heads: int, mask: SparseMatrix, p_bits: int = 8) -
     return int(lib.mc_attention_workspace_bytes_bits(heads, mask.handle, p_bits))
 
 
+def attention_workspace_needed(heads: int, dk: int, mask: SparseMatrix, p_bits: int = 8, options: Options | None = None) -> int:
+    """Bytes of workspace the layer will really use (0 when the fused kernel takes it)."""
+    return int(lib.mc_attention_workspace_needed(heads, dk, mask.handle, p_bits,
+                                                 None if options is None else ctypes.byref(options)))
+
+
 def sparse_attention(Q8, K8, V8, mask: SparseMatrix, s_q, s_k, s_v, s_p, out=None, workspace=None,
-                     p_bits: int = 8, qkv_bits: int = 8, out_dtype=torch.float32):
+                     p_bits: int = 8, qkv_bits: int = 8, out_dtype=torch.float32, options: Options | None = None):
     """Quantized sparse self-attention; Q8/K8/V8: (heads, L, dk) or (batch, heads, L, dk) int8
     device tensors, or for qkv_bits=4 uint8 tensors of half the last dimension with two 4-bit
     values per byte.  p_bits is the width of the re-quantised softmax output (8 or 16);
@@ -386,13 +433,19 @@ def sparse_attention(Q8, K8, V8, mask: SparseMatrix, s_q, s_k, s_v, s_p, out=Non
     if out is None:
         out = torch.empty_strided(oshape, st + (1,), dtype=out_dtype, device=Q8.device)   # the inputs' layout
     assert out.is_cuda and out.dtype == out_dtype and out.shape == oshape and out.stride() == st + (1,)
-    need = attention_workspace_bytes(heads, mask, p_bits)
     if workspace is None:
-        workspace = torch.empty(need, dtype=torch.uint8, device=Q8.device)
-    assert workspace.is_cuda and workspace.is_contiguous()
+        need = attention_workspace_needed(heads, dk, mask, p_bits, options)
+        workspace = torch.empty(need, dtype=torch.uint8, device=Q8.device) if need else None
+    ws_ptr, ws_bytes = (None, 0) if workspace is None else (workspace.data_ptr(), workspace.numel() * workspace.element_size())
+    assert workspace is None or (workspace.is_cuda and workspace.is_contiguous())
+    if options is not None:
+        _check(lib.mc_sparse_attention_ex(Q8.data_ptr(), K8.data_ptr(), V8.data_ptr(), batch, heads, L, dk, bs, hs, ts,
+                                          mask.handle, p_bits, qkv_bits, float(s_q), float(s_k), float(s_v), float(s_p),
+                                          OUT_TYPE[out_dtype], ctypes.byref(options), out.data_ptr(), ws_ptr, ws_bytes,
+                                          _stream()), "mc_sparse_attention_ex")
+        return out
     _check(lib.mc_sparse_attention_out(Q8.data_ptr(), K8.data_ptr(), V8.data_ptr(), batch, heads, L, dk, bs, hs, ts,
                                        mask.handle, p_bits, qkv_bits, float(s_q), float(s_k), float(s_v), float(s_p),
-                                       OUT_TYPE[out_dtype], out.data_ptr(), workspace.data_ptr(),
-                                       workspace.numel() * workspace.element_size(), _stream()),
+                                       OUT_TYPE[out_dtype], out.data_ptr(), ws_ptr, ws_bytes, _stream()),
            "mc_sparse_attention_out")
     return out

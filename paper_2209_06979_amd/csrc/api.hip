@@ -6,17 +6,41 @@
 #include <cmath>
 #include <cstdio>
 #include <cstdlib>
+#include <mutex>
 #include <new>
 #include <vector>
 
 namespace {
 
-int g_variant_bnb = 0, g_variant_waves = 0;
-int g_sddmm_waves = -1;   // -1 automatic, 0 direct-load kernel, 1/2/4/8 waves of the LDS-staged kernel
-int g_attention_mode = 0; // 0 automatic, 1 always the pipeline of separate kernels, 2..5 see mc_set_attention_mode
-int g_spmm_items = 1;     // 1: matrices with very unequal panels run through their work items
-int g_softmax_variant = 0; // 0: automatic; 1: a workgroup per panel; 2: the any-length softmax kernel always
-int g_spmm_stages = 2;    // chunks in flight per wave of the SpMM kernel (1 or 2)
+// The calling thread's default choices (all zero = automatic).  A compute call copies either the
+// options it was handed or these once, at entry, and never looks at shared state afterwards.
+thread_local mc_options t_options = {};
+
+bool valid_options(const mc_options &o)
+{
+    const int b = o.spmm_row_tile_bytes, w = o.spmm_waves, d = o.sddmm_waves;
+    if (b != 0 && b != 64 && b != 128 && b != 256) return false;
+    if (w != 0 && w != 1 && w != 2 && w != 4 && w != 8) return false;
+    if (o.spmm_stages < 0 || o.spmm_stages > 2) return false;
+    if (o.spmm_splitting != 0 && o.spmm_splitting != -1) return false;
+    if (o.spmm_slab < -1 || o.spmm_slab > 1) return false;
+    if (d != 0 && d != -1 && d != 1 && d != 2 && d != 4 && d != 8) return false;
+    if (o.softmax_variant < 0 || o.softmax_variant > 2) return false;
+    if (o.attention_mode < 0 || o.attention_mode > 5) return false;
+    return true;
+}
+
+// The options of one call: the caller's (validated), or the thread's defaults.
+int resolve_options(const mc_options *given, mc_options *out)
+{
+    if (given) {
+        if (!valid_options(*given)) return MC_EINVAL;
+        *out = *given;
+    } else {
+        *out = t_options;
+    }
+    return MC_OK;
+}
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline int lhs_bits_of(mc_prec p)
@@ -66,9 +90,9 @@ void free_device(mc_mat *A)
 
 // Waves per panel for SDDMM: enough to put about 2048 waves on the chip (4096 of the light ones
 // that stage rows of 32 bytes, or 64 bytes of nibbles), fewer than twice the chunks of an average panel.
-int choose_sddmm_waves(const mc_mat *mask, int batch, int row_bytes, int bits)
+int choose_sddmm_waves(const mc_mat *mask, int batch, int row_bytes, int bits, const mc_options &o)
 {
-    if (g_sddmm_waves >= 0) return g_sddmm_waves;
+    if (o.sddmm_waves != 0) return o.sddmm_waves < 0 ? 0 : o.sddmm_waves; // 0 selects the direct-load kernel in launch_sddmm
     const double avg = mask->P ? (double)(mask->nslots / MC_CHUNK) / mask->P : 0.0;
     const double groups = (double)mask->P * (batch > 0 ? batch : 1);
     const double target = (row_bytes <= 32 || (bits == 4 && row_bytes <= 64)) ? 4096.0 : 2048.0;
@@ -84,9 +108,10 @@ int choose_sddmm_waves(const mc_mat *mask, int batch, int row_bytes, int bits)
 // never more waves than a panel has chunks.
 // max_unit: chunks of the longest unit of work (panel or work item) of this launch.
 // lhs_bits: width of the sparse operand's values in this launch (a mask carries none of its own).
-void choose_variant(const mc_mat *A, int lhs_bits, int row_bytes, bool r4, int batch, int max_unit, int *bnb, int *waves)
+void choose_variant(const mc_mat *A, int lhs_bits, int row_bytes, bool r4, int batch, int max_unit, const mc_options &o, int *bnb,
+                    int *waves)
 {
-    int b = g_variant_bnb, w = g_variant_waves;
+    int b = o.spmm_row_tile_bytes, w = o.spmm_waves;
     const double avg = A->P ? (double)(A->nslots / MC_CHUNK) / A->P : 0.0;
     if (b == 0) {
         if (r4) {
@@ -108,7 +133,7 @@ void choose_variant(const mc_mat *A, int lhs_bits, int row_bytes, bool r4, int b
     // few panels: narrower tiles until there is a workgroup for every compute unit (a 256 x 2304 matrix
     // with rows of 512 bytes: 5.7 us on 256-byte tiles, 3.3 us on 64-byte ones)
     // (rows of nibbles, fewer than 512 panels: until the panels' chunks can occupy 4096 of the light waves)
-    if (g_variant_bnb == 0) {
+    if (o.spmm_row_tile_bytes == 0) {
         const double nb = (batch > 0 ? batch : 1), per_group = std::min(8.0, std::max(1.0, avg));
         while (b > 64 && (double)A->P * ((row_bytes + b - 1) / b) * nb < 256.0) b /= 2;
         if (r4 && A->P < 512)
@@ -153,48 +178,72 @@ extern "C" const char *mc_version(void) { return "0.1 gfx950"; }
 
 extern "C" const char *mc_last_error_detail(void) { return g_detail; }
 
+extern "C" void mc_options_init(mc_options *o)
+{
+    if (o) *o = mc_options{};
+}
+
+extern "C" int mc_set_thread_options(const mc_options *o)
+{
+    if (!o) {
+        t_options = mc_options{};
+        return MC_OK;
+    }
+    if (!valid_options(*o)) return MC_EINVAL;
+    t_options = *o;
+    return MC_OK;
+}
+
+extern "C" int mc_get_thread_options(mc_options *o)
+{
+    if (!o) return MC_EINVAL;
+    *o = t_options;
+    return MC_OK;
+}
+
+// The older one-knob setters: each changes one field of the calling thread's defaults.
+namespace {
+template <class F> int set_field(F &&f)
+{
+    mc_options o = t_options;
+    f(o);
+    if (!valid_options(o)) return MC_EINVAL;
+    t_options = o;
+    return MC_OK;
+}
+} // namespace
+
 extern "C" int mc_set_spmm_variant(int bytes_per_row_tile, int waves)
 {
-    if (bytes_per_row_tile != 0 && bytes_per_row_tile != 64 && bytes_per_row_tile != 128 && bytes_per_row_tile != 256)
-        return MC_EINVAL;
-    if (waves != 0 && waves != 1 && waves != 2 && waves != 4 && waves != 8) return MC_EINVAL;
-    g_variant_bnb = bytes_per_row_tile;
-    g_variant_waves = waves;
-    return MC_OK;
+    return set_field([&](mc_options &o) { o.spmm_row_tile_bytes = bytes_per_row_tile; o.spmm_waves = waves; });
 }
 
 extern "C" int mc_set_spmm_stages(int stages)
 {
     if (stages != 1 && stages != 2) return MC_EINVAL;
-    g_spmm_stages = stages;
-    return MC_OK;
+    return set_field([&](mc_options &o) { o.spmm_stages = stages; });
 }
 
 extern "C" int mc_set_spmm_splitting(int enable)
 {
-    g_spmm_items = enable ? 1 : 0;
-    return MC_OK;
+    return set_field([&](mc_options &o) { o.spmm_splitting = enable ? 0 : -1; });
 }
 
 extern "C" int mc_set_sddmm_variant(int waves)
 {
-    if (waves != -1 && waves != 0 && waves != 1 && waves != 2 && waves != 4 && waves != 8) return MC_EINVAL;
-    g_sddmm_waves = waves;
-    return MC_OK;
+    // this setter's own convention: -1 automatic, 0 the direct-load kernel
+    if (waves < -1) return MC_EINVAL;
+    return set_field([&](mc_options &o) { o.sddmm_waves = (waves == -1) ? 0 : (waves == 0 ? -1 : waves); });
 }
 
 extern "C" int mc_set_softmax_variant(int variant)
 {
-    if (variant != 0 && variant != 1 && variant != 2) return MC_EINVAL;
-    g_softmax_variant = variant;
-    return MC_OK;
+    return set_field([&](mc_options &o) { o.softmax_variant = variant; });
 }
 
 extern "C" int mc_set_attention_mode(int mode)
 {
-    if (mode < 0 || mode > 5) return MC_EINVAL;
-    g_attention_mode = mode;
-    return MC_OK;
+    return set_field([&](mc_options &o) { o.attention_mode = mode; });
 }
 
 extern "C" int mc_mat_create(int M, int K, int V, int lhs_bits, const int32_t *row_ptr, const int32_t *col_idx,
@@ -349,18 +398,32 @@ extern "C" int mc_mat_set_values_device(mc_mat *A, const void *values_dev, void 
     return MC_OK;
 }
 
-extern "C" int mc_spmm(const mc_mat *A, const void *B_dev, int N, int ldb, mc_prec prec, int32_t *C_dev, int ldc,
-                       void *stream)
+namespace {
+// Every compute call works on the device the operand was created on: its buffers are not
+// addressable from another one.
+bool on_device_of(const mc_mat *A)
 {
-    return mc_spmm_flags(A, B_dev, N, ldb, prec, 0u, C_dev, ldc, stream);
+    int cur = -1;
+    if (!hip_ok(hipGetDevice(&cur), "hipGetDevice")) return false;
+    if (cur != A->device) {
+        snprintf(g_detail, sizeof g_detail, "sparse operand lives on device %d, the current device is %d", A->device, cur);
+        return false;
+    }
+    return true;
 }
 
-namespace {
+inline int spmm_stages_for(const mc_options &o, int K, int64_t ldb_bytes, int row_bytes)
+{
+    return (o.spmm_stages != 1 && (int64_t)(K - 1) * ldb_bytes + row_bytes < ((int64_t)1 << 32)) ? 2 : 1;
+}
+
 // out_mode 0: int32 results; 1 / 2: scale * result as fp32 / fp16 (fused dequantisation)
 int spmm_impl(const mc_mat *A, const void *B_dev, int N, int ldb, mc_prec prec, unsigned flags, int out_mode,
-              float scale, void *C_dev, int ldc, void *stream)
+              float scale, void *C_dev, int ldc, const mc_options *opts, void *stream)
 {
     if (!A || !B_dev || !C_dev) return MC_EINVAL;
+    mc_options o;
+    if (resolve_options(opts, &o) != MC_OK) return MC_EINVAL;
     if (!valid_prec((int)prec)) return MC_EUNSUPPORTED;
     if (flags & ~(unsigned)(MC_LHS_UNSIGNED | MC_RHS_UNSIGNED)) return MC_EINVAL;
     if (flags && prec != MC_L8R8 && prec != MC_L8R4 && prec != MC_L4R4) return MC_EUNSUPPORTED;
@@ -373,6 +436,7 @@ int spmm_impl(const mc_mat *A, const void *B_dev, int N, int ldb, mc_prec prec, 
     if (!aligned16(B_dev) || !aligned16(C_dev)) return MC_EALIGN;
     if (rb == 4 && A->K > ((flags != 0) ? 32768 : 131072)) return MC_EUNSUPPORTED;
     if (out_mode && !std::isfinite(scale)) return MC_EINVAL;
+    if (!on_device_of(A)) return MC_EINVAL;
 
     SpmmArgs a = {};
     a.lhs_unsigned = (flags & MC_LHS_UNSIGNED) ? 1 : 0; a.rhs_unsigned = (flags & MC_RHS_UNSIGNED) ? 1 : 0;
@@ -382,12 +446,12 @@ int spmm_impl(const mc_mat *A, const void *B_dev, int N, int ldb, mc_prec prec, 
     a.row_bytes = N * rb / 8;
     a.C = C_dev; a.ldc = ldc; a.C_batch_stride = 0;
     a.P = A->P; a.V = A->V; a.batch = 1; a.float_out = out_mode; a.out_scale = out_mode ? scale : 1.f;
-    a.stages = (g_spmm_stages == 2 && (int64_t)(A->K - 1) * a.ldb_bytes + a.row_bytes < ((int64_t)1 << 32)) ? 2 : 1;
+    a.stages = spmm_stages_for(o, A->K, a.ldb_bytes, a.row_bytes);
     a.max_unit_chunks = A->max_panel_chunks;
-    const bool use_items = A->n_items && g_spmm_items && out_mode == 0;
+    const bool use_items = A->n_items && o.spmm_splitting == 0 && out_mode == 0;
     if (use_items) a.max_unit_chunks = A->max_item_chunks;
     int bnb, waves;
-    choose_variant(A, A->lhs_bits, a.row_bytes, rb == 4, 1, a.max_unit_chunks, &bnb, &waves);
+    choose_variant(A, A->lhs_bits, a.row_bytes, rb == 4, 1, a.max_unit_chunks, o, &bnb, &waves);
     if (use_items) {
         // very unequal panels: long ones are shared by several workgroups that add into cleared rows
         // (integer results only: a scaled, rounded result cannot be accumulated piecewise)
@@ -400,17 +464,30 @@ int spmm_impl(const mc_mat *A, const void *B_dev, int N, int ldb, mc_prec prec, 
 }
 } // namespace
 
+extern "C" int mc_spmm(const mc_mat *A, const void *B_dev, int N, int ldb, mc_prec prec, int32_t *C_dev, int ldc,
+                       void *stream)
+{
+    return spmm_impl(A, B_dev, N, ldb, prec, 0u, 0, 1.f, C_dev, ldc, nullptr, stream);
+}
+
 extern "C" int mc_spmm_flags(const mc_mat *A, const void *B_dev, int N, int ldb, mc_prec prec, unsigned flags,
                              int32_t *C_dev, int ldc, void *stream)
 {
-    return spmm_impl(A, B_dev, N, ldb, prec, flags, 0, 1.f, C_dev, ldc, stream);
+    return spmm_impl(A, B_dev, N, ldb, prec, flags, 0, 1.f, C_dev, ldc, nullptr, stream);
+}
+
+extern "C" int mc_spmm_ex(const mc_mat *A, const void *B_dev, int N, int ldb, mc_prec prec, unsigned flags,
+                          const mc_options *options, int32_t *C_dev, int ldc, void *stream)
+{
+    const mc_options automatic = {};
+    return spmm_impl(A, B_dev, N, ldb, prec, flags, 0, 1.f, C_dev, ldc, options ? options : &automatic, stream);
 }
 
 extern "C" int mc_spmm_dequant(const mc_mat *A, const void *B_dev, int N, int ldb, mc_prec prec, unsigned flags,
                                float scale, mc_out_type out_type, void *C_dev, int ldc, void *stream)
 {
     if (out_type != MC_OUT_F32 && out_type != MC_OUT_F16) return MC_EUNSUPPORTED;
-    return spmm_impl(A, B_dev, N, ldb, prec, flags, out_type == MC_OUT_F16 ? 2 : 1, scale, C_dev, ldc, stream);
+    return spmm_impl(A, B_dev, N, ldb, prec, flags, out_type == MC_OUT_F16 ? 2 : 1, scale, C_dev, ldc, nullptr, stream);
 }
 
 extern "C" int64_t mc_probe_gather_sink_len(const mc_mat *A, int N, mc_prec prec)
@@ -428,6 +505,8 @@ extern "C" int mc_probe_gather(const mc_mat *A, const void *B_dev, int N, int ld
     const int rb = rhs_bits_of(prec);
     if (N <= 0 || N % (128 / rb) != 0 || ldb < N) return MC_EINVAL;
     if (((int64_t)ldb * rb / 8) % 16 != 0 || !aligned16(B_dev)) return MC_EALIGN;
+    if (!on_device_of(A)) return MC_EINVAL;
+    const mc_options o = t_options;
     SpmmArgs a = {};
     a.panel_ptr = A->d_panel_ptr; a.slot_idx = A->d_slot_idx;
     a.vals = nullptr; a.vals_batch_stride = 0;
@@ -436,22 +515,18 @@ extern "C" int mc_probe_gather(const mc_mat *A, const void *B_dev, int N, int ld
     a.C = nullptr; a.ldc = 0; a.C_batch_stride = 0;
     a.P = A->P; a.V = A->V; a.batch = 1; a.float_out = 0; a.out_scale = 1.f;
     int bnb, waves;
-    choose_variant(A, A->lhs_bits, a.row_bytes, rb == 4, 1, A->max_panel_chunks, &bnb, &waves);
+    choose_variant(A, A->lhs_bits, a.row_bytes, rb == 4, 1, A->max_panel_chunks, o, &bnb, &waves);
     MC_HIP(launch_gather_probe(a, bnb, waves, sink_dev, static_cast<hipStream_t>(stream)));
     return MC_OK;
 }
 
-extern "C" int mc_sddmm(const void *Q_dev, int ldq, const void *Kmat_dev, int ldk, int Kd, const mc_mat *mask,
-                        mc_prec prec, int32_t *S_dev, void *stream)
-{
-    return mc_sddmm_flags(Q_dev, ldq, Kmat_dev, ldk, Kd, mask, prec, 0u, S_dev, stream);
-}
-
 namespace {
 int sddmm_impl(const void *Q_dev, int ldq, const void *Kmat_dev, int ldk, int Kd, const mc_mat *mask, mc_prec prec,
-               unsigned flags, int out_mode, float scale, void *S_dev, void *stream)
+               unsigned flags, int out_mode, float scale, void *S_dev, const mc_options *opts, void *stream)
 {
     if (!Q_dev || !Kmat_dev || !mask) return MC_EINVAL;
+    mc_options o;
+    if (resolve_options(opts, &o) != MC_OK) return MC_EINVAL;
     if (!S_dev && mask->nvec > 0) return MC_EINVAL; // (a mask without any vector has an empty output)
     if (!valid_prec((int)prec)) return MC_EUNSUPPORTED;
     if (flags & ~(unsigned)(MC_LHS_UNSIGNED | MC_RHS_UNSIGNED)) return MC_EINVAL;
@@ -464,6 +539,7 @@ int sddmm_impl(const void *Q_dev, int ldq, const void *Kmat_dev, int ldk, int Kd
     if (!aligned16(Q_dev) || !aligned16(Kmat_dev) || !aligned16(S_dev)) return MC_EALIGN;
     if (out_mode && !std::isfinite(scale)) return MC_EINVAL;
     if (mask->nvec == 0) return MC_OK;
+    if (!on_device_of(mask)) return MC_EINVAL;
 
     SddmmArgs a = {};
     a.float_out = out_mode; a.out_scale = out_mode ? scale : 1.f;
@@ -474,16 +550,29 @@ int sddmm_impl(const void *Q_dev, int ldq, const void *Kmat_dev, int ldk, int Kd
     a.S = S_dev; a.S_batch_stride = 0;
     a.P = mask->P; a.V = mask->V; a.batch = 1;
     a.lhs_unsigned = (flags & MC_LHS_UNSIGNED) ? 1 : 0; a.rhs_unsigned = (flags & MC_RHS_UNSIGNED) ? 1 : 0;
-    if (mask->n_items && g_spmm_items) { a.items = mask->d_items; a.n_units = mask->n_items; } // very unequal panels
-    MC_HIP(launch_sddmm(bits, a, choose_sddmm_waves(mask, 1, a.row_bytes, bits), static_cast<hipStream_t>(stream)));
+    if (mask->n_items && o.spmm_splitting == 0) { a.items = mask->d_items; a.n_units = mask->n_items; } // very unequal panels
+    MC_HIP(launch_sddmm(bits, a, choose_sddmm_waves(mask, 1, a.row_bytes, bits, o), static_cast<hipStream_t>(stream)));
     return MC_OK;
 }
 } // namespace
 
+extern "C" int mc_sddmm(const void *Q_dev, int ldq, const void *Kmat_dev, int ldk, int Kd, const mc_mat *mask,
+                        mc_prec prec, int32_t *S_dev, void *stream)
+{
+    return sddmm_impl(Q_dev, ldq, Kmat_dev, ldk, Kd, mask, prec, 0u, 0, 1.f, S_dev, nullptr, stream);
+}
+
 extern "C" int mc_sddmm_flags(const void *Q_dev, int ldq, const void *Kmat_dev, int ldk, int Kd, const mc_mat *mask,
                               mc_prec prec, unsigned flags, int32_t *S_dev, void *stream)
 {
-    return sddmm_impl(Q_dev, ldq, Kmat_dev, ldk, Kd, mask, prec, flags, 0, 1.f, S_dev, stream);
+    return sddmm_impl(Q_dev, ldq, Kmat_dev, ldk, Kd, mask, prec, flags, 0, 1.f, S_dev, nullptr, stream);
+}
+
+extern "C" int mc_sddmm_ex(const void *Q_dev, int ldq, const void *Kmat_dev, int ldk, int Kd, const mc_mat *mask,
+                           mc_prec prec, unsigned flags, const mc_options *options, int32_t *S_dev, void *stream)
+{
+    const mc_options automatic = {};
+    return sddmm_impl(Q_dev, ldq, Kmat_dev, ldk, Kd, mask, prec, flags, 0, 1.f, S_dev, options ? options : &automatic, stream);
 }
 
 extern "C" int mc_sddmm_dequant(const void *Q_dev, int ldq, const void *Kmat_dev, int ldk, int Kd, const mc_mat *mask,
@@ -492,7 +581,7 @@ extern "C" int mc_sddmm_dequant(const void *Q_dev, int ldq, const void *Kmat_dev
 {
     if (out_type != MC_OUT_F32 && out_type != MC_OUT_F16) return MC_EUNSUPPORTED;
     return sddmm_impl(Q_dev, ldq, Kmat_dev, ldk, Kd, mask, prec, flags, out_type == MC_OUT_F16 ? 2 : 1, scale, S_dev,
-                      stream);
+                      nullptr, stream);
 }
 
 extern "C" int mc_absmax(const float *x_dev, int64_t n, float *result_dev, void *stream)
@@ -521,12 +610,14 @@ extern "C" int mc_sparse_softmax_bits(const mc_mat *mask, int batch, const int32
     if (code_bits != 8 && code_bits != 16) return MC_EUNSUPPORTED;
     if (!std::isfinite(score_scale) || !std::isfinite(inv_s_p)) return MC_EINVAL;
     if (mask->nvec == 0) return MC_OK; // nothing stored: empty input and output
+    if (!on_device_of(mask)) return MC_EINVAL;
+    const mc_options o = t_options;
     SoftmaxArgs a = {};
     a.row_ptr = mask->d_row_ptr; a.S = S_dev; a.codes = codes_dev;
     a.batch_stride = mask->nvec * mask->V;
     a.score_scale = score_scale; a.inv_s_p = inv_s_p;
     a.P = mask->P; a.V = mask->V; a.batch = batch; a.code_bits = code_bits;
-    a.max_panel_chunks = mask->max_panel_chunks; a.variant = g_softmax_variant;
+    a.max_panel_chunks = mask->max_panel_chunks; a.variant = o.softmax_variant;
     MC_HIP(launch_softmax(a, static_cast<hipStream_t>(stream)));
     return MC_OK;
 }
@@ -538,13 +629,15 @@ extern "C" int mc_sparse_softmax_to_mat(mc_mat *P, const int32_t *S_dev, float s
     if (P->nslots == 0) return MC_OK;
     if (P->lhs_bits != 8 && P->lhs_bits != 16) return MC_EUNSUPPORTED;
     if (!std::isfinite(score_scale) || !std::isfinite(inv_s_p)) return MC_EINVAL;
+    if (!on_device_of(P)) return MC_EINVAL;
+    const mc_options o = t_options;
     SoftmaxArgs a = {};
     a.row_ptr = P->d_row_ptr; a.S = S_dev; a.codes = nullptr;
     a.panel_ptr = P->d_panel_ptr; a.dev_vals = P->d_vals; a.dev_batch_stride = 0;
     a.batch_stride = P->nvec * P->V;
     a.score_scale = score_scale; a.inv_s_p = inv_s_p;
     a.P = P->P; a.V = P->V; a.batch = 1; a.code_bits = P->lhs_bits;
-    a.max_panel_chunks = P->max_panel_chunks; a.variant = g_softmax_variant;
+    a.max_panel_chunks = P->max_panel_chunks; a.variant = o.softmax_variant;
     MC_HIP(launch_softmax(a, static_cast<hipStream_t>(stream)));
     return MC_OK;
 }
@@ -573,7 +666,7 @@ AttnWs attn_layout(int heads, const mc_mat *mask, int p_bits)
 int attention_pipeline(const uint8_t *Q, const uint8_t *Km, const uint8_t *Vm, int heads, int dk, int qkv_bits,
                        int p_bits, int64_t head_stride_bytes, int64_t token_stride_bytes, int64_t o_head_stride,
                        int64_t o_token_stride, const mc_mat *mask, float s_q, float s_k, float s_v, float s_p,
-                       void *O, int out_f16, void *workspace_dev, hipStream_t s)
+                       void *O, int out_f16, void *workspace_dev, const mc_options &o, hipStream_t s)
 {
     const AttnWs ws = attn_layout(heads, mask, p_bits);
     const int64_t nnz = mask->nvec * mask->V;
@@ -588,8 +681,8 @@ int attention_pipeline(const uint8_t *Q, const uint8_t *Km, const uint8_t *Vm, i
     d.Kmat = Km; d.ldk_bytes = token_stride_bytes; d.K_batch_stride = head_stride_bytes;
     d.row_bytes = row_bytes; d.S = scores; d.S_batch_stride = nnz;
     d.P = mask->P; d.V = 8; d.batch = heads;
-    if (mask->n_items && g_spmm_items) { d.items = mask->d_items; d.n_units = mask->n_items; } // very unequal panels
-    MC_HIP(launch_sddmm(qkv_bits, d, choose_sddmm_waves(mask, heads, row_bytes, qkv_bits), s));
+    if (mask->n_items && o.spmm_splitting == 0) { d.items = mask->d_items; d.n_units = mask->n_items; } // very unequal panels
+    MC_HIP(launch_sddmm(qkv_bits, d, choose_sddmm_waves(mask, heads, row_bytes, qkv_bits, o), s));
 
     // the softmax writes its codes in the layout the SpMM reads (Section 4.3 lets the producer
     // pick the output format by the consumer)
@@ -598,7 +691,7 @@ int attention_pipeline(const uint8_t *Q, const uint8_t *Km, const uint8_t *Vm, i
     f.codes = nullptr; f.panel_ptr = mask->d_panel_ptr; f.dev_vals = pvals; f.dev_batch_stride = mask->nslots * 8 * pb;
     f.score_scale = s_q * s_k / std::sqrt((float)dk); f.inv_s_p = 1.f / s_p;
     f.P = mask->P; f.V = 8; f.batch = heads; f.code_bits = p_bits;
-    f.max_panel_chunks = mask->max_panel_chunks; f.variant = g_softmax_variant;
+    f.max_panel_chunks = mask->max_panel_chunks; f.variant = o.softmax_variant;
     MC_HIP(launch_softmax(f, s));
 
     SpmmArgs m = {};
@@ -607,90 +700,48 @@ int attention_pipeline(const uint8_t *Q, const uint8_t *Km, const uint8_t *Vm, i
     m.B = Vm; m.ldb_bytes = token_stride_bytes; m.B_batch_stride = head_stride_bytes;
     m.row_bytes = row_bytes; m.C = O; m.ldc = o_token_stride; m.C_batch_stride = o_head_stride;
     m.P = mask->P; m.V = 8; m.batch = heads; m.float_out = out_f16 ? 2 : 1; m.out_scale = s_p * s_v;
-    m.stages = (g_spmm_stages == 2 && (int64_t)(mask->K - 1) * m.ldb_bytes + m.row_bytes < ((int64_t)1 << 32)) ? 2 : 1;
+    m.stages = spmm_stages_for(o, mask->K, m.ldb_bytes, m.row_bytes);
     m.max_unit_chunks = mask->max_panel_chunks;
     int bnb, waves;
-    choose_variant(mask, p_bits, m.row_bytes, qkv_bits == 4, heads, mask->max_panel_chunks, &bnb, &waves);
+    choose_variant(mask, p_bits, m.row_bytes, qkv_bits == 4, heads, mask->max_panel_chunks, o, &bnb, &waves);
     const mc_prec prec = (p_bits == 16) ? (qkv_bits == 4 ? MC_L16R4 : MC_L16R8) : (qkv_bits == 4 ? MC_L8R4 : MC_L8R8);
     MC_HIP(launch_spmm(prec, m, bnb, waves, s));
     return MC_OK;
 }
-} // namespace
 
-extern "C" size_t mc_attention_workspace_bytes_bits(int heads, const mc_mat *mask, int p_bits)
+// Whether the single fused kernel takes this layer (else the pipeline of separate kernels, which needs a workspace).
+bool attention_is_fused(const mc_mat *mask, int dk, const mc_options &o)
 {
-    if (!mask || heads <= 0 || (p_bits != 8 && p_bits != 16)) return 0;
-    return attn_layout(heads, mask, p_bits).total;
+    return o.attention_mode != 1 && (dk == 64 || dk == 128) &&
+           mask->max_panel_chunks * MC_CHUNK <= attention_fused_max_vectors();
 }
 
-extern "C" size_t mc_attention_workspace_bytes(int heads, const mc_mat *mask)
-{
-    return mc_attention_workspace_bytes_bits(heads, mask, 8);
-}
-
-extern "C" int mc_sparse_attention(const int8_t *Q_dev, const int8_t *Km_dev, const int8_t *Vm_dev, int heads, int L,
-                                   int dk, const mc_mat *mask, float s_q, float s_k, float s_v, float s_p,
-                                   float *O_dev, void *workspace_dev, size_t workspace_bytes, void *stream)
-{
-    return mc_sparse_attention_strided(Q_dev, Km_dev, Vm_dev, heads, L, dk, (int64_t)L * dk, dk, mask, s_q, s_k, s_v,
-                                       s_p, O_dev, workspace_dev, workspace_bytes, stream);
-}
-
-extern "C" int mc_sparse_attention_strided(const int8_t *Q_dev, const int8_t *Km_dev, const int8_t *Vm_dev, int heads,
-                                           int L, int dk, int64_t head_stride, int64_t token_stride,
-                                           const mc_mat *mask, float s_q, float s_k, float s_v, float s_p,
-                                           float *O_dev, void *workspace_dev, size_t workspace_bytes, void *stream)
-{
-    return mc_sparse_attention_bits(Q_dev, Km_dev, Vm_dev, heads, L, dk, head_stride, token_stride, mask, 8, 8, s_q,
-                                    s_k, s_v, s_p, O_dev, workspace_dev, workspace_bytes, stream);
-}
-
-extern "C" int mc_sparse_attention_bits(const void *Q_dev, const void *Km_dev, const void *Vm_dev, int heads, int L,
-                                        int dk, int64_t head_stride, int64_t token_stride, const mc_mat *mask,
-                                        int p_bits, int qkv_bits, float s_q, float s_k, float s_v, float s_p,
-                                        float *O_dev, void *workspace_dev, size_t workspace_bytes, void *stream)
-{
-    return mc_sparse_attention_batched(Q_dev, Km_dev, Vm_dev, 1, heads, L, dk, 0, head_stride, token_stride, mask,
-                                       p_bits, qkv_bits, s_q, s_k, s_v, s_p, O_dev, workspace_dev, workspace_bytes,
-                                       stream);
-}
-
-extern "C" int mc_sparse_attention_batched(const void *Q_dev, const void *Km_dev, const void *Vm_dev, int batch,
-                                           int heads, int L, int dk, int64_t batch_stride, int64_t head_stride,
-                                           int64_t token_stride, const mc_mat *mask, int p_bits, int qkv_bits,
-                                           float s_q, float s_k, float s_v, float s_p, float *O_dev,
-                                           void *workspace_dev, size_t workspace_bytes, void *stream)
-{
-    return mc_sparse_attention_out(Q_dev, Km_dev, Vm_dev, batch, heads, L, dk, batch_stride, head_stride, token_stride,
-                                   mask, p_bits, qkv_bits, s_q, s_k, s_v, s_p, MC_OUT_F32, O_dev, workspace_dev,
-                                   workspace_bytes, stream);
-}
-
-extern "C" int mc_sparse_attention_out(const void *Q_dev, const void *Km_dev, const void *Vm_dev, int batch, int heads,
-                                       int L, int dk, int64_t batch_stride, int64_t head_stride, int64_t token_stride,
-                                       const mc_mat *mask, int p_bits, int qkv_bits, float s_q, float s_k, float s_v,
-                                       float s_p, mc_out_type out_type, void *O_dev, void *workspace_dev,
-                                       size_t workspace_bytes, void *stream)
+int attention_impl(const void *Q_dev, const void *Km_dev, const void *Vm_dev, int batch, int heads, int L, int dk,
+                   int64_t batch_stride, int64_t head_stride, int64_t token_stride, const mc_mat *mask, int p_bits,
+                   int qkv_bits, float s_q, float s_k, float s_v, float s_p, mc_out_type out_type, void *O_dev,
+                   void *workspace_dev, size_t workspace_bytes, const mc_options *opts, void *stream)
 {
     if (out_type != MC_OUT_F32 && out_type != MC_OUT_F16) return MC_EUNSUPPORTED;
     const int out_f16 = (out_type == MC_OUT_F16) ? 1 : 0;
-    if (!Q_dev || !Km_dev || !Vm_dev || !mask || !O_dev || !workspace_dev) return MC_EINVAL;
+    if (!Q_dev || !Km_dev || !Vm_dev || !mask || !O_dev) return MC_EINVAL;
+    mc_options o;
+    if (resolve_options(opts, &o) != MC_OK) return MC_EINVAL;
     if ((p_bits != 8 && p_bits != 16) || (qkv_bits != 8 && qkv_bits != 4)) return MC_EUNSUPPORTED;
     const int epp = 128 / qkv_bits; // elements per 16-byte piece
     if (batch <= 0 || batch > 65535 || heads <= 0 || L <= 0 || dk <= 0 || dk % epp != 0) return MC_EINVAL;
     if (mask->M != L || mask->K != L || mask->V != 8) return MC_EINVAL;
-    if (!(s_p > 0.f) || !std::isfinite(s_q * s_k * s_v / s_p)) return MC_EINVAL;
+    // symmetric quantisation scales are positive; the fused kernel takes the row maximum on the
+    // integer scores, which is the maximum of the scaled ones only for a positive scale
+    if (!(s_q > 0.f) || !(s_k > 0.f) || !(s_v > 0.f) || !(s_p > 0.f) || !std::isfinite(s_q * s_k * s_v / s_p)) return MC_EINVAL;
     if (token_stride < dk || head_stride < dk || (batch > 1 && batch_stride < dk)) return MC_EINVAL;
     if ((int64_t)(L - 1) * token_stride + (int64_t)(heads - 1) * head_stride + dk > (int64_t)INT32_MAX) return MC_EINVAL;
     if (L > (1 << 24) || token_stride >= (1 << 24)) return MC_EINVAL; // kernels use 24-bit multiplies
     if (token_stride % epp != 0 || head_stride % epp != 0 || batch_stride % epp != 0) return MC_EALIGN;
     if (!aligned16(Q_dev) || !aligned16(Km_dev) || !aligned16(Vm_dev) || !aligned16(O_dev)) return MC_EALIGN;
-    if ((reinterpret_cast<uintptr_t>(workspace_dev) & 255u) != 0) return MC_EALIGN;
-    if (workspace_bytes < attn_layout(heads, mask, p_bits).total) return MC_ENOMEM;
+    if (!on_device_of(mask)) return MC_EINVAL;
     hipStream_t s = static_cast<hipStream_t>(stream);
 
-    if (g_attention_mode != 1 && (dk == 64 || dk == 128) &&
-        mask->max_panel_chunks * MC_CHUNK <= attention_fused_max_vectors()) {
+    if (attention_is_fused(mask, dk, o)) {
         AttnArgs f;
         f.panel_ptr = mask->d_panel_ptr; f.slot_idx = mask->d_slot_idx;
         f.Q = static_cast<const uint8_t *>(Q_dev); f.Km = static_cast<const uint8_t *>(Km_dev);
@@ -708,7 +759,7 @@ extern "C" int mc_sparse_attention_out(const void *Q_dev, const void *Km_dev, co
         const bool short_rows = dk == 64 || qkv_bits == 4;
         const bool pairs = short_rows && head_stride == dk && heads % 2 == 0 && !(p_bits == 16 && qkv_bits == 4);
         int hpg;
-        if (g_attention_mode == 0) {
+        if (o.attention_mode == 0) {
             // Halving the gather requests pays once the launch fills the chip (2048 (panel, head) units and
             // more: 13.3 against 15.6 us for 4096 of them; 5.0 against 4.7 us for 128).  Smaller launches get
             // more waves per unit instead, until about 2048 waves are in flight and while every wave still
@@ -718,14 +769,21 @@ extern "C" int mc_sparse_attention_out(const void *Q_dev, const void *Km_dev, co
             hpg = (pairs && units >= 2048) ? 2 : 1;
             if (hpg == 1) while (wpp < 4 && units * wpp * 2 <= 2048 && wpp * 2 <= avg) wpp *= 2;
         } else {
-            if (g_attention_mode == 3 && wpp < 2) wpp = 2;
-            if (g_attention_mode == 4) wpp = 4;
-            hpg = (g_attention_mode != 2 && pairs) ? 2 : 1;
+            if (o.attention_mode == 3 && wpp < 2) wpp = 2;
+            if (o.attention_mode == 4) wpp = 4;
+            hpg = (o.attention_mode != 2 && pairs) ? 2 : 1;
         }
         MC_HIP(launch_attention_fused(f, hpg, wpp, p_bits, qkv_bits, dk, s));
         return MC_OK;
     }
-    // the kernel pipeline runs the batch items one after the other through the same workspace
+    // the kernel pipeline keeps its intermediates in a workspace (none are needed when nothing is stored)
+    const size_t need = attn_layout(heads, mask, p_bits).total;
+    if (need > 0) {
+        if (!workspace_dev) return MC_EINVAL;
+        if ((reinterpret_cast<uintptr_t>(workspace_dev) & 255u) != 0) return MC_EALIGN;
+        if (workspace_bytes < need) return MC_ENOMEM;
+    }
+    // the batch items run one after the other through the same workspace
     for (int b = 0; b < batch; ++b) {
         const int64_t ib = (int64_t)b * batch_stride * qkv_bits / 8;
         const int rc = attention_pipeline(static_cast<const uint8_t *>(Q_dev) + ib, static_cast<const uint8_t *>(Km_dev) + ib,
@@ -733,8 +791,88 @@ extern "C" int mc_sparse_attention_out(const void *Q_dev, const void *Km_dev, co
                                           head_stride * qkv_bits / 8, token_stride * qkv_bits / 8, head_stride,
                                           token_stride, mask, s_q, s_k, s_v, s_p,
                                           static_cast<uint8_t *>(O_dev) + (int64_t)b * batch_stride * (out_f16 ? 2 : 4),
-                                          out_f16, workspace_dev, s);
+                                          out_f16, workspace_dev, o, s);
         if (rc != MC_OK) return rc;
     }
     return MC_OK;
+}
+} // namespace
+
+extern "C" size_t mc_attention_workspace_bytes_bits(int heads, const mc_mat *mask, int p_bits)
+{
+    if (!mask || heads <= 0 || (p_bits != 8 && p_bits != 16)) return 0;
+    return attn_layout(heads, mask, p_bits).total;
+}
+
+extern "C" size_t mc_attention_workspace_bytes(int heads, const mc_mat *mask)
+{
+    return mc_attention_workspace_bytes_bits(heads, mask, 8);
+}
+
+extern "C" size_t mc_attention_workspace_needed(int heads, int dk, const mc_mat *mask, int p_bits, const mc_options *options)
+{
+    if (!mask || heads <= 0 || (p_bits != 8 && p_bits != 16)) return 0;
+    mc_options o;
+    if (resolve_options(options, &o) != MC_OK) return 0;
+    return attention_is_fused(mask, dk, o) ? 0 : attn_layout(heads, mask, p_bits).total;
+}
+
+extern "C" int mc_sparse_attention(const int8_t *Q_dev, const int8_t *Km_dev, const int8_t *Vm_dev, int heads, int L,
+                                   int dk, const mc_mat *mask, float s_q, float s_k, float s_v, float s_p,
+                                   float *O_dev, void *workspace_dev, size_t workspace_bytes, void *stream)
+{
+    return attention_impl(Q_dev, Km_dev, Vm_dev, 1, heads, L, dk, 0, (int64_t)L * dk, dk, mask, 8, 8, s_q, s_k, s_v, s_p,
+                          MC_OUT_F32, O_dev, workspace_dev, workspace_bytes, nullptr, stream);
+}
+
+extern "C" int mc_sparse_attention_strided(const int8_t *Q_dev, const int8_t *Km_dev, const int8_t *Vm_dev, int heads,
+                                           int L, int dk, int64_t head_stride, int64_t token_stride,
+                                           const mc_mat *mask, float s_q, float s_k, float s_v, float s_p,
+                                           float *O_dev, void *workspace_dev, size_t workspace_bytes, void *stream)
+{
+    return attention_impl(Q_dev, Km_dev, Vm_dev, 1, heads, L, dk, 0, head_stride, token_stride, mask, 8, 8, s_q, s_k, s_v,
+                          s_p, MC_OUT_F32, O_dev, workspace_dev, workspace_bytes, nullptr, stream);
+}
+
+extern "C" int mc_sparse_attention_bits(const void *Q_dev, const void *Km_dev, const void *Vm_dev, int heads, int L,
+                                        int dk, int64_t head_stride, int64_t token_stride, const mc_mat *mask,
+                                        int p_bits, int qkv_bits, float s_q, float s_k, float s_v, float s_p,
+                                        float *O_dev, void *workspace_dev, size_t workspace_bytes, void *stream)
+{
+    return attention_impl(Q_dev, Km_dev, Vm_dev, 1, heads, L, dk, 0, head_stride, token_stride, mask, p_bits, qkv_bits, s_q,
+                          s_k, s_v, s_p, MC_OUT_F32, O_dev, workspace_dev, workspace_bytes, nullptr, stream);
+}
+
+extern "C" int mc_sparse_attention_batched(const void *Q_dev, const void *Km_dev, const void *Vm_dev, int batch,
+                                           int heads, int L, int dk, int64_t batch_stride, int64_t head_stride,
+                                           int64_t token_stride, const mc_mat *mask, int p_bits, int qkv_bits,
+                                           float s_q, float s_k, float s_v, float s_p, float *O_dev,
+                                           void *workspace_dev, size_t workspace_bytes, void *stream)
+{
+    return attention_impl(Q_dev, Km_dev, Vm_dev, batch, heads, L, dk, batch_stride, head_stride, token_stride, mask, p_bits,
+                          qkv_bits, s_q, s_k, s_v, s_p, MC_OUT_F32, O_dev, workspace_dev, workspace_bytes, nullptr,
+                          stream);
+}
+
+extern "C" int mc_sparse_attention_out(const void *Q_dev, const void *Km_dev, const void *Vm_dev, int batch, int heads,
+                                       int L, int dk, int64_t batch_stride, int64_t head_stride, int64_t token_stride,
+                                       const mc_mat *mask, int p_bits, int qkv_bits, float s_q, float s_k, float s_v,
+                                       float s_p, mc_out_type out_type, void *O_dev, void *workspace_dev,
+                                       size_t workspace_bytes, void *stream)
+{
+    return attention_impl(Q_dev, Km_dev, Vm_dev, batch, heads, L, dk, batch_stride, head_stride, token_stride, mask, p_bits,
+                          qkv_bits, s_q, s_k, s_v, s_p, out_type, O_dev, workspace_dev, workspace_bytes, nullptr,
+                          stream);
+}
+
+extern "C" int mc_sparse_attention_ex(const void *Q_dev, const void *Km_dev, const void *Vm_dev, int batch, int heads,
+                                      int L, int dk, int64_t batch_stride, int64_t head_stride, int64_t token_stride,
+                                      const mc_mat *mask, int p_bits, int qkv_bits, float s_q, float s_k, float s_v,
+                                      float s_p, mc_out_type out_type, const mc_options *options, void *O_dev,
+                                      void *workspace_dev, size_t workspace_bytes, void *stream)
+{
+    const mc_options automatic = {};
+    return attention_impl(Q_dev, Km_dev, Vm_dev, batch, heads, L, dk, batch_stride, head_stride, token_stride, mask, p_bits,
+                          qkv_bits, s_q, s_k, s_v, s_p, out_type, O_dev, workspace_dev, workspace_bytes,
+                          options ? options : &automatic, stream);
 }
