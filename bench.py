@@ -58,11 +58,18 @@ def build_problem():
     for i, prec in enumerate(["L8R8", "L4R4"]):
         prob["sddmm_" + prec] = wl.sddmm_case(M, K, KD_SDDMM, V, SPARSITY, prec, wl.seed_for(3, 10 * i))
     att = wl.attention_case(HEADS, L_ATT, DK, V, SPARSITY, wl.seed_for(5))
-    for n in ("q", "k", "v"):
-        att[n + "8"], att["s_" + n] = wl.quantize_inputs_int8(att[n])
     att["s_p"] = np.float32(1.0 / 127.0)
     prob["attention"] = att
     return prob
+
+
+def quantize_on_gpu(mc, torch, x, bits=8):
+    """The layer's input quantisation done by the library itself (mc_absmax + mc_quantize): fp32 host
+    array -> (integer codes as a host array, packed two per byte for bits=4; fp32 scale)."""
+    xd = torch.from_numpy(np.ascontiguousarray(x)).cuda()
+    amax = float(mc.absmax(xd).cpu()[0])
+    s = np.float32(np.float64(amax) / (127.0 if bits == 8 else 7.0))
+    return mc.quantize(xd, float(s), bits).cpu().numpy(), s
 
 
 def spmm_alg_bytes(nvec, P, lbits, rbits, N):
@@ -118,6 +125,8 @@ def main():
         return
 
     prob = build_problem()
+    for n in ("q", "k", "v"):
+        prob["attention"][n + "8"], prob["attention"]["s_" + n] = quantize_on_gpu(mc, torch, prob["attention"][n])
     t0 = time.perf_counter()
     kernels = []  # name, launch(), ops, algorithmic bytes, device kernel name
 
@@ -454,7 +463,7 @@ def measure_extras(mc, torch, prob, stream, reps, up):
     O = torch.empty((HEADS, L_ATT, DK), dtype=torch.float32, device="cuda")
     for name, p_bits, qkv_bits in (("attention_16b8b", 16, 8), ("attention_8b4b", 8, 4)):
         if qkv_bits == 4:
-            (q, s_q), (k, s_k), (v, s_v) = (wl.quantize_inputs_int4(att[n]) for n in "qkv")
+            (q, s_q), (k, s_k), (v, s_v) = (quantize_on_gpu(mc, torch, att[n], 4) for n in "qkv")
         else:
             q, k, v, s_q, s_k, s_v = att["q8"], att["k8"], att["v8"], att["s_q"], att["s_k"], att["s_v"]
         q, k, v = up(q), up(k), up(v)
@@ -488,7 +497,7 @@ def measure_extras(mc, torch, prob, stream, reps, up):
                                           hbm_frac=round(HEADS * nsc * 5 / us / 1e3 / HBM_PEAK_GBS, 3))
     del Ssm, csm
     # the same layer with head dimension 128 (rows of 128 bytes): the fused kernel and the three kernels
-    x128, s128 = wl.quantize_inputs_int8(wl.normal_fp32((HEADS, L_ATT, 128), wl.seed_for(5, 9)))
+    x128, s128 = quantize_on_gpu(mc, torch, wl.normal_fp32((HEADS, L_ATT, 128), wl.seed_for(5, 9)))
     q128 = tmaj(x128) # serves as Q, K and V: timing only
     O128 = torch.empty((L_ATT, HEADS, 128), dtype=torch.float32, device="cuda").permute(1, 0, 2)
     for name, mode in (("attention_8b8b_dk128", 0), ("attention_8b8b_dk128_three_kernels", 1)):
@@ -546,7 +555,7 @@ def measure_extras(mc, torch, prob, stream, reps, up):
             else:
                 O = torch.empty((batch, heads, L, DK), dtype=torch.float32, device="cuda")
             for name, p_bits, qkv_bits in (("8b-8b", 8, 8), ("16b-8b", 16, 8), ("8b-4b", 8, 4)):
-                xq, sx = (wl.quantize_inputs_int4 if qkv_bits == 4 else wl.quantize_inputs_int8)(x)
+                xq, sx = quantize_on_gpu(mc, torch, x, qkv_bits)
                 # the same tensor serves as Q, K and V: timing only
                 q = up(np.ascontiguousarray(np.transpose(xq, (0, 2, 1, 3)))).permute(0, 2, 1, 3) if layout == "token" else up(xq)
                 ws = torch.empty(mc.attention_workspace_bytes(heads, m, p_bits), dtype=torch.uint8, device="cuda")

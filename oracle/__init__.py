@@ -141,6 +141,18 @@ def unpack_int4(packed, unsigned: bool = False) -> np.ndarray:
     return out
 
 
+def pack_int4(q) -> np.ndarray:
+    """Inverse of ``unpack_int4`` for values in [-8, 7] (or [0, 15]): two 4-bit values per byte along the
+    last axis, element 2j in bits 3:0 and element 2j+1 in bits 7:4 of byte j.  Returns uint8 with the
+    last axis halved."""
+    q = np.asarray(q).astype(np.int64)
+    if q.shape[-1] % 2:
+        raise ValueError("the last axis must hold an even number of 4-bit values")
+    if q.size and (q.min() < -8 or q.max() > 15):
+        raise ValueError("value outside four bits")
+    return ((q[..., 0::2] & 15) | ((q[..., 1::2] & 15) << 4)).astype(np.uint8)
+
+
 def stored_flags(M: int, K: int, V: int, row_ptr, col_idx) -> np.ndarray:
     """(M//V, K) uint8 flags of the stored vectors of a BCRS pattern with V x 1 blocks."""
     P = M // V
@@ -299,9 +311,12 @@ def dequantize(acc, scale, out_bits: int = 32) -> np.ndarray:
         return x.astype(np.float32 if out_bits == 32 else np.float16)
 
 
-# Largest code of the re-quantised softmax output.  8 bits: the int8 maximum.  16 bits: the
-# largest value whose split into two SIGNED bytes (hi = (c + 128) >> 8) still fits, which is
-# what a signed x signed matrix unit can take as a two-plane operand.
+# Largest code of the re-quantised softmax output.  8 bits: the int8 maximum.  16 bits: 32639, a
+# CONVENTION of this build and not a statement of the paper (which fixes no code range for its
+# "16b" layers): it is the largest value whose split into two SIGNED bytes (hi = (c + 128) >> 8)
+# still fits, i.e. the limit of a signed x signed matrix unit fed a two-plane operand.  The
+# ceiling is only reached when s_p is chosen below 1/32639; with the default s_p = 1/32639 the
+# clamp is inactive and the codes are rint(p / s_p) as for any other static scale.
 P_CODE_MAX = {8: 127, 16: 32639}
 
 

@@ -1,8 +1,8 @@
 """Seeded synthetic inputs shaped like the paper's workloads.
 
 This module only draws random patterns and values (NumPy PCG64, fixed seeds).  It
-holds none of the method's arithmetic and is the one piece shared by the GPU tests,
-the benchmark and the CPU oracle's tests.
+holds none of the method's arithmetic (not even the quantisation of the layer's inputs)
+and is the one piece shared by the GPU tests, the benchmark and the CPU oracle's tests.
 
 The paper evaluates on DLMC matrices dilated to V x 1 vectors (Section 5) and on a
 sparse-Transformer attention layer (Section 5.3).  Neither data set is available, so
@@ -133,25 +133,3 @@ def attention_case(heads, L, dk, V, sparsity, seed: int):
                 q=normal_fp32((heads, L, dk), seed + 1),
                 k=normal_fp32((heads, L, dk), seed + 2),
                 v=normal_fp32((heads, L, dk), seed + 3))
-
-
-def quantize_inputs_int8(x: np.ndarray):
-    """Input preparation for the attention layer: fp32 tensor -> (int8 codes, fp32 scale).
-
-    One symmetric scale per tensor, s = max|x| / 127, codes = rint(x / s) clipped to
-    [-127, 127].  It is done once on the host so that the CPU oracle and the GPU path
-    start from the very same int8 tensors; the hot path itself begins at those codes.
-    """
-    s = np.float32(np.max(np.abs(x.astype(np.float64))) / 127.0)
-    q = np.clip(np.rint(x.astype(np.float64) / np.float64(s)), -127, 127).astype(np.int8)
-    return q, s
-
-
-def quantize_inputs_int4(x: np.ndarray):
-    """As quantize_inputs_int8 with 4-bit codes: s = max|x| / 7, codes in [-7, 7], packed two
-    per byte along the last axis (element 2j in bits 3:0, element 2j+1 in bits 7:4).
-    Returns (packed uint8 array with half the last dimension, fp32 scale)."""
-    s = np.float32(np.max(np.abs(x.astype(np.float64))) / 7.0)
-    q = np.clip(np.rint(x.astype(np.float64) / np.float64(s)), -7, 7).astype(np.int64)
-    packed = (q[..., 0::2] & 15) | ((q[..., 1::2] & 15) << 4)
-    return packed.astype(np.uint8), s

@@ -14,6 +14,7 @@ import numpy as np
 import pytest
 
 from paper_2209_06979_amd import workloads as wl
+import input_prep as prep
 from gpu_util import torch_dev, run_spmm_oracle, run_sddmm_oracle
 
 pytestmark = pytest.mark.gpu
@@ -159,7 +160,7 @@ def _attention_f16(heads, L, dk, sparsity, seed, p_bits=8, qkv_bits=8, token_maj
           f"mode={mode} batch={batch}", flush=True)
     items = [wl.attention_case(heads, L, dk, V, sparsity, seed + i) for i in range(max(batch, 1))]
     c = items[0]
-    quant = wl.quantize_inputs_int4 if qkv_bits == 4 else wl.quantize_inputs_int8
+    quant = prep.quantize_inputs_int4 if qkv_bits == 4 else prep.quantize_inputs_int8
     # one scale per tensor over the whole batch: quantise the stacked tensors
     stacked = {n: np.stack([it[n] for it in items]) for n in "qkv"}
     (q, s_q), (k, s_k), (v, s_v) = (quant(stacked[n]) for n in "qkv")

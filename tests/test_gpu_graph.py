@@ -3,6 +3,7 @@ import numpy as np
 import pytest
 
 from paper_2209_06979_amd import workloads as wl
+import input_prep as prep
 
 pytestmark = pytest.mark.gpu
 
@@ -18,8 +19,8 @@ def test_graph_replays_match_eager():
     mask = mc.SparseMatrix(512, 512, 8, s["row_ptr"], s["col_idx"])
     Q, Km = torch.from_numpy(s["Q"]).to(dev), torch.from_numpy(s["Kmat"]).to(dev)
     a = wl.attention_case(2, 512, 64, 8, 0.8, 13)
-    q8, s_q = wl.quantize_inputs_int8(a["q"]); k8, s_k = wl.quantize_inputs_int8(a["k"])
-    v8, s_v = wl.quantize_inputs_int8(a["v"])
+    q8, s_q = prep.quantize_inputs_int8(a["q"]); k8, s_k = prep.quantize_inputs_int8(a["k"])
+    v8, s_v = prep.quantize_inputs_int8(a["v"])
     amask = mc.SparseMatrix(512, 512, 8, a["row_ptr"], a["col_idx"])
     q8, k8, v8 = (torch.from_numpy(t).to(dev) for t in (q8, k8, v8))
     C = torch.empty((512, 128), dtype=torch.int32, device=dev)

@@ -23,15 +23,15 @@ def test_absmax_and_int8_codes_equal_the_oracle(shape):
 
 
 @pytest.mark.parametrize("shape", [(2, 64, 16), (8, 4096, 64), (3, 1002), (1, 2)])
-def test_int4_codes_and_packing_equal_the_input_preparation(shape):
+def test_int4_codes_and_packing_equal_the_oracle(shape):
     import torch
     import oracle
     from paper_2209_06979_amd import binding as mc
     x = wl.normal_fp32(shape, 6100 + len(shape))
-    packed, s = wl.quantize_inputs_int4(x)                 # pinned to the oracle's quantiser in the CPU tests
+    q, s = oracle.quantize_per_tensor(x, 4)
+    packed = oracle.pack_int4(q)
     got = mc.quantize(torch.from_numpy(x).cuda(), float(s), 4).cpu().numpy()
     assert got.dtype == np.uint8 and got.shape == packed.shape and np.array_equal(got, packed)
-    q = oracle.quantize_per_tensor(x, 4)[0]
     assert np.array_equal(oracle.unpack_int4(got).astype(np.int8), q)
 
 

@@ -7,6 +7,7 @@ import numpy as np
 import pytest
 
 from paper_2209_06979_amd import workloads as wl
+import input_prep as prep
 from gpu_util import run_spmm_gpu, run_spmm_oracle, run_sddmm_gpu, run_sddmm_oracle
 
 pytestmark = pytest.mark.gpu
@@ -99,7 +100,7 @@ def test_random_attention(seed):
         p_bits, qkv_bits = int(rng.choice([8, 16])), int(rng.choice([8, 4]))
         mode, tmaj, f16 = int(rng.choice([0, 1, 2, 3, 4, 5])), bool(rng.integers(2)), bool(rng.integers(2))
         c = wl.attention_case(heads, L, dk, 8, s, int(rng.integers(1 << 30)))
-        quant = wl.quantize_inputs_int4 if qkv_bits == 4 else wl.quantize_inputs_int8
+        quant = prep.quantize_inputs_int4 if qkv_bits == 4 else prep.quantize_inputs_int8
         (q, s_q), (k, s_k), (v, s_v) = (quant(c[nm]) for nm in "qkv")
         s_p = np.float32(1.0 / oracle.P_CODE_MAX[p_bits] / float(rng.choice([1, 1, 3])))
         print(f"#{n} attention heads={heads} L={L} dk={dk} s={s} {p_bits}b-{qkv_bits}b mode={mode} token_major={tmaj} "

@@ -3,6 +3,7 @@ import numpy as np
 import pytest
 
 from paper_2209_06979_amd import workloads as wl
+import input_prep as prep
 from gpu_util import run_sddmm_gpu, run_sddmm_oracle, torch_dev
 
 pytestmark = pytest.mark.gpu
@@ -121,8 +122,8 @@ def _attention_check(heads, L, dk, sparsity, seed, mode=0, token_major=False):
     from paper_2209_06979_amd import binding as mc
     V = 8
     c = wl.attention_case(heads, L, dk, V, sparsity, seed)
-    q8, s_q = wl.quantize_inputs_int8(c["q"]); k8, s_k = wl.quantize_inputs_int8(c["k"])
-    v8, s_v = wl.quantize_inputs_int8(c["v"])
+    q8, s_q = prep.quantize_inputs_int8(c["q"]); k8, s_k = prep.quantize_inputs_int8(c["k"])
+    v8, s_v = prep.quantize_inputs_int8(c["v"])
     s_p = np.float32(1.0 / 127.0)
     print(f"attention heads={heads} L={L} dk={dk} s={sparsity} mode={mode} token_major={token_major}", flush=True)
     mask = mc.SparseMatrix(L, L, V, c["row_ptr"], c["col_idx"])
@@ -222,9 +223,9 @@ def test_attention_ragged_rows():
     V, L, dk, heads = 8, 512, 64, 2
     counts = np.r_[[0, 1, 2, 15, 16, 17, 63, 64, 65, 127, 128, 129, 300, 511, 512, 0], np.full(L // V - 16, 40)]
     rp, ci = wl.ragged_pattern(L, L, V, counts, 1300)
-    q8, s_q = wl.quantize_inputs_int8(wl.normal_fp32((heads, L, dk), 1301))
-    k8, s_k = wl.quantize_inputs_int8(wl.normal_fp32((heads, L, dk), 1302))
-    v8, s_v = wl.quantize_inputs_int8(wl.normal_fp32((heads, L, dk), 1303))
+    q8, s_q = prep.quantize_inputs_int8(wl.normal_fp32((heads, L, dk), 1301))
+    k8, s_k = prep.quantize_inputs_int8(wl.normal_fp32((heads, L, dk), 1302))
+    v8, s_v = prep.quantize_inputs_int8(wl.normal_fp32((heads, L, dk), 1303))
     s_p = np.float32(1 / 127)
     want, _, probs, _ = oracle.attention(q8, k8, v8, rp, ci, V, s_q, s_k, s_v, s_p)
     amb = _tie_ambiguous(probs, s_p).reshape(heads, -1, V)

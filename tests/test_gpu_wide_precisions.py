@@ -4,6 +4,7 @@ import numpy as np
 import pytest
 
 from paper_2209_06979_amd import workloads as wl
+import input_prep as prep
 from gpu_util import run_spmm_gpu, run_spmm_oracle, run_sddmm_gpu, run_sddmm_oracle
 
 pytestmark = pytest.mark.gpu
@@ -171,7 +172,7 @@ def _attention_variant_check(heads, L, dk, sparsity, seed, p_bits, qkv_bits, tok
     from test_gpu_sddmm import _tie_ambiguous, _layout
     V = 8
     c = wl.attention_case(heads, L, dk, V, sparsity, seed)
-    quant = wl.quantize_inputs_int4 if qkv_bits == 4 else wl.quantize_inputs_int8
+    quant = prep.quantize_inputs_int4 if qkv_bits == 4 else prep.quantize_inputs_int8
     (q, s_q), (k, s_k), (v, s_v) = (quant(c[n]) for n in "qkv")
     s_p = np.float32(1.0 / oracle.P_CODE_MAX[p_bits]) if s_p is None else np.float32(s_p)
     vmax = 7 if qkv_bits == 4 else 127
@@ -285,7 +286,7 @@ def test_attention_16b8b_ragged_rows():
     V, L, dk, heads = 8, 512, 64, 2
     counts = np.r_[[0, 1, 2, 15, 16, 17, 63, 64, 65, 127, 128, 129, 300, 511, 512, 0], np.full(L // V - 16, 40)]
     rp, ci = wl.ragged_pattern(L, L, V, counts, 4200)
-    (q, s_q), (k, s_k), (v, s_v) = (wl.quantize_inputs_int8(wl.normal_fp32((heads, L, dk), 4201 + i)) for i in range(3))
+    (q, s_q), (k, s_k), (v, s_v) = (prep.quantize_inputs_int8(wl.normal_fp32((heads, L, dk), 4201 + i)) for i in range(3))
     s_p = np.float32(1 / 32639)
     want = oracle.attention(q, k, v, rp, ci, V, s_q, s_k, s_v, s_p, p_bits=16)[0]
     mask = mc.SparseMatrix(L, L, V, rp, ci)
@@ -332,7 +333,7 @@ def test_attention_batched_long_panels_equal_item_by_item(L, dk, sparsity, mode)
     from paper_2209_06979_amd import binding as mc
     B, heads, V = 2, 2, 8
     c = wl.attention_case(B * heads, L, dk, V, sparsity, 4450 + dk)
-    (q, s_q), (k, s_k), (v, s_v) = (wl.quantize_inputs_int8(c[n]) for n in "qkv")
+    (q, s_q), (k, s_k), (v, s_v) = (prep.quantize_inputs_int8(c[n]) for n in "qkv")
     s_p = np.float32(1.0 / 127.0)
     mask = mc.SparseMatrix(L, L, V, c["row_ptr"], c["col_idx"])
     try:
@@ -378,7 +379,7 @@ def test_attention_batched_equals_item_by_item(p_bits, qkv_bits, mode):
     from paper_2209_06979_amd import binding as mc
     B, heads, L, dk, V = 3, 4, 512, 64, 8
     c = wl.attention_case(B * heads, L, dk, V, 0.8, 4400)
-    quant = wl.quantize_inputs_int4 if qkv_bits == 4 else wl.quantize_inputs_int8
+    quant = prep.quantize_inputs_int4 if qkv_bits == 4 else prep.quantize_inputs_int8
     (q, s_q), (k, s_k), (v, s_v) = (quant(c[n]) for n in "qkv")
     s_p = np.float32(1.0 / (32639.0 if p_bits == 16 else 127.0))
     mask = mc.SparseMatrix(L, L, V, c["row_ptr"], c["col_idx"])

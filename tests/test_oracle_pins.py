@@ -9,6 +9,7 @@ import torch
 
 import oracle
 from paper_2209_06979_amd import workloads as wl
+import input_prep as prep
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
 
@@ -407,13 +408,33 @@ def test_requantize_rounding():
     del p
 
 
-def test_quantizer_agrees_with_input_preparation():
-    x = wl.normal_fp32((2, 64, 16), 5)
-    q1, s1 = oracle.quantize_per_tensor(x)
-    q2, s2 = wl.quantize_inputs_int8(x)
-    assert s1 == s2 and np.array_equal(q1, q2)
-    assert np.abs(q1).max() == 127
-    assert np.max(np.abs(q1 * np.float64(s1) - x)) <= 0.5 * s1 + 1e-7
+def test_quantizer_hand_worked_values_and_bounds():
+    """Symmetric per-tensor quantisation (Section 5.3, first step) on values worked out by hand: with max|x| = 2
+    the 8-bit scale is 2/127 and x/s = 63.5 x; the 4-bit scale is 2/7 and x/s = 3.5 x."""
+    x = np.array([-2.0, -1.01, 0.3, 0.52, 2.0, 0.0], np.float32)
+    q8, s8 = oracle.quantize_per_tensor(x, 8)
+    assert s8 == np.float32(2.0 / 127.0) and q8.tolist() == [-127, -64, 19, 33, 127, 0]
+    q4, s4 = oracle.quantize_per_tensor(x, 4)
+    assert s4 == np.float32(2.0 / 7.0) and q4.tolist() == [-7, -4, 1, 2, 7, 0]
+    y = wl.normal_fp32((2, 64, 16), 5)
+    q, s = oracle.quantize_per_tensor(y)
+    assert np.abs(q).max() == 127
+    assert np.max(np.abs(q * np.float64(s) - y)) <= 0.5 * s + 1e-7
+
+
+def test_pack_int4_explicit_bytes_and_round_trip():
+    """Element 2j sits in bits 3:0 and element 2j+1 in bits 7:4 of byte j, two's complement."""
+    assert oracle.pack_int4(np.array([1, 2, -1, 7, -8, 0])).tolist() == [0x21, 0x7F, 0x08]
+    allb = np.arange(256, dtype=np.uint8).reshape(128, 2)
+    assert np.array_equal(oracle.pack_int4(oracle.unpack_int4(allb)), allb)
+    q = np.random.default_rng(3).integers(-8, 8, size=(5, 3, 8))
+    assert np.array_equal(oracle.unpack_int4(oracle.pack_int4(q)), q)
+    with pytest.raises(ValueError):
+        oracle.pack_int4(np.array([1, 2, 3]))
+    with pytest.raises(ValueError):
+        oracle.pack_int4(np.array([16, 0]))
+    packed, s = prep.quantize_inputs_int4(np.array([[-2.0, 0.3, 0.52, 2.0]], np.float32))
+    assert packed.tolist() == [[0x19, 0x72]] and s == np.float32(2.0 / 7.0)
 
 
 def test_attention_against_dense_torch_reference():
@@ -421,8 +442,8 @@ def test_attention_against_dense_torch_reference():
     positions and the same fake-quantisation steps."""
     heads, L, dk, V = 2, 64, 16, 8
     c = wl.attention_case(heads, L, dk, V, 0.75, 900)
-    q8, s_q = wl.quantize_inputs_int8(c["q"]); k8, s_k = wl.quantize_inputs_int8(c["k"])
-    v8, s_v = wl.quantize_inputs_int8(c["v"])
+    q8, s_q = prep.quantize_inputs_int8(c["q"]); k8, s_k = prep.quantize_inputs_int8(c["k"])
+    v8, s_v = prep.quantize_inputs_int8(c["v"])
     s_p = np.float32(1.0 / 127.0)
     O, scores, probs, codes = oracle.attention(q8, k8, v8, c["row_ptr"], c["col_idx"], V, s_q, s_k, s_v, s_p)
     flags = oracle.stored_flags(L, L, V, c["row_ptr"], c["col_idx"])
@@ -504,7 +525,7 @@ def test_dequantize_rounds_once_to_nearest_even():
 def test_attention_output_types_are_single_roundings():
     heads, L, dk, V = 2, 64, 16, 8
     c = wl.attention_case(heads, L, dk, V, 0.75, 902)
-    (q, s_q), (k, s_k), (v, s_v) = (wl.quantize_inputs_int8(c[n]) for n in "qkv")
+    (q, s_q), (k, s_k), (v, s_v) = (prep.quantize_inputs_int8(c[n]) for n in "qkv")
     args = (q, k, v, c["row_ptr"], c["col_idx"], V, s_q, s_k, s_v, np.float32(1 / 127))
     O64 = oracle.attention(*args)[0]
     O16 = oracle.attention(*args, out_bits=16)[0]
@@ -531,7 +552,7 @@ def test_attention_variants_against_dense_torch_reference(p_bits, qkv_bits):
     heads, L, dk, V = 2, 64, 16, 8
     c = wl.attention_case(heads, L, dk, V, 0.75, 901)
     if qkv_bits == 4:
-        (q, s_q), (k, s_k), (v, s_v) = (wl.quantize_inputs_int4(c[n]) for n in "qkv")
+        (q, s_q), (k, s_k), (v, s_v) = (prep.quantize_inputs_int4(c[n]) for n in "qkv")
         # unpack by an independent formula: sign-extend nibbles with int8 shifts
         def widen(p):
             lo = (np.left_shift(p, 4).astype(np.uint8).view(np.int8) >> 4)
@@ -542,7 +563,7 @@ def test_attention_variants_against_dense_torch_reference(p_bits, qkv_bits):
             oq, os_ = oracle.quantize_per_tensor(c[t], 4)
             assert os_ == ts and np.array_equal(oq, tq) and np.abs(tq).max() == 7
     else:
-        (q, s_q), (k, s_k), (v, s_v) = (wl.quantize_inputs_int8(c[n]) for n in "qkv")
+        (q, s_q), (k, s_k), (v, s_v) = (prep.quantize_inputs_int8(c[n]) for n in "qkv")
         qi, ki, vi = q, k, v
     pmax = {8: 127, 16: 32639}[p_bits]
     s_p = np.float32(1.0 / pmax)
