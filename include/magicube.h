@@ -357,6 +357,24 @@ int mc_sparse_attention_ex(const void *Q_dev, const void *Km_dev, const void *Vm
                            mc_out_type out_type, const mc_options *options, void *O_dev, void *workspace_dev,
                            size_t workspace_bytes, void *stream);
 
+/* For callers that cannot allocate device memory or hand over a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): mc_sparse_attention_ex without the
+ * workspace arguments.  When the layer runs as the pipeline of separate kernels, its intermediates
+ * go to an array the library itself holds in device memory -- MC_STATIC_SCRATCH_BYTES per GPU the
+ * library has run on, from the first such call on that GPU until the process ends.  A layer whose
+ * intermediates (mc_attention_workspace_bytes_bits(heads, mask, p_bits) bytes) exceed that size is
+ * refused with MC_ENOMEM before anything is launched (mc_last_error_detail() gives both sizes).  The
+ * call allocates nothing and frees nothing; the first call on a device looks up the array's address
+ * (make it once outside a graph capture).  All calls on one GPU share the array: every call
+ * overwrites all of it that it reads, so nothing has to be cleared between calls, but two calls that
+ * overlap in time on the same GPU (different streams, different threads) race on it.  options ==
+ * NULL: the calling thread's defaults.  Results equal mc_sparse_attention_ex's. */
+#define MC_STATIC_SCRATCH_BYTES (16u << 20)
+int mc_sparse_attention_static(const void *Q_dev, const void *Km_dev, const void *Vm_dev, int batch, int heads, int L,
+                               int dk, int64_t batch_stride, int64_t head_stride, int64_t token_stride,
+                               const mc_mat *mask, int p_bits, int qkv_bits, float s_q, float s_k, float s_v,
+                               float s_p, mc_out_type out_type, const mc_options *options, void *O_dev, void *stream);
+
 /* ------------------------------------------------------------------------------------
  * One-knob setters kept for existing callers, tests and measurements.  Each changes one field of
  * the CALLING THREAD's default options (see mc_set_thread_options); none is needed for

@@ -104,6 +104,9 @@ def _load() -> ctypes.CDLL:
     L.mc_sparse_attention_ex.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int64, c_int64,
                                          c_int64, c_void_p, c_int, c_int, c_float, c_float, c_float, c_float, c_int,
                                          POINTER(Options), c_void_p, c_void_p, c_size_t, c_void_p]
+    L.mc_sparse_attention_static.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int64, c_int64,
+                                             c_int64, c_void_p, c_int, c_int, c_float, c_float, c_float, c_float, c_int,
+                                             POINTER(Options), c_void_p, c_void_p]
     L.mc_attention_workspace_needed.argtypes = [c_int, c_int, c_void_p, c_int, POINTER(Options)]
     L.mc_attention_workspace_needed.restype = c_size_t
     L.mc_set_spmm_variant.argtypes = [c_int, c_int]
@@ -118,7 +121,7 @@ def _load() -> ctypes.CDLL:
                  "mc_absmax", "mc_quantize", "mc_sparse_attention_out", "mc_spmm_dequant", "mc_sddmm_dequant", "mc_sparse_softmax_to_mat",
                  "mc_set_spmm_variant", "mc_set_attention_mode", "mc_set_sddmm_variant", "mc_set_spmm_splitting", "mc_set_spmm_stages",
                  "mc_set_softmax_variant", "mc_set_thread_options", "mc_get_thread_options", "mc_spmm_ex", "mc_sddmm_ex",
-                 "mc_sparse_attention_ex"):
+                 "mc_sparse_attention_ex", "mc_sparse_attention_static"):
         getattr(L, name).restype = c_int
     return L
 
@@ -407,6 +410,30 @@ def attention_workspace_needed(heads: int, dk: int, mask: SparseMatrix, p_bits: 
     """Bytes of workspace the layer will really use (0 when the fused kernel takes it)."""
     return int(lib.mc_attention_workspace_needed(heads, dk, mask.handle, p_bits,
                                                  None if options is None else ctypes.byref(options)))
+
+
+STATIC_SCRATCH_BYTES = 16 << 20
+
+
+def sparse_attention_static(Q8, K8, V8, mask: SparseMatrix, s_q, s_k, s_v, s_p, out, p_bits: int = 8, qkv_bits: int = 8,
+                            options: Options | None = None):
+    """sparse_attention for callers that cannot allocate: no workspace argument (the library's own per-GPU array
+    holds the intermediates) and a caller-provided ``out``.  This wrapper allocates nothing on the device either."""
+    epb = 8 // qkv_bits
+    batched = Q8.dim() == 4
+    batch = Q8.shape[0] if batched else 1
+    heads, L, dkb = Q8.shape[-3:]
+    dk = dkb * epb
+    st = tuple(x * epb for x in Q8.stride()[:-1])
+    bs, hs, ts = (st if batched else (0,) + st)
+    for t in (Q8, K8, V8):
+        assert t.is_cuda and t.element_size() == 1 and t.shape == Q8.shape and t.stride() == Q8.stride() and t.stride(-1) == 1
+    assert out.is_cuda and out.dtype in OUT_TYPE and out.shape == tuple(Q8.shape[:-1]) + (dk,) and out.stride() == st + (1,)
+    _check(lib.mc_sparse_attention_static(Q8.data_ptr(), K8.data_ptr(), V8.data_ptr(), batch, heads, L, dk, bs, hs, ts,
+                                          mask.handle, p_bits, qkv_bits, float(s_q), float(s_k), float(s_v), float(s_p),
+                                          OUT_TYPE[out.dtype], None if options is None else ctypes.byref(options),
+                                          out.data_ptr(), _stream()), "mc_sparse_attention_static")
+    return out
 
 
 def sparse_attention(Q8, K8, V8, mask: SparseMatrix, s_q, s_k, s_v, s_p, out=None, workspace=None,

@@ -716,10 +716,36 @@ bool attention_is_fused(const mc_mat *mask, int dk, const mc_options &o)
            mask->max_panel_chunks * MC_CHUNK <= attention_fused_max_vectors();
 }
 
+// Memory the library itself provides to callers that cannot allocate (mc_sparse_attention_static):
+// one array per GPU, in that GPU's memory for the life of the process; its address on each device is
+// looked up once, with that device current.
+constexpr size_t STATIC_SCRATCH_BYTES = MC_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+constexpr int MAX_DEVICES = 64;
+void *g_scratch_ptr[MAX_DEVICES] = {};
+std::mutex g_scratch_mutex;
+
+int static_scratch(void **ptr)
+{
+    int dev = -1;
+    if (!hip_ok(hipGetDevice(&dev), "hipGetDevice")) return MC_EHIP;
+    if (dev < 0 || dev >= MAX_DEVICES) return MC_EUNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (!hip_ok(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)), "hipGetSymbolAddress(scratch)")) return MC_EHIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return MC_OK;
+}
+
+// use_static: the intermediates of the kernel pipeline go to the library's per-device array instead
+// of a caller's workspace
 int attention_impl(const void *Q_dev, const void *Km_dev, const void *Vm_dev, int batch, int heads, int L, int dk,
                    int64_t batch_stride, int64_t head_stride, int64_t token_stride, const mc_mat *mask, int p_bits,
                    int qkv_bits, float s_q, float s_k, float s_v, float s_p, mc_out_type out_type, void *O_dev,
-                   void *workspace_dev, size_t workspace_bytes, const mc_options *opts, void *stream)
+                   void *workspace_dev, size_t workspace_bytes, bool use_static, const mc_options *opts, void *stream)
 {
     if (out_type != MC_OUT_F32 && out_type != MC_OUT_F16) return MC_EUNSUPPORTED;
     const int out_f16 = (out_type == MC_OUT_F16) ? 1 : 0;
@@ -778,7 +804,15 @@ int attention_impl(const void *Q_dev, const void *Km_dev, const void *Vm_dev, in
     }
     // the kernel pipeline keeps its intermediates in a workspace (none are needed when nothing is stored)
     const size_t need = attn_layout(heads, mask, p_bits).total;
-    if (need > 0) {
+    if (use_static) {
+        if (need > STATIC_SCRATCH_BYTES) {
+            snprintf(g_detail, sizeof g_detail, "the layer's intermediates need %zu bytes, the library's own array holds %zu",
+                     need, STATIC_SCRATCH_BYTES);
+            return MC_ENOMEM;
+        }
+        const int rc = static_scratch(&workspace_dev);
+        if (rc != MC_OK) return rc;
+    } else if (need > 0) {
         if (!workspace_dev) return MC_EINVAL;
         if ((reinterpret_cast<uintptr_t>(workspace_dev) & 255u) != 0) return MC_EALIGN;
         if (workspace_bytes < need) return MC_ENOMEM;
@@ -822,7 +856,7 @@ extern "C" int mc_sparse_attention(const int8_t *Q_dev, const int8_t *Km_dev, co
                                    float *O_dev, void *workspace_dev, size_t workspace_bytes, void *stream)
 {
     return attention_impl(Q_dev, Km_dev, Vm_dev, 1, heads, L, dk, 0, (int64_t)L * dk, dk, mask, 8, 8, s_q, s_k, s_v, s_p,
-                          MC_OUT_F32, O_dev, workspace_dev, workspace_bytes, nullptr, stream);
+                          MC_OUT_F32, O_dev, workspace_dev, workspace_bytes, false, nullptr, stream);
 }
 
 extern "C" int mc_sparse_attention_strided(const int8_t *Q_dev, const int8_t *Km_dev, const int8_t *Vm_dev, int heads,
@@ -831,7 +865,7 @@ extern "C" int mc_sparse_attention_strided(const int8_t *Q_dev, const int8_t *Km
                                            float *O_dev, void *workspace_dev, size_t workspace_bytes, void *stream)
 {
     return attention_impl(Q_dev, Km_dev, Vm_dev, 1, heads, L, dk, 0, head_stride, token_stride, mask, 8, 8, s_q, s_k, s_v,
-                          s_p, MC_OUT_F32, O_dev, workspace_dev, workspace_bytes, nullptr, stream);
+                          s_p, MC_OUT_F32, O_dev, workspace_dev, workspace_bytes, false, nullptr, stream);
 }
 
 extern "C" int mc_sparse_attention_bits(const void *Q_dev, const void *Km_dev, const void *Vm_dev, int heads, int L,
@@ -840,7 +874,7 @@ extern "C" int mc_sparse_attention_bits(const void *Q_dev, const void *Km_dev, c
                                         float *O_dev, void *workspace_dev, size_t workspace_bytes, void *stream)
 {
     return attention_impl(Q_dev, Km_dev, Vm_dev, 1, heads, L, dk, 0, head_stride, token_stride, mask, p_bits, qkv_bits, s_q,
-                          s_k, s_v, s_p, MC_OUT_F32, O_dev, workspace_dev, workspace_bytes, nullptr, stream);
+                          s_k, s_v, s_p, MC_OUT_F32, O_dev, workspace_dev, workspace_bytes, false, nullptr, stream);
 }
 
 extern "C" int mc_sparse_attention_batched(const void *Q_dev, const void *Km_dev, const void *Vm_dev, int batch,
@@ -850,7 +884,7 @@ extern "C" int mc_sparse_attention_batched(const void *Q_dev, const void *Km_dev
                                            void *workspace_dev, size_t workspace_bytes, void *stream)
 {
     return attention_impl(Q_dev, Km_dev, Vm_dev, batch, heads, L, dk, batch_stride, head_stride, token_stride, mask, p_bits,
-                          qkv_bits, s_q, s_k, s_v, s_p, MC_OUT_F32, O_dev, workspace_dev, workspace_bytes, nullptr,
+                          qkv_bits, s_q, s_k, s_v, s_p, MC_OUT_F32, O_dev, workspace_dev, workspace_bytes, false, nullptr,
                           stream);
 }
 
@@ -861,7 +895,7 @@ extern "C" int mc_sparse_attention_out(const void *Q_dev, const void *Km_dev, co
                                        size_t workspace_bytes, void *stream)
 {
     return attention_impl(Q_dev, Km_dev, Vm_dev, batch, heads, L, dk, batch_stride, head_stride, token_stride, mask, p_bits,
-                          qkv_bits, s_q, s_k, s_v, s_p, out_type, O_dev, workspace_dev, workspace_bytes, nullptr,
+                          qkv_bits, s_q, s_k, s_v, s_p, out_type, O_dev, workspace_dev, workspace_bytes, false, nullptr,
                           stream);
 }
 
@@ -873,6 +907,16 @@ extern "C" int mc_sparse_attention_ex(const void *Q_dev, const void *Km_dev, con
 {
     const mc_options automatic = {};
     return attention_impl(Q_dev, Km_dev, Vm_dev, batch, heads, L, dk, batch_stride, head_stride, token_stride, mask, p_bits,
-                          qkv_bits, s_q, s_k, s_v, s_p, out_type, O_dev, workspace_dev, workspace_bytes,
+                          qkv_bits, s_q, s_k, s_v, s_p, out_type, O_dev, workspace_dev, workspace_bytes, false,
                           options ? options : &automatic, stream);
+}
+
+extern "C" int mc_sparse_attention_static(const void *Q_dev, const void *Km_dev, const void *Vm_dev, int batch, int heads,
+                                          int L, int dk, int64_t batch_stride, int64_t head_stride, int64_t token_stride,
+                                          const mc_mat *mask, int p_bits, int qkv_bits, float s_q, float s_k, float s_v,
+                                          float s_p, mc_out_type out_type, const mc_options *options, void *O_dev,
+                                          void *stream)
+{
+    return attention_impl(Q_dev, Km_dev, Vm_dev, batch, heads, L, dk, batch_stride, head_stride, token_stride, mask, p_bits,
+                          qkv_bits, s_q, s_k, s_v, s_p, out_type, O_dev, nullptr, 0, true, options, stream);
 }
