@@ -93,7 +93,11 @@ typedef struct mc_options {
                                 less than 4 GiB and no wave has more than 4 chunks), 1 or 2               */
     int spmm_splitting;      /* 0 automatic (very unequal panels are cut into work items, see
                                 mc_set_spmm_splitting), -1 never                                           */
-    int spmm_slab;           /* reserved, must be -1, 0 or 1                                               */
+    int spmm_slab;           /* the SpMM form that keeps blocks of B resident in LDS and reads the gathered
+                                rows from there: 0 automatic (when it is expected to be faster: dense
+                                matrices), -1 never (also: mc_mat_create on this thread does not build the
+                                K-blocked copy of the operand that form needs), 1 whenever the operand has
+                                that copy and the precision has an 8- or 4-bit B without unsigned flags    */
     int sddmm_waves;         /* 0 automatic, -1 the kernel that loads operands straight from memory,
                                 1, 2, 4 or 8 waves per panel of the kernel that stages Kmat rows in LDS   */
     int softmax_variant;     /* 0 automatic, 1 a workgroup per panel also for short panels, 2 always the
@@ -145,6 +149,30 @@ int mc_pack_host(int M, int K, int V, int lhs_bits, const int32_t *row_ptr, cons
  * P+1, nvec and nvec*V elements of the given width. */
 int mc_unpack_host(int M, int K, int V, int lhs_bits, const int32_t *panel_ptr, const int32_t *slot_idx,
                    const void *slot_vals, int32_t *row_ptr, int32_t *col_idx, void *values);
+
+/* K-blocked variant of the device format (Section 4.1 leaves the stride to the kernel; Section 4.2
+ * notes that rows of the dense operand have no reuse in on-chip memory when every panel gathers
+ * them anew -- this layout is what lets a workgroup keep a block of rows resident instead): the
+ * vectors of a panel are also grouped by the block of MC_KBLOCK consecutive columns they fall in,
+ * each (panel, block) list zero-padded to whole chunks of 64, so that a chunk only names rows of
+ * one block.  nblk = ceil(K / MC_KBLOCK).
+ *   blk_ptr   P*nblk + 1 int32: first chunk of (panel p, block b) at [p*nblk + b]; the chunks of a
+ *             panel are consecutive over its blocks
+ *   blk_rows  nchunks*64 uint16: row of each slot inside its block (column - b*MC_KBLOCK); padded
+ *             slots repeat the list's last real row
+ *   blk_vals  vals_bytes bytes, chunk by chunk in the layout of mc_pack_host's slot_vals
+ *   blk_src   nchunks*64 int32: interchange index of the vector in each slot, -1 for padding
+ * Same validation and error codes as mc_pack_host.  Pure host code. */
+#define MC_KBLOCK 1024
+typedef struct {
+    int32_t nblk;        /* K-blocks                                                  */
+    int64_t nchunks;     /* chunks over all (panel, block) lists                      */
+    int64_t vals_bytes;  /* bytes of the packed value array (0 for lhs_bits == 0)     */
+} mc_blocked_layout;
+int mc_blocked_query(int M, int K, int V, int lhs_bits, const int32_t *row_ptr, const int32_t *col_idx,
+                     mc_blocked_layout *out);
+int mc_pack_blocked_host(int M, int K, int V, int lhs_bits, const int32_t *row_ptr, const int32_t *col_idx,
+                         const void *values, int32_t *blk_ptr, uint16_t *blk_rows, void *blk_vals, int32_t *blk_src);
 
 /* ------------------------------------------------------------------------------------
  * Device-resident sparse operand.

@@ -32,6 +32,13 @@ class Layout(ctypes.Structure):
     _fields_ = [("P", c_int32), ("nvec", c_int64), ("nslots", c_int64), ("vals_bytes", c_int64)]
 
 
+class BlockedLayout(ctypes.Structure):
+    _fields_ = [("nblk", c_int32), ("nchunks", c_int64), ("vals_bytes", c_int64)]
+
+
+KBLOCK = 1024
+
+
 class Options(ctypes.Structure):
     """mc_options: kernel-variant choices of one call; all zero = automatic."""
     _fields_ = [("spmm_row_tile_bytes", c_int), ("spmm_waves", c_int), ("spmm_stages", c_int), ("spmm_splitting", c_int),
@@ -58,6 +65,8 @@ def _load() -> ctypes.CDLL:
     L.mc_layout_query.argtypes = [c_int, c_int, c_int, c_int, i32p, POINTER(Layout)]
     L.mc_pack_host.argtypes = [c_int, c_int, c_int, c_int, i32p, i32p, c_void_p, i32p, i32p, c_void_p]
     L.mc_unpack_host.argtypes = [c_int, c_int, c_int, c_int, i32p, i32p, c_void_p, i32p, i32p, c_void_p]
+    L.mc_blocked_query.argtypes = [c_int, c_int, c_int, c_int, i32p, i32p, POINTER(BlockedLayout)]
+    L.mc_pack_blocked_host.argtypes = [c_int, c_int, c_int, c_int, i32p, i32p, c_void_p, i32p, c_void_p, c_void_p, i32p]
     L.mc_mat_create.argtypes = [c_int, c_int, c_int, c_int, i32p, i32p, c_void_p, c_void_p, POINTER(c_void_p)]
     L.mc_mat_set_values_device.argtypes = [c_void_p, c_void_p, c_void_p]
     L.mc_mat_destroy.argtypes = [c_void_p]; L.mc_mat_destroy.restype = None
@@ -121,7 +130,7 @@ def _load() -> ctypes.CDLL:
                  "mc_absmax", "mc_quantize", "mc_sparse_attention_out", "mc_spmm_dequant", "mc_sddmm_dequant", "mc_sparse_softmax_to_mat",
                  "mc_set_spmm_variant", "mc_set_attention_mode", "mc_set_sddmm_variant", "mc_set_spmm_splitting", "mc_set_spmm_stages",
                  "mc_set_softmax_variant", "mc_set_thread_options", "mc_get_thread_options", "mc_spmm_ex", "mc_sddmm_ex",
-                 "mc_sparse_attention_ex", "mc_sparse_attention_static"):
+                 "mc_sparse_attention_ex", "mc_sparse_attention_static", "mc_blocked_query", "mc_pack_blocked_host"):
         getattr(L, name).restype = c_int
     return L
 
@@ -170,6 +179,25 @@ def pack_host(M, K, V, lhs_bits, row_ptr, col_idx, values):
                             None if vals is None else vals.ctypes.data, _p32(panel_ptr), _p32(slot_idx),
                             slot_vals.ctypes.data), "mc_pack_host")
     return panel_ptr, slot_idx[:lay.nslots], slot_vals[:lay.vals_bytes]
+
+
+def pack_blocked_host(M, K, V, lhs_bits, row_ptr, col_idx, values):
+    """Interchange arrays -> (nblk, blk_ptr, blk_rows, blk_vals, blk_src): the K-blocked variant of the format."""
+    rp, ci = _i32(row_ptr), _i32(col_idx)
+    if rp.shape[0] < 1 or (M > 0 and V > 0 and M % V == 0 and rp.shape[0] != M // V + 1) or ci.shape[0] != int(rp[-1]):
+        raise MagicubeError(MC_EINVAL, "pack_blocked_host(array lengths)")
+    bl = BlockedLayout()
+    _check(lib.mc_blocked_query(M, K, V, lhs_bits, _p32(rp), _p32(ci), ctypes.byref(bl)), "mc_blocked_query")
+    P = M // V
+    blk_ptr = np.zeros(P * bl.nblk + 1, np.int32)
+    blk_rows = np.zeros(max(bl.nchunks * CHUNK, 1), np.uint16)
+    blk_src = np.zeros(max(bl.nchunks * CHUNK, 1), np.int32)
+    blk_vals = np.zeros(max(bl.vals_bytes, 1), np.uint8)
+    vals = None if values is None else np.ascontiguousarray(values)
+    _check(lib.mc_pack_blocked_host(M, K, V, lhs_bits, _p32(rp), _p32(ci), None if vals is None else vals.ctypes.data,
+                                    _p32(blk_ptr), blk_rows.ctypes.data, blk_vals.ctypes.data, _p32(blk_src)),
+           "mc_pack_blocked_host")
+    return bl.nblk, blk_ptr, blk_rows[:bl.nchunks * CHUNK], blk_vals[:bl.vals_bytes], blk_src[:bl.nchunks * CHUNK]
 
 
 def unpack_host(M, K, V, lhs_bits, panel_ptr, slot_idx, slot_vals):
@@ -287,7 +315,7 @@ OUT_TYPE = {torch.float32: 0, torch.float16: 1}
 
 
 def spmm_dequant(A: SparseMatrix, B, prec: str, scale: float, out_dtype=torch.float32, out=None,
-                 lhs_unsigned: bool = False, rhs_unsigned: bool = False):
+                 lhs_unsigned: bool = False, rhs_unsigned: bool = False):  # kernel variants: the thread's options
     """C = scale * (A * B) as fp32 or fp16 (M x N): SpMM with the dequantisation fused into the kernel."""
     assert B.is_cuda and B.dim() == 2 and B.stride(1) == 1
     rbits = RHS_BITS[prec]

@@ -78,6 +78,19 @@ bool hip_ok(hipError_t e, const char *what)
         if (!hip_ok((call), #call)) return MC_EHIP; \
     } while (0)
 
+// Every compute call works on the device the operand was created on: its buffers are not
+// addressable from another one.
+bool on_device_of(const mc_mat *A)
+{
+    int cur = -1;
+    if (!hip_ok(hipGetDevice(&cur), "hipGetDevice")) return false;
+    if (cur != A->device) {
+        snprintf(g_detail, sizeof g_detail, "sparse operand lives on device %d, the current device is %d", A->device, cur);
+        return false;
+    }
+    return true;
+}
+
 void free_device(mc_mat *A)
 {
     if (A->d_panel_ptr) (void)hipFree(A->d_panel_ptr);
@@ -86,6 +99,10 @@ void free_device(mc_mat *A)
     if (A->d_vals) (void)hipFree(A->d_vals);
     if (A->d_items) (void)hipFree(A->d_items);
     if (A->d_split_panels) (void)hipFree(A->d_split_panels);
+    if (A->d_blk_ptr) (void)hipFree(A->d_blk_ptr);
+    if (A->d_blk_rows) (void)hipFree(A->d_blk_rows);
+    if (A->d_blk_vals) (void)hipFree(A->d_blk_vals);
+    if (A->d_blk_src) (void)hipFree(A->d_blk_src);
 }
 
 // Waves per panel for SDDMM: enough to put about 2048 waves on the chip (4096 of the light ones
@@ -283,6 +300,8 @@ extern "C" int mc_mat_create(int M, int K, int V, int lhs_bits, const int32_t *r
     A->d_items = A->d_split_panels = nullptr;
     A->n_items = A->n_split = 0;
     A->max_item_chunks = 0;
+    A->nblk = 0; A->blk_chunks = 0; A->blk_valid = false;
+    A->d_blk_ptr = nullptr; A->d_blk_rows = nullptr; A->d_blk_vals = nullptr; A->d_blk_src = nullptr;
     // Work items: only when the longest panel is far above the average; a panel is then cut into
     // pieces of at most `cap` chunks (cap = three times the average, at least 8: smaller pieces
     // balance better but cost the SpMM more in atomics than they gain; measured).
@@ -331,6 +350,38 @@ extern "C" int mc_mat_create(int M, int K, int V, int lhs_bits, const int32_t *r
             for (size_t i = 0; i < items.size(); i += 4) A->max_item_chunks = std::max(A->max_item_chunks, items[i + 2] - items[i + 1]);
         }
     }
+    // K-blocked copy for the SpMM that keeps blocks of B resident in LDS: for operands with values whose
+    // panels are about equally long and dense enough that the per-(panel, block) padding stays moderate
+    // (at most half as many slots again as there are vectors), unless the thread's options rule that kernel out.
+    std::vector<int32_t> blk_ptr, blk_src;
+    std::vector<uint16_t> blk_rows;
+    std::vector<uint8_t> blk_vals;
+    if (lhs_bits != 0 && lay.nvec > 0 && (A->n_items == 0 || t_options.spmm_slab == 1) && t_options.spmm_slab != -1) {
+        mc_blocked_layout bl;
+        // (spmm_slab == 1 on the creating thread: built whatever the shape, so that the form can be forced)
+        const bool forced = t_options.spmm_slab == 1;
+        if (mc_blocked_query(M, K, V, lhs_bits, row_ptr, col_idx, &bl) == MC_OK && bl.nblk <= 63 && bl.nchunks > 0 &&
+            (forced || (bl.nchunks * MC_CHUNK <= lay.nvec + lay.nvec / 2 &&
+                        A->max_panel_chunks <= 2.0 * (double)(lay.nslots / MC_CHUNK) / lay.P + 1.0))) {
+            try {
+                blk_ptr.resize((size_t)lay.P * bl.nblk + 1);
+                blk_rows.resize((size_t)bl.nchunks * MC_CHUNK);
+                blk_src.resize((size_t)bl.nchunks * MC_CHUNK);
+                blk_vals.resize((size_t)bl.vals_bytes);
+            } catch (const std::bad_alloc &) {
+                delete A;
+                return MC_ENOMEM;
+            }
+            rc = mc_pack_blocked_host(M, K, V, lhs_bits, row_ptr, col_idx, values, blk_ptr.data(), blk_rows.data(),
+                                      blk_vals.data(), blk_src.data());
+            if (rc != MC_OK) {
+                delete A;
+                return rc;
+            }
+            A->nblk = bl.nblk;
+            A->blk_chunks = bl.nchunks;
+        }
+    }
     hipStream_t s = static_cast<hipStream_t>(stream);
 #define MC_TRY(call) (ok = ok && hip_ok((call), #call))
     bool ok = true;
@@ -352,6 +403,17 @@ extern "C" int mc_mat_create(int M, int K, int V, int lhs_bits, const int32_t *r
         MC_TRY(hipMemcpyAsync(A->d_items, items.data(), sizeof(int32_t) * items.size(), hipMemcpyHostToDevice, s));
         MC_TRY(hipMemcpyAsync(A->d_split_panels, split_panels.data(), sizeof(int32_t) * split_panels.size(),
                               hipMemcpyHostToDevice, s));
+    }
+    if (A->blk_chunks) {
+        MC_TRY(hipMalloc(&A->d_blk_ptr, sizeof(int32_t) * blk_ptr.size()));
+        MC_TRY(hipMalloc(&A->d_blk_rows, sizeof(uint16_t) * blk_rows.size()));
+        MC_TRY(hipMalloc(&A->d_blk_src, sizeof(int32_t) * blk_src.size()));
+        MC_TRY(hipMalloc(&A->d_blk_vals, blk_vals.size()));
+        MC_TRY(hipMemcpyAsync(A->d_blk_ptr, blk_ptr.data(), sizeof(int32_t) * blk_ptr.size(), hipMemcpyHostToDevice, s));
+        MC_TRY(hipMemcpyAsync(A->d_blk_rows, blk_rows.data(), sizeof(uint16_t) * blk_rows.size(), hipMemcpyHostToDevice, s));
+        MC_TRY(hipMemcpyAsync(A->d_blk_src, blk_src.data(), sizeof(int32_t) * blk_src.size(), hipMemcpyHostToDevice, s));
+        MC_TRY(hipMemcpyAsync(A->d_blk_vals, blk_vals.data(), blk_vals.size(), hipMemcpyHostToDevice, s));
+        A->blk_valid = true;
     }
     MC_TRY(hipStreamSynchronize(s)); // host staging buffers die at return
 #undef MC_TRY
@@ -389,32 +451,68 @@ extern "C" int mc_mat_set_values_device(mc_mat *A, const void *values_dev, void 
     if (A->lhs_bits == 0) return MC_EINVAL;        // a pattern-only mask holds no values
     if (A->nslots == 0) return MC_OK;              // no stored vector: nothing to replace
     if (!values_dev) return MC_EINVAL;
+    if (!on_device_of(A)) return MC_EINVAL;
     RepackArgs r;
     r.panel_ptr = A->d_panel_ptr; r.row_ptr = A->d_row_ptr;
     r.src = static_cast<const uint8_t *>(values_dev); r.src_batch_stride = 0;
     r.dst = A->d_vals; r.dst_batch_stride = 0;
     r.P = A->P; r.V = A->V; r.bits = (A->lhs_bits == 12) ? 16 : A->lhs_bits; r.batch = 1;
     MC_HIP(launch_repack(r, static_cast<hipStream_t>(stream)));
+    if (A->d_blk_vals) { // the K-blocked copy follows
+        MC_HIP(launch_repack_blocked(A->d_blk_src, r.src, A->d_blk_vals, A->blk_chunks, A->V, r.bits, static_cast<hipStream_t>(stream)));
+        A->blk_valid = true;
+    }
     return MC_OK;
 }
 
 namespace {
-// Every compute call works on the device the operand was created on: its buffers are not
-// addressable from another one.
-bool on_device_of(const mc_mat *A)
-{
-    int cur = -1;
-    if (!hip_ok(hipGetDevice(&cur), "hipGetDevice")) return false;
-    if (cur != A->device) {
-        snprintf(g_detail, sizeof g_detail, "sparse operand lives on device %d, the current device is %d", A->device, cur);
-        return false;
-    }
-    return true;
-}
-
 inline int spmm_stages_for(const mc_options &o, int K, int64_t ldb_bytes, int row_bytes)
 {
     return (o.spmm_stages != 1 && (int64_t)(K - 1) * ldb_bytes + row_bytes < ((int64_t)1 << 32)) ? 2 : 1;
+}
+
+// Work split of the SpMM that keeps K-blocks of B resident in LDS: one workgroup per (64-byte column
+// tile, group of ppg consecutive panels); about one workgroup per compute unit (each takes 128 KB of
+// LDS), more groups when a wave would otherwise own more panels than its registers hold.
+struct SlabPlan { int ppg, wpp, nc, ppw; int64_t workgroups; };
+bool plan_slab(const mc_mat *A, int row_bytes, bool r4, int batch, SlabPlan *pl)
+{
+    const int T = (row_bytes + 63) / 64, max_ppw = r4 ? 2 : 4, NC = 15;
+    int64_t G = (256 + (int64_t)T * batch - 1) / ((int64_t)T * batch);
+    if (G > A->P) G = A->P;
+    if (G < 1) G = 1;
+    int ppg = (int)((A->P + G - 1) / G);
+    if (ppg > NC * max_ppw) ppg = NC * max_ppw;
+    G = (A->P + ppg - 1) / ppg;
+    pl->ppg = ppg;
+    pl->workgroups = G * T * batch;
+    if (ppg >= NC) {
+        const int need = (ppg + NC - 1) / NC;
+        pl->nc = NC; pl->wpp = 1; pl->ppw = need <= 1 ? 1 : (need <= 2 ? 2 : 4);
+    } else {
+        // fewer panels than waves: several waves share a panel's chunks, at most four and no more than a
+        // (panel, block) list has chunks on average
+        const double per_list = (double)A->blk_chunks / ((double)A->P * A->nblk);
+        int wpp = NC / ppg;
+        if (wpp > 4) wpp = 4;
+        while (wpp > 1 && wpp > per_list) --wpp;
+        pl->nc = ppg * wpp; pl->wpp = wpp; pl->ppw = 1;
+    }
+    return pl->ppw <= max_ppw;
+}
+
+// Whether the LDS-resident form is expected to beat the gather form (times in microseconds, rates measured
+// on MI355X: about 17 TB/s of rows gathered from L2, about 40 TB/s of rows read from LDS at random row
+// numbers, about 14 TB/s of slab fill; the fill overlaps the reads).
+bool slab_pays(const mc_mat *A, int row_bytes, const SlabPlan &pl)
+{
+    const double tiles64 = (double)((row_bytes + 63) / 64) * 64.0;
+    const double t_gather = 2.5 + (double)A->nvec * row_bytes / 17e6;
+    const double t_lds = (double)A->blk_chunks * MC_CHUNK * tiles64 / 40e6;
+    const double t_fill = (double)pl.workgroups * A->nblk * (MC_KBLOCK * 64.0) / 14e6;
+    const double rounds = std::ceil((double)pl.workgroups / 256.0) / ((double)pl.workgroups / 256.0);
+    const double t_slab = 4.0 + std::max(t_lds, t_fill) * std::max(1.0, rounds);
+    return t_slab < 0.85 * t_gather;
 }
 
 // out_mode 0: int32 results; 1 / 2: scale * result as fp32 / fp16 (fused dequantisation)
@@ -446,6 +544,22 @@ int spmm_impl(const mc_mat *A, const void *B_dev, int N, int ldb, mc_prec prec, 
     a.row_bytes = N * rb / 8;
     a.C = C_dev; a.ldc = ldc; a.C_batch_stride = 0;
     a.P = A->P; a.V = A->V; a.batch = 1; a.float_out = out_mode; a.out_scale = out_mode ? scale : 1.f;
+    // dense matrices: blocks of B resident in LDS instead of a gather per stored vector
+    if (o.spmm_slab != -1 && A->d_blk_vals && A->blk_valid && flags == 0 && rb != 16 && o.spmm_row_tile_bytes == 0 &&
+        o.spmm_waves == 0) {
+        SlabPlan pl;
+        if (plan_slab(A, a.row_bytes, rb == 4, 1, &pl) && (o.spmm_slab == 1 || slab_pays(A, a.row_bytes, pl))) {
+            SlabArgs sa = {};
+            sa.blk_ptr = A->d_blk_ptr; sa.blk_rows = A->d_blk_rows; sa.vals = A->d_blk_vals; sa.vals_batch_stride = 0;
+            sa.B = a.B; sa.ldb_bytes = a.ldb_bytes; sa.B_batch_stride = 0; sa.row_bytes = a.row_bytes; sa.K = A->K;
+            sa.C = C_dev; sa.ldc = ldc; sa.C_batch_stride = 0;
+            sa.P = A->P; sa.V = A->V; sa.batch = 1; sa.nblk = A->nblk;
+            sa.float_out = out_mode; sa.out_scale = a.out_scale;
+            sa.ppg = pl.ppg; sa.wpp = pl.wpp; sa.nc = pl.nc;
+            MC_HIP(launch_spmm_slab(prec, sa, pl.ppw, static_cast<hipStream_t>(stream)));
+            return MC_OK;
+        }
+    }
     a.stages = spmm_stages_for(o, A->K, a.ldb_bytes, a.row_bytes);
     a.max_unit_chunks = A->max_panel_chunks;
     const bool use_items = A->n_items && o.spmm_splitting == 0 && out_mode == 0;
@@ -638,6 +752,7 @@ extern "C" int mc_sparse_softmax_to_mat(mc_mat *P, const int32_t *S_dev, float s
     a.score_scale = score_scale; a.inv_s_p = inv_s_p;
     a.P = P->P; a.V = P->V; a.batch = 1; a.code_bits = P->lhs_bits;
     a.max_panel_chunks = P->max_panel_chunks; a.variant = o.softmax_variant;
+    P->blk_valid = false; // only the panel format receives the new values
     MC_HIP(launch_softmax(a, static_cast<hipStream_t>(stream)));
     return MC_OK;
 }

@@ -38,6 +38,31 @@ inline int nibble_at(const uint8_t *bytes, int64_t elem)
     return (elem & 1) ? (b >> 4) : (b & 15);
 }
 
+// Writes the V elements of interchange vector `vec` into slot `slot` (0..63) of a chunk of packed
+// values (layout: see mc_pack_host).  The chunk must have been zeroed.
+inline int put_vector(uint8_t *chunk, int V, int lhs_bits, int slot, const void *values, int64_t vec)
+{
+    const int g = slot / 16, b = slot % 16;
+    for (int v = 0; v < V; ++v) {
+        const int64_t e = vec * V + v; // element in interchange order
+        if (lhs_bits == 8) {
+            chunk[g * (16 * V) + v * 16 + b] = static_cast<const uint8_t *>(values)[e];
+        } else if (lhs_bits == 16 || lhs_bits == 12) {
+            int8_t hi, l8;
+            const int x = static_cast<const int16_t *>(values)[e];
+            if (lhs_bits == 12 && (x < -2048 || x > 2047)) return MC_ERANGE;
+            if (!split_balanced(x, &hi, &l8)) return MC_ERANGE;
+            chunk[g * (32 * V) + v * 16 + b] = (uint8_t)hi;
+            chunk[g * (32 * V) + 16 * V + v * 16 + b] = (uint8_t)l8;
+        } else { // 4 bits
+            const int nib = nibble_at(static_cast<const uint8_t *>(values), e);
+            uint8_t *byte = &chunk[g * (8 * V) + v * 8 + (b & 7)];
+            *byte |= (uint8_t)((b < 8) ? nib : (nib << 4));
+        }
+    }
+    return MC_OK;
+}
+
 } // namespace
 
 extern "C" int mc_layout_query(int M, int K, int V, int lhs_bits, const int32_t *row_ptr, mc_layout *out)
@@ -99,25 +124,8 @@ extern "C" int mc_pack_host(int M, int K, int V, int lhs_bits, const int32_t *ro
         const int64_t s0 = panel_ptr[2 * p];
         for (int64_t i = 0; i < n; ++i) {
             const int64_t s = s0 + i;
-            uint8_t *chunk = dst + (s / MC_CHUNK) * cbytes;
-            const int g = (int)(s % MC_CHUNK) / 16, b = (int)(s % 16);
-            for (int v = 0; v < V; ++v) {
-                const int64_t e = (lo + i) * V + v; // element in interchange order
-                if (lhs_bits == 8) {
-                    chunk[g * (16 * V) + v * 16 + b] = static_cast<const uint8_t *>(values)[e];
-                } else if (lhs_bits == 16 || lhs_bits == 12) {
-                    int8_t hi, l8;
-                    const int x = static_cast<const int16_t *>(values)[e];
-                    if (lhs_bits == 12 && (x < -2048 || x > 2047)) return MC_ERANGE;
-                    if (!split_balanced(x, &hi, &l8)) return MC_ERANGE;
-                    chunk[g * (32 * V) + v * 16 + b] = (uint8_t)hi;
-                    chunk[g * (32 * V) + 16 * V + v * 16 + b] = (uint8_t)l8;
-                } else { // 4 bits
-                    const int nib = nibble_at(static_cast<const uint8_t *>(values), e);
-                    uint8_t *byte = &chunk[g * (8 * V) + v * 8 + (b & 7)];
-                    *byte |= (uint8_t)((b < 8) ? nib : (nib << 4));
-                }
-            }
+            rc = put_vector(dst + (s / MC_CHUNK) * cbytes, V, lhs_bits, (int)(s % MC_CHUNK), values, lo + i);
+            if (rc != MC_OK) return rc;
         }
     }
     return MC_OK;
@@ -164,5 +172,86 @@ extern "C" int mc_unpack_host(int M, int K, int V, int lhs_bits, const int32_t *
         }
         row_ptr[p + 1] = (int32_t)out;
     }
+    return MC_OK;
+}
+
+// ---- K-blocked variant of the format -------------------------------------------------------
+// For kernels that keep a block of MC_KBLOCK consecutive rows of the dense operand resident in
+// on-chip memory: the vectors of a panel are additionally grouped by the K-block their column
+// falls in, and each (panel, block) list is padded to whole chunks on its own, so that every
+// chunk only names rows of one block (as 16-bit row numbers inside that block).
+extern "C" int mc_blocked_query(int M, int K, int V, int lhs_bits, const int32_t *row_ptr, const int32_t *col_idx,
+                                mc_blocked_layout *out)
+{
+    mc_layout lay;
+    int rc = mc_layout_query(M, K, V, lhs_bits, row_ptr, &lay);
+    if (rc != MC_OK) return rc;
+    if (!out || (lay.nvec && !col_idx)) return MC_EINVAL;
+    const int nblk = (K + MC_KBLOCK - 1) / MC_KBLOCK;
+    int64_t nchunks = 0;
+    for (int p = 0; p < lay.P; ++p) {
+        int64_t i = row_ptr[p];
+        const int64_t end = row_ptr[p + 1];
+        int32_t prev = -1;
+        for (int b = 0; b < nblk; ++b) {
+            int64_t n = 0;
+            while (i < end && col_idx[i] < (int64_t)(b + 1) * MC_KBLOCK) {
+                if (col_idx[i] <= prev || col_idx[i] >= K) return MC_EINVAL;
+                prev = col_idx[i];
+                ++i; ++n;
+            }
+            nchunks += (n + MC_CHUNK - 1) / MC_CHUNK;
+        }
+        if (i != end) return MC_EINVAL; // a column at or beyond K
+    }
+    if (nchunks * MC_CHUNK > (int64_t)INT32_MAX - MC_CHUNK) return MC_EINVAL;
+    out->nblk = nblk;
+    out->nchunks = nchunks;
+    out->vals_bytes = lhs_bits ? nchunks * chunk_value_bytes(V, lhs_bits) : 0;
+    return MC_OK;
+}
+
+extern "C" int mc_pack_blocked_host(int M, int K, int V, int lhs_bits, const int32_t *row_ptr, const int32_t *col_idx,
+                                    const void *values, int32_t *blk_ptr, uint16_t *blk_rows, void *blk_vals,
+                                    int32_t *blk_src)
+{
+    mc_blocked_layout bl;
+    int rc = mc_blocked_query(M, K, V, lhs_bits, row_ptr, col_idx, &bl);
+    if (rc != MC_OK) return rc;
+    if (!blk_ptr || (bl.nchunks && (!blk_rows || !blk_src))) return MC_EINVAL;
+    const bool with_vals = lhs_bits != 0 && values != nullptr;
+    if (with_vals && bl.vals_bytes && !blk_vals) return MC_EINVAL;
+    if (with_vals) std::memset(blk_vals, 0, (size_t)bl.vals_bytes);
+    uint8_t *dst = static_cast<uint8_t *>(blk_vals);
+    const int64_t cbytes = lhs_bits ? chunk_value_bytes(V, lhs_bits) : 0;
+    const int P = M / V;
+    int64_t chunk = 0;
+    for (int p = 0; p < P; ++p) {
+        int64_t i = row_ptr[p];
+        const int64_t end = row_ptr[p + 1];
+        for (int b = 0; b < bl.nblk; ++b) {
+            blk_ptr[(int64_t)p * bl.nblk + b] = (int32_t)chunk;
+            int64_t n = 0;
+            int last_row = 0;
+            while (i < end && col_idx[i] < (int64_t)(b + 1) * MC_KBLOCK) {
+                const int64_t slot = chunk * MC_CHUNK + n;
+                last_row = col_idx[i] - b * MC_KBLOCK;
+                blk_rows[slot] = (uint16_t)last_row;
+                blk_src[slot] = (int32_t)i;
+                if (with_vals) {
+                    rc = put_vector(dst + (slot / MC_CHUNK) * cbytes, V, lhs_bits, (int)(slot % MC_CHUNK), values, i);
+                    if (rc != MC_OK) return rc;
+                }
+                ++i; ++n;
+            }
+            const int64_t npad = (n + MC_CHUNK - 1) / MC_CHUNK * MC_CHUNK;
+            for (int64_t k = n; k < npad; ++k) { // padded slots: a row of this block, zero values, no source vector
+                blk_rows[chunk * MC_CHUNK + k] = (uint16_t)last_row;
+                blk_src[chunk * MC_CHUNK + k] = -1;
+            }
+            chunk += npad / MC_CHUNK;
+        }
+    }
+    blk_ptr[(int64_t)P * bl.nblk] = (int32_t)chunk;
     return MC_OK;
 }

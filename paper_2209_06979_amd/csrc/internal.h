@@ -22,6 +22,15 @@ struct mc_mat {
     int32_t *d_split_panels;   // n_split: the panels that have several items
     int n_items, n_split;
     int max_item_chunks;       // chunks of the longest item
+    // K-blocked copy of the operand for the SpMM that keeps blocks of B resident in LDS (null when not
+    // built: pattern-only masks, very sparse or very unequal matrices, more than 63 K-blocks)
+    int nblk;                  // K-blocks of MC_KBLOCK rows
+    int64_t blk_chunks;        // chunks over all (panel, block) lists
+    int32_t *d_blk_ptr;        // P*nblk + 1
+    uint16_t *d_blk_rows;      // blk_chunks * 64
+    uint8_t *d_blk_vals;       // blk_chunks * chunk bytes
+    int32_t *d_blk_src;        // blk_chunks * 64: interchange vector of each slot, -1 for padding
+    bool blk_valid;            // false once the values were replaced in the panel format only
 };
 
 // One SpMM launch (optionally a batch of problems sharing the sparsity pattern).
@@ -47,6 +56,25 @@ struct SpmmArgs {
     int n_units;               // items, or P
     int stages;                // chunks in flight per wave: 1 or 2 (2 needs B to span less than 4 GiB)
     int max_unit_chunks;       // chunks of the longest unit of work (panel or work item)
+};
+
+// One launch of the SpMM that keeps K-blocks of B resident in LDS (see spmm_slab_kernels.hip).
+struct SlabArgs {
+    const int32_t *blk_ptr;
+    const uint16_t *blk_rows;
+    const uint8_t *vals;
+    int64_t vals_batch_stride; // bytes
+    const uint8_t *B;
+    int64_t ldb_bytes, B_batch_stride;
+    int row_bytes, K;
+    void *C;
+    int64_t ldc, C_batch_stride;
+    int P, V, batch, nblk;
+    int float_out;
+    float out_scale;
+    int ppg;                   // consecutive panels per workgroup
+    int wpp;                   // waves sharing a panel (its chunks dealt round-robin)
+    int nc;                    // computing waves per workgroup (one more wave fills the slab); nc / wpp panels at a time
 };
 
 struct SddmmArgs {
@@ -109,6 +137,10 @@ struct AttnArgs {
 };
 
 hipError_t launch_spmm(mc_prec prec, const SpmmArgs &a, int bnb, int waves, hipStream_t s);
+// ppw: panels per computing wave (1, 2 or 4; 4 only with an 8-bit B).  Precisions with a 16-bit B are not built.
+hipError_t launch_spmm_slab(mc_prec prec, const SlabArgs &a, int ppw, hipStream_t s);
+hipError_t launch_repack_blocked(const int32_t *blk_src, const uint8_t *src, uint8_t *dst, int64_t nchunks, int V, int bits,
+                                 hipStream_t s);
 // clears the C rows (int32, n columns) of the listed panels
 hipError_t launch_zero_rows(int32_t *C, int64_t ldc, int n, int V, const int32_t *panels, int n_panels, hipStream_t s);
 // the gather of launch_spmm alone (same tile variant); sink: one int32 per workgroup (P * row tiles)

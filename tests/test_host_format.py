@@ -175,3 +175,56 @@ def test_entry_points_reject_bad_arguments_before_touching_the_gpu():
     assert L.mc_set_sddmm_variant(3) == mc.MC_EINVAL and L.mc_set_sddmm_variant(-1) == mc.MC_OK
     assert L.mc_attention_workspace_bytes_bits(4, None, 8) == 0
     assert L.mc_probe_gather_sink_len(None, 16, 0) == 0
+
+
+# ---- K-blocked variant of the format --------------------------------------------------------
+@pytest.mark.parametrize("V", [2, 4, 8])
+@pytest.mark.parametrize("bits", [4, 8, 16])
+def test_blocked_format_holds_the_same_matrix(V, bits):
+    """Every stored vector appears exactly once, in the list of the K-block its column falls in, with its own
+    values; every list is padded to whole chunks with zero values and a row of the same block."""
+    K = 2500                                               # three blocks of 1024 columns, the last one partial
+    counts = [0, 1, 63, 64, 65, 700, 0, 17, 2500]
+    M, K, rp, ci, vals = _case(V, bits, counts, K=K, seed=20 * V + bits)
+    nblk, bp, rows, bv, src = mc.pack_blocked_host(M, K, V, bits, rp, ci, vals)
+    assert nblk == 3 and bp[0] == 0 and len(bp) == len(counts) * nblk + 1 and (np.diff(bp) >= 0).all()
+    assert len(rows) == bp[-1] * 64 == len(src)
+    # the ordinary device format of the same data, as the reference for the value layout of a chunk
+    vbytes = 64 * V * bits // 8
+    seen = np.zeros(len(ci), np.int64)
+    for p in range(len(counts)):
+        for b in range(nblk):
+            c0, c1 = bp[p * nblk + b], bp[p * nblk + b + 1]
+            want = [i for i in range(rp[p], rp[p + 1]) if b * 1024 <= ci[i] < (b + 1) * 1024]
+            assert c1 - c0 == (len(want) + 63) // 64
+            s = src[c0 * 64:c1 * 64]
+            assert s[:len(want)].tolist() == want and (s[len(want):] == -1).all()
+            r = rows[c0 * 64:c1 * 64].astype(np.int64)
+            assert np.array_equal(r[:len(want)] + b * 1024, ci[want])
+            assert (r[len(want):] == (r[len(want) - 1] if want else 0)).all()
+            seen[want] += 1
+            # values: pack the same vectors as one panel of an ordinary matrix and compare chunk by chunk
+            if want:
+                sub_rp = np.array([0, len(want)], np.int32)
+                sub_vals = np.ascontiguousarray(vals)[want]
+                _, _, ref = mc.pack_host(V, K, V, bits, sub_rp, ci[want], sub_vals)
+                assert np.array_equal(bv[c0 * vbytes:c1 * vbytes], ref)
+    assert (seen == 1).all()
+
+
+def test_blocked_format_argument_checks():
+    V, K = 8, 3000
+    rp, ci = wl.ragged_pattern(16, K, V, [5, 9], 3)
+    vals = wl.uniform_int8((len(ci), V), 4)
+    bad = ci.copy(); bad[1] = bad[0]                         # not ascending
+    with pytest.raises(mc.MagicubeError):
+        mc.pack_blocked_host(16, K, V, 8, rp, bad, vals)
+    bad = ci.copy(); bad[-1] = K                             # column out of range
+    with pytest.raises(mc.MagicubeError):
+        mc.pack_blocked_host(16, K, V, 8, rp, bad, vals)
+    v16 = wl.uniform_int16((len(ci), V), 5, 32640, 32767)    # cannot be split into two signed bytes
+    with pytest.raises(mc.MagicubeError) as e:
+        mc.pack_blocked_host(16, K, V, 16, rp, ci, v16)
+    assert e.value.status == mc.MC_ERANGE
+    nblk, bp, rows, bv, src = mc.pack_blocked_host(16, K, V, 0, rp, ci, None)   # pattern only
+    assert nblk == 3 and len(bv) == 0 and bp[-1] * 64 == len(rows)
