@@ -98,6 +98,9 @@ typedef struct mc_options {
                                 matrices), -1 never (also: mc_mat_create on this thread does not build the
                                 K-blocked copy of the operand that form needs), 1 whenever the operand has
                                 that copy and the precision has an 8- or 4-bit B without unsigned flags    */
+    int spmm_slab_waves;     /* that form's computing waves per workgroup: 0 automatic, else 1 .. 15           */
+    int spmm_slab_panels;    /* that form's panels per computing wave: 0 automatic, else 1, 2 or 4 (4 only with
+                                an 8-bit B)                                                                */
     int sddmm_waves;         /* 0 automatic, -1 the kernel that loads operands straight from memory,
                                 1, 2, 4 or 8 waves per panel of the kernel that stages Kmat rows in LDS   */
     int softmax_variant;     /* 0 automatic, 1 a workgroup per panel also for short panels, 2 always the
@@ -159,7 +162,9 @@ int mc_unpack_host(int M, int K, int V, int lhs_bits, const int32_t *panel_ptr, 
  *   blk_ptr   P*nblk + 1 int32: first chunk of (panel p, block b) at [p*nblk + b]; the chunks of a
  *             panel are consecutive over its blocks
  *   blk_rows  nchunks*64 uint16: row of each slot inside its block (column - b*MC_KBLOCK); padded
- *             slots repeat the list's last real row
+ *             slots repeat the list's last real row.  Inside a chunk, slot s sits at position
+ *             (s/16)*16 + (s%8)*2 + (s%16)/8: slots s and s+8 of a sub-stride of 16 are neighbours
+ *             (one lane of the kernel addresses exactly these two and reads them as one word)
  *   blk_vals  vals_bytes bytes, chunk by chunk in the layout of mc_pack_host's slot_vals
  *   blk_src   nchunks*64 int32: interchange index of the vector in each slot, -1 for padding
  * Same validation and error codes as mc_pack_host.  Pure host code. */

@@ -42,7 +42,7 @@ KBLOCK = 1024
 class Options(ctypes.Structure):
     """mc_options: kernel-variant choices of one call; all zero = automatic."""
     _fields_ = [("spmm_row_tile_bytes", c_int), ("spmm_waves", c_int), ("spmm_stages", c_int), ("spmm_splitting", c_int),
-                ("spmm_slab", c_int), ("sddmm_waves", c_int), ("softmax_variant", c_int), ("attention_mode", c_int)]
+                ("spmm_slab", c_int), ("spmm_slab_waves", c_int), ("spmm_slab_panels", c_int), ("sddmm_waves", c_int), ("softmax_variant", c_int), ("attention_mode", c_int)]
 
 
 class MagicubeError(RuntimeError):

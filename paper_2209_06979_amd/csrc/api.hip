@@ -24,6 +24,8 @@ bool valid_options(const mc_options &o)
     if (o.spmm_stages < 0 || o.spmm_stages > 2) return false;
     if (o.spmm_splitting != 0 && o.spmm_splitting != -1) return false;
     if (o.spmm_slab < -1 || o.spmm_slab > 1) return false;
+    if (o.spmm_slab_waves < 0 || o.spmm_slab_waves > 15) return false;
+    if (o.spmm_slab_panels != 0 && o.spmm_slab_panels != 1 && o.spmm_slab_panels != 2 && o.spmm_slab_panels != 4) return false;
     if (d != 0 && d != -1 && d != 1 && d != 2 && d != 4 && d != 8) return false;
     if (o.softmax_variant < 0 || o.softmax_variant > 2) return false;
     if (o.attention_mode < 0 || o.attention_mode > 5) return false;
@@ -361,7 +363,8 @@ extern "C" int mc_mat_create(int M, int K, int V, int lhs_bits, const int32_t *r
         // (spmm_slab == 1 on the creating thread: built whatever the shape, so that the form can be forced)
         const bool forced = t_options.spmm_slab == 1;
         if (mc_blocked_query(M, K, V, lhs_bits, row_ptr, col_idx, &bl) == MC_OK && bl.nblk <= 63 && bl.nchunks > 0 &&
-            (forced || (bl.nchunks * MC_CHUNK <= lay.nvec + lay.nvec / 2 &&
+            (forced || ((double)lay.nvec >= 160.0 * lay.P * bl.nblk && // (below about 160 vectors per list the form never won)
+                        bl.nchunks * MC_CHUNK <= lay.nvec + lay.nvec / 2 &&
                         A->max_panel_chunks <= 2.0 * (double)(lay.nslots / MC_CHUNK) / lay.P + 1.0))) {
             try {
                 blk_ptr.resize((size_t)lay.P * bl.nblk + 1);
@@ -474,45 +477,54 @@ inline int spmm_stages_for(const mc_options &o, int K, int64_t ldb_bytes, int ro
 // Work split of the SpMM that keeps K-blocks of B resident in LDS: one workgroup per (64-byte column
 // tile, group of ppg consecutive panels); about one workgroup per compute unit (each takes 128 KB of
 // LDS), more groups when a wave would otherwise own more panels than its registers hold.
-struct SlabPlan { int ppg, wpp, nc, ppw; int64_t workgroups; };
-bool plan_slab(const mc_mat *A, int row_bytes, bool r4, int batch, SlabPlan *pl)
+struct SlabPlan { int groups, ppg, wpp, nc, ppw, passes; int64_t workgroups; };
+bool plan_slab(const mc_mat *A, int row_bytes, bool r4, int batch, const mc_options &o, SlabPlan *pl)
 {
-    const int T = (row_bytes + 63) / 64, max_ppw = r4 ? 2 : 4, NC = 15;
+    const int T = (row_bytes + 63) / 64, max_ppw = r4 ? 2 : 4;
     int64_t G = (256 + (int64_t)T * batch - 1) / ((int64_t)T * batch);
     if (G > A->P) G = A->P;
     if (G < 1) G = 1;
-    int ppg = (int)((A->P + G - 1) / G);
-    if (ppg > NC * max_ppw) ppg = NC * max_ppw;
+    const int ppg = (int)((A->P + G - 1) / G);
     G = (A->P + ppg - 1) / ppg;
+    pl->groups = (int)G;
     pl->ppg = ppg;
     pl->workgroups = G * T * batch;
-    if (ppg >= NC) {
-        const int need = (ppg + NC - 1) / NC;
-        pl->nc = NC; pl->wpp = 1; pl->ppw = need <= 1 ? 1 : (need <= 2 ? 2 : 4);
+    // Twelve computing waves and four filling ones (one filling wave alone is bound by the latency of its own
+    // copies: 3.3 against 1.6 us per 64 KB block).  More panels than waves: two panels per wave and as many
+    // passes over K as it takes (measured against 8 x 2, 8 x 4, 12 x 1 and 15 x 1/2/4: 12 x 2 is the fastest or
+    // within 5 % of it from 13 panels per workgroup on).  Fewer panels than waves: several waves share a panel's
+    // chunks, at most four and no more than a (panel, block) list has chunks on average.
+    if (ppg > 12) {
+        pl->nc = 12; pl->wpp = 1; pl->ppw = 2; pl->passes = (ppg + 23) / 24;
     } else {
-        // fewer panels than waves: several waves share a panel's chunks, at most four and no more than a
-        // (panel, block) list has chunks on average
         const double per_list = (double)A->blk_chunks / ((double)A->P * A->nblk);
-        int wpp = NC / ppg;
+        int wpp = 12 / ppg;
         if (wpp > 4) wpp = 4;
         while (wpp > 1 && wpp > per_list) --wpp;
-        pl->nc = ppg * wpp; pl->wpp = wpp; pl->ppw = 1;
+        pl->nc = ppg * wpp; pl->wpp = wpp; pl->ppw = 1; pl->passes = 1;
+    }
+    if (o.spmm_slab_waves || o.spmm_slab_panels) {
+        // a pinned shape: one wave per panel, as many passes as it takes
+        pl->nc = o.spmm_slab_waves ? o.spmm_slab_waves : pl->nc;
+        pl->ppw = o.spmm_slab_panels ? o.spmm_slab_panels : pl->ppw;
+        pl->wpp = 1;
+        pl->passes = (ppg + pl->nc * pl->ppw - 1) / (pl->nc * pl->ppw);
     }
     return pl->ppw <= max_ppw;
 }
 
-// Whether the LDS-resident form is expected to beat the gather form (times in microseconds, rates measured
-// on MI355X: about 17 TB/s of rows gathered from L2, about 40 TB/s of rows read from LDS at random row
-// numbers, about 14 TB/s of slab fill; the fill overlaps the reads).
-bool slab_pays(const mc_mat *A, int row_bytes, const SlabPlan &pl)
+// Whether the LDS-resident form is expected to beat the gather form.  Both times (microseconds) are fits to
+// measurements on MI355X over V, sparsity and N at K = 4096: the gather form moves its rows at about 19.5 TB/s after
+// 2.5 us of launch and ramp; the LDS-resident form pays about 2 us per K-block and pass for the fill it cannot
+// hide and 21.6 ns per chunk step of a compute unit.
+bool slab_pays(const mc_mat *A, int row_bytes, int batch, const SlabPlan &pl)
 {
-    const double tiles64 = (double)((row_bytes + 63) / 64) * 64.0;
-    const double t_gather = 2.5 + (double)A->nvec * row_bytes / 17e6;
-    const double t_lds = (double)A->blk_chunks * MC_CHUNK * tiles64 / 40e6;
-    const double t_fill = (double)pl.workgroups * A->nblk * (MC_KBLOCK * 64.0) / 14e6;
-    const double rounds = std::ceil((double)pl.workgroups / 256.0) / ((double)pl.workgroups / 256.0);
-    const double t_slab = 4.0 + std::max(t_lds, t_fill) * std::max(1.0, rounds);
-    return t_slab < 0.85 * t_gather;
+    const double T = (double)((row_bytes + 63) / 64);
+    const double t_gather = 2.5 + (double)A->nvec * row_bytes * batch / 19.5e6;
+    const double steps = (double)A->blk_chunks * T * batch / 256.0;
+    const double rounds = std::max(1.0, std::ceil((double)pl.workgroups / 256.0) / ((double)pl.workgroups / 256.0));
+    const double t_slab = 2.5 + (pl.passes * 2.0 * A->nblk + 0.0216 * steps) * rounds;
+    return t_slab < 0.92 * t_gather;
 }
 
 // out_mode 0: int32 results; 1 / 2: scale * result as fp32 / fp16 (fused dequantisation)
@@ -548,14 +560,15 @@ int spmm_impl(const mc_mat *A, const void *B_dev, int N, int ldb, mc_prec prec, 
     if (o.spmm_slab != -1 && A->d_blk_vals && A->blk_valid && flags == 0 && rb != 16 && o.spmm_row_tile_bytes == 0 &&
         o.spmm_waves == 0) {
         SlabPlan pl;
-        if (plan_slab(A, a.row_bytes, rb == 4, 1, &pl) && (o.spmm_slab == 1 || slab_pays(A, a.row_bytes, pl))) {
+        if (plan_slab(A, a.row_bytes, rb == 4, 1, o, &pl) && (o.spmm_slab == 1 || slab_pays(A, a.row_bytes, 1, pl))) {
             SlabArgs sa = {};
             sa.blk_ptr = A->d_blk_ptr; sa.blk_rows = A->d_blk_rows; sa.vals = A->d_blk_vals; sa.vals_batch_stride = 0;
             sa.B = a.B; sa.ldb_bytes = a.ldb_bytes; sa.B_batch_stride = 0; sa.row_bytes = a.row_bytes; sa.K = A->K;
             sa.C = C_dev; sa.ldc = ldc; sa.C_batch_stride = 0;
             sa.P = A->P; sa.V = A->V; sa.batch = 1; sa.nblk = A->nblk;
             sa.float_out = out_mode; sa.out_scale = a.out_scale;
-            sa.ppg = pl.ppg; sa.wpp = pl.wpp; sa.nc = pl.nc;
+            sa.groups = pl.groups; sa.ppg = pl.ppg; sa.wpp = pl.wpp; sa.nc = pl.nc;
+            sa.nf = 16 - sa.nc < 4 ? 16 - sa.nc : 4;
             MC_HIP(launch_spmm_slab(prec, sa, pl.ppw, static_cast<hipStream_t>(stream)));
             return MC_OK;
         }

@@ -63,6 +63,11 @@ inline int put_vector(uint8_t *chunk, int V, int lhs_bits, int slot, const void 
     return MC_OK;
 }
 
+// Position of slot s (0..63) of a chunk in the K-blocked format's row array: the two slots one lane of the
+// kernel addresses (s and s + 8 inside a sub-stride of 16) are neighbours, so that they travel as one 32-bit word.
+inline int64_t chunk_base(int64_t slot) { return slot / MC_CHUNK * MC_CHUNK; }
+inline int row_position(int s) { return (s / 16) * 16 + (s % 8) * 2 + (s % 16) / 8; }
+
 } // namespace
 
 extern "C" int mc_layout_query(int M, int K, int V, int lhs_bits, const int32_t *row_ptr, mc_layout *out)
@@ -236,7 +241,7 @@ extern "C" int mc_pack_blocked_host(int M, int K, int V, int lhs_bits, const int
             while (i < end && col_idx[i] < (int64_t)(b + 1) * MC_KBLOCK) {
                 const int64_t slot = chunk * MC_CHUNK + n;
                 last_row = col_idx[i] - b * MC_KBLOCK;
-                blk_rows[slot] = (uint16_t)last_row;
+                blk_rows[chunk_base(slot) + row_position((int)(slot % MC_CHUNK))] = (uint16_t)last_row;
                 blk_src[slot] = (int32_t)i;
                 if (with_vals) {
                     rc = put_vector(dst + (slot / MC_CHUNK) * cbytes, V, lhs_bits, (int)(slot % MC_CHUNK), values, i);
@@ -246,7 +251,7 @@ extern "C" int mc_pack_blocked_host(int M, int K, int V, int lhs_bits, const int
             }
             const int64_t npad = (n + MC_CHUNK - 1) / MC_CHUNK * MC_CHUNK;
             for (int64_t k = n; k < npad; ++k) { // padded slots: a row of this block, zero values, no source vector
-                blk_rows[chunk * MC_CHUNK + k] = (uint16_t)last_row;
+                blk_rows[chunk_base(chunk * MC_CHUNK + k) + row_position((int)(k % MC_CHUNK))] = (uint16_t)last_row;
                 blk_src[chunk * MC_CHUNK + k] = -1;
             }
             chunk += npad / MC_CHUNK;

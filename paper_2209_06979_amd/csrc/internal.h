@@ -72,9 +72,11 @@ struct SlabArgs {
     int P, V, batch, nblk;
     int float_out;
     float out_scale;
-    int ppg;                   // consecutive panels per workgroup
+    int groups;                // panel groups (workgroups per column tile)
+    int ppg;                   // consecutive panels per workgroup (taken in passes of (nc / wpp) * panels-per-wave)
     int wpp;                   // waves sharing a panel (its chunks dealt round-robin)
-    int nc;                    // computing waves per workgroup (one more wave fills the slab); nc / wpp panels at a time
+    int nc;                    // computing waves per workgroup; nc / wpp panels at a time
+    int nf;                    // filling waves (after the computing ones); nc + nf <= 16
 };
 
 struct SddmmArgs {

@@ -31,4 +31,29 @@ __device__ __forceinline__ v4i load_a(const uint8_t *vals, int64_t chunk, int V,
 }
 
 
+// The same operand in two steps, for kernels that request it several chunks ahead: load_a_raw only loads
+// (so that nothing has to wait for the data yet), finish_a turns the loaded registers into the MFMA operand.
+// MFMA rows beyond the V rows of a panel (whose results are never stored) receive a copy of row 0 instead
+// of zeros: the load then needs no per-lane condition.
+template <int LB>
+__device__ __forceinline__ v4i load_a_raw(const uint8_t *vals, int64_t chunk, int V, int row, int g)
+{
+    if (LB == 16) {
+        const int v = ((row & 7) < V) ? (row & 7) : 0;
+        return *reinterpret_cast<const v4i *>(vals + chunk * (128 * V) + g * (32 * V) + (row >> 3) * (16 * V) + v * 16);
+    } else if (LB == 4) {
+        const int v = (row < V) ? row : 0;
+        const v2i x = *reinterpret_cast<const v2i *>(vals + chunk * (32 * V) + g * (8 * V) + v * 8);
+        return (v4i){x.x, x.y, 0, 0};
+    } else {
+        const int v = (row < V) ? row : 0;
+        return *reinterpret_cast<const v4i *>(vals + chunk * (64 * V) + g * (16 * V) + v * 16);
+    }
+}
+template <int LB> __device__ __forceinline__ v4i finish_a(v4i raw)
+{
+    if (LB == 4) return (v4i){(raw.x << 4) & (int)0xF0F0F0F0, (raw.y << 4) & (int)0xF0F0F0F0, raw.x & (int)0xF0F0F0F0, raw.y & (int)0xF0F0F0F0};
+    return raw;
+}
+
 } // namespace mcu

@@ -199,7 +199,8 @@ def test_blocked_format_holds_the_same_matrix(V, bits):
             assert c1 - c0 == (len(want) + 63) // 64
             s = src[c0 * 64:c1 * 64]
             assert s[:len(want)].tolist() == want and (s[len(want):] == -1).all()
-            r = rows[c0 * 64:c1 * 64].astype(np.int64)
+            pos = np.array([(t // 16) * 16 + (t % 8) * 2 + (t % 16) // 8 for t in range(64)])   # slot -> place in its chunk
+            r = rows[c0 * 64:c1 * 64].astype(np.int64).reshape(-1, 64)[:, pos].reshape(-1)
             assert np.array_equal(r[:len(want)] + b * 1024, ci[want])
             assert (r[len(want):] == (r[len(want) - 1] if want else 0)).all()
             seen[want] += 1
