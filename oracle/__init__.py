@@ -244,6 +244,24 @@ def sddmm(M, Nc, V, row_ptr, col_idx, Q, Kmat, prec: str, lhs_unsigned: bool = F
     return sddmm_dense(dense_rhs_as_int(Q, bits, lhs_unsigned), dense_rhs_as_int(Kmat, bits, rhs_unsigned), flags, V)
 
 
+# Largest magnitude of a re-quantised SDDMM result: symmetric, 8 bits: 127; 16 bits: 32639 (the same convention
+# as P_CODE_MAX: the largest value a two-signed-byte operand can hold).
+S_CODE_MAX = {8: 127, 16: 32639}
+
+
+def requantize_scores(S, scale, bits: int = 8) -> np.ndarray:
+    """Integer codes of SDDMM results that feed a following SpMM as its sparse operand (Section 4.3 lets the
+    SDDMM write the format of the next operator, whose operands are 8- or 16-bit integers):
+    code = clamp(rint(S * scale), -S_CODE_MAX, S_CODE_MAX), ties to even.
+
+    The decision is taken in the kernel's precision, binary32 (the paper fixes none): the int32 score is
+    converted to fp32 (round to nearest even), multiplied by the fp32 scale with ONE rounding, and that
+    product is rounded to an integer.  numpy's float32 arithmetic is IEEE and does exactly this."""
+    x = np.asarray(S).astype(np.int64).astype(np.float32) * np.float32(scale)
+    q = np.clip(np.rint(x), -S_CODE_MAX[bits], S_CODE_MAX[bits])
+    return q.astype(np.int8 if bits == 8 else np.int16)
+
+
 # --------------------------------------------------------------------------- #
 # Integer splitting (Section 4.4)                                              #
 # --------------------------------------------------------------------------- #

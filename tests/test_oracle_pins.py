@@ -600,3 +600,29 @@ def test_generators_are_seeded_and_exact():
     rp, ci = wl.vector_sparse_pattern(64, 64, 8, 0.5, 3, keep_diagonal=True)
     for p in range(8):
         assert set(range(8 * p, 8 * p + 8)) <= set(ci[rp[p]:rp[p + 1]].tolist())
+
+
+def test_requantize_scores_hand_worked_and_exact_route():
+    """SDDMM results turned into the next SpMM's integer operand (Section 4.3): explicit values with exact binary
+    products (ties go to even, the clamp is symmetric), and a second route through exact rational arithmetic
+    wherever the fp32 product is exact."""
+    from fractions import Fraction
+    S = np.array([0, 1, 3, 5, -1, -3, 7, 254, 255, -255, 1000, -100000], np.int32)
+    assert oracle.requantize_scores(S, 0.5).tolist() == [0, 0, 2, 2, 0, -2, 4, 127, 127, -127, 127, -127]
+    assert oracle.requantize_scores(S, 0.5, 16).tolist() == [0, 0, 2, 2, 0, -2, 4, 127, 128, -128, 500, -32639]
+    assert oracle.requantize_scores(np.array([65278, 65279, 70000]), 0.5, 16).tolist() == [32639, 32639, 32639]
+    # scale 2^-k, scores below 2^24: the fp32 product is exact, so rint of the exact rational must agree
+    rng = np.random.default_rng(9)
+    S = rng.integers(-(1 << 23), 1 << 23, size=4000).astype(np.int32)
+    for k in (3, 10, 17):
+        want = []
+        for v in S.tolist():
+            q = Fraction(v, 1 << k)
+            f = q.numerator // q.denominator
+            r = q - f
+            n = f + (1 if r > Fraction(1, 2) or (r == Fraction(1, 2) and f % 2) else 0)
+            want.append(max(-32639, min(32639, n)))
+        assert oracle.requantize_scores(S, 2.0 ** -k, 16).tolist() == want
+    # scores beyond 2^24 are first rounded to fp32 (to even): 2^24 + 1 -> 2^24
+    assert oracle.requantize_scores(np.array([(1 << 24) + 1, (1 << 24) + 3]), 2.0 ** -10, 16).tolist() == [16384, 16384]
+    assert oracle.requantize_scores(np.array([5]), 0.1).dtype == np.int8 and oracle.requantize_scores(np.array([5]), 0.1, 16).dtype == np.int16
