@@ -278,6 +278,20 @@ int mc_sddmm_ex(const void *Q_dev, int ldq, const void *Kmat_dev, int ldk, int K
 int mc_sddmm_dequant(const void *Q_dev, int ldq, const void *Kmat_dev, int ldk, int Kd, const mc_mat *mask,
                      mc_prec prec, unsigned flags, float scale, mc_out_type out_type, void *S_dev, void *stream);
 
+/* SDDMM that writes the operand format of a following SpMM (Section 4.3: the output is stored in the
+ * strided format when the next operator is SpMM): the scores are re-quantised in the kernel's epilogue,
+ *   code = clamp(rint(score * scale), -qmax, qmax),  qmax = 127 (8-bit P) or 32639 (16-bit P),
+ * -- the int32 score converted to fp32, one fp32 product, rounded to nearest even -- and written
+ * straight into the device-resident values of P, whose pattern is the mask (padded slots: zeros), so
+ * that mc_spmm(P, ...) can follow without an interchange-order round trip.
+ *   P       a matrix created with values (e.g. zeros) of 8 or 16 bits; all its values are replaced.
+ *           Pattern-only mask: MC_EINVAL; other widths: MC_EUNSUPPORTED.
+ *   prec    width of Q and Kmat: MC_L8R8, MC_L4R4 or MC_L16R16 (as mc_sddmm; signed operands)
+ * Other arguments and requirements as mc_sddmm; scale must be finite.  Kernel variants: the calling
+ * thread's options. */
+int mc_sddmm_to_mat(const void *Q_dev, int ldq, const void *Kmat_dev, int ldk, int Kd, mc_prec prec, float scale,
+                    mc_mat *P, void *stream);
+
 /* ------------------------------------------------------------------------------------
  * Sparse softmax with fused (de)quantisation (Section 5.3): for each row (p, v) over its
  * stored entries i:  x_i = S[i*V+v] * score_scale;  p_i = exp(x_i - max) / sum;

@@ -102,6 +102,7 @@ def _load() -> ctypes.CDLL:
     L.mc_sddmm_dequant.argtypes = [c_void_p, c_int, c_void_p, c_int, c_int, c_void_p, c_int, ctypes.c_uint, c_float, c_int,
                                    c_void_p, c_void_p]
     L.mc_sparse_softmax_to_mat.argtypes = [c_void_p, c_void_p, c_float, c_float, c_void_p]
+    L.mc_sddmm_to_mat.argtypes = [c_void_p, c_int, c_void_p, c_int, c_int, c_int, c_float, c_void_p, c_void_p]
     L.mc_absmax.argtypes = [c_void_p, c_int64, c_void_p, c_void_p]
     L.mc_quantize.argtypes = [c_void_p, c_int64, c_float, c_int, c_void_p, c_void_p]
     L.mc_options_init.argtypes = [POINTER(Options)]; L.mc_options_init.restype = None
@@ -130,7 +131,7 @@ def _load() -> ctypes.CDLL:
                  "mc_absmax", "mc_quantize", "mc_sparse_attention_out", "mc_spmm_dequant", "mc_sddmm_dequant", "mc_sparse_softmax_to_mat",
                  "mc_set_spmm_variant", "mc_set_attention_mode", "mc_set_sddmm_variant", "mc_set_spmm_splitting", "mc_set_spmm_stages",
                  "mc_set_softmax_variant", "mc_set_thread_options", "mc_get_thread_options", "mc_spmm_ex", "mc_sddmm_ex",
-                 "mc_sparse_attention_ex", "mc_sparse_attention_static", "mc_blocked_query", "mc_pack_blocked_host"):
+                 "mc_sparse_attention_ex", "mc_sparse_attention_static", "mc_blocked_query", "mc_pack_blocked_host", "mc_sddmm_to_mat"):
         getattr(L, name).restype = c_int
     return L
 
@@ -381,6 +382,17 @@ def sddmm_dequant(Q, Kmat, mask: SparseMatrix, prec: str, scale: float, out_dtyp
                                 Kmat.stride(0) * Kmat.element_size() * 8 // bits, Kd, mask.handle, PREC[prec], flags,
                                 float(scale), OUT_TYPE[out_dtype], out.data_ptr(), _stream()), "mc_sddmm_dequant")
     return out
+
+
+def sddmm_to_mat(Q, Kmat, P: SparseMatrix, prec: str, scale: float) -> None:
+    """(Q * Kmat^T) at P's pattern, re-quantised to P's 8- or 16-bit integers and written into P's device values."""
+    assert Q.is_cuda and Kmat.is_cuda and Q.dim() == 2 and Kmat.dim() == 2
+    assert Q.stride(1) == 1 and Kmat.stride(1) == 1 and Q.shape[1] == Kmat.shape[1] and Q.element_size() == Kmat.element_size()
+    bits = LHS_BITS[prec]
+    Kd = Q.shape[1] * Q.element_size() * 8 // bits
+    _check(lib.mc_sddmm_to_mat(Q.data_ptr(), Q.stride(0) * Q.element_size() * 8 // bits, Kmat.data_ptr(),
+                               Kmat.stride(0) * Kmat.element_size() * 8 // bits, Kd, PREC[prec], float(scale), P.handle,
+                               _stream()), "mc_sddmm_to_mat")
 
 
 def absmax(x, out=None):

@@ -711,6 +711,37 @@ extern "C" int mc_sddmm_dequant(const void *Q_dev, int ldq, const void *Kmat_dev
                       nullptr, stream);
 }
 
+extern "C" int mc_sddmm_to_mat(const void *Q_dev, int ldq, const void *Kmat_dev, int ldk, int Kd, mc_prec prec, float scale,
+                               mc_mat *P, void *stream)
+{
+    if (!Q_dev || !Kmat_dev || !P) return MC_EINVAL;
+    if (prec != MC_L8R8 && prec != MC_L4R4 && prec != MC_L16R16) return MC_EUNSUPPORTED;
+    if (P->lhs_bits == 0) return MC_EINVAL;                      // a pattern-only mask has no values to receive the codes
+    if (P->lhs_bits != 8 && P->lhs_bits != 16) return MC_EUNSUPPORTED;
+    const int bits = lhs_bits_of(prec);
+    if (Kd <= 0 || Kd % (128 / bits) != 0 || ldq < Kd || ldk < Kd) return MC_EINVAL;
+    if (((int64_t)ldq * bits / 8) % 16 != 0 || ((int64_t)ldk * bits / 8) % 16 != 0) return MC_EALIGN;
+    if (!aligned16(Q_dev) || !aligned16(Kmat_dev)) return MC_EALIGN;
+    if (!std::isfinite(scale)) return MC_EINVAL;
+    if (P->nvec == 0) return MC_OK;
+    if (!on_device_of(P)) return MC_EINVAL;
+    const mc_options o = t_options;
+
+    SddmmArgs a = {};
+    a.float_out = 3; a.out_scale = scale;
+    a.dev_vals = P->d_vals; a.dev_batch_stride = 0; a.code_bits = P->lhs_bits;
+    a.panel_ptr = P->d_panel_ptr; a.row_ptr = P->d_row_ptr; a.slot_idx = P->d_slot_idx;
+    a.Q = static_cast<const uint8_t *>(Q_dev); a.ldq_bytes = (int64_t)ldq * bits / 8; a.Q_batch_stride = 0;
+    a.Kmat = static_cast<const uint8_t *>(Kmat_dev); a.ldk_bytes = (int64_t)ldk * bits / 8; a.K_batch_stride = 0;
+    a.row_bytes = Kd * bits / 8;
+    a.S = nullptr; a.S_batch_stride = 0;
+    a.P = P->P; a.V = P->V; a.batch = 1;
+    if (P->n_items && o.spmm_splitting == 0) { a.items = P->d_items; a.n_units = P->n_items; }
+    P->blk_valid = false; // only the panel format receives the new values
+    MC_HIP(launch_sddmm(bits, a, choose_sddmm_waves(P, 1, a.row_bytes, bits, o), static_cast<hipStream_t>(stream)));
+    return MC_OK;
+}
+
 extern "C" int mc_absmax(const float *x_dev, int64_t n, float *result_dev, void *stream)
 {
     if (!x_dev || !result_dev || n < 0) return MC_EINVAL;

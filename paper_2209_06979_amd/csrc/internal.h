@@ -90,8 +90,12 @@ struct SddmmArgs {
     int row_bytes;             // Kd * bits / 8
     void *S;                   // int32, float or half (see float_out)
     int64_t S_batch_stride;    // elements
-    int float_out;             // 0: int32; 1: float(score) * out_scale as fp32; 2: the same rounded to fp16
+    int float_out;             // 0: int32; 1: float(score) * out_scale as fp32; 2: the same rounded to fp16;
+                               // 3: integer codes clamp(rint(score * out_scale)) into a sparse operand's device format
     float out_scale;
+    uint8_t *dev_vals;         // float_out 3: the operand's value array, its bytes per batch item, its code width (8 / 16)
+    int64_t dev_batch_stride;
+    int code_bits;
     int P, V, batch;
     int lhs_unsigned, rhs_unsigned; // 4- and 8-bit operands read as non-negative values
     const int32_t *items;      // optional work items (see mc_mat): null = one workgroup per panel

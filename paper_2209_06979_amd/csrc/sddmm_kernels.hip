@@ -103,9 +103,36 @@ __device__ __forceinline__ v4h to_half4(v4f f) { return (v4h){(_Float16)f.x, (_F
 
 // DQ: fused dequantisation (Section 5.3).  A compile-time switch: the integer path keeps its
 // straight-line stores, which the scheduler interleaves with the next tile's MFMAs.
+// float_out 3 (only with DQ): the scores leave as integer codes clamp(rint(score * out_scale)) of 8 or 16 bits,
+// written into the device panel format of a sparse operand with the mask's pattern (Section 4.3: the
+// SDDMM writes the format the following SpMM reads); padded slots receive zeros.  s0: first slot of the panel.
 template <bool DQ>
-__device__ __forceinline__ void store_scores(const SddmmArgs &a, int64_t out0, int slot, int n, int g, v4i acc)
+__device__ __forceinline__ void store_scores(const SddmmArgs &a, int64_t out0, int s0, int slot, int n, int g, v4i acc)
 {
+    if (DQ && a.float_out == 3) {
+        if (4 * g >= a.V) return;
+        const int64_t gs = (int64_t)s0 + slot;                 // slot of the whole matrix
+        const int sub = (int)(gs % MC_CHUNK) / 16, b = (int)(gs % 16);
+        const float qmax = (a.code_bits == 16) ? 32639.f : 127.f;
+        uint8_t *chunk = a.dev_vals + (int64_t)blockIdx.y * a.dev_batch_stride + (gs / MC_CHUNK) * (MC_CHUNK * a.V * a.code_bits / 8);
+        const int nr = a.V - 4 * g < 4 ? a.V - 4 * g : 4;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            if (r >= nr) break;
+            // one fp32 product, rounded to nearest even, then clamped: the same arithmetic as the oracle's
+            const float x = __builtin_rintf((float)acc[r] * a.out_scale);
+            const int code = (slot < n) ? (int)__builtin_fminf(__builtin_fmaxf(x, -qmax), qmax) : 0;
+            const int v = 4 * g + r;
+            if (a.code_bits == 8) {
+                chunk[sub * (16 * a.V) + v * 16 + b] = (uint8_t)code;
+            } else {
+                const int hi = (code + 128) >> 8, lo = code - hi * 256;   // two signed bytes: code = 256 * hi + lo
+                chunk[sub * (32 * a.V) + v * 16 + b] = (uint8_t)hi;
+                chunk[sub * (32 * a.V) + 16 * a.V + v * 16 + b] = (uint8_t)lo;
+            }
+        }
+        return;
+    }
     // accumulator register r of lane (j, g) is row 4g + r of vector `slot`
     if (slot < n && 4 * g < a.V) {
         const int64_t off = out0 + (int64_t)slot * a.V + 4 * g;
@@ -266,7 +293,7 @@ __global__ __launch_bounds__(64 * WK) void sddmm_lds_kernel(SddmmArgs a)
                 }
                 if (h == SEGS - 1) {
                     if (!U) {
-                        store_scores<DQ>(a, out0, (cb + c) * MC_CHUNK + s, n, g, finish_tile<PB>(acc[tl], acc2[tl]));
+                        store_scores<DQ>(a, out0, s0, (cb + c) * MC_CHUNK + s, n, g, finish_tile<PB>(acc[tl], acc2[tl]));
                     } else {
                         // sum (q'+cq)(k'+ck) = sum q'k' + ck sum q' + cq sum k' + cq ck n, with cq = ck = 128 in the
                         // scale the operand bytes carry (nibbles: 16 x their value)
@@ -276,7 +303,7 @@ __global__ __launch_bounds__(64 * WK) void sddmm_lds_kernel(SddmmArgs a)
                         if (a.lhs_unsigned) r += (v4i){cs << 7, cs << 7, cs << 7, cs << 7};
                         if (PB == 4) r = r >> 8;
                         r += (v4i){cqck, cqck, cqck, cqck};
-                        store_scores<DQ>(a, out0, (cb + c) * MC_CHUNK + s, n, g, r);
+                        store_scores<DQ>(a, out0, s0, (cb + c) * MC_CHUNK + s, n, g, r);
                     }
                 }
             }
@@ -360,7 +387,7 @@ __global__ __launch_bounds__(64 * WK) void sddmm_nib32_kernel(SddmmArgs a)
             }
             acc = acc >> 8; // both operands carried a factor 16
             if (U) acc += (v4i){cqck, cqck, cqck, cqck};
-            store_scores<DQ>(a, out0, (cb + c) * MC_CHUNK + s, n, g, acc);
+            store_scores<DQ>(a, out0, s0, (cb + c) * MC_CHUNK + s, n, g, acc);
         }
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); // reads done before the rows are overwritten
     }
@@ -380,7 +407,9 @@ __global__ __launch_bounds__(64 * SDDMM_WAVES) void sddmm_direct_kernel(SddmmArg
         panel = it.x; cb = it.y; ce = it.z;
     }
     const int s0 = a.panel_ptr[2 * panel], n = a.panel_ptr[2 * panel + 1] - s0;
-    const int tile0 = 4 * cb, ntile = (ce < 0) ? (n + 15) / 16 : min((n + 15) / 16, 4 * ce);
+    // (codes written into an operand's device format also cover the padded slots of the last chunk, with zeros)
+    const int tiles_all = (DQ && a.float_out == 3) ? (n + MC_CHUNK - 1) / MC_CHUNK * 4 : (n + 15) / 16;
+    const int tile0 = 4 * cb, ntile = (ce < 0) ? tiles_all : min(tiles_all, 4 * ce);
     const int64_t out0 = (int64_t)batch * a.S_batch_stride + (int64_t)a.row_ptr[panel] * a.V;
     const uint8_t *Qpanel = a.Q + (int64_t)batch * a.Q_batch_stride + (int64_t)panel * a.V * a.ldq_bytes;
     const uint8_t *Km = a.Kmat + (int64_t)batch * a.K_batch_stride + g * LANEB;
@@ -427,7 +456,7 @@ __global__ __launch_bounds__(64 * SDDMM_WAVES) void sddmm_direct_kernel(SddmmArg
                 mma_step<PB>(q, k, k2, acc, acc2);
             }
         }
-        store_scores<DQ>(a, out0, slot, n, g, finish_tile<PB>(acc, acc2));
+        store_scores<DQ>(a, out0, s0, slot, n, g, finish_tile<PB>(acc, acc2));
     }
 }
 
@@ -451,7 +480,9 @@ __global__ __launch_bounds__(64 * SDDMM_WAVES) void sddmm_unsigned_kernel(SddmmA
         panel = it.x; cb = it.y; ce = it.z;
     }
     const int s0 = a.panel_ptr[2 * panel], n = a.panel_ptr[2 * panel + 1] - s0;
-    const int tile0 = 4 * cb, ntile = (ce < 0) ? (n + 15) / 16 : min((n + 15) / 16, 4 * ce);
+    // (codes written into an operand's device format also cover the padded slots of the last chunk, with zeros)
+    const int tiles_all = (DQ && a.float_out == 3) ? (n + MC_CHUNK - 1) / MC_CHUNK * 4 : (n + 15) / 16;
+    const int tile0 = 4 * cb, ntile = (ce < 0) ? tiles_all : min(tiles_all, 4 * ce);
     const int64_t out0 = (int64_t)batch * a.S_batch_stride + (int64_t)a.row_ptr[panel] * a.V;
     const uint8_t *Qrow = a.Q + (int64_t)batch * a.Q_batch_stride + (int64_t)(panel * a.V + (j < a.V ? j : 0)) * a.ldq_bytes + g * 16;
     const uint8_t *Km = a.Kmat + (int64_t)batch * a.K_batch_stride + g * 16;
@@ -504,7 +535,7 @@ __global__ __launch_bounds__(64 * SDDMM_WAVES) void sddmm_unsigned_kernel(SddmmA
         if (a.lhs_unsigned) acc += (v4i){cs << 7, cs << 7, cs << 7, cs << 7};
         if (PB == 4) acc = acc >> 8;
         acc += (v4i){cqck, cqck, cqck, cqck};
-        store_scores<DQ>(a, out0, slot, n, g, acc);
+        store_scores<DQ>(a, out0, s0, slot, n, g, acc);
     }
 }
 
