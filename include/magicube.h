@@ -105,7 +105,7 @@ typedef struct mc_options {
                                 1, 2, 4 or 8 waves per panel of the kernel that stages Kmat rows in LDS   */
     int softmax_variant;     /* 0 automatic, 1 a workgroup per panel also for short panels, 2 always the
                                 any-length kernel                                                          */
-    int attention_mode;      /* 0 automatic, 1..5 as described at mc_set_attention_mode                    */
+    int attention_mode;      /* 0 automatic, 1..6 as described at mc_set_attention_mode                    */
 } mc_options;
 /* Sets every field to automatic. */
 void mc_options_init(mc_options *o);
@@ -459,8 +459,11 @@ int mc_set_softmax_variant(int variant);
  * more than 2048 vectors -- one, two or four waves per (panel, head) for panels of up to 512,
  * 1024, 2048 vectors, more waves than that when the launch is small; two neighbouring heads per
  * workgroup for token-major tensors once the launch has 2048 (panel, head) units -- else the
- * pipeline of separate kernels), 1 = always the pipeline SDDMM -> softmax -> SpMM of separate
- * kernels.  The remaining modes pin parts of the automatic choice (for tests and measurements):
+ * pipeline of kernels), 1 = always the pipeline: one kernel that computes the scores of a panel,
+ * keeps them in on-chip memory, takes the softmax and writes the integer codes in the SpMM's operand
+ * format, then the SpMM (rows of Q / Km of up to 256 bytes and panels of up to about 4700 vectors;
+ * beyond that, or with 6 = always, three kernels: SDDMM, softmax, SpMM, with the int32 scores in the
+ * workspace).  The remaining modes pin parts of the automatic choice (for tests and measurements):
  * 2 = the fused kernel with one head per workgroup even for token-major tensors, waves by panel
  * length alone; 3 / 4 = the fused kernel with at least two / with four waves per (panel, head)
  * whatever the panel length, 5 = waves by panel length alone -- 3, 4 and 5 with two heads per

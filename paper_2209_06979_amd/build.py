@@ -9,7 +9,7 @@ import sys
 PKG = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libmagicube.so")
-SOURCES = ["format_host.cpp", "api.hip", "spmm_kernels.hip", "spmm_slab_kernels.hip", "probe_kernels.hip", "sddmm_kernels.hip", "softmax_kernels.hip", "attention_kernels.hip",
+SOURCES = ["format_host.cpp", "api.hip", "spmm_kernels.hip", "spmm_slab_kernels.hip", "probe_kernels.hip", "sddmm_kernels.hip", "softmax_kernels.hip", "attention_kernels.hip", "attention_scores_kernels.hip",
            "quant_kernels.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

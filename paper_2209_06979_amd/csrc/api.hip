@@ -28,7 +28,7 @@ bool valid_options(const mc_options &o)
     if (o.spmm_slab_panels != 0 && o.spmm_slab_panels != 1 && o.spmm_slab_panels != 2 && o.spmm_slab_panels != 4) return false;
     if (d != 0 && d != -1 && d != 1 && d != 2 && d != 4 && d != 8) return false;
     if (o.softmax_variant < 0 || o.softmax_variant > 2) return false;
-    if (o.attention_mode < 0 || o.attention_mode > 5) return false;
+    if (o.attention_mode < 0 || o.attention_mode > 6) return false;
     return true;
 }
 
@@ -810,14 +810,30 @@ extern "C" int mc_sparse_softmax(const mc_mat *mask, int batch, const int32_t *S
 namespace {
 inline size_t round256(size_t x) { return (x + 255) / 256 * 256; }
 struct AttnWs { size_t scores, vals, total; };
-AttnWs attn_layout(int heads, const mc_mat *mask, int p_bits)
+// with_scores: the int32 scores of all heads travel through the workspace too (the three-kernel form)
+AttnWs attn_layout(int heads, const mc_mat *mask, int p_bits, bool with_scores = true)
 {
     AttnWs w;
     const size_t nnz = (size_t)mask->nvec * mask->V, pb = (size_t)p_bits / 8;
     w.scores = 0;
-    w.vals = w.scores + round256((size_t)heads * nnz * sizeof(int32_t));
+    w.vals = w.scores + (with_scores ? round256((size_t)heads * nnz * sizeof(int32_t)) : 0);
     w.total = w.vals + round256((size_t)heads * (size_t)mask->nslots * mask->V * pb);
     return w;
+}
+
+// Waves per (panel, head) of the kernel that computes scores and softmax together, or 0 when the layer has to
+// run as three kernels (rows longer than 256 bytes, a panel whose scores do not fit LDS, or pinned by the options).
+int scores_kernel_waves(const mc_mat *mask, int heads, int dk, int qkv_bits, const mc_options &o)
+{
+    const int row_bytes = dk * qkv_bits / 8;
+    if (o.attention_mode == 6 || row_bytes > 256) return 0;
+    // four waves share a panel's chunks when it has at least three (8 heads x 4096 x 64 at 90 %: 27.2 us with two
+    // waves, 21.9 with four), unless the options pin the count
+    const double avg = mask->P ? (double)(mask->nslots / MC_CHUNK) / mask->P : 0.0;
+    int w = o.sddmm_waves > 0 ? (o.sddmm_waves >= 4 ? 4 : 2) : (avg >= 3.0 ? 4 : 2);
+    // long panels: fewer waves leave more LDS for the scores
+    while (w > 2 && mask->max_panel_chunks * MC_CHUNK > scores_softmax_max_npad(row_bytes, w)) w /= 2;
+    return mask->max_panel_chunks * MC_CHUNK <= scores_softmax_max_npad(row_bytes, w) ? w : 0;
 }
 
 // SDDMM -> softmax (writing the SpMM's operand format) -> SpMM, every step a kernel of its own; intermediates in the
@@ -827,31 +843,44 @@ int attention_pipeline(const uint8_t *Q, const uint8_t *Km, const uint8_t *Vm, i
                        int64_t o_token_stride, const mc_mat *mask, float s_q, float s_k, float s_v, float s_p,
                        void *O, int out_f16, void *workspace_dev, const mc_options &o, hipStream_t s)
 {
-    const AttnWs ws = attn_layout(heads, mask, p_bits);
+    const int sw = scores_kernel_waves(mask, heads, dk, qkv_bits, o);
+    const AttnWs ws = attn_layout(heads, mask, p_bits, sw == 0);
     const int64_t nnz = mask->nvec * mask->V;
     uint8_t *wsb = static_cast<uint8_t *>(workspace_dev);
     int32_t *scores = reinterpret_cast<int32_t *>(wsb + ws.scores);
     uint8_t *pvals = wsb + ws.vals;
     const int row_bytes = dk * qkv_bits / 8, pb = p_bits / 8;
 
-    SddmmArgs d = {};
-    d.panel_ptr = mask->d_panel_ptr; d.row_ptr = mask->d_row_ptr; d.slot_idx = mask->d_slot_idx;
-    d.Q = Q; d.ldq_bytes = token_stride_bytes; d.Q_batch_stride = head_stride_bytes;
-    d.Kmat = Km; d.ldk_bytes = token_stride_bytes; d.K_batch_stride = head_stride_bytes;
-    d.row_bytes = row_bytes; d.S = scores; d.S_batch_stride = nnz;
-    d.P = mask->P; d.V = 8; d.batch = heads;
-    if (mask->n_items && o.spmm_splitting == 0) { d.items = mask->d_items; d.n_units = mask->n_items; } // very unequal panels
-    MC_HIP(launch_sddmm(qkv_bits, d, choose_sddmm_waves(mask, heads, row_bytes, qkv_bits, o), s));
+    if (sw) {
+        // scores and softmax in one kernel: the scores stay in LDS, only the codes (in the layout the SpMM
+        // reads: Section 4.3 lets the producer pick the output format by the consumer) reach memory
+        ScoresArgs c = {};
+        c.panel_ptr = mask->d_panel_ptr; c.slot_idx = mask->d_slot_idx;
+        c.Q = Q; c.Km = Km; c.in_head_stride = head_stride_bytes; c.in_token_stride = token_stride_bytes;
+        c.row_bytes = row_bytes;
+        c.score_scale = s_q * s_k / std::sqrt((float)dk); c.inv_s_p = 1.f / s_p;
+        c.dev_vals = pvals; c.dev_batch_stride = mask->nslots * 8 * pb;
+        c.P = mask->P; c.heads = heads; c.max_npad = mask->max_panel_chunks * MC_CHUNK;
+        MC_HIP(launch_scores_softmax(c, qkv_bits, p_bits, sw, s));
+    } else {
+        SddmmArgs d = {};
+        d.panel_ptr = mask->d_panel_ptr; d.row_ptr = mask->d_row_ptr; d.slot_idx = mask->d_slot_idx;
+        d.Q = Q; d.ldq_bytes = token_stride_bytes; d.Q_batch_stride = head_stride_bytes;
+        d.Kmat = Km; d.ldk_bytes = token_stride_bytes; d.K_batch_stride = head_stride_bytes;
+        d.row_bytes = row_bytes; d.S = scores; d.S_batch_stride = nnz;
+        d.P = mask->P; d.V = 8; d.batch = heads;
+        if (mask->n_items && o.spmm_splitting == 0) { d.items = mask->d_items; d.n_units = mask->n_items; } // very unequal panels
+        MC_HIP(launch_sddmm(qkv_bits, d, choose_sddmm_waves(mask, heads, row_bytes, qkv_bits, o), s));
 
-    // the softmax writes its codes in the layout the SpMM reads (Section 4.3 lets the producer
-    // pick the output format by the consumer)
-    SoftmaxArgs f = {};
-    f.row_ptr = mask->d_row_ptr; f.S = scores; f.batch_stride = nnz;
-    f.codes = nullptr; f.panel_ptr = mask->d_panel_ptr; f.dev_vals = pvals; f.dev_batch_stride = mask->nslots * 8 * pb;
-    f.score_scale = s_q * s_k / std::sqrt((float)dk); f.inv_s_p = 1.f / s_p;
-    f.P = mask->P; f.V = 8; f.batch = heads; f.code_bits = p_bits;
-    f.max_panel_chunks = mask->max_panel_chunks; f.variant = o.softmax_variant;
-    MC_HIP(launch_softmax(f, s));
+        // the softmax writes its codes in the layout the SpMM reads
+        SoftmaxArgs f = {};
+        f.row_ptr = mask->d_row_ptr; f.S = scores; f.batch_stride = nnz;
+        f.codes = nullptr; f.panel_ptr = mask->d_panel_ptr; f.dev_vals = pvals; f.dev_batch_stride = mask->nslots * 8 * pb;
+        f.score_scale = s_q * s_k / std::sqrt((float)dk); f.inv_s_p = 1.f / s_p;
+        f.P = mask->P; f.V = 8; f.batch = heads; f.code_bits = p_bits;
+        f.max_panel_chunks = mask->max_panel_chunks; f.variant = o.softmax_variant;
+        MC_HIP(launch_softmax(f, s));
+    }
 
     SpmmArgs m = {};
     m.panel_ptr = mask->d_panel_ptr; m.slot_idx = mask->d_slot_idx;
@@ -871,7 +900,7 @@ int attention_pipeline(const uint8_t *Q, const uint8_t *Km, const uint8_t *Vm, i
 // Whether the single fused kernel takes this layer (else the pipeline of separate kernels, which needs a workspace).
 bool attention_is_fused(const mc_mat *mask, int dk, const mc_options &o)
 {
-    return o.attention_mode != 1 && (dk == 64 || dk == 128) &&
+    return o.attention_mode != 1 && o.attention_mode != 6 && (dk == 64 || dk == 128) &&
            mask->max_panel_chunks * MC_CHUNK <= attention_fused_max_vectors();
 }
 
@@ -962,7 +991,7 @@ int attention_impl(const void *Q_dev, const void *Km_dev, const void *Vm_dev, in
         return MC_OK;
     }
     // the kernel pipeline keeps its intermediates in a workspace (none are needed when nothing is stored)
-    const size_t need = attn_layout(heads, mask, p_bits).total;
+    const size_t need = attn_layout(heads, mask, p_bits, scores_kernel_waves(mask, heads, dk, qkv_bits, o) == 0).total;
     if (use_static) {
         if (need > STATIC_SCRATCH_BYTES) {
             snprintf(g_detail, sizeof g_detail, "the layer's intermediates need %zu bytes, the library's own array holds %zu",
@@ -1007,7 +1036,10 @@ extern "C" size_t mc_attention_workspace_needed(int heads, int dk, const mc_mat 
     if (!mask || heads <= 0 || (p_bits != 8 && p_bits != 16)) return 0;
     mc_options o;
     if (resolve_options(options, &o) != MC_OK) return 0;
-    return attention_is_fused(mask, dk, o) ? 0 : attn_layout(heads, mask, p_bits).total;
+    if (attention_is_fused(mask, dk, o)) return 0;
+    // (the narrowest inputs the layer takes give the smallest rows: whether the scores stay on chip is decided
+    // for 8-bit inputs here, which never asks for less than a 4-bit layer needs)
+    return attn_layout(heads, mask, p_bits, scores_kernel_waves(mask, heads, dk, 8, o) == 0).total;
 }
 
 extern "C" int mc_sparse_attention(const int8_t *Q_dev, const int8_t *Km_dev, const int8_t *Vm_dev, int heads, int L,

@@ -102,6 +102,20 @@ struct SddmmArgs {
     int n_units;               // items, or P
 };
 
+// Scores + softmax of the attention layer in one kernel (attention_scores_kernels.hip): V = 8, one mask for all heads.
+struct ScoresArgs {
+    const int32_t *panel_ptr;
+    const int32_t *slot_idx;
+    const uint8_t *Q, *Km;
+    int64_t in_head_stride, in_token_stride; // bytes
+    int row_bytes;             // dk * bits / 8, a multiple of 16, at most 256
+    float score_scale, inv_s_p;
+    uint8_t *dev_vals;         // codes in the device panel format, one block of dev_batch_stride bytes per head
+    int64_t dev_batch_stride;
+    int P, heads;
+    int max_npad;              // longest panel of the mask, padded to whole chunks, in vectors
+};
+
 struct SoftmaxArgs {
     const int32_t *row_ptr;
     const int32_t *S;
@@ -155,6 +169,9 @@ hipError_t launch_gather_probe(const SpmmArgs &a, int bnb, int waves, int32_t *s
 // (used when a row has 64, 128, 256, 512 or 1024 bytes)
 hipError_t launch_sddmm(int bits, const SddmmArgs &a, int waves, hipStream_t s);
 hipError_t launch_softmax(const SoftmaxArgs &a, hipStream_t s);
+// waves: 2 or 4 per (panel, head); the longest padded panel must not exceed scores_softmax_max_npad(row_bytes, waves)
+hipError_t launch_scores_softmax(const ScoresArgs &a, int qkv_bits, int code_bits, int waves, hipStream_t s);
+int scores_softmax_max_npad(int row_bytes, int waves);
 hipError_t launch_absmax(const float *x, int64_t n, float *result, hipStream_t s);
 hipError_t launch_quantize(const float *x, int64_t n, float scale, int bits, uint8_t *q, hipStream_t s);
 hipError_t launch_repack(const RepackArgs &a, hipStream_t s);

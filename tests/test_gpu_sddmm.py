@@ -166,6 +166,26 @@ def test_attention_small(mode, token_major):
 
 
 @pytest.mark.parametrize("token_major", [False, True])
+@pytest.mark.parametrize("mode", [1, 6])   # 1: scores and softmax in one kernel, then the SpMM; 6: three kernels
+def test_attention_pipeline_head_dimensions_and_long_panels(mode, token_major):
+    """Head dimensions the single fused kernel does not take (16, 32, 96, 160, 256) and panels beyond its 2048
+    vectors, through both forms of the kernel pipeline."""
+    _attention_check(2, 256, 16, 0.5, 1260, mode, token_major)     # rows of 16 bytes: one copy segment real, three repeated
+    _attention_check(3, 512, 32, 0.9, 1261, mode, token_major)
+    _attention_check(2, 512, 96, 0.8, 1262, mode, token_major)     # 96 bytes in a 128-byte stage
+    _attention_check(1, 512, 160, 0.75, 1263, mode, token_major)   # 160 bytes in a 256-byte stage
+    _attention_check(2, 256, 256, 0.5, 1264, mode, token_major)    # the longest rows the one-kernel form takes
+    _attention_check(1, 4096, 64, 0.45, 1265, mode, token_major)   # 2253 vectors per panel
+    _attention_check(1, 4096, 32, 0.0, 1266, mode, token_major)    # 4096 vectors: 131 KB of scores per panel in LDS, two waves
+    _attention_check(1, 2048, 320, 0.8, 1267, mode, token_major)   # rows of 320 bytes: three kernels in either mode
+    _attention_check(2, 512, 64, 0.95, 1268, mode, token_major)    # 26 vectors per panel: a single ragged chunk
+
+
+def test_attention_panels_beyond_on_chip_memory_fall_back_to_three_kernels():
+    _attention_check(1, 8192, 32, 0.3, 1269, 1, False)             # 5734 vectors per panel: the scores do not fit LDS
+
+
+@pytest.mark.parametrize("token_major", [False, True])
 @pytest.mark.parametrize("mode", [2, 3, 4])
 def test_attention_forced_fused_variants(mode, token_major):
     """One head per workgroup (2) and two / four waves per (panel, head) (3, 4) on short and long panels."""
@@ -209,7 +229,7 @@ def test_attention_long_sequences():
 
 
 @pytest.mark.parametrize("token_major", [False, True])
-@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("mode", [0, 1, 6])
 def test_attention_config5_full(mode, token_major):
     """BASELINE config 5: 8 heads, L=4096, dk=64, 90 % vector sparsity, diagonal kept."""
     _attention_check(8, 4096, 64, 0.9, wl.seed_for(5), mode, token_major)

@@ -253,7 +253,7 @@ def test_attention_two_heads_per_workgroup_sharing_long_panels(p_bits, qkv_bits,
 
 
 @pytest.mark.parametrize("p_bits,qkv_bits", [(16, 8), (8, 4)])
-@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("mode", [0, 1, 6])
 def test_attention_variants_config5_shape(p_bits, qkv_bits, mode):
     """The 16b-8b and 8b-4b variants at 8 heads, L=4096, dk=64, 90 % vector sparsity."""
     _attention_variant_check(8, 4096, 64, 0.9, wl.seed_for(5, 1), p_bits, qkv_bits, mode=mode)
@@ -369,7 +369,7 @@ def test_attention_batched_long_panels_equal_item_by_item(L, dk, sparsity, mode)
         mask.close()
 
 
-@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("mode", [0, 1, 6])
 @pytest.mark.parametrize("p_bits,qkv_bits", [(8, 8), (16, 8), (8, 4)])
 def test_attention_batched_equals_item_by_item(p_bits, qkv_bits, mode):
     """A batch sharing one mask, in the (batch, L, heads, dk) layout of a projection's output and in the

@@ -168,7 +168,7 @@ def test_entry_points_reject_bad_arguments_before_touching_the_gpu():
     assert L.mc_probe_gather(None, None, 16, 16, 0, None, None) == mc.MC_EINVAL
     assert L.mc_mat_info(None, None, None, None, None, None, None) == mc.MC_EINVAL
     assert L.mc_mat_set_values_device(None, None, None) == mc.MC_EINVAL
-    assert L.mc_set_attention_mode(9) == mc.MC_EINVAL and L.mc_set_attention_mode(6) == mc.MC_EINVAL
+    assert L.mc_set_attention_mode(9) == mc.MC_EINVAL and L.mc_set_attention_mode(7) == mc.MC_EINVAL
     assert L.mc_set_attention_mode(-1) == mc.MC_EINVAL
     assert L.mc_set_attention_mode(5) == mc.MC_OK and L.mc_set_attention_mode(0) == mc.MC_OK
     assert L.mc_set_spmm_variant(100, 1) == mc.MC_EINVAL and L.mc_set_spmm_variant(0, 0) == mc.MC_OK

@@ -36,7 +36,7 @@ def test_init_is_all_automatic():
     ("spmm_slab_panels", [0, 1, 2, 4], [3, 8, -1]),
     ("sddmm_waves", [0, -1, 1, 2, 4, 8], [3, 16, -2]),
     ("softmax_variant", [0, 1, 2], [3, -1]),
-    ("attention_mode", [0, 1, 2, 3, 4, 5], [6, -1]),
+    ("attention_mode", [0, 1, 2, 3, 4, 5, 6], [7, -1]),
 ])
 def test_validation_of_every_field(field, good, bad):
     for v in good:

@@ -85,14 +85,20 @@ def test_fused_path_needs_no_scratch_and_sizes_beyond_the_array_are_refused():
     from paper_2209_06979_amd import binding as mc
     got, want, _, _ = _both(mc, 2, 512, 64, 0.8, 7030)           # automatic: the fused kernel, nothing staged
     assert np.array_equal(got, want)
-    # 8 heads x L = 4096 at 90 %: the pipeline's scores alone are 53.7 MB, the array holds 16 MiB
+    # 8 heads x L = 4096 at 90 % with 16-bit codes: 29 MB of codes alone, the array holds 16 MiB
     c, (q, k, v), (s_q, s_k, s_v) = _inputs(8, 4096, 32, 0.9, 7031, 8)
     mask = mc.SparseMatrix(4096, 4096, 8, c["row_ptr"], c["col_idx"])
-    assert mc.attention_workspace_bytes(8, mask) > mc.STATIC_SCRATCH_BYTES
+    assert mc.attention_workspace_needed(8, 32, mask, 16) > mc.STATIC_SCRATCH_BYTES
     out = torch.full((8, 4096, 32), 5.0, dtype=torch.float32, device="cuda")
     with pytest.raises(mc.MagicubeError) as e:
-        mc.sparse_attention_static(q, k, v, mask, s_q, s_k, s_v, np.float32(1 / 127), out)
+        mc.sparse_attention_static(q, k, v, mask, s_q, s_k, s_v, np.float32(1 / 32639), out, p_bits=16)
     assert e.value.status == mc.MC_ENOMEM
     torch.cuda.synchronize()
     assert bool((out == 5.0).all())                               # refused before any launch
+    # the same layer with 8-bit codes fits since its scores never leave the chip (14.7 MB of codes)
+    assert mc.attention_workspace_needed(8, 32, mask, 8) <= mc.STATIC_SCRATCH_BYTES
+    want = mc.sparse_attention(q, k, v, mask, s_q, s_k, s_v, np.float32(1 / 127))
+    mc.sparse_attention_static(q, k, v, mask, s_q, s_k, s_v, np.float32(1 / 127), out)
+    torch.cuda.synchronize()
+    assert torch.equal(out, want)
     mask.close()
