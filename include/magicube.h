@@ -75,7 +75,8 @@ typedef enum { MC_OUT_F32 = 0, MC_OUT_F16 = 1 } mc_out_type;
 typedef struct mc_mat mc_mat; /* opaque: device-resident sparse matrix or mask */
 
 const char *mc_strerror(int status);
-/* "major.minor gfx950": build identification. */
+/* "major.minor+<source id> gfx950": build identification; the source id (12 hex digits) changes with any
+ * source file or compiler flag of the library, so a stored measurement can name the build it belongs to. */
 const char *mc_version(void);
 /* After a call returned MC_EHIP on this thread: which HIP call failed and its message
  * (empty string if none yet).  The pointer stays valid for the thread's lifetime. */
@@ -230,6 +231,9 @@ int mc_spmm_flags(const mc_mat *A, const void *B_dev, int N, int ldb, mc_prec pr
  * thread's defaults are).  MC_EINVAL for an option value outside its list. */
 int mc_spmm_ex(const mc_mat *A, const void *B_dev, int N, int ldb, mc_prec prec, unsigned flags,
                const mc_options *options, int32_t *C_dev, int ldc, void *stream);
+/* Which form mc_spmm_ex would run for this operand, width and options (host only, launches nothing):
+ * 0 = rows of B gathered per stored vector, 1 = K-blocks of B resident in LDS.  Negative: an error code. */
+int mc_spmm_form(const mc_mat *A, int N, mc_prec prec, const mc_options *options);
 
 /* SpMM with fused dequantisation (Section 5.3: the integer product is turned into real values
  * in the kernel's epilogue): C = scale * (A * B), each element computed as float(int32 result) *
@@ -250,6 +254,13 @@ int mc_spmm_dequant(const mc_mat *A, const void *B_dev, int N, int ldb, mc_prec 
 int64_t mc_probe_gather_sink_len(const mc_mat *A, int N, mc_prec prec);
 int mc_probe_gather(const mc_mat *A, const void *B_dev, int N, int ldb, mc_prec prec, int32_t *sink_dev,
                     void *stream);
+
+/* Measurement aid (Section 5 reports its kernels against the peak of the matrix unit): the matrix unit
+ * alone.  `workgroups` workgroups of four waves each issue iters * 8 independent 16x16x64 int8 MFMAs on
+ * registers, i.e. workgroups * 4 * iters * 8 * 32768 operations without any memory traffic; timing it gives
+ * the int8 rate this device sustains in practice, to set beside the published peak.
+ *   sink_dev   workgroups * 256 int32, receives the (meaningless) sums. */
+int mc_probe_mfma(int workgroups, int iters, int32_t *sink_dev, void *stream);
 
 /* ------------------------------------------------------------------------------------
  * SDDMM (Section 4.3): for every stored vector i of the mask (panel p, column c):

@@ -102,6 +102,8 @@ def _load() -> ctypes.CDLL:
     L.mc_sddmm_dequant.argtypes = [c_void_p, c_int, c_void_p, c_int, c_int, c_void_p, c_int, ctypes.c_uint, c_float, c_int,
                                    c_void_p, c_void_p]
     L.mc_sparse_softmax_to_mat.argtypes = [c_void_p, c_void_p, c_float, c_float, c_void_p]
+    L.mc_spmm_form.argtypes = [c_void_p, c_int, c_int, POINTER(Options)]
+    L.mc_probe_mfma.argtypes = [c_int, c_int, c_void_p, c_void_p]
     L.mc_sddmm_to_mat.argtypes = [c_void_p, c_int, c_void_p, c_int, c_int, c_int, c_float, c_void_p, c_void_p]
     L.mc_absmax.argtypes = [c_void_p, c_int64, c_void_p, c_void_p]
     L.mc_quantize.argtypes = [c_void_p, c_int64, c_float, c_int, c_void_p, c_void_p]
@@ -131,7 +133,7 @@ def _load() -> ctypes.CDLL:
                  "mc_absmax", "mc_quantize", "mc_sparse_attention_out", "mc_spmm_dequant", "mc_sddmm_dequant", "mc_sparse_softmax_to_mat",
                  "mc_set_spmm_variant", "mc_set_attention_mode", "mc_set_sddmm_variant", "mc_set_spmm_splitting", "mc_set_spmm_stages",
                  "mc_set_softmax_variant", "mc_set_thread_options", "mc_get_thread_options", "mc_spmm_ex", "mc_sddmm_ex",
-                 "mc_sparse_attention_ex", "mc_sparse_attention_static", "mc_blocked_query", "mc_pack_blocked_host", "mc_sddmm_to_mat"):
+                 "mc_sparse_attention_ex", "mc_sparse_attention_static", "mc_blocked_query", "mc_pack_blocked_host", "mc_sddmm_to_mat", "mc_probe_mfma", "mc_spmm_form"):
         getattr(L, name).restype = c_int
     return L
 
@@ -315,6 +317,14 @@ def spmm(A: SparseMatrix, B, prec: str, out=None, lhs_unsigned: bool = False, rh
 OUT_TYPE = {torch.float32: 0, torch.float16: 1}
 
 
+def spmm_form(A: SparseMatrix, N: int, prec: str, options: Options | None = None) -> str:
+    """The form mc_spmm_ex would take for this operand: "gather" or "lds" (K-blocks of B resident in LDS)."""
+    r = lib.mc_spmm_form(A.handle, N, PREC[prec], ctypes.byref(options) if options is not None else None)
+    if r < 0:
+        _check(r, "mc_spmm_form")
+    return "lds" if r else "gather"
+
+
 def spmm_dequant(A: SparseMatrix, B, prec: str, scale: float, out_dtype=torch.float32, out=None,
                  lhs_unsigned: bool = False, rhs_unsigned: bool = False):  # kernel variants: the thread's options
     """C = scale * (A * B) as fp32 or fp16 (M x N): SpMM with the dequantisation fused into the kernel."""
@@ -340,6 +350,14 @@ def probe_gather(A: SparseMatrix, B, prec: str, sink=None):
         sink = torch.zeros(int(lib.mc_probe_gather_sink_len(A.handle, N, PREC[prec])), dtype=torch.int32, device=B.device)
     _check(lib.mc_probe_gather(A.handle, B.data_ptr(), N, B.stride(0) * B.element_size() * 8 // rbits, PREC[prec],
                                sink.data_ptr(), _stream()), "mc_probe_gather")
+    return sink
+
+
+def probe_mfma(workgroups: int, iters: int, sink=None):
+    """Only MFMAs (a measurement aid): workgroups * 4 waves * iters * 8 instructions of 32768 int8 operations each."""
+    if sink is None:
+        sink = torch.empty(workgroups * 256, dtype=torch.int32, device="cuda")
+    _check(lib.mc_probe_mfma(workgroups, iters, sink.data_ptr(), _stream()), "mc_probe_mfma")
     return sink
 
 

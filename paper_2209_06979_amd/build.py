@@ -1,6 +1,7 @@
 """Builds libmagicube.so (HIP kernels + C ABI) in-tree for gfx950 with hipcc."""
 from __future__ import annotations
 
+import hashlib
 import os
 import re
 import subprocess
@@ -23,15 +24,30 @@ FLAGS = [
 ]
 
 
+def source_id() -> str:
+    """Twelve hex digits that change with any source file or compiler flag of the library; mc_version() carries
+    them, so that a stored profile can say which build it was taken from."""
+    h = hashlib.sha256(" ".join(FLAGS).encode())
+    for name in sorted(os.listdir(CSRC)):
+        if name.endswith((".hip", ".cpp", ".h")):
+            with open(os.path.join(CSRC, name), "rb") as f:
+                h.update(name.encode() + b"\0" + f.read())
+    with open(os.path.join(os.path.dirname(PKG), "include", "magicube.h"), "rb") as f:
+        h.update(f.read())
+    return h.hexdigest()[:12]
+
+
 def build_library(verbose: bool = False, jobs: int = 4) -> str:
     """Compiles every source, checks the kernels' resource usage (see check_resources) and links the library."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     objdir = os.path.join(PKG, "_build")
     os.makedirs(objdir, exist_ok=True)
     procs, objs, table = [], [], []
+    sid = source_id()
     for src in SOURCES:
         obj = os.path.join(objdir, os.path.splitext(src)[0] + ".o")
-        cmd = [hipcc, *FLAGS, "-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [hipcc, *FLAGS, *([f'-DMC_SOURCE_ID="{sid}"'] if src == "api.hip" else []),
+               "-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))

@@ -193,7 +193,10 @@ extern "C" const char *mc_strerror(int status)
     }
 }
 
-extern "C" const char *mc_version(void) { return "0.1 gfx950"; }
+#ifndef MC_SOURCE_ID
+#define MC_SOURCE_ID "unidentified"
+#endif
+extern "C" const char *mc_version(void) { return "0.2+" MC_SOURCE_ID " gfx950"; }
 
 extern "C" const char *mc_last_error_detail(void) { return g_detail; }
 
@@ -527,6 +530,15 @@ bool slab_pays(const mc_mat *A, int row_bytes, int batch, const SlabPlan &pl)
     return t_slab < 0.92 * t_gather;
 }
 
+// The form one SpMM call takes: true = K-blocks of B resident in LDS (then *pl is its work split).
+bool slab_chosen(const mc_mat *A, int row_bytes, int rb, unsigned flags, const mc_options &o, SlabPlan *pl)
+{
+    if (o.spmm_slab == -1 || !A->d_blk_vals || !A->blk_valid || flags != 0 || rb == 16 || o.spmm_row_tile_bytes != 0 ||
+        o.spmm_waves != 0)
+        return false;
+    return plan_slab(A, row_bytes, rb == 4, 1, o, pl) && (o.spmm_slab == 1 || slab_pays(A, row_bytes, 1, *pl));
+}
+
 // out_mode 0: int32 results; 1 / 2: scale * result as fp32 / fp16 (fused dequantisation)
 int spmm_impl(const mc_mat *A, const void *B_dev, int N, int ldb, mc_prec prec, unsigned flags, int out_mode,
               float scale, void *C_dev, int ldc, const mc_options *opts, void *stream)
@@ -557,10 +569,9 @@ int spmm_impl(const mc_mat *A, const void *B_dev, int N, int ldb, mc_prec prec, 
     a.C = C_dev; a.ldc = ldc; a.C_batch_stride = 0;
     a.P = A->P; a.V = A->V; a.batch = 1; a.float_out = out_mode; a.out_scale = out_mode ? scale : 1.f;
     // dense matrices: blocks of B resident in LDS instead of a gather per stored vector
-    if (o.spmm_slab != -1 && A->d_blk_vals && A->blk_valid && flags == 0 && rb != 16 && o.spmm_row_tile_bytes == 0 &&
-        o.spmm_waves == 0) {
+    {
         SlabPlan pl;
-        if (plan_slab(A, a.row_bytes, rb == 4, 1, o, &pl) && (o.spmm_slab == 1 || slab_pays(A, a.row_bytes, 1, pl))) {
+        if (slab_chosen(A, a.row_bytes, rb, flags, o, &pl)) {
             SlabArgs sa = {};
             sa.blk_ptr = A->d_blk_ptr; sa.blk_rows = A->d_blk_rows; sa.vals = A->d_blk_vals; sa.vals_batch_stride = 0;
             sa.B = a.B; sa.ldb_bytes = a.ldb_bytes; sa.B_batch_stride = 0; sa.row_bytes = a.row_bytes; sa.K = A->K;
@@ -610,6 +621,17 @@ extern "C" int mc_spmm_ex(const mc_mat *A, const void *B_dev, int N, int ldb, mc
     return spmm_impl(A, B_dev, N, ldb, prec, flags, 0, 1.f, C_dev, ldc, options ? options : &automatic, stream);
 }
 
+extern "C" int mc_spmm_form(const mc_mat *A, int N, mc_prec prec, const mc_options *options)
+{
+    if (!A || N <= 0 || !valid_prec((int)prec) || A->lhs_bits != lhs_bits_of(prec)) return MC_EINVAL;
+    const mc_options automatic = {};
+    mc_options o;
+    if (resolve_options(options ? options : &automatic, &o) != MC_OK) return MC_EINVAL;
+    SlabPlan pl;
+    const int rb = rhs_bits_of(prec);
+    return slab_chosen(A, N * rb / 8, rb, 0u, o, &pl) ? 1 : 0;
+}
+
 extern "C" int mc_spmm_dequant(const mc_mat *A, const void *B_dev, int N, int ldb, mc_prec prec, unsigned flags,
                                float scale, mc_out_type out_type, void *C_dev, int ldc, void *stream)
 {
@@ -644,6 +666,13 @@ extern "C" int mc_probe_gather(const mc_mat *A, const void *B_dev, int N, int ld
     int bnb, waves;
     choose_variant(A, A->lhs_bits, a.row_bytes, rb == 4, 1, A->max_panel_chunks, o, &bnb, &waves);
     MC_HIP(launch_gather_probe(a, bnb, waves, sink_dev, static_cast<hipStream_t>(stream)));
+    return MC_OK;
+}
+
+extern "C" int mc_probe_mfma(int workgroups, int iters, int32_t *sink_dev, void *stream)
+{
+    if (!sink_dev || workgroups <= 0 || workgroups > 65535 || iters <= 0) return MC_EINVAL;
+    MC_HIP(launch_mfma_probe(workgroups, iters, sink_dev, static_cast<hipStream_t>(stream)));
     return MC_OK;
 }
 

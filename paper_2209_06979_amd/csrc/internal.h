@@ -165,6 +165,8 @@ hipError_t launch_repack_blocked(const int32_t *blk_src, const uint8_t *src, uin
 hipError_t launch_zero_rows(int32_t *C, int64_t ldc, int n, int V, const int32_t *panels, int n_panels, hipStream_t s);
 // the gather of launch_spmm alone (same tile variant); sink: one int32 per workgroup (P * row tiles)
 hipError_t launch_gather_probe(const SpmmArgs &a, int bnb, int waves, int32_t *sink, hipStream_t s);
+// `workgroups` x 4 waves x `iters` x 8 MFMAs (16x16x64 i8); sink: workgroups * 256 int32
+hipError_t launch_mfma_probe(int workgroups, int iters, int32_t *sink, hipStream_t s);
 // waves: 0 = the direct-load kernel; 1, 2, 4, 8 = waves per panel of the LDS-staged kernel
 // (used when a row has 64, 128, 256, 512 or 1024 bytes)
 hipError_t launch_sddmm(int bits, const SddmmArgs &a, int waves, hipStream_t s);

@@ -70,7 +70,32 @@ template <int BNB> hipError_t launch_bnb(const SpmmArgs &a, int waves, int32_t *
     return hipGetLastError();
 }
 
+// The matrix unit alone: every wave issues `iters` rounds of eight independent v_mfma_i32_16x16x64_i8 on
+// registers (no memory traffic inside the loop); the sums go to `sink` so that nothing is optimised away.
+__global__ __launch_bounds__(256) void mfma_probe_kernel(int iters, int32_t *sink)
+{
+    v4i acc[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) acc[t] = (v4i){0, 0, 0, 0};
+    const int l = threadIdx.x;
+    v4i a = {l, l + 1, l + 2, l + 3}, b = {l * 3, l * 5, l * 7, l * 11};
+    for (int i = 0; i < iters; ++i) {
+#pragma unroll
+        for (int t = 0; t < 8; ++t) acc[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b, acc[t], 0, 0, 0);
+    }
+    v4i s = acc[0];
+#pragma unroll
+    for (int t = 1; t < 8; ++t) s += acc[t];
+    sink[(size_t)blockIdx.x * 256 + l] = s.x + s.y + s.z + s.w;
+}
+
 } // namespace
+
+hipError_t launch_mfma_probe(int workgroups, int iters, int32_t *sink, hipStream_t s)
+{
+    hipLaunchKernelGGL(mfma_probe_kernel, dim3((unsigned)workgroups), dim3(256), 0, s, iters, sink);
+    return hipGetLastError();
+}
 
 hipError_t launch_gather_probe(const SpmmArgs &a, int bnb, int waves, int32_t *sink, hipStream_t s)
 {
