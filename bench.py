@@ -446,6 +446,14 @@ def run_skew(mc, torch):
             row["spmm_whole_panels_us"] = round(time_graph(torch, stream, [lambda: mc.spmm(A, B, "L8R8", out=C, options=whole)] * 50, rounds=3), 2)
             row["sddmm_us"] = round(time_graph(torch, stream, [lambda: mc.sddmm(Q, Km, A, "L8R8", out=S)] * 50, rounds=3), 2)
             row["sddmm_whole_panels_us"] = round(time_graph(torch, stream, [lambda: mc.sddmm(Q, Km, A, "L8R8", out=S, options=whole)] * 50, rounds=3), 2)
+            # the attention layer as a pipeline of kernels (head dimension 96 has no fused kernel): its last SpMM
+            # writes rounded values, so shared panels go through int32 rows of the workspace first
+            x = torch.randint(-127, 128, (L_ATT, HEADS, 96), dtype=torch.int8, device="cuda").permute(1, 0, 2)
+            O = torch.empty((L_ATT, HEADS, 96), dtype=torch.float32, device="cuda").permute(1, 0, 2)
+            for key, o in (("attention_dk96_us", mc.Options()), ("attention_dk96_whole_panels_us", whole)):
+                ws = torch.empty(max(16, mc.attention_workspace_needed(HEADS, 96, A, 8, o)), dtype=torch.uint8, device="cuda")
+                row[key] = round(time_graph(torch, stream, [lambda: mc.sparse_attention(x, x, x, A, 0.02, 0.02, 0.02, 1 / 127, out=O,
+                                                                                        workspace=ws, options=o)] * 20, rounds=3), 2)
             row["spmm_eff_tops"] = round(2 * nvec * V * N_SPMM / row["spmm_us"] / 1e6, 1)
             row["sddmm_eff_tops"] = round(2 * nvec * V * KD_SDDMM / row["sddmm_us"] / 1e6, 1)
             rows.append(row)

@@ -240,7 +240,8 @@ int mc_spmm_form(const mc_mat *A, int N, mc_prec prec, const mc_options *options
  * scale in fp32 and, for MC_OUT_F16, rounded to nearest even (magnitudes beyond the fp16 range
  * become infinity).  C_dev: M x N row-major float or half, 16-byte aligned, ldc a multiple of 4.
  * scale must be finite.  Other arguments and limits as mc_spmm_flags.  Panels of very unequal
- * length are not shared between workgroups here (a rounded result cannot be added up piecewise). */
+ * length are not shared between workgroups here (a rounded result cannot be added up piecewise, and
+ * this call has no workspace for exact partial sums; the attention layer's last SpMM has one). */
 int mc_spmm_dequant(const mc_mat *A, const void *B_dev, int N, int ldb, mc_prec prec, unsigned flags, float scale,
                     mc_out_type out_type, void *C_dev, int ldc, void *stream);
 
@@ -355,9 +356,13 @@ int mc_sparse_softmax_to_mat(mc_mat *P, const int32_t *S_dev, float score_scale,
  * mask stores nothing.
  * ---------------------------------------------------------------------------------- */
 size_t mc_attention_workspace_bytes(int heads, const mc_mat *mask);
-/* Bytes of workspace the layer will really use for this head dimension and these options
- * (NULL: the calling thread's defaults): 0 when the fused kernel runs, else
- * mc_attention_workspace_bytes_bits(heads, mask, p_bits). */
+/* Bytes of workspace the layer makes use of for this head dimension and these options (NULL: the
+ * calling thread's defaults): 0 when the fused kernel runs; else the codes of all heads, plus the
+ * int32 scores when they travel through memory (three kernels), plus -- for a mask with panels many
+ * times longer than the average, unless spmm_splitting is -1 -- int32 output rows of those panels,
+ * which several workgroups of the last SpMM then share.  mc_attention_workspace_bytes[_bits] (codes
+ * and scores) is always enough to run; with less than the figure returned here the long panels are
+ * simply not shared (same results, a longer tail). */
 size_t mc_attention_workspace_needed(int heads, int dk, const mc_mat *mask, int p_bits, const mc_options *options);
 /* The same layer for any regular layout: element (head h, token l, d) of Q, Km, Vm (int8)
  * and of O (fp32) sits at h*head_stride + l*token_stride + d (strides in elements, both

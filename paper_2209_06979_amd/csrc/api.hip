@@ -330,7 +330,8 @@ extern "C" int mc_mat_create(int M, int K, int V, int lhs_bits, const int32_t *r
                         items.insert(items.end(), {p, 0, c, 0});
                     } else {
                         const int per = (c + pieces - 1) / pieces;
-                        for (int b = 0; b < c; b += per) items.insert(items.end(), {p, b, std::min(c, b + per), 1});
+                        // (fourth field: 1 + the panel's position in split_panels)
+                        for (int b = 0; b < c; b += per) items.insert(items.end(), {p, b, std::min(c, b + per), (int)split_panels.size()});
                     }
                 }
             } catch (const std::bad_alloc &) {
@@ -838,17 +839,21 @@ extern "C" int mc_sparse_softmax(const mc_mat *mask, int batch, const int32_t *S
 
 namespace {
 inline size_t round256(size_t x) { return (x + 255) / 256 * 256; }
-struct AttnWs { size_t scores, vals, total; };
-// with_scores: the int32 scores of all heads travel through the workspace too (the three-kernel form)
-AttnWs attn_layout(int heads, const mc_mat *mask, int p_bits, bool with_scores = true)
+struct AttnWs { size_t scores, vals, acc, total; };
+// with_scores: the int32 scores of all heads travel through the workspace too (the three-kernel form).
+// acc_dk != 0: room for the int32 output rows (acc_dk columns) of the panels that several workgroups share.
+AttnWs attn_layout(int heads, const mc_mat *mask, int p_bits, bool with_scores = true, int acc_dk = 0)
 {
     AttnWs w;
     const size_t nnz = (size_t)mask->nvec * mask->V, pb = (size_t)p_bits / 8;
     w.scores = 0;
     w.vals = w.scores + (with_scores ? round256((size_t)heads * nnz * sizeof(int32_t)) : 0);
-    w.total = w.vals + round256((size_t)heads * (size_t)mask->nslots * mask->V * pb);
+    w.acc = w.vals + round256((size_t)heads * (size_t)mask->nslots * mask->V * pb);
+    w.total = w.acc + round256((size_t)heads * (size_t)mask->n_split * mask->V * (size_t)acc_dk * sizeof(int32_t));
     return w;
 }
+// Whether the pipeline's SpMM shares long panels between workgroups (it then needs the extra workspace rows).
+inline bool pipeline_splits(const mc_mat *mask, const mc_options &o) { return mask->n_items > 0 && o.spmm_splitting == 0; }
 
 // Waves per (panel, head) of the kernel that computes scores and softmax together, or 0 when the layer has to
 // run as three kernels (rows longer than 256 bytes, a panel whose scores do not fit LDS, or pinned by the options).
@@ -870,10 +875,10 @@ int scores_kernel_waves(const mc_mat *mask, int heads, int dk, int qkv_bits, con
 int attention_pipeline(const uint8_t *Q, const uint8_t *Km, const uint8_t *Vm, int heads, int dk, int qkv_bits,
                        int p_bits, int64_t head_stride_bytes, int64_t token_stride_bytes, int64_t o_head_stride,
                        int64_t o_token_stride, const mc_mat *mask, float s_q, float s_k, float s_v, float s_p,
-                       void *O, int out_f16, void *workspace_dev, const mc_options &o, hipStream_t s)
+                       void *O, int out_f16, void *workspace_dev, bool split_panels, const mc_options &o, hipStream_t s)
 {
     const int sw = scores_kernel_waves(mask, heads, dk, qkv_bits, o);
-    const AttnWs ws = attn_layout(heads, mask, p_bits, sw == 0);
+    const AttnWs ws = attn_layout(heads, mask, p_bits, sw == 0, split_panels ? dk : 0);
     const int64_t nnz = mask->nvec * mask->V;
     uint8_t *wsb = static_cast<uint8_t *>(workspace_dev);
     int32_t *scores = reinterpret_cast<int32_t *>(wsb + ws.scores);
@@ -919,10 +924,21 @@ int attention_pipeline(const uint8_t *Q, const uint8_t *Km, const uint8_t *Vm, i
     m.P = mask->P; m.V = 8; m.batch = heads; m.float_out = out_f16 ? 2 : 1; m.out_scale = s_p * s_v;
     m.stages = spmm_stages_for(o, mask->K, m.ldb_bytes, m.row_bytes);
     m.max_unit_chunks = mask->max_panel_chunks;
+    if (split_panels) {
+        // Very unequal panels: the long ones are shared by several workgroups.  A rounded result cannot be added
+        // up piecewise, so those add their exact int32 tiles into rows of the workspace (cleared first), which a
+        // last small kernel scales and writes to O; all other panels write O directly, as without the split.
+        m.items = mask->d_items; m.n_units = mask->n_items; m.max_unit_chunks = mask->max_item_chunks;
+        m.acc = reinterpret_cast<int32_t *>(wsb + ws.acc); m.acc_ld = dk; m.n_split = mask->n_split;
+        MC_HIP(launch_zero_ints(m.acc, (int64_t)heads * mask->n_split * 8 * dk, s));
+    }
     int bnb, waves;
-    choose_variant(mask, p_bits, m.row_bytes, qkv_bits == 4, heads, mask->max_panel_chunks, o, &bnb, &waves);
+    choose_variant(mask, p_bits, m.row_bytes, qkv_bits == 4, heads, m.max_unit_chunks, o, &bnb, &waves);
     const mc_prec prec = (p_bits == 16) ? (qkv_bits == 4 ? MC_L16R4 : MC_L16R8) : (qkv_bits == 4 ? MC_L8R4 : MC_L8R8);
     MC_HIP(launch_spmm(prec, m, bnb, waves, s));
+    if (split_panels)
+        MC_HIP(launch_finish_split_rows(m.acc, dk, mask->n_split, 8, heads, mask->d_split_panels, O, o_token_stride,
+                                        o_head_stride, m.float_out, m.out_scale, s));
     return MC_OK;
 }
 
@@ -1020,7 +1036,11 @@ int attention_impl(const void *Q_dev, const void *Km_dev, const void *Vm_dev, in
         return MC_OK;
     }
     // the kernel pipeline keeps its intermediates in a workspace (none are needed when nothing is stored)
-    const size_t need = attn_layout(heads, mask, p_bits, scores_kernel_waves(mask, heads, dk, qkv_bits, o) == 0).total;
+    const bool with_scores = scores_kernel_waves(mask, heads, dk, qkv_bits, o) == 0;
+    const size_t need = attn_layout(heads, mask, p_bits, with_scores).total;
+    // sharing long panels between workgroups takes some more room; without it they run whole (same results)
+    const size_t need_split = attn_layout(heads, mask, p_bits, with_scores, dk).total;
+    const bool split_panels = pipeline_splits(mask, o) && (use_static ? need_split <= STATIC_SCRATCH_BYTES : workspace_bytes >= need_split);
     if (use_static) {
         if (need > STATIC_SCRATCH_BYTES) {
             snprintf(g_detail, sizeof g_detail, "the layer's intermediates need %zu bytes, the library's own array holds %zu",
@@ -1042,7 +1062,7 @@ int attention_impl(const void *Q_dev, const void *Km_dev, const void *Vm_dev, in
                                           head_stride * qkv_bits / 8, token_stride * qkv_bits / 8, head_stride,
                                           token_stride, mask, s_q, s_k, s_v, s_p,
                                           static_cast<uint8_t *>(O_dev) + (int64_t)b * batch_stride * (out_f16 ? 2 : 4),
-                                          out_f16, workspace_dev, o, s);
+                                          out_f16, workspace_dev, split_panels, o, s);
         if (rc != MC_OK) return rc;
     }
     return MC_OK;
@@ -1068,7 +1088,7 @@ extern "C" size_t mc_attention_workspace_needed(int heads, int dk, const mc_mat 
     if (attention_is_fused(mask, dk, o)) return 0;
     // (the narrowest inputs the layer takes give the smallest rows: whether the scores stay on chip is decided
     // for 8-bit inputs here, which never asks for less than a 4-bit layer needs)
-    return attn_layout(heads, mask, p_bits, scores_kernel_waves(mask, heads, dk, 8, o) == 0).total;
+    return attn_layout(heads, mask, p_bits, scores_kernel_waves(mask, heads, dk, 8, o) == 0, pipeline_splits(mask, o) ? dk : 0).total;
 }
 
 extern "C" int mc_sparse_attention(const int8_t *Q_dev, const int8_t *Km_dev, const int8_t *Vm_dev, int heads, int L,

@@ -56,6 +56,10 @@ struct SpmmArgs {
     int n_units;               // items, or P
     int stages;                // chunks in flight per wave: 1 or 2 (2 needs B to span less than 4 GiB)
     int max_unit_chunks;       // chunks of the longest unit of work (panel or work item)
+    // optional: items of a split panel add their int32 results here instead of into C (which may then be float or
+    // half): cleared rows [batch][split panel][V][acc_ld], finished by launch_finish_split_rows
+    int32_t *acc;
+    int acc_ld, n_split;
 };
 
 // One launch of the SpMM that keeps K-blocks of B resident in LDS (see spmm_slab_kernels.hip).
@@ -163,6 +167,10 @@ hipError_t launch_repack_blocked(const int32_t *blk_src, const uint8_t *src, uin
                                  hipStream_t s);
 // clears the C rows (int32, n columns) of the listed panels
 hipError_t launch_zero_rows(int32_t *C, int64_t ldc, int n, int V, const int32_t *panels, int n_panels, hipStream_t s);
+hipError_t launch_zero_ints(int32_t *p, int64_t n, hipStream_t s); // n a multiple of 4, p 16-byte aligned
+// C rows of the split panels = scale * float(acc rows) (float_out 1: fp32, 2: fp16); acc as in SpmmArgs, n columns
+hipError_t launch_finish_split_rows(const int32_t *acc, int n, int n_split, int V, int batch, const int32_t *panels, void *C,
+                                    int64_t ldc, int64_t C_batch_stride, int float_out, float scale, hipStream_t s);
 // the gather of launch_spmm alone (same tile variant); sink: one int32 per workgroup (P * row tiles)
 hipError_t launch_gather_probe(const SpmmArgs &a, int bnb, int waves, int32_t *sink, hipStream_t s);
 // `workgroups` x 4 waves x `iters` x 8 MFMAs (16x16x64 i8); sink: workgroups * 256 int32

@@ -321,7 +321,11 @@ __global__ __launch_bounds__(64 * WK) void spmm_kernel(SpmmArgs a)
             s = (v4i){(s.y << 8) + s.x + fix, (s.w << 8) + s.z + fix, (s2.y << 8) + s2.x + fix, (s2.w << 8) + s2.z + fix};
         }
         const int64_t off = (int64_t)batch * a.C_batch_stride + (int64_t)(panel * a.V + row) * a.ldc + gcol;
-        if (a.float_out) {
+        if (split && a.acc) {
+            // a shared panel whose final values are rounded: the exact partial sums meet in int32 rows of their own
+            int32_t *c = a.acc + (((int64_t)batch * a.n_split + (split - 1)) * a.V + row) * a.acc_ld + gcol;
+            atomicAdd(c, s.x); atomicAdd(c + 1, s.y); atomicAdd(c + 2, s.z); atomicAdd(c + 3, s.w);
+        } else if (a.float_out) {
             const v4f f = {s.x * a.out_scale, s.y * a.out_scale, s.z * a.out_scale, s.w * a.out_scale};
             if (a.float_out == 2) __builtin_nontemporal_store(mcu::to_half4(f), reinterpret_cast<mcu::v4h *>(static_cast<_Float16 *>(a.C) + off));
             else __builtin_nontemporal_store(f, reinterpret_cast<v4f *>(static_cast<float *>(a.C) + off));
@@ -394,7 +398,46 @@ __global__ __launch_bounds__(256) void zero_rows_kernel(int32_t *C, int64_t ldc,
     }
 }
 
+__global__ __launch_bounds__(256) void zero_ints_kernel(int32_t *p, int64_t n4)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n4) reinterpret_cast<v4i *>(p)[i] = (v4i){0, 0, 0, 0};
+}
+
+__global__ __launch_bounds__(256) void finish_split_rows_kernel(const int32_t *acc, int n, int n_split, int V, const int32_t *panels,
+                                                                void *C, int64_t ldc, int64_t C_batch_stride, int float_out, float scale)
+{
+    const int sp = blockIdx.x, batch = blockIdx.y, panel = panels[sp];
+    const int per_row = n / 4;
+    const int32_t *src = acc + ((int64_t)batch * n_split + sp) * V * n;
+    for (int p = threadIdx.x; p < V * per_row; p += 256) {
+        const int row = p / per_row, col = (p % per_row) * 4;
+        const v4i s = *reinterpret_cast<const v4i *>(src + (int64_t)row * n + col);
+        const v4f f = {s.x * scale, s.y * scale, s.z * scale, s.w * scale};
+        const int64_t off = (int64_t)batch * C_batch_stride + (int64_t)(panel * V + row) * ldc + col;
+        if (float_out == 2) *reinterpret_cast<mcu::v4h *>(static_cast<_Float16 *>(C) + off) = mcu::to_half4(f);
+        else *reinterpret_cast<v4f *>(static_cast<float *>(C) + off) = f;
+    }
+}
+
 } // namespace
+
+hipError_t launch_zero_ints(int32_t *p, int64_t n, hipStream_t s)
+{
+    if (n <= 0) return hipSuccess;
+    const int64_t n4 = n / 4;
+    hipLaunchKernelGGL(zero_ints_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, s, p, n4);
+    return hipGetLastError();
+}
+
+hipError_t launch_finish_split_rows(const int32_t *acc, int n, int n_split, int V, int batch, const int32_t *panels, void *C,
+                                    int64_t ldc, int64_t C_batch_stride, int float_out, float scale, hipStream_t s)
+{
+    if (n_split == 0 || batch == 0 || n == 0) return hipSuccess;
+    hipLaunchKernelGGL(finish_split_rows_kernel, dim3((unsigned)n_split, (unsigned)batch), dim3(256), 0, s, acc, n, n_split, V, panels,
+                       C, ldc, C_batch_stride, float_out, scale);
+    return hipGetLastError();
+}
 
 hipError_t launch_zero_rows(int32_t *C, int64_t ldc, int n, int V, const int32_t *panels, int n_panels, hipStream_t s)
 {

@@ -266,6 +266,49 @@ def test_attention_ragged_rows():
     mask.close()
 
 
+@pytest.mark.parametrize("p_bits,out_dtype", [(8, "float32"), (16, "float32"), (8, "float16")])
+@pytest.mark.parametrize("dk", [64, 96])
+def test_attention_pipeline_shares_very_long_panels(dk, p_bits, out_dtype):
+    """A mask with a few panels many times longer than the rest: in the kernel pipeline the last SpMM cuts them into
+    work items whose exact int32 tiles meet in workspace rows before they are scaled and rounded, so the output is
+    the same, bit for bit, as with whole panels; and it matches the oracle."""
+    import torch
+    import oracle
+    from paper_2209_06979_amd import binding as mc
+    V, L, heads = 8, 2048, 2
+    counts = np.r_[[2048, 1500, 0, 1], np.full(L // V - 4, 30)]
+    rp, ci = wl.ragged_pattern(L, L, V, counts, 1400)
+    (q8, s_q), (k8, s_k), (v8, s_v) = (prep.quantize_inputs_int8(wl.normal_fp32((heads, L, dk), 1401 + i)) for i in range(3))
+    s_p = np.float32(1.0 / oracle.P_CODE_MAX[p_bits])
+    dt = getattr(torch, out_dtype)
+    mask = mc.SparseMatrix(L, L, V, rp, ci)
+    results = {}
+    for mode in (1, 6):
+        for split in (0, -1):
+            o = mc.Options(attention_mode=mode, spmm_splitting=split)
+            need = mc.attention_workspace_needed(heads, dk, mask, p_bits, o)
+            for ws_bytes in ((need, need - 256) if split == 0 else (need,)):   # too small for the shared rows: whole panels
+                ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+                out = torch.full((heads, L, dk), float("nan"), dtype=dt, device="cuda")
+                mc.sparse_attention(torch.from_numpy(q8).cuda(), torch.from_numpy(k8).cuda(), torch.from_numpy(v8).cuda(), mask,
+                                    s_q, s_k, s_v, s_p, out=out, workspace=ws, p_bits=p_bits, out_dtype=dt, options=o)
+                torch.cuda.synchronize()
+                results[(mode, split, ws_bytes == need)] = out.cpu().numpy()
+        assert (mc.attention_workspace_needed(heads, dk, mask, p_bits, mc.Options(attention_mode=mode, spmm_splitting=-1))
+                < mc.attention_workspace_needed(heads, dk, mask, p_bits, mc.Options(attention_mode=mode)))
+    ref = results[(1, -1, True)]
+    assert np.isfinite(ref).all()
+    for key, O in results.items():
+        assert np.array_equal(O, ref), key
+    want, _, probs, _ = oracle.attention(q8, k8, v8, rp, ci, V, s_q, s_k, s_v, s_p, p_bits=p_bits)
+    amb = _tie_ambiguous(probs, s_p).reshape(heads, -1, V)
+    tol = np.full((heads, L), 1e-3 if out_dtype == "float32" else 3e-3)
+    for p in range(L // V):
+        tol[:, p * V:(p + 1) * V] += amb[:, rp[p]:rp[p + 1], :].sum(axis=1) * float(s_p) * float(s_v) * 127
+    assert (np.abs(ref.astype(np.float64) - want) <= tol[:, :, None]).all()
+    mask.close()
+
+
 @pytest.mark.parametrize("prec,Kd,s,V", [("L8R8", 128, 0.9, 8), ("L8R8", 64, 0.7, 4), ("L4R4", 256, 0.7, 8),
                                           ("L8R8", 256, 0.95, 2), ("L4R4", 64, 0.95, 4)])
 def test_config3_more_points_full_size(prec, Kd, s, V):
