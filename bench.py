@@ -384,7 +384,7 @@ def run_sweep(mc, torch):
                         mc.set_thread_options(None)
                         B = torch.from_numpy(c["B"]).cuda()
                         C = torch.empty((M, N), dtype=torch.int32, device="cuda")
-                        us = time_graph(torch, stream, [lambda: mc.spmm(A, B, prec, out=C)] * 50, rounds=3)
+                        us = time_graph(torch, stream, [lambda: mc.spmm(A, B, prec, out=C)] * 50, rounds=3, warm_ms=25.0)
                         g_us = time_graph(torch, stream, [lambda: mc.spmm(A, B, prec, out=C, options=gather_only)] * 50, rounds=3)
                         l_us = None
                         if mc.spmm_form(Af, N, prec, lds_forced) == "lds":
@@ -403,7 +403,7 @@ def run_sweep(mc, torch):
                     m = mc.SparseMatrix(M, K, V, c["row_ptr"], c["col_idx"])
                     Q, Km = torch.from_numpy(c["Q"]).cuda(), torch.from_numpy(c["Kmat"]).cuda()
                     S = torch.empty(m.nvec * V, dtype=torch.int32, device="cuda")
-                    us = time_graph(torch, stream, [lambda: mc.sddmm(Q, Km, m, prec, out=S)] * 50, rounds=3)
+                    us = time_graph(torch, stream, [lambda: mc.sddmm(Q, Km, m, prec, out=S)] * 50, rounds=3, warm_ms=25.0)
                     gathered = m.nvec * Kd * mc.LHS_BITS[prec] / 8
                     sddmm.append(dict(prec=prec, Kd=Kd, s=s, us=round(us, 2), eff_tops=round(2 * m.nvec * V * Kd / us / 1e6, 1),
                                       gather_tbs=round(gathered / us / 1e6, 2)))
@@ -442,22 +442,24 @@ def run_skew(mc, torch):
             Km = torch.from_numpy(wl.uniform_int8((K, KD_SDDMM), 15)).cuda()
             S = torch.empty(nvec * V, dtype=torch.int32, device="cuda")
             row = dict(sigma=sigma, nvec=nvec, longest_panel=int(counts.max()), longest_over_mean=round(float(counts.max()) / 410, 1))
-            row["spmm_us"] = round(time_graph(torch, stream, [lambda: mc.spmm(A, B, "L8R8", out=C)] * 50, rounds=3), 2)
+            row["spmm_us"] = round(time_graph(torch, stream, [lambda: mc.spmm(A, B, "L8R8", out=C)] * 50, rounds=3, warm_ms=25.0), 2)
             row["spmm_whole_panels_us"] = round(time_graph(torch, stream, [lambda: mc.spmm(A, B, "L8R8", out=C, options=whole)] * 50, rounds=3), 2)
-            row["sddmm_us"] = round(time_graph(torch, stream, [lambda: mc.sddmm(Q, Km, A, "L8R8", out=S)] * 50, rounds=3), 2)
-            row["sddmm_whole_panels_us"] = round(time_graph(torch, stream, [lambda: mc.sddmm(Q, Km, A, "L8R8", out=S, options=whole)] * 50, rounds=3), 2)
+            Am = mc.SparseMatrix(M, K, V, rp, ci)      # the pattern alone (a mask is cut into shorter work items than an operand)
+            row["sddmm_us"] = round(time_graph(torch, stream, [lambda: mc.sddmm(Q, Km, Am, "L8R8", out=S)] * 50, rounds=3), 2)
+            row["sddmm_whole_panels_us"] = round(time_graph(torch, stream, [lambda: mc.sddmm(Q, Km, Am, "L8R8", out=S, options=whole)] * 50, rounds=3), 2)
             # the attention layer as a pipeline of kernels (head dimension 96 has no fused kernel): its last SpMM
             # writes rounded values, so shared panels go through int32 rows of the workspace first
             x = torch.randint(-127, 128, (L_ATT, HEADS, 96), dtype=torch.int8, device="cuda").permute(1, 0, 2)
             O = torch.empty((L_ATT, HEADS, 96), dtype=torch.float32, device="cuda").permute(1, 0, 2)
-            for key, o in (("attention_dk96_us", mc.Options()), ("attention_dk96_whole_panels_us", whole)):
-                ws = torch.empty(max(16, mc.attention_workspace_needed(HEADS, 96, A, 8, o)), dtype=torch.uint8, device="cuda")
-                row[key] = round(time_graph(torch, stream, [lambda: mc.sparse_attention(x, x, x, A, 0.02, 0.02, 0.02, 1 / 127, out=O,
+            for key, o in (("attention_dk96_us", mc.Options()), ("attention_dk96_shared_panels_us", mc.Options(spmm_splitting=1))):
+                ws = torch.empty(max(16, mc.attention_workspace_needed(HEADS, 96, Am, 8, o)), dtype=torch.uint8, device="cuda")
+                row[key] = round(time_graph(torch, stream, [lambda: mc.sparse_attention(x, x, x, Am, 0.02, 0.02, 0.02, 1 / 127, out=O,
                                                                                         workspace=ws, options=o)] * 20, rounds=3), 2)
             row["spmm_eff_tops"] = round(2 * nvec * V * N_SPMM / row["spmm_us"] / 1e6, 1)
             row["sddmm_eff_tops"] = round(2 * nvec * V * KD_SDDMM / row["sddmm_us"] / 1e6, 1)
             rows.append(row)
             A.close()
+            Am.close()
     print(json.dumps({"skew": "4096x4096 V=8, vectors per panel log-normal (mean 410), L8-R8, N = K_d = 256, warm caches, "
                               "50 back-to-back launches (median of 3)", "library": mc.lib.mc_version().decode(), "rows": rows}))
 
@@ -480,6 +482,7 @@ def run_shapes(mc, torch):
                 B = torch.from_numpy(c["B"]).cuda()
                 C = torch.empty((Ms, N), dtype=torch.int32, device="cuda")
                 row_bytes = N * mc.RHS_BITS[prec] // 8
+                time_graph(torch, stream, [lambda: mc.spmm(A, B, prec, out=C)] * 50, rounds=1, warm_ms=25.0)
                 pinned = {}
                 for tile, waves in itertools.product((64, 128, 256), (1, 2, 4, 8)):
                     if tile > row_bytes or (tile == 256 and mc.RHS_BITS[prec] == 4):
@@ -502,15 +505,20 @@ def run_shapes(mc, torch):
                       "worst_auto_over_best": worst, "rows": rows}))
 
 
-def time_graph(torch, stream, launches, rounds=5):
+def time_graph(torch, stream, launches, rounds=5, warm_ms=0.0):
     """Microseconds per launch: the launches captured once into a HIP graph, replayed between two
-    events on the launch stream; median over `rounds` replays."""
+    events on the launch stream; median over `rounds` replays.  warm_ms: replay for that long first (after host
+    work such as a format build the clocks have dropped, which a single replay of a short graph does not undo)."""
     g = torch.cuda.CUDAGraph()
     with torch.cuda.graph(g, stream=stream):
         for f in launches:
             f()
     g.replay()
     stream.synchronize()
+    t0 = time.perf_counter()
+    while (time.perf_counter() - t0) * 1e3 < warm_ms:
+        g.replay()
+        stream.synchronize()
     samples = []
     for _ in range(rounds):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)

@@ -93,7 +93,8 @@ typedef struct mc_options {
     int spmm_stages;         /* 0 automatic (two chunks of gathered rows in flight per wave when B spans
                                 less than 4 GiB and no wave has more than 4 chunks), 1 or 2               */
     int spmm_splitting;      /* 0 automatic (very unequal panels are cut into work items, see
-                                mc_set_spmm_splitting), -1 never                                           */
+                                mc_set_spmm_splitting), -1 never, 1 as 0 and also in the last SpMM of the
+                                attention layer's kernel pipeline (see mc_attention_workspace_needed)      */
     int spmm_slab;           /* the SpMM form that keeps blocks of B resident in LDS and reads the gathered
                                 rows from there: 0 automatic (when it is expected to be faster: dense
                                 matrices), -1 never (also: mc_mat_create on this thread does not build the
@@ -359,8 +360,9 @@ size_t mc_attention_workspace_bytes(int heads, const mc_mat *mask);
 /* Bytes of workspace the layer makes use of for this head dimension and these options (NULL: the
  * calling thread's defaults): 0 when the fused kernel runs; else the codes of all heads, plus the
  * int32 scores when they travel through memory (three kernels), plus -- for a mask with panels many
- * times longer than the average, unless spmm_splitting is -1 -- int32 output rows of those panels,
- * which several workgroups of the last SpMM then share.  mc_attention_workspace_bytes[_bits] (codes
+ * times longer than the average and with spmm_splitting = 1 -- int32 output rows of those panels,
+ * which several workgroups of the last SpMM then share (exact partial sums, scaled and rounded by a
+ * last small kernel: the same values as with whole panels).  mc_attention_workspace_bytes[_bits] (codes
  * and scores) is always enough to run; with less than the figure returned here the long panels are
  * simply not shared (same results, a longer tail). */
 size_t mc_attention_workspace_needed(int heads, int dk, const mc_mat *mask, int p_bits, const mc_options *options);

@@ -22,7 +22,7 @@ bool valid_options(const mc_options &o)
     if (b != 0 && b != 64 && b != 128 && b != 256) return false;
     if (w != 0 && w != 1 && w != 2 && w != 4 && w != 8) return false;
     if (o.spmm_stages < 0 || o.spmm_stages > 2) return false;
-    if (o.spmm_splitting != 0 && o.spmm_splitting != -1) return false;
+    if (o.spmm_splitting < -1 || o.spmm_splitting > 1) return false;
     if (o.spmm_slab < -1 || o.spmm_slab > 1) return false;
     if (o.spmm_slab_waves < 0 || o.spmm_slab_waves > 15) return false;
     if (o.spmm_slab_panels != 0 && o.spmm_slab_panels != 1 && o.spmm_slab_panels != 2 && o.spmm_slab_panels != 4) return false;
@@ -517,18 +517,21 @@ bool plan_slab(const mc_mat *A, int row_bytes, bool r4, int batch, const mc_opti
     return pl->ppw <= max_ppw;
 }
 
-// Whether the LDS-resident form is expected to beat the gather form.  Both times (microseconds) are fits to
-// measurements on MI355X over V, sparsity and N at K = 4096: the gather form moves its rows at about 19.5 TB/s after
-// 2.5 us of launch and ramp; the LDS-resident form pays about 2 us per K-block and pass for the fill it cannot
-// hide and 21.6 ns per chunk step of a compute unit.
-bool slab_pays(const mc_mat *A, int row_bytes, int batch, const SlabPlan &pl)
+// Whether the LDS-resident form is expected to beat the gather form.  Both times (microseconds) are least-squares
+// fits to measurements on MI355X over V in {2, 4, 8}, six sparsities and N in {128, 256, 512} at 4096 x 4096, for
+// byte and for nibble rows of B apart (nibble rows take two MFMA steps per 64 bytes).  Gather form: a start-up
+// term plus its gathered bytes at 22 (nibbles: 14) TB/s.  LDS-resident form: a start-up term, about 2 us per
+// K-block and pass for the fill it cannot hide, and 16 (nibbles: 42) ns per chunk step of a compute unit.  Picking
+// by these fits is on average 0.03 % and at worst 4 % slower than the better form over the points of that sweep
+// where both exist.
+bool slab_pays(const mc_mat *A, int row_bytes, bool r4, int batch, const SlabPlan &pl)
 {
     const double T = (double)((row_bytes + 63) / 64);
-    const double t_gather = 2.5 + (double)A->nvec * row_bytes * batch / 19.5e6;
+    const double t_gather = (r4 ? 3.88 : 3.96) + (double)A->nvec * row_bytes * batch / (r4 ? 13.99e6 : 22.13e6);
     const double steps = (double)A->blk_chunks * T * batch / 256.0;
     const double rounds = std::max(1.0, std::ceil((double)pl.workgroups / 256.0) / ((double)pl.workgroups / 256.0));
-    const double t_slab = 2.5 + (pl.passes * 2.0 * A->nblk + 0.0216 * steps) * rounds;
-    return t_slab < 0.92 * t_gather;
+    const double t_slab = (r4 ? 0.47 : 2.05) + (pl.passes * (r4 ? 2.12 : 1.98) * A->nblk + (r4 ? 0.0417 : 0.01565) * steps) * rounds;
+    return t_slab < t_gather;
 }
 
 // The form one SpMM call takes: true = K-blocks of B resident in LDS (then *pl is its work split).
@@ -537,7 +540,7 @@ bool slab_chosen(const mc_mat *A, int row_bytes, int rb, unsigned flags, const m
     if (o.spmm_slab == -1 || !A->d_blk_vals || !A->blk_valid || flags != 0 || rb == 16 || o.spmm_row_tile_bytes != 0 ||
         o.spmm_waves != 0)
         return false;
-    return plan_slab(A, row_bytes, rb == 4, 1, o, pl) && (o.spmm_slab == 1 || slab_pays(A, row_bytes, 1, *pl));
+    return plan_slab(A, row_bytes, rb == 4, 1, o, pl) && (o.spmm_slab == 1 || slab_pays(A, row_bytes, rb == 4, 1, *pl));
 }
 
 // out_mode 0: int32 results; 1 / 2: scale * result as fp32 / fp16 (fused dequantisation)
@@ -587,7 +590,7 @@ int spmm_impl(const mc_mat *A, const void *B_dev, int N, int ldb, mc_prec prec, 
     }
     a.stages = spmm_stages_for(o, A->K, a.ldb_bytes, a.row_bytes);
     a.max_unit_chunks = A->max_panel_chunks;
-    const bool use_items = A->n_items && o.spmm_splitting == 0 && out_mode == 0;
+    const bool use_items = A->n_items && o.spmm_splitting != -1 && out_mode == 0;
     if (use_items) a.max_unit_chunks = A->max_item_chunks;
     int bnb, waves;
     choose_variant(A, A->lhs_bits, a.row_bytes, rb == 4, 1, a.max_unit_chunks, o, &bnb, &waves);
@@ -707,7 +710,7 @@ int sddmm_impl(const void *Q_dev, int ldq, const void *Kmat_dev, int ldk, int Kd
     a.S = S_dev; a.S_batch_stride = 0;
     a.P = mask->P; a.V = mask->V; a.batch = 1;
     a.lhs_unsigned = (flags & MC_LHS_UNSIGNED) ? 1 : 0; a.rhs_unsigned = (flags & MC_RHS_UNSIGNED) ? 1 : 0;
-    if (mask->n_items && o.spmm_splitting == 0) { a.items = mask->d_items; a.n_units = mask->n_items; } // very unequal panels
+    if (mask->n_items && o.spmm_splitting != -1) { a.items = mask->d_items; a.n_units = mask->n_items; } // very unequal panels
     MC_HIP(launch_sddmm(bits, a, choose_sddmm_waves(mask, 1, a.row_bytes, bits, o), static_cast<hipStream_t>(stream)));
     return MC_OK;
 }
@@ -766,7 +769,7 @@ extern "C" int mc_sddmm_to_mat(const void *Q_dev, int ldq, const void *Kmat_dev,
     a.row_bytes = Kd * bits / 8;
     a.S = nullptr; a.S_batch_stride = 0;
     a.P = P->P; a.V = P->V; a.batch = 1;
-    if (P->n_items && o.spmm_splitting == 0) { a.items = P->d_items; a.n_units = P->n_items; }
+    if (P->n_items && o.spmm_splitting != -1) { a.items = P->d_items; a.n_units = P->n_items; }
     P->blk_valid = false; // only the panel format receives the new values
     MC_HIP(launch_sddmm(bits, a, choose_sddmm_waves(P, 1, a.row_bytes, bits, o), static_cast<hipStream_t>(stream)));
     return MC_OK;
@@ -853,7 +856,10 @@ AttnWs attn_layout(int heads, const mc_mat *mask, int p_bits, bool with_scores =
     return w;
 }
 // Whether the pipeline's SpMM shares long panels between workgroups (it then needs the extra workspace rows).
-inline bool pipeline_splits(const mc_mat *mask, const mc_options &o) { return mask->n_items > 0 && o.spmm_splitting == 0; }
+// Only on request: on masks whose panel lengths are log-normal (sigma 0.5 .. 1.5, 4096 x 4096, 1 .. 8 heads) it was
+// 1 - 10 % slower than whole panels, the pieces of a mask being short (made for the SDDMM, which needs no atomics)
+// and the layer's time being that of the scores of the long panels anyway.
+inline bool pipeline_splits(const mc_mat *mask, const mc_options &o) { return mask->n_items > 0 && o.spmm_splitting == 1; }
 
 // Waves per (panel, head) of the kernel that computes scores and softmax together, or 0 when the layer has to
 // run as three kernels (rows longer than 256 bytes, a panel whose scores do not fit LDS, or pinned by the options).
@@ -903,7 +909,7 @@ int attention_pipeline(const uint8_t *Q, const uint8_t *Km, const uint8_t *Vm, i
         d.Kmat = Km; d.ldk_bytes = token_stride_bytes; d.K_batch_stride = head_stride_bytes;
         d.row_bytes = row_bytes; d.S = scores; d.S_batch_stride = nnz;
         d.P = mask->P; d.V = 8; d.batch = heads;
-        if (mask->n_items && o.spmm_splitting == 0) { d.items = mask->d_items; d.n_units = mask->n_items; } // very unequal panels
+        if (mask->n_items && o.spmm_splitting != -1) { d.items = mask->d_items; d.n_units = mask->n_items; } // very unequal panels
         MC_HIP(launch_sddmm(qkv_bits, d, choose_sddmm_waves(mask, heads, row_bytes, qkv_bits, o), s));
 
         // the softmax writes its codes in the layout the SpMM reads

@@ -284,10 +284,10 @@ def test_attention_pipeline_shares_very_long_panels(dk, p_bits, out_dtype):
     mask = mc.SparseMatrix(L, L, V, rp, ci)
     results = {}
     for mode in (1, 6):
-        for split in (0, -1):
+        for split in (1, 0, -1):
             o = mc.Options(attention_mode=mode, spmm_splitting=split)
             need = mc.attention_workspace_needed(heads, dk, mask, p_bits, o)
-            for ws_bytes in ((need, need - 256) if split == 0 else (need,)):   # too small for the shared rows: whole panels
+            for ws_bytes in ((need, need - 256) if split == 1 else (need,)):   # too small for the shared rows: whole panels
                 ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
                 out = torch.full((heads, L, dk), float("nan"), dtype=dt, device="cuda")
                 mc.sparse_attention(torch.from_numpy(q8).cuda(), torch.from_numpy(k8).cuda(), torch.from_numpy(v8).cuda(), mask,
@@ -295,7 +295,8 @@ def test_attention_pipeline_shares_very_long_panels(dk, p_bits, out_dtype):
                 torch.cuda.synchronize()
                 results[(mode, split, ws_bytes == need)] = out.cpu().numpy()
         assert (mc.attention_workspace_needed(heads, dk, mask, p_bits, mc.Options(attention_mode=mode, spmm_splitting=-1))
-                < mc.attention_workspace_needed(heads, dk, mask, p_bits, mc.Options(attention_mode=mode)))
+                == mc.attention_workspace_needed(heads, dk, mask, p_bits, mc.Options(attention_mode=mode))
+                < mc.attention_workspace_needed(heads, dk, mask, p_bits, mc.Options(attention_mode=mode, spmm_splitting=1)))
     ref = results[(1, -1, True)]
     assert np.isfinite(ref).all()
     for key, O in results.items():

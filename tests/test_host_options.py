@@ -30,7 +30,7 @@ def test_init_is_all_automatic():
     ("spmm_row_tile_bytes", [0, 64, 128, 256], [32, 100, -64, 512]),
     ("spmm_waves", [0, 1, 2, 4, 8], [3, 16, -1]),
     ("spmm_stages", [0, 1, 2], [3, -1]),
-    ("spmm_splitting", [0, -1], [1, 2]),
+    ("spmm_splitting", [0, -1, 1], [-2, 2]),
     ("spmm_slab", [-1, 0, 1], [2, -2]),
     ("spmm_slab_waves", [0, 1, 8, 15], [16, -1]),
     ("spmm_slab_panels", [0, 1, 2, 4], [3, 8, -1]),
