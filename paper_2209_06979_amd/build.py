@@ -10,7 +10,7 @@ import sys
 PKG = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libmagicube.so")
-SOURCES = ["format_host.cpp", "api.hip", "spmm_kernels.hip", "spmm_slab_kernels.hip", "probe_kernels.hip", "sddmm_kernels.hip", "softmax_kernels.hip", "attention_kernels.hip", "attention_scores_kernels.hip",
+SOURCES = ["format_host.cpp", "api.hip", "spmm_kernels.hip", "spmm_slab_kernels.hip", "probe_kernels.hip", "sddmm_kernels.hip", "softmax_kernels.hip", "attention_kernels.hip", "attention_pad_kernels.hip", "attention_scores_kernels.hip",
            "quant_kernels.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -107,8 +107,13 @@ def check_resources(table) -> None:
     guarded = set()
     for src in SOURCES:
         with open(os.path.join(CSRC, src)) as f:
-            if "copy16_to_lds(" in f.read():
-                guarded.add(src)
+            text = f.read()
+        for inc in re.findall(r'#include "([^"]+)"', text):      # kernels that live in a header of this directory
+            if inc != "lds_async.h" and os.path.exists(os.path.join(CSRC, inc)):
+                with open(os.path.join(CSRC, inc)) as f:
+                    text += f.read()
+        if "copy16_to_lds(" in text:
+            guarded.add(src)
     bad = [k for k in table if k["source"] in guarded and
            (int(k.get("ScratchSize [bytes/lane]", 0)) or int(k.get("VGPRs Spill", 0)) or int(k.get("SGPRs Spill", 0)))]
     if bad:

@@ -949,9 +949,11 @@ int attention_pipeline(const uint8_t *Q, const uint8_t *Km, const uint8_t *Vm, i
 }
 
 // Whether the single fused kernel takes this layer (else the pipeline of separate kernels, which needs a workspace).
-bool attention_is_fused(const mc_mat *mask, int dk, const mc_options &o)
+// (Head dimensions up to 128 whose rows are whole 16-byte pieces; those below 64 or between 64 and 128 run in the
+// next larger tile with the missing pieces read as zeros.)
+bool attention_is_fused(const mc_mat *mask, int dk, int qkv_bits, const mc_options &o)
 {
-    return o.attention_mode != 1 && o.attention_mode != 6 && (dk == 64 || dk == 128) &&
+    return o.attention_mode != 1 && o.attention_mode != 6 && dk <= 128 && (dk * qkv_bits / 8) % 16 == 0 &&
            mask->max_panel_chunks * MC_CHUNK <= attention_fused_max_vectors();
 }
 
@@ -1006,8 +1008,10 @@ int attention_impl(const void *Q_dev, const void *Km_dev, const void *Vm_dev, in
     if (!on_device_of(mask)) return MC_EINVAL;
     hipStream_t s = static_cast<hipStream_t>(stream);
 
-    if (attention_is_fused(mask, dk, o)) {
+    if (attention_is_fused(mask, dk, qkv_bits, o)) {
+        const int tile = dk <= 64 ? 64 : 128;     // the kernel's head dimension
         AttnArgs f;
+        f.real_pieces = dk * qkv_bits / 8 / 16; f.out_cols = dk;
         f.panel_ptr = mask->d_panel_ptr; f.slot_idx = mask->d_slot_idx;
         f.Q = static_cast<const uint8_t *>(Q_dev); f.Km = static_cast<const uint8_t *>(Km_dev);
         f.Vm = static_cast<const uint8_t *>(Vm_dev); f.O = static_cast<float *>(O_dev); f.out_f16 = out_f16;
@@ -1022,7 +1026,7 @@ int attention_impl(const void *Q_dev, const void *Km_dev, const void *Vm_dev, in
         // gather 128 bytes per token (not for 16-bit codes with 4-bit inputs, whose output tile does not fit
         // that kernel's stages)
         const bool short_rows = dk == 64 || qkv_bits == 4;
-        const bool pairs = short_rows && head_stride == dk && heads % 2 == 0 && !(p_bits == 16 && qkv_bits == 4);
+        const bool pairs = dk == tile && short_rows && head_stride == dk && heads % 2 == 0 && !(p_bits == 16 && qkv_bits == 4);
         int hpg;
         if (o.attention_mode == 0) {
             // Halving the gather requests pays once the launch fills the chip (2048 (panel, head) units and
@@ -1038,7 +1042,8 @@ int attention_impl(const void *Q_dev, const void *Km_dev, const void *Vm_dev, in
             if (o.attention_mode == 4) wpp = 4;
             hpg = (o.attention_mode != 2 && pairs) ? 2 : 1;
         }
-        MC_HIP(launch_attention_fused(f, hpg, wpp, p_bits, qkv_bits, dk, s));
+        if (dk == tile) MC_HIP(launch_attention_fused(f, hpg, wpp, p_bits, qkv_bits, dk, s));
+        else MC_HIP(launch_attention_fused_padded(f, wpp, p_bits, qkv_bits, tile, s));
         return MC_OK;
     }
     // the kernel pipeline keeps its intermediates in a workspace (none are needed when nothing is stored)
@@ -1091,7 +1096,8 @@ extern "C" size_t mc_attention_workspace_needed(int heads, int dk, const mc_mat 
     if (!mask || heads <= 0 || (p_bits != 8 && p_bits != 16)) return 0;
     mc_options o;
     if (resolve_options(options, &o) != MC_OK) return 0;
-    if (attention_is_fused(mask, dk, o)) return 0;
+    // (8-bit inputs decide here; a 4-bit layer whose rows are not whole pieces then needs what is returned)
+    if (attention_is_fused(mask, dk, 8, o)) return 0;
     // (the narrowest inputs the layer takes give the smallest rows: whether the scores stay on chip is decided
     // for 8-bit inputs here, which never asks for less than a 4-bit layer needs)
     return attn_layout(heads, mask, p_bits, scores_kernel_waves(mask, heads, dk, 8, o) == 0, pipeline_splits(mask, o) ? dk : 0).total;

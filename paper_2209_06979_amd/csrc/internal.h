@@ -158,6 +158,9 @@ struct AttnArgs {
     float score_scale, inv_s_p, out_scale;
     int P, heads, batch;
     int out_f16;                             // 1: O holds fp16 (the fp32 result rounded to nearest even)
+    // head dimensions below the kernel's tile (launch_attention_fused_padded): 16-byte pieces a Q / Kmat / V row
+    // really has, and columns of O
+    int real_pieces, out_cols;
 };
 
 hipError_t launch_spmm(mc_prec prec, const SpmmArgs &a, int bnb, int waves, hipStream_t s);
@@ -189,4 +192,6 @@ hipError_t launch_repack(const RepackArgs &a, hipStream_t s);
 // bytes and an even head count, and is not available for 16-bit codes with 4-bit inputs
 hipError_t launch_attention_fused(const AttnArgs &a, int heads_per_group, int waves_per_panel, int p_bits, int qkv_bits,
                                   int dk, hipStream_t s);
+// the same kernel for head dimensions below its tile (64 or 128): one head per workgroup; a.real_pieces, a.out_cols set
+hipError_t launch_attention_fused_padded(const AttnArgs &a, int waves_per_panel, int p_bits, int qkv_bits, int tile, hipStream_t s);
 int attention_fused_max_vectors(); // longest panel (in vectors) the fused kernel accepts

@@ -198,7 +198,7 @@ def _attention_f16(heads, L, dk, sparsity, seed, p_bits=8, qkv_bits=8, token_maj
 def test_attention_fp16_output_small(token_major, mode):
     _attention_f16(2, 256, 64, 0.75, 6600, token_major=token_major, mode=mode)
     _attention_f16(2, 1024, 64, 0.6, 6601, token_major=token_major, mode=mode)     # 7 chunks, ragged tail
-    _attention_f16(3, 512, 32, 0.9, 6602, token_major=token_major, mode=mode)      # dk = 32: kernel pipeline
+    _attention_f16(3, 512, 32, 0.9, 6602, token_major=token_major, mode=mode)      # dk = 32
 
 
 @pytest.mark.parametrize("p_bits,qkv_bits", [(16, 8), (8, 4), (16, 4)])
@@ -208,6 +208,13 @@ def test_attention_fp16_output_variants(p_bits, qkv_bits):
     _attention_f16(2, 2048, 64, 0.6, 6612, p_bits, qkv_bits)                       # two waves per (panel, head)
     _attention_f16(2, 2048, 64, 0.6, 6613, p_bits, qkv_bits, token_major=True, mode=3)
     _attention_f16(2, 2048, 64, 0.3, 6614, p_bits, qkv_bits, token_major=True, mode=4)     # four waves per (panel, head)
+
+
+@pytest.mark.parametrize("dk", [16, 48, 96])
+def test_attention_fp16_output_head_dimensions_below_the_tile(dk):
+    _attention_f16(2, 512, dk, 0.8, 6640 + dk, token_major=True)
+    _attention_f16(1, 2048, dk, 0.6, 6650 + dk)                                    # two waves per (panel, head)
+    _attention_f16(2, 512, dk, 0.8, 6660 + dk, token_major=True, batch=2)
 
 
 @pytest.mark.parametrize("p_bits", [8, 16])

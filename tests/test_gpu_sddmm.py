@@ -158,7 +158,7 @@ def _attention_check(heads, L, dk, sparsity, seed, mode=0, token_major=False):
 @pytest.mark.parametrize("mode", [0, 1, 5])   # 5: two heads per workgroup on token-major tensors also in small launches
 def test_attention_small(mode, token_major):
     _attention_check(2, 256, 64, 0.75, 1200, mode, token_major)   # one chunk per panel
-    _attention_check(3, 512, 32, 0.9, 1201, mode, token_major)    # dk = 32: always the kernel pipeline
+    _attention_check(3, 512, 32, 0.9, 1201, mode, token_major)    # dk = 32: half of every row of the fused kernel's tile is padding
     _attention_check(2, 1024, 64, 0.6, 1202, mode, token_major)   # 410 vectors per panel: 7 chunks, ragged tail
     _attention_check(3, 1024, 64, 0.8, 1205, mode, token_major)   # odd head count: one head per workgroup
     _attention_check(2, 2048, 64, 0.75, 1203, mode, token_major)  # 512 vectors: the longest panel the fused kernel takes
@@ -179,6 +179,27 @@ def test_attention_pipeline_head_dimensions_and_long_panels(mode, token_major):
     _attention_check(1, 4096, 32, 0.0, 1266, mode, token_major)    # 4096 vectors: 131 KB of scores per panel in LDS, two waves
     _attention_check(1, 2048, 320, 0.8, 1267, mode, token_major)   # rows of 320 bytes: three kernels in either mode
     _attention_check(2, 512, 64, 0.95, 1268, mode, token_major)    # 26 vectors per panel: a single ragged chunk
+
+
+@pytest.mark.parametrize("token_major", [False, True])
+@pytest.mark.parametrize("mode", [0, 3, 4])   # automatic; two / four waves per (panel, head)
+def test_attention_fused_kernel_head_dimensions_below_its_tile(mode, token_major):
+    """Head dimensions 16 .. 112 run in the fused kernel's tile of 64 or 128 with the missing pieces of every row
+    read as zeros (no workspace needed)."""
+    from paper_2209_06979_amd import binding as mc
+    c = wl.attention_case(1, 256, 16, 8, 0.5, 1)
+    m = mc.SparseMatrix(256, 256, 8, c["row_ptr"], c["col_idx"])
+    for dk in (16, 32, 48, 80, 96, 112):
+        assert mc.attention_workspace_needed(2, dk, m, 8, mc.Options(attention_mode=mode)) == 0
+    m.close()
+    _attention_check(2, 256, 16, 0.5, 1270, mode, token_major)     # one piece of four
+    _attention_check(3, 512, 32, 0.9, 1271, mode, token_major)
+    _attention_check(2, 1024, 48, 0.6, 1272, mode, token_major)    # 7 chunks, ragged tail
+    _attention_check(2, 512, 80, 0.8, 1273, mode, token_major)     # five pieces of eight
+    _attention_check(3, 1024, 96, 0.6, 1274, mode, token_major)
+    _attention_check(1, 512, 112, 0.75, 1275, mode, token_major)
+    _attention_check(1, 2048, 32, 0.4, 1276, mode, token_major)    # 1229 vectors: four waves in every mode
+    _attention_check(2, 2048, 96, 0.6, 1277, mode, token_major)    # 819 vectors: at least two waves
 
 
 def test_attention_panels_beyond_on_chip_memory_fall_back_to_three_kernels():

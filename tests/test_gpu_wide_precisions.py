@@ -209,6 +209,15 @@ def _attention_variant_check(heads, L, dk, sparsity, seed, p_bits, qkv_bits, tok
     print(f"  max abs err {err.max():.3e}; clean rows {clean.mean():.3f} max err {err[clean].max():.3e}", flush=True)
 
 
+@pytest.mark.parametrize("p_bits,qkv_bits,dk", [(16, 8, 32), (16, 8, 96), (8, 4, 32), (8, 4, 96), (16, 4, 32), (16, 4, 96), (8, 4, 64)])
+@pytest.mark.parametrize("token_major", [False, True])
+def test_attention_variants_head_dimensions_below_the_tile(p_bits, qkv_bits, dk, token_major):
+    """16-bit codes and 4-bit inputs with rows shorter than the fused kernel's tile (4-bit inputs: head dimensions
+    that are multiples of 32)."""
+    _attention_variant_check(2, 512, dk, 0.8, 4300 + dk, p_bits, qkv_bits, token_major)
+    _attention_variant_check(1, 2048, dk, 0.6, 4310 + dk, p_bits, qkv_bits, token_major)   # 819 vectors: two waves
+
+
 @pytest.mark.parametrize("p_bits,qkv_bits", [(16, 8), (8, 4), (16, 4)])
 @pytest.mark.parametrize("token_major", [False, True])
 @pytest.mark.parametrize("mode", [0, 1, 5])                   # automatic / kernel pipeline / two heads per workgroup

@@ -40,13 +40,13 @@ def _both(mc, heads, L, dk, sparsity, seed, p_bits=8, qkv_bits=8, options=None, 
 
 
 def test_two_calls_second_smaller_equal_the_workspace_entry_point():
-    """dk = 32 always runs as the kernel pipeline, whose scores and codes live in the library's array.  Both entry
+    """dk = 160 always runs as the kernel pipeline, whose codes (and scores) live in the library's array.  Both entry
     points launch the same kernels on the same inputs, so the outputs must be identical bit for bit."""
     from paper_2209_06979_amd import binding as mc
-    print("no-alloc: 3 heads x 512 x 32, then 2 heads x 256 x 32", flush=True)
-    got, want, _, _ = _both(mc, 3, 512, 32, 0.8, 7001)
+    print("no-alloc: 3 heads x 512 x 160, then 2 heads x 256 x 160", flush=True)
+    got, want, _, _ = _both(mc, 3, 512, 160, 0.8, 7001)
     assert not np.isnan(got).any() and np.array_equal(got, want)
-    got, want, _, _ = _both(mc, 2, 256, 32, 0.75, 7002)       # smaller: the array still holds the first call's data
+    got, want, _, _ = _both(mc, 2, 256, 160, 0.75, 7002)       # smaller: the array still holds the first call's data
     assert not np.isnan(got).any() and np.array_equal(got, want)
 
 
@@ -54,8 +54,8 @@ def test_against_the_oracle_after_a_larger_call():
     """The second, smaller call also agrees with the CPU oracle (so stale contents of the shared array are not read)."""
     import oracle
     from paper_2209_06979_amd import binding as mc
-    _both(mc, 4, 1024, 32, 0.8, 7003)
-    got, want, c, (q, k, v, s_q, s_k, s_v, s_p) = _both(mc, 2, 256, 32, 0.75, 7004)
+    _both(mc, 4, 1024, 160, 0.8, 7003)
+    got, want, c, (q, k, v, s_q, s_k, s_v, s_p) = _both(mc, 2, 256, 160, 0.75, 7004)
     ref, _, probs, _ = oracle.attention(q.cpu().numpy(), k.cpu().numpy(), v.cpu().numpy(), c["row_ptr"], c["col_idx"], 8,
                                         s_q, s_k, s_v, s_p)
     x = probs / np.float64(s_p)
@@ -86,17 +86,17 @@ def test_fused_path_needs_no_scratch_and_sizes_beyond_the_array_are_refused():
     got, want, _, _ = _both(mc, 2, 512, 64, 0.8, 7030)           # automatic: the fused kernel, nothing staged
     assert np.array_equal(got, want)
     # 8 heads x L = 4096 at 90 % with 16-bit codes: 29 MB of codes alone, the array holds 16 MiB
-    c, (q, k, v), (s_q, s_k, s_v) = _inputs(8, 4096, 32, 0.9, 7031, 8)
+    c, (q, k, v), (s_q, s_k, s_v) = _inputs(8, 4096, 160, 0.9, 7031, 8)
     mask = mc.SparseMatrix(4096, 4096, 8, c["row_ptr"], c["col_idx"])
-    assert mc.attention_workspace_needed(8, 32, mask, 16) > mc.STATIC_SCRATCH_BYTES
-    out = torch.full((8, 4096, 32), 5.0, dtype=torch.float32, device="cuda")
+    assert mc.attention_workspace_needed(8, 160, mask, 16) > mc.STATIC_SCRATCH_BYTES
+    out = torch.full((8, 4096, 160), 5.0, dtype=torch.float32, device="cuda")
     with pytest.raises(mc.MagicubeError) as e:
         mc.sparse_attention_static(q, k, v, mask, s_q, s_k, s_v, np.float32(1 / 32639), out, p_bits=16)
     assert e.value.status == mc.MC_ENOMEM
     torch.cuda.synchronize()
     assert bool((out == 5.0).all())                               # refused before any launch
     # the same layer with 8-bit codes fits since its scores never leave the chip (14.7 MB of codes)
-    assert mc.attention_workspace_needed(8, 32, mask, 8) <= mc.STATIC_SCRATCH_BYTES
+    assert mc.attention_workspace_needed(8, 160, mask, 8) <= mc.STATIC_SCRATCH_BYTES
     want = mc.sparse_attention(q, k, v, mask, s_q, s_k, s_v, np.float32(1 / 127))
     mc.sparse_attention_static(q, k, v, mask, s_q, s_k, s_v, np.float32(1 / 127), out)
     torch.cuda.synchronize()
