@@ -447,14 +447,15 @@ def run_skew(mc, torch):
             Am = mc.SparseMatrix(M, K, V, rp, ci)      # the pattern alone (a mask is cut into shorter work items than an operand)
             row["sddmm_us"] = round(time_graph(torch, stream, [lambda: mc.sddmm(Q, Km, Am, "L8R8", out=S)] * 50, rounds=3), 2)
             row["sddmm_whole_panels_us"] = round(time_graph(torch, stream, [lambda: mc.sddmm(Q, Km, Am, "L8R8", out=S, options=whole)] * 50, rounds=3), 2)
-            # the attention layer as a pipeline of kernels (head dimension 96 has no fused kernel): its last SpMM
-            # writes rounded values, so shared panels go through int32 rows of the workspace first
-            x = torch.randint(-127, 128, (L_ATT, HEADS, 96), dtype=torch.int8, device="cuda").permute(1, 0, 2)
-            O = torch.empty((L_ATT, HEADS, 96), dtype=torch.float32, device="cuda").permute(1, 0, 2)
-            for key, o in (("attention_dk96_us", mc.Options()), ("attention_dk96_shared_panels_us", mc.Options(spmm_splitting=1))):
-                ws = torch.empty(max(16, mc.attention_workspace_needed(HEADS, 96, Am, 8, o)), dtype=torch.uint8, device="cuda")
-                row[key] = round(time_graph(torch, stream, [lambda: mc.sparse_attention(x, x, x, Am, 0.02, 0.02, 0.02, 1 / 127, out=O,
-                                                                                        workspace=ws, options=o)] * 20, rounds=3), 2)
+            # the attention layer, 8 heads (timing only: one random tensor serves as Q, K and V): the fused kernel runs
+            # the panels of such a mask class by class (1, 2, 4, 8 waves per panel); the kernel pipeline for comparison
+            for dk in (64, 128):
+                x = torch.randint(-127, 128, (L_ATT, HEADS, dk), dtype=torch.int8, device="cuda").permute(1, 0, 2)
+                O = torch.empty((L_ATT, HEADS, dk), dtype=torch.float32, device="cuda").permute(1, 0, 2)
+                for key, o in ((f"attention_dk{dk}_us", mc.Options()), (f"attention_dk{dk}_kernel_pipeline_us", mc.Options(attention_mode=1))):
+                    ws = torch.empty(max(16, mc.attention_workspace_needed(HEADS, dk, Am, 8, o)), dtype=torch.uint8, device="cuda")
+                    row[key] = round(time_graph(torch, stream, [lambda: mc.sparse_attention(x, x, x, Am, 0.02, 0.02, 0.02, 1 / 127, out=O,
+                                                                                            workspace=ws, options=o)] * 20, rounds=3), 2)
             row["spmm_eff_tops"] = round(2 * nvec * V * N_SPMM / row["spmm_us"] / 1e6, 1)
             row["sddmm_eff_tops"] = round(2 * nvec * V * KD_SDDMM / row["sddmm_us"] / 1e6, 1)
             rows.append(row)

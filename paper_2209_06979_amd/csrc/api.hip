@@ -105,6 +105,7 @@ void free_device(mc_mat *A)
     if (A->d_blk_rows) (void)hipFree(A->d_blk_rows);
     if (A->d_blk_vals) (void)hipFree(A->d_blk_vals);
     if (A->d_blk_src) (void)hipFree(A->d_blk_src);
+    if (A->d_class_panels) (void)hipFree(A->d_class_panels);
 }
 
 // Waves per panel for SDDMM: enough to put about 2048 waves on the chip (4096 of the light ones
@@ -307,6 +308,30 @@ extern "C" int mc_mat_create(int M, int K, int V, int lhs_bits, const int32_t *r
     A->max_item_chunks = 0;
     A->nblk = 0; A->blk_chunks = 0; A->blk_valid = false;
     A->d_blk_ptr = nullptr; A->d_blk_rows = nullptr; A->d_blk_vals = nullptr; A->d_blk_src = nullptr;
+    A->d_class_panels = nullptr;
+    // Length classes of the panels (V = 8: the attention kernel gives a panel 1, 2, 4 or 8 waves)
+    std::vector<int32_t> class_panels;
+    for (int b = 0; b <= 4; ++b) A->class_start[b] = 0;
+    if (V == 8 && lay.P > 0) {
+        auto class_of = [&](int p) {
+            const int c = (row_ptr[p + 1] - row_ptr[p] + MC_CHUNK - 1) / MC_CHUNK;
+            return c <= 8 ? 0 : (c <= 16 ? 1 : (c <= 32 ? 2 : 3));
+        };
+        int count[4] = {0, 0, 0, 0};
+        for (int p = 0; p < lay.P; ++p) ++count[class_of(p)];
+        if ((count[0] > 0) + (count[1] > 0) + (count[2] > 0) + (count[3] > 0) > 1) {
+            try {
+                class_panels.resize((size_t)lay.P);
+            } catch (const std::bad_alloc &) {
+                delete A;
+                return MC_ENOMEM;
+            }
+            int next[4];
+            for (int b = 0, at = 0; b < 4; ++b) { A->class_start[b] = next[b] = at; at += count[b]; }
+            A->class_start[4] = lay.P;
+            for (int p = 0; p < lay.P; ++p) class_panels[(size_t)next[class_of(p)]++] = p;
+        }
+    }
     // Work items: only when the longest panel is far above the average; a panel is then cut into
     // pieces of at most `cap` chunks (cap = three times the average, at least 8: smaller pieces
     // balance better but cost the SpMM more in atomics than they gain; measured).
@@ -421,6 +446,10 @@ extern "C" int mc_mat_create(int M, int K, int V, int lhs_bits, const int32_t *r
         MC_TRY(hipMemcpyAsync(A->d_blk_src, blk_src.data(), sizeof(int32_t) * blk_src.size(), hipMemcpyHostToDevice, s));
         MC_TRY(hipMemcpyAsync(A->d_blk_vals, blk_vals.data(), blk_vals.size(), hipMemcpyHostToDevice, s));
         A->blk_valid = true;
+    }
+    if (!class_panels.empty()) {
+        MC_TRY(hipMalloc(&A->d_class_panels, sizeof(int32_t) * class_panels.size()));
+        MC_TRY(hipMemcpyAsync(A->d_class_panels, class_panels.data(), sizeof(int32_t) * class_panels.size(), hipMemcpyHostToDevice, s));
     }
     MC_TRY(hipStreamSynchronize(s)); // host staging buffers die at return
 #undef MC_TRY
@@ -1019,31 +1048,46 @@ int attention_impl(const void *Q_dev, const void *Km_dev, const void *Vm_dev, in
         f.in_head_stride = head_stride * qkv_bits / 8; f.in_token_stride = token_stride * qkv_bits / 8;
         f.in_batch_stride = batch_stride * qkv_bits / 8;
         f.score_scale = s_q * s_k / std::sqrt((float)dk); f.inv_s_p = 1.f / s_p; f.out_scale = s_p * s_v;
-        f.P = mask->P; f.heads = heads; f.batch = batch;
-        // a wave keeps at most 8 chunks of scores in registers: longer panels are shared by 2 or 4 waves
-        int wpp = (mask->max_panel_chunks > 16) ? 4 : (mask->max_panel_chunks > 8 ? 2 : 1);
+        f.heads = heads; f.batch = batch;
         // neighbouring heads contiguous inside a token, rows of at most 64 bytes: two heads per workgroup can
         // gather 128 bytes per token (not for 16-bit codes with 4-bit inputs, whose output tile does not fit
         // that kernel's stages)
         const bool short_rows = dk == 64 || qkv_bits == 4;
         const bool pairs = dk == tile && short_rows && head_stride == dk && heads % 2 == 0 && !(p_bits == 16 && qkv_bits == 4);
-        int hpg;
-        if (o.attention_mode == 0) {
-            // Halving the gather requests pays once the launch fills the chip (2048 (panel, head) units and
-            // more: 13.3 against 15.6 us for 4096 of them; 5.0 against 4.7 us for 128).  Smaller launches get
-            // more waves per unit instead, until about 2048 waves are in flight and while every wave still
-            // has a chunk (256 units of 7 chunks: 5.9 us with one wave each, 4.5 us with four).
-            const int64_t units = (int64_t)mask->P * heads * batch;
-            const double avg = mask->P ? (double)(mask->nslots / MC_CHUNK) / mask->P : 0.0;
-            hpg = (pairs && units >= 2048) ? 2 : 1;
-            if (hpg == 1) while (wpp < 4 && units * wpp * 2 <= 2048 && wpp * 2 <= avg) wpp *= 2;
+        const double avg = mask->P ? (double)(mask->nslots / MC_CHUNK) / mask->P : 0.0;
+        // One launch for the panels in `list` (null: all), none of which has more than max_chunks chunks.
+        auto launch = [&](const int32_t *list, int n_panels, int max_chunks) -> hipError_t {
+            f.panel_list = list; f.P = n_panels;
+            // a wave keeps at most 8 chunks of scores in registers: longer panels are shared by 2, 4 or 8 waves
+            int wpp = max_chunks > 32 ? 8 : (max_chunks > 16 ? 4 : (max_chunks > 8 ? 2 : 1));
+            int hpg;
+            if (o.attention_mode == 0) {
+                // Halving the gather requests pays once the launch fills the chip (2048 (panel, head) units and
+                // more: 13.3 against 15.6 us for 4096 of them; 5.0 against 4.7 us for 128).  Smaller launches get
+                // more waves per unit instead, until about 2048 waves are in flight and while every wave still
+                // has a chunk (256 units of 7 chunks: 5.9 us with one wave each, 4.5 us with four).
+                const int64_t units = (int64_t)n_panels * heads * batch;
+                hpg = (pairs && units >= 2048 && wpp < 8) ? 2 : 1;
+                if (hpg == 1) while (wpp < 4 && units * wpp * 2 <= 2048 && wpp * 2 <= avg) wpp *= 2;
+            } else {
+                if (o.attention_mode == 3 && wpp < 2) wpp = 2;
+                if (o.attention_mode == 4 && wpp < 4) wpp = 4;
+                hpg = (o.attention_mode != 2 && pairs && wpp < 8) ? 2 : 1;
+            }
+            if (dk == tile) return launch_attention_fused(f, hpg, wpp, p_bits, qkv_bits, dk, s);
+            return launch_attention_fused_padded(f, wpp, p_bits, qkv_bits, tile, s);
+        };
+        // Panels of very different lengths (the longest at least twice the average and more than one wave's
+        // worth), automatic mode: one launch per length class, so that short panels are not given the many waves
+        // the longest one needs.  Otherwise one launch sized by the longest panel.
+        if (o.attention_mode == 0 && mask->d_class_panels && mask->max_panel_chunks > 8 && mask->max_panel_chunks >= 2.0 * avg) {
+            for (int b = 0; b < 4; ++b) {
+                const int n = mask->class_start[b + 1] - mask->class_start[b];
+                if (n > 0) MC_HIP(launch(mask->d_class_panels + mask->class_start[b], n, b == 3 ? mask->max_panel_chunks : (8 << b)));
+            }
         } else {
-            if (o.attention_mode == 3 && wpp < 2) wpp = 2;
-            if (o.attention_mode == 4) wpp = 4;
-            hpg = (o.attention_mode != 2 && pairs) ? 2 : 1;
+            MC_HIP(launch(nullptr, mask->P, mask->max_panel_chunks));
         }
-        if (dk == tile) MC_HIP(launch_attention_fused(f, hpg, wpp, p_bits, qkv_bits, dk, s));
-        else MC_HIP(launch_attention_fused_padded(f, wpp, p_bits, qkv_bits, tile, s));
         return MC_OK;
     }
     // the kernel pipeline keeps its intermediates in a workspace (none are needed when nothing is stored)

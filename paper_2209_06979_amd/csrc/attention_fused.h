@@ -92,7 +92,7 @@ __device__ __forceinline__ float row16_sum(float v)
 // number, see the copy layout below); the Q registers of those pieces are zero as well.  Zero columns add
 // nothing to a score and give zero output columns, which are not stored.  One head per workgroup only.
 template <int MAXCH, int HPW, int PB, int QB, int KS, int DK, bool PAD = false>
-__global__ __launch_bounds__(64 * HPW * KS, (((HPW == 1 && PB == 8 && KS == 1 && DK == 64) || (HPW == 2 && DK == 64 && QB == 8)) ? 4 : 3))
+__global__ __launch_bounds__(64 * HPW * KS, (((HPW == 1 && PB == 8 && KS == 1 && DK == 64) || (HPW == 2 && DK == 64 && QB == 8)) ? 4 : (KS == 8 ? 2 : 3)))
 void attention_fused_kernel(AttnArgs a)
 {
     static_assert(!PAD || HPW == 1, "shorter rows: one head per workgroup");
@@ -136,7 +136,8 @@ void attention_fused_kernel(AttnArgs a)
     // head group, an XCD only ever sees the head groups congruent to its number, so its L2 has
     // to hold the Kmat and V rows of those heads only.
     const int groups = a.heads / HPW;
-    const int hgrp = blockIdx.x % groups, panel = blockIdx.x / groups;
+    const int hgrp = blockIdx.x % groups;
+    const int panel = a.panel_list ? a.panel_list[blockIdx.x / groups] : (int)(blockIdx.x / groups);
     const int head = hgrp * HPW + w;
     const int s0 = a.panel_ptr[2 * panel], n = a.panel_ptr[2 * panel + 1] - s0;
     const int nch = (n + MC_CHUNK - 1) / MC_CHUNK;

@@ -1,10 +1,11 @@
 // Launchers of the fused attention kernel for head dimensions 64 and 128 (rows that fill the kernel's tile).
 #include "attention_fused.h"
 
-int attention_fused_max_vectors() { return 4 * 8 * 64; }
+int attention_fused_max_vectors() { return 8 * 8 * 64; }
 
 template <int PB, int QB, int DK> hipError_t launch_pq(const AttnArgs &a, int heads_per_group, int waves_per_panel, hipStream_t s)
 {
+    if (heads_per_group == 2 && waves_per_panel == 8) return hipErrorInvalidValue;
     if (heads_per_group == 2) {
         // (16-bit codes with 4-bit Q/K/V: the two-plane output tile does not fit the stage; rows of 128
         // bytes: one head per workgroup)
@@ -15,6 +16,8 @@ template <int PB, int QB, int DK> hipError_t launch_pq(const AttnArgs &a, int he
             else if (waves_per_panel == 2) hipLaunchKernelGGL((attention_fused_kernel<8, 2, PB, QB, 2, DK>), grid, dim3(256), 0, s, a);
             else hipLaunchKernelGGL((attention_fused_kernel<8, 2, PB, QB, 1, DK>), grid, dim3(128), 0, s, a);
         }
+    } else if (waves_per_panel == 8) {
+        hipLaunchKernelGGL((attention_fused_kernel<8, 1, PB, QB, 8, DK>), dim3((unsigned)a.P * (unsigned)a.heads, (unsigned)a.batch), dim3(512), 0, s, a);
     } else if (waves_per_panel == 4) {
         hipLaunchKernelGGL((attention_fused_kernel<8, 1, PB, QB, 4, DK>), dim3((unsigned)a.P * (unsigned)a.heads, (unsigned)a.batch), dim3(256), 0, s, a);
     } else if (waves_per_panel == 2) {
@@ -25,8 +28,8 @@ template <int PB, int QB, int DK> hipError_t launch_pq(const AttnArgs &a, int he
     return hipGetLastError();
 }
 
-// waves_per_panel: 1, 2 or 4 waves share the chunks of one (panel, head); a wave holds at most 8 chunks
-// of scores in registers, so a panel may have up to 512 * waves_per_panel vectors.
+// waves_per_panel: 1, 2, 4 or 8 waves share the chunks of one (panel, head) (8: one head per workgroup only); a wave
+// holds at most 8 chunks of scores in registers, so a panel may have up to 512 * waves_per_panel vectors.
 // dk: 64 or 128
 hipError_t launch_attention_fused(const AttnArgs &a, int heads_per_group, int waves_per_panel, int p_bits, int qkv_bits,
                                   int dk, hipStream_t s)

@@ -7,7 +7,8 @@ namespace {
 template <int PB, int QB, int DK> hipError_t launch_padded(const AttnArgs &a, int waves_per_panel, hipStream_t s)
 {
     const dim3 grid((unsigned)a.P * (unsigned)a.heads, (unsigned)a.batch);
-    if (waves_per_panel == 4) hipLaunchKernelGGL((attention_fused_kernel<8, 1, PB, QB, 4, DK, true>), grid, dim3(256), 0, s, a);
+    if (waves_per_panel == 8) hipLaunchKernelGGL((attention_fused_kernel<8, 1, PB, QB, 8, DK, true>), grid, dim3(512), 0, s, a);
+    else if (waves_per_panel == 4) hipLaunchKernelGGL((attention_fused_kernel<8, 1, PB, QB, 4, DK, true>), grid, dim3(256), 0, s, a);
     else if (waves_per_panel == 2) hipLaunchKernelGGL((attention_fused_kernel<8, 1, PB, QB, 2, DK, true>), grid, dim3(128), 0, s, a);
     else hipLaunchKernelGGL((attention_fused_kernel<8, 1, PB, QB, 1, DK, true>), grid, dim3(64), 0, s, a);
     return hipGetLastError();

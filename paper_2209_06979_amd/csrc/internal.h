@@ -31,6 +31,11 @@ struct mc_mat {
     uint8_t *d_blk_vals;       // blk_chunks * chunk bytes
     int32_t *d_blk_src;        // blk_chunks * 64: interchange vector of each slot, -1 for padding
     bool blk_valid;            // false once the values were replaced in the panel format only
+    // Panels sorted by length class for kernels that give a panel 1, 2, 4 or 8 waves (V = 8 only; null when every
+    // panel falls into one class): class b holds the panels of at most 8 << b chunks that class b - 1 does not
+    // hold; class 3 also takes what is longer still.
+    int32_t *d_class_panels;   // P panel numbers, class after class
+    int class_start[5];        // first entry of each class in d_class_panels; [4] = P
 };
 
 // One SpMM launch (optionally a batch of problems sharing the sparsity pattern).
@@ -156,7 +161,8 @@ struct AttnArgs {
     int64_t in_head_stride, in_token_stride; // bytes of Q, Km, Vm
     int64_t batch_stride, in_batch_stride;   // between batch items: elements of O, bytes of Q, Km, Vm
     float score_scale, inv_s_p, out_scale;
-    int P, heads, batch;
+    int P, heads, batch;                     // P: panels of this launch
+    const int32_t *panel_list;               // their numbers (null: 0 .. P-1)
     int out_f16;                             // 1: O holds fp16 (the fp32 result rounded to nearest even)
     // head dimensions below the kernel's tile (launch_attention_fused_padded): 16-byte pieces a Q / Kmat / V row
     // really has, and columns of O

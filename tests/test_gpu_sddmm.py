@@ -116,12 +116,17 @@ def _layout(t, token_major):
     return x.permute(1, 0, 2).contiguous().permute(1, 0, 2) if token_major else x
 
 
-def _attention_check(heads, L, dk, sparsity, seed, mode=0, token_major=False):
+def _attention_check(heads, L, dk, sparsity, seed, mode=0, token_major=False, counts=None):
+    """counts: vectors per panel of a mask with panels of unequal length (sparsity is then ignored)."""
     import torch
     import oracle
     from paper_2209_06979_amd import binding as mc
     V = 8
-    c = wl.attention_case(heads, L, dk, V, sparsity, seed)
+    if counts is None:
+        c = wl.attention_case(heads, L, dk, V, sparsity, seed)
+    else:
+        rp, ci = wl.ragged_pattern(L, L, V, counts, seed)
+        c = dict(row_ptr=rp, col_idx=ci, **{n: wl.normal_fp32((heads, L, dk), seed + 1 + i) for i, n in enumerate("qkv")})
     q8, s_q = prep.quantize_inputs_int8(c["q"]); k8, s_k = prep.quantize_inputs_int8(c["k"])
     v8, s_v = prep.quantize_inputs_int8(c["v"])
     s_p = np.float32(1.0 / 127.0)
@@ -149,7 +154,7 @@ def _attention_check(heads, L, dk, sparsity, seed, mode=0, token_major=False):
     err = np.abs(O - want)
     assert (err <= tol).all(), f"max err {err.max()} (ambiguous entries: {int(amb.sum())})"
     clean = n_amb_rows == 0
-    assert clean.mean() > 0.9
+    assert clean.mean() > (0.9 if counts is None else 0.5)      # (rows of thousands of entries hold more near-ties)
     print(f"  max abs err {err.max():.3e}; clean rows max err {err[clean].max():.3e}; ambiguous {int(amb.sum())}",
           flush=True)
 
@@ -200,6 +205,35 @@ def test_attention_fused_kernel_head_dimensions_below_its_tile(mode, token_major
     _attention_check(1, 512, 112, 0.75, 1275, mode, token_major)
     _attention_check(1, 2048, 32, 0.4, 1276, mode, token_major)    # 1229 vectors: four waves in every mode
     _attention_check(2, 2048, 96, 0.6, 1277, mode, token_major)    # 819 vectors: at least two waves
+
+
+def _lognormal_counts(P, mean, sigma, cap, seed):
+    rng = np.random.default_rng(seed)
+    c = rng.lognormal(0.0, sigma, P)
+    return np.clip(np.rint(c / c.mean() * mean), 0, cap).astype(np.int64)
+
+
+@pytest.mark.parametrize("token_major", [False, True])
+@pytest.mark.parametrize("dk", [64, 96, 128])
+def test_attention_panels_of_very_different_lengths_run_class_by_class(dk, token_major):
+    """Masks whose panels span all four length classes (up to 8, 16, 32 and 64 chunks): one launch of the fused
+    kernel per class, with 1, 2, 4 and 8 waves per (panel, head)."""
+    L = 4096
+    counts = _lognormal_counts(L // 8, 300, 1.0, L, 1280)
+    counts[:6] = [4096, 0, 2049, 2048, 513, 1]
+    assert (counts > 2048).sum() >= 2 and ((counts > 1024) & (counts <= 2048)).any() and ((counts > 512) & (counts <= 1024)).any()
+    _attention_check(2, L, dk, None, 1281 + dk, 0, token_major, counts=counts)
+    # two classes only, the long one with a single panel
+    counts = np.full(L // 8, 100)
+    counts[77] = 3000
+    _attention_check(3, L, dk, None, 1290 + dk, 0, token_major, counts=counts)
+
+
+@pytest.mark.parametrize("token_major", [False, True])
+def test_attention_eight_waves_per_panel(token_major):
+    _attention_check(1, 4096, 64, 0.45, 1295, 0, token_major)      # 2253 vectors in every panel: 36 chunks, eight waves
+    _attention_check(2, 4096, 32, 0.0, 1296, 0, token_major)       # full panels of 4096 vectors, rows of half a tile
+    _attention_check(1, 4096, 128, 0.3, 1297, 4, token_major)      # mode 4 asks for four waves: eight where needed
 
 
 def test_attention_panels_beyond_on_chip_memory_fall_back_to_three_kernels():
