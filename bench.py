@@ -129,6 +129,11 @@ def main():
     ap.add_argument("--shapes", action="store_true",
                     help="instead of the step: matrices with few panels or short panels; the automatic kernel variant "
                          "against every pinned tile / wave variant")
+    ap.add_argument("--table", action="store_true",
+                    help="with --sweep / --skew / --shapes: print a plain-text table instead of the JSON object")
+    ap.add_argument("--point", default="",
+                    help="instead of the step: one SpMM configuration 'prec:V:sparsity:N:form' (form: gather, lds or auto) at "
+                         "4096 x 4096, launched --steps times one by one (for counter and trace collection), e.g. L8R8:2:0.5:512:lds")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 64 MiB device copy, the known-size kernel that scales FETCH_SIZE / WRITE_SIZE")
     args = ap.parse_args()
@@ -145,14 +150,12 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 
-    if args.sweep:
-        run_sweep(mc, torch)
+    if args.sweep or args.skew or args.shapes:
+        result = run_sweep(mc, torch) if args.sweep else (run_skew(mc, torch) if args.skew else run_shapes(mc, torch))
+        print(as_table(result) if args.table else json.dumps(result))
         return
-    if args.skew:
-        run_skew(mc, torch)
-        return
-    if args.shapes:
-        run_shapes(mc, torch)
+    if args.point:
+        print(json.dumps(run_point(mc, torch, args.point, args.steps, args.warmup, args.calib_copy)))
         return
 
     prob = build_problem()
@@ -343,6 +346,7 @@ def main():
         "step": {"ms": round(ms_per_step, 4), "aggregate_tops": round(aggregate, 2), "ops": int(total_ops)},
         "sddmm_l8r8_tops": (per_kernel.get("sddmm_L8R8") or {}).get("eff_tops"),
         "headline_spmm_l8r8": dict(per_kernel.get("spmm_L8R8") or {}, **((extras or {}).get("headline") or {})),
+        "headline_at_16x_rows": (extras or {}).get("headline_at_16x_rows"),
         "mfma_i8_peak": (extras or {}).get("mfma_i8_peak"),
         "launch_floor_us": (extras or {}).get("launch_floor_us"),
         "cold_cache_us": (extras or {}).get("cold_us"),
@@ -408,8 +412,50 @@ def run_sweep(mc, torch):
                     sddmm.append(dict(prec=prec, Kd=Kd, s=s, us=round(us, 2), eff_tops=round(2 * m.nvec * V * Kd / us / 1e6, 1),
                                       gather_tbs=round(gathered / us / 1e6, 2)))
                     m.close()
-    print(json.dumps({"sweep": "4096x4096, warm caches, 50 back-to-back launches per point (median of 3)",
-                      "library": mc.lib.mc_version().decode(), "spmm": spmm, "sddmm": sddmm}))
+    return {"sweep": "4096x4096, warm caches, 50 back-to-back launches per point (median of 3)",
+            "library": mc.lib.mc_version().decode(), "spmm": spmm, "sddmm": sddmm}
+
+
+def as_table(result):
+    """The result of --sweep / --skew / --shapes as aligned text columns (one table per list of rows)."""
+    lines = []
+    for key, val in result.items():
+        if not (isinstance(val, list) and val and isinstance(val[0], dict)):
+            lines.append(f"{key}: {val}")
+            continue
+        cols = [c for c in val[0] if not isinstance(val[0][c], dict)]
+        width = {c: max(len(c), *(len(str(r.get(c))) for r in val)) for c in cols}
+        lines += ["", f"[{key}]", "  ".join(c.rjust(width[c]) for c in cols)]
+        lines += ["  ".join(str(r.get(c)).rjust(width[c]) for c in cols) for r in val]
+    return "\n".join(lines)
+
+
+def run_point(mc, torch, spec, steps, warmup, calib_copy):
+    """One SpMM configuration launched eagerly, for a profiler to look at."""
+    from paper_2209_06979_amd import workloads as wl
+    prec, Vv, s, N, form = spec.split(":")
+    Vv, s, N = int(Vv), float(s), int(N)
+    o = {"gather": mc.Options(spmm_slab=-1), "lds": mc.Options(spmm_slab=1), "auto": None}[form]
+    c = wl.spmm_case(M, K, N, Vv, s, prec, wl.seed_for(2, 1))
+    if form == "lds":
+        mc.set_thread_options(o)
+    A = mc.SparseMatrix(M, K, Vv, c["row_ptr"], c["col_idx"], c["values"], mc.LHS_BITS[prec])
+    mc.set_thread_options(None)
+    B = torch.from_numpy(c["B"]).cuda()
+    C = torch.empty((M, N), dtype=torch.int32, device="cuda")
+    if calib_copy:
+        src = torch.empty(64 * 1024 * 1024, dtype=torch.uint8, device="cuda")
+        torch.empty_like(src).copy_(src)
+    for _ in range(warmup):
+        mc.spmm(A, B, prec, out=C, options=o)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        mc.spmm(A, B, prec, out=C, options=o)
+    torch.cuda.synchronize()
+    return dict(point=spec, form_run=mc.spmm_form(A, N, prec, o), launches=steps,
+                us_per_launch_eager=round((time.perf_counter() - t0) / steps * 1e6, 2), nvec=A.nvec,
+                gathered_bytes=int(A.nvec * N * mc.RHS_BITS[prec] // 8), library=mc.lib.mc_version().decode())
 
 
 def lognormal_counts(P, mean, sigma, Kcols, rng):
@@ -461,8 +507,9 @@ def run_skew(mc, torch):
             rows.append(row)
             A.close()
             Am.close()
-    print(json.dumps({"skew": "4096x4096 V=8, vectors per panel log-normal (mean 410), L8-R8, N = K_d = 256, warm caches, "
-                              "50 back-to-back launches (median of 3)", "library": mc.lib.mc_version().decode(), "rows": rows}))
+    return {"skew": "4096x4096 V=8, vectors per panel log-normal (mean 410), L8-R8, N = K_d = 256, attention with 8 heads, "
+                    "warm caches, 50 (attention: 20) back-to-back launches (median of 3)",
+            "library": mc.lib.mc_version().decode(), "rows": rows}
 
 
 def run_shapes(mc, torch):
@@ -501,9 +548,9 @@ def run_shapes(mc, torch):
                 A.close()
     worst = max(r["auto_over_best"] for r in rows)
     within5 = sum(r["auto_over_best"] <= 1.05 for r in rows)
-    print(json.dumps({"shapes": "SpMM, V=8, warm caches, 50 back-to-back launches (median of 3); pinned = tile bytes x waves",
-                      "library": mc.lib.mc_version().decode(), "points": len(rows), "within_5_percent_of_best": within5,
-                      "worst_auto_over_best": worst, "rows": rows}))
+    return {"shapes": "SpMM, V=8, warm caches, 50 back-to-back launches (median of 3); pinned = tile bytes x waves",
+            "library": mc.lib.mc_version().decode(), "points": len(rows), "within_5_percent_of_best": within5,
+            "worst_auto_over_best": worst, "rows": rows}
 
 
 def time_graph(torch, stream, launches, rounds=5, warm_ms=0.0):
@@ -618,6 +665,19 @@ def measure_extras(mc, torch, prob, stream, reps, up):
         peak[rb] = Ag.nvec * rb / best / 1e6   # TB/s
         Ag.close()
     out["gather_peak_tbs"] = {"rows_64B": round(peak[64], 2), "rows_128B": round(peak[128], 2)}
+    # The headline SpMM with 16 times the rows (65,536 x 4096, same sparsity, V and N): a launch of many rounds of
+    # workgroups, where start-up, the chain of dependent first loads and the tail no longer count.
+    cb = wl.spmm_case(16 * M, K, N_SPMM, V, SPARSITY, "L8R8", wl.seed_for(2, 950))
+    Ab = mc.SparseMatrix(16 * M, K, V, cb["row_ptr"], cb["col_idx"], cb["values"], 8)
+    Bb, Cb = up(cb["B"]), torch.empty((16 * M, N_SPMM), dtype=torch.int32, device="cuda")
+    usb = time_graph(torch, stream, [lambda: mc.spmm(Ab, Bb, "L8R8", out=Cb)] * 10)
+    algb = Ab.nvec * V + 4 * Ab.nvec + 8 * (16 * M // V) + K * N_SPMM + 4 * 16 * M * N_SPMM
+    out["headline_at_16x_rows"] = dict(us=round(usb, 2), eff_tops=round(2 * Ab.nvec * V * N_SPMM / usb / 1e6, 1),
+                                       alg_gbs=round(algb / usb / 1e3, 1), hbm_frac=round(algb / usb / 1e3 / HBM_PEAK_GBS, 4),
+                                       gather_tbs=round(Ab.nvec * N_SPMM / usb / 1e6, 2),
+                                       frac_of_gather_peak=round(Ab.nvec * N_SPMM / usb / 1e6 / peak[128], 3))
+    Ab.close()
+    del Bb, Cb
     out["headline"]["frac_of_gather_peak"] = round(nvec * N_SPMM / peak[128] / 1e6 / warm, 3)
 
     # The matrix unit alone: 1024 workgroups x 4 waves x 2000 x 8 MFMAs (16x16x64 int8, 32768 operations each) on
@@ -625,8 +685,19 @@ def measure_extras(mc, torch, prob, stream, reps, up):
     wg, iters = 1024, 2000
     sink = mc.probe_mfma(wg, iters)
     us = min(time_graph(torch, stream, [lambda: mc.probe_mfma(wg, iters, sink=sink)] * 3) for _ in range(3))
+    # one wave per SIMD (256 workgroups of 4 waves): the first wave's own count of shader-clock cycles and of ticks
+    # of the constant 100 MHz clock over its loop tell cycles per MFMA and the clock under this load apart
+    sink1 = mc.probe_mfma(256, iters)
+    us1 = min(time_graph(torch, stream, [lambda: mc.probe_mfma(256, iters, sink=sink1)] * 3) for _ in range(3))
+    cyc, ticks = (int(v) for v in sink1[:2].cpu())
     out["mfma_i8_peak"] = dict(measured_tops=round(wg * 4 * iters * 8 * 32768 / us / 1e6, 1), published_tops=I8_MFMA_PEAK_TOPS,
-                               us=round(us, 1), instructions=wg * 4 * iters * 8)
+                               us=round(us, 1), instructions=wg * 4 * iters * 8,
+                               one_wave_per_simd=dict(tops=round(256 * 4 * iters * 8 * 32768 / us1 / 1e6, 1),
+                                                      shader_cycles_per_mfma=round(cyc / (iters * 8), 2),
+                                                      shader_clock_ghz=round(cyc / max(ticks, 1) * 0.1, 3)))
+    # four waves per SIMD keep the matrix unit busy: cycles it spends per instruction at the clock just measured
+    out["mfma_i8_peak"]["shader_cycles_per_mfma_of_a_busy_simd"] = round(
+        out["mfma_i8_peak"]["one_wave_per_simd"]["shader_clock_ghz"] * 1e3 * us / (wg * 4 * iters * 8 / 1024), 2)
     # What one kernel launch costs inside a graph whatever it does: one workgroup, one MFMA round.
     s1 = mc.probe_mfma(1, 1)
     out["launch_floor_us"] = round(time_graph(torch, stream, [lambda: mc.probe_mfma(1, 1, sink=s1)] * reps), 2)

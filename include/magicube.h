@@ -261,7 +261,9 @@ int mc_probe_gather(const mc_mat *A, const void *B_dev, int N, int ldb, mc_prec 
  * alone.  `workgroups` workgroups of four waves each issue iters * 8 independent 16x16x64 int8 MFMAs on
  * registers, i.e. workgroups * 4 * iters * 8 * 32768 operations without any memory traffic; timing it gives
  * the int8 rate this device sustains in practice, to set beside the published peak.
- *   sink_dev   workgroups * 256 int32, receives the (meaningless) sums. */
+ *   sink_dev   workgroups * 256 int32, receives the (meaningless) sums, except that the first wave reports
+ *              its own loop in the first two: shader-clock cycles, and ticks of the constant 100 MHz clock
+ *              (so cycles per MFMA and the clock frequency under this load can be told apart). */
 int mc_probe_mfma(int workgroups, int iters, int32_t *sink_dev, void *stream);
 
 /* ------------------------------------------------------------------------------------

@@ -36,7 +36,7 @@ def bench_name(kernel: str):
 
 
 def short(kernel: str) -> str:
-    m = re.search(r"(\w+_kernel<[^>]*>)", kernel)
+    m = re.search(r"(\w+_kernel<[^>]*>)", kernel) or re.search(r"(\w+)\(", kernel)
     return m.group(1) if m else kernel[-48:]
 
 
@@ -78,7 +78,9 @@ def main(argv):
         avg = {c: sum(v) / len(v) for c, v in per[k].items()}
         n = max(len(v) for v in per[k].values())
         print(f"  {short(k)}  (n={n})")
-        print("      " + "  ".join(f"{c}={avg[c]:.0f}" for c in counters if c in avg))
+        have = [f"{c}={avg[c]:.0f}" for c in counters if c in avg]
+        for i in range(0, len(have), 4):
+            print("      " + "  ".join(have[i:i + 4]))
     if fs and wsf:
         print()
         print("HBM-side bytes per launch (counter x 1024 x scale factor):")

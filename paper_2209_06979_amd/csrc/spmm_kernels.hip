@@ -78,6 +78,19 @@ template <int BNB, int WK, int LB, int RB, bool U = false, int NS = 1> struct Sp
     static constexpr int OTILE = OROWS * TST * 4;        // bytes of one wave's partial tile
     static constexpr int PERWAVE = (NS * STAGE > OTILE) ? NS * STAGE : OTILE;
     static constexpr int LDS = WK * PERWAVE;
+    // Which LDS row (within the RPI rows a load instruction writes) holds slot group r (slots r*NI .. r*NI+NI-1), and
+    // back.  A transposing read's lane groups g and g + 1 (32 lanes, 256 bytes of banks) ask for slot groups 2g + h and
+    // 2g + 2 + h (NI 8) or 4g + .. and 4g + 4 + .. (NI 4); in slot-group order those rows lie 256 bytes apart, i.e. in
+    // the same banks, and every read took two conflict cycles.  Putting the bit g & 1 into address bit 7 instead
+    // spreads them over all banks.
+    static constexpr int row_of_group(int r)
+    {
+        return NI == 8 ? (((r & 1) << 2) | (r >> 1)) : (NI == 4 ? ((r & 9) | ((r & 2) << 1) | ((r & 4) >> 1)) : r);
+    }
+    static constexpr int group_of_row(int row)
+    {
+        return NI == 8 ? (((row & 3) << 1) | (row >> 2)) : (NI == 4 ? ((row & 9) | ((row & 2) << 1) | ((row & 4) >> 1)) : row);
+    }
 };
 
 template <int BNB, int WK, int LB, int RB, bool U = false, int NS = 1>
@@ -119,13 +132,13 @@ __global__ __launch_bounds__(64 * WK) void spmm_kernel(SpmmArgs a)
     for (int t = 0; t < NACC; ++t) acc[t] = (v4i){0, 0, 0, 0};
 
     // Load instruction i of a chunk: lane (rg, seg) copies segment seg ^ (i & SWZ) of the
-    // row in slot rg*NI + i to LDS byte i*1024 + lane*16, i.e. LDS row i*RPI + rg.  The NI
+    // row in slot group_of_row(rg)*NI + i to LDS byte i*1024 + lane*16, i.e. LDS row i*RPI + rg.  The NI
     // column indices a lane needs are consecutive slots: NI/4 128-bit index loads.
     // A segment beyond the row end is replaced by segment 0 (its columns are never stored),
     // so that every chunk issues exactly the same number of memory instructions.
     auto load_idx = [&](int c, v4i (&dst)[NI / 4]) {
 #pragma unroll
-        for (int t = 0; t < NI / 4; ++t) dst[t] = *reinterpret_cast<const v4i *>(idx + c * MC_CHUNK + rg * NI + 4 * t);
+        for (int t = 0; t < NI / 4; ++t) dst[t] = *reinterpret_cast<const v4i *>(idx + c * MC_CHUNK + Cfg::group_of_row(rg) * NI + 4 * t);
     };
     int segoff[NI];
 #pragma unroll
@@ -142,7 +155,7 @@ __global__ __launch_bounds__(64 * WK) void spmm_kernel(SpmmArgs a)
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
         const int s = g * 16 + 8 * h + ii;
-        const int i = s % NI, r = s / NI;
+        const int i = s % NI, r = Cfg::row_of_group(s / NI);
         rd_base[h] = i * 1024 + r * BNB + ((i & Cfg::SWZ) * 16) + 8 * (src & 1);
     }
     // R16: lanes that own an even byte column (low bytes) flip the top bit of every byte
