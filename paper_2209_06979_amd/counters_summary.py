@@ -1,7 +1,9 @@
 """Turns the counter files of `rocprofv3 --pmc ... -- python3 bench.py --eager ... --calib-copy` runs into the
 short text table kept with the profiles.
 
-    python -m paper_2209_06979_amd.counters_summary <dir with one sub-directory per counter pass>  > summary.txt
+    python -m paper_2209_06979_amd.counters_summary <dir with one sub-directory per counter pass> [name,name,...]  > summary.txt
+
+(the optional second argument keeps only the kernels whose name contains one of the given pieces)
 
 Every `*_counter_collection.csv` below the directory is read; counters are averaged over the dispatches of a
 kernel.  FETCH_SIZE and WRITE_SIZE (KiB per dispatch) are scaled by what the same counter reads for the plain
@@ -60,11 +62,14 @@ def read(directory: str):
 
 
 def main(argv):
-    if len(argv) != 2:
+    if len(argv) not in (2, 3):
         print(__doc__, file=sys.stderr)
         return 2
     from . import binding as mc
     per, copy = read(argv[1])
+    if len(argv) == 3:          # keep only kernels whose name contains one of these comma-separated pieces
+        keep = argv[2].split(",")
+        per = {k: v for k, v in per.items() if any(piece in k for piece in keep)}
     fs = COPY_BYTES / 1024.0 / copy["FETCH_SIZE"] if copy.get("FETCH_SIZE") else None
     wsf = COPY_BYTES / 1024.0 / copy["WRITE_SIZE"] if copy.get("WRITE_SIZE") else None
     print(f"library: {mc.lib.mc_version().decode()}")

@@ -143,7 +143,8 @@ __global__ __launch_bounds__(64 * WK) void spmm_kernel(SpmmArgs a)
     int segoff[NI];
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
-        const int lseg = seg ^ (i & Cfg::SWZ);
+        // (rows of 256 bytes: the row's parity picks the 128-byte half as well, for the same reason as row_of_group)
+        const int lseg = seg ^ (i & Cfg::SWZ) ^ ((NI == 16) ? ((rg & 1) << 3) : 0);
         segoff[i] = (nb0 + lseg * 16 < a.row_bytes) ? lseg * 16 : 0;
     }
     const int nmy = (nch > w) ? (nch - w + WK - 1) / WK : 0; // chunks of this wave: w, w+WK, ...
@@ -156,7 +157,7 @@ __global__ __launch_bounds__(64 * WK) void spmm_kernel(SpmmArgs a)
     for (int h = 0; h < 2; ++h) {
         const int s = g * 16 + 8 * h + ii;
         const int i = s % NI, r = Cfg::row_of_group(s / NI);
-        rd_base[h] = i * 1024 + r * BNB + ((i & Cfg::SWZ) * 16) + 8 * (src & 1);
+        rd_base[h] = i * 1024 + r * BNB + (((i & Cfg::SWZ) ^ ((NI == 16) ? ((r & 1) << 3) : 0)) * 16) + 8 * (src & 1);
     }
     // R16: lanes that own an even byte column (low bytes) flip the top bit of every byte
     const int lowflip = (R16 && !(j & 1)) ? (int)0x80808080 : 0;
