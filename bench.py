@@ -775,14 +775,16 @@ def measure_extras(mc, torch, prob, stream, reps, up):
         us = time_graph(torch, stream, [lambda: mc.sparse_attention(q128, q128, q128, amask, s128, s128, s128, att["s_p"],
                                                                     out=O128, workspace=wsm, options=o)] * reps)
         wide[name] = dict(us=round(us, 2), eff_tops=round(HEADS * 2 * (2 * amask.nvec * V * 128) / us / 1e6, 1))
-    # a head dimension the fused kernel does not cover (96): the general path is what runs
-    x96, s96 = quantize_on_gpu(mc, torch, wl.normal_fp32((HEADS, L_ATT, 96), wl.seed_for(5, 10)))
-    q96 = tmaj(x96)
-    O96 = torch.empty((L_ATT, HEADS, 96), dtype=torch.float32, device="cuda").permute(1, 0, 2)
-    wsm = torch.empty(max(16, mc.attention_workspace_needed(HEADS, 96, amask, 8)), dtype=torch.uint8, device="cuda")
-    us = time_graph(torch, stream, [lambda: mc.sparse_attention(q96, q96, q96, amask, s96, s96, s96, att["s_p"],
-                                                                out=O96, workspace=wsm)] * reps)
-    wide["attention_8b8b_dk96"] = dict(us=round(us, 2), eff_tops=round(HEADS * 2 * (2 * amask.nvec * V * 96) / us / 1e6, 1))
+    # head dimensions below the fused kernel's tile of 64 or 128 (rows with fewer 16-byte pieces than the tile), and one
+    # above every tile (160: the kernel pipeline is what runs)
+    for dkx in (32, 96, 160):
+        xx, sx = quantize_on_gpu(mc, torch, wl.normal_fp32((HEADS, L_ATT, dkx), wl.seed_for(5, 10 + dkx)))
+        qx = tmaj(xx)
+        Ox = torch.empty((L_ATT, HEADS, dkx), dtype=torch.float32, device="cuda").permute(1, 0, 2)
+        wsm = torch.empty(max(16, mc.attention_workspace_needed(HEADS, dkx, amask, 8)), dtype=torch.uint8, device="cuda")
+        us = time_graph(torch, stream, [lambda: mc.sparse_attention(qx, qx, qx, amask, sx, sx, sx, att["s_p"],
+                                                                    out=Ox, workspace=wsm)] * reps)
+        wide[f"attention_8b8b_dk{dkx}"] = dict(us=round(us, 2), eff_tops=round(HEADS * 2 * (2 * amask.nvec * V * dkx) / us / 1e6, 1))
     amask.close()
     cc = prob["spmm_L8R8"]
     A = mc.SparseMatrix(M, K, V, cc["row_ptr"], cc["col_idx"], cc["values"], 8)
