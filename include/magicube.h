@@ -108,6 +108,10 @@ typedef struct mc_options {
     int softmax_variant;     /* 0 automatic, 1 a workgroup per panel also for short panels, 2 always the
                                 any-length kernel                                                          */
     int attention_mode;      /* 0 automatic, 1..6 as described at mc_set_attention_mode                    */
+    int spmm_merge;          /* the SpMM on the operand's merged copy (see mc_merge_host): 0 automatic (when
+                                the copy exists and is expected to be faster), -1 never (also: mc_mat_create on
+                                this thread does not build the copy), 1 whenever the copy exists (and
+                                mc_mat_create on this thread builds it whatever the shape)                  */
 } mc_options;
 /* Sets every field to automatic. */
 void mc_options_init(mc_options *o);
@@ -182,6 +186,37 @@ int mc_pack_blocked_host(int M, int K, int V, int lhs_bits, const int32_t *row_p
                          const void *values, int32_t *blk_ptr, uint16_t *blk_rows, void *blk_vals, int32_t *blk_src);
 
 /* ------------------------------------------------------------------------------------
+ * Merged panels: a second copy of an SpMM operand with vectors of V * group rows.
+ *
+ * The MFMA's row operand has 16 rows, a panel of the format fills V of them, and every panel
+ * fetches the rows of the dense operand its own vectors name (Section 4.2).  `group`
+ * consecutive panels can share both: merged into one panel of V * group rows (8, or 16 for 4-
+ * and 8-bit values) whose vectors sit at the union of the panels' columns, with zeros where a
+ * panel holds no vector -- explicit zeros are legal inside stored vectors, so the product is
+ * unchanged.  A row of the dense operand is then fetched once per group instead of once per
+ * panel that names it (random patterns at 50 % sparsity, V = 2, group 8: a quarter of the
+ * fetches), padding to whole chunks shrinks, and the matrix unit does useful work in every row.
+ *
+ * mc_merged_query: panels and vectors of the merged operand.  group must be 2, 4 or 8 with
+ * V * group == 8 or (lhs_bits 4 / 8 only) 16; the last merged panel may cover fewer panels.
+ * mc_merge_host writes the merged operand as interchange arrays:
+ *   m_row_ptr  P_merged + 1,  m_col_idx  nvec_merged (ascending per merged panel)
+ *   m_values   nvec_merged * V * group elements of the operand's width (NULL: pattern only);
+ *              rows g*V .. g*V+V-1 of a merged vector belong to panel p0 + g of its group
+ *   m_src      nvec_merged * group int32: interchange vector that fills those rows, -1 = zeros
+ * Same validation and error codes as mc_pack_host.  Pure host code.
+ * ---------------------------------------------------------------------------------- */
+typedef struct {
+    int32_t group;       /* panels per merged panel                                   */
+    int32_t P;           /* merged panels = ceil(P / group)                           */
+    int64_t nvec;        /* vectors of the merged operand                             */
+} mc_merged_layout;
+int mc_merged_query(int M, int K, int V, int lhs_bits, const int32_t *row_ptr, const int32_t *col_idx, int group,
+                    mc_merged_layout *out);
+int mc_merge_host(int M, int K, int V, int lhs_bits, const int32_t *row_ptr, const int32_t *col_idx, const void *values,
+                  int group, int32_t *m_row_ptr, int32_t *m_col_idx, void *m_values, int32_t *m_src);
+
+/* ------------------------------------------------------------------------------------
  * Device-resident sparse operand.
  * ---------------------------------------------------------------------------------- */
 /* Builds the device format from HOST interchange arrays and uploads it on `stream`
@@ -200,6 +235,9 @@ int mc_mat_set_values_device(mc_mat *A, const void *values_dev, void *stream);
 void mc_mat_destroy(mc_mat *A);
 /* Shape queries; return MC_EINVAL on a null handle. */
 int mc_mat_info(const mc_mat *A, int *M, int *K, int *V, int *lhs_bits, int64_t *nvec, int64_t *nslots);
+/* The operand's merged copy (see mc_merge_host), which mc_mat_create builds for operands with values and
+ * V < 16 rows to share: *group = panels per merged panel (0: no such copy), *nvec = its vectors. */
+int mc_mat_merged_info(const mc_mat *A, int *group, int64_t *nvec);
 
 /* ------------------------------------------------------------------------------------
  * SpMM (Section 4.2): C = A * B, exact int32.
@@ -233,7 +271,8 @@ int mc_spmm_flags(const mc_mat *A, const void *B_dev, int N, int ldb, mc_prec pr
 int mc_spmm_ex(const mc_mat *A, const void *B_dev, int N, int ldb, mc_prec prec, unsigned flags,
                const mc_options *options, int32_t *C_dev, int ldc, void *stream);
 /* Which form mc_spmm_ex would run for this operand, width and options (host only, launches nothing):
- * 0 = rows of B gathered per stored vector, 1 = K-blocks of B resident in LDS.  Negative: an error code. */
+ * bit 0: 0 = rows of B gathered per stored vector, 1 = K-blocks of B resident in LDS; bit 1 (value 2): on the
+ * operand's merged copy (see mc_merge_host).  Negative: an error code. */
 int mc_spmm_form(const mc_mat *A, int N, mc_prec prec, const mc_options *options);
 
 /* SpMM with fused dequantisation (Section 5.3: the integer product is turned into real values

@@ -39,10 +39,15 @@ class BlockedLayout(ctypes.Structure):
 KBLOCK = 1024
 
 
+class MergedLayout(ctypes.Structure):
+    _fields_ = [("group", c_int32), ("P", c_int32), ("nvec", c_int64)]
+
+
 class Options(ctypes.Structure):
     """mc_options: kernel-variant choices of one call; all zero = automatic."""
     _fields_ = [("spmm_row_tile_bytes", c_int), ("spmm_waves", c_int), ("spmm_stages", c_int), ("spmm_splitting", c_int),
-                ("spmm_slab", c_int), ("spmm_slab_waves", c_int), ("spmm_slab_panels", c_int), ("sddmm_waves", c_int), ("softmax_variant", c_int), ("attention_mode", c_int)]
+                ("spmm_slab", c_int), ("spmm_slab_waves", c_int), ("spmm_slab_panels", c_int), ("sddmm_waves", c_int), ("softmax_variant", c_int), ("attention_mode", c_int),
+                ("spmm_merge", c_int)]
 
 
 class MagicubeError(RuntimeError):
@@ -103,6 +108,9 @@ def _load() -> ctypes.CDLL:
                                    c_void_p, c_void_p]
     L.mc_sparse_softmax_to_mat.argtypes = [c_void_p, c_void_p, c_float, c_float, c_void_p]
     L.mc_spmm_form.argtypes = [c_void_p, c_int, c_int, POINTER(Options)]
+    L.mc_mat_merged_info.argtypes = [c_void_p, POINTER(c_int), POINTER(c_int64)]
+    L.mc_merged_query.argtypes = [c_int, c_int, c_int, c_int, i32p, i32p, c_int, POINTER(MergedLayout)]
+    L.mc_merge_host.argtypes = [c_int, c_int, c_int, c_int, i32p, i32p, c_void_p, c_int, i32p, i32p, c_void_p, i32p]
     L.mc_probe_mfma.argtypes = [c_int, c_int, c_void_p, c_void_p]
     L.mc_sddmm_to_mat.argtypes = [c_void_p, c_int, c_void_p, c_int, c_int, c_int, c_float, c_void_p, c_void_p]
     L.mc_absmax.argtypes = [c_void_p, c_int64, c_void_p, c_void_p]
@@ -133,7 +141,8 @@ def _load() -> ctypes.CDLL:
                  "mc_absmax", "mc_quantize", "mc_sparse_attention_out", "mc_spmm_dequant", "mc_sddmm_dequant", "mc_sparse_softmax_to_mat",
                  "mc_set_spmm_variant", "mc_set_attention_mode", "mc_set_sddmm_variant", "mc_set_spmm_splitting", "mc_set_spmm_stages",
                  "mc_set_softmax_variant", "mc_set_thread_options", "mc_get_thread_options", "mc_spmm_ex", "mc_sddmm_ex",
-                 "mc_sparse_attention_ex", "mc_sparse_attention_static", "mc_blocked_query", "mc_pack_blocked_host", "mc_sddmm_to_mat", "mc_probe_mfma", "mc_spmm_form"):
+                 "mc_sparse_attention_ex", "mc_sparse_attention_static", "mc_blocked_query", "mc_pack_blocked_host", "mc_sddmm_to_mat", "mc_probe_mfma", "mc_spmm_form",
+                 "mc_mat_merged_info", "mc_merged_query", "mc_merge_host"):
         getattr(L, name).restype = c_int
     return L
 
@@ -203,6 +212,26 @@ def pack_blocked_host(M, K, V, lhs_bits, row_ptr, col_idx, values):
     return bl.nblk, blk_ptr, blk_rows[:bl.nchunks * CHUNK], blk_vals[:bl.vals_bytes], blk_src[:bl.nchunks * CHUNK]
 
 
+def merge_host(M, K, V, lhs_bits, row_ptr, col_idx, values, group):
+    """Interchange arrays -> (m_row_ptr, m_col_idx, m_values, m_src): `group` consecutive panels as one panel of
+    V * group rows at the union of their columns (m_values: bytes in interchange order, None for a pattern)."""
+    rp, ci = _i32(row_ptr), _i32(col_idx)
+    if rp.shape[0] < 1 or (M > 0 and V > 0 and M % V == 0 and rp.shape[0] != M // V + 1) or ci.shape[0] != int(rp[-1]):
+        raise MagicubeError(MC_EINVAL, "merge_host(array lengths)")
+    ml = MergedLayout()
+    _check(lib.mc_merged_query(M, K, V, lhs_bits, _p32(rp), _p32(ci), group, ctypes.byref(ml)), "mc_merged_query")
+    m_row_ptr = np.zeros(ml.P + 1, np.int32)
+    m_col_idx = np.zeros(max(ml.nvec, 1), np.int32)
+    m_src = np.zeros(max(ml.nvec * group, 1), np.int32)
+    vals = None if values is None else np.ascontiguousarray(values)
+    nbytes = ml.nvec * group * V * _container_bits(lhs_bits) // 8
+    m_values = None if vals is None else np.zeros(max(nbytes, 1), np.uint8)
+    _check(lib.mc_merge_host(M, K, V, lhs_bits, _p32(rp), _p32(ci), None if vals is None else vals.ctypes.data, group,
+                             _p32(m_row_ptr), _p32(m_col_idx), None if m_values is None else m_values.ctypes.data, _p32(m_src)),
+           "mc_merge_host")
+    return m_row_ptr, m_col_idx[:ml.nvec], (None if m_values is None else m_values[:nbytes]), m_src[:ml.nvec * group]
+
+
 def unpack_host(M, K, V, lhs_bits, panel_ptr, slot_idx, slot_vals):
     pp, si = _i32(panel_ptr), _i32(slot_idx)
     P = M // V
@@ -238,6 +267,9 @@ class SparseMatrix:
         nvec, nslots = c_int64(), c_int64()
         _check(lib.mc_mat_info(h, None, None, None, None, ctypes.byref(nvec), ctypes.byref(nslots)), "mc_mat_info")
         self.nvec, self.nslots = nvec.value, nslots.value
+        grp, mnvec = c_int(), c_int64()
+        _check(lib.mc_mat_merged_info(h, ctypes.byref(grp), ctypes.byref(mnvec)), "mc_mat_merged_info")
+        self.merge_group, self.merged_nvec = grp.value, mnvec.value   # 0: the operand has no merged copy
 
     def set_values(self, values_dev) -> None:
         """values_dev: device tensor, nvec*V elements in interchange (vector-major) order."""
@@ -322,7 +354,15 @@ def spmm_form(A: SparseMatrix, N: int, prec: str, options: Options | None = None
     r = lib.mc_spmm_form(A.handle, N, PREC[prec], ctypes.byref(options) if options is not None else None)
     if r < 0:
         _check(r, "mc_spmm_form")
-    return "lds" if r else "gather"
+    return "lds" if r & 1 else "gather"
+
+
+def spmm_on_merged(A: SparseMatrix, N: int, prec: str, options: Options | None = None) -> bool:
+    """Whether mc_spmm_ex would run on the operand's merged copy (panels sharing the MFMA's 16 rows)."""
+    r = lib.mc_spmm_form(A.handle, N, PREC[prec], ctypes.byref(options) if options is not None else None)
+    if r < 0:
+        _check(r, "mc_spmm_form")
+    return bool(r & 2)
 
 
 def spmm_dequant(A: SparseMatrix, B, prec: str, scale: float, out_dtype=torch.float32, out=None,

@@ -29,6 +29,7 @@ bool valid_options(const mc_options &o)
     if (d != 0 && d != -1 && d != 1 && d != 2 && d != 4 && d != 8) return false;
     if (o.softmax_variant < 0 || o.softmax_variant > 2) return false;
     if (o.attention_mode < 0 || o.attention_mode > 6) return false;
+    if (o.spmm_merge < -1 || o.spmm_merge > 1) return false;
     return true;
 }
 
@@ -106,6 +107,13 @@ void free_device(mc_mat *A)
     if (A->d_blk_vals) (void)hipFree(A->d_blk_vals);
     if (A->d_blk_src) (void)hipFree(A->d_blk_src);
     if (A->d_class_panels) (void)hipFree(A->d_class_panels);
+    if (A->d_merge_src) (void)hipFree(A->d_merge_src);
+    if (A->d_merge_vals) (void)hipFree(A->d_merge_vals);
+    if (A->merged) {
+        free_device(A->merged);
+        delete A->merged;
+        A->merged = nullptr;
+    }
 }
 
 // Waves per panel for SDDMM: enough to put about 2048 waves on the chip (4096 of the light ones
@@ -138,14 +146,14 @@ void choose_variant(const mc_mat *A, int lhs_bits, int row_bytes, bool r4, int b
             // a 64-byte tile of nibbles already yields 128 output columns
             // (rows of 128 bytes: the wider tile only for long panels, and not with a two-plane A and V = 8,
             // i.e. 16 output rows per tile: L16-R4, N=256, 70 % sparse 13.4 us on 128-byte, 11.2 us on 64-byte tiles)
-            const bool two_planes = (lhs_bits != 8 && lhs_bits != 4 && A->V == 8);
+            const bool two_planes = (lhs_bits != 8 && lhs_bits != 4 && A->V == 8) || A->V == 16; // 16 output rows per tile
             b = ((row_bytes >= 256 && avg >= 2.0) || (row_bytes >= 128 && avg >= 16.0 && !two_planes)) ? 128 : 64;
         } else {
             b = 128;
             if (row_bytes < 128 || (row_bytes == 128 && avg < 4.0) || (row_bytes < 512 && avg < 2.0) || avg < 3.0) b = 64;
             // wide tiles for panels of 8 chunks and more; with a two-plane A and V = 8 (16 output rows per
             // tile) only for long rows
-            if (row_bytes >= 256 && avg >= 8.0 && (lhs_bits == 8 || A->V < 8 || row_bytes >= 512)) b = 256;
+            if (row_bytes >= 256 && avg >= 8.0 && ((lhs_bits == 8 && A->V <= 8) || A->V < 8 || row_bytes >= 512)) b = 256;
             if (row_bytes >= 1024 && avg >= 6.0) b = 256; // eight and more 128-byte tiles would each re-read A
         }
     }
@@ -167,7 +175,7 @@ void choose_variant(const mc_mat *A, int lhs_bits, int row_bytes, bool r4, int b
         while (w < 8 && groups * w * 2 <= target && w * 2 <= avg) w *= 2;
         // long panels on the narrower tiles: at most 16 chunks per wave (8 with a two-plane A and V = 8)
         if (!r4 && b != 256) {
-            const double per_wave = (lhs_bits != 8 && A->V == 8) ? 8.0 : 16.0;
+            const double per_wave = ((lhs_bits != 8 && A->V == 8) || A->V == 16) ? 8.0 : 16.0;
             while (w < 8 && avg > per_wave * w) w *= 2;
         }
         // unequal panels (longest unit above twice the average): the longest unit sets the time of the
@@ -269,14 +277,25 @@ extern "C" int mc_set_attention_mode(int mode)
     return set_field([&](mc_options &o) { o.attention_mode = mode; });
 }
 
-extern "C" int mc_mat_create(int M, int K, int V, int lhs_bits, const int32_t *row_ptr, const int32_t *col_idx,
-                             const void *values, void *stream, mc_mat **out)
+namespace {
+// Whether mc_mat_create builds the merged copy (lay: the operand, ml: its merged form).  The copy holds
+// ml.nvec * rows values; which of the two a call uses is decided per call (merged_pays).
+bool merged_worth_building(const mc_layout &lay, const mc_merged_layout &ml, int V)
+{
+    (void)V;
+    return ml.nvec <= lay.nvec;
+}
+
+// child: the merged copy of another operand (V up to 16, never merged again)
+int mat_create_impl(int M, int K, int V, int lhs_bits, const int32_t *row_ptr, const int32_t *col_idx, const void *values,
+                    void *stream, bool child, mc_mat **out)
 {
     if (!out) return MC_EINVAL;
     *out = nullptr;
     if (!values) lhs_bits = 0;
+    if (!child && V == 16) return MC_EINVAL;
     mc_layout lay;
-    int rc = mc_layout_query(M, K, V, lhs_bits, row_ptr, &lay);
+    int rc = mc_layout_query_wide(M, K, V, lhs_bits, row_ptr, &lay);
     if (rc != MC_OK) return rc;
 
     std::vector<int32_t> panel_ptr, slot_idx;
@@ -288,8 +307,8 @@ extern "C" int mc_mat_create(int M, int K, int V, int lhs_bits, const int32_t *r
     } catch (const std::bad_alloc &) {
         return MC_ENOMEM;
     }
-    rc = mc_pack_host(M, K, V, lhs_bits, row_ptr, col_idx, values, panel_ptr.data(), slot_idx.data(),
-                      vals.empty() ? nullptr : vals.data());
+    rc = mc_pack_host_wide(M, K, V, lhs_bits, row_ptr, col_idx, values, panel_ptr.data(), slot_idx.data(),
+                           vals.empty() ? nullptr : vals.data());
     if (rc != MC_OK) return rc;
 
     mc_mat *A = new (std::nothrow) mc_mat();
@@ -309,6 +328,7 @@ extern "C" int mc_mat_create(int M, int K, int V, int lhs_bits, const int32_t *r
     A->nblk = 0; A->blk_chunks = 0; A->blk_valid = false;
     A->d_blk_ptr = nullptr; A->d_blk_rows = nullptr; A->d_blk_vals = nullptr; A->d_blk_src = nullptr;
     A->d_class_panels = nullptr;
+    A->merged = nullptr; A->merge_group = 0; A->d_merge_src = nullptr; A->d_merge_vals = nullptr; A->merged_valid = false;
     // Length classes of the panels (V = 8: the attention kernel gives a panel 1, 2, 4 or 8 waves)
     std::vector<int32_t> class_panels;
     for (int b = 0; b <= 4; ++b) A->class_start[b] = 0;
@@ -391,7 +411,7 @@ extern "C" int mc_mat_create(int M, int K, int V, int lhs_bits, const int32_t *r
         mc_blocked_layout bl;
         // (spmm_slab == 1 on the creating thread: built whatever the shape, so that the form can be forced)
         const bool forced = t_options.spmm_slab == 1;
-        if (mc_blocked_query(M, K, V, lhs_bits, row_ptr, col_idx, &bl) == MC_OK && bl.nblk <= 63 && bl.nchunks > 0 &&
+        if (mc_blocked_query_wide(M, K, V, lhs_bits, row_ptr, col_idx, &bl) == MC_OK && bl.nblk <= 63 && bl.nchunks > 0 &&
             (forced || ((double)lay.nvec >= 160.0 * lay.P * bl.nblk && // (below about 160 vectors per list the form never won)
                         bl.nchunks * MC_CHUNK <= lay.nvec + lay.nvec / 2 &&
                         A->max_panel_chunks <= 2.0 * (double)(lay.nslots / MC_CHUNK) / lay.P + 1.0))) {
@@ -404,8 +424,8 @@ extern "C" int mc_mat_create(int M, int K, int V, int lhs_bits, const int32_t *r
                 delete A;
                 return MC_ENOMEM;
             }
-            rc = mc_pack_blocked_host(M, K, V, lhs_bits, row_ptr, col_idx, values, blk_ptr.data(), blk_rows.data(),
-                                      blk_vals.data(), blk_src.data());
+            rc = mc_pack_blocked_host_wide(M, K, V, lhs_bits, row_ptr, col_idx, values, blk_ptr.data(), blk_rows.data(),
+                                           blk_vals.data(), blk_src.data());
             if (rc != MC_OK) {
                 delete A;
                 return rc;
@@ -451,6 +471,49 @@ extern "C" int mc_mat_create(int M, int K, int V, int lhs_bits, const int32_t *r
         MC_TRY(hipMalloc(&A->d_class_panels, sizeof(int32_t) * class_panels.size()));
         MC_TRY(hipMemcpyAsync(A->d_class_panels, class_panels.data(), sizeof(int32_t) * class_panels.size(), hipMemcpyHostToDevice, s));
     }
+    // Merged copy for the SpMM: panels of fewer rows than the matrix unit takes share one panel of 16 rows (4- and
+    // 8-bit values) or 8 rows (two byte planes), see mc_merge_host.  Not for operands without vectors, and not
+    // when the thread's options rule it out.
+    std::vector<int32_t> m_src;
+    int64_t m_vals_bytes = 0;
+    if (!child && lhs_bits != 0 && lay.nvec > 0 && t_options.spmm_merge != -1) {
+        const int rows = (lhs_bits == 4 || lhs_bits == 8) ? 16 : 8, group = rows / V;
+        mc_merged_layout ml;
+        if (group >= 2 && mc_merged_query(M, K, V, lhs_bits, row_ptr, col_idx, group, &ml) == MC_OK && ml.nvec > 0 &&
+            (t_options.spmm_merge == 1 || merged_worth_building(lay, ml, V))) {
+            std::vector<int32_t> m_row_ptr, m_col_idx;
+            std::vector<uint8_t> m_values;
+            const int64_t vb = (int64_t)V * (lhs_bits == 12 ? 16 : lhs_bits) / 8;
+            try {
+                m_row_ptr.resize((size_t)ml.P + 1);
+                m_col_idx.resize((size_t)ml.nvec);
+                m_values.resize((size_t)(ml.nvec * group * vb));
+                m_src.resize((size_t)(ml.nvec * group));
+            } catch (const std::bad_alloc &) {
+                free_device(A);
+                delete A;
+                return MC_ENOMEM;
+            }
+            rc = mc_merge_host(M, K, V, lhs_bits, row_ptr, col_idx, values, group, m_row_ptr.data(), m_col_idx.data(), m_values.data(),
+                               m_src.data());
+            if (rc == MC_OK)
+                rc = mat_create_impl(ml.P * rows, K, rows, lhs_bits, m_row_ptr.data(), m_col_idx.data(), m_values.data(), stream, true,
+                                     &A->merged);
+            if (rc != MC_OK) {
+                free_device(A);
+                delete A;
+                return rc;
+            }
+            A->merge_group = group;
+            m_vals_bytes = (int64_t)m_values.size();
+        }
+    }
+    if (A->merged) {
+        MC_TRY(hipMalloc(&A->d_merge_src, sizeof(int32_t) * m_src.size()));
+        MC_TRY(hipMalloc(&A->d_merge_vals, (size_t)m_vals_bytes));
+        MC_TRY(hipMemcpyAsync(A->d_merge_src, m_src.data(), sizeof(int32_t) * m_src.size(), hipMemcpyHostToDevice, s));
+        A->merged_valid = true;
+    }
     MC_TRY(hipStreamSynchronize(s)); // host staging buffers die at return
 #undef MC_TRY
     if (!ok) {
@@ -459,6 +522,21 @@ extern "C" int mc_mat_create(int M, int K, int V, int lhs_bits, const int32_t *r
         return MC_EHIP;
     }
     *out = A;
+    return MC_OK;
+}
+} // namespace
+
+extern "C" int mc_mat_create(int M, int K, int V, int lhs_bits, const int32_t *row_ptr, const int32_t *col_idx,
+                             const void *values, void *stream, mc_mat **out)
+{
+    return mat_create_impl(M, K, V, lhs_bits, row_ptr, col_idx, values, stream, false, out);
+}
+
+extern "C" int mc_mat_merged_info(const mc_mat *A, int *group, int64_t *nvec)
+{
+    if (!A) return MC_EINVAL;
+    if (group) *group = A->merged ? A->merge_group : 0;
+    if (nvec) *nvec = A->merged ? A->merged->nvec : 0;
     return MC_OK;
 }
 
@@ -498,13 +576,23 @@ extern "C" int mc_mat_set_values_device(mc_mat *A, const void *values_dev, void 
         MC_HIP(launch_repack_blocked(A->d_blk_src, r.src, A->d_blk_vals, A->blk_chunks, A->V, r.bits, static_cast<hipStream_t>(stream)));
         A->blk_valid = true;
     }
+    if (A->merged) { // and the merged copy: its values in interchange order first, then its own formats
+        const int vb = A->V * r.bits / 8;
+        MC_HIP(launch_merge_values(A->d_merge_src, r.src, A->d_merge_vals, A->merged->nvec * A->merge_group, vb,
+                                   static_cast<hipStream_t>(stream)));
+        const int rc = mc_mat_set_values_device(A->merged, A->d_merge_vals, stream);
+        if (rc != MC_OK) return rc;
+        A->merged_valid = true;
+    }
     return MC_OK;
 }
 
 namespace {
 inline int spmm_stages_for(const mc_options &o, int K, int64_t ldb_bytes, int row_bytes)
 {
-    return (o.spmm_stages != 1 && (int64_t)(K - 1) * ldb_bytes + row_bytes < ((int64_t)1 << 32)) ? 2 : 1;
+    // (the two-chunk form works out a lane's offset into B with one 24-bit multiply-add)
+    return (o.spmm_stages != 1 && (int64_t)(K - 1) * ldb_bytes + row_bytes < ((int64_t)1 << 32) && K <= (1 << 24) &&
+            ldb_bytes < (1 << 24)) ? 2 : 1;
 }
 
 // Work split of the SpMM that keeps K-blocks of B resident in LDS: one workgroup per (64-byte column
@@ -572,6 +660,21 @@ bool slab_chosen(const mc_mat *A, int row_bytes, int rb, unsigned flags, const m
     return plan_slab(A, row_bytes, rb == 4, 1, o, pl) && (o.spmm_slab == 1 || slab_pays(A, row_bytes, rb == 4, 1, *pl));
 }
 
+// Whether an SpMM call runs on the operand's merged copy.
+bool merged_chosen(const mc_mat *A, int row_bytes, unsigned flags, const mc_options &o)
+{
+    if (!A->merged || !A->merged_valid || o.spmm_merge == -1) return false;
+    if (flags != 0 && A->merged->V > 8) return false;
+    if (o.spmm_merge == 1) return true;
+    // Merged panels of 8 rows (two-plane values) run in the same kernel shape as unmerged ones with fewer gathered
+    // rows, fewer padded slots and fewer panels: faster at 34 of 36 points of a 4096 x 4096 sweep (V = 2 / 4, six
+    // sparsities, N = 128 .. 512), at worst 9 % slower.
+    if (A->merged->V <= 8) return true;
+    // Merged panels of 16 rows gather fewer rows (padded slots included) but run fewer, longer panels with 16-row
+    // tiles; in the same sweep (V = 2 / 4 / 8) they are the faster form once they save about 24 MB of gathered rows.
+    return (double)(A->nslots - A->merged->nslots) * row_bytes >= 24e6;
+}
+
 // out_mode 0: int32 results; 1 / 2: scale * result as fp32 / fp16 (fused dequantisation)
 int spmm_impl(const mc_mat *A, const void *B_dev, int N, int ldb, mc_prec prec, unsigned flags, int out_mode,
               float scale, void *C_dev, int ldc, const mc_options *opts, void *stream)
@@ -593,7 +696,13 @@ int spmm_impl(const mc_mat *A, const void *B_dev, int N, int ldb, mc_prec prec, 
     if (out_mode && !std::isfinite(scale)) return MC_EINVAL;
     if (!on_device_of(A)) return MC_EINVAL;
 
+    // the operand's merged copy (panels of 8 or 16 rows at the union of their columns) where it is expected to be faster;
+    // a 16-row panel leaves no MFMA row for the column sums that unsigned operands need
+    const int rows = A->M;
+    if (merged_chosen(A, N * rb / 8, flags, o)) A = A->merged;
+
     SpmmArgs a = {};
+    a.rows = rows;
     a.lhs_unsigned = (flags & MC_LHS_UNSIGNED) ? 1 : 0; a.rhs_unsigned = (flags & MC_RHS_UNSIGNED) ? 1 : 0;
     a.panel_ptr = A->d_panel_ptr; a.slot_idx = A->d_slot_idx;
     a.vals = A->d_vals; a.vals_batch_stride = 0;
@@ -609,7 +718,7 @@ int spmm_impl(const mc_mat *A, const void *B_dev, int N, int ldb, mc_prec prec, 
             sa.blk_ptr = A->d_blk_ptr; sa.blk_rows = A->d_blk_rows; sa.vals = A->d_blk_vals; sa.vals_batch_stride = 0;
             sa.B = a.B; sa.ldb_bytes = a.ldb_bytes; sa.B_batch_stride = 0; sa.row_bytes = a.row_bytes; sa.K = A->K;
             sa.C = C_dev; sa.ldc = ldc; sa.C_batch_stride = 0;
-            sa.P = A->P; sa.V = A->V; sa.batch = 1; sa.nblk = A->nblk;
+            sa.P = A->P; sa.V = A->V; sa.batch = 1; sa.nblk = A->nblk; sa.rows = rows;
             sa.float_out = out_mode; sa.out_scale = a.out_scale;
             sa.groups = pl.groups; sa.ppg = pl.ppg; sa.wpp = pl.wpp; sa.nc = pl.nc;
             sa.nf = 16 - sa.nc < 4 ? 16 - sa.nc : 4;
@@ -662,7 +771,9 @@ extern "C" int mc_spmm_form(const mc_mat *A, int N, mc_prec prec, const mc_optio
     if (resolve_options(options ? options : &automatic, &o) != MC_OK) return MC_EINVAL;
     SlabPlan pl;
     const int rb = rhs_bits_of(prec);
-    return slab_chosen(A, N * rb / 8, rb, 0u, o, &pl) ? 1 : 0;
+    const bool merged = merged_chosen(A, N * rb / 8, 0u, o);
+    if (merged) A = A->merged;
+    return (slab_chosen(A, N * rb / 8, rb, 0u, o, &pl) ? 1 : 0) | (merged ? 2 : 0);
 }
 
 extern "C" int mc_spmm_dequant(const mc_mat *A, const void *B_dev, int N, int ldb, mc_prec prec, unsigned flags,
@@ -695,7 +806,7 @@ extern "C" int mc_probe_gather(const mc_mat *A, const void *B_dev, int N, int ld
     a.B = static_cast<const uint8_t *>(B_dev); a.ldb_bytes = (int64_t)ldb * rb / 8; a.B_batch_stride = 0;
     a.row_bytes = N * rb / 8;
     a.C = nullptr; a.ldc = 0; a.C_batch_stride = 0;
-    a.P = A->P; a.V = A->V; a.batch = 1; a.float_out = 0; a.out_scale = 1.f;
+    a.P = A->P; a.V = A->V; a.rows = A->M; a.batch = 1; a.float_out = 0; a.out_scale = 1.f;
     int bnb, waves;
     choose_variant(A, A->lhs_bits, a.row_bytes, rb == 4, 1, A->max_panel_chunks, o, &bnb, &waves);
     MC_HIP(launch_gather_probe(a, bnb, waves, sink_dev, static_cast<hipStream_t>(stream)));
@@ -800,6 +911,7 @@ extern "C" int mc_sddmm_to_mat(const void *Q_dev, int ldq, const void *Kmat_dev,
     a.P = P->P; a.V = P->V; a.batch = 1;
     if (P->n_items && o.spmm_splitting != -1) { a.items = P->d_items; a.n_units = P->n_items; }
     P->blk_valid = false; // only the panel format receives the new values
+    P->merged_valid = false;
     MC_HIP(launch_sddmm(bits, a, choose_sddmm_waves(P, 1, a.row_bytes, bits, o), static_cast<hipStream_t>(stream)));
     return MC_OK;
 }
@@ -859,6 +971,7 @@ extern "C" int mc_sparse_softmax_to_mat(mc_mat *P, const int32_t *S_dev, float s
     a.P = P->P; a.V = P->V; a.batch = 1; a.code_bits = P->lhs_bits;
     a.max_panel_chunks = P->max_panel_chunks; a.variant = o.softmax_variant;
     P->blk_valid = false; // only the panel format receives the new values
+    P->merged_valid = false;
     MC_HIP(launch_softmax(a, static_cast<hipStream_t>(stream)));
     return MC_OK;
 }
@@ -956,7 +1069,7 @@ int attention_pipeline(const uint8_t *Q, const uint8_t *Km, const uint8_t *Vm, i
     m.vals = pvals; m.vals_batch_stride = mask->nslots * 8 * pb;
     m.B = Vm; m.ldb_bytes = token_stride_bytes; m.B_batch_stride = head_stride_bytes;
     m.row_bytes = row_bytes; m.C = O; m.ldc = o_token_stride; m.C_batch_stride = o_head_stride;
-    m.P = mask->P; m.V = 8; m.batch = heads; m.float_out = out_f16 ? 2 : 1; m.out_scale = s_p * s_v;
+    m.P = mask->P; m.V = 8; m.rows = mask->M; m.batch = heads; m.float_out = out_f16 ? 2 : 1; m.out_scale = s_p * s_v;
     m.stages = spmm_stages_for(o, mask->K, m.ldb_bytes, m.row_bytes);
     m.max_unit_chunks = mask->max_panel_chunks;
     if (split_panels) {

@@ -9,7 +9,10 @@
 // consecutive reduction bytes of one row.
 #include "internal.h"
 
+#include <algorithm>
+#include <climits>
 #include <cstring>
+#include <vector>
 
 namespace {
 
@@ -70,11 +73,24 @@ inline int row_position(int s) { return (s / 16) * 16 + (s % 8) * 2 + (s % 16) /
 
 } // namespace
 
+// The builders below exist in two forms: the exported ones take the vector lengths of the interchange format
+// (2, 4, 8); the *_wide ones also take 16 for 4- and 8-bit values, which only the library's own merged copy of
+// an operand uses (see mc_merge_host): sixteen rows fill the MFMA's row operand completely.
+static bool valid_V(int V, int lhs_bits, bool wide)
+{
+    return V == 2 || V == 4 || V == 8 || (wide && V == 16 && (lhs_bits == 4 || lhs_bits == 8));
+}
+
 extern "C" int mc_layout_query(int M, int K, int V, int lhs_bits, const int32_t *row_ptr, mc_layout *out)
+{
+    return V == 16 ? MC_EINVAL : mc_layout_query_wide(M, K, V, lhs_bits, row_ptr, out);
+}
+
+int mc_layout_query_wide(int M, int K, int V, int lhs_bits, const int32_t *row_ptr, mc_layout *out)
 {
     if (!row_ptr || !out) return MC_EINVAL;
     if (M <= 0 || K <= 0) return MC_EINVAL;
-    if (V != 2 && V != 4 && V != 8) return MC_EINVAL;
+    if (!valid_V(V, lhs_bits, true)) return MC_EINVAL;
     if (M % V != 0) return MC_EINVAL;
     if (!valid_lhs_bits(lhs_bits)) return MC_EINVAL;
     const int P = M / V;
@@ -96,8 +112,14 @@ extern "C" int mc_layout_query(int M, int K, int V, int lhs_bits, const int32_t 
 extern "C" int mc_pack_host(int M, int K, int V, int lhs_bits, const int32_t *row_ptr, const int32_t *col_idx,
                             const void *values, int32_t *panel_ptr, int32_t *slot_idx, void *slot_vals)
 {
+    return V == 16 ? MC_EINVAL : mc_pack_host_wide(M, K, V, lhs_bits, row_ptr, col_idx, values, panel_ptr, slot_idx, slot_vals);
+}
+
+int mc_pack_host_wide(int M, int K, int V, int lhs_bits, const int32_t *row_ptr, const int32_t *col_idx,
+                      const void *values, int32_t *panel_ptr, int32_t *slot_idx, void *slot_vals)
+{
     mc_layout lay;
-    int rc = mc_layout_query(M, K, V, lhs_bits, row_ptr, &lay);
+    int rc = mc_layout_query_wide(M, K, V, lhs_bits, row_ptr, &lay);
     if (rc != MC_OK) return rc;
     if (!panel_ptr || (lay.nslots && !slot_idx) || (lay.nvec && !col_idx)) return MC_EINVAL;
     const bool with_vals = lhs_bits != 0 && values != nullptr;
@@ -188,8 +210,14 @@ extern "C" int mc_unpack_host(int M, int K, int V, int lhs_bits, const int32_t *
 extern "C" int mc_blocked_query(int M, int K, int V, int lhs_bits, const int32_t *row_ptr, const int32_t *col_idx,
                                 mc_blocked_layout *out)
 {
+    return V == 16 ? MC_EINVAL : mc_blocked_query_wide(M, K, V, lhs_bits, row_ptr, col_idx, out);
+}
+
+int mc_blocked_query_wide(int M, int K, int V, int lhs_bits, const int32_t *row_ptr, const int32_t *col_idx,
+                          mc_blocked_layout *out)
+{
     mc_layout lay;
-    int rc = mc_layout_query(M, K, V, lhs_bits, row_ptr, &lay);
+    int rc = mc_layout_query_wide(M, K, V, lhs_bits, row_ptr, &lay);
     if (rc != MC_OK) return rc;
     if (!out || (lay.nvec && !col_idx)) return MC_EINVAL;
     const int nblk = (K + MC_KBLOCK - 1) / MC_KBLOCK;
@@ -220,8 +248,14 @@ extern "C" int mc_pack_blocked_host(int M, int K, int V, int lhs_bits, const int
                                     const void *values, int32_t *blk_ptr, uint16_t *blk_rows, void *blk_vals,
                                     int32_t *blk_src)
 {
+    return V == 16 ? MC_EINVAL : mc_pack_blocked_host_wide(M, K, V, lhs_bits, row_ptr, col_idx, values, blk_ptr, blk_rows, blk_vals, blk_src);
+}
+
+int mc_pack_blocked_host_wide(int M, int K, int V, int lhs_bits, const int32_t *row_ptr, const int32_t *col_idx,
+                              const void *values, int32_t *blk_ptr, uint16_t *blk_rows, void *blk_vals, int32_t *blk_src)
+{
     mc_blocked_layout bl;
-    int rc = mc_blocked_query(M, K, V, lhs_bits, row_ptr, col_idx, &bl);
+    int rc = mc_blocked_query_wide(M, K, V, lhs_bits, row_ptr, col_idx, &bl);
     if (rc != MC_OK) return rc;
     if (!blk_ptr || (bl.nchunks && (!blk_rows || !blk_src))) return MC_EINVAL;
     const bool with_vals = lhs_bits != 0 && values != nullptr;
@@ -258,5 +292,88 @@ extern "C" int mc_pack_blocked_host(int M, int K, int V, int lhs_bits, const int
         }
     }
     blk_ptr[(int64_t)P * bl.nblk] = (int32_t)chunk;
+    return MC_OK;
+}
+
+// ---- merged panels ----------------------------------------------------------------------------
+// `group` consecutive panels of V rows become one panel of V * group rows whose stored vectors sit at the
+// union of the panels' columns; a panel that has no vector at a column of the union contributes zeros there
+// (explicit zeros are legal inside stored vectors).  The product with a dense matrix is unchanged, the rows
+// of the dense operand named by a column are fetched once for all the panels of a group instead of once per
+// panel that holds it, and the MFMA's 16-row operand fills up.
+extern "C" int mc_merged_query(int M, int K, int V, int lhs_bits, const int32_t *row_ptr, const int32_t *col_idx, int group,
+                               mc_merged_layout *out)
+{
+    mc_layout lay;
+    int rc = mc_layout_query(M, K, V, lhs_bits, row_ptr, &lay);
+    if (rc != MC_OK) return rc;
+    if (!out || (lay.nvec && !col_idx)) return MC_EINVAL;
+    if (group < 2 || (V * group != 8 && V * group != 16)) return MC_EINVAL;
+    if (V * group == 16 && lhs_bits != 4 && lhs_bits != 8) return MC_EINVAL;
+    const int Pm = (lay.P + group - 1) / group;
+    int64_t nvec = 0;
+    std::vector<int64_t> at((size_t)group);
+    for (int sp = 0; sp < Pm; ++sp) {
+        const int p0 = sp * group, np = std::min(group, lay.P - p0);
+        for (int g = 0; g < np; ++g) {
+            at[(size_t)g] = row_ptr[p0 + g];
+            int32_t prev = -1;
+            for (int64_t i = row_ptr[p0 + g]; i < row_ptr[p0 + g + 1]; ++i) { // ascending, inside [0, K)
+                if (col_idx[i] <= prev || col_idx[i] >= K) return MC_EINVAL;
+                prev = col_idx[i];
+            }
+        }
+        for (;;) { // one column of the union per round: the smallest column any panel still has
+            int32_t c = INT32_MAX;
+            for (int g = 0; g < np; ++g)
+                if (at[(size_t)g] < row_ptr[p0 + g + 1]) c = std::min(c, col_idx[at[(size_t)g]]);
+            if (c == INT32_MAX) break;
+            for (int g = 0; g < np; ++g)
+                if (at[(size_t)g] < row_ptr[p0 + g + 1] && col_idx[at[(size_t)g]] == c) ++at[(size_t)g];
+            ++nvec;
+        }
+    }
+    if (nvec > (int64_t)INT32_MAX - MC_CHUNK) return MC_EINVAL;
+    out->group = group;
+    out->P = Pm;
+    out->nvec = nvec;
+    return MC_OK;
+}
+
+extern "C" int mc_merge_host(int M, int K, int V, int lhs_bits, const int32_t *row_ptr, const int32_t *col_idx, const void *values,
+                             int group, int32_t *m_row_ptr, int32_t *m_col_idx, void *m_values, int32_t *m_src)
+{
+    mc_merged_layout ml;
+    int rc = mc_merged_query(M, K, V, lhs_bits, row_ptr, col_idx, group, &ml);
+    if (rc != MC_OK) return rc;
+    if (!m_row_ptr || (ml.nvec && (!m_col_idx || !m_src))) return MC_EINVAL;
+    const bool with_vals = lhs_bits != 0 && values != nullptr && m_values != nullptr;
+    const int P = M / V;
+    const int64_t vb = (int64_t)V * storage_bits(lhs_bits) / 8; // bytes of one panel's share of a merged vector
+    const uint8_t *src = static_cast<const uint8_t *>(values);
+    uint8_t *dst = static_cast<uint8_t *>(m_values);
+    if (with_vals) std::memset(dst, 0, (size_t)(ml.nvec * group * vb));
+    std::vector<int64_t> at((size_t)group);
+    int64_t out = 0;
+    m_row_ptr[0] = 0;
+    for (int sp = 0; sp < ml.P; ++sp) {
+        const int p0 = sp * group, np = std::min(group, P - p0);
+        for (int g = 0; g < np; ++g) at[(size_t)g] = row_ptr[p0 + g];
+        for (;;) {
+            int32_t c = INT32_MAX;
+            for (int g = 0; g < np; ++g)
+                if (at[(size_t)g] < row_ptr[p0 + g + 1]) c = std::min(c, col_idx[at[(size_t)g]]);
+            if (c == INT32_MAX) break;
+            m_col_idx[out] = c;
+            for (int g = 0; g < group; ++g) {
+                int64_t from = -1;
+                if (g < np && at[(size_t)g] < row_ptr[p0 + g + 1] && col_idx[at[(size_t)g]] == c) from = at[(size_t)g]++;
+                m_src[out * group + g] = (int32_t)from;
+                if (with_vals && from >= 0) std::memcpy(dst + (out * group + g) * vb, src + from * vb, (size_t)vb);
+            }
+            ++out;
+        }
+        m_row_ptr[sp + 1] = (int32_t)out;
+    }
     return MC_OK;
 }

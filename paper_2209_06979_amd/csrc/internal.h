@@ -36,7 +36,24 @@ struct mc_mat {
     // hold; class 3 also takes what is longer still.
     int32_t *d_class_panels;   // P panel numbers, class after class
     int class_start[5];        // first entry of each class in d_class_panels; [4] = P
+    // Merged copy for the SpMM (null when not built): `merge_group` consecutive panels as one panel of
+    // V * merge_group rows at the union of their columns (see mc_merge_host); a complete operand of its own
+    // (work items, K-blocked copy), never merged again.  Its rows may run past M: launches on it pass M as the
+    // number of output rows.
+    mc_mat *merged;
+    int merge_group;
+    int32_t *d_merge_src;      // merged nvec * merge_group: interchange vector of each panel's share, -1 = zeros
+    uint8_t *d_merge_vals;     // staging for mc_mat_set_values_device: the merged operand's values in interchange order
+    bool merged_valid;         // false once the values were replaced in the panel format only
 };
+
+// Builders that also take V = 16 (4- and 8-bit values): the library's merged copies only.
+int mc_layout_query_wide(int M, int K, int V, int lhs_bits, const int32_t *row_ptr, mc_layout *out);
+int mc_pack_host_wide(int M, int K, int V, int lhs_bits, const int32_t *row_ptr, const int32_t *col_idx, const void *values,
+                      int32_t *panel_ptr, int32_t *slot_idx, void *slot_vals);
+int mc_blocked_query_wide(int M, int K, int V, int lhs_bits, const int32_t *row_ptr, const int32_t *col_idx, mc_blocked_layout *out);
+int mc_pack_blocked_host_wide(int M, int K, int V, int lhs_bits, const int32_t *row_ptr, const int32_t *col_idx, const void *values,
+                              int32_t *blk_ptr, uint16_t *blk_rows, void *blk_vals, int32_t *blk_src);
 
 // One SpMM launch (optionally a batch of problems sharing the sparsity pattern).
 struct SpmmArgs {
@@ -52,6 +69,7 @@ struct SpmmArgs {
     int64_t ldc;               // elements
     int64_t C_batch_stride;    // elements
     int P, V, batch;
+    int rows;                  // rows of C (a merged operand's last panel may run past them); V up to 16
     int float_out;             // 0: int32; 1: float(acc) * out_scale as fp32; 2: the same rounded to fp16
     float out_scale;
     int lhs_unsigned, rhs_unsigned; // 4- and 8-bit operands read as non-negative values
@@ -60,6 +78,7 @@ struct SpmmArgs {
     const int32_t *items;
     int n_units;               // items, or P
     int stages;                // chunks in flight per wave: 1 or 2 (2 needs B to span less than 4 GiB)
+    int ntiles, tile_shift;    // filled by the launcher: column tiles (workgroups) per unit, and their log2 (-1: not a power of two)
     int max_unit_chunks;       // chunks of the longest unit of work (panel or work item)
     // optional: items of a split panel add their int32 results here instead of into C (which may then be float or
     // half): cleared rows [batch][split panel][V][acc_ld], finished by launch_finish_split_rows
@@ -79,6 +98,7 @@ struct SlabArgs {
     void *C;
     int64_t ldc, C_batch_stride;
     int P, V, batch, nblk;
+    int rows;                  // rows of C (see SpmmArgs)
     int float_out;
     float out_scale;
     int groups;                // panel groups (workgroups per column tile)
@@ -194,6 +214,9 @@ int scores_softmax_max_npad(int row_bytes, int waves);
 hipError_t launch_absmax(const float *x, int64_t n, float *result, hipStream_t s);
 hipError_t launch_quantize(const float *x, int64_t n, float scale, int bits, uint8_t *q, hipStream_t s);
 hipError_t launch_repack(const RepackArgs &a, hipStream_t s);
+// values of a merged operand in interchange order from the original operand's: share (i, g) of vb bytes = vector
+// merge_src[i * group + g] of src, or zeros
+hipError_t launch_merge_values(const int32_t *merge_src, const uint8_t *src, uint8_t *dst, int64_t shares, int vb, hipStream_t s);
 // dk is 64 or 128.  heads_per_group 2 needs head_stride == dk (token-major layout), rows of at most 64
 // bytes and an even head count, and is not available for 16-bit codes with 4-bit inputs
 hipError_t launch_attention_fused(const AttnArgs &a, int heads_per_group, int waves_per_panel, int p_bits, int qkv_bits,

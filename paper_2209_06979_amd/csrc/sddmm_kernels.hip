@@ -570,3 +570,21 @@ hipError_t launch_repack(const RepackArgs &a, hipStream_t s)
     hipLaunchKernelGGL(repack_kernel, grid, block, 0, s, a);
     return hipGetLastError();
 }
+
+namespace {
+// One thread per share (merged vector i, panel g of its group): vb bytes copied from the vector that fills it, or zeros.
+__global__ __launch_bounds__(256) void merge_values_kernel(const int32_t *merge_src, const uint8_t *src, uint8_t *dst, int64_t shares, int vb)
+{
+    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (t >= shares) return;
+    const int64_t from = merge_src[t];
+    for (int b = 0; b < vb; ++b) dst[t * vb + b] = (from >= 0) ? src[from * vb + b] : (uint8_t)0;
+}
+} // namespace
+
+hipError_t launch_merge_values(const int32_t *merge_src, const uint8_t *src, uint8_t *dst, int64_t shares, int vb, hipStream_t s)
+{
+    if (shares == 0) return hipSuccess;
+    hipLaunchKernelGGL(merge_values_kernel, dim3((unsigned)((shares + 255) / 256)), dim3(256), 0, s, merge_src, src, dst, shares, vb);
+    return hipGetLastError();
+}

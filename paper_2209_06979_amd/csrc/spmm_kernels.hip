@@ -107,8 +107,9 @@ __global__ __launch_bounds__(64 * WK) void spmm_kernel(SpmmArgs a)
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int j = lane & 15, g = lane >> 4;
     const int rg = lane / LPR, seg = lane % LPR;
-    const int ntiles = (a.row_bytes + BNB - 1) / BNB;
-    const int unit = blockIdx.x / ntiles, tile = blockIdx.x % ntiles;
+    // workgroups of a unit: a.ntiles column tiles, a power of two when a.tile_shift >= 0
+    const int unit = (a.tile_shift >= 0) ? (int)(blockIdx.x >> a.tile_shift) : (int)(blockIdx.x / a.ntiles);
+    const int tile = (int)(blockIdx.x - unit * a.ntiles);
     const int batch = blockIdx.y;
     const int nb0 = tile * BNB;
 
@@ -118,7 +119,8 @@ __global__ __launch_bounds__(64 * WK) void spmm_kernel(SpmmArgs a)
         const v4i it = *reinterpret_cast<const v4i *>(a.items + 4 * unit);
         panel = it.x; cb = it.y; ce = it.z; split = it.w;
     }
-    const int s0 = a.panel_ptr[2 * panel], s1 = a.panel_ptr[2 * panel + 1];
+    const v2i pp = *reinterpret_cast<const v2i *>(a.panel_ptr + 2 * panel); // first slot, end slot: one load
+    const int s0 = pp.x, s1 = pp.y;
     if (ce < 0) ce = (s1 - s0 + MC_CHUNK - 1) / MC_CHUNK;
     const int nch = ce - cb;                       // chunks of this unit: cb .. ce-1
     const int64_t chunk0 = s0 / MC_CHUNK + cb;
@@ -148,6 +150,11 @@ __global__ __launch_bounds__(64 * WK) void spmm_kernel(SpmmArgs a)
         segoff[i] = (nb0 + lseg * 16 < a.row_bytes) ? lseg * 16 : 0;
     }
     const int nmy = (nch > w) ? (nch - w + WK - 1) / WK : 0; // chunks of this wave: w, w+WK, ...
+
+    // piece pc of the finished tile = 4 columns of one of its 8 rows; this thread owns pieces tid, tid + 64 WK, ...
+    const int ncols = R4 ? a.row_bytes * 2 : (R16 ? a.row_bytes / 2 : a.row_bytes);
+    constexpr int PIECES = 8 * (OUTC / 4);
+    constexpr int NPC = (PIECES + 64 * WK - 1) / (64 * WK);
 
     // LDS byte address (within a stage) of this lane's source piece for the transposing
     // read of half h (slots g*16 + 8h .. +7), before the column-tile XOR.
@@ -221,7 +228,8 @@ __global__ __launch_bounds__(64 * WK) void spmm_kernel(SpmmArgs a)
         // point, so that the compiler's waits land here, where nothing else is in flight.  The
         // loop then contains copies (assembly, no register destination) and LDS reads only, and
         // vector-memory operations complete in issue order: "at most NI outstanding" right after
-        // the NI copies of chunk k+1 means that chunk k has arrived.
+        // the NI copies of chunk k+1 means that chunk k has arrived.  (Row numbers and row strides are
+        // below 2^24 here -- the launcher checks it -- so a lane's offset is one 24-bit multiply-add.)
         constexpr int MAXL = SPMM_PIPE_CHUNKS;
         const unsigned stage_u = mcu::lds_addr_uniform(stage);
         const unsigned ldb32 = (unsigned)a.ldb_bytes;
@@ -245,7 +253,7 @@ __global__ __launch_bounds__(64 * WK) void spmm_kernel(SpmmArgs a)
         auto issue = [&](int st, const v4i (&ixs)[NI / 4]) {
 #pragma unroll
             for (int i = 0; i < NI; ++i)
-                mcu::copy16_to_lds(Bb, (unsigned)ixs[i >> 2][i & 3] * ldb32 + (unsigned)segoff[i], stage_u + st * Cfg::STAGE + i * 1024);
+                mcu::copy16_to_lds(Bb, __umul24((unsigned)ixs[i >> 2][i & 3], ldb32) + (unsigned)segoff[i], stage_u + st * Cfg::STAGE + i * 1024);
         };
         if (nmy > 0) issue(0, ix[0]);
         mcu::static_for<MAXL>([&](auto Lc) {
@@ -266,98 +274,117 @@ __global__ __launch_bounds__(64 * WK) void spmm_kernel(SpmmArgs a)
     // ---- partial tiles -> LDS (each wave into its own region), row-major int32 ----------
     // accumulator register r of lane (j, g) is output row 4g + r; MFMA ct covers tile bytes
     // 16*ct .. 16*ct+15, i.e. column 16*ct + j (R8) or columns 32*ct + 2j, 2j+1 (R4).
+    // A one-plane operand of 16 rows (the merged copy of an operand) passes through the tile in two
+    // halves of 8 rows: lane groups 0, 1 first, then 2, 3.
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     int *tile_w = reinterpret_cast<int *>(stage);
     constexpr int OROWS = Cfg::OROWS;
-    if (4 * g < OROWS) {
-#pragma unroll
-        for (int ct = 0; ct < LPR; ++ct)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                if (!R4) {
-                    tile_w[(4 * g + r) * TST + ct * 16 + j] = acc[ct][r];
-                } else {
-                    *reinterpret_cast<v2i *>(&tile_w[(4 * g + r) * TST + ct * 32 + 2 * j]) = (v2i){acc[2 * ct][r], acc[2 * ct + 1][r]};
-                }
-            }
-        if ((R16 || U) && j == 0) { // the row sums ride in the padding column of the tile
-#pragma unroll
-            for (int r = 0; r < 4; ++r) tile_w[(4 * g + r) * TST + COLS] = acc[XACC][r];
-        }
-    }
-    __syncthreads();
-
-    // ---- sum over the waves, finish the arithmetic, store 16 bytes per thread -------------
-    // Every plane sum is exact in int32 (R4: after its shift); the recombinations wrap.
-    const int ncols = R4 ? a.row_bytes * 2 : (R16 ? a.row_bytes / 2 : a.row_bytes);
-    constexpr int PIECES = 8 * (OUTC / 4);
     constexpr int SH = R4 ? (LB == 4 ? 8 : 4) : 0;       // scale carried by widened nibbles
-    for (int pc = tid; pc < PIECES; pc += 64 * WK) {
-        const int row = pc / (OUTC / 4), col = (pc % (OUTC / 4)) * 4;
-        const int gcol = tile * OUTC + col;
-        if (row >= a.V || gcol >= ncols) continue;
-        const int tcol = R16 ? 2 * col : col;            // first column in the partial tile
-        v4i s = {0, 0, 0, 0}, lo = {0, 0, 0, 0}, s2 = {0, 0, 0, 0}, lo2 = {0, 0, 0, 0}, cs = {0, 0, 0, 0};
-        int rs = 0, rs_lo = 0;
+    const int nhalf = (!L16 && !U && a.V > 8) ? 2 : 1;
+    for (int hf = 0; hf < nhalf; ++hf) {
+        if (hf) __syncthreads();                         // the first half's tiles have been read
+        const int gg = g - 2 * hf;
+        if (gg >= 0 && 4 * gg < OROWS) {
 #pragma unroll
-        for (int ww = 0; ww < WK; ++ww) {
-            const int *t = reinterpret_cast<const int *>(lds + ww * Cfg::PERWAVE);
-            s += *reinterpret_cast<const v4i *>(&t[row * TST + tcol]);
-            if (L16) lo += *reinterpret_cast<const v4i *>(&t[(row + 8) * TST + tcol]);
-            if (U) {
-                cs += *reinterpret_cast<const v4i *>(&t[8 * TST + tcol]);
-                rs += t[row * TST + COLS];
+            for (int ct = 0; ct < LPR; ++ct)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    if (!R4) {
+                        tile_w[(4 * gg + r) * TST + ct * 16 + j] = acc[ct][r];
+                    } else {
+                        *reinterpret_cast<v2i *>(&tile_w[(4 * gg + r) * TST + ct * 32 + 2 * j]) = (v2i){acc[2 * ct][r], acc[2 * ct + 1][r]};
+                    }
+                }
+            if ((R16 || U) && j == 0) { // the row sums ride in the padding column of the tile
+#pragma unroll
+                for (int r = 0; r < 4; ++r) tile_w[(4 * gg + r) * TST + COLS] = acc[XACC][r];
             }
-            if (R16) {
-                s2 += *reinterpret_cast<const v4i *>(&t[row * TST + tcol + 4]);
-                rs += t[row * TST + COLS];
-                if (L16) {
-                    lo2 += *reinterpret_cast<const v4i *>(&t[(row + 8) * TST + tcol + 4]);
-                    rs_lo += t[(row + 8) * TST + COLS];
+        }
+        __syncthreads();
+
+        // ---- sum over the waves, finish the arithmetic, store 16 bytes per thread -------------
+        // Every plane sum is exact in int32 (R4: after its shift); the recombinations wrap.
+        // All LDS reads of a thread's pieces first (a piece beyond the tile reads the last one again), then the stores.
+        v4i fin[NPC];
+#pragma unroll
+        for (int q = 0; q < NPC; ++q) {
+            const int pc = (tid + q * 64 * WK < PIECES) ? tid + q * 64 * WK : PIECES - 1;
+            const int row = pc / (OUTC / 4), col = (pc % (OUTC / 4)) * 4;
+            const int tcol = R16 ? 2 * col : col;            // first column in the partial tile
+            v4i s = {0, 0, 0, 0}, lo = {0, 0, 0, 0}, s2 = {0, 0, 0, 0}, lo2 = {0, 0, 0, 0}, cs = {0, 0, 0, 0};
+            int rs = 0, rs_lo = 0;
+#pragma unroll
+            for (int ww = 0; ww < WK; ++ww) {
+                const int *t = reinterpret_cast<const int *>(lds + ww * Cfg::PERWAVE);
+                s += *reinterpret_cast<const v4i *>(&t[row * TST + tcol]);
+                if (L16) lo += *reinterpret_cast<const v4i *>(&t[(row + 8) * TST + tcol]);
+                if (U) {
+                    cs += *reinterpret_cast<const v4i *>(&t[8 * TST + tcol]);
+                    rs += t[row * TST + COLS];
+                }
+                if (R16) {
+                    s2 += *reinterpret_cast<const v4i *>(&t[row * TST + tcol + 4]);
+                    rs += t[row * TST + COLS];
+                    if (L16) {
+                        lo2 += *reinterpret_cast<const v4i *>(&t[(row + 8) * TST + tcol + 4]);
+                        rs_lo += t[(row + 8) * TST + COLS];
+                    }
                 }
             }
+            if (U) {
+                // sum (a'+ca)(b'+cb): the operand bytes carry a' and b' (times 16 for nibbles), and
+                // cb * 16^[R4] = ca * 16^[L4] = 128, so both corrections are the sums shifted by 7
+                if (a.rhs_unsigned) s += (v4i){rs << 7, rs << 7, rs << 7, rs << 7};
+                if (a.lhs_unsigned) s += cs << 7;
+            }
+            if (R4) { s = s >> SH; lo = lo >> SH; }
+            if (U && a.lhs_unsigned && a.rhs_unsigned) {
+                const int cc = (LB == 4 ? 8 : 128) * (RB == 4 ? 8 : 128) * (nch * MC_CHUNK); // ca * cb * slots (padded ones included: their a' is -ca)
+                s += (v4i){cc, cc, cc, cc};
+            }
+            if (L16) { s = (s << 8) + lo; s2 = (s2 << 8) + lo2; rs = (rs << 8) + rs_lo; }
+            if (R16) {
+                // byte columns (low, high) of four B elements: A*b = (A*hi << 8) + A*(low ^ 0x80) + 128 * rowsum(A)
+                const int fix = rs << 7;
+                s = (v4i){(s.y << 8) + s.x + fix, (s.w << 8) + s.z + fix, (s2.y << 8) + s2.x + fix, (s2.w << 8) + s2.z + fix};
+            }
+            fin[q] = s;
         }
-        if (U) {
-            // sum (a'+ca)(b'+cb): the operand bytes carry a' and b' (times 16 for nibbles), and
-            // cb * 16^[R4] = ca * 16^[L4] = 128, so both corrections are the sums shifted by 7
-            if (a.rhs_unsigned) s += (v4i){rs << 7, rs << 7, rs << 7, rs << 7};
-            if (a.lhs_unsigned) s += cs << 7;
-        }
-        if (R4) { s = s >> SH; lo = lo >> SH; }
-        if (U && a.lhs_unsigned && a.rhs_unsigned) {
-            const int cc = (LB == 4 ? 8 : 128) * (RB == 4 ? 8 : 128) * (nch * MC_CHUNK); // ca * cb * slots (padded ones included: their a' is -ca)
-            s += (v4i){cc, cc, cc, cc};
-        }
-        if (L16) { s = (s << 8) + lo; s2 = (s2 << 8) + lo2; rs = (rs << 8) + rs_lo; }
-        if (R16) {
-            // byte columns (low, high) of four B elements: A*b = (A*hi << 8) + A*(low ^ 0x80) + 128 * rowsum(A)
-            const int fix = rs << 7;
-            s = (v4i){(s.y << 8) + s.x + fix, (s.w << 8) + s.z + fix, (s2.y << 8) + s2.x + fix, (s2.w << 8) + s2.z + fix};
-        }
-        const int64_t off = (int64_t)batch * a.C_batch_stride + (int64_t)(panel * a.V + row) * a.ldc + gcol;
-        if (split && a.acc) {
-            // a shared panel whose final values are rounded: the exact partial sums meet in int32 rows of their own
-            int32_t *c = a.acc + (((int64_t)batch * a.n_split + (split - 1)) * a.V + row) * a.acc_ld + gcol;
-            atomicAdd(c, s.x); atomicAdd(c + 1, s.y); atomicAdd(c + 2, s.z); atomicAdd(c + 3, s.w);
-        } else if (a.float_out) {
-            const v4f f = {s.x * a.out_scale, s.y * a.out_scale, s.z * a.out_scale, s.w * a.out_scale};
-            if (a.float_out == 2) __builtin_nontemporal_store(mcu::to_half4(f), reinterpret_cast<mcu::v4h *>(static_cast<_Float16 *>(a.C) + off));
-            else __builtin_nontemporal_store(f, reinterpret_cast<v4f *>(static_cast<float *>(a.C) + off));
-        } else if (split) {
-            // several units own this panel: exact, order-independent integer accumulation into rows
-            // that were cleared before the launch
-            int32_t *c = static_cast<int32_t *>(a.C) + off;
-            atomicAdd(c, s.x); atomicAdd(c + 1, s.y); atomicAdd(c + 2, s.z); atomicAdd(c + 3, s.w);
-        } else {
-            __builtin_nontemporal_store(s, reinterpret_cast<v4i *>(static_cast<int32_t *>(a.C) + off));
+#pragma unroll
+        for (int q = 0; q < NPC; ++q) {
+            const int pc = tid + q * 64 * WK;
+            const int row = pc / (OUTC / 4) + 8 * hf, gcol = tile * OUTC + (pc % (OUTC / 4)) * 4;
+            const int crow = panel * a.V + row;              // row of C
+            if (pc >= PIECES || row >= a.V || crow >= a.rows || gcol >= ncols) continue;
+            const v4i s = fin[q];
+            const int64_t off = (int64_t)batch * a.C_batch_stride + (int64_t)crow * a.ldc + gcol;
+            if (split && a.acc) {
+                // a shared panel whose final values are rounded: the exact partial sums meet in int32 rows of their own
+                int32_t *c = a.acc + (((int64_t)batch * a.n_split + (split - 1)) * a.V + row) * a.acc_ld + gcol;
+                atomicAdd(c, s.x); atomicAdd(c + 1, s.y); atomicAdd(c + 2, s.z); atomicAdd(c + 3, s.w);
+            } else if (a.float_out) {
+                const v4f f = {s.x * a.out_scale, s.y * a.out_scale, s.z * a.out_scale, s.w * a.out_scale};
+                if (a.float_out == 2) __builtin_nontemporal_store(mcu::to_half4(f), reinterpret_cast<mcu::v4h *>(static_cast<_Float16 *>(a.C) + off));
+                else __builtin_nontemporal_store(f, reinterpret_cast<v4f *>(static_cast<float *>(a.C) + off));
+            } else if (split) {
+                // several units own this panel: exact, order-independent integer accumulation into rows
+                // that were cleared before the launch
+                int32_t *c = static_cast<int32_t *>(a.C) + off;
+                atomicAdd(c, s.x); atomicAdd(c + 1, s.y); atomicAdd(c + 2, s.z); atomicAdd(c + 3, s.w);
+            } else {
+                __builtin_nontemporal_store(s, reinterpret_cast<v4i *>(static_cast<int32_t *>(a.C) + off));
+            }
         }
     }
 }
 
-template <int BNB, int WK, int LB, int RB, bool U, int NS> hipError_t launch_one(const SpmmArgs &a, hipStream_t s)
+template <int BNB, int WK, int LB, int RB, bool U, int NS> hipError_t launch_one(SpmmArgs a, hipStream_t s)
 {
-    const int ntiles = (a.row_bytes + BNB - 1) / BNB;
-    dim3 grid((unsigned)((a.items ? a.n_units : a.P) * ntiles), (unsigned)a.batch), block(64 * WK);
+    a.ntiles = (a.row_bytes + BNB - 1) / BNB;
+    a.tile_shift = -1;
+    for (int sh = 0; sh < 31; ++sh)
+        if ((1 << sh) == a.ntiles) a.tile_shift = sh;
+    dim3 grid((unsigned)((a.items ? a.n_units : a.P) * a.ntiles), (unsigned)a.batch), block(64 * WK);
     hipLaunchKernelGGL((spmm_kernel<BNB, WK, LB, RB, U, NS>), grid, block, 0, s, a);
     return hipGetLastError();
 }

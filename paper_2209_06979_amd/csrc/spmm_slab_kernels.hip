@@ -71,6 +71,7 @@ __global__ __launch_bounds__(1024) void spmm_slab_kernel(SlabArgs a)
     if (grp >= a.groups) return;
     const int nb0 = tile * TILE_BYTES;
     const uint8_t *Bb = a.B + (int64_t)batch * a.B_batch_stride + nb0;
+    const int nhalf = (!L16 && a.V > 8) ? 2 : 1;          // halves of 8 rows a finished tile is staged in
     const int slots = a.nc / a.wpp;                       // panels in work at the same time per PPW
     const int per_pass = slots * PPW;
     const int npass = (a.ppg + per_pass - 1) / per_pass;
@@ -99,9 +100,10 @@ __global__ __launch_bounds__(1024) void spmm_slab_kernel(SlabArgs a)
                 // next iteration overwrites
                 asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
             }
-            // the output stage of the computing waves uses the buffers: 2 barriers per panel of a wave,
-            // one more before the next pass may fill again
-            for (int i = 0; i < 2 * PPW + (pass + 1 < npass ? 1 : 0); ++i) asm volatile("s_barrier" ::: "memory");
+            // the output stage of the computing waves uses the buffers: 2 barriers per panel of a wave and half of
+            // its rows (a one-plane operand of 16 rows is staged in two halves), one more before the next pass may
+            // fill again
+            for (int i = 0; i < 2 * PPW * nhalf + (pass + 1 < npass ? 1 : 0); ++i) asm volatile("s_barrier" ::: "memory");
         }
         return;
     }
@@ -214,40 +216,43 @@ __global__ __launch_bounds__(1024) void spmm_slab_kernel(SlabArgs a)
         // i.e. column 16ct + j (8-bit B) or columns 32ct + 2j, 2j+1 (4-bit B)
 #pragma unroll
         for (int i = 0; i < PPW; ++i) {
-            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); // the slab (or the previous panel's tiles) is no longer read
-            if (4 * g < OROWS) {
+            for (int hf = 0; hf < nhalf; ++hf) {
+                asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); // the slab (or the previous tiles) is no longer read
+                const int gg = g - 2 * hf;                // lane groups 2 hf, 2 hf + 1 hold rows 8 hf .. 8 hf + 7 of a one-plane tile
+                if (gg >= 0 && 4 * gg < OROWS) {
 #pragma unroll
-                for (int ct = 0; ct < 4; ++ct)
+                    for (int ct = 0; ct < 4; ++ct)
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        if (!R4) tile_w[(4 * g + r) * TST + ct * 16 + j] = acc[i][ct][r];
-                        else *reinterpret_cast<v2i *>(&tile_w[(4 * g + r) * TST + ct * 32 + 2 * j]) = (v2i){acc[i][2 * ct][r], acc[i][2 * ct + 1][r]};
-                    }
-            }
-            asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); // the staged tiles are complete
-            const int p = p_begin + slot + i * slots;
-            if (p < g_end) {
-                constexpr int PIECES = 8 * (COLS / 4);
-                for (int pc = k * 64 + lane; pc < PIECES; pc += 64 * a.wpp) {
-                    const int row = pc / (COLS / 4), col = (pc % (COLS / 4)) * 4;
-                    const int gcol = tile * COLS + col;
-                    if (row >= a.V || gcol >= ncols) continue;
-                    v4i s = {0, 0, 0, 0}, lo = {0, 0, 0, 0};
-                    for (int ww = 0; ww < a.wpp; ++ww) {
-                        const int *t = reinterpret_cast<const int *>(lds + (slot * a.wpp + ww) * Cfg::PERWAVE);
-                        s += *reinterpret_cast<const v4i *>(&t[row * TST + col]);
-                        if (L16) lo += *reinterpret_cast<const v4i *>(&t[(row + 8) * TST + col]);
-                    }
-                    // every plane sum is exact in int32 (4-bit B: after its shift); the recombination wraps
-                    if (R4) { s = s >> Cfg::SH; lo = lo >> Cfg::SH; }
-                    if (L16) s = (s << 8) + lo;
-                    const int64_t off = (int64_t)batch * a.C_batch_stride + (int64_t)(p * a.V + row) * a.ldc + gcol;
-                    if (a.float_out) {
-                        const v4f f = {s.x * a.out_scale, s.y * a.out_scale, s.z * a.out_scale, s.w * a.out_scale};
-                        if (a.float_out == 2) __builtin_nontemporal_store(mcu::to_half4(f), reinterpret_cast<mcu::v4h *>(static_cast<_Float16 *>(a.C) + off));
-                        else __builtin_nontemporal_store(f, reinterpret_cast<v4f *>(static_cast<float *>(a.C) + off));
-                    } else {
-                        __builtin_nontemporal_store(s, reinterpret_cast<v4i *>(static_cast<int32_t *>(a.C) + off));
+                        for (int r = 0; r < 4; ++r) {
+                            if (!R4) tile_w[(4 * gg + r) * TST + ct * 16 + j] = acc[i][ct][r];
+                            else *reinterpret_cast<v2i *>(&tile_w[(4 * gg + r) * TST + ct * 32 + 2 * j]) = (v2i){acc[i][2 * ct][r], acc[i][2 * ct + 1][r]};
+                        }
+                }
+                asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); // the staged tiles are complete
+                const int p = p_begin + slot + i * slots;
+                if (p < g_end) {
+                    constexpr int PIECES = 8 * (COLS / 4);
+                    for (int pc = k * 64 + lane; pc < PIECES; pc += 64 * a.wpp) {
+                        const int trow = pc / (COLS / 4), col = (pc % (COLS / 4)) * 4;
+                        const int row = trow + 8 * hf, gcol = tile * COLS + col;
+                        if (row >= a.V || p * a.V + row >= a.rows || gcol >= ncols) continue;
+                        v4i s = {0, 0, 0, 0}, lo = {0, 0, 0, 0};
+                        for (int ww = 0; ww < a.wpp; ++ww) {
+                            const int *t = reinterpret_cast<const int *>(lds + (slot * a.wpp + ww) * Cfg::PERWAVE);
+                            s += *reinterpret_cast<const v4i *>(&t[trow * TST + col]);
+                            if (L16) lo += *reinterpret_cast<const v4i *>(&t[(trow + 8) * TST + col]);
+                        }
+                        // every plane sum is exact in int32 (4-bit B: after its shift); the recombination wraps
+                        if (R4) { s = s >> Cfg::SH; lo = lo >> Cfg::SH; }
+                        if (L16) s = (s << 8) + lo;
+                        const int64_t off = (int64_t)batch * a.C_batch_stride + (int64_t)(p * a.V + row) * a.ldc + gcol;
+                        if (a.float_out) {
+                            const v4f f = {s.x * a.out_scale, s.y * a.out_scale, s.z * a.out_scale, s.w * a.out_scale};
+                            if (a.float_out == 2) __builtin_nontemporal_store(mcu::to_half4(f), reinterpret_cast<mcu::v4h *>(static_cast<_Float16 *>(a.C) + off));
+                            else __builtin_nontemporal_store(f, reinterpret_cast<v4f *>(static_cast<float *>(a.C) + off));
+                        } else {
+                            __builtin_nontemporal_store(s, reinterpret_cast<v4i *>(static_cast<int32_t *>(a.C) + off));
+                        }
                     }
                 }
             }

@@ -20,7 +20,7 @@ def _fields(o):
 
 
 def test_init_is_all_automatic():
-    o = mc.Options(1, 2, 3, 4, 5, 6, 7, 8, 9, 10)
+    o = mc.Options(1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11)
     mc.lib.mc_options_init(ctypes.byref(o))
     assert set(_fields(o).values()) == {0}
     assert set(_fields(mc.get_thread_options()).values()) == {0}
@@ -37,6 +37,7 @@ def test_init_is_all_automatic():
     ("sddmm_waves", [0, -1, 1, 2, 4, 8], [3, 16, -2]),
     ("softmax_variant", [0, 1, 2], [3, -1]),
     ("attention_mode", [0, 1, 2, 3, 4, 5, 6], [7, -1]),
+    ("spmm_merge", [-1, 0, 1], [2, -2]),
 ])
 def test_validation_of_every_field(field, good, bad):
     for v in good:
@@ -63,7 +64,8 @@ def test_one_knob_setters_fill_the_thread_defaults():
     mc.set_attention_mode(3)
     o = mc.get_thread_options()
     assert _fields(o) == dict(spmm_row_tile_bytes=64, spmm_waves=4, spmm_stages=1, spmm_splitting=-1, spmm_slab=0,
-                              spmm_slab_waves=0, spmm_slab_panels=0, sddmm_waves=-1, softmax_variant=2, attention_mode=3)
+                              spmm_slab_waves=0, spmm_slab_panels=0, sddmm_waves=-1, softmax_variant=2, attention_mode=3,
+                              spmm_merge=0)
     mc.set_sddmm_variant(-1)         # -1 = automatic
     mc.set_spmm_splitting(True)
     assert mc.get_thread_options().sddmm_waves == 0 and mc.get_thread_options().spmm_splitting == 0
