@@ -132,8 +132,11 @@ def main():
     ap.add_argument("--table", action="store_true",
                     help="with --sweep / --skew / --shapes: print a plain-text table instead of the JSON object")
     ap.add_argument("--point", default="",
-                    help="instead of the step: one SpMM configuration 'prec:V:sparsity:N:form' (form: gather, lds or auto) at "
+                    help="instead of the step: one SpMM configuration 'prec:V:sparsity:N:form' (form: gather, lds, merged, merged-lds or auto) at "
                          "4096 x 4096, launched --steps times one by one (for counter and trace collection), e.g. L8R8:2:0.5:512:lds")
+    ap.add_argument("--phases", action="store_true",
+                    help="instead of the step: the headline L8-R8 SpMM run through the instrumented copy of its kernel "
+                         "(mc_probe_spmm_phases); prints when its waves reach each stage of the kernel")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 64 MiB device copy, the known-size kernel that scales FETCH_SIZE / WRITE_SIZE")
     args = ap.parse_args()
@@ -150,8 +153,9 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 
-    if args.sweep or args.skew or args.shapes:
-        result = run_sweep(mc, torch) if args.sweep else (run_skew(mc, torch) if args.skew else run_shapes(mc, torch))
+    if args.sweep or args.skew or args.shapes or args.phases:
+        result = (run_sweep(mc, torch) if args.sweep else run_skew(mc, torch) if args.skew else
+                  run_shapes(mc, torch) if args.shapes else run_phases(mc, torch))
         print(as_table(result) if args.table else json.dumps(result))
         return
     if args.point:
@@ -367,13 +371,16 @@ def main():
 def run_sweep(mc, torch):
     """The grids of the SpMM and SDDMM precision sweeps (Section 5.2 figures' shapes: vector lengths, sparsities,
     widths of the dense operand, precisions) on seeded synthetic 4096 x 4096 patterns, warm caches.  Every SpMM point
-    is timed three ways: rows of B gathered per stored vector (`gather_us`), K-blocks of B resident in LDS (`lds_us`,
-    null where that form does not exist: two-plane right operands, more than 63 K-blocks) and what the library picks
-    by itself (`us`, `form`)."""
+    is timed on the operand as given -- rows of B gathered per stored vector (`gather_us`), K-blocks of B resident in
+    LDS (`lds_us`, null where that form does not exist: two-plane right operands, more than 63 K-blocks) -- on its
+    merged copy (`merged_gather_us`, `merged_lds_us`: consecutive panels sharing one panel of 16 or 8 rows; null
+    where there is nothing to merge) and as the library picks by itself (`us`, `form`, `merged`);
+    `auto_over_best` = us / the fastest of the pinned forms."""
     from paper_2209_06979_amd import workloads as wl
     stream = torch.cuda.Stream()
     spmm, sddmm = [], []
-    gather_only, lds_forced = mc.Options(spmm_slab=-1), mc.Options(spmm_slab=1)
+    gather_only, lds_forced = mc.Options(spmm_slab=-1, spmm_merge=-1), mc.Options(spmm_slab=1, spmm_merge=-1)
+    m_gather, m_lds, build_all = mc.Options(spmm_slab=-1, spmm_merge=1), mc.Options(spmm_slab=1, spmm_merge=1), mc.Options(spmm_slab=1, spmm_merge=1)
     with torch.cuda.stream(stream):
         for prec in ("L8R8", "L8R4", "L4R4", "L16R8"):
             for Vv in (2, 4, 8):
@@ -383,7 +390,7 @@ def run_sweep(mc, torch):
                             continue     # the mixed-precision configuration: V = 8, N = 256
                         c = wl.spmm_case(M, K, N, Vv, s, prec, wl.seed_for(2, 1))
                         A = mc.SparseMatrix(M, K, Vv, c["row_ptr"], c["col_idx"], c["values"], mc.LHS_BITS[prec])
-                        mc.set_thread_options(lds_forced)      # the creating thread's option: build the K-blocked copy anyway
+                        mc.set_thread_options(build_all)       # the creating thread's options: build the K-blocked and merged copies anyway
                         Af = mc.SparseMatrix(M, K, Vv, c["row_ptr"], c["col_idx"], c["values"], mc.LHS_BITS[prec])
                         mc.set_thread_options(None)
                         B = torch.from_numpy(c["B"]).cuda()
@@ -393,9 +400,18 @@ def run_sweep(mc, torch):
                         l_us = None
                         if mc.spmm_form(Af, N, prec, lds_forced) == "lds":
                             l_us = time_graph(torch, stream, [lambda: mc.spmm(Af, B, prec, out=C, options=lds_forced)] * 50, rounds=3)
+                        mg_us = ml_us = None
+                        if Af.merge_group:
+                            mg_us = time_graph(torch, stream, [lambda: mc.spmm(Af, B, prec, out=C, options=m_gather)] * 50, rounds=3)
+                            if mc.spmm_form(Af, N, prec, m_lds) == "lds":
+                                ml_us = time_graph(torch, stream, [lambda: mc.spmm(Af, B, prec, out=C, options=m_lds)] * 50, rounds=3)
                         gathered = A.nvec * N * mc.RHS_BITS[prec] / 8
+                        r2 = lambda x: round(x, 2) if x is not None else None
                         spmm.append(dict(prec=prec, V=Vv, s=s, N=N, us=round(us, 2), form=mc.spmm_form(A, N, prec),
-                                         gather_us=round(g_us, 2), lds_us=(round(l_us, 2) if l_us is not None else None),
+                                         merged=int(mc.spmm_on_merged(A, N, prec)),
+                                         gather_us=round(g_us, 2), lds_us=r2(l_us), merged_gather_us=r2(mg_us), merged_lds_us=r2(ml_us),
+                                         auto_over_best=round(us / min(x for x in (g_us, l_us, mg_us, ml_us) if x is not None), 3),
+                                         nvec=A.nvec, merged_nvec=(Af.merged_nvec if Af.merge_group else None),
                                          eff_tops=round(2 * A.nvec * Vv * N / us / 1e6, 1),
                                          gather_tbs=round(gathered / g_us / 1e6, 2)))
                         A.close()
@@ -435,9 +451,10 @@ def run_point(mc, torch, spec, steps, warmup, calib_copy):
     from paper_2209_06979_amd import workloads as wl
     prec, Vv, s, N, form = spec.split(":")
     Vv, s, N = int(Vv), float(s), int(N)
-    o = {"gather": mc.Options(spmm_slab=-1), "lds": mc.Options(spmm_slab=1), "auto": None}[form]
+    o = {"gather": mc.Options(spmm_slab=-1, spmm_merge=-1), "lds": mc.Options(spmm_slab=1, spmm_merge=-1),
+         "merged": mc.Options(spmm_slab=-1, spmm_merge=1), "merged-lds": mc.Options(spmm_slab=1, spmm_merge=1), "auto": None}[form]
     c = wl.spmm_case(M, K, N, Vv, s, prec, wl.seed_for(2, 1))
-    if form == "lds":
+    if form != "auto":
         mc.set_thread_options(o)
     A = mc.SparseMatrix(M, K, Vv, c["row_ptr"], c["col_idx"], c["values"], mc.LHS_BITS[prec])
     mc.set_thread_options(None)
@@ -453,9 +470,50 @@ def run_point(mc, torch, spec, steps, warmup, calib_copy):
     for _ in range(steps):
         mc.spmm(A, B, prec, out=C, options=o)
     torch.cuda.synchronize()
-    return dict(point=spec, form_run=mc.spmm_form(A, N, prec, o), launches=steps,
+    return dict(point=spec, form_run=mc.spmm_form(A, N, prec, o), on_merged_copy=mc.spmm_on_merged(A, N, prec, o), launches=steps,
                 us_per_launch_eager=round((time.perf_counter() - t0) / steps * 1e6, 2), nvec=A.nvec,
                 gathered_bytes=int(A.nvec * N * mc.RHS_BITS[prec] // 8), library=mc.lib.mc_version().decode())
+
+
+def run_phases(mc, torch):
+    """Where the time of the headline SpMM goes: the same kernel with ten clock readings per wave (mc_probe_spmm_phases),
+    launched back to back like the timed kernel; the readings of the last launches, relative to the first wave's start."""
+    from paper_2209_06979_amd import workloads as wl
+    c = wl.spmm_case(M, K, 256, V, SPARSITY, "L8R8", wl.seed_for(2, 1))
+    A = mc.SparseMatrix(M, K, V, c["row_ptr"], c["col_idx"], c["values"], 8)
+    B = torch.from_numpy(c["B"]).cuda()
+    ref = mc.spmm(A, B, "L8R8", options=mc.Options(spmm_merge=-1, spmm_slab=-1))
+    stream = torch.cuda.Stream()
+    names = ["wave started", "kernel arguments and panel pointers arrived", "column indices and A operands arrived",
+             "rows of the first chunk landed", "all chunks in the accumulators", "partial tile written",
+             "workgroup barrier passed", "output pieces summed", "stores issued", "stores acknowledged"]
+    samples = []
+    with torch.cuda.stream(stream):
+        plain_us = time_graph(torch, stream, [lambda: mc.spmm(A, B, "L8R8", out=ref)] * 100, rounds=3, warm_ms=25.0)
+        out, trace = mc.probe_spmm_phases(A, B)
+        probe_us = time_graph(torch, stream, [lambda: mc.probe_spmm_phases(A, B, out=out, trace=trace)] * 100, rounds=3)
+        for _ in range(5):
+            for _ in range(20):
+                mc.probe_spmm_phases(A, B, out=out, trace=trace)
+            stream.synchronize()
+            samples.append(trace.cpu().numpy().astype(np.int64) * 0.01)      # 100 MHz ticks -> microseconds
+    assert torch.equal(out, ref), "the instrumented kernel's product differs"
+    rows = []
+    spans = [float((t[:, 9].max() - t[:, 0].min())) for t in samples]
+    t = samples[int(np.argsort(spans)[len(spans) // 2])]                       # the launch with the median span
+    rel = t - t[:, 0].min()
+    for k, n in enumerate(names):
+        col = rel[:, k]
+        rows.append(dict(stage=n, first=round(float(col.min()), 2), p10=round(float(np.percentile(col, 10)), 2),
+                         median=round(float(np.median(col)), 2), p90=round(float(np.percentile(col, 90)), 2),
+                         last=round(float(col.max()), 2),
+                         median_since_previous_stage=(round(float(np.median(t[:, k] - t[:, k - 1])), 2) if k else 0.0)))
+    A.close()
+    return {"phases": "SpMM L8-R8 4096x4096 V=8 s=0.9 N=256, kernel spmm_kernel<128,2,8,8,false,2> with time stamps; microseconds "
+                      "after the first wave of the launch started; one launch (the median of 5 by span) of 2048 waves",
+            "library": mc.lib.mc_version().decode(), "us_per_launch_plain_kernel": round(plain_us, 2),
+            "us_per_launch_instrumented_kernel": round(probe_us, 2),
+            "span_first_start_to_last_store_us": [round(x, 2) for x in sorted(spans)], "waves": rows}
 
 
 def lognormal_counts(P, mean, sigma, Kcols, rng):
@@ -802,7 +860,7 @@ def measure_extras(mc, torch, prob, stream, reps, up):
     for name, (Ax, Bx, Cx) in (("headline_4096x4096_s0.9_N256", (A, B, C32)), ("section5.1_shape_256x2304_s0.7_N512", (A2, B2, C2))):
         row = {}
         for step, (tile, waves, stages) in (("plain", (64, 1, 1)), ("tile_and_waves_chosen", (0, 0, 1)), ("two_chunks_in_flight", (0, 0, 2))):
-            o = mc.Options(spmm_row_tile_bytes=tile, spmm_waves=waves, spmm_stages=stages, spmm_slab=-1)
+            o = mc.Options(spmm_row_tile_bytes=tile, spmm_waves=waves, spmm_stages=stages, spmm_slab=-1, spmm_merge=-1)
             row[step + "_us"] = round(time_graph(torch, stream, [lambda: mc.spmm(Ax, Bx, "L8R8", out=Cx, options=o)] * reps), 2)
         row["automatic_us"] = round(time_graph(torch, stream, [lambda: mc.spmm(Ax, Bx, "L8R8", out=Cx)] * reps), 2)
         row["automatic_form"] = mc.spmm_form(Ax, Bx.shape[1], "L8R8")

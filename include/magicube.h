@@ -296,6 +296,22 @@ int64_t mc_probe_gather_sink_len(const mc_mat *A, int N, mc_prec prec);
 int mc_probe_gather(const mc_mat *A, const void *B_dev, int N, int ldb, mc_prec prec, int32_t *sink_dev,
                     void *stream);
 
+/* Measurement aid (the paper's Algorithm 1 and Section 4.2.4 are about hiding the latency between the steps of
+ * one thread block; this shows where that latency sits here): the L8-R8 SpMM kernel on 128-byte row tiles, two
+ * waves per panel, two chunks in flight -- the form the 4096 x 4096, 90 % sparse, N = 256 problem runs in --
+ * computes C exactly as mc_spmm does and also records, per wave, ten readings of the device's constant 100 MHz
+ * clock: 0 wave started, 1 kernel arguments and panel pointers arrived, 2 column indices and A operands arrived
+ * (first row copies issued next), 3 rows of the wave's first chunk landed, 4 all chunks in the accumulators,
+ * 5 partial tile written, 6 workgroup barrier passed, 7 the thread's output pieces summed, 8 stores issued,
+ * 9 stores acknowledged.
+ *   trace_dev  int64 array of mc_probe_spmm_phases_len(A, N) entries: wave w of workgroup g (= panel *
+ *              tiles + tile) writes entries (2 g + w) * 10 .. + 9
+ * MC_EUNSUPPORTED unless A holds 8-bit values in panels of at most 8 chunks, none of them cut into work
+ * items, and B spans less than 4 GiB with rows below 16 MiB.  Other checks as mc_spmm. */
+int64_t mc_probe_spmm_phases_len(const mc_mat *A, int N);
+int mc_probe_spmm_phases(const mc_mat *A, const void *B_dev, int N, int ldb, int32_t *C_dev, int ldc, int64_t *trace_dev,
+                         void *stream);
+
 /* Measurement aid (Section 5 reports its kernels against the peak of the matrix unit): the matrix unit
  * alone.  `workgroups` workgroups of four waves each issue iters * 8 independent 16x16x64 int8 MFMAs on
  * registers, i.e. workgroups * 4 * iters * 8 * 32768 operations without any memory traffic; timing it gives

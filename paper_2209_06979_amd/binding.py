@@ -112,6 +112,8 @@ def _load() -> ctypes.CDLL:
     L.mc_merged_query.argtypes = [c_int, c_int, c_int, c_int, i32p, i32p, c_int, POINTER(MergedLayout)]
     L.mc_merge_host.argtypes = [c_int, c_int, c_int, c_int, i32p, i32p, c_void_p, c_int, i32p, i32p, c_void_p, i32p]
     L.mc_probe_mfma.argtypes = [c_int, c_int, c_void_p, c_void_p]
+    L.mc_probe_spmm_phases_len.argtypes = [c_void_p, c_int]; L.mc_probe_spmm_phases_len.restype = c_int64
+    L.mc_probe_spmm_phases.argtypes = [c_void_p, c_void_p, c_int, c_int, c_void_p, c_int, c_void_p, c_void_p]
     L.mc_sddmm_to_mat.argtypes = [c_void_p, c_int, c_void_p, c_int, c_int, c_int, c_float, c_void_p, c_void_p]
     L.mc_absmax.argtypes = [c_void_p, c_int64, c_void_p, c_void_p]
     L.mc_quantize.argtypes = [c_void_p, c_int64, c_float, c_int, c_void_p, c_void_p]
@@ -142,7 +144,7 @@ def _load() -> ctypes.CDLL:
                  "mc_set_spmm_variant", "mc_set_attention_mode", "mc_set_sddmm_variant", "mc_set_spmm_splitting", "mc_set_spmm_stages",
                  "mc_set_softmax_variant", "mc_set_thread_options", "mc_get_thread_options", "mc_spmm_ex", "mc_sddmm_ex",
                  "mc_sparse_attention_ex", "mc_sparse_attention_static", "mc_blocked_query", "mc_pack_blocked_host", "mc_sddmm_to_mat", "mc_probe_mfma", "mc_spmm_form",
-                 "mc_mat_merged_info", "mc_merged_query", "mc_merge_host"):
+                 "mc_mat_merged_info", "mc_merged_query", "mc_merge_host", "mc_probe_spmm_phases"):
         getattr(L, name).restype = c_int
     return L
 
@@ -391,6 +393,20 @@ def probe_gather(A: SparseMatrix, B, prec: str, sink=None):
     _check(lib.mc_probe_gather(A.handle, B.data_ptr(), N, B.stride(0) * B.element_size() * 8 // rbits, PREC[prec],
                                sink.data_ptr(), _stream()), "mc_probe_gather")
     return sink
+
+
+def probe_spmm_phases(A: SparseMatrix, B, out=None, trace=None):
+    """The L8-R8 SpMM in its 128-byte-tile, two-wave, two-chunks-in-flight form with ten clock readings per wave
+    (a measurement aid); returns (C, trace) with trace an int64 tensor of shape (waves, 10), 100 MHz ticks."""
+    assert B.is_cuda and B.dim() == 2 and B.stride(1) == 1 and B.element_size() == 1
+    N = B.shape[1]
+    if out is None:
+        out = torch.empty((A.M, N), dtype=torch.int32, device=B.device)
+    if trace is None:
+        trace = torch.zeros((int(lib.mc_probe_spmm_phases_len(A.handle, N)) // 10, 10), dtype=torch.int64, device=B.device)
+    _check(lib.mc_probe_spmm_phases(A.handle, B.data_ptr(), N, B.stride(0), out.data_ptr(), out.stride(0), trace.data_ptr(),
+                                    _stream()), "mc_probe_spmm_phases")
+    return out, trace
 
 
 def probe_mfma(workgroups: int, iters: int, sink=None):

@@ -644,7 +644,13 @@ bool plan_slab(const mc_mat *A, int row_bytes, bool r4, int batch, const mc_opti
 bool slab_pays(const mc_mat *A, int row_bytes, bool r4, int batch, const SlabPlan &pl)
 {
     const double T = (double)((row_bytes + 63) / 64);
-    const double t_gather = (r4 ? 3.88 : 3.96) + (double)A->nvec * row_bytes * batch / (r4 ? 13.99e6 : 22.13e6);
+    double t_gather = (r4 ? 3.88 : 3.96) + (double)A->nvec * row_bytes * batch / (r4 ? 13.99e6 : 22.13e6);
+    if (A->V == 16) {
+        // merged copies (16-row panels, fewer and longer): the gather form fitted on the merged operands of the same sweep
+        const double t0 = r4 ? 3.9 : (row_bytes >= 512 ? 4.4 : 3.3);
+        const double rate = r4 ? (row_bytes == 128 ? 10.0e6 : 12.5e6) : (row_bytes >= 512 ? 20.5e6 : 17.7e6);
+        t_gather = t0 + (double)A->nvec * row_bytes * batch / rate;
+    }
     const double steps = (double)A->blk_chunks * T * batch / 256.0;
     const double rounds = std::max(1.0, std::ceil((double)pl.workgroups / 256.0) / ((double)pl.workgroups / 256.0));
     const double t_slab = (r4 ? 0.47 : 2.05) + (pl.passes * (r4 ? 2.12 : 1.98) * A->nblk + (r4 ? 0.0417 : 0.01565) * steps) * rounds;
@@ -810,6 +816,33 @@ extern "C" int mc_probe_gather(const mc_mat *A, const void *B_dev, int N, int ld
     int bnb, waves;
     choose_variant(A, A->lhs_bits, a.row_bytes, rb == 4, 1, A->max_panel_chunks, o, &bnb, &waves);
     MC_HIP(launch_gather_probe(a, bnb, waves, sink_dev, static_cast<hipStream_t>(stream)));
+    return MC_OK;
+}
+
+extern "C" int64_t mc_probe_spmm_phases_len(const mc_mat *A, int N)
+{
+    if (!A || N <= 0) return 0;
+    return (int64_t)A->P * ((N + 127) / 128) * 2 * 10;
+}
+
+extern "C" int mc_probe_spmm_phases(const mc_mat *A, const void *B_dev, int N, int ldb, int32_t *C_dev, int ldc, int64_t *trace_dev,
+                                    void *stream)
+{
+    if (!A || !B_dev || !C_dev || !trace_dev) return MC_EINVAL;
+    if (N <= 0 || N % 16 != 0 || ldb < N || ldc < N) return MC_EINVAL;
+    if (ldb % 16 != 0 || ldc % 4 != 0 || !aligned16(B_dev) || !aligned16(C_dev)) return MC_EALIGN;
+    if (!on_device_of(A)) return MC_EINVAL;
+    const mc_options automatic = {};
+    if (A->lhs_bits != 8 || !A->d_vals || A->max_panel_chunks > 2 * 4 || spmm_stages_for(automatic, A->K, ldb, N) != 2)
+        return MC_EUNSUPPORTED;
+    SpmmArgs a = {};
+    a.panel_ptr = A->d_panel_ptr; a.slot_idx = A->d_slot_idx; a.vals = A->d_vals;
+    a.B = static_cast<const uint8_t *>(B_dev); a.ldb_bytes = ldb; a.row_bytes = N;
+    a.C = C_dev; a.ldc = ldc;
+    a.P = A->P; a.V = A->V; a.rows = A->M; a.batch = 1; a.out_scale = 1.f;
+    a.stages = 2; a.max_unit_chunks = A->max_panel_chunks;
+    a.trace = reinterpret_cast<long long *>(trace_dev);
+    MC_HIP(launch_spmm_phase_probe(a, static_cast<hipStream_t>(stream)));
     return MC_OK;
 }
 

@@ -84,6 +84,7 @@ struct SpmmArgs {
     // half): cleared rows [batch][split panel][V][acc_ld], finished by launch_finish_split_rows
     int32_t *acc;
     int acc_ld, n_split;
+    long long *trace;          // measurement aid (launch_spmm_phase_probe only): time stamps per wave
 };
 
 // One launch of the SpMM that keeps K-blocks of B resident in LDS (see spmm_slab_kernels.hip).
@@ -190,6 +191,9 @@ struct AttnArgs {
 };
 
 hipError_t launch_spmm(mc_prec prec, const SpmmArgs &a, int bnb, int waves, hipStream_t s);
+// the L8-R8 SpMM (128-byte tiles, 2 waves per panel, two chunks in flight; every panel at most 8 chunks, whole panels,
+// B below 4 GiB) with 10 time stamps per wave written to a.trace
+hipError_t launch_spmm_phase_probe(const SpmmArgs &a, hipStream_t s);
 // ppw: panels per computing wave (1, 2 or 4; 4 only with an 8-bit B).  Precisions with a 16-bit B are not built.
 hipError_t launch_spmm_slab(mc_prec prec, const SlabArgs &a, int ppw, hipStream_t s);
 hipError_t launch_repack_blocked(const int32_t *blk_src, const uint8_t *src, uint8_t *dst, int64_t nchunks, int V, int bits,

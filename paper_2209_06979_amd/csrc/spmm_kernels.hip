@@ -93,10 +93,26 @@ template <int BNB, int WK, int LB, int RB, bool U = false, int NS = 1> struct Sp
     }
 };
 
-template <int BNB, int WK, int LB, int RB, bool U = false, int NS = 1>
+// Time stamps of a wave's progress (measurement aid: TR is true in one instantiation only, which
+// mc_probe_spmm_phases launches; every other kernel carries none of this).  Ticks of the constant 100 MHz clock.
+template <bool TR> struct PhaseClock {
+    long long t[TR ? 10 : 1] = {};
+    __device__ __forceinline__ void stamp(int k)
+    {
+        if constexpr (TR) {
+            __builtin_amdgcn_sched_barrier(0);
+            t[k] = wall_clock64();
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+};
+
+template <int BNB, int WK, int LB, int RB, bool U = false, int NS = 1, bool TR = false>
 __global__ __launch_bounds__(64 * WK) void spmm_kernel(SpmmArgs a)
 {
     using Cfg = SpmmCfg<BNB, WK, LB, RB, U, NS>;
+    PhaseClock<TR> clk;
+    clk.stamp(0);                                        // the wave has started
     constexpr int LPR = Cfg::LPR, NI = Cfg::NI, RPI = Cfg::RPI, NACC = Cfg::NACC, COLS = Cfg::COLS, TST = Cfg::TST;
     constexpr int OUTC = Cfg::OUTC;
     constexpr bool R4 = Cfg::R4, R16 = Cfg::R16, L16 = Cfg::L16;
@@ -121,6 +137,10 @@ __global__ __launch_bounds__(64 * WK) void spmm_kernel(SpmmArgs a)
     }
     const v2i pp = *reinterpret_cast<const v2i *>(a.panel_ptr + 2 * panel); // first slot, end slot: one load
     const int s0 = pp.x, s1 = pp.y;
+    if constexpr (TR) {
+        asm volatile("" ::"s"(s0), "s"(s1));             // (the stamp waits for the pointers)
+        clk.stamp(1);                                    // kernel arguments and panel pointers have arrived
+    }
     if (ce < 0) ce = (s1 - s0 + MC_CHUNK - 1) / MC_CHUNK;
     const int nch = ce - cb;                       // chunks of this unit: cb .. ce-1
     const int64_t chunk0 = s0 / MC_CHUNK + cb;
@@ -255,6 +275,8 @@ __global__ __launch_bounds__(64 * WK) void spmm_kernel(SpmmArgs a)
             for (int i = 0; i < NI; ++i)
                 mcu::copy16_to_lds(Bb, __umul24((unsigned)ixs[i >> 2][i & 3], ldb32) + (unsigned)segoff[i], stage_u + st * Cfg::STAGE + i * 1024);
         };
+        clk.stamp(2);                                    // column indices and A operands have arrived
+        if (nmy == 0) clk.stamp(3);                      // (a wave without chunks waits for no rows)
         if (nmy > 0) issue(0, ix[0]);
         mcu::static_for<MAXL>([&](auto Lc) {
             constexpr int l = decltype(Lc)::value;
@@ -265,6 +287,7 @@ __global__ __launch_bounds__(64 * WK) void spmm_kernel(SpmmArgs a)
                 } else {
                     mcu::vm_wait<0>();
                 }
+                if (l == 0) clk.stamp(3);                // the rows of the wave's first chunk have landed
                 compute(stage + (l & 1) * Cfg::STAGE, av[l]);
                 mcu::lgkm_wait(); // the reads of this stage have returned before it is refilled
             }
@@ -277,6 +300,7 @@ __global__ __launch_bounds__(64 * WK) void spmm_kernel(SpmmArgs a)
     // A one-plane operand of 16 rows (the merged copy of an operand) passes through the tile in two
     // halves of 8 rows: lane groups 0, 1 first, then 2, 3.
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    clk.stamp(4);                                        // all chunks of the wave are in its accumulators
     int *tile_w = reinterpret_cast<int *>(stage);
     constexpr int OROWS = Cfg::OROWS;
     constexpr int SH = R4 ? (LB == 4 ? 8 : 4) : 0;       // scale carried by widened nibbles
@@ -300,7 +324,9 @@ __global__ __launch_bounds__(64 * WK) void spmm_kernel(SpmmArgs a)
                 for (int r = 0; r < 4; ++r) tile_w[(4 * gg + r) * TST + COLS] = acc[XACC][r];
             }
         }
+        if (hf == 0) clk.stamp(5);                       // partial tile written
         __syncthreads();
+        if (hf == 0) clk.stamp(6);                       // the other waves' tiles are there too
 
         // ---- sum over the waves, finish the arithmetic, store 16 bytes per thread -------------
         // Every plane sum is exact in int32 (R4: after its shift); the recombinations wrap.
@@ -350,6 +376,12 @@ __global__ __launch_bounds__(64 * WK) void spmm_kernel(SpmmArgs a)
             }
             fin[q] = s;
         }
+        if constexpr (TR) {
+            if (hf == 0) {
+                asm volatile("" ::"v"(fin[0]), "v"(fin[NPC - 1]));
+                clk.stamp(7);                            // this thread's pieces are summed
+            }
+        }
 #pragma unroll
         for (int q = 0; q < NPC; ++q) {
             const int pc = tid + q * 64 * WK;
@@ -374,6 +406,16 @@ __global__ __launch_bounds__(64 * WK) void spmm_kernel(SpmmArgs a)
             } else {
                 __builtin_nontemporal_store(s, reinterpret_cast<v4i *>(static_cast<int32_t *>(a.C) + off));
             }
+        }
+    }
+    if constexpr (TR) {
+        clk.stamp(8);                                    // stores issued
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        clk.stamp(9);                                    // stores acknowledged
+        if (a.trace && lane == 0) {
+            long long *t = a.trace + ((int64_t)blockIdx.x * WK + w) * 10;
+#pragma unroll
+            for (int q = 0; q < 10; ++q) t[q] = clk.t[q];
         }
     }
 }
@@ -484,6 +526,20 @@ hipError_t launch_zero_rows(int32_t *C, int64_t ldc, int n, int V, const int32_t
 {
     if (n_panels == 0 || n == 0) return hipSuccess;
     hipLaunchKernelGGL(zero_rows_kernel, dim3((unsigned)n_panels), dim3(256), 0, s, C, ldc, n, V, panels);
+    return hipGetLastError();
+}
+
+// The L8-R8 kernel on 128-byte tiles with two waves per panel and two chunks in flight, instrumented with time stamps
+// (see PhaseClock): a.trace receives 10 stamps per wave, wave w of workgroup g at (g * 2 + w) * 10.
+hipError_t launch_spmm_phase_probe(const SpmmArgs &a, hipStream_t s)
+{
+    if (a.P == 0 || a.row_bytes == 0) return hipSuccess;
+    SpmmArgs b = a;
+    b.ntiles = (a.row_bytes + 127) / 128;
+    b.tile_shift = -1;
+    for (int sh = 0; sh < 31; ++sh)
+        if ((1 << sh) == b.ntiles) b.tile_shift = sh;
+    hipLaunchKernelGGL((spmm_kernel<128, 2, 8, 8, false, 2, true>), dim3((unsigned)(a.P * b.ntiles)), dim3(128), 0, s, b);
     return hipGetLastError();
 }
 

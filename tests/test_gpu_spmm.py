@@ -192,6 +192,34 @@ def test_few_panels_take_narrow_tiles(prec, M, K, N, s):
     _check(wl.spmm_case(M, K, N, 8, s, prec, 7100 + M))
 
 
+def test_phase_probe_computes_the_product_and_stamps_every_wave_in_order():
+    """The instrumented instantiation of the SpMM kernel: the same product as the oracle's, and per wave ten clock
+    readings that never run backwards; operands outside its one kernel form are refused."""
+    import torch
+    from paper_2209_06979_amd import binding as mc
+    V, K, N = 8, 900, 320                                      # 2.5 tiles of 128 bytes
+    counts = [0, 1, 63, 64, 65, 129, 300, 512, 7, 0, 450]
+    M = V * len(counts)
+    rp, ci = wl.ragged_pattern(M, K, V, counts, 181)
+    c = dict(M=M, K=K, N=N, V=V, prec="L8R8", row_ptr=rp, col_idx=ci, values=wl.uniform_int8((len(ci), V), 182),
+             B=wl.uniform_int8((K, N), 183))
+    A = mc.SparseMatrix(M, K, V, rp, ci, c["values"], 8)
+    out = torch.full((M, N), -7777777, dtype=torch.int32, device="cuda")
+    _, trace = mc.probe_spmm_phases(A, torch.from_numpy(c["B"]).cuda(), out=out)
+    torch.cuda.synchronize()
+    A.close()
+    assert np.array_equal(out.cpu().numpy(), run_spmm_oracle(c))
+    t = trace.cpu().numpy()
+    assert t.shape == (len(counts) * 3 * 2, 10) and (t > 0).all()
+    assert (np.diff(t, axis=1) >= 0).all()
+    assert t.max() - t.min() < 100_000                         # all within a millisecond of each other (100 MHz ticks)
+    long_panels = mc.SparseMatrix(8, K, V, [0, 600], np.arange(600, dtype=np.int32), wl.uniform_int8((600, V), 184), 8)
+    with pytest.raises(mc.MagicubeError) as e:                 # 10 chunks: more than two waves keep in flight
+        mc.probe_spmm_phases(long_panels, torch.from_numpy(c["B"]).cuda())
+    assert e.value.status == mc.MC_EUNSUPPORTED
+    long_panels.close()
+
+
 @pytest.mark.parametrize("bnb,waves", [(64, 1), (128, 2), (256, 4)])
 def test_gather_probe_fetches_the_rows_spmm_would(bnb, waves):
     """The gather-only measurement kernel: every workgroup reports the first word of its staged rows."""

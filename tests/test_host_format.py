@@ -175,6 +175,9 @@ def test_entry_points_reject_bad_arguments_before_touching_the_gpu():
     assert L.mc_set_sddmm_variant(3) == mc.MC_EINVAL and L.mc_set_sddmm_variant(-1) == mc.MC_OK
     assert L.mc_attention_workspace_bytes_bits(4, None, 8) == 0
     assert L.mc_probe_gather_sink_len(None, 16, 0) == 0
+    assert L.mc_probe_spmm_phases_len(None, 16) == 0
+    assert L.mc_probe_spmm_phases(None, None, 16, 16, None, 16, None, None) == mc.MC_EINVAL
+    assert L.mc_mat_merged_info(None, None, None) == mc.MC_EINVAL
 
 
 # ---- K-blocked variant of the format --------------------------------------------------------
