@@ -316,10 +316,13 @@ int mat_create_impl(int M, int K, int V, int lhs_bits, const int32_t *row_ptr, c
     A->M = M; A->K = K; A->V = V; A->lhs_bits = lhs_bits; A->P = lay.P;
     A->nvec = lay.nvec; A->nslots = lay.nslots; A->vals_bytes = lay.vals_bytes;
     A->max_panel_chunks = 0;
+    int min_panel_chunks = INT32_MAX;
     for (int p = 0; p < lay.P; ++p) {
         const int c = (row_ptr[p + 1] - row_ptr[p] + MC_CHUNK - 1) / MC_CHUNK;
         if (c > A->max_panel_chunks) A->max_panel_chunks = c;
+        if (c < min_panel_chunks) min_panel_chunks = c;
     }
+    A->uniform_chunks = (lay.P > 0 && min_panel_chunks == A->max_panel_chunks && min_panel_chunks > 0) ? min_panel_chunks : 0;
     A->d_panel_ptr = A->d_row_ptr = A->d_slot_idx = nullptr;
     A->d_vals = nullptr;
     A->d_items = A->d_split_panels = nullptr;
@@ -733,6 +736,7 @@ int spmm_impl(const mc_mat *A, const void *B_dev, int N, int ldb, mc_prec prec, 
         }
     }
     a.stages = spmm_stages_for(o, A->K, a.ldb_bytes, a.row_bytes);
+    a.uniform_chunks = A->uniform_chunks;
     a.max_unit_chunks = A->max_panel_chunks;
     const bool use_items = A->n_items && o.spmm_splitting != -1 && out_mode == 0;
     if (use_items) a.max_unit_chunks = A->max_item_chunks;
@@ -840,7 +844,7 @@ extern "C" int mc_probe_spmm_phases(const mc_mat *A, const void *B_dev, int N, i
     a.B = static_cast<const uint8_t *>(B_dev); a.ldb_bytes = ldb; a.row_bytes = N;
     a.C = C_dev; a.ldc = ldc;
     a.P = A->P; a.V = A->V; a.rows = A->M; a.batch = 1; a.out_scale = 1.f;
-    a.stages = 2; a.max_unit_chunks = A->max_panel_chunks;
+    a.stages = 2; a.max_unit_chunks = A->max_panel_chunks; a.uniform_chunks = A->uniform_chunks;
     a.trace = reinterpret_cast<long long *>(trace_dev);
     MC_HIP(launch_spmm_phase_probe(a, static_cast<hipStream_t>(stream)));
     return MC_OK;
@@ -1104,6 +1108,7 @@ int attention_pipeline(const uint8_t *Q, const uint8_t *Km, const uint8_t *Vm, i
     m.row_bytes = row_bytes; m.C = O; m.ldc = o_token_stride; m.C_batch_stride = o_head_stride;
     m.P = mask->P; m.V = 8; m.rows = mask->M; m.batch = heads; m.float_out = out_f16 ? 2 : 1; m.out_scale = s_p * s_v;
     m.stages = spmm_stages_for(o, mask->K, m.ldb_bytes, m.row_bytes);
+    m.uniform_chunks = mask->uniform_chunks;
     m.max_unit_chunks = mask->max_panel_chunks;
     if (split_panels) {
         // Very unequal panels: the long ones are shared by several workgroups.  A rounded result cannot be added

@@ -10,6 +10,7 @@ struct mc_mat {
     int M, K, V, lhs_bits, P;
     int64_t nvec, nslots, vals_bytes;
     int max_panel_chunks;      // longest panel, in chunks of 64 vectors
+    int uniform_chunks;        // chunks of every panel when all panels have the same number (and at least one), else 0
     int device;                // HIP device the buffers live on
     int32_t *d_panel_ptr;      // 2*P: chunk-aligned first slot, real end slot
     int32_t *d_row_ptr;        // P+1: interchange row pointers (vector offsets)
@@ -78,6 +79,7 @@ struct SpmmArgs {
     const int32_t *items;
     int n_units;               // items, or P
     int stages;                // chunks in flight per wave: 1 or 2 (2 needs B to span less than 4 GiB)
+    int uniform_chunks;        // > 0: every panel has this many chunks and starts at panel * uniform_chunks * 64 (panel_ptr is not read)
     int ntiles, tile_shift;    // filled by the launcher: column tiles (workgroups) per unit, and their log2 (-1: not a power of two)
     int max_unit_chunks;       // chunks of the longest unit of work (panel or work item)
     // optional: items of a split panel add their int32 results here instead of into C (which may then be float or

@@ -135,13 +135,22 @@ __global__ __launch_bounds__(64 * WK) void spmm_kernel(SpmmArgs a)
         const v4i it = *reinterpret_cast<const v4i *>(a.items + 4 * unit);
         panel = it.x; cb = it.y; ce = it.z; split = it.w;
     }
-    const v2i pp = *reinterpret_cast<const v2i *>(a.panel_ptr + 2 * panel); // first slot, end slot: one load
-    const int s0 = pp.x, s1 = pp.y;
+    // Panels that all have the same number of chunks start at a computable slot: no trip to memory for the panel
+    // pointers, on which every later load of the workgroup depends (padded slots carry zero values, so the real end
+    // of the panel is not needed either).
+    int s0;
+    if (a.uniform_chunks > 0) {
+        s0 = panel * a.uniform_chunks * MC_CHUNK;
+        if (ce < 0) ce = a.uniform_chunks;
+    } else {
+        const v2i pp = *reinterpret_cast<const v2i *>(a.panel_ptr + 2 * panel); // first slot, end slot: one load
+        s0 = pp.x;
+        if (ce < 0) ce = (pp.y - s0 + MC_CHUNK - 1) / MC_CHUNK;
+    }
     if constexpr (TR) {
-        asm volatile("" ::"s"(s0), "s"(s1));             // (the stamp waits for the pointers)
+        asm volatile("" ::"s"(s0), "s"(ce));             // (the stamp waits for the pointers)
         clk.stamp(1);                                    // kernel arguments and panel pointers have arrived
     }
-    if (ce < 0) ce = (s1 - s0 + MC_CHUNK - 1) / MC_CHUNK;
     const int nch = ce - cb;                       // chunks of this unit: cb .. ce-1
     const int64_t chunk0 = s0 / MC_CHUNK + cb;
     const int32_t *idx = a.slot_idx + s0 + cb * MC_CHUNK;
