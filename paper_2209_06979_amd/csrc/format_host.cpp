@@ -76,9 +76,9 @@ inline int row_position(int s) { return (s / 16) * 16 + (s % 8) * 2 + (s % 16) /
 // The builders below exist in two forms: the exported ones take the vector lengths of the interchange format
 // (2, 4, 8); the *_wide ones also take 16 for 4- and 8-bit values, which only the library's own merged copy of
 // an operand uses (see mc_merge_host): sixteen rows fill the MFMA's row operand completely.
-static bool valid_V(int V, int lhs_bits, bool wide)
+static bool valid_V_wide(int V, int lhs_bits)
 {
-    return V == 2 || V == 4 || V == 8 || (wide && V == 16 && (lhs_bits == 4 || lhs_bits == 8));
+    return V == 2 || V == 4 || V == 8 || (V == 16 && (lhs_bits == 4 || lhs_bits == 8));
 }
 
 extern "C" int mc_layout_query(int M, int K, int V, int lhs_bits, const int32_t *row_ptr, mc_layout *out)
@@ -90,7 +90,7 @@ int mc_layout_query_wide(int M, int K, int V, int lhs_bits, const int32_t *row_p
 {
     if (!row_ptr || !out) return MC_EINVAL;
     if (M <= 0 || K <= 0) return MC_EINVAL;
-    if (!valid_V(V, lhs_bits, true)) return MC_EINVAL;
+    if (!valid_V_wide(V, lhs_bits)) return MC_EINVAL;
     if (M % V != 0) return MC_EINVAL;
     if (!valid_lhs_bits(lhs_bits)) return MC_EINVAL;
     const int P = M / V;

@@ -8,10 +8,15 @@ def torch_dev(a: np.ndarray):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
-def run_spmm_gpu(case, variant=(0, 0)):
+def run_spmm_gpu(case, variant=(0, 0), merge=0):
+    """merge: the operand's merged copy forced (1: built and used wherever the call allows it), forbidden (-1) or
+    left to the library (0)."""
     import torch
     from paper_2209_06979_amd import binding as mc
     bits = mc.LHS_BITS[case["prec"]]
+    o = mc.get_thread_options()
+    o.spmm_merge = merge
+    mc.set_thread_options(o)
     A = mc.SparseMatrix(case["M"], case["K"], case["V"], case["row_ptr"], case["col_idx"], case["values"], bits)
     mc.set_spmm_variant(*variant)
     try:
@@ -24,6 +29,9 @@ def run_spmm_gpu(case, variant=(0, 0)):
         return C.cpu().numpy()
     finally:
         mc.set_spmm_variant(0, 0)
+        o = mc.get_thread_options()
+        o.spmm_merge = 0
+        mc.set_thread_options(o)
         A.close()
 
 

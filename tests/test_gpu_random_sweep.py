@@ -41,12 +41,13 @@ def test_random_spmm(seed):
             splitting = bool(rng.integers(2))
         variant = (int(rng.choice([0, 64, 128, 256])), int(rng.choice([0, 1, 2, 4, 8])))
         stages = int(rng.choice([1, 2]))
-        print(f"#{n} spmm {prec} M={M} K={K} N={N} V={V} s={s} variant={variant} stages={stages} "
+        merge = int(rng.choice([0, 1, 1, -1]))
+        print(f"#{n} spmm {prec} M={M} K={K} N={N} V={V} s={s} variant={variant} stages={stages} merge={merge} "
               f"unsigned={case.get('lhs_unsigned', False)},{case.get('rhs_unsigned', False)}", flush=True)
         mc.set_spmm_stages(stages)
         mc.set_spmm_splitting(splitting)
         try:
-            got = run_spmm_gpu(case, variant)
+            got = run_spmm_gpu(case, variant, merge)
         finally:
             mc.set_spmm_stages(2)
             mc.set_spmm_splitting(True)
