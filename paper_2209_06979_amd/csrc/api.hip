@@ -817,6 +817,7 @@ extern "C" int mc_probe_gather(const mc_mat *A, const void *B_dev, int N, int ld
     a.row_bytes = N * rb / 8;
     a.C = nullptr; a.ldc = 0; a.C_batch_stride = 0;
     a.P = A->P; a.V = A->V; a.rows = A->M; a.batch = 1; a.float_out = 0; a.out_scale = 1.f;
+    a.uniform_chunks = A->uniform_chunks;
     int bnb, waves;
     choose_variant(A, A->lhs_bits, a.row_bytes, rb == 4, 1, A->max_panel_chunks, o, &bnb, &waves);
     MC_HIP(launch_gather_probe(a, bnb, waves, sink_dev, static_cast<hipStream_t>(stream)));

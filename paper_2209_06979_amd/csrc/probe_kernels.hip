@@ -25,8 +25,16 @@ __global__ __launch_bounds__(64 * WK) void gather_probe_kernel(SpmmArgs a, int32
     const int ntiles = (a.row_bytes + BNB - 1) / BNB;
     const int panel = blockIdx.x / ntiles, tile = blockIdx.x % ntiles;
     const int nb0 = tile * BNB;
-    const int s0 = a.panel_ptr[2 * panel], s1 = a.panel_ptr[2 * panel + 1];
-    const int nch = (s1 - s0 + MC_CHUNK - 1) / MC_CHUNK;
+    // (the panel's first slot and chunk count as spmm_kernel finds them: computed when all panels are equally long)
+    int s0, nch;
+    if (a.uniform_chunks > 0) {
+        s0 = panel * a.uniform_chunks * MC_CHUNK;
+        nch = a.uniform_chunks;
+    } else {
+        const int2 pp = *reinterpret_cast<const int2 *>(a.panel_ptr + 2 * panel);
+        s0 = pp.x;
+        nch = (pp.y - s0 + MC_CHUNK - 1) / MC_CHUNK;
+    }
     const int32_t *idx = a.slot_idx + s0;
     const uint8_t *Bb = a.B + nb0;
     char *stage = lds + w * (64 * BNB);
