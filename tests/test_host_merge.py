@@ -77,3 +77,17 @@ def test_merged_query_rejects_what_it_cannot_build():
     # the public builders keep to the interchange format's vector lengths
     lay = mc.Layout()
     assert mc.lib.mc_layout_query(32, K, 16, 8, mc._p32(mc._i32(np.array([0, 1, 2]))), lay) == mc.MC_EINVAL
+
+
+def test_pattern_only_and_empty_operands():
+    counts = [0, 0, 0, 0, 0]
+    M, K, rp, ci, vals = _case(2, 8, counts)
+    m_rp, m_ci, m_vals, m_src = mc.merge_host(M, K, 2, 8, rp, ci, vals, 4)
+    assert list(m_rp) == [0, 0, 0] and len(m_ci) == 0 and len(m_src) == 0 and len(m_vals) == 0
+    M, K, rp, ci, vals = _case(4, 8, [5, 0, 9])
+    m_rp, m_ci, m_vals, m_src = mc.merge_host(M, K, 4, 0, rp, ci, None, 2)      # a pattern without values
+    assert m_vals is None
+    flags = oracle.stored_flags(M, K, 4, rp, ci)
+    assert np.array_equal(m_ci[m_rp[0]:m_rp[1]], np.flatnonzero(flags[0] | flags[1]))
+    assert np.array_equal(m_ci[m_rp[1]:m_rp[2]], np.flatnonzero(flags[2]))
+    assert (m_src.reshape(-1, 2)[m_rp[1]:, 1] == -1).all()                       # the ragged group's missing panel
