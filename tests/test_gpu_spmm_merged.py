@@ -228,3 +228,10 @@ def test_full_size_points_of_the_sweep_grid(V, s, N, prec):
     assert on_merged and np.array_equal(got, want)
     got, on_merged, _ = _run(c, _opts(0))
     assert on_merged and np.array_equal(got, want)
+
+
+@pytest.mark.parametrize("prec", ["L8R8", "L4R4", "L16R8"])
+def test_large_dimensions(prec):
+    """A tall 32768 x 4096 operand with V = 2 (2048 merged panels, or 4096 of 8 rows) and a 16384 x 16384 one with V = 4."""
+    _check(wl.spmm_case(32768, 4096, 64, 2, 0.95, prec, 9960))
+    _check(wl.spmm_case(16384, 16384, 128, 4, 0.98, prec, 9961))
